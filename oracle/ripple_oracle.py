@@ -1,0 +1,294 @@
+"""CPU oracle for incremental GNN inference on an evolving graph (fp64).
+
+TEST INFRASTRUCTURE ONLY. This file is the slow, plain statement of what the
+GPU library must compute. Only the tests, the smoke check and the benchmark's
+CPU-baseline leg may import it; the product path never does, and this file
+imports nothing from the product.
+
+What it computes. The paper states that its incremental propagation yields,
+at every hop, exactly what layer-wise recomputation on the updated graph
+yields, up to floating-point rounding (Sec. 3.3.3, the cancelling-terms
+example for h^2_D; Sec. 5, last paragraph). The oracle is therefore that
+definition written out: after a batch has been applied to the graph, every
+embedding of every layer is recomputed from the features with Eq. (1)-(2)
+(Sec. 2.1) in float64. Independently it derives, by set operations only, which
+vertices the batch can affect at each hop (Sec. 3.2's per-update-type
+description; Sec. 2.2's worked example).
+
+Readings taken where the paper leaves a choice (each is listed in the design doc):
+  * sum / mean as in Table 1; mean of an empty neighbourhood is the zero vector;
+  * GraphConv: h = act(x W + b), no self term (Sec. 3.3.3 example);
+    GraphSAGE: h = act(h_self W_self + x W_neigh + b) (Eq. 2's UPDATE takes both);
+    GIN: h = act(MLP((1+eps) h_self + x)) (Sec. 6.3.1: GI-S adds the vertex's
+    own embedding to its in-neighbours');
+  * operations of a batch are applied in array order; invalid ones (dead or
+    out-of-range endpoint, duplicate edge, missing edge, adding a live vertex,
+    deleting or updating a dead one) are rejected and skipped;
+  * a deleted vertex loses all incident edges (Sec. 3.2) and its rows are zero;
+  * affected sets are topological: a vertex is affected whether or not its
+    value ends up different (Sec. 3.3.1: every vertex of the tree is updated).
+
+Parity pins (tests/test_oracle_*.py): brute-force per-vertex neighbourhood
+recursion on small graphs, the closed form (A^T)^L H W1..WL for the linear
+case, the all-ones mean fixed point, isolated vertices, the paper's worked
+edge-addition example for the affected sets, and planted-mistake checks.
+The numeric values of the paper's own runs are unpinned: it prints none.
+"""
+from __future__ import annotations
+
+import dataclasses
+import numpy as np
+import scipy.sparse as sp
+
+EDGE_ADD, EDGE_DEL, VERTEX_ADD, VERTEX_DEL, FEAT_UPDATE = 0, 1, 2, 3, 4
+
+
+# --------------------------------------------------------------------------
+# graph state
+# --------------------------------------------------------------------------
+class GraphState:
+    """Simple directed graph with vertex features, float64.
+
+    Edges live in a sorted base array of keys u*cap+v (and a second copy keyed
+    v*cap+u for in-neighbour lookups), minus a set of deleted base keys, plus
+    the edges added later; this keeps per-batch mutation cheap on graphs with
+    10^8 edges.
+    """
+
+    def __init__(self, n_vertices: int, vertex_capacity: int, src, dst, feats):
+        self.cap = int(vertex_capacity)
+        self.alive = np.zeros(self.cap, dtype=bool)
+        self.alive[:n_vertices] = True
+        s = np.asarray(src, dtype=np.int64)
+        d = np.asarray(dst, dtype=np.int64)
+        self.base = np.unique(s * self.cap + d)
+        if self.base.size != s.size:
+            raise ValueError("initial edge list contains duplicates")
+        self.base_t = np.sort(d * self.cap + s)
+        self.removed = set()                        # base keys (u*cap+v) no longer present
+        self.added_out = {}                         # u -> set of v, edges not in base
+        self.added_in = {}                          # v -> set of u
+        self.n_added = 0
+        f = np.asarray(feats, dtype=np.float64)
+        self.h0 = np.zeros((self.cap, f.shape[1]), dtype=np.float64)
+        self.h0[:n_vertices] = f
+
+    # -- edges ---------------------------------------------------------------
+    def _in_base(self, key: int) -> bool:
+        i = int(np.searchsorted(self.base, key))
+        return i < self.base.size and int(self.base[i]) == key
+
+    def has_edge(self, u: int, v: int) -> bool:
+        if v in self.added_out.get(u, ()):
+            return True
+        key = u * self.cap + v
+        return key not in self.removed and self._in_base(key)
+
+    def _insert(self, u: int, v: int):
+        key = u * self.cap + v
+        if key in self.removed:
+            self.removed.discard(key)
+        else:
+            self.added_out.setdefault(u, set()).add(v)
+            self.added_in.setdefault(v, set()).add(u)
+            self.n_added += 1
+
+    def _erase(self, u: int, v: int):
+        if v in self.added_out.get(u, ()):
+            self.added_out[u].discard(v)
+            self.added_in[v].discard(u)
+            self.n_added -= 1
+        else:
+            self.removed.add(u * self.cap + v)
+
+    def edges(self):
+        """(src, dst) int64 arrays of the current edge set."""
+        keep = np.ones(self.base.size, dtype=bool)
+        if self.removed:
+            gone = np.fromiter(self.removed, dtype=np.int64, count=len(self.removed))
+            keep[np.searchsorted(self.base, gone)] = False
+        extra = np.array([u * self.cap + v for u, vs in self.added_out.items() for v in vs],
+                         dtype=np.int64)
+        keys = np.concatenate([self.base[keep], extra])
+        return keys // self.cap, keys % self.cap
+
+    def n_edges(self) -> int:
+        return self.base.size - len(self.removed) + self.n_added
+
+    def out_neighbours(self, u: int) -> list:
+        lo, hi = np.searchsorted(self.base, [u * self.cap, (u + 1) * self.cap])
+        res = [int(k) % self.cap for k in self.base[lo:hi].tolist() if k not in self.removed]
+        return res + sorted(self.added_out.get(u, ()))
+
+    def in_neighbours(self, v: int) -> list:
+        lo, hi = np.searchsorted(self.base_t, [v * self.cap, (v + 1) * self.cap])
+        res = []
+        for k in self.base_t[lo:hi].tolist():
+            u = k % self.cap
+            if u * self.cap + v not in self.removed:
+                res.append(u)
+        return res + sorted(self.added_in.get(v, ()))
+
+    # -- one batch -------------------------------------------------------------
+    def apply_batch(self, ops, payload) -> "BatchRecord":
+        """Apply operations in array order (Sec. 3.3, Apply step).
+
+        Returns which operations were accepted and the root sets the
+        affected-set derivation needs.
+        """
+        ops = np.asarray(ops, dtype=np.int64).reshape(-1, 4)
+        payload = np.asarray(payload, dtype=np.float64).reshape(-1, self.h0.shape[1])
+        rec = BatchRecord(accepted=np.zeros(len(ops), dtype=bool))
+        for i, (kind, u, v, row) in enumerate(ops.tolist()):
+            if kind in (EDGE_ADD, EDGE_DEL):
+                if not (0 <= u < self.cap and 0 <= v < self.cap):
+                    continue
+                if not (self.alive[u] and self.alive[v]):
+                    continue
+                present = self.has_edge(u, v)
+                if kind == EDGE_ADD and not present:
+                    self._insert(u, v)
+                elif kind == EDGE_DEL and present:
+                    self._erase(u, v)
+                else:
+                    continue
+                rec.sinks.add(v)
+            elif kind == VERTEX_ADD:
+                if not (0 <= u < self.cap) or self.alive[u] or not (0 <= row < len(payload)):
+                    continue
+                self.alive[u] = True
+                self.h0[u] = payload[row]
+                rec.added.add(u)
+            elif kind == VERTEX_DEL:
+                if not (0 <= u < self.cap) or not self.alive[u]:
+                    continue
+                for y in self.out_neighbours(u):    # Sec. 3.2: all incident edges go first
+                    self._erase(u, y)
+                    rec.sinks.add(y)
+                for x in self.in_neighbours(u):
+                    self._erase(x, u)
+                self.alive[u] = False
+                self.h0[u] = 0.0
+                rec.removed.add(u)
+                rec.added.discard(u)
+                rec.feat.discard(u)
+            elif kind == FEAT_UPDATE:
+                if not (0 <= u < self.cap) or not self.alive[u] or not (0 <= row < len(payload)):
+                    continue
+                self.h0[u] = payload[row]
+                rec.feat.add(u)
+            else:
+                continue
+            rec.accepted[i] = True
+        return rec
+
+
+@dataclasses.dataclass
+class BatchRecord:
+    accepted: np.ndarray
+    sinks: set = dataclasses.field(default_factory=set)     # sinks of changed edges
+    added: set = dataclasses.field(default_factory=set)     # vertices created
+    removed: set = dataclasses.field(default_factory=set)   # vertices deleted
+    feat: set = dataclasses.field(default_factory=set)      # feature replaced
+
+
+# --------------------------------------------------------------------------
+# layer math, Eq. (1)-(2)
+# --------------------------------------------------------------------------
+def _act(name: str, z: np.ndarray) -> np.ndarray:
+    if name == "relu":
+        return np.maximum(z, 0.0)
+    if name == "none":
+        return z
+    raise ValueError(name)
+
+
+def aggregate(state: GraphState, h_prev: np.ndarray, agg: str) -> np.ndarray:
+    """Eq. (1): x_v = AGG over in-neighbours u of v of h_prev[u] (Table 1)."""
+    src, dst = state.edges()
+    a_in = sp.csr_matrix((np.ones(src.size), (dst, src)), shape=(state.cap, state.cap))
+    x = a_in @ h_prev                                            # sum over in-neighbours
+    if agg == "mean":
+        deg = np.bincount(dst, minlength=state.cap).astype(np.float64)
+        x = x / np.maximum(deg, 1.0)[:, None]                    # empty neighbourhood: 0
+    elif agg != "sum":
+        raise ValueError(agg)
+    return x
+
+
+def layer_forward(state: GraphState, layer: dict, h_prev: np.ndarray) -> np.ndarray:
+    """Eq. (2): h_v = act(UPDATE(h_prev[v], x_v)) for every live vertex; dead rows are 0."""
+    d_in = layer["d_in"]
+    x = aggregate(state, h_prev, layer["agg"])
+    w0 = np.asarray(layer["W0"], dtype=np.float64)
+    b0 = np.asarray(layer["b0"], dtype=np.float64)
+    if layer["self"] == "none":
+        z = x @ w0 + b0
+    elif layer["self"] == "concat":
+        z = h_prev @ w0[:d_in] + x @ w0[d_in:] + b0
+    elif layer["self"] == "add":
+        z = ((1.0 + layer["eps"]) * h_prev + x) @ w0 + b0
+    else:
+        raise ValueError(layer["self"])
+    if layer["d_hidden"]:
+        z = _act(layer["act_inner"], z)
+        z = z @ np.asarray(layer["W1"], dtype=np.float64) + np.asarray(layer["b1"], dtype=np.float64)
+    h = _act(layer["act_out"], z)
+    h[~state.alive] = 0.0
+    return h
+
+
+def full_recompute(state: GraphState, model) -> list:
+    """All embeddings of all layers on the current graph: [H^0, H^1, ..., H^L]."""
+    hs = [state.h0.copy()]
+    hs[0][~state.alive] = 0.0
+    for layer in model:
+        hs.append(layer_forward(state, layer, hs[-1]))
+    return hs
+
+
+# --------------------------------------------------------------------------
+# affected sets (Sec. 2.2 example, Sec. 3.2, Sec. 3.3)
+# --------------------------------------------------------------------------
+def affected_sets(state_after: GraphState, rec: BatchRecord, model) -> list:
+    """Sorted vertex ids whose layer-l embedding the batch can change, l = 0..L.
+
+    Hop 0: vertices whose features were written. Hop l: sinks of every changed
+    edge (an edge's sink is touched at every hop, Sec. 3.2 and the inbox example
+    of Sec. 3.3.2), out-neighbours in the updated graph of hop l-1's set, that
+    set itself when the layer reads the vertex's own previous embedding, and
+    created vertices (Sec. 3.2: a new vertex updates its own embeddings);
+    deleted vertices are dropped.
+    """
+    src, dst = state_after.edges()
+    alive = state_after.alive
+    cur = {w for w in (rec.feat | rec.added) if alive[w]}
+    out = [np.array(sorted(cur), dtype=np.int64)]
+    for layer in model:
+        mask = np.zeros(state_after.cap, dtype=bool)
+        if cur:
+            mask[list(cur)] = True
+        nxt = set(dst[mask[src]].tolist())
+        nxt |= rec.sinks | rec.added
+        if layer["self"] != "none":
+            nxt |= cur
+        cur = {w for w in nxt if alive[w]}
+        out.append(np.array(sorted(cur), dtype=np.int64))
+    return out
+
+
+# --------------------------------------------------------------------------
+# error metric used by every comparison against this oracle
+# --------------------------------------------------------------------------
+def max_rel_err(got: np.ndarray, want: np.ndarray, alive: np.ndarray) -> float:
+    """max over rows of ||got-want||_inf / max(||want||_inf, tau), where tau is
+    the mean of ||want||_inf over live rows. Element-wise relative error is
+    undefined at ReLU zeros, so rows are normalised by their own magnitude with
+    the layer's typical magnitude as floor."""
+    got = np.asarray(got, dtype=np.float64)
+    want = np.asarray(want, dtype=np.float64)
+    row = np.abs(want).max(axis=1) if want.shape[1] else np.zeros(len(want))
+    tau = float(row[alive].mean()) if alive.any() else 1.0
+    tau = tau if tau > 0 else 1.0
+    diff = np.abs(got - want).max(axis=1) if want.shape[1] else np.zeros(len(want))
+    return float((diff / np.maximum(row, tau)).max()) if len(want) else 0.0

@@ -1,0 +1,282 @@
+"""Pins for the CPU oracle: everything here checks oracle/ against something
+other than itself (brute force, closed forms, the paper's worked example)."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import ripple_inputs as ri
+from bruteforce import embed, in_lists
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def small_case(seed, n=40, e=160, d0=5, kind="gcn_sum", widths=(5, 7, 6, 4), dead=()):
+    rng = np.random.default_rng(seed)
+    keys = rng.choice(n * n, size=e, replace=False)
+    src, dst = keys // n, keys % n
+    keep = src != dst
+    src, dst = src[keep], dst[keep]
+    feats = rng.standard_normal((n, d0))
+    model = ri.make_model(kind, widths, seed + 1)
+    st = oracle.GraphState(n, n + 4, src, dst, feats)
+    return st, model, src, dst, feats
+
+
+@pytest.mark.parametrize("kind", ["gcn_sum", "gcn_mean", "sage_mean", "sage_sum", "gin_sum"])
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_layerwise_equals_vertexwise_bruteforce(kind, seed):
+    st, model, src, dst, feats = small_case(seed, kind=kind)
+    hs = oracle.full_recompute(st, model)
+    nbrs = in_lists(st.cap, src, dst)
+    f = np.zeros((st.cap, feats.shape[1]))
+    f[: len(feats)] = feats
+    memo = {}
+    for l in range(len(model) + 1):
+        for v in range(st.cap):
+            want = embed(v, l, model, f, nbrs, st.alive, memo)
+            np.testing.assert_allclose(hs[l][v], want, rtol=1e-12, atol=1e-12)
+
+
+def test_bruteforce_after_batch_with_all_update_kinds():
+    st, model, src, dst, feats = small_case(7, kind="sage_mean")
+    n = len(feats)
+    rng = np.random.default_rng(3)
+    payload = rng.standard_normal((3, feats.shape[1]))
+    s0, d0_ = int(src[0]), int(dst[0])
+    ops = [(ri.OP_EDGE_DEL, s0, d0_, 0), (ri.OP_EDGE_ADD, 1, 2, 0) if not st.has_edge(1, 2)
+           else (ri.OP_EDGE_ADD, 1, 3, 0),
+           (ri.OP_FEAT_UPDATE, 5, 0, 0), (ri.OP_VERTEX_ADD, n, 0, 1), (ri.OP_EDGE_ADD, n, 4, 0),
+           (ri.OP_EDGE_ADD, 6, n, 0), (ri.OP_VERTEX_DEL, 9, 0, 0), (ri.OP_FEAT_UPDATE, 9, 0, 2)]
+    rec = st.apply_batch(np.array(ops, dtype=np.uint32), payload)
+    assert rec.accepted.tolist() == [True] * 7 + [False]      # update of a deleted vertex
+    hs = oracle.full_recompute(st, model)
+    es, ed = st.edges()
+    nbrs = in_lists(st.cap, es, ed)
+    memo = {}
+    for v in range(st.cap):
+        want = embed(v, len(model), model, st.h0, nbrs, st.alive, memo)
+        np.testing.assert_allclose(hs[-1][v], want, rtol=1e-12, atol=1e-12)
+    assert not st.alive[9] and np.all(hs[-1][9] == 0)
+    assert 9 not in es and 9 not in ed
+
+
+def test_linear_sum_closed_form():
+    """No activation, no bias, sum: H^L = (A^T)^L H^0 W^1 ... W^L."""
+    st, model, src, dst, feats = small_case(11, kind="gcn_sum")
+    for lay in model:
+        lay["act_out"] = "none"
+        lay["b0"] = np.zeros_like(lay["b0"])
+    hs = oracle.full_recompute(st, model)
+    a = np.zeros((st.cap, st.cap))
+    for s, d in zip(src, dst):
+        a[s, d] += 1.0                                   # a[u, v] = 1 for edge u -> v
+    want = st.h0.copy()
+    for lay in model:
+        want = a.T @ want
+    for lay in model:
+        want = want @ np.asarray(lay["W0"], dtype=np.float64)
+    np.testing.assert_allclose(hs[-1], want, rtol=1e-11, atol=1e-11)
+
+
+def test_mean_of_ones_is_ones():
+    n, d = 30, 4
+    rng = np.random.default_rng(5)
+    ring_s = np.arange(n)
+    ring_d = (np.arange(n) + 1) % n                      # every vertex has an in-edge
+    extra = rng.choice(n * n, size=60, replace=False)
+    es, ed = extra // n, extra % n
+    keep = (es != ed) & (ed != (es + 1) % n)
+    src = np.concatenate([ring_s, es[keep]])
+    dst = np.concatenate([ring_d, ed[keep]])
+    st = oracle.GraphState(n, n, src, dst, np.ones((n, d)))
+    lay = dict(d_in=d, d_hidden=0, d_out=d, agg="mean", self="none", eps=0.0, act_inner="none",
+               act_out="relu", W0=np.eye(d, dtype=np.float32), b0=np.zeros(d, np.float32),
+               W1=None, b1=None)
+    hs = oracle.full_recompute(st, [lay, lay, lay])
+    np.testing.assert_allclose(hs[-1], np.ones((n, d)), rtol=0, atol=1e-15)
+
+
+@pytest.mark.parametrize("kind", ["gcn_sum", "sage_mean", "gin_sum"])
+def test_isolated_vertex(kind):
+    st, model, src, dst, feats = small_case(21, kind=kind, widths=(5, 6))
+    iso = st.cap - 1                                   # make one spare id live and isolated
+    f = np.random.default_rng(2).standard_normal((1, 5))
+    st.apply_batch(np.array([(ri.OP_VERTEX_ADD, iso, 0, 0)], dtype=np.uint32), f)
+    h1 = oracle.full_recompute(st, model)[1][iso]
+    lay = model[0]
+    W0, b0 = lay["W0"].astype(np.float64), lay["b0"].astype(np.float64)
+    if kind == "gcn_sum":
+        want = b0                                        # nothing aggregated: act(b), last layer no act
+    elif kind == "sage_mean":
+        want = f[0] @ W0[:5] + b0
+    else:
+        want = np.maximum(f[0] @ W0 + b0, 0) @ lay["W1"].astype(np.float64) + lay["b1"]
+    np.testing.assert_allclose(h1, want, rtol=1e-13, atol=1e-13)
+
+
+# ---- planted mistakes: each plausible slip must trip the brute-force pin ----
+def _bf_all(model, st, src, dst):
+    nbrs = in_lists(st.cap, src, dst)
+    memo = {}
+    L = len(model)
+    return np.stack([embed(v, L, model, st.h0, nbrs, st.alive, memo) for v in range(st.cap)])
+
+
+def test_planted_mistakes_are_caught():
+    st, model, src, dst, feats = small_case(31, kind="sage_mean")
+    good = oracle.full_recompute(st, model)[-1]
+    np.testing.assert_allclose(good, _bf_all(model, st, src, dst), rtol=1e-12, atol=1e-12)
+    # (a) edge direction swapped
+    st_rev = oracle.GraphState(len(feats), st.cap, dst, src, feats)
+    assert np.abs(oracle.full_recompute(st_rev, model)[-1] - good).max() > 1e-3
+    # (b) self and neighbour halves of the SAGE weight swapped
+    sw = [dict(l, W0=np.vstack([l["W0"][l["d_in"]:], l["W0"][:l["d_in"]]])) for l in model]
+    assert np.abs(oracle.full_recompute(st, sw)[-1] - good).max() > 1e-3
+    # (c) mean replaced by sum
+    sm = [dict(l, agg="sum") for l in model]
+    assert np.abs(oracle.full_recompute(st, sm)[-1] - good).max() > 1e-3
+    # (d) bias dropped
+    nb = [dict(l, b0=np.zeros_like(l["b0"])) for l in model]
+    assert np.abs(oracle.full_recompute(st, nb)[-1] - good).max() > 1e-3
+    # (e) GIN: eps sign / self term dropped
+    st2, gin, s2, d2, f2 = small_case(32, kind="gin_sum")
+    for l in gin:
+        l["eps"] = 0.25
+    g = oracle.full_recompute(st2, gin)[-1]
+    np.testing.assert_allclose(g, _bf_all(gin, st2, s2, d2), rtol=1e-12, atol=1e-12)
+    assert np.abs(oracle.full_recompute(st2, [dict(l, eps=-0.25) for l in gin])[-1] - g).max() > 1e-4
+
+
+# ---- affected sets -------------------------------------------------------------
+def _read_golden():
+    sec, cur = {}, None
+    with open(os.path.join(GOLDEN, "worked_example.txt")) as fh:
+        for line in fh:
+            line = line.strip()
+            if not line or line.startswith("#"):
+                continue
+            if line.startswith("["):
+                cur = line.strip("[]")
+                sec[cur] = []
+            else:
+                sec[cur].append(line.split())
+    return sec
+
+
+def _example_state():
+    g = _read_golden()
+    names = "ABCDE"
+    idx = {c: i for i, c in enumerate(names)}
+    src = [idx[a] for a, b in g["edges"]]
+    dst = [idx[b] for a, b in g["edges"]]
+    st = oracle.GraphState(5, 5, src, dst, np.random.default_rng(0).standard_normal((5, 3)))
+    return g, idx, st
+
+
+def _ids(idx, toks):
+    return sorted(idx[t] for t in toks)
+
+
+def test_paper_worked_example_edge_addition():
+    g, idx, st = _example_state()
+    model3 = ri.make_model("gcn_sum", (3, 3, 3, 3), 1)
+    (a, b), = g["add_edge"]
+    rec = st.apply_batch(np.array([(ri.OP_EDGE_ADD, idx[a], idx[b], 0)], dtype=np.uint32),
+                         np.zeros((0, 3)))
+    assert rec.accepted.all()
+    sets = oracle.affected_sets(st, rec, model3)
+    assert sets[0].tolist() == []
+    assert sets[1].tolist() == _ids(idx, g["expect_hop1"][0])
+    assert sets[2].tolist() == _ids(idx, g["expect_hop2"][0])
+    assert set(_ids(idx, g["expect_hop3_superset"][0])) <= set(sets[3].tolist())
+    sink = idx[g["sink_every_hop"][0][0]]
+    assert all(sink in s for s in sets[1:])
+
+
+def test_paper_worked_example_vertex_delete_and_feature_update():
+    g, idx, st = _example_state()
+    model = ri.make_model("gcn_sum", (3, 3, 3), 1)
+    (a, b), = g["add_edge"]
+    st.apply_batch(np.array([(ri.OP_EDGE_ADD, idx[a], idx[b], 0)], dtype=np.uint32), np.zeros((0, 3)))
+    c = idx[g["feature_update"][0][0]]
+    rec = st.apply_batch(np.array([(ri.OP_FEAT_UPDATE, c, 0, 0)], dtype=np.uint32), np.ones((1, 3)))
+    sets = oracle.affected_sets(st, rec, model)
+    assert sets[0].tolist() == [c]
+    assert sets[1].tolist() == _ids(idx, g["expect_feature_hop1"][0])
+    c = idx[g["delete_vertex"][0][0]]
+    rec = st.apply_batch(np.array([(ri.OP_VERTEX_DEL, c, 0, 0)], dtype=np.uint32), np.zeros((0, 3)))
+    sets = oracle.affected_sets(st, rec, model)
+    assert sets[1].tolist() == _ids(idx, g["expect_delete_hop1"][0])
+    es, ed = st.edges()
+    assert c not in es and c not in ed and st.n_edges() == 5
+
+
+@pytest.mark.parametrize("kind", ["gcn_sum", "sage_mean", "gin_sum"])
+@pytest.mark.parametrize("seed", [0, 1, 2, 3])
+def test_affected_set_equals_rows_that_change(kind, seed):
+    """With linear activations and generic real inputs, the rows of H^l that a
+    batch really changes are exactly the topological affected set; with ReLU
+    they are a subset of it."""
+    for linear in (True, False):
+        st, model, src, dst, feats = small_case(100 + seed, n=60, e=150, kind=kind)
+        if linear:
+            for lay in model:
+                lay["act_out"] = "none"
+                lay["act_inner"] = "none"
+        before = oracle.full_recompute(st, model)
+        cfg_rng = np.random.default_rng(seed)
+        n = len(feats)
+        ops, rows = [], []
+        es, ed = st.edges()
+        pick = cfg_rng.choice(len(es), size=3, replace=False)
+        for i in pick:
+            ops.append((ri.OP_EDGE_DEL, int(es[i]), int(ed[i]), 0))
+        while len(ops) < 6:
+            u, v = cfg_rng.integers(n, size=2)
+            if u != v and not st.has_edge(int(u), int(v)):
+                ops.append((ri.OP_EDGE_ADD, int(u), int(v), 0))
+        for w in cfg_rng.choice(n, size=2, replace=False):
+            rows.append(cfg_rng.standard_normal(feats.shape[1]))
+            ops.append((ri.OP_FEAT_UPDATE, int(w), 0, len(rows) - 1))
+        rec = st.apply_batch(np.array(ops, dtype=np.uint32), np.array(rows))
+        after = oracle.full_recompute(st, model)
+        sets = oracle.affected_sets(st, rec, model)
+        for l in range(len(model) + 1):
+            changed = set(np.nonzero(np.abs(after[l] - before[l]).max(axis=1) > 0)[0].tolist())
+            if linear:
+                assert changed == set(sets[l].tolist()), (l, kind)
+            else:
+                assert changed <= set(sets[l].tolist()), (l, kind)
+
+
+def test_apply_batch_validation_in_array_order():
+    st, model, src, dst, feats = small_case(41)
+    n = len(feats)
+    u, v = int(src[0]), int(dst[0])
+    ops = [(ri.OP_EDGE_ADD, u, v, 0),          # duplicate -> rejected
+           (ri.OP_EDGE_DEL, u, v, 0),          # ok
+           (ri.OP_EDGE_DEL, u, v, 0),          # now missing -> rejected
+           (ri.OP_EDGE_ADD, u, v, 0),          # ok again
+           (ri.OP_EDGE_ADD, n, 0, 0),          # n is dead -> rejected
+           (ri.OP_VERTEX_ADD, n, 0, 0),        # ok
+           (ri.OP_VERTEX_ADD, n, 0, 0),        # already live -> rejected
+           (ri.OP_EDGE_ADD, n, 0, 0),          # ok now
+           (ri.OP_VERTEX_DEL, st.cap - 1, 0, 0),   # dead -> rejected
+           (ri.OP_FEAT_UPDATE, st.cap + 5, 0, 0),  # out of range -> rejected
+           (7, 0, 0, 0)]                       # unknown kind -> rejected
+    e0 = st.n_edges()
+    rec = st.apply_batch(np.array(ops, dtype=np.uint32), np.ones((1, feats.shape[1])))
+    assert rec.accepted.tolist() == [False, True, False, True, False, True, False, True,
+                                     False, False, False]
+    assert st.n_edges() == e0 + 1
+    assert rec.sinks == {v, 0} and rec.added == {n}
+
+
+def test_max_rel_err_metric():
+    want = np.array([[1.0, -2.0], [0.0, 0.0], [10.0, 0.0]])
+    got = want + np.array([[0.0, 0.02], [0.04, 0.0], [0.0, 0.5]])
+    alive = np.array([True, True, True])
+    # row norms 2, 0, 10 -> tau = 4; errors 0.02/4, 0.04/4, 0.5/10
+    assert abs(oracle.max_rel_err(got, want, alive) - 0.05) < 1e-15
