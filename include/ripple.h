@@ -1,0 +1,193 @@
+/*
+ * ripple.h - C ABI of the MI355X incremental GNN inference library.
+ *
+ * The library keeps, resident on one GPU, a directed graph (out- and in-
+ * adjacency), the vertex features H^0 and every layer's embeddings H^1..H^L
+ * of an L-layer GNN, plus one cached un-normalised neighbourhood sum X^l per
+ * layer. After a batch of graph updates it refreshes only the embeddings the
+ * batch can affect, by propagating embedding deltas hop by hop (paper Sec. 3.3),
+ * and the result equals layer-wise recomputation on the updated graph up to
+ * floating-point rounding (Sec. 3.3.3; Sec. 5, last paragraph).
+ *
+ * Conventions for every call:
+ *   - returns a ripple_status; nothing throws or aborts across this boundary;
+ *     ripple_last_error() gives a text for the last failure on that context;
+ *   - input pointers are borrowed for the duration of the call only; outputs
+ *     are caller-allocated; the context owns all device memory it needs;
+ *   - "host or device" pointers may be pageable/pinned host memory or memory of
+ *     the context's GPU; "host" pointers must be host memory;
+ *   - all GPU work is enqueued on the stream given at init and the call returns
+ *     after that stream has been synchronised (trigger-based inference,
+ *     Sec. 2.2: results are available as soon as the batch is done);
+ *   - a context is not thread-safe; call order is
+ *     init_graph -> load_model -> full_infer -> (apply_updates | get_*)*,
+ *     violations return RIPPLE_ESTATE.
+ *   - matrices are row-major; vertex ids are 0 .. vertex_capacity-1.
+ */
+#ifndef RIPPLE_H
+#define RIPPLE_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ripple_ctx ripple_ctx;   /* opaque */
+
+typedef enum {
+    RIPPLE_OK = 0,
+    RIPPLE_EINVAL = 1,      /* bad argument (null pointer, id out of range, bad enum, bad shape) */
+    RIPPLE_ESTATE = 2,      /* call order violated */
+    RIPPLE_ECAPACITY = 3,   /* vertex/edge capacity exceeded; state unchanged */
+    RIPPLE_ENOMEM = 4,      /* device or host allocation failed */
+    RIPPLE_EDEVICE = 5      /* a HIP call failed */
+} ripple_status;
+
+/* The five update types of Sec. 3.1. */
+typedef enum {
+    RIPPLE_EDGE_ADD = 0,      /* edge u -> v */
+    RIPPLE_EDGE_DEL = 1,      /* edge u -> v */
+    RIPPLE_VERTEX_ADD = 2,    /* vertex u, features = payload row feat_row */
+    RIPPLE_VERTEX_DEL = 3,    /* vertex u and all its incident edges (Sec. 3.2) */
+    RIPPLE_FEAT_UPDATE = 4    /* h^0_u = payload row feat_row */
+} ripple_op_kind;
+
+typedef struct {
+    uint32_t kind;       /* ripple_op_kind */
+    uint32_t u;
+    uint32_t v;          /* sink of an edge op; ignored otherwise */
+    uint32_t feat_row;   /* row of the batch's feature payload; ignored for edge ops and VERTEX_DEL */
+} ripple_update;         /* 16 bytes */
+
+typedef enum { RIPPLE_AGG_SUM = 0, RIPPLE_AGG_MEAN = 1 } ripple_agg;           /* Table 1 */
+typedef enum {
+    RIPPLE_SELF_NONE = 0,    /* GraphConv:  h = act(x W0 + b0)                               */
+    RIPPLE_SELF_CONCAT = 1,  /* GraphSAGE:  h = act([h_self | x] W0 + b0), W0 is [2 d_in x .] */
+    RIPPLE_SELF_ADD = 2      /* GIN:        h = act(MLP((1+eps) h_self + x))                  */
+} ripple_self;
+typedef enum { RIPPLE_ACT_NONE = 0, RIPPLE_ACT_RELU = 1 } ripple_act;
+typedef enum { RIPPLE_STORE_F32 = 0, RIPPLE_STORE_BF16 = 1 } ripple_store;
+
+/* One GNN layer (Eq. 1-2). x is the sum (RIPPLE_AGG_SUM) or the mean
+ * (RIPPLE_AGG_MEAN; zero for a vertex without in-neighbours) of the previous
+ * layer's embeddings of the vertex's in-neighbours. With d_hidden == 0 the
+ * update is one linear map W0 [K x d_out], K = d_in (2*d_in for SELF_CONCAT);
+ * with d_hidden > 0 it is W0 [K x d_hidden], act_inner, W1 [d_hidden x d_out].
+ * act_out is applied last. Weights and biases are float32 host arrays. */
+typedef struct {
+    uint32_t d_in, d_hidden, d_out;
+    uint32_t agg;          /* ripple_agg  */
+    uint32_t self_mode;    /* ripple_self */
+    float    eps;          /* SELF_ADD only */
+    uint32_t act_inner;    /* ripple_act, used when d_hidden > 0 */
+    uint32_t act_out;      /* ripple_act */
+    const float *W0, *b0;  /* host */
+    const float *W1, *b1;  /* host; NULL when d_hidden == 0 */
+} ripple_layer_desc;
+
+#define RIPPLE_MAX_LAYERS 8
+
+/* Filled by ripple_apply_updates. */
+typedef struct {
+    uint32_t n_ops;                               /* operations submitted                        */
+    uint32_t n_applied;                           /* accepted and applied                        */
+    uint32_t n_rejected;                          /* individually invalid, skipped               */
+    uint32_t n_sub_batches;                       /* 1 unless operations of the batch conflicted */
+    uint32_t n_compactions;                       /* graph-store compactions run by this call    */
+    uint32_t n_alive;                             /* live vertices after the batch               */
+    uint64_t n_edges;                             /* edges after the batch                       */
+    uint32_t affected[RIPPLE_MAX_LAYERS + 1];     /* a_l = |A_l|, l = 0..L (Sec. 3.5)            */
+    uint64_t messages[RIPPLE_MAX_LAYERS + 1];     /* delta messages sent into layer l (index 0 unused) */
+    uint32_t n_structural;                        /* added/removed edges incl. those of deleted vertices */
+} ripple_batch_result;
+
+/* Accumulated per-kernel-class timing and work counters (RIPPLE_OPT_TIMING). */
+#define RIPPLE_N_PHASES 8
+enum { RIPPLE_PH_INGEST = 0, RIPPLE_PH_STRUCT = 1, RIPPLE_PH_FRONTIER = 2, RIPPLE_PH_SCATTER = 3,
+       RIPPLE_PH_COMPACT = 4, RIPPLE_PH_TRANSFORM = 5, RIPPLE_PH_OTHER = 6, RIPPLE_PH_TOTAL = 7 };
+typedef struct {
+    uint64_t batches;
+    double   ms[RIPPLE_N_PHASES][RIPPLE_MAX_LAYERS + 1];       /* summed HIP-event time per phase and layer */
+    uint64_t launches[RIPPLE_N_PHASES][RIPPLE_MAX_LAYERS + 1];
+    uint64_t rows[RIPPLE_MAX_LAYERS + 1];                      /* sum of a_l                                 */
+    uint64_t msgs[RIPPLE_MAX_LAYERS + 1];                      /* sum of messages into layer l               */
+} ripple_stats;
+
+typedef enum {
+    RIPPLE_OPT_TIMING = 0,        /* 0/1: record HIP events around every kernel class (default 0) */
+    RIPPLE_OPT_SCATTER_MODE = 1   /* 0 auto, 1 push (float atomics), 2 pull (segmented reduction over in-rows) */
+} ripple_option;
+
+/* Build the graph store and upload features (the state the paper's Sec. 3.1
+ * assumes before updates stream in). Vertices 0..n_vertices-1 are live, ids up
+ * to vertex_capacity-1 may be created later. src/dst: host, n_edges entries,
+ * distinct edges src[i] -> dst[i] between live vertices (self-loops allowed,
+ * duplicates are a precondition violation). features: host float32
+ * [n_vertices x d0]. store: RIPPLE_STORE_F32 or RIPPLE_STORE_BF16 (embeddings
+ * kept in bfloat16; cached sums and all accumulation stay float32).
+ * hip_stream: a hipStream_t (NULL = the default stream). */
+ripple_status ripple_init_graph(ripple_ctx **out, uint32_t n_vertices, uint32_t vertex_capacity,
+                                uint64_t n_edges, uint64_t edge_capacity,
+                                const uint32_t *src, const uint32_t *dst,
+                                const float *features, uint32_t d0, int store, void *hip_stream);
+
+/* Copy the model to the GPU. layers[0].d_in must equal d0 and widths must chain. */
+ripple_status ripple_load_model(ripple_ctx *ctx, uint32_t n_layers, const ripple_layer_desc *layers);
+
+/* Bootstrap: compute X^l and H^l for all layers and all live vertices on the
+ * current graph (Sec. 3.1: initial embeddings exist before updates arrive). */
+ripple_status ripple_full_infer(ripple_ctx *ctx);
+
+/* Apply one batch (Sec. 3.3): operations take effect in array order; invalid
+ * ones (dead endpoint, existing edge added, missing edge deleted, live vertex
+ * added, dead vertex deleted/updated) are rejected one by one and counted; ids
+ * >= vertex_capacity, unknown kinds or feat_row >= n_feat_rows fail the whole
+ * call with RIPPLE_EINVAL before anything changes. Then deltas are propagated
+ * through all layers. ops: host or device. feat_payload: host or device
+ * float32 [n_feat_rows x d0]. res may be NULL. */
+ripple_status ripple_apply_updates(ripple_ctx *ctx, const ripple_update *ops, uint32_t n_ops,
+                                   const float *feat_payload, uint32_t n_feat_rows,
+                                   ripple_batch_result *res);
+
+/* Rows ids[0..n_ids) of H^layer (layer 0 = features) as float32 into out
+ * [n_ids x d_layer] (host or device). ids: host or device, or NULL for rows
+ * 0..n_ids-1. Rows of dead vertices are zero. */
+ripple_status ripple_get_embeddings(ripple_ctx *ctx, uint32_t layer, const uint32_t *ids,
+                                    uint32_t n_ids, float *out);
+
+/* Same for the cached un-normalised neighbourhood sums X^layer, layer = 1..L
+ * (width d_{layer-1}); used to check the invariant X^l[v] = sum of H^{l-1} over
+ * v's in-neighbours. */
+ripple_status ripple_get_aggregates(ripple_ctx *ctx, uint32_t layer, const uint32_t *ids,
+                                    uint32_t n_ids, float *out);
+
+/* Vertices the last batch could affect at `layer` (0..L), ascending, into
+ * ids_out (host, room for cap ids); *n_out receives the set size even when it
+ * exceeds cap (then only cap ids are written). */
+ripple_status ripple_get_affected(ripple_ctx *ctx, uint32_t layer, uint32_t *ids_out, uint32_t cap,
+                                  uint32_t *n_out);
+
+/* Current edge set read back from the out-adjacency (direction 0) or the
+ * in-adjacency (direction 1) as src -> dst pairs, in storage order (host
+ * arrays with room for cap edges). */
+ripple_status ripple_export_edges(ripple_ctx *ctx, int direction, uint32_t *src_out, uint32_t *dst_out,
+                                  uint64_t cap, uint64_t *n_out);
+
+/* In-degree (direction 1) or out-degree (direction 0) of every vertex id, and
+ * the live flag (0/1) per id; host arrays of vertex_capacity entries; either may be NULL. */
+ripple_status ripple_get_degrees(ripple_ctx *ctx, int direction, uint32_t *deg_out, uint8_t *alive_out);
+
+/* Rebuild both adjacency pools without holes (also runs by itself when a pool fills up). */
+ripple_status ripple_compact(ripple_ctx *ctx);
+
+ripple_status ripple_set_option(ripple_ctx *ctx, int option, int64_t value);
+ripple_status ripple_get_stats(ripple_ctx *ctx, ripple_stats *out, int reset);
+
+void ripple_destroy(ripple_ctx *ctx);
+const char *ripple_last_error(const ripple_ctx *ctx);   /* never NULL; "" when ctx is NULL */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RIPPLE_H */

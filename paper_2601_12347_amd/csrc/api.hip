@@ -1,0 +1,878 @@
+// C ABI of the library: context lifetime, model upload, bootstrap inference,
+// the per-batch driver (host-side validation and conflict splitting, then the
+// device pipeline Apply -> per layer {frontier, scatter, transform}), and the
+// read-back calls the tests use.
+#include "common.h"
+#include "kernels.h"
+
+#include <cstring>
+#include <new>
+
+// ---------------------------------------------------------------------------------
+// timing
+// ---------------------------------------------------------------------------------
+struct PhaseTimer {
+    struct Rec {
+        int phase, layer, e0, e1;
+    };
+    std::vector<hipEvent_t> ev;
+    std::vector<Rec> recs;
+    int used = 0;
+    int get(ripple_ctx *c) {
+        if (used == (int)ev.size()) {
+            hipEvent_t e;
+            if (hipEventCreate(&e) != hipSuccess) return -1;
+            ev.push_back(e);
+        }
+        return used++;
+    }
+};
+
+int rp_timer_begin(ripple_ctx *c) {
+    if (!c->opt_timing) return -1;
+    int e = c->timer->get(c);
+    if (e >= 0) hipEventRecord(c->timer->ev[e], c->stream);
+    return e;
+}
+
+void rp_timer_end(ripple_ctx *c, int token, int phase, int layer) {
+    if (token < 0) return;
+    int e = c->timer->get(c);
+    if (e < 0) return;
+    hipEventRecord(c->timer->ev[e], c->stream);
+    c->timer->recs.push_back({phase, layer, token, e});
+}
+
+static void timer_collect(ripple_ctx *c) {       // after the stream has been synchronised
+    PhaseTimer *t = c->timer;
+    for (const auto &r : t->recs) {
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, t->ev[r.e0], t->ev[r.e1]) == hipSuccess) {
+            c->stats.ms[r.phase][r.layer] += ms;
+            c->stats.launches[r.phase][r.layer] += 1;
+        }
+    }
+    t->recs.clear();
+    t->used = 0;
+}
+
+// ---------------------------------------------------------------------------------
+// small kernels
+// ---------------------------------------------------------------------------------
+__global__ void k_store_rows(const float *src, void *dst, size_t n, int store) {
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {
+        if (store) ((__hip_bfloat16 *)dst)[i] = __float2bfloat16(src[i]);
+        else ((float *)dst)[i] = src[i];
+    }
+}
+
+__global__ void k_gather_rows(const void *M, int store, uint32_t d, const uint32_t *ids, uint32_t first,
+                              size_t n_rows, uint32_t n_cap, float *out) {
+    size_t total = n_rows * d, stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        size_t r = i / d;
+        uint32_t col = (uint32_t)(i % d);
+        uint32_t id = ids ? ids[r] : (uint32_t)(first + r);
+        float v = 0.0f;
+        if (id < n_cap) v = rp_load_h(M, store, (size_t)id * d + col);
+        out[i] = v;
+    }
+}
+
+__global__ void k_or_words(uint32_t *dst, const uint32_t *src, uint32_t n) {
+    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n && src[i]) dst[i] |= src[i];
+}
+
+__global__ void k_meta_len2(const uint2 *meta, uint32_t n_cap, uint32_t *len) {
+    uint32_t v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v < n_cap) len[v] = meta[v].y;
+}
+
+__global__ __launch_bounds__(256) void k_export_rows(const uint2 *meta, const uint32_t *pool, const uint32_t *off,
+                                                     uint32_t n_cap, int direction, uint32_t *src_out,
+                                                     uint32_t *dst_out) {
+    const int lane = rp_lane();
+    uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    for (uint32_t v = gw; v < n_cap; v += nw) {
+        uint2 m = meta[v];
+        uint32_t o = off[v];
+        for (uint32_t i = lane; i < m.y; i += 64) {
+            uint32_t nb = pool[m.x + i];
+            src_out[o + i] = direction ? nb : v;
+            dst_out[o + i] = direction ? v : nb;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// helpers
+// ---------------------------------------------------------------------------------
+static bool is_device_ptr(const void *p) {
+    hipPointerAttribute_t at;
+    hipError_t e = hipPointerGetAttributes(&at, p);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return at.type == hipMemoryTypeDevice || at.type == hipMemoryTypeManaged;
+}
+
+template <typename T>
+static ripple_status dev_alloc(ripple_ctx *c, T **p, size_t count, bool zero) {
+    size_t bytes = (count ? count : 1) * sizeof(T);
+    hipError_t e = hipMalloc((void **)p, bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        c->err = "device allocation of " + std::to_string(bytes) + " bytes failed";
+        *p = nullptr;
+        return RIPPLE_ENOMEM;
+    }
+    if (zero) RP_HIP(c, hipMemsetAsync(*p, 0, bytes, c->stream));
+    return RIPPLE_OK;
+}
+
+#define RP_TRY(expr)                         \
+    do {                                     \
+        ripple_status rc__ = (expr);         \
+        if (rc__ != RIPPLE_OK) return rc__;  \
+    } while (0)
+
+static size_t elem_size(const ripple_ctx *c) { return c->store ? 2 : 4; }
+
+static ripple_status fail(ripple_ctx *c, ripple_status rc, const char *msg) {
+    c->err = msg;
+    return rc;
+}
+
+// ---------------------------------------------------------------------------------
+// init / destroy
+// ---------------------------------------------------------------------------------
+extern "C" ripple_status ripple_init_graph(ripple_ctx **out, uint32_t n_vertices, uint32_t vertex_capacity,
+                                           uint64_t n_edges, uint64_t edge_capacity, const uint32_t *src,
+                                           const uint32_t *dst, const float *features, uint32_t d0, int store,
+                                           void *hip_stream) {
+    if (!out) return RIPPLE_EINVAL;
+    *out = nullptr;
+    if (vertex_capacity == 0 || n_vertices > vertex_capacity || vertex_capacity > (1u << 31) || d0 == 0 ||
+        d0 > 1024 || n_edges > edge_capacity || (store != RIPPLE_STORE_F32 && store != RIPPLE_STORE_BF16) ||
+        (n_edges && (!src || !dst)) || (n_vertices && !features))
+        return RIPPLE_EINVAL;
+    uint64_t pool_cap = edge_capacity + edge_capacity / 4 + 8ull * vertex_capacity + 1024;
+    if (pool_cap >= (1ull << 32)) return RIPPLE_EINVAL;
+    ripple_ctx *c = new (std::nothrow) ripple_ctx();
+    if (!c) return RIPPLE_ENOMEM;
+    *out = c;                                   // returned even on failure so that the error text can be read
+    c->timer = new (std::nothrow) PhaseTimer();
+    memset(&c->stats, 0, sizeof(c->stats));
+    c->stream = (hipStream_t)hip_stream;
+    RP_HIP(c, hipGetDevice(&c->device));
+    int cu = 0;
+    RP_HIP(c, hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, c->device));
+    c->n_cu = cu > 0 ? (uint32_t)cu : 256u;
+    c->n_cap = vertex_capacity;
+    c->n_words = rp_div_up(vertex_capacity, 32);
+    c->e_cap = edge_capacity;
+    c->pool_cap = pool_cap;
+    c->store = store;
+    c->d[0] = d0;
+    const size_t n = c->n_cap;
+    RP_TRY(dev_alloc(c, &c->out_meta, n, true));
+    RP_TRY(dev_alloc(c, &c->in_meta, n, true));
+    RP_TRY(dev_alloc(c, &c->out_capv, n, true));
+    RP_TRY(dev_alloc(c, &c->in_capv, n, true));
+    RP_TRY(dev_alloc(c, &c->vstate, n, true));
+    RP_TRY(dev_alloc(c, &c->pend_out, n, true));
+    RP_TRY(dev_alloc(c, &c->pend_in, n, true));
+    RP_TRY(dev_alloc(c, &c->dead_out, n, true));
+    RP_TRY(dev_alloc(c, &c->dead_in, n, true));
+    RP_TRY(dev_alloc(c, &c->out_pool, (size_t)pool_cap, false));
+    RP_TRY(dev_alloc(c, &c->in_pool, (size_t)pool_cap, false));
+    RP_TRY(dev_alloc(c, &c->alive, (size_t)c->n_words, true));
+    c->n_part = std::max(rp_div_up(n, 1024), rp_div_up(c->n_words, 256)) + 1;
+    RP_TRY(dev_alloc(c, &c->part_cnt, (size_t)c->n_part, true));
+    RP_TRY(dev_alloc(c, &c->part_deg, (size_t)c->n_part, true));
+    RP_TRY(dev_alloc(c, &c->ctr, 1, true));
+    RP_HIP(c, hipHostMalloc((void **)&c->ctr_host, sizeof(DevCtr), hipHostMallocDefault));
+    memset(c->ctr_host, 0, sizeof(DevCtr));
+    {   // features
+        void *h0 = nullptr;
+        size_t bytes = n * d0 * elem_size(c);
+        hipError_t e = hipMalloc(&h0, bytes ? bytes : 4);
+        if (e != hipSuccess) return fail(c, RIPPLE_ENOMEM, "device allocation of the feature matrix failed");
+        c->H[0] = h0;
+        RP_HIP(c, hipMemsetAsync(h0, 0, bytes, c->stream));
+        if (n_vertices) {
+            size_t cnt = (size_t)n_vertices * d0;
+            if (store == RIPPLE_STORE_F32) {
+                RP_HIP(c, hipMemcpyAsync(h0, features, cnt * 4, hipMemcpyHostToDevice, c->stream));
+            } else {
+                float *tmp = nullptr;
+                RP_TRY(dev_alloc(c, &tmp, cnt, false));
+                RP_HIP(c, hipMemcpyAsync(tmp, features, cnt * 4, hipMemcpyHostToDevice, c->stream));
+                hipLaunchKernelGGL(k_store_rows, dim3(c->n_cu * 8), dim3(256), 0, c->stream, tmp, h0, cnt, 1);
+                RP_HIP(c, hipStreamSynchronize(c->stream));
+                hipFree(tmp);
+            }
+        }
+    }
+    RP_TRY(rp_build_graph(c, n_vertices, n_edges, src, dst));
+    // counters that persist across batches
+    c->ctr_host->n_alive = n_vertices;
+    c->ctr_host->n_edges = n_edges;
+    RP_HIP(c, hipMemcpyAsync(&c->ctr->n_alive, &c->ctr_host->n_alive, 4, hipMemcpyHostToDevice, c->stream));
+    RP_HIP(c, hipMemcpyAsync(&c->ctr->n_edges, &c->ctr_host->n_edges, 8, hipMemcpyHostToDevice, c->stream));
+    RP_HIP(c, hipStreamSynchronize(c->stream));
+    c->state = 1;
+    return RIPPLE_OK;
+}
+
+extern "C" void ripple_destroy(ripple_ctx *c) {
+    if (!c) return;
+    hipStreamSynchronize(c->stream);
+    void *ptrs[] = {c->out_meta, c->in_meta, c->out_capv, c->in_capv, c->vstate, c->pend_out, c->pend_in, c->dead_out,
+                    c->dead_in, c->out_pool, c->in_pool, c->alive, c->part_cnt, c->part_deg, c->ctr, c->D[0], c->D[1],
+                    c->tmp, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ops_d, c->payload_d,
+                    c->op_status, c->op_pos_out, c->op_pos_in, c->touch_out, c->touch_in, c->exp_kind, c->exp_a,
+                    c->exp_b, c->st_src, c->st_dst, c->st_sign, c->gather_d, c->gather_ids};
+    for (void *p : ptrs)
+        if (p) hipFree(p);
+    for (uint32_t l = 0; l <= RIPPLE_MAX_LAYERS; ++l) {
+        if (c->H[l]) hipFree(c->H[l]);
+        if (c->X[l]) hipFree(c->X[l]);
+    }
+    for (uint32_t l = 0; l < c->L; ++l) {
+        LayerDev &ly = c->layers[l];
+        void *w[] = {ly.W0, ly.b0, ly.W1, ly.b1, ly.W0h, ly.W1h};
+        for (void *p : w)
+            if (p) hipFree(p);
+    }
+    if (c->ctr_host) hipHostFree(c->ctr_host);
+    if (c->ops_pin) hipHostFree(c->ops_pin);
+    if (c->payload_pin) hipHostFree(c->payload_pin);
+    if (c->timer) {
+        for (hipEvent_t e : c->timer->ev) hipEventDestroy(e);
+        delete c->timer;
+    }
+    delete c;
+}
+
+extern "C" const char *ripple_last_error(const ripple_ctx *c) { return c ? c->err.c_str() : ""; }
+
+// ---------------------------------------------------------------------------------
+// model
+// ---------------------------------------------------------------------------------
+static uint32_t pad_n(uint32_t n) { return n <= 64 ? 64u : (n <= 128 ? 128u : rp_round_up(n, 256)); }
+
+static ripple_status upload_padded(ripple_ctx *c, const float *w, const float *b, uint32_t K, uint32_t N,
+                                   uint32_t Kpad, uint32_t Npad, float **W_d, float **b_d) {
+    std::vector<float> wp((size_t)Kpad * Npad, 0.0f), bp(Npad, 0.0f);
+    for (uint32_t k = 0; k < K; ++k) memcpy(&wp[(size_t)k * Npad], &w[(size_t)k * N], (size_t)N * 4);
+    memcpy(bp.data(), b, (size_t)N * 4);
+    RP_TRY(dev_alloc(c, W_d, wp.size(), false));
+    RP_TRY(dev_alloc(c, b_d, bp.size(), false));
+    RP_HIP(c, hipMemcpy(*W_d, wp.data(), wp.size() * 4, hipMemcpyHostToDevice));
+    RP_HIP(c, hipMemcpy(*b_d, bp.data(), bp.size() * 4, hipMemcpyHostToDevice));
+    return RIPPLE_OK;
+}
+
+extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, const ripple_layer_desc *layers) {
+    if (!c) return RIPPLE_EINVAL;
+    if (c->state != 1) return fail(c, RIPPLE_ESTATE, "load_model needs a context fresh from init_graph");
+    if (!layers || n_layers == 0 || n_layers > RIPPLE_MAX_LAYERS) return fail(c, RIPPLE_EINVAL, "bad layer count");
+    uint32_t prev = c->d[0];
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        const ripple_layer_desc &s = layers[l];
+        if (s.d_in != prev || s.d_out == 0 || s.d_out > 1024 || s.d_hidden > 1024 || s.agg > RIPPLE_AGG_MEAN ||
+            s.self_mode > RIPPLE_SELF_ADD || s.act_inner > RIPPLE_ACT_RELU || s.act_out > RIPPLE_ACT_RELU || !s.W0 ||
+            !s.b0 || (s.d_hidden && (!s.W1 || !s.b1)))
+            return fail(c, RIPPLE_EINVAL, "bad layer descriptor (widths must chain, dims <= 1024, pointers set)");
+        prev = s.d_out;
+    }
+    c->L = n_layers;
+    c->dmax = c->d[0];
+    c->hmax = 0;
+    for (uint32_t l = 0; l < n_layers; ++l) {
+        const ripple_layer_desc &s = layers[l];
+        LayerDev &ly = c->layers[l];
+        memset(&ly, 0, sizeof(ly));
+        ly.d_in = s.d_in;
+        ly.d_hidden = s.d_hidden;
+        ly.d_out = s.d_out;
+        ly.K = (s.self_mode == RIPPLE_SELF_CONCAT) ? 2 * s.d_in : s.d_in;
+        ly.agg = s.agg;
+        ly.self_mode = s.self_mode;
+        ly.act_inner = s.act_inner;
+        ly.act_out = s.act_out;
+        ly.eps = s.eps;
+        uint32_t n0 = s.d_hidden ? s.d_hidden : s.d_out;
+        ly.K0pad = rp_round_up(ly.K, 32);
+        ly.N0pad = pad_n(n0);
+        RP_TRY(upload_padded(c, s.W0, s.b0, ly.K, n0, ly.K0pad, ly.N0pad, &ly.W0, &ly.b0));
+        if (s.d_hidden) {
+            ly.K1pad = rp_round_up(s.d_hidden, 32);
+            ly.N1pad = pad_n(s.d_out);
+            RP_TRY(upload_padded(c, s.W1, s.b1, s.d_hidden, s.d_out, ly.K1pad, ly.N1pad, &ly.W1, &ly.b1));
+        }
+        c->d[l + 1] = s.d_out;
+        c->dmax = std::max(c->dmax, s.d_out);
+        c->hmax = std::max(c->hmax, s.d_hidden);
+    }
+    const size_t n = c->n_cap;
+    for (uint32_t l = 1; l <= c->L; ++l) {
+        void *h = nullptr;
+        size_t bytes = n * c->d[l] * elem_size(c);
+        if (hipMalloc(&h, bytes) != hipSuccess) return fail(c, RIPPLE_ENOMEM, "device allocation of H failed");
+        c->H[l] = h;
+        RP_HIP(c, hipMemsetAsync(h, 0, bytes, c->stream));
+        RP_TRY(dev_alloc(c, &c->X[l], n * c->d[l - 1], true));
+    }
+    RP_TRY(dev_alloc(c, &c->D[0], n * c->dmax, false));
+    RP_TRY(dev_alloc(c, &c->D[1], n * c->dmax, false));
+    if (c->hmax) RP_TRY(dev_alloc(c, &c->tmp, n * c->hmax, false));
+    // bitmaps: layers 0..L, then S, then V_added, contiguous; reporting copies separately
+    uint32_t *bmall = nullptr, *repall = nullptr, *lists = nullptr, *eoffs = nullptr;
+    RP_TRY(dev_alloc(c, &bmall, (size_t)c->n_words * (c->L + 3), true));
+    RP_TRY(dev_alloc(c, &repall, (size_t)c->n_words * (c->L + 1), true));
+    RP_TRY(dev_alloc(c, &lists, (n + 1) * (c->L + 1), true));
+    RP_TRY(dev_alloc(c, &eoffs, (n + 1) * (c->L + 1), true));
+    for (uint32_t l = 0; l <= c->L; ++l) {
+        c->bm[l] = bmall + (size_t)l * c->n_words;
+        c->rep[l] = repall + (size_t)l * c->n_words;
+        c->list[l] = lists + (size_t)l * (n + 1);
+        c->eoff[l] = eoffs + (size_t)l * (n + 1);
+    }
+    c->bm_sink = bmall + (size_t)(c->L + 1) * c->n_words;
+    c->bm_vadd = bmall + (size_t)(c->L + 2) * c->n_words;
+    RP_TRY(dev_alloc(c, &c->all_list, n + 1, true));
+    RP_HIP(c, hipStreamSynchronize(c->stream));
+    c->state = 2;
+    return RIPPLE_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// bootstrap inference
+// ---------------------------------------------------------------------------------
+extern "C" ripple_status ripple_full_infer(ripple_ctx *c) {
+    if (!c) return RIPPLE_EINVAL;
+    if (c->state < 2) return fail(c, RIPPLE_ESTATE, "full_infer needs init_graph and load_model first");
+    // all live vertices as one list (the alive bitmap itself is the source)
+    hipLaunchKernelGGL(k_or_words, dim3(rp_div_up(c->n_words, 256)), dim3(256), 0, c->stream, c->bm[0], c->alive,
+                       c->n_words);
+    rp_launch_bitmap_to_list(c, c->bm[0], c->all_list, &c->ctr->a[0]);
+    for (uint32_t l = 1; l <= c->L; ++l) {
+        rp_launch_pull_all(c, l);
+        rp_launch_transform(c, l, c->all_list, &c->ctr->a[0], false);
+    }
+    rp_launch_batch_reset(c);
+    RP_HIP(c, hipStreamSynchronize(c->stream));
+    RP_HIP(c, hipGetLastError());
+    for (uint32_t l = 0; l <= c->L; ++l) c->last_a[l] = 0;
+    c->last_from_rep = false;
+    c->state = 3;
+    return RIPPLE_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// per-batch driver
+// ---------------------------------------------------------------------------------
+// Flat hash over the keys a sub-batch has touched: edge (u,v) -> present,
+// vertex w -> flags. Entries are valid only for the current generation.
+struct TouchTable {
+    std::vector<uint64_t> keys;
+    std::vector<uint32_t> gen;
+    std::vector<uint8_t> val;
+    uint32_t cur = 1;
+    size_t mask = 0;
+    void reserve(size_t n_keys) {
+        size_t want = 64;
+        while (want < n_keys * 4) want <<= 1;
+        if (want > keys.size()) {
+            keys.assign(want, 0);
+            gen.assign(want, 0);
+            val.assign(want, 0);
+            cur = 1;
+        }
+        mask = keys.size() - 1;
+    }
+    void next_generation() {
+        if (++cur == 0) {
+            std::fill(gen.begin(), gen.end(), 0);
+            cur = 1;
+        }
+    }
+    uint8_t *find(uint64_t key, bool insert) {
+        size_t h = (size_t)((key * 0x9E3779B97F4A7C15ull) >> 20) & mask;
+        for (;;) {
+            if (gen[h] != cur) {
+                if (!insert) return nullptr;
+                gen[h] = cur;
+                keys[h] = key;
+                val[h] = 0;
+                return &val[h];
+            }
+            if (keys[h] == key) return &val[h];
+            h = (h + 1) & mask;
+        }
+    }
+};
+
+#define TF_EDGE_REF 1
+#define TF_FEAT 2
+#define TF_VADD 4
+#define TF_VDEL 8
+
+struct SubBatch {
+    uint32_t begin, end;
+    bool has_vdel, has_vertex_or_feat;
+};
+
+// Cut the batch where an operation depends on an earlier one of the same piece, so that every
+// piece can be applied in parallel with the same result as applying it in array order.
+static void split_batch(const ripple_update *ops, uint32_t n, TouchTable &tt, std::vector<SubBatch> &out) {
+    out.clear();
+    tt.reserve((size_t)n * 3 + 16);
+    tt.next_generation();
+    SubBatch cur{0, 0, false, false};
+    const uint64_t VKEY = 0x8000000000000000ull;
+    for (uint32_t i = 0; i < n; ++i) {
+        const ripple_update &op = ops[i];
+        for (int attempt = 0; attempt < 2; ++attempt) {
+            bool conflict = false;
+            if (op.kind == RIPPLE_EDGE_ADD || op.kind == RIPPLE_EDGE_DEL) {
+                uint64_t ek = ((uint64_t)op.u << 32) | op.v;
+                uint8_t *fu = tt.find(VKEY | op.u, false), *fv = tt.find(VKEY | op.v, false);
+                if (tt.find(ek, false) || (fu && (*fu & TF_VDEL)) || (fv && (*fv & TF_VDEL))) conflict = true;
+                else {
+                    *tt.find(ek, true) = 1;
+                    *tt.find(VKEY | op.u, true) |= TF_EDGE_REF;
+                    *tt.find(VKEY | op.v, true) |= TF_EDGE_REF;
+                }
+            } else {
+                uint8_t *f = tt.find(VKEY | op.u, false);
+                uint8_t flags = f ? *f : 0;
+                if (op.kind == RIPPLE_FEAT_UPDATE) {
+                    if (flags & (TF_FEAT | TF_VADD | TF_VDEL)) conflict = true;
+                    else *tt.find(VKEY | op.u, true) |= TF_FEAT;
+                } else {
+                    if (flags) conflict = true;
+                    else *tt.find(VKEY | op.u, true) |= (op.kind == RIPPLE_VERTEX_ADD ? TF_VADD : TF_VDEL);
+                }
+            }
+            if (!conflict) break;
+            cur.end = i;                       // close the piece before this operation and start afresh
+            out.push_back(cur);
+            cur = SubBatch{i, i, false, false};
+            tt.next_generation();
+        }
+        if (op.kind == RIPPLE_VERTEX_DEL) cur.has_vdel = true;
+        if (op.kind >= RIPPLE_VERTEX_ADD) cur.has_vertex_or_feat = true;
+    }
+    cur.end = n;
+    if (cur.end > cur.begin || out.empty()) out.push_back(cur);
+}
+
+static ripple_status ensure_batch_buffers(ripple_ctx *c, uint32_t n_ops, uint32_t n_feat, uint32_t want_exp) {
+    if (n_ops > c->ops_cap || want_exp > c->exp_cap) {
+        RP_HIP(c, hipStreamSynchronize(c->stream));
+        uint32_t cap = std::max<uint32_t>(std::max<uint32_t>(n_ops, c->ops_cap), 4096);
+        cap = rp_round_up(cap + cap / 2, 1024);
+        uint32_t exp = std::max<uint32_t>(std::max<uint32_t>(want_exp, c->exp_cap), 1u << 20);
+        void *old[] = {c->ops_d, c->op_status, c->op_pos_out, c->op_pos_in, c->touch_out, c->touch_in, c->exp_kind,
+                       c->exp_a, c->exp_b, c->st_src, c->st_dst, c->st_sign};
+        for (void *p : old)
+            if (p) hipFree(p);
+        c->ops_cap = c->exp_cap = c->touch_cap = c->struct_cap = 0;
+        RP_TRY(dev_alloc(c, &c->ops_d, cap, false));
+        RP_TRY(dev_alloc(c, &c->op_status, cap, true));
+        RP_TRY(dev_alloc(c, &c->op_pos_out, cap, true));
+        RP_TRY(dev_alloc(c, &c->op_pos_in, cap, true));
+        RP_TRY(dev_alloc(c, &c->touch_out, (size_t)cap + exp, false));
+        RP_TRY(dev_alloc(c, &c->touch_in, (size_t)cap + exp, false));
+        RP_TRY(dev_alloc(c, &c->exp_kind, exp, false));
+        RP_TRY(dev_alloc(c, &c->exp_a, exp, false));
+        RP_TRY(dev_alloc(c, &c->exp_b, exp, false));
+        RP_TRY(dev_alloc(c, &c->st_src, (size_t)cap + exp, false));
+        RP_TRY(dev_alloc(c, &c->st_dst, (size_t)cap + exp, false));
+        RP_TRY(dev_alloc(c, &c->st_sign, (size_t)cap + exp, false));
+        c->ops_cap = cap;
+        c->exp_cap = exp;
+        c->touch_cap = cap + exp;
+        c->struct_cap = cap + exp;
+    }
+    if (n_ops > c->pin_ops_cap) {
+        if (c->ops_pin) hipHostFree(c->ops_pin);
+        c->ops_pin = nullptr;
+        c->pin_ops_cap = 0;
+        RP_HIP(c, hipHostMalloc((void **)&c->ops_pin, (size_t)c->ops_cap * sizeof(ripple_update), hipHostMallocDefault));
+        c->pin_ops_cap = c->ops_cap;
+    }
+    if (n_feat > c->feat_cap) {
+        RP_HIP(c, hipStreamSynchronize(c->stream));
+        uint32_t cap = rp_round_up(std::max<uint32_t>(n_feat + n_feat / 2, 1024), 256);
+        if (c->payload_d) hipFree(c->payload_d);
+        if (c->payload_pin) hipHostFree(c->payload_pin);
+        c->payload_d = nullptr;
+        c->payload_pin = nullptr;
+        c->feat_cap = 0;
+        RP_TRY(dev_alloc(c, &c->payload_d, (size_t)cap * c->d[0], false));
+        RP_HIP(c, hipHostMalloc((void **)&c->payload_pin, (size_t)cap * c->d[0] * 4, hipHostMallocDefault));
+        c->feat_cap = cap;
+    }
+    return RIPPLE_OK;
+}
+
+static bool layer_self(const ripple_ctx *c, uint32_t l) { return c->layers[l - 1].self_mode != RIPPLE_SELF_NONE; }
+
+// Enqueue one conflict-free piece: Apply, then hop by hop frontier / scatter / transform.
+static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
+    const uint32_t n = sb.end - sb.begin;
+    int t = rp_timer_begin(c);
+    rp_launch_batch_reset(c);
+    rp_launch_mutate(c, n, sb.has_vdel, sb.has_vertex_or_feat);
+    rp_launch_list_eoff(c, 0);
+    rp_timer_end(c, t, RIPPLE_PH_INGEST, 0);
+    if (multi)
+        hipLaunchKernelGGL(k_or_words, dim3(rp_div_up(c->n_words, 256)), dim3(256), 0, c->stream, c->rep[0], c->bm[0],
+                           c->n_words);
+    for (uint32_t l = 1; l <= c->L; ++l) {
+        t = rp_timer_begin(c);
+        rp_launch_frontier_mark(c, l, layer_self(c, l) ? 1 : 0);
+        rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
+        t = rp_timer_begin(c);
+        rp_launch_scatter_push(c, l);
+        rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l);
+        t = rp_timer_begin(c);
+        rp_launch_frontier_compact(c, l, true, l < c->L, multi);
+        rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l);
+        t = rp_timer_begin(c);
+        rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], l < c->L);
+        rp_timer_end(c, t, RIPPLE_PH_TRANSFORM, (int)l);
+    }
+}
+
+extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update *ops, uint32_t n_ops,
+                                              const float *feat_payload, uint32_t n_feat_rows,
+                                              ripple_batch_result *res) {
+    if (!c) return RIPPLE_EINVAL;
+    if (c->state != 3) return fail(c, RIPPLE_ESTATE, "apply_updates needs full_infer first");
+    if ((n_ops && !ops) || (n_feat_rows && !feat_payload)) return fail(c, RIPPLE_EINVAL, "null batch pointer");
+    if (res) memset(res, 0, sizeof(*res));
+    static thread_local TouchTable tt;
+    static thread_local std::vector<SubBatch> pieces;
+    hipStream_t s = c->stream;
+    int t_total = rp_timer_begin(c);
+
+    RP_TRY(ensure_batch_buffers(c, n_ops, n_feat_rows, 0));
+    // operations are needed on the host (validation, conflict analysis)
+    const ripple_update *hops = ops;
+    if (n_ops && is_device_ptr(ops)) {
+        RP_HIP(c, hipMemcpyAsync(c->ops_pin, ops, (size_t)n_ops * sizeof(ripple_update), hipMemcpyDeviceToHost, s));
+        RP_HIP(c, hipStreamSynchronize(s));
+        hops = c->ops_pin;
+    }
+    for (uint32_t i = 0; i < n_ops; ++i) {
+        const ripple_update &op = hops[i];
+        bool bad = op.kind > RIPPLE_FEAT_UPDATE || op.u >= c->n_cap;
+        if (!bad && op.kind <= RIPPLE_EDGE_DEL) bad = op.v >= c->n_cap;
+        if (!bad && (op.kind == RIPPLE_VERTEX_ADD || op.kind == RIPPLE_FEAT_UPDATE)) bad = op.feat_row >= n_feat_rows;
+        if (bad) return fail(c, RIPPLE_EINVAL, "operation with unknown kind, vertex id or payload row out of range");
+    }
+    if (n_ops == 0) {                              // nothing to do: the affected sets become empty
+        rp_launch_batch_reset(c);
+        RP_HIP(c, hipMemcpyAsync(c->ctr_host, c->ctr, sizeof(DevCtr), hipMemcpyDeviceToHost, s));
+        RP_HIP(c, hipStreamSynchronize(s));
+        for (uint32_t l = 0; l <= c->L; ++l) c->last_a[l] = 0;
+        c->last_from_rep = false;
+        if (res) {
+            res->n_sub_batches = 0;
+            res->n_alive = c->ctr_host->n_alive;
+            res->n_edges = c->ctr_host->n_edges;
+        }
+        return RIPPLE_OK;
+    }
+    split_batch(hops, n_ops, tt, pieces);
+    const bool multi = pieces.size() > 1;
+    if (hops != c->ops_pin) memcpy(c->ops_pin, hops, (size_t)n_ops * sizeof(ripple_update));
+
+    // payload: used in place when it already lives on the device
+    float *payload_saved = c->payload_d;
+    if (n_feat_rows) {
+        size_t bytes = (size_t)n_feat_rows * c->d[0] * 4;
+        if (is_device_ptr(feat_payload)) {
+            c->payload_d = const_cast<float *>(feat_payload);
+        } else {
+            memcpy(c->payload_pin, feat_payload, bytes);
+            RP_HIP(c, hipMemcpyAsync(c->payload_d, c->payload_pin, bytes, hipMemcpyHostToDevice, s));
+        }
+    }
+    if (multi)
+        RP_HIP(c, hipMemsetAsync(c->rep[0], 0, (size_t)c->n_words * (c->L + 1) * 4, s));
+
+    ripple_status rc = RIPPLE_OK;
+    uint32_t applied = 0, rejected = 0, n_struct = 0, compactions = 0;
+    uint64_t msgs[RIPPLE_MAX_LAYERS + 1] = {0};
+    for (size_t p = 0; p < pieces.size() && rc == RIPPLE_OK; ++p) {
+        const SubBatch &sb = pieces[p];
+        const uint32_t n = sb.end - sb.begin;
+        for (int attempt = 0;; ++attempt) {
+            RP_HIP(c, hipMemcpyAsync(c->ops_d, c->ops_pin + sb.begin, (size_t)n * sizeof(ripple_update),
+                                     hipMemcpyHostToDevice, s));
+            enqueue_piece(c, sb, multi);
+            RP_HIP(c, hipMemcpyAsync(c->ctr_host, c->ctr, sizeof(DevCtr), hipMemcpyDeviceToHost, s));
+            RP_HIP(c, hipStreamSynchronize(s));
+            const DevCtr &h = *c->ctr_host;
+            if (!h.abort_flag) break;
+            if (h.abort_flag & 8u) {
+                c->err = "graph store consistency error " + std::to_string(h.error);
+                rc = RIPPLE_EDEVICE;
+                break;
+            }
+            if (h.abort_flag & 2u) {
+                rc = fail(c, RIPPLE_ECAPACITY, "edge capacity exceeded");
+                break;
+            }
+            if (attempt >= 2) {
+                rc = fail(c, RIPPLE_ECAPACITY, "adjacency pool exhausted even after compaction");
+                break;
+            }
+            if (h.abort_flag & 4u) {
+                uint32_t want = h.need_exp + h.need_exp / 2 + 1024;
+                ripple_status r2 = ensure_batch_buffers(c, c->ops_cap, 0, want);
+                if (r2 != RIPPLE_OK) {
+                    rc = r2;
+                    break;
+                }
+            }
+            if (h.abort_flag & 1u) {
+                ripple_status r2 = rp_compact(c);
+                ++compactions;
+                if (r2 != RIPPLE_OK) {
+                    rc = r2;
+                    break;
+                }
+            }
+        }
+        if (rc != RIPPLE_OK) break;
+        const DevCtr &h = *c->ctr_host;
+        applied += h.n_applied;
+        rejected += h.n_rejected;
+        n_struct += h.n_struct;
+        for (uint32_t l = 1; l <= c->L; ++l) msgs[l] += h.m[l];
+        if (!multi)
+            for (uint32_t l = 0; l <= c->L; ++l) c->last_a[l] = h.a[l];
+    }
+    c->payload_d = payload_saved;
+    if (rc != RIPPLE_OK) return rc;
+    RP_HIP(c, hipGetLastError());
+    if (multi) {                                   // sizes of the united sets
+        for (uint32_t l = 0; l <= c->L; ++l) rp_launch_bitmap_to_list(c, c->rep[l], c->all_list, &c->ctr->a[l]);
+        RP_HIP(c, hipMemcpyAsync(c->ctr_host, c->ctr, sizeof(DevCtr), hipMemcpyDeviceToHost, s));
+        RP_HIP(c, hipStreamSynchronize(s));
+        for (uint32_t l = 0; l <= c->L; ++l) c->last_a[l] = c->ctr_host->a[l];
+    }
+    c->last_from_rep = multi;
+    rp_timer_end(c, t_total, RIPPLE_PH_TOTAL, 0);
+    if (c->opt_timing) {
+        RP_HIP(c, hipStreamSynchronize(s));
+        timer_collect(c);
+        c->stats.batches += 1;
+        for (uint32_t l = 0; l <= c->L; ++l) {
+            c->stats.rows[l] += c->last_a[l];
+            c->stats.msgs[l] += msgs[l];
+        }
+    }
+    if (res) {
+        res->n_ops = n_ops;
+        res->n_applied = applied;
+        res->n_rejected = rejected;
+        res->n_sub_batches = (uint32_t)pieces.size();
+        res->n_compactions = compactions;
+        res->n_alive = c->ctr_host->n_alive;
+        res->n_edges = c->ctr_host->n_edges;
+        res->n_structural = n_struct;
+        for (uint32_t l = 0; l <= c->L; ++l) {
+            res->affected[l] = c->last_a[l];
+            res->messages[l] = msgs[l];
+        }
+    }
+    return RIPPLE_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// read-back
+// ---------------------------------------------------------------------------------
+static ripple_status gather_rows(ripple_ctx *c, const void *M, int store, uint32_t d, const uint32_t *ids,
+                                 uint32_t n_ids, float *out) {
+    if (n_ids == 0) return RIPPLE_OK;
+    if (!out) return fail(c, RIPPLE_EINVAL, "null output pointer");
+    hipStream_t s = c->stream;
+    const uint32_t *ids_d = nullptr;
+    if (ids) {
+        if (is_device_ptr(ids)) {
+            ids_d = ids;
+        } else {
+            for (uint32_t i = 0; i < n_ids; ++i)
+                if (ids[i] >= c->n_cap) return fail(c, RIPPLE_EINVAL, "vertex id out of range");
+            if (n_ids > c->gather_ids_cap) {
+                if (c->gather_ids) hipFree(c->gather_ids);
+                c->gather_ids = nullptr;
+                c->gather_ids_cap = 0;
+                RP_TRY(dev_alloc(c, &c->gather_ids, (size_t)n_ids, false));
+                c->gather_ids_cap = n_ids;
+            }
+            RP_HIP(c, hipMemcpyAsync(c->gather_ids, ids, (size_t)n_ids * 4, hipMemcpyHostToDevice, s));
+            ids_d = c->gather_ids;
+        }
+    } else if (n_ids > c->n_cap) {
+        return fail(c, RIPPLE_EINVAL, "more rows requested than vertex_capacity");
+    }
+    if (!ids && !store) {                           // contiguous float32 rows: plain copy
+        RP_HIP(c, hipMemcpyAsync(out, M, (size_t)n_ids * d * 4, hipMemcpyDefault, s));
+        RP_HIP(c, hipStreamSynchronize(s));
+        return RIPPLE_OK;
+    }
+    const size_t chunk_rows = std::max<size_t>(1, ((size_t)64 << 20) / d);
+    const size_t need = std::min<size_t>(chunk_rows, n_ids) * d;
+    if (need > c->gather_cap) {
+        if (c->gather_d) hipFree(c->gather_d);
+        c->gather_d = nullptr;
+        c->gather_cap = 0;
+        RP_TRY(dev_alloc(c, &c->gather_d, need, false));
+        c->gather_cap = need;
+    }
+    for (size_t r0 = 0; r0 < n_ids; r0 += chunk_rows) {
+        size_t rows = std::min<size_t>(chunk_rows, n_ids - r0);
+        uint32_t gb = std::min<uint32_t>(rp_div_up(rows * d, 256), c->n_cu * 16);
+        hipLaunchKernelGGL(k_gather_rows, dim3(gb), dim3(256), 0, s, M, store, d, ids_d ? ids_d + r0 : nullptr,
+                           (uint32_t)r0, rows, c->n_cap, c->gather_d);
+        RP_HIP(c, hipMemcpyAsync(out + r0 * d, c->gather_d, rows * d * 4, hipMemcpyDefault, s));
+        RP_HIP(c, hipStreamSynchronize(s));
+    }
+    return RIPPLE_OK;
+}
+
+extern "C" ripple_status ripple_get_embeddings(ripple_ctx *c, uint32_t layer, const uint32_t *ids, uint32_t n_ids,
+                                               float *out) {
+    if (!c) return RIPPLE_EINVAL;
+    if (c->state < 1 || (layer > 0 && c->state < 3)) return fail(c, RIPPLE_ESTATE, "embeddings not computed yet");
+    if (layer > c->L) return fail(c, RIPPLE_EINVAL, "layer out of range");
+    return gather_rows(c, c->H[layer], c->store, c->d[layer], ids, n_ids, out);
+}
+
+extern "C" ripple_status ripple_get_aggregates(ripple_ctx *c, uint32_t layer, const uint32_t *ids, uint32_t n_ids,
+                                               float *out) {
+    if (!c) return RIPPLE_EINVAL;
+    if (c->state < 3) return fail(c, RIPPLE_ESTATE, "aggregates not computed yet");
+    if (layer == 0 || layer > c->L) return fail(c, RIPPLE_EINVAL, "layer out of range");
+    return gather_rows(c, c->X[layer], 0, c->d[layer - 1], ids, n_ids, out);
+}
+
+extern "C" ripple_status ripple_get_affected(ripple_ctx *c, uint32_t layer, uint32_t *ids_out, uint32_t cap,
+                                             uint32_t *n_out) {
+    if (!c) return RIPPLE_EINVAL;
+    if (c->state != 3) return fail(c, RIPPLE_ESTATE, "no batch has been applied");
+    if (layer > c->L || !n_out || (cap && !ids_out)) return fail(c, RIPPLE_EINVAL, "bad argument");
+    hipStream_t s = c->stream;
+    uint32_t *bitmap = c->last_from_rep ? c->rep[layer] : c->bm[layer];
+    uint32_t *cnt_d = &c->ctr->pad0;               // spare counter word
+    rp_launch_bitmap_to_list(c, bitmap, c->all_list, cnt_d);
+    uint32_t n = 0;
+    RP_HIP(c, hipMemcpyAsync(&n, cnt_d, 4, hipMemcpyDeviceToHost, s));
+    RP_HIP(c, hipStreamSynchronize(s));
+    *n_out = n;
+    uint32_t m = std::min(n, cap);
+    if (m) RP_HIP(c, hipMemcpy(ids_out, c->all_list, (size_t)m * 4, hipMemcpyDeviceToHost));
+    return RIPPLE_OK;
+}
+
+extern "C" ripple_status ripple_export_edges(ripple_ctx *c, int direction, uint32_t *src_out, uint32_t *dst_out,
+                                             uint64_t cap, uint64_t *n_out) {
+    if (!c) return RIPPLE_EINVAL;
+    if (c->state < 1) return fail(c, RIPPLE_ESTATE, "no graph");
+    if (!n_out || (direction != 0 && direction != 1)) return fail(c, RIPPLE_EINVAL, "bad argument");
+    hipStream_t s = c->stream;
+    const uint2 *meta = direction ? c->in_meta : c->out_meta;
+    const uint32_t *pool = direction ? c->in_pool : c->out_pool;
+    uint32_t *len = nullptr, *off = nullptr, *total_d = nullptr, *sd = nullptr, *dd = nullptr;
+    RP_TRY(dev_alloc(c, &len, (size_t)c->n_cap, false));
+    RP_TRY(dev_alloc(c, &off, (size_t)c->n_cap, false));
+    RP_TRY(dev_alloc(c, &total_d, 16, true));
+    uint32_t vb = rp_div_up(c->n_cap, 256);
+    hipLaunchKernelGGL(k_meta_len2, dim3(vb), dim3(256), 0, s, meta, c->n_cap, len);
+    rp_exclusive_scan(s, len, off, c->n_cap, c->part_cnt, total_d);
+    uint32_t total = 0;
+    RP_HIP(c, hipMemcpyAsync(&total, total_d, 4, hipMemcpyDeviceToHost, s));
+    RP_HIP(c, hipStreamSynchronize(s));
+    *n_out = total;
+    ripple_status rc = RIPPLE_OK;
+    if (total && total <= cap) {
+        if (!src_out || !dst_out) rc = fail(c, RIPPLE_EINVAL, "null output pointer");
+        else {
+            rc = dev_alloc(c, &sd, (size_t)total, false);
+            if (rc == RIPPLE_OK) rc = dev_alloc(c, &dd, (size_t)total, false);
+            if (rc == RIPPLE_OK) {
+                hipLaunchKernelGGL(k_export_rows, dim3(c->n_cu * 8), dim3(256), 0, s, meta, pool, off, c->n_cap,
+                                   direction, sd, dd);
+                hipMemcpyAsync(src_out, sd, (size_t)total * 4, hipMemcpyDeviceToHost, s);
+                hipMemcpyAsync(dst_out, dd, (size_t)total * 4, hipMemcpyDeviceToHost, s);
+                if (hipStreamSynchronize(s) != hipSuccess) rc = fail(c, RIPPLE_EDEVICE, "export failed");
+            }
+        }
+    }
+    hipFree(len);
+    hipFree(off);
+    hipFree(total_d);
+    if (sd) hipFree(sd);
+    if (dd) hipFree(dd);
+    return rc;
+}
+
+extern "C" ripple_status ripple_get_degrees(ripple_ctx *c, int direction, uint32_t *deg_out, uint8_t *alive_out) {
+    if (!c) return RIPPLE_EINVAL;
+    if (c->state < 1) return fail(c, RIPPLE_ESTATE, "no graph");
+    if (direction != 0 && direction != 1) return fail(c, RIPPLE_EINVAL, "bad direction");
+    hipStream_t s = c->stream;
+    if (deg_out) {
+        uint32_t *len = nullptr;
+        RP_TRY(dev_alloc(c, &len, (size_t)c->n_cap, false));
+        hipLaunchKernelGGL(k_meta_len2, dim3(rp_div_up(c->n_cap, 256)), dim3(256), 0, s,
+                           direction ? c->in_meta : c->out_meta, c->n_cap, len);
+        hipMemcpyAsync(deg_out, len, (size_t)c->n_cap * 4, hipMemcpyDeviceToHost, s);
+        hipError_t e = hipStreamSynchronize(s);
+        hipFree(len);
+        if (e != hipSuccess) return fail(c, RIPPLE_EDEVICE, "degree read-back failed");
+    }
+    if (alive_out) {
+        std::vector<uint32_t> bm(c->n_words);
+        RP_HIP(c, hipMemcpy(bm.data(), c->alive, (size_t)c->n_words * 4, hipMemcpyDeviceToHost));
+        for (uint32_t v = 0; v < c->n_cap; ++v) alive_out[v] = (bm[v >> 5] >> (v & 31)) & 1u;
+    }
+    return RIPPLE_OK;
+}
+
+extern "C" ripple_status ripple_compact(ripple_ctx *c) {
+    if (!c) return RIPPLE_EINVAL;
+    if (c->state < 1) return fail(c, RIPPLE_ESTATE, "no graph");
+    return rp_compact(c);
+}
+
+extern "C" ripple_status ripple_set_option(ripple_ctx *c, int option, int64_t value) {
+    if (!c) return RIPPLE_EINVAL;
+    switch (option) {
+    case RIPPLE_OPT_TIMING: c->opt_timing = value ? 1 : 0; return RIPPLE_OK;
+    case RIPPLE_OPT_SCATTER_MODE:
+        if (value < 0 || value > 2) return fail(c, RIPPLE_EINVAL, "scatter mode must be 0, 1 or 2");
+        c->opt_scatter = (int)value;
+        return RIPPLE_OK;
+    default: return fail(c, RIPPLE_EINVAL, "unknown option");
+    }
+}
+
+extern "C" ripple_status ripple_get_stats(ripple_ctx *c, ripple_stats *out, int reset) {
+    if (!c || !out) return RIPPLE_EINVAL;
+    *out = c->stats;
+    if (reset) memset(&c->stats, 0, sizeof(c->stats));
+    return RIPPLE_OK;
+}

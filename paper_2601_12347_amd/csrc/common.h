@@ -1,0 +1,172 @@
+// Internal definitions shared by the host code and the gfx950 kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <hip/hip_bf16.h>
+#include <stdint.h>
+#include <string>
+#include <vector>
+
+#include "../../include/ripple.h"
+
+#define RP_TOMB 0xFFFFFFFFu          // hole left in an adjacency row by a deletion
+#define RP_WAVE 64
+
+// per-vertex scratch bits kept in vstate[] while a batch is being applied
+#define VS_TOUCH_OUT 1u              // out-row is on the touched list
+#define VS_TOUCH_IN 2u
+#define VS_ADDING 4u                 // created by this (sub-)batch
+#define VS_DYING 8u                  // deleted by this (sub-)batch
+
+// expanded edge of a deleted vertex
+#define EXP_NONE 0u
+#define EXP_OUT 1u                   // (w -> y): erase w from y's in-row
+#define EXP_IN 2u                    // (x -> w): erase w from x's out-row
+
+struct DevCtr {                      // device-resident counters, one instance per context
+    uint32_t a[RIPPLE_MAX_LAYERS + 1];        // |A_l|
+    uint32_t m[RIPPLE_MAX_LAYERS + 1];        // out-edges walked from A_{l-1}
+    uint32_t n_struct;
+    uint32_t n_touch_out, n_touch_in;
+    uint32_t n_exp;                           // expanded edges of deleted vertices
+    uint32_t need_exp;                        // upper bound of n_exp computed while validating
+    uint32_t n_applied, n_rejected;
+    uint32_t n_add, n_del;                    // accepted edge adds / deletes (ops only)
+    uint32_t need_out, need_in;               // pool entries relocation will take
+    uint32_t out_top, in_top;                 // first free pool entry
+    uint32_t n_alive;
+    uint32_t n_vadd;
+    uint32_t abort_flag;                      // written by k_decide: 0 ok, bit0 pool, bit1 edges, bit2 scratch
+    uint32_t pad0;
+    unsigned long long n_edges;
+    uint32_t error;                           // sticky consistency error seen by a kernel
+    uint32_t pad1;
+};
+
+struct LayerDev {
+    uint32_t d_in, d_hidden, d_out, K;        // K = rows of W0
+    uint32_t agg, self_mode, act_inner, act_out;
+    float eps;
+    // weights padded to [Kpad x Npad] (Kpad multiple of 32, Npad multiple of 64), zero filled
+    float *W0, *b0, *W1, *b1;
+    __hip_bfloat16 *W0h, *W1h;                // bf16 copies (bf16 store only)
+    uint32_t K0pad, N0pad, K1pad, N1pad;
+};
+
+struct PhaseTimer;
+
+struct ripple_ctx {
+    int device = 0;
+    hipStream_t stream = nullptr;
+    std::string err;
+    int state = 0;                             // 1 graph, 2 model, 3 inferred
+    uint32_t n_cap = 0, n_words = 0;           // vertex capacity, bitmap words
+    uint64_t e_cap = 0;
+    uint64_t pool_cap = 0;
+    int store = 0;                             // ripple_store
+    uint32_t L = 0;
+    uint32_t d[RIPPLE_MAX_LAYERS + 1] = {0};
+    uint32_t dmax = 0, hmax = 0;               // widest layer / widest hidden
+    LayerDev layers[RIPPLE_MAX_LAYERS];
+
+    // graph store
+    uint2 *out_meta = nullptr, *in_meta = nullptr;      // {start, len} per vertex
+    uint32_t *out_capv = nullptr, *in_capv = nullptr;   // row capacity
+    uint32_t *out_pool = nullptr, *in_pool = nullptr;
+    uint32_t *alive = nullptr;                          // bitmap
+    uint32_t *vstate = nullptr;                         // VS_* bits, zero between batches
+    uint32_t *pend_out = nullptr, *pend_in = nullptr;   // appended this batch
+    uint32_t *dead_out = nullptr, *dead_in = nullptr;   // tombstones this batch
+
+    // embeddings and cached sums
+    void *H[RIPPLE_MAX_LAYERS + 1] = {nullptr};
+    float *X[RIPPLE_MAX_LAYERS + 1] = {nullptr};
+    float *D[2] = {nullptr, nullptr};                   // compact delta rows, ping-pong
+    float *tmp = nullptr;                               // hidden activations of two-stage updates
+
+    // frontier
+    uint32_t *bm[RIPPLE_MAX_LAYERS + 1] = {nullptr};    // dirty bitmap per layer
+    uint32_t *bm_sink = nullptr, *bm_vadd = nullptr;    // S and V_added
+    uint32_t *rep[RIPPLE_MAX_LAYERS + 1] = {nullptr};   // union over sub-batches (reporting)
+    uint32_t *list[RIPPLE_MAX_LAYERS + 1] = {nullptr};  // A_l, ascending (l >= 1); op order for l = 0
+    uint32_t *eoff[RIPPLE_MAX_LAYERS + 1] = {nullptr};  // exclusive scan of out-degrees over A_l, +1 entry
+    uint32_t *part_cnt = nullptr, *part_deg = nullptr;  // per-block partial sums of the compaction
+    uint32_t n_part = 0;
+    uint32_t *all_list = nullptr;                       // scratch list (live vertices) for full inference
+
+    // batch staging
+    uint32_t ops_cap = 0, feat_cap = 0;
+    ripple_update *ops_d = nullptr;
+    float *payload_d = nullptr;
+    uint32_t *op_status = nullptr, *op_pos_out = nullptr, *op_pos_in = nullptr;
+    uint32_t *touch_out = nullptr, *touch_in = nullptr;  // touched row lists
+    uint32_t touch_cap = 0;
+    uint32_t exp_cap = 0;
+    uint32_t *exp_kind = nullptr, *exp_a = nullptr, *exp_b = nullptr;
+    uint32_t struct_cap = 0;
+    uint32_t *st_src = nullptr, *st_dst = nullptr;
+    float *st_sign = nullptr;
+    DevCtr *ctr = nullptr;
+    DevCtr *ctr_host = nullptr;                         // pinned mirror
+    ripple_update *ops_pin = nullptr;                   // pinned staging for ops
+    float *payload_pin = nullptr;
+    uint32_t pin_ops_cap = 0, pin_feat_cap = 0;
+
+    // gather staging for get_* calls
+    float *gather_d = nullptr;
+    uint32_t *gather_ids = nullptr;
+    size_t gather_cap = 0, gather_ids_cap = 0;
+
+    // last batch's sets (reporting)
+    uint32_t last_a[RIPPLE_MAX_LAYERS + 1] = {0};
+    bool last_from_rep = false;
+
+    // options
+    int opt_timing = 0;
+    int opt_scatter = 0;
+    ripple_stats stats;
+    PhaseTimer *timer = nullptr;
+    uint32_t n_cu = 256;
+};
+
+// ---- host helpers -----------------------------------------------------------------
+#define RP_HIP(ctx, call)                                                              \
+    do {                                                                               \
+        hipError_t e__ = (call);                                                       \
+        if (e__ != hipSuccess) {                                                       \
+            (ctx)->err = std::string(#call) + ": " + hipGetErrorString(e__);          \
+            return RIPPLE_EDEVICE;                                                     \
+        }                                                                              \
+    } while (0)
+
+static inline uint32_t rp_div_up(uint64_t a, uint64_t b) { return (uint32_t)((a + b - 1) / b); }
+static inline uint32_t rp_round_up(uint32_t a, uint32_t b) { return (a + b - 1) / b * b; }
+
+// ---- device helpers -----------------------------------------------------------------
+#ifdef __HIPCC__
+__device__ __forceinline__ int rp_lane() { return threadIdx.x & 63; }
+__device__ __forceinline__ bool rp_bit(const uint32_t *bm, uint32_t v) { return (bm[v >> 5] >> (v & 31)) & 1u; }
+__device__ __forceinline__ void rp_set_bit(uint32_t *bm, uint32_t v) {
+    uint32_t m = 1u << (v & 31);
+    if (!(bm[v >> 5] & m)) atomicOr(&bm[v >> 5], m);
+}
+__device__ __forceinline__ float rp_bf2f(__hip_bfloat16 x) { return __bfloat162float(x); }
+__device__ __forceinline__ float rp_load_h(const void *H, int store, size_t idx) {
+    return store ? __bfloat162float(((const __hip_bfloat16 *)H)[idx]) : ((const float *)H)[idx];
+}
+__device__ __forceinline__ uint32_t rp_row_cap(uint32_t need) {   // capacity given to a relocated row
+    uint32_t c = need + (need >> 1) + 4u;
+    return (c + 3u) & ~3u;
+}
+// position of `target` in row[0..len), searched by one wavefront; -1 when absent
+__device__ __forceinline__ int rp_wave_find(const uint32_t *row, uint32_t len, uint32_t target) {
+    const int lane = rp_lane();
+    for (uint32_t base = 0; base < len; base += 64) {
+        uint32_t i = base + lane;
+        bool hit = (i < len) && (row[i] == target);
+        unsigned long long m = __ballot(hit);
+        if (m) return (int)(base + __ffsll((long long)m) - 1);
+    }
+    return -1;
+}
+#endif

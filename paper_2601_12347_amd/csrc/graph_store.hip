@@ -1,0 +1,775 @@
+// GPU-resident graph store: out- and in-adjacency kept as per-vertex rows with
+// slack inside two pools, built from a COO edge list, mutated by batches of
+// updates (the Apply step of Sec. 3.3), and compacted when a pool fills up.
+//
+// A batch is applied in two phases. Validation decides, against the graph as
+// it stands, which operations are accepted and how much pool space they need;
+// nothing is modified. Only if everything fits does the commit phase run:
+// deletions leave tombstones that one wavefront per touched row squeezes out,
+// rows that would overflow move to fresh space at the pool's end, additions
+// are appended. Deleting a vertex expands into deleting its incident edges
+// (Sec. 3.2, vertex deletion). The host guarantees that operations inside one
+// launch sequence never touch the same edge twice nor a vertex that the same
+// sequence adds or deletes (other than a new vertex's own edges), so all
+// operations can be handled in parallel without changing the array-order result.
+#include "common.h"
+#include "kernels.h"
+
+// ---------------------------------------------------------------------------------
+// exclusive scan over uint32 (two kernels: block sums, then per-block prefix + scan)
+// ---------------------------------------------------------------------------------
+#define SCAN_PER_BLOCK 1024
+
+__device__ __forceinline__ uint32_t block_sum_256(uint32_t v, uint32_t *sh) {
+    const int tid = threadIdx.x;
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o);
+    if ((tid & 63) == 0) sh[tid >> 6] = v;
+    __syncthreads();
+    uint32_t t = sh[0] + sh[1] + sh[2] + sh[3];
+    __syncthreads();
+    return t;
+}
+
+__global__ __launch_bounds__(256) void k_scan_partial(const uint32_t *in, uint32_t n, uint32_t *part) {
+    __shared__ uint32_t sh[4];
+    uint32_t base = blockIdx.x * SCAN_PER_BLOCK + threadIdx.x * 4;
+    uint32_t s = 0;
+    for (int k = 0; k < 4; ++k)
+        if (base + k < n) s += in[base + k];
+    uint32_t t = block_sum_256(s, sh);
+    if (threadIdx.x == 0) part[blockIdx.x] = t;
+}
+
+__global__ __launch_bounds__(256) void k_scan_final(const uint32_t *in, uint32_t *out, uint32_t n,
+                                                    const uint32_t *part, uint32_t *total_out) {
+    __shared__ uint32_t sh[4];
+    __shared__ uint32_t wsum[4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t pre = 0;
+    for (uint32_t b = tid; b < blockIdx.x; b += 256) pre += part[b];
+    pre = block_sum_256(pre, sh);
+    uint32_t base = blockIdx.x * SCAN_PER_BLOCK + tid * 4;
+    uint32_t v[4], s = 0;
+    for (int k = 0; k < 4; ++k) {
+        v[k] = (base + k < n) ? in[base + k] : 0u;
+        s += v[k];
+    }
+    uint32_t incl = s;                                  // inclusive scan inside the wavefront
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t t = __shfl_up(incl, o);
+        if (lane >= o) incl += t;
+    }
+    if (lane == 63) wsum[wave] = incl;
+    __syncthreads();
+    uint32_t woff = 0;
+    for (int w = 0; w < wave; ++w) woff += wsum[w];
+    uint32_t run = pre + woff + incl - s;
+    for (int k = 0; k < 4; ++k) {
+        if (base + k < n) out[base + k] = run;
+        run += v[k];
+    }
+    if (total_out && blockIdx.x == gridDim.x - 1 && tid == 255) *total_out = run;
+}
+
+// out[i] = exclusive prefix of in[0..n); *total_out = sum. part: scratch of ceil(n/1024) words.
+void rp_exclusive_scan(hipStream_t s, const uint32_t *in, uint32_t *out, uint32_t n, uint32_t *part,
+                       uint32_t *total_out) {
+    if (n == 0) return;
+    uint32_t nb = rp_div_up(n, SCAN_PER_BLOCK);
+    hipLaunchKernelGGL(k_scan_partial, dim3(nb), dim3(256), 0, s, in, n, part);
+    hipLaunchKernelGGL(k_scan_final, dim3(nb), dim3(256), 0, s, in, out, n, part, total_out);
+}
+
+// ---------------------------------------------------------------------------------
+// build from COO
+// ---------------------------------------------------------------------------------
+__global__ void k_degree_count(const uint32_t *src, const uint32_t *dst, uint64_t n_edges, uint32_t n_vertices,
+                               uint32_t *deg_out, uint32_t *deg_in, uint32_t *err) {
+    uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t e = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_edges; e += stride) {
+        uint32_t s = src[e], d = dst[e];
+        if (s >= n_vertices || d >= n_vertices) {
+            *err = 1;
+            continue;
+        }
+        atomicAdd(&deg_out[s], 1u);
+        atomicAdd(&deg_in[d], 1u);
+    }
+}
+
+__global__ void k_fresh_caps(const uint32_t *len, const uint32_t *alive, uint32_t n_cap, uint32_t *capv) {
+    uint32_t v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= n_cap) return;
+    uint32_t l = len[v];
+    bool live = rp_bit(alive, v);
+    capv[v] = (live || l) ? ((l + (l >> 3) + 4u + 3u) & ~3u) : 0u;
+}
+
+__global__ void k_meta_len(const uint2 *meta, uint32_t n_cap, uint32_t *len) {
+    uint32_t v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v < n_cap) len[v] = meta[v].y;
+}
+
+__global__ void k_init_meta(const uint32_t *start, uint32_t n_cap, uint2 *meta) {
+    uint32_t v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v < n_cap) meta[v] = make_uint2(start[v], 0u);
+}
+
+__global__ void k_fill_rows(const uint32_t *key, const uint32_t *val, uint64_t n_edges, uint2 *meta,
+                            uint32_t *pool) {
+    uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t e = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_edges; e += stride) {
+        uint32_t k = key[e];
+        uint32_t p = atomicAdd(&((uint32_t *)meta)[2 * (size_t)k + 1], 1u);
+        pool[meta[k].x + p] = val[e];
+    }
+}
+
+__global__ void k_set_alive_prefix(uint32_t *alive, uint32_t n_words, uint32_t n_vertices) {
+    uint32_t w = blockIdx.x * blockDim.x + threadIdx.x;
+    if (w >= n_words) return;
+    uint32_t lo = w * 32u;
+    uint32_t bits = 0;
+    if (lo + 32u <= n_vertices) bits = 0xFFFFFFFFu;
+    else if (lo < n_vertices) bits = (1u << (n_vertices - lo)) - 1u;
+    alive[w] = bits;
+}
+
+ripple_status rp_build_graph(ripple_ctx *c, uint32_t n_vertices, uint64_t n_edges, const uint32_t *src_h,
+                             const uint32_t *dst_h) {
+    hipStream_t s = c->stream;
+    uint32_t *src_d = nullptr, *dst_d = nullptr, *tmp = nullptr, *err_d = nullptr;
+    size_t eb = (size_t)(n_edges ? n_edges : 1) * sizeof(uint32_t);
+    RP_HIP(c, hipMalloc(&src_d, eb));
+    RP_HIP(c, hipMalloc(&dst_d, eb));
+    RP_HIP(c, hipMalloc(&tmp, (size_t)c->n_cap * 4 * 2 + 64));
+    RP_HIP(c, hipMalloc(&err_d, 64));
+    RP_HIP(c, hipMemsetAsync(err_d, 0, 64, s));
+    if (n_edges) {
+        RP_HIP(c, hipMemcpyAsync(src_d, src_h, eb, hipMemcpyHostToDevice, s));
+        RP_HIP(c, hipMemcpyAsync(dst_d, dst_h, eb, hipMemcpyHostToDevice, s));
+    }
+    uint32_t *deg_out = tmp, *deg_in = tmp + c->n_cap;
+    RP_HIP(c, hipMemsetAsync(tmp, 0, (size_t)c->n_cap * 8, s));
+    hipLaunchKernelGGL(k_set_alive_prefix, dim3(rp_div_up(c->n_words, 256)), dim3(256), 0, s, c->alive,
+                       c->n_words, n_vertices);
+    uint32_t gb = (uint32_t)std::min<uint64_t>(rp_div_up(n_edges ? n_edges : 1, 256), 65536);
+    hipLaunchKernelGGL(k_degree_count, dim3(gb), dim3(256), 0, s, src_d, dst_d, n_edges, n_vertices, deg_out,
+                       deg_in, err_d);
+    uint32_t vb = rp_div_up(c->n_cap, 256);
+    // caps -> starts, for both directions; pend_* serve as scratch for the scan output
+    hipLaunchKernelGGL(k_fresh_caps, dim3(vb), dim3(256), 0, s, deg_out, c->alive, c->n_cap, c->out_capv);
+    hipLaunchKernelGGL(k_fresh_caps, dim3(vb), dim3(256), 0, s, deg_in, c->alive, c->n_cap, c->in_capv);
+    rp_exclusive_scan(s, c->out_capv, c->pend_out, c->n_cap, c->part_cnt, &c->ctr->out_top);
+    rp_exclusive_scan(s, c->in_capv, c->pend_in, c->n_cap, c->part_deg, &c->ctr->in_top);
+    hipLaunchKernelGGL(k_init_meta, dim3(vb), dim3(256), 0, s, c->pend_out, c->n_cap, c->out_meta);
+    hipLaunchKernelGGL(k_init_meta, dim3(vb), dim3(256), 0, s, c->pend_in, c->n_cap, c->in_meta);
+    uint32_t err_h = 0;
+    RP_HIP(c, hipMemcpyAsync(&err_h, err_d, 4, hipMemcpyDeviceToHost, s));
+    RP_HIP(c, hipMemcpyAsync(c->ctr_host, c->ctr, sizeof(DevCtr), hipMemcpyDeviceToHost, s));
+    RP_HIP(c, hipStreamSynchronize(s));
+    ripple_status rc = RIPPLE_OK;
+    if (err_h) {
+        c->err = "edge endpoint is not a live vertex (id >= n_vertices)";
+        rc = RIPPLE_EINVAL;
+    } else if (c->ctr_host->out_top > c->pool_cap || c->ctr_host->in_top > c->pool_cap) {
+        c->err = "edge_capacity too small for the initial graph";
+        rc = RIPPLE_ECAPACITY;
+    } else if (n_edges) {
+        hipLaunchKernelGGL(k_fill_rows, dim3(gb), dim3(256), 0, s, src_d, dst_d, n_edges, c->out_meta, c->out_pool);
+        hipLaunchKernelGGL(k_fill_rows, dim3(gb), dim3(256), 0, s, dst_d, src_d, n_edges, c->in_meta, c->in_pool);
+    }
+    hipMemsetAsync(c->pend_out, 0, (size_t)c->n_cap * 4, s);
+    hipMemsetAsync(c->pend_in, 0, (size_t)c->n_cap * 4, s);
+    hipStreamSynchronize(s);
+    hipFree(src_d);
+    hipFree(dst_d);
+    hipFree(tmp);
+    hipFree(err_d);
+    if (rc == RIPPLE_OK) RP_HIP(c, hipGetLastError());
+    return rc;
+}
+
+// ---------------------------------------------------------------------------------
+// compaction: fresh caps, scan, copy every row into a new pool
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_copy_rows(uint2 *meta, const uint32_t *new_start, uint32_t n_cap,
+                                                   const uint32_t *old_pool, uint32_t *new_pool) {
+    const int lane = rp_lane();
+    uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    for (uint32_t v = gw; v < n_cap; v += nw) {
+        uint2 m = meta[v];
+        uint32_t ns = new_start[v];
+        for (uint32_t i = lane; i < m.y; i += 64) new_pool[ns + i] = old_pool[m.x + i];
+        if (lane == 0) meta[v] = make_uint2(ns, m.y);
+    }
+}
+
+static ripple_status compact_one(ripple_ctx *c, uint2 *meta, uint32_t *capv, uint32_t **pool, uint32_t *top_d,
+                                 uint32_t *scratch_len, uint32_t *scratch_start) {
+    hipStream_t s = c->stream;
+    uint32_t vb = rp_div_up(c->n_cap, 256);
+    uint32_t *new_pool = nullptr;
+    RP_HIP(c, hipMalloc(&new_pool, (size_t)c->pool_cap * 4));
+    hipLaunchKernelGGL(k_meta_len, dim3(vb), dim3(256), 0, s, meta, c->n_cap, scratch_len);
+    hipLaunchKernelGGL(k_fresh_caps, dim3(vb), dim3(256), 0, s, scratch_len, c->alive, c->n_cap, capv);
+    rp_exclusive_scan(s, capv, scratch_start, c->n_cap, c->part_cnt, top_d);
+    hipLaunchKernelGGL(k_copy_rows, dim3(c->n_cu * 8), dim3(256), 0, s, meta, scratch_start, c->n_cap, *pool,
+                       new_pool);
+    RP_HIP(c, hipStreamSynchronize(s));
+    hipFree(*pool);
+    *pool = new_pool;
+    return RIPPLE_OK;
+}
+
+ripple_status rp_compact(ripple_ctx *c) {
+    // pend_* / dead_* are zero between batches and serve as scratch here
+    ripple_status rc = compact_one(c, c->out_meta, c->out_capv, &c->out_pool, &c->ctr->out_top, c->pend_out,
+                                   c->dead_out);
+    if (rc != RIPPLE_OK) return rc;
+    rc = compact_one(c, c->in_meta, c->in_capv, &c->in_pool, &c->ctr->in_top, c->pend_in, c->dead_in);
+    if (rc != RIPPLE_OK) return rc;
+    hipStream_t s = c->stream;
+    RP_HIP(c, hipMemsetAsync(c->pend_out, 0, (size_t)c->n_cap * 4, s));
+    RP_HIP(c, hipMemsetAsync(c->pend_in, 0, (size_t)c->n_cap * 4, s));
+    RP_HIP(c, hipMemsetAsync(c->dead_out, 0, (size_t)c->n_cap * 4, s));
+    RP_HIP(c, hipMemsetAsync(c->dead_in, 0, (size_t)c->n_cap * 4, s));
+    RP_HIP(c, hipStreamSynchronize(s));
+    return RIPPLE_OK;
+}
+
+// ---------------------------------------------------------------------------------
+// batch application
+// ---------------------------------------------------------------------------------
+struct MutArgs {
+    const ripple_update *ops;
+    uint32_t n_ops;
+    const float *payload;
+    uint32_t *status, *pos_out, *pos_in;
+    uint2 *out_meta, *in_meta;
+    uint32_t *out_capv, *in_capv;
+    uint32_t *out_pool, *in_pool;
+    uint32_t *alive, *vstate;
+    uint32_t *pend_out, *pend_in, *dead_out, *dead_in;
+    uint32_t *touch_out, *touch_in;
+    uint32_t touch_cap;
+    uint32_t *exp_kind, *exp_a, *exp_b;
+    uint32_t exp_cap;
+    uint32_t *st_src, *st_dst;
+    float *st_sign;
+    uint32_t struct_cap;
+    uint32_t *bm0, *bm_sink, *bm_vadd;
+    uint32_t *list0;
+    float *D0;
+    DevCtr *ctr;
+    uint32_t n_cap;
+    unsigned long long e_cap, pool_cap;
+    int store;
+    uint32_t L;
+    uint32_t d[RIPPLE_MAX_LAYERS + 1];
+    void *H[RIPPLE_MAX_LAYERS + 1];
+    float *X[RIPPLE_MAX_LAYERS + 1];
+};
+
+__device__ __forceinline__ void touch_row(const MutArgs &a, uint32_t x, uint32_t bit) {
+    uint32_t old = atomicOr(&a.vstate[x], bit);
+    if (old & bit) return;
+    uint32_t *cnt = (bit == VS_TOUCH_OUT) ? &a.ctr->n_touch_out : &a.ctr->n_touch_in;
+    uint32_t *lst = (bit == VS_TOUCH_OUT) ? a.touch_out : a.touch_in;
+    uint32_t p = atomicAdd(cnt, 1u);
+    if (p < a.touch_cap) lst[p] = x;
+    else a.ctr->error = 2;
+}
+
+__global__ void k_vertex_validate(MutArgs a) {
+    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= a.n_ops) return;
+    ripple_update op = a.ops[i];
+    uint32_t st = 0;
+    if (op.kind == RIPPLE_VERTEX_ADD) {
+        if (!rp_bit(a.alive, op.u)) {
+            st = 1;
+            atomicOr(&a.vstate[op.u], VS_ADDING);
+        }
+    } else if (op.kind == RIPPLE_VERTEX_DEL) {
+        if (rp_bit(a.alive, op.u)) {
+            st = 1;
+            atomicOr(&a.vstate[op.u], VS_DYING);
+            atomicAdd(&a.ctr->need_exp, a.out_meta[op.u].y + a.in_meta[op.u].y);
+        }
+    } else if (op.kind == RIPPLE_FEAT_UPDATE) {
+        st = rp_bit(a.alive, op.u) ? 1u : 0u;
+    } else {
+        return;                                   // edge operations: k_edge_validate
+    }
+    a.status[i] = st;
+}
+
+__global__ __launch_bounds__(256) void k_edge_validate(MutArgs a) {
+    const int lane = rp_lane();
+    uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    for (uint32_t i = gw; i < a.n_ops; i += nw) {
+        ripple_update op = a.ops[i];
+        if (op.kind != RIPPLE_EDGE_ADD && op.kind != RIPPLE_EDGE_DEL) continue;
+        uint32_t u = op.u, v = op.v;
+        bool ok = (rp_bit(a.alive, u) || (a.vstate[u] & VS_ADDING)) &&
+                  (rp_bit(a.alive, v) || (a.vstate[v] & VS_ADDING));
+        uint32_t st = 0;
+        int po = -1, pi = -1;
+        if (ok) {
+            uint2 mo = a.out_meta[u], mi = a.in_meta[v];
+            if (op.kind == RIPPLE_EDGE_ADD) {
+                int p = (mo.y <= mi.y) ? rp_wave_find(a.out_pool + mo.x, mo.y, v)
+                                       : rp_wave_find(a.in_pool + mi.x, mi.y, u);
+                st = (p < 0) ? 1u : 0u;
+            } else {
+                po = rp_wave_find(a.out_pool + mo.x, mo.y, v);
+                if (po >= 0) {
+                    pi = rp_wave_find(a.in_pool + mi.x, mi.y, u);
+                    if (pi >= 0) st = 1;
+                    else if (lane == 0) a.ctr->error = 3;     // the two adjacencies disagree
+                }
+            }
+        }
+        if (lane == 0) {
+            a.status[i] = st;
+            if (st) {
+                if (op.kind == RIPPLE_EDGE_ADD) {
+                    atomicAdd(&a.pend_out[u], 1u);
+                    atomicAdd(&a.pend_in[v], 1u);
+                    atomicAdd(&a.ctr->n_add, 1u);
+                } else {
+                    a.pos_out[i] = (uint32_t)po;
+                    a.pos_in[i] = (uint32_t)pi;
+                    atomicAdd(&a.dead_out[u], 1u);
+                    atomicAdd(&a.dead_in[v], 1u);
+                    atomicAdd(&a.ctr->n_del, 1u);
+                }
+                touch_row(a, u, VS_TOUCH_OUT);
+                touch_row(a, v, VS_TOUCH_IN);
+            }
+        }
+    }
+}
+
+__global__ void k_capacity(MutArgs a) {
+    uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
+    uint32_t no = min(a.ctr->n_touch_out, a.touch_cap), ni = min(a.ctr->n_touch_in, a.touch_cap);
+    if (j < no) {
+        uint32_t x = a.touch_out[j], pend = a.pend_out[x];
+        uint32_t need = a.out_meta[x].y - a.dead_out[x] + pend;
+        if (pend && need > a.out_capv[x]) atomicAdd(&a.ctr->need_out, rp_row_cap(need));
+    } else if (j < no + ni) {
+        uint32_t x = a.touch_in[j - no], pend = a.pend_in[x];
+        uint32_t need = a.in_meta[x].y - a.dead_in[x] + pend;
+        if (pend && need > a.in_capv[x]) atomicAdd(&a.ctr->need_in, rp_row_cap(need));
+    }
+}
+
+__global__ void k_decide(MutArgs a) {
+    if (blockIdx.x || threadIdx.x) return;
+    DevCtr *c = a.ctr;
+    uint32_t flag = 0;
+    if ((unsigned long long)c->out_top + c->need_out > a.pool_cap ||
+        (unsigned long long)c->in_top + c->need_in > a.pool_cap)
+        flag |= 1u;
+    if (c->n_edges + c->n_add > a.e_cap + c->n_del) flag |= 2u;
+    if (c->need_exp > a.exp_cap || (unsigned long long)c->n_add + c->n_del + c->need_exp > a.struct_cap ||
+        (unsigned long long)c->n_add + c->n_del + c->need_exp > a.touch_cap)
+        flag |= 4u;
+    if (c->error) flag |= 8u;
+    c->abort_flag = flag;
+}
+
+// slot in a global list for every lane with pred, one atomic per wavefront
+__device__ __forceinline__ uint32_t wave_reserve(uint32_t *counter, bool pred) {
+    unsigned long long m = __ballot(pred);
+    if (!m) return 0;
+    const int lane = rp_lane();
+    int leader = __ffsll((long long)m) - 1;
+    uint32_t base = 0;
+    if (lane == leader) base = atomicAdd(counter, (uint32_t)__popcll(m));
+    base = __shfl(base, leader);
+    return base + (uint32_t)__popcll(m & ((1ull << lane) - 1ull));
+}
+
+__global__ __launch_bounds__(256) void k_expand_vdel(MutArgs a) {
+    if (a.ctr->abort_flag) return;
+    const int lane = rp_lane();
+    uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    for (uint32_t i = gw; i < a.n_ops; i += nw) {
+        ripple_update op = a.ops[i];
+        if (op.kind != RIPPLE_VERTEX_DEL || !a.status[i]) continue;
+        uint32_t w = op.u;
+        uint2 mo = a.out_meta[w], mi = a.in_meta[w];
+        uint32_t base = 0;
+        if (lane == 0) base = atomicAdd(&a.ctr->n_exp, mo.y + mi.y);
+        base = __shfl(base, 0);
+        uint32_t gone = mo.y;                               // every out-edge disappears
+        for (uint32_t j0 = 0; j0 < mo.y; j0 += 64) {
+            uint32_t j = j0 + lane;
+            bool valid = j < mo.y;
+            uint32_t y = valid ? a.out_pool[mo.x + j] : 0u;
+            bool keep = valid && !(a.vstate[y] & VS_DYING);
+            if (valid) {
+                a.exp_kind[base + j] = keep ? EXP_OUT : EXP_NONE;
+                a.exp_a[base + j] = w;
+                a.exp_b[base + j] = y;
+            }
+            uint32_t s = wave_reserve(&a.ctr->n_struct, keep);
+            if (keep) {
+                if (s < a.struct_cap) {
+                    a.st_src[s] = w;
+                    a.st_dst[s] = y;
+                    a.st_sign[s] = -1.0f;
+                }
+                rp_set_bit(a.bm_sink, y);
+            }
+        }
+        uint32_t cnt_in = 0;
+        for (uint32_t j0 = 0; j0 < mi.y; j0 += 64) {
+            uint32_t j = j0 + lane;
+            bool valid = j < mi.y;
+            uint32_t x = valid ? a.in_pool[mi.x + j] : 0u;
+            bool keep = valid && !(a.vstate[x] & VS_DYING);   // edges between two dying vertices count once
+            if (valid) {
+                a.exp_kind[base + mo.y + j] = keep ? EXP_IN : EXP_NONE;
+                a.exp_a[base + mo.y + j] = x;
+                a.exp_b[base + mo.y + j] = w;
+            }
+            cnt_in += (uint32_t)__popcll(__ballot(keep));
+        }
+        gone += cnt_in;
+        if (lane == 0) atomicAdd(&a.ctr->n_edges, (unsigned long long)(-(long long)gone));
+    }
+}
+
+__global__ __launch_bounds__(256) void k_expand_apply(MutArgs a) {
+    if (a.ctr->abort_flag) return;
+    const int lane = rp_lane();
+    uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    uint32_t n = min(a.ctr->n_exp, a.exp_cap);
+    for (uint32_t e = gw; e < n; e += nw) {
+        uint32_t kind = a.exp_kind[e];
+        if (kind == EXP_NONE) continue;
+        uint32_t x = a.exp_a[e], y = a.exp_b[e];
+        if (kind == EXP_OUT) {                               // x -> y with x dying: erase x from y's in-row
+            uint2 mi = a.in_meta[y];
+            int p = rp_wave_find(a.in_pool + mi.x, mi.y, x);
+            if (lane == 0) {
+                if (p >= 0) {
+                    a.in_pool[mi.x + p] = RP_TOMB;
+                    atomicAdd(&a.dead_in[y], 1u);
+                    touch_row(a, y, VS_TOUCH_IN);
+                } else a.ctr->error = 4;
+            }
+        } else {                                             // x -> y with y dying: erase y from x's out-row
+            uint2 mo = a.out_meta[x];
+            int p = rp_wave_find(a.out_pool + mo.x, mo.y, y);
+            if (lane == 0) {
+                if (p >= 0) {
+                    a.out_pool[mo.x + p] = RP_TOMB;
+                    atomicAdd(&a.dead_out[x], 1u);
+                    touch_row(a, x, VS_TOUCH_OUT);
+                } else a.ctr->error = 5;
+            }
+        }
+    }
+}
+
+// tombstone deleted edges, list every changed edge as a structural term, count results
+__global__ __launch_bounds__(256) void k_apply_edges(MutArgs a) {
+    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    bool in_range = i < a.n_ops;
+    bool aborted = a.ctr->abort_flag != 0;
+    ripple_update op = in_range ? a.ops[i] : ripple_update{99u, 0u, 0u, 0u};
+    bool acc = in_range && a.status[i] != 0;
+    unsigned long long ma = __ballot(acc), mr = __ballot(in_range && !acc);
+    if (rp_lane() == 0 && !aborted) {
+        if (ma) atomicAdd(&a.ctr->n_applied, (uint32_t)__popcll(ma));
+        if (mr) atomicAdd(&a.ctr->n_rejected, (uint32_t)__popcll(mr));
+    }
+    if (aborted) return;
+    bool edge = acc && (op.kind == RIPPLE_EDGE_ADD || op.kind == RIPPLE_EDGE_DEL);
+    uint32_t s = wave_reserve(&a.ctr->n_struct, edge);
+    if (!edge) return;
+    if (op.kind == RIPPLE_EDGE_DEL) {
+        a.out_pool[a.out_meta[op.u].x + a.pos_out[i]] = RP_TOMB;
+        a.in_pool[a.in_meta[op.v].x + a.pos_in[i]] = RP_TOMB;
+    }
+    if (s < a.struct_cap) {
+        a.st_src[s] = op.u;
+        a.st_dst[s] = op.v;
+        a.st_sign[s] = (op.kind == RIPPLE_EDGE_ADD) ? 1.0f : -1.0f;
+    }
+    rp_set_bit(a.bm_sink, op.v);
+}
+
+// feature writes (with the hop-0 delta), vertex creation, vertex removal
+__global__ __launch_bounds__(256) void k_apply_vertices(MutArgs a) {
+    if (a.ctr->abort_flag) return;
+    const int lane = rp_lane();
+    uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    const uint32_t d0 = a.d[0];
+    for (uint32_t i = gw; i < a.n_ops; i += nw) {
+        ripple_update op = a.ops[i];
+        if (!a.status[i]) continue;
+        uint32_t w = op.u;
+        if (op.kind == RIPPLE_FEAT_UPDATE || op.kind == RIPPLE_VERTEX_ADD) {
+            uint32_t slot = 0;
+            if (lane == 0) slot = atomicAdd(&a.ctr->a[0], 1u);
+            slot = __shfl(slot, 0);
+            const float *row = a.payload + (size_t)op.feat_row * d0;
+            for (uint32_t c = lane; c < d0; c += 64) {
+                float nv = row[c];
+                size_t idx = (size_t)w * d0 + c;
+                float old;
+                if (a.store) {
+                    __hip_bfloat16 *h = (__hip_bfloat16 *)a.H[0];
+                    old = __bfloat162float(h[idx]);
+                    __hip_bfloat16 r = __float2bfloat16(nv);
+                    nv = __bfloat162float(r);
+                    h[idx] = r;
+                } else {
+                    float *h = (float *)a.H[0];
+                    old = h[idx];
+                    h[idx] = nv;
+                }
+                a.D0[(size_t)slot * d0 + c] = nv - old;
+            }
+            if (lane == 0) {
+                a.list0[slot] = w;
+                rp_set_bit(a.bm0, w);
+                if (op.kind == RIPPLE_VERTEX_ADD) {
+                    atomicOr(&a.alive[w >> 5], 1u << (w & 31));
+                    rp_set_bit(a.bm_vadd, w);
+                    atomicAdd(&a.ctr->n_alive, 1u);
+                    atomicAdd(&a.ctr->n_vadd, 1u);
+                }
+            }
+        } else if (op.kind == RIPPLE_VERTEX_DEL) {
+            for (uint32_t l = 0; l <= a.L; ++l) {
+                uint32_t dl = a.d[l];
+                for (uint32_t c = lane; c < dl; c += 64) {
+                    size_t idx = (size_t)w * dl + c;
+                    if (a.store) ((__hip_bfloat16 *)a.H[l])[idx] = __float2bfloat16(0.0f);
+                    else ((float *)a.H[l])[idx] = 0.0f;
+                }
+                if (l >= 1) {
+                    uint32_t dp = a.d[l - 1];
+                    for (uint32_t c = lane; c < dp; c += 64) a.X[l][(size_t)w * dp + c] = 0.0f;
+                }
+            }
+            if (lane == 0) {
+                atomicAnd(&a.alive[w >> 5], ~(1u << (w & 31)));
+                a.out_meta[w].y = 0;
+                a.in_meta[w].y = 0;
+                atomicSub(&a.ctr->n_alive, 1u);
+            }
+        }
+    }
+}
+
+// one wavefront per touched row: squeeze tombstones out, move the row if the
+// pending appends do not fit, reset the row's scratch counters
+__global__ __launch_bounds__(256) void k_cleanup_rows(MutArgs a) {
+    const int lane = rp_lane();
+    const bool aborted = a.ctr->abort_flag != 0;
+    uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    uint32_t no = min(a.ctr->n_touch_out, a.touch_cap), ni = min(a.ctr->n_touch_in, a.touch_cap);
+    for (uint32_t j = gw; j < no + ni; j += nw) {
+        const bool is_out = j < no;
+        const uint32_t x = is_out ? a.touch_out[j] : a.touch_in[j - no];
+        uint2 *meta = is_out ? a.out_meta : a.in_meta;
+        uint32_t *capv = is_out ? a.out_capv : a.in_capv;
+        uint32_t *pool = is_out ? a.out_pool : a.in_pool;
+        uint32_t *deadv = is_out ? a.dead_out : a.dead_in;
+        uint32_t *pendv = is_out ? a.pend_out : a.pend_in;
+        uint32_t *top = is_out ? &a.ctr->out_top : &a.ctr->in_top;
+        if (!aborted) {
+            uint2 m = meta[x];
+            uint32_t dead = deadv[x], pend = pendv[x];
+            uint32_t len = m.y;
+            if (dead && len) {
+                uint32_t w = 0;
+                for (uint32_t base = 0; base < len; base += 64) {
+                    uint32_t i = base + lane;
+                    uint32_t val = (i < len) ? pool[m.x + i] : RP_TOMB;
+                    bool keep = val != RP_TOMB;
+                    unsigned long long mask = __ballot(keep);
+                    uint32_t off = (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+                    if (keep) pool[m.x + w + off] = val;
+                    w += (uint32_t)__popcll(mask);
+                }
+                len = w;
+            }
+            uint32_t need = len + pend;
+            if (pend && need > capv[x]) {
+                uint32_t ncap = rp_row_cap(need);
+                uint32_t ns = 0;
+                if (lane == 0) ns = atomicAdd(top, ncap);
+                ns = __shfl(ns, 0);
+                if ((unsigned long long)ns + ncap <= a.pool_cap) {
+                    for (uint32_t i = lane; i < len; i += 64) pool[ns + i] = pool[m.x + i];
+                    m.x = ns;
+                    if (lane == 0) capv[x] = ncap;
+                } else if (lane == 0) {
+                    a.ctr->error = 6;                        // cannot happen: space was checked before commit
+                }
+            }
+            if (lane == 0) meta[x] = make_uint2(m.x, len);
+        }
+        if (lane == 0) {
+            deadv[x] = 0;
+            pendv[x] = 0;
+            atomicAnd(&a.vstate[x], ~(is_out ? VS_TOUCH_OUT : VS_TOUCH_IN));
+        }
+    }
+}
+
+__global__ void k_apply_adds(MutArgs a) {
+    uint32_t i = blockIdx.x * blockDim.x + threadIdx.x;
+    const bool aborted = a.ctr->abort_flag != 0;
+    if (i == 0 && !aborted) {
+        atomicAdd(&a.ctr->n_edges, (unsigned long long)a.ctr->n_add);
+        atomicAdd(&a.ctr->n_edges, (unsigned long long)(-(long long)a.ctr->n_del));
+    }
+    if (i >= a.n_ops) return;
+    ripple_update op = a.ops[i];
+    if (op.kind == RIPPLE_VERTEX_ADD || op.kind == RIPPLE_VERTEX_DEL) {
+        atomicAnd(&a.vstate[op.u], ~(VS_ADDING | VS_DYING));
+        return;
+    }
+    if (aborted || op.kind != RIPPLE_EDGE_ADD || !a.status[i]) return;
+    uint32_t p = atomicAdd(&((uint32_t *)a.out_meta)[2 * (size_t)op.u + 1], 1u);
+    if (p < a.out_capv[op.u]) a.out_pool[a.out_meta[op.u].x + p] = op.v;
+    else a.ctr->error = 7;
+    p = atomicAdd(&((uint32_t *)a.in_meta)[2 * (size_t)op.v + 1], 1u);
+    if (p < a.in_capv[op.v]) a.in_pool[a.in_meta[op.v].x + p] = op.u;
+    else a.ctr->error = 7;
+}
+
+// X^l[v] += sign * H^{l-1}[u] for every changed edge and every layer, taken
+// while all H still hold their pre-batch values (Sec. 3.3.3: an added edge
+// uses 0 as the source's old embedding, a deleted edge 0 as its new one).
+__global__ __launch_bounds__(256) void k_struct_scatter(MutArgs a) {
+    if (a.ctr->abort_flag) return;
+    const int lane = rp_lane();
+    uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    uint32_t n = min(a.ctr->n_struct, a.struct_cap);
+    unsigned long long total = (unsigned long long)n * a.L;
+    for (unsigned long long t = gw; t < total; t += nw) {
+        uint32_t e = (uint32_t)(t / a.L), l = (uint32_t)(t % a.L) + 1;
+        uint32_t u = a.st_src[e], v = a.st_dst[e];
+        float sg = a.st_sign[e];
+        uint32_t dp = a.d[l - 1];
+        for (uint32_t c = lane; c < dp; c += 64) {
+            float val = rp_load_h(a.H[l - 1], a.store, (size_t)u * dp + c);
+            if (val != 0.0f) unsafeAtomicAdd(&a.X[l][(size_t)v * dp + c], sg * val);
+        }
+    }
+}
+
+__global__ void k_batch_reset(DevCtr *ctr, uint32_t *bitmaps, size_t n_bitmap_words) {
+    size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_bitmap_words; i += stride) bitmaps[i] = 0;
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        for (int l = 0; l <= RIPPLE_MAX_LAYERS; ++l) {
+            ctr->a[l] = 0;
+            ctr->m[l] = 0;
+        }
+        ctr->n_struct = 0;
+        ctr->n_touch_out = ctr->n_touch_in = 0;
+        ctr->n_exp = ctr->need_exp = 0;
+        ctr->n_applied = ctr->n_rejected = 0;
+        ctr->n_add = ctr->n_del = 0;
+        ctr->need_out = ctr->need_in = 0;
+        ctr->n_vadd = 0;
+        ctr->abort_flag = 0;
+    }
+}
+
+static MutArgs make_args(ripple_ctx *c, uint32_t n_ops) {
+    MutArgs a;
+    a.ops = c->ops_d;
+    a.n_ops = n_ops;
+    a.payload = c->payload_d;
+    a.status = c->op_status;
+    a.pos_out = c->op_pos_out;
+    a.pos_in = c->op_pos_in;
+    a.out_meta = c->out_meta;
+    a.in_meta = c->in_meta;
+    a.out_capv = c->out_capv;
+    a.in_capv = c->in_capv;
+    a.out_pool = c->out_pool;
+    a.in_pool = c->in_pool;
+    a.alive = c->alive;
+    a.vstate = c->vstate;
+    a.pend_out = c->pend_out;
+    a.pend_in = c->pend_in;
+    a.dead_out = c->dead_out;
+    a.dead_in = c->dead_in;
+    a.touch_out = c->touch_out;
+    a.touch_in = c->touch_in;
+    a.touch_cap = c->touch_cap;
+    a.exp_kind = c->exp_kind;
+    a.exp_a = c->exp_a;
+    a.exp_b = c->exp_b;
+    a.exp_cap = c->exp_cap;
+    a.st_src = c->st_src;
+    a.st_dst = c->st_dst;
+    a.st_sign = c->st_sign;
+    a.struct_cap = c->struct_cap;
+    a.bm0 = c->bm[0];
+    a.bm_sink = c->bm_sink;
+    a.bm_vadd = c->bm_vadd;
+    a.list0 = c->list[0];
+    a.D0 = c->D[0];
+    a.ctr = c->ctr;
+    a.n_cap = c->n_cap;
+    a.e_cap = c->e_cap;
+    a.pool_cap = c->pool_cap;
+    a.store = c->store;
+    a.L = c->L;
+    for (uint32_t l = 0; l <= RIPPLE_MAX_LAYERS; ++l) {
+        a.d[l] = c->d[l];
+        a.H[l] = c->H[l];
+        a.X[l] = c->X[l];
+    }
+    return a;
+}
+
+void rp_launch_batch_reset(ripple_ctx *c) {
+    // the per-layer bitmaps, S and V_added are one allocation starting at bm[0]
+    size_t words = (size_t)c->n_words * (c->L + 3);
+    uint32_t gb = std::min<uint32_t>(rp_div_up(words, 256), c->n_cu * 4);
+    hipLaunchKernelGGL(k_batch_reset, dim3(gb), dim3(256), 0, c->stream, c->ctr, c->bm[0], words);
+}
+
+// Enqueue the whole Apply step for the n_ops operations staged in ops_d / payload_d.
+void rp_launch_mutate(ripple_ctx *c, uint32_t n_ops, bool has_vertex_del, bool has_vertex_or_feat) {
+    if (n_ops == 0) return;
+    hipStream_t s = c->stream;
+    MutArgs a = make_args(c, n_ops);
+    uint32_t tb = rp_div_up(n_ops, 256);                              // thread per op
+    uint32_t wb = std::min<uint32_t>(rp_div_up(n_ops, 4), c->n_cu * 8);  // wavefront per op
+    uint32_t big = c->n_cu * 8;
+    hipLaunchKernelGGL(k_vertex_validate, dim3(tb), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(k_edge_validate, dim3(wb), dim3(256), 0, s, a);
+    uint32_t touch_threads = 2 * n_ops;                               // validation touches <= n_ops rows per side
+    hipLaunchKernelGGL(k_capacity, dim3(rp_div_up(touch_threads, 256)), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(k_decide, dim3(1), dim3(64), 0, s, a);
+    if (has_vertex_del) {
+        hipLaunchKernelGGL(k_expand_vdel, dim3(wb), dim3(256), 0, s, a);
+        hipLaunchKernelGGL(k_expand_apply, dim3(big), dim3(256), 0, s, a);
+    }
+    hipLaunchKernelGGL(k_apply_edges, dim3(tb), dim3(256), 0, s, a);
+    int t = rp_timer_begin(c);
+    hipLaunchKernelGGL(k_struct_scatter, dim3(has_vertex_del ? big : std::min<uint32_t>(big, rp_div_up((uint64_t)n_ops * c->L, 4))),
+                       dim3(256), 0, s, a);
+    rp_timer_end(c, t, RIPPLE_PH_STRUCT, 0);
+    if (has_vertex_or_feat) hipLaunchKernelGGL(k_apply_vertices, dim3(wb), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(k_cleanup_rows, dim3(has_vertex_del ? big : std::min<uint32_t>(big, rp_div_up(2 * (uint64_t)n_ops, 4))),
+                       dim3(256), 0, s, a);
+    hipLaunchKernelGGL(k_apply_adds, dim3(tb), dim3(256), 0, s, a);
+}

@@ -1,0 +1,30 @@
+// Host-side launchers implemented next to their kernels.
+#pragma once
+#include "common.h"
+#include <algorithm>
+
+// graph_store.hip
+void rp_exclusive_scan(hipStream_t s, const uint32_t *in, uint32_t *out, uint32_t n, uint32_t *part,
+                       uint32_t *total_out);
+ripple_status rp_build_graph(ripple_ctx *c, uint32_t n_vertices, uint64_t n_edges, const uint32_t *src_h,
+                             const uint32_t *dst_h);
+ripple_status rp_compact(ripple_ctx *c);
+void rp_launch_batch_reset(ripple_ctx *c);
+void rp_launch_mutate(ripple_ctx *c, uint32_t n_ops, bool has_vertex_del, bool has_vertex_or_feat);
+
+// frontier.hip
+void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l, int self_term);
+void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool merge_roots, bool want_deg, bool accumulate_rep);
+void rp_launch_bitmap_to_list(ripple_ctx *c, uint32_t *bitmap, uint32_t *out_list, uint32_t *count_d);
+void rp_launch_list_eoff(ripple_ctx *c, uint32_t l);
+
+// scatter.hip
+void rp_launch_scatter_push(ripple_ctx *c, uint32_t l);
+void rp_launch_pull_all(ripple_ctx *c, uint32_t l);
+
+// transform.hip
+void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool emit_delta);
+
+// api.hip: HIP-event timing of kernel classes (no-ops unless RIPPLE_OPT_TIMING is on)
+int rp_timer_begin(ripple_ctx *c);
+void rp_timer_end(ripple_ctx *c, int token, int phase, int layer);

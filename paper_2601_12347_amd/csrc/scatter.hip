@@ -1,0 +1,147 @@
+// Delta aggregation (the Send / Aggregate steps of Sec. 3.3): every vertex u of
+// A_{l-1} sends m = h_u(new) - h_u(old) (Sec. 3.3.3, sum) along its out-edges
+// of the updated graph and the messages arriving at v are added into the cached
+// un-normalised sum X^l[v] (the vertex's hop-l inbox, Sec. 3.3.2). Mean needs
+// no separate message: X stays a plain sum and the in-degree divides it when
+// the row is transformed.
+//
+// Push kernel: the flattened (source, out-edge) space is cut into equal chunks
+// via the out-degree prefix, one wavefront walks a chunk, holds the source's
+// delta row in registers across that source's edges and adds it to the
+// destination rows with hardware float atomics (order-free, Sec. 3.3.3).
+//
+// Bootstrap kernel: X^l[v] = sum over v's in-row of H^{l-1}, one wavefront per row.
+#include "common.h"
+#include "kernels.h"
+
+__device__ __forceinline__ uint32_t seg_search2(const uint32_t *off, uint32_t lo, uint32_t hi, uint32_t e) {
+    while (lo < hi) {
+        uint32_t mid = (lo + hi + 1) >> 1;
+        if (off[mid] <= e) lo = mid;
+        else hi = mid - 1;
+    }
+    return lo;
+}
+
+#define PUSH_CHUNK 64
+
+template <int NJ>
+__global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, const uint32_t *count_ptr,
+                                                      const uint32_t *eoff, const float *D, uint32_t d,
+                                                      const uint2 *out_meta, const uint32_t *out_pool, float *X) {
+    const uint32_t count = *count_ptr;
+    if (count == 0) return;
+    const int lane = rp_lane();
+    const uint32_t M = eoff[count];
+    const uint32_t n_chunks = (M + PUSH_CHUNK - 1) / PUSH_CHUNK;
+    const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    for (uint32_t c = gw; c < n_chunks; c += nw) {
+        const uint32_t e0 = c * PUSH_CHUNK, e1 = min(M, e0 + PUSH_CHUNK);
+        const uint32_t i_lo = seg_search2(eoff, 0, count - 1, e0);
+        const uint32_t i_hi = seg_search2(eoff, i_lo, count - 1, e1 - 1);
+        const uint32_t e = e0 + lane;
+        uint32_t my_i = 0, my_v = 0;
+        if (e < e1) {
+            my_i = seg_search2(eoff, i_lo, i_hi, e);
+            my_v = out_pool[out_meta[list[my_i]].x + (e - eoff[my_i])];
+        }
+        const int n_here = (int)(e1 - e0);
+        uint32_t cur = 0xFFFFFFFFu;
+        float dreg[NJ];
+        bool nz = false;
+        for (int k = 0; k < n_here; ++k) {
+            const uint32_t ik = __shfl(my_i, k), vk = __shfl(my_v, k);
+            if (ik != cur) {                                    // same for all lanes
+                cur = ik;
+                bool any = false;
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    uint32_t col = lane + 64 * j;
+                    dreg[j] = (col < d) ? D[(size_t)ik * d + col] : 0.0f;
+                    any |= dreg[j] != 0.0f;
+                }
+                nz = __ballot(any) != 0ull;
+            }
+            if (!nz) continue;                                  // an all-zero delta changes nothing
+            float *xr = X + (size_t)vk * d;
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                uint32_t col = lane + 64 * j;
+                if (col < d) unsafeAtomicAdd(&xr[col], dreg[j]);
+            }
+        }
+    }
+}
+
+void rp_launch_scatter_push(ripple_ctx *c, uint32_t l) {
+    const uint32_t d = c->d[l - 1];
+    const float *D = c->D[(l - 1) & 1];
+    dim3 grid(c->n_cu * 8), block(256);
+#define PUSH_CASE(NJ)                                                                                         \
+    hipLaunchKernelGGL(k_scatter_push<NJ>, grid, block, 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],      \
+                       c->eoff[l - 1], D, d, c->out_meta, c->out_pool, c->X[l])
+    if (d <= 64) PUSH_CASE(1);
+    else if (d <= 128) PUSH_CASE(2);
+    else if (d <= 256) PUSH_CASE(4);
+    else if (d <= 512) PUSH_CASE(8);
+    else PUSH_CASE(16);
+#undef PUSH_CASE
+}
+
+// ---------------------------------------------------------------------------------
+// bootstrap aggregation: X[v] = sum_{u in in-row(v)} H_prev[u]
+// ---------------------------------------------------------------------------------
+template <int NJ, int STORE>
+__global__ __launch_bounds__(256) void k_pull_all(const uint2 *in_meta, const uint32_t *in_pool, uint32_t n_cap,
+                                                  const void *Hprev, uint32_t d, float *X) {
+    const int lane = rp_lane();
+    const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    for (uint32_t v = gw; v < n_cap; v += nw) {
+        const uint2 m = in_meta[v];
+        float acc[NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
+        for (uint32_t base = 0; base < m.y; base += 64) {
+            const uint32_t i = base + lane;
+            const uint32_t my_u = (i < m.y) ? in_pool[m.x + i] : 0u;
+            const int n_here = (int)min(64u, m.y - base);
+            for (int k = 0; k < n_here; ++k) {
+                const uint32_t u = __shfl(my_u, k);
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    uint32_t col = lane + 64 * j;
+                    if (col < d) {
+                        size_t idx = (size_t)u * d + col;
+                        acc[j] += STORE ? __bfloat162float(((const __hip_bfloat16 *)Hprev)[idx])
+                                        : ((const float *)Hprev)[idx];
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            uint32_t col = lane + 64 * j;
+            if (col < d) X[(size_t)v * d + col] = acc[j];
+        }
+    }
+}
+
+void rp_launch_pull_all(ripple_ctx *c, uint32_t l) {
+    const uint32_t d = c->d[l - 1];
+    dim3 grid(c->n_cu * 16), block(256);
+#define PULL_CASE(NJ)                                                                                          \
+    do {                                                                                                       \
+        if (c->store)                                                                                          \
+            hipLaunchKernelGGL((k_pull_all<NJ, 1>), grid, block, 0, c->stream, c->in_meta, c->in_pool, c->n_cap, \
+                               c->H[l - 1], d, c->X[l]);                                                       \
+        else                                                                                                   \
+            hipLaunchKernelGGL((k_pull_all<NJ, 0>), grid, block, 0, c->stream, c->in_meta, c->in_pool, c->n_cap, \
+                               c->H[l - 1], d, c->X[l]);                                                       \
+    } while (0)
+    if (d <= 64) PULL_CASE(1);
+    else if (d <= 128) PULL_CASE(2);
+    else if (d <= 256) PULL_CASE(4);
+    else if (d <= 512) PULL_CASE(8);
+    else PULL_CASE(16);
+#undef PULL_CASE
+}

@@ -1,0 +1,116 @@
+"""Side-by-side driver for the parity tests: the same seeded inputs go to the
+GPU library (through its C ABI binding) and to the CPU oracle, and every
+observable is compared."""
+import numpy as np
+
+import oracle
+import paper_2601_12347_amd as rp
+import ripple_inputs as ri
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}      # max relative error per layer (metric: oracle.max_rel_err)
+
+
+class Pair:
+    def __init__(self, n, cap, src, dst, feats, model, store="f32", edge_capacity=None):
+        self.n, self.cap, self.model, self.store = n, cap, model, store
+        self.widths = [model[0]["d_in"]] + [l["d_out"] for l in model]
+        self.L = len(model)
+        self.ora = oracle.GraphState(n, cap, src, dst, feats)
+        self.ctx = rp.ripple_init_graph(n, cap, src, dst, feats, store=store, edge_capacity=edge_capacity)
+        rp.ripple_load_model(self.ctx, model)
+        rp.ripple_full_infer(self.ctx)
+
+    def close(self):
+        rp.ripple_destroy(self.ctx)
+        self.ctx = None
+
+    def gpu_layer(self, l):
+        return rp.ripple_get_embeddings(self.ctx, l, self.widths[l], n_rows=self.cap)
+
+    def check_embeddings(self, tol=None, want=None):
+        tol = TOL[self.store] if tol is None else tol
+        want = oracle.full_recompute(self.ora, self.model) if want is None else want
+        errs = []
+        for l in range(self.L + 1):
+            got = self.gpu_layer(l)
+            assert np.isfinite(got).all()
+            err = oracle.max_rel_err(got, want[l], self.ora.alive)
+            errs.append(err)
+            assert err <= tol, f"layer {l}: max rel err {err:.3e} > {tol}"
+            assert not got[~self.ora.alive].any(), f"layer {l}: dead rows must be zero"
+        return errs, want
+
+    def check_aggregates(self, tol=None):
+        """X^l[v] must equal the sum over v's in-neighbours of the stored H^{l-1}."""
+        tol = 1e-4 if tol is None else tol
+        src, dst = self.ora.edges()
+        for l in range(1, self.L + 1):
+            h_prev = self.gpu_layer(l - 1).astype(np.float64)
+            want = np.zeros_like(h_prev)
+            np.add.at(want, dst, h_prev[src])
+            got = rp.ripple_get_aggregates(self.ctx, l, self.widths[l - 1], n_rows=self.cap)
+            err = oracle.max_rel_err(got, want, self.ora.alive)
+            assert err <= tol, f"aggregate {l}: {err:.3e}"
+
+    def check_graph(self):
+        src, dst = self.ora.edges()
+        want = np.sort(src * self.cap + dst)
+        for direction in (0, 1):
+            s, d, n = rp.ripple_export_edges(self.ctx, direction, want.size + 16)
+            assert n == want.size, (direction, n, want.size)
+            got = np.sort(s.astype(np.int64) * self.cap + d)
+            assert np.array_equal(got, want), f"adjacency {direction} differs from the oracle's edge set"
+        deg_in, alive = rp.ripple_get_degrees(self.ctx, 1, self.cap)
+        assert np.array_equal(alive, self.ora.alive)
+        assert np.array_equal(deg_in, np.bincount(dst, minlength=self.cap))
+        deg_out, _ = rp.ripple_get_degrees(self.ctx, 0, self.cap)
+        assert np.array_equal(deg_out, np.bincount(src, minlength=self.cap))
+
+    def step(self, ops, payload, check=True, tol=None):
+        """Apply one batch on both sides; compare acceptance, affected sets and (optionally) all rows."""
+        before = [self.gpu_layer(l) for l in range(self.L + 1)] if check else None
+        rec = self.ora.apply_batch(ops, payload)
+        res = rp.ripple_apply_updates(self.ctx, ops, payload)
+        assert res.n_applied == int(rec.accepted.sum()), (res.n_applied, int(rec.accepted.sum()))
+        assert res.n_rejected == int((~rec.accepted).sum())
+        assert res.n_edges == self.ora.n_edges()
+        assert res.n_alive == int(self.ora.alive.sum())
+        sets = oracle.affected_sets(self.ora, rec, self.model)
+        for l in range(self.L + 1):
+            got, n = rp.ripple_get_affected(self.ctx, l, self.cap)
+            assert n == res.affected[l] == len(sets[l]), (l, n, res.affected[l], len(sets[l]))
+            assert np.array_equal(got.astype(np.int64), sets[l]), f"affected set of layer {l} differs"
+        if check:
+            errs, want = self.check_embeddings(tol)
+            for l in range(self.L + 1):                       # rows outside A_l keep their bits
+                after = self.gpu_layer(l)
+                clean = np.ones(self.cap, dtype=bool)
+                clean[sets[l]] = False
+                clean[list(rec.removed)] = False
+                assert np.array_equal(after[clean], before[l][clean]), f"layer {l}: a clean row changed"
+        return res, rec, sets
+
+
+def make_pair(n=300, e=1500, d0=12, kind="gcn_sum", widths=(12, 20, 8), store="f32", seed=0, slack=64,
+              gamma=2.1, top_share=0.03, edge_capacity=None):
+    src, dst, out_law, in_law = ri.chung_lu_graph(n, e, gamma, top_share, seed)
+    feats = ri.features(n, d0, seed + 1)
+    model = ri.make_model(kind, widths, seed + 2)
+    pair = Pair(n, n + slack, src, dst, feats, model, store=store, edge_capacity=edge_capacity)
+    return pair, (src, dst, out_law, in_law)
+
+
+def make_stream(pair, graph, mix, seed):
+    src, dst, out_law, in_law = graph
+    return ri.UpdateStream(pair.n, pair.cap, src, dst, out_law, in_law, pair.widths[0], mix, seed)
+
+
+def config_pair(cfg, store=None):
+    src, dst, out_law, in_law = ri.chung_lu_graph(cfg.n, cfg.e, cfg.gamma, cfg.top_share, cfg.graph_seed)
+    feats = ri.features(cfg.n, cfg.d0, cfg.feat_seed)
+    model = ri.make_model(cfg.model, cfg.widths, cfg.weight_seed)
+    pair = Pair(cfg.n, cfg.vertex_capacity, src, dst, feats, model, store=store or cfg.store,
+                edge_capacity=cfg.edge_capacity)
+    stream = ri.UpdateStream(cfg.n, cfg.vertex_capacity, src, dst, out_law, in_law, cfg.d0, cfg.mix,
+                             cfg.stream_seed)
+    return pair, stream

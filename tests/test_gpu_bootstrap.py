@@ -1,0 +1,104 @@
+"""ripple_full_infer against the oracle's layer-wise recompute (Eq. 1-2)."""
+import numpy as np
+import pytest
+
+import paper_2601_12347_amd as rp
+import ripple_inputs as ri
+from harness import make_pair, config_pair, Pair
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("kind,widths", [
+    ("gcn_sum", (12, 20, 8)),
+    ("gcn_mean", (12, 70, 33)),          # ragged widths: not multiples of 4, tails in every tile
+    ("sage_mean", (16, 40, 24, 10)),
+    ("sage_sum", (13, 29, 7)),
+    ("gin_sum", (16, 32, 12)),
+])
+def test_bootstrap_matches_oracle(kind, widths):
+    print("case", kind, widths, flush=True)
+    pair, _ = make_pair(n=700, e=5000, d0=widths[0], kind=kind, widths=widths, seed=3)
+    try:
+        pair.check_graph()
+        pair.check_embeddings()
+        pair.check_aggregates()
+    finally:
+        pair.close()
+
+
+def test_bootstrap_wide_layers_span_several_tiles():
+    print("case wide", flush=True)
+    pair, _ = make_pair(n=1500, e=9000, d0=100, kind="sage_mean", widths=(100, 256, 300, 47), seed=5)
+    try:
+        pair.check_embeddings()
+    finally:
+        pair.close()
+
+
+def test_bootstrap_bf16_store():
+    print("case bf16", flush=True)
+    pair, _ = make_pair(n=700, e=5000, d0=16, kind="gcn_sum", widths=(16, 64, 24), store="bf16", seed=4)
+    try:
+        pair.check_embeddings()
+    finally:
+        pair.close()
+
+
+def test_bootstrap_tiny_config():
+    print("case tiny config", flush=True)
+    pair, _ = config_pair(ri.get_config("tiny_gcn_sum"))
+    try:
+        pair.check_graph()
+        pair.check_embeddings()
+        pair.check_aggregates()
+    finally:
+        pair.close()
+
+
+def test_empty_graph_and_isolated_vertices():
+    print("case empty", flush=True)
+    feats = ri.features(5, 8, 1)
+    model = ri.make_model("gcn_sum", (8, 8, 4), 2)
+    e = np.zeros(0, dtype=np.uint32)
+    pair = Pair(5, 9, e, e, feats, model)
+    try:
+        pair.check_graph()
+        pair.check_embeddings()
+    finally:
+        pair.close()
+
+
+def test_call_order_and_argument_errors():
+    print("case errors", flush=True)
+    feats = ri.features(4, 8, 1)
+    model = ri.make_model("gcn_sum", (8, 4), 2)
+    src = np.array([0, 1], dtype=np.uint32)
+    dst = np.array([1, 2], dtype=np.uint32)
+    with pytest.raises(rp.RippleError) as ei:                     # endpoint beyond the live range
+        rp.ripple_init_graph(4, 8, np.array([0, 5], dtype=np.uint32), dst, feats)
+    assert ei.value.status == rp.binding.RIPPLE_EINVAL
+    ctx = rp.ripple_init_graph(4, 8, src, dst, feats)
+    try:
+        with pytest.raises(rp.RippleError) as ei:
+            rp.ripple_full_infer(ctx)                             # no model yet
+        assert ei.value.status == rp.binding.RIPPLE_ESTATE
+        with pytest.raises(rp.RippleError) as ei:
+            rp.ripple_apply_updates(ctx, np.zeros((1, 4), np.uint32), None)
+        assert ei.value.status == rp.binding.RIPPLE_ESTATE
+        bad = ri.make_model("gcn_sum", (7, 4), 2)                 # widths do not chain with d0 = 8
+        with pytest.raises(rp.RippleError) as ei:
+            rp.ripple_load_model(ctx, bad)
+        assert ei.value.status == rp.binding.RIPPLE_EINVAL
+        rp.ripple_load_model(ctx, model)
+        rp.ripple_full_infer(ctx)
+        for ops in ([(9, 0, 0, 0)], [(ri.OP_EDGE_ADD, 0, 8, 0)], [(ri.OP_FEAT_UPDATE, 1, 0, 3)]):
+            with pytest.raises(rp.RippleError) as ei:             # unknown kind / id / payload row
+                rp.ripple_apply_updates(ctx, np.array(ops, dtype=np.uint32), np.zeros((1, 8), np.float32))
+            assert ei.value.status == rp.binding.RIPPLE_EINVAL
+        with pytest.raises(rp.RippleError):
+            rp.ripple_get_embeddings(ctx, 5, 4, n_rows=2)
+        out = rp.ripple_get_embeddings(ctx, 1, 4, ids=np.array([3, 7], dtype=np.uint32))
+        assert not out[1].any()                                   # id 7 was never created
+    finally:
+        rp.ripple_destroy(ctx)
