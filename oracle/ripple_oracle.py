@@ -137,6 +137,8 @@ class GraphState:
         affected-set derivation needs.
         """
         ops = np.asarray(ops, dtype=np.int64).reshape(-1, 4)
+        if payload is None:
+            payload = np.zeros((0, self.h0.shape[1]))
         payload = np.asarray(payload, dtype=np.float64).reshape(-1, self.h0.shape[1])
         rec = BatchRecord(accepted=np.zeros(len(ops), dtype=bool))
         for i, (kind, u, v, row) in enumerate(ops.tolist()):

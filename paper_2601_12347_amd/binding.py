@@ -75,6 +75,13 @@ def load_library():
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is missing: build it with "
                            "`python -m paper_2601_12347_amd.build` (needs hipcc)")
+    # PyTorch (the caller's device-memory and stream provider) bundles its own HIP runtime.
+    # Two HIP runtimes in one process do not share the GPU, so torch is imported first and
+    # libripple.so then binds to the runtime that is already loaded.
+    try:
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     lib = C.CDLL(LIB_PATH)
     vp, u32, u64 = C.c_void_p, C.c_uint32, C.c_uint64
     lib.ripple_init_graph.argtypes = [C.POINTER(vp), u32, u32, u64, u64, vp, vp, vp, u32, C.c_int, vp]
