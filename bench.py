@@ -1,0 +1,229 @@
+#!/usr/bin/env python3
+"""Benchmark of the incremental-propagation hot path on one MI355X.
+
+One step = one batch of updates through ripple_apply_updates (ingest + apply,
+then per layer frontier, scatter, transform), host entry to synchronised return,
+with the batch's operations and feature rows already resident in HBM. Prints ONE
+JSON line: updates/s over the timed batches, p50/p99 batch latency, the roofline
+figures of the dominant kernel (HIP-event time measured inside the library on its
+own stream, algorithmic bytes/flops from the per-batch work counters) and the CPU
+oracle's rate on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_PEAK_TFLOPS = {"f32": 157.3, "bf16": 2500.0}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def algorithmic_work(st, model, widths, store, L):
+    """Per (phase, layer): algorithmic bytes and flops summed over the timed batches.
+
+    scatter(l):   every delta row once, the out-row index pairs and column ids once, and each
+                  distinct destination row of X^l read and written once;
+    frontier(l):  index pairs + column ids of the walked out-rows, the list written, the
+                  bitmap words read and written;
+    transform(l): per dirty row the gathered input row, old H read, new H and delta written;
+                  flops 2*K*d_out per row (plus the hidden stage for two-stage updates).
+    """
+    s_h = 2 if store == "bf16" else 4
+    out = {}
+    for l in range(1, L + 1):
+        lay = model[l - 1]
+        d_prev, d_out = widths[l - 1], widths[l]
+        a_prev, a_l, m_l, t_l = st.rows[l - 1], st.rows[l], st.msgs[l], st.touched[l]
+        out[("scatter", l)] = dict(bytes=a_prev * d_prev * 4 + 8 * a_prev + 4 * m_l + 2 * t_l * d_prev * 4, flops=m_l * d_prev)
+        out[("frontier", l)] = dict(bytes=8 * a_prev + 4 * m_l + 4 * a_l, flops=0)
+        k = lay["d_in"] * (2 if lay["self"] == "concat" else 1)
+        if lay["d_hidden"]:
+            flops = 2 * a_l * (k * lay["d_hidden"] + lay["d_hidden"] * d_out)
+        else:
+            flops = 2 * a_l * k * d_out
+        in_bytes = lay["d_in"] * 4 + (lay["d_in"] * s_h if lay["self"] != "none" else 0)
+        out[("transform", l)] = dict(bytes=a_l * (in_bytes + d_out * s_h * 2 + (d_out * 4 if l < L else 0) + 4), flops=flops)
+    return out
+
+
+def cpu_baseline(cfg, bs, scale):
+    """The oracle on a 1/scale copy of the workload (same recipe, N/scale vertices, E/scale
+    edges, bs/scale updates): one batch applied and everything recomputed in fp64. Recompute
+    cost is linear in N and E (Sec. 3.5's operation count with a_l = N), so the full-size time
+    per batch is estimated as scale times the sample's."""
+    import oracle
+    import ripple_inputs as ri
+    n, e = max(cfg.n // scale, 64), max(cfg.e // scale, 256)
+    src, dst, out_law, in_law = ri.chung_lu_graph(n, e, cfg.gamma, min(cfg.top_share * scale, 0.05), cfg.graph_seed)
+    feats = ri.features(n, cfg.d0, cfg.feat_seed)
+    model = ri.make_model(cfg.model, cfg.widths, cfg.weight_seed)
+    stream = ri.UpdateStream(n, n + cfg.vertex_slack, src, dst, out_law, in_law, cfg.d0, cfg.mix, cfg.stream_seed)
+    st = oracle.GraphState(n, n + cfg.vertex_slack, src, dst, feats)
+    sample_bs = max(bs // scale, 1)
+    ops, payload, n_upd = stream.next_batch(sample_bs)
+    t0 = time.perf_counter()
+    rec = st.apply_batch(ops, payload)
+    hs = oracle.full_recompute(st, model)
+    oracle.affected_sets(st, rec, model)
+    dt = time.perf_counter() - t0
+    try:
+        from threadpoolctl import threadpool_info
+        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
+    except Exception:
+        cores = os.cpu_count() or 1
+    est_full = dt * scale
+    return {"value": bs / est_full, "unit": "updates/s", "cores": int(cores), "kind": "oracle",
+            "sample": f"fp64 full recompute + affected sets for one batch on a 1/{scale}-scale graph of the same "
+                      f"recipe ({n} vertices, {e} edges, {sample_bs} updates): {dt:.2f} s, scaled x{scale} to the "
+                      f"full graph ({est_full:.1f} s per batch of {bs})",
+            "sample_seconds": dt}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="dense_sage_mean")
+    ap.add_argument("--bs", type=int, default=0, help="updates per batch (default: the config's largest)")
+    ap.add_argument("--cpu-scale", type=int, default=0, help="oracle sample is a 1/scale graph (0 = auto)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--scatter-mode", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2601_12347_amd as rp
+    import ripple_inputs as ri
+
+    cfg = ri.get_config(args.config)
+    bs = args.bs or max(cfg.batch_sizes)
+    t0 = time.time()
+    src, dst, out_law, in_law = ri.chung_lu_graph(cfg.n, cfg.e, cfg.gamma, cfg.top_share, cfg.graph_seed)
+    feats = ri.features(cfg.n, cfg.d0, cfg.feat_seed)
+    model = ri.make_model(cfg.model, cfg.widths, cfg.weight_seed)
+    log(f"[bench] graph {cfg.name}: {cfg.n} vertices, {cfg.e} edges generated in {time.time() - t0:.1f}s")
+    t0 = time.time()
+    ctx = rp.ripple_init_graph(cfg.n, cfg.vertex_capacity, src, dst, feats, store=cfg.store,
+                               edge_capacity=cfg.edge_capacity)
+    rp.ripple_load_model(ctx, model)
+    rp.ripple_full_infer(ctx)
+    log(f"[bench] graph store built and bootstrap inference done in {time.time() - t0:.1f}s")
+    t0 = time.time()
+    stream = ri.UpdateStream(cfg.n, cfg.vertex_capacity, src, dst, out_law, in_law, cfg.d0, cfg.mix, cfg.stream_seed)
+    del src, dst
+    batches = []
+    for _ in range(args.warmup + args.steps):
+        ops, payload, n_upd = stream.next_batch(bs)
+        ops_t = torch.from_numpy(ops.view(np.int32).copy()).cuda()
+        pay_t = torch.from_numpy(payload).cuda() if len(payload) else None
+        batches.append((ops_t, pay_t, len(ops), len(payload), n_upd))
+    torch.cuda.synchronize()
+    del stream
+    log(f"[bench] {len(batches)} batches of {bs} updates staged in HBM in {time.time() - t0:.1f}s")
+
+    rp.ripple_set_option(ctx, rp.OPT_SCATTER_MODE, args.scatter_mode)
+
+    def run(b):
+        ops_t, pay_t, n_ops, n_rows, _ = b
+        return rp.ripple_apply_updates(ctx, ops_t.data_ptr(), pay_t.data_ptr() if pay_t is not None else None,
+                                       n_ops=n_ops, n_feat_rows=n_rows)
+
+    for b in batches[:args.warmup]:
+        run(b)
+    rp.ripple_set_option(ctx, rp.OPT_TIMING, 1)
+    rp.ripple_get_stats(ctx, reset=True)
+    torch.cuda.synchronize()
+    lat, n_updates, applied = [], 0, 0
+    t_begin = time.perf_counter()
+    for b in batches[args.warmup:]:
+        t1 = time.perf_counter()
+        res = run(b)
+        lat.append(time.perf_counter() - t1)
+        n_updates += b[4]
+        applied += res.n_applied
+    torch.cuda.synchronize()
+    total = time.perf_counter() - t_begin
+    st = rp.ripple_get_stats(ctx, reset=False)
+    rp.ripple_set_option(ctx, rp.OPT_TIMING, 0)
+
+    L = len(model)
+    work = algorithmic_work(st, model, cfg.widths, cfg.store, L)
+    phase_idx = {"frontier": 2, "scatter": 3, "transform": 5}
+    kernels = {}
+    for (ph, l), w in work.items():
+        ms = st.ms[phase_idx[ph]][l]
+        n_launch = st.launches[phase_idx[ph]][l]
+        if not n_launch or ms <= 0:
+            continue
+        ent = {"ms_per_launch": ms / n_launch, "launches": int(n_launch),
+               "GBps": w["bytes"] / (ms * 1e-3) / 1e9, "hbm_frac": w["bytes"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        if ph == "transform":
+            ent["TFLOPs"] = w["flops"] / (ms * 1e-3) / 1e12
+            ent["mfma_frac"] = ent["TFLOPs"] / MFMA_PEAK_TFLOPS["f32"]
+        kernels[f"{ph}_l{l}"] = ent
+    other = {name: st.ms[i][0] / max(st.batches, 1) for i, name in ((0, "ingest"), (1, "struct"), (7, "total"))}
+    for l in range(1, L + 1):
+        other[f"compact_l{l}"] = st.ms[4][l] / max(st.batches, 1)
+    dom = max(kernels, key=lambda k: kernels[k]["ms_per_launch"] * kernels[k]["launches"]) if kernels else None
+    roofline = None
+    if dom:
+        k = kernels[dom]
+        ph, l = dom.split("_l")
+        l = int(l)
+        w = work[(ph, l)]
+        # transform is priced against the matrix-core peak only where its arithmetic intensity
+        # clears the ridge (peak flops / peak bytes); otherwise it is HBM-bound
+        ridge = MFMA_PEAK_TFLOPS["f32"] * 1e12 / (HBM_PEAK_GBS * 1e9)
+        if ph == "transform" and w["flops"] / max(w["bytes"], 1) >= ridge:
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": k["TFLOPs"], "peak": MFMA_PEAK_TFLOPS["f32"],
+                        "unit": "TFLOP/s", "frac": k["mfma_frac"], "traffic": None}
+        else:
+            roofline = {"kernel": dom, "bound": "hbm", "achieved": k["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                        "frac": k["hbm_frac"], "traffic": None}
+    lat_ms = np.array(lat) * 1e3
+    result = {
+        "metric": "graph updates/sec (and p50 batch latency), 3-layer GraphSAGE-mean on a 2.45M-vertex/124M-edge graph"
+        if cfg.name == "dense_sage_mean" else f"graph updates/sec, {cfg.name}",
+        "value": n_updates / total, "unit": "updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": total / max(args.steps, 1) * 1e3, "p50_ms": float(np.percentile(lat_ms, 50)),
+        "p99_ms": float(np.percentile(lat_ms, 99)), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32" if cfg.store == "f32" else "bf16", "data": "synthetic",
+        "config": {"workload": f"{cfg.name}: Chung-Lu gamma={cfg.gamma}, {cfg.n} vertices, {cfg.e} edges, "
+                               f"widths {'->'.join(map(str, cfg.widths))}, {bs} updates/batch "
+                               f"(50% edge add, 30% edge delete, 20% feature update)",
+                   "batch_size": bs, "updates_applied": int(applied)},
+        "per_batch": {"a_l": [st.rows[l] / max(st.batches, 1) for l in range(L + 1)],
+                      "messages_l": [st.msgs[l] / max(st.batches, 1) for l in range(L + 1)],
+                      "phase_ms": other},
+        "kernels": kernels,
+        "roofline": roofline,
+    }
+    rp.ripple_destroy(ctx)
+    del batches
+    torch.cuda.empty_cache()
+    if not args.no_cpu_baseline:
+        scale = args.cpu_scale or (16 if cfg.e > 10_000_000 else 1)
+        t0 = time.time()
+        result["cpu_baseline"] = cpu_baseline(cfg, bs, scale)
+        log(f"[bench] CPU oracle sample took {time.time() - t0:.1f}s")
+    print(json.dumps(result), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -112,6 +112,7 @@ typedef struct {
     uint64_t launches[RIPPLE_N_PHASES][RIPPLE_MAX_LAYERS + 1];
     uint64_t rows[RIPPLE_MAX_LAYERS + 1];                      /* sum of a_l                                 */
     uint64_t msgs[RIPPLE_MAX_LAYERS + 1];                      /* sum of messages into layer l               */
+    uint64_t touched[RIPPLE_MAX_LAYERS + 1];                   /* sum of distinct destinations of those messages */
 } ripple_stats;
 
 typedef enum {

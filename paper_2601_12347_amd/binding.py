@@ -61,7 +61,8 @@ class Stats(C.Structure):
                 ("ms", (C.c_double * (RIPPLE_MAX_LAYERS + 1)) * RIPPLE_N_PHASES),
                 ("launches", (C.c_uint64 * (RIPPLE_MAX_LAYERS + 1)) * RIPPLE_N_PHASES),
                 ("rows", C.c_uint64 * (RIPPLE_MAX_LAYERS + 1)),
-                ("msgs", C.c_uint64 * (RIPPLE_MAX_LAYERS + 1))]
+                ("msgs", C.c_uint64 * (RIPPLE_MAX_LAYERS + 1)),
+                ("touched", C.c_uint64 * (RIPPLE_MAX_LAYERS + 1))]
 
 
 _lib = None

@@ -538,13 +538,13 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
                            c->n_words);
     for (uint32_t l = 1; l <= c->L; ++l) {
         t = rp_timer_begin(c);
-        rp_launch_frontier_mark(c, l, layer_self(c, l) ? 1 : 0);
+        rp_launch_frontier_mark(c, l);
         rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
         t = rp_timer_begin(c);
         rp_launch_scatter_push(c, l);
         rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l);
         t = rp_timer_begin(c);
-        rp_launch_frontier_compact(c, l, true, l < c->L, multi);
+        rp_launch_frontier_compact(c, l, layer_self(c, l), l < c->L, multi);
         rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l);
         t = rp_timer_begin(c);
         rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], l < c->L);
@@ -612,7 +612,7 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
 
     ripple_status rc = RIPPLE_OK;
     uint32_t applied = 0, rejected = 0, n_struct = 0, compactions = 0;
-    uint64_t msgs[RIPPLE_MAX_LAYERS + 1] = {0};
+    uint64_t msgs[RIPPLE_MAX_LAYERS + 1] = {0}, tchd[RIPPLE_MAX_LAYERS + 1] = {0};
     for (size_t p = 0; p < pieces.size() && rc == RIPPLE_OK; ++p) {
         const SubBatch &sb = pieces[p];
         const uint32_t n = sb.end - sb.begin;
@@ -659,7 +659,10 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
         applied += h.n_applied;
         rejected += h.n_rejected;
         n_struct += h.n_struct;
-        for (uint32_t l = 1; l <= c->L; ++l) msgs[l] += h.m[l];
+        for (uint32_t l = 1; l <= c->L; ++l) {
+            msgs[l] += h.m[l];
+            tchd[l] += h.touched[l];
+        }
         if (!multi)
             for (uint32_t l = 0; l <= c->L; ++l) c->last_a[l] = h.a[l];
     }
@@ -681,6 +684,7 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
         for (uint32_t l = 0; l <= c->L; ++l) {
             c->stats.rows[l] += c->last_a[l];
             c->stats.msgs[l] += msgs[l];
+            c->stats.touched[l] += tchd[l];
         }
     }
     if (res) {

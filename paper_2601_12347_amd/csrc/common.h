@@ -26,6 +26,7 @@
 struct DevCtr {                      // device-resident counters, one instance per context
     uint32_t a[RIPPLE_MAX_LAYERS + 1];        // |A_l|
     uint32_t m[RIPPLE_MAX_LAYERS + 1];        // out-edges walked from A_{l-1}
+    uint32_t touched[RIPPLE_MAX_LAYERS + 1];  // distinct live destinations of those edges
     uint32_t n_struct;
     uint32_t n_touch_out, n_touch_in;
     uint32_t n_exp;                           // expanded edges of deleted vertices

@@ -19,16 +19,14 @@ __device__ __forceinline__ uint32_t seg_search(const uint32_t *off, uint32_t lo,
 
 #define MARK_CHUNK 256
 
-// mark out-neighbours of every vertex of A_{l-1} (and A_{l-1} itself for layers with a self term)
+// mark the out-neighbours of every vertex of A_{l-1}
 __global__ __launch_bounds__(256) void k_frontier_mark(const uint32_t *list, const uint32_t *count_ptr,
                                                        const uint32_t *eoff, const uint2 *out_meta,
-                                                       const uint32_t *out_pool, uint32_t *bm, int self_term) {
+                                                       const uint32_t *out_pool, uint32_t *bm) {
     const uint32_t count = *count_ptr;
     if (count == 0) return;
     const int lane = rp_lane();
     const uint32_t gt = blockIdx.x * blockDim.x + threadIdx.x, nt = gridDim.x * blockDim.x;
-    if (self_term)
-        for (uint32_t i = gt; i < count; i += nt) rp_set_bit(bm, list[i]);
     const uint32_t M = eoff[count];
     const uint32_t n_chunks = (M + MARK_CHUNK - 1) / MARK_CHUNK;
     const uint32_t gw = gt >> 6, nw = nt >> 6;
@@ -45,20 +43,23 @@ __global__ __launch_bounds__(256) void k_frontier_mark(const uint32_t *list, con
     }
 }
 
-// pass 1: merge the root sets into the layer's bitmap, restrict to live vertices,
-// count vertices and (optionally) their out-degrees per block of 256 words
-__global__ __launch_bounds__(256) void k_frontier_count(uint32_t *bm, const uint32_t *bm_sink, const uint32_t *bm_vadd,
-                                                        const uint32_t *alive, uint32_t n_words, const uint2 *out_meta,
-                                                        int want_deg, uint32_t *part_cnt, uint32_t *part_deg,
-                                                        uint32_t *rep) {
-    __shared__ uint32_t sh[8];
+// pass 1: merge the root sets (S, V_added, and the previous hop's set when the layer has a
+// self term) into the layer's bitmap, restrict to live vertices, count vertices and
+// (optionally) their out-degrees per block of 256 words
+__global__ __launch_bounds__(256) void k_frontier_count(uint32_t *bm, const uint32_t *bm_prev, const uint32_t *bm_sink,
+                                                        const uint32_t *bm_vadd, const uint32_t *alive, uint32_t n_words,
+                                                        const uint2 *out_meta, int want_deg, uint32_t *part_cnt,
+                                                        uint32_t *part_deg, uint32_t *rep, uint32_t *touched_out) {
+    __shared__ uint32_t sh[12];
     const int tid = threadIdx.x;
     uint32_t idx = blockIdx.x * 256 + tid;
-    uint32_t w = 0;
+    uint32_t w = 0, tch = 0;
     if (idx < n_words) {
-        w = bm[idx];
-        if (bm_sink) w |= bm_sink[idx] | bm_vadd[idx];
-        w &= alive[idx];
+        const uint32_t live = alive[idx];
+        w = bm[idx] & live;
+        tch = __popc(w);                         // vertices that received at least one message
+        if (bm_sink) w |= (bm_sink[idx] | bm_vadd[idx]) & live;
+        if (bm_prev) w |= bm_prev[idx] & live;
         bm[idx] = w;
         if (rep && w) rep[idx] |= w;
     }
@@ -74,15 +75,19 @@ __global__ __launch_bounds__(256) void k_frontier_count(uint32_t *bm, const uint
     for (int o = 32; o > 0; o >>= 1) {
         cnt += __shfl_down(cnt, o);
         deg += __shfl_down(deg, o);
+        tch += __shfl_down(tch, o);
     }
     if ((tid & 63) == 0) {
         sh[tid >> 6] = cnt;
         sh[4 + (tid >> 6)] = deg;
+        sh[8 + (tid >> 6)] = tch;
     }
     __syncthreads();
     if (tid == 0) {
         part_cnt[blockIdx.x] = sh[0] + sh[1] + sh[2] + sh[3];
         part_deg[blockIdx.x] = sh[4] + sh[5] + sh[6] + sh[7];
+        const uint32_t t = sh[8] + sh[9] + sh[10] + sh[11];
+        if (touched_out && t) atomicAdd(touched_out, t);
     }
 }
 
@@ -192,18 +197,18 @@ __global__ __launch_bounds__(1024) void k_list_eoff(const uint32_t *list, const 
     }
 }
 
-void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l, int self_term) {
+void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l) {
     hipLaunchKernelGGL(k_frontier_mark, dim3(c->n_cu * 4), dim3(256), 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],
-                       c->eoff[l - 1], c->out_meta, c->out_pool, c->bm[l], self_term);
+                       c->eoff[l - 1], c->out_meta, c->out_pool, c->bm[l]);
 }
 
-// bitmap of layer l (merged with S and V_added when merge_roots) -> list[l], eoff[l], ctr->a[l], ctr->m[l+1]
-void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool merge_roots, bool want_deg, bool accumulate_rep) {
+// bitmap of layer l, merged with S, V_added (and A_{l-1} when self_term) -> list[l], eoff[l], ctr->a[l], ctr->m[l+1]
+void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool want_deg, bool accumulate_rep) {
     uint32_t nb = rp_div_up(c->n_words, 256);
     hipLaunchKernelGGL(k_frontier_count, dim3(nb), dim3(256), 0, c->stream, c->bm[l],
-                       merge_roots ? c->bm_sink : (const uint32_t *)nullptr, c->bm_vadd, c->alive, c->n_words,
-                       c->out_meta, want_deg ? 1 : 0, c->part_cnt, c->part_deg,
-                       accumulate_rep ? c->rep[l] : (uint32_t *)nullptr);
+                       self_term ? c->bm[l - 1] : (const uint32_t *)nullptr, c->bm_sink, c->bm_vadd, c->alive,
+                       c->n_words, c->out_meta, want_deg ? 1 : 0, c->part_cnt, c->part_deg,
+                       accumulate_rep ? c->rep[l] : (uint32_t *)nullptr, &c->ctr->touched[l]);
     hipLaunchKernelGGL(k_frontier_emit, dim3(nb), dim3(256), 0, c->stream, c->bm[l], c->n_words, c->out_meta,
                        want_deg ? 1 : 0, c->part_cnt, c->part_deg, c->list[l], c->eoff[l], &c->ctr->a[l],
                        (want_deg && l < RIPPLE_MAX_LAYERS) ? &c->ctr->m[l + 1] : (uint32_t *)nullptr);
@@ -213,8 +218,8 @@ void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool merge_roots, boo
 void rp_launch_bitmap_to_list(ripple_ctx *c, uint32_t *bitmap, uint32_t *out_list, uint32_t *count_d) {
     uint32_t nb = rp_div_up(c->n_words, 256);
     hipLaunchKernelGGL(k_frontier_count, dim3(nb), dim3(256), 0, c->stream, bitmap, (const uint32_t *)nullptr,
-                       (const uint32_t *)nullptr, c->alive, c->n_words, c->out_meta, 0, c->part_cnt, c->part_deg,
-                       (uint32_t *)nullptr);
+                       (const uint32_t *)nullptr, (const uint32_t *)nullptr, c->alive, c->n_words, c->out_meta, 0,
+                       c->part_cnt, c->part_deg, (uint32_t *)nullptr, (uint32_t *)nullptr);
     hipLaunchKernelGGL(k_frontier_emit, dim3(nb), dim3(256), 0, c->stream, bitmap, c->n_words, c->out_meta, 0,
                        c->part_cnt, c->part_deg, out_list, (uint32_t *)nullptr, count_d, (uint32_t *)nullptr);
 }

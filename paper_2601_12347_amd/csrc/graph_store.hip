@@ -677,6 +677,7 @@ __global__ void k_batch_reset(DevCtr *ctr, uint32_t *bitmaps, size_t n_bitmap_wo
         for (int l = 0; l <= RIPPLE_MAX_LAYERS; ++l) {
             ctr->a[l] = 0;
             ctr->m[l] = 0;
+            ctr->touched[l] = 0;
         }
         ctr->n_struct = 0;
         ctr->n_touch_out = ctr->n_touch_in = 0;

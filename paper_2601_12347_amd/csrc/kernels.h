@@ -13,8 +13,8 @@ void rp_launch_batch_reset(ripple_ctx *c);
 void rp_launch_mutate(ripple_ctx *c, uint32_t n_ops, bool has_vertex_del, bool has_vertex_or_feat);
 
 // frontier.hip
-void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l, int self_term);
-void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool merge_roots, bool want_deg, bool accumulate_rep);
+void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l);
+void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool want_deg, bool accumulate_rep);
 void rp_launch_bitmap_to_list(ripple_ctx *c, uint32_t *bitmap, uint32_t *out_list, uint32_t *count_d);
 void rp_launch_list_eoff(ripple_ctx *c, uint32_t l);
 
