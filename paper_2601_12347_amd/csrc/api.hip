@@ -193,6 +193,7 @@ extern "C" ripple_status ripple_init_graph(ripple_ctx **out, uint32_t n_vertices
     c->n_part = std::max(rp_div_up(n, 1024), rp_div_up(c->n_words, 256)) + 1;
     RP_TRY(dev_alloc(c, &c->part_cnt, (size_t)c->n_part, true));
     RP_TRY(dev_alloc(c, &c->part_deg, (size_t)c->n_part, true));
+    RP_TRY(dev_alloc(c, &c->part_ideg, (size_t)c->n_part, true));
     RP_TRY(dev_alloc(c, &c->ctr, 1, true));
     RP_HIP(c, hipHostMalloc((void **)&c->ctr_host, sizeof(DevCtr), hipHostMallocDefault));
     memset(c->ctr_host, 0, sizeof(DevCtr));
@@ -232,7 +233,7 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
     if (!c) return;
     hipStreamSynchronize(c->stream);
     void *ptrs[] = {c->out_meta, c->in_meta, c->out_capv, c->in_capv, c->vstate, c->pend_out, c->pend_in, c->dead_out,
-                    c->dead_in, c->out_pool, c->in_pool, c->alive, c->part_cnt, c->part_deg, c->ctr, c->D[0], c->D[1],
+                    c->dead_in, c->out_pool, c->in_pool, c->alive, c->part_cnt, c->part_deg, c->part_ideg, c->ioff[0], c->wrank[0], c->ctr, c->D[0], c->D[1],
                     c->tmp, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ops_d, c->payload_d,
                     c->op_status, c->op_pos_out, c->op_pos_in, c->touch_out, c->touch_in, c->exp_kind, c->exp_a,
                     c->exp_b, c->st_src, c->st_dst, c->st_sign, c->gather_d, c->gather_ids};
@@ -332,16 +333,20 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
     RP_TRY(dev_alloc(c, &c->D[1], n * c->dmax, false));
     if (c->hmax) RP_TRY(dev_alloc(c, &c->tmp, n * c->hmax, false));
     // bitmaps: layers 0..L, then S, then V_added, contiguous; reporting copies separately
-    uint32_t *bmall = nullptr, *repall = nullptr, *lists = nullptr, *eoffs = nullptr;
+    uint32_t *bmall = nullptr, *repall = nullptr, *lists = nullptr, *eoffs = nullptr, *ioffs = nullptr, *wranks = nullptr;
     RP_TRY(dev_alloc(c, &bmall, (size_t)c->n_words * (c->L + 3), true));
     RP_TRY(dev_alloc(c, &repall, (size_t)c->n_words * (c->L + 1), true));
     RP_TRY(dev_alloc(c, &lists, (n + 1) * (c->L + 1), true));
     RP_TRY(dev_alloc(c, &eoffs, (n + 1) * (c->L + 1), true));
+    RP_TRY(dev_alloc(c, &ioffs, (n + 1) * (c->L + 1), true));
+    RP_TRY(dev_alloc(c, &wranks, (size_t)c->n_words * (c->L + 1), true));
     for (uint32_t l = 0; l <= c->L; ++l) {
         c->bm[l] = bmall + (size_t)l * c->n_words;
         c->rep[l] = repall + (size_t)l * c->n_words;
         c->list[l] = lists + (size_t)l * (n + 1);
         c->eoff[l] = eoffs + (size_t)l * (n + 1);
+        c->ioff[l] = ioffs + (size_t)l * (n + 1);
+        c->wrank[l] = wranks + (size_t)l * c->n_words;
     }
     c->bm_sink = bmall + (size_t)(c->L + 1) * c->n_words;
     c->bm_vadd = bmall + (size_t)(c->L + 2) * c->n_words;
@@ -537,15 +542,18 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
         hipLaunchKernelGGL(k_or_words, dim3(rp_div_up(c->n_words, 256)), dim3(256), 0, c->stream, c->rep[0], c->bm[0],
                            c->n_words);
     for (uint32_t l = 1; l <= c->L; ++l) {
+        // hop 1 always pushes: hop-0 rows are in operation order, not ranked by vertex id
+        const bool may_pull = l >= 2 && c->opt_scatter != 1;
         t = rp_timer_begin(c);
         rp_launch_frontier_mark(c, l);
         rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
         t = rp_timer_begin(c);
-        rp_launch_scatter_push(c, l);
-        rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l);
-        t = rp_timer_begin(c);
-        rp_launch_frontier_compact(c, l, layer_self(c, l), l < c->L, multi);
+        rp_launch_frontier_compact(c, l, layer_self(c, l), l < c->L, true, multi);
         rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l);
+        t = rp_timer_begin(c);
+        if (c->opt_scatter != 2 || !may_pull) rp_launch_scatter_push(c, l, may_pull);
+        if (may_pull) rp_launch_scatter_pull(c, l);
+        rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l);
         t = rp_timer_begin(c);
         rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], l < c->L);
         rp_timer_end(c, t, RIPPLE_PH_TRANSFORM, (int)l);
@@ -869,6 +877,10 @@ extern "C" ripple_status ripple_set_option(ripple_ctx *c, int option, int64_t va
     case RIPPLE_OPT_SCATTER_MODE:
         if (value < 0 || value > 2) return fail(c, RIPPLE_EINVAL, "scatter mode must be 0, 1 or 2");
         c->opt_scatter = (int)value;
+        return RIPPLE_OK;
+    case RIPPLE_OPT_PULL_RATIO:
+        if (value < 1 || value > 1024) return fail(c, RIPPLE_EINVAL, "pull ratio must be in 1..1024");
+        c->opt_pull_ratio = (int)value;
         return RIPPLE_OK;
     default: return fail(c, RIPPLE_EINVAL, "unknown option");
     }

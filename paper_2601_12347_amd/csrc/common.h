@@ -27,6 +27,7 @@ struct DevCtr {                      // device-resident counters, one instance p
     uint32_t a[RIPPLE_MAX_LAYERS + 1];        // |A_l|
     uint32_t m[RIPPLE_MAX_LAYERS + 1];        // out-edges walked from A_{l-1}
     uint32_t touched[RIPPLE_MAX_LAYERS + 1];  // distinct live destinations of those edges
+    uint32_t isum[RIPPLE_MAX_LAYERS + 1];     // sum of in-degrees over A_l
     uint32_t n_struct;
     uint32_t n_touch_out, n_touch_in;
     uint32_t n_exp;                           // expanded edges of deleted vertices
@@ -91,7 +92,9 @@ struct ripple_ctx {
     uint32_t *rep[RIPPLE_MAX_LAYERS + 1] = {nullptr};   // union over sub-batches (reporting)
     uint32_t *list[RIPPLE_MAX_LAYERS + 1] = {nullptr};  // A_l, ascending (l >= 1); op order for l = 0
     uint32_t *eoff[RIPPLE_MAX_LAYERS + 1] = {nullptr};  // exclusive scan of out-degrees over A_l, +1 entry
-    uint32_t *part_cnt = nullptr, *part_deg = nullptr;  // per-block partial sums of the compaction
+    uint32_t *part_cnt = nullptr, *part_deg = nullptr, *part_ideg = nullptr;  // per-block partial sums
+    uint32_t *ioff[RIPPLE_MAX_LAYERS + 1] = {nullptr};  // exclusive scan of in-degrees over A_l, +1 entry
+    uint32_t *wrank[RIPPLE_MAX_LAYERS + 1] = {nullptr}; // list position of the first vertex of each bitmap word
     uint32_t n_part = 0;
     uint32_t *all_list = nullptr;                       // scratch list (live vertices) for full inference
 
@@ -125,6 +128,7 @@ struct ripple_ctx {
     // options
     int opt_timing = 0;
     int opt_scatter = 0;
+    int opt_pull_ratio = 2;                     // pull when messages * width * ratio >= scanned in-edges
     ripple_stats stats;
     PhaseTimer *timer = nullptr;
     uint32_t n_cu = 256;

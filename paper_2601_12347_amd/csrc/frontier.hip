@@ -6,6 +6,7 @@
 // wavefronts regardless of degree skew.
 #include "common.h"
 #include "kernels.h"
+#include <cstring>
 
 // largest i in [lo, hi] with off[i] <= e   (off is non-decreasing, off[lo] <= e)
 __device__ __forceinline__ uint32_t seg_search(const uint32_t *off, uint32_t lo, uint32_t hi, uint32_t e) {
@@ -43,124 +44,151 @@ __global__ __launch_bounds__(256) void k_frontier_mark(const uint32_t *list, con
     }
 }
 
+struct CompactArgs {
+    uint32_t *bm;                  // the layer's bitmap: out-neighbour marks in, final set out
+    const uint32_t *bm_prev;       // previous hop's set (layers with a self term) or null
+    const uint32_t *bm_sink;       // S or null
+    const uint32_t *bm_vadd;       // V_added (read only when bm_sink is set)
+    const uint32_t *alive;
+    uint32_t n_words;
+    const uint2 *out_meta, *in_meta;
+    int want_out, want_in;         // emit out-degree / in-degree prefixes over the list
+    uint32_t *part_cnt, *part_out, *part_in;
+    uint32_t *rep;                 // reporting union or null
+    uint32_t *touched_out;         // += vertices that received a message, or null
+    uint32_t *list, *eoff, *ioff;  // outputs
+    uint32_t *wrank;               // per bitmap word: list position of its first vertex, or null
+    uint32_t *count_out, *msgs_out, *isum_out;
+};
+
+__device__ __forceinline__ void word_degrees(const CompactArgs &a, uint32_t idx, uint32_t w, uint32_t &dout,
+                                             uint32_t &din) {
+    dout = din = 0;
+    if (!(a.want_out | a.want_in)) return;
+    while (w) {
+        uint32_t v = idx * 32 + (__ffs(w) - 1);
+        w &= w - 1;
+        if (a.want_out) dout += a.out_meta[v].y;
+        if (a.want_in) din += a.in_meta[v].y;
+    }
+}
+
 // pass 1: merge the root sets (S, V_added, and the previous hop's set when the layer has a
 // self term) into the layer's bitmap, restrict to live vertices, count vertices and
-// (optionally) their out-degrees per block of 256 words
-__global__ __launch_bounds__(256) void k_frontier_count(uint32_t *bm, const uint32_t *bm_prev, const uint32_t *bm_sink,
-                                                        const uint32_t *bm_vadd, const uint32_t *alive, uint32_t n_words,
-                                                        const uint2 *out_meta, int want_deg, uint32_t *part_cnt,
-                                                        uint32_t *part_deg, uint32_t *rep, uint32_t *touched_out) {
-    __shared__ uint32_t sh[12];
+// (optionally) their degrees per block of 256 words
+__global__ __launch_bounds__(256) void k_frontier_count(CompactArgs a) {
+    __shared__ uint32_t sh[16];
     const int tid = threadIdx.x;
     uint32_t idx = blockIdx.x * 256 + tid;
     uint32_t w = 0, tch = 0;
-    if (idx < n_words) {
-        const uint32_t live = alive[idx];
-        w = bm[idx] & live;
+    if (idx < a.n_words) {
+        const uint32_t live = a.alive[idx];
+        w = a.bm[idx] & live;
         tch = __popc(w);                         // vertices that received at least one message
-        if (bm_sink) w |= (bm_sink[idx] | bm_vadd[idx]) & live;
-        if (bm_prev) w |= bm_prev[idx] & live;
-        bm[idx] = w;
-        if (rep && w) rep[idx] |= w;
+        if (a.bm_sink) w |= (a.bm_sink[idx] | a.bm_vadd[idx]) & live;
+        if (a.bm_prev) w |= a.bm_prev[idx] & live;
+        a.bm[idx] = w;
+        if (a.rep && w) a.rep[idx] |= w;
     }
-    uint32_t cnt = __popc(w), deg = 0;
-    if (want_deg) {
-        uint32_t t = w;
-        while (t) {
-            uint32_t b = __ffs(t) - 1;
-            t &= t - 1;
-            deg += out_meta[idx * 32 + b].y;
-        }
-    }
+    uint32_t cnt = __popc(w), dout, din;
+    word_degrees(a, idx, w, dout, din);
     for (int o = 32; o > 0; o >>= 1) {
         cnt += __shfl_down(cnt, o);
-        deg += __shfl_down(deg, o);
+        dout += __shfl_down(dout, o);
+        din += __shfl_down(din, o);
         tch += __shfl_down(tch, o);
     }
     if ((tid & 63) == 0) {
         sh[tid >> 6] = cnt;
-        sh[4 + (tid >> 6)] = deg;
-        sh[8 + (tid >> 6)] = tch;
+        sh[4 + (tid >> 6)] = dout;
+        sh[8 + (tid >> 6)] = din;
+        sh[12 + (tid >> 6)] = tch;
     }
     __syncthreads();
     if (tid == 0) {
-        part_cnt[blockIdx.x] = sh[0] + sh[1] + sh[2] + sh[3];
-        part_deg[blockIdx.x] = sh[4] + sh[5] + sh[6] + sh[7];
-        const uint32_t t = sh[8] + sh[9] + sh[10] + sh[11];
-        if (touched_out && t) atomicAdd(touched_out, t);
+        a.part_cnt[blockIdx.x] = sh[0] + sh[1] + sh[2] + sh[3];
+        a.part_out[blockIdx.x] = sh[4] + sh[5] + sh[6] + sh[7];
+        a.part_in[blockIdx.x] = sh[8] + sh[9] + sh[10] + sh[11];
+        const uint32_t t = sh[12] + sh[13] + sh[14] + sh[15];
+        if (a.touched_out && t) atomicAdd(a.touched_out, t);
     }
 }
 
-// pass 2: write the ascending list and the out-degree prefix
-__global__ __launch_bounds__(256) void k_frontier_emit(const uint32_t *bm, uint32_t n_words, const uint2 *out_meta,
-                                                       int want_deg, const uint32_t *part_cnt, const uint32_t *part_deg,
-                                                       uint32_t *list, uint32_t *eoff, uint32_t *count_out,
-                                                       uint32_t *msgs_out) {
-    __shared__ uint32_t sh[8];
-    __shared__ uint32_t wc[4], wd[4];
+// pass 2: write the ascending list, the degree prefixes and the per-word ranks
+__global__ __launch_bounds__(256) void k_frontier_emit(CompactArgs a) {
+    __shared__ uint32_t sh[12];
+    __shared__ uint32_t wc[4], wo[4], wi[4];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    uint32_t pc = 0, pd = 0;
+    uint32_t pc = 0, po = 0, pi = 0;
     for (uint32_t b = tid; b < blockIdx.x; b += 256) {
-        pc += part_cnt[b];
-        pd += part_deg[b];
+        pc += a.part_cnt[b];
+        po += a.part_out[b];
+        pi += a.part_in[b];
     }
     for (int o = 32; o > 0; o >>= 1) {
         pc += __shfl_down(pc, o);
-        pd += __shfl_down(pd, o);
+        po += __shfl_down(po, o);
+        pi += __shfl_down(pi, o);
     }
     if (lane == 0) {
         sh[wave] = pc;
-        sh[4 + wave] = pd;
+        sh[4 + wave] = po;
+        sh[8 + wave] = pi;
     }
     __syncthreads();
     pc = sh[0] + sh[1] + sh[2] + sh[3];
-    pd = sh[4] + sh[5] + sh[6] + sh[7];
+    po = sh[4] + sh[5] + sh[6] + sh[7];
+    pi = sh[8] + sh[9] + sh[10] + sh[11];
     uint32_t idx = blockIdx.x * 256 + tid;
-    uint32_t w = (idx < n_words) ? bm[idx] : 0u;
-    uint32_t cnt = __popc(w), deg = 0;
-    if (want_deg) {
-        uint32_t t = w;
-        while (t) {
-            uint32_t b = __ffs(t) - 1;
-            t &= t - 1;
-            deg += out_meta[idx * 32 + b].y;
-        }
-    }
-    uint32_t ic = cnt, id = deg;
+    uint32_t w = (idx < a.n_words) ? a.bm[idx] : 0u;
+    uint32_t cnt = __popc(w), dout, din;
+    word_degrees(a, idx, w, dout, din);
+    uint32_t ic = cnt, io = dout, ii = din;
     for (int o = 1; o < 64; o <<= 1) {
-        uint32_t tc = __shfl_up(ic, o), td = __shfl_up(id, o);
+        uint32_t tc = __shfl_up(ic, o), to = __shfl_up(io, o), ti = __shfl_up(ii, o);
         if (lane >= o) {
             ic += tc;
-            id += td;
+            io += to;
+            ii += ti;
         }
     }
     if (lane == 63) {
         wc[wave] = ic;
-        wd[wave] = id;
+        wo[wave] = io;
+        wi[wave] = ii;
     }
     __syncthreads();
-    uint32_t oc = pc + ic - cnt, od = pd + id - deg;
+    uint32_t oc = pc + ic - cnt, oo = po + io - dout, oi = pi + ii - din;
     for (int k = 0; k < wave; ++k) {
         oc += wc[k];
-        od += wd[k];
+        oo += wo[k];
+        oi += wi[k];
     }
+    if (a.wrank && idx < a.n_words) a.wrank[idx] = oc;
     uint32_t t = w;
     while (t) {
-        uint32_t b = __ffs(t) - 1;
+        uint32_t v = idx * 32 + (__ffs(t) - 1);
         t &= t - 1;
-        uint32_t v = idx * 32 + b;
-        list[oc] = v;
-        if (want_deg) {
-            eoff[oc] = od;
-            od += out_meta[v].y;
+        a.list[oc] = v;
+        if (a.want_out) {
+            a.eoff[oc] = oo;
+            oo += a.out_meta[v].y;
+        }
+        if (a.want_in) {
+            a.ioff[oc] = oi;
+            oi += a.in_meta[v].y;
         }
         ++oc;
     }
-    if (blockIdx.x == gridDim.x - 1 && tid == 255) {     // oc/od now hold the grand totals
-        *count_out = oc;
-        if (want_deg) {
-            eoff[oc] = od;
-            if (msgs_out) *msgs_out = od;
+    if (blockIdx.x == gridDim.x - 1 && tid == 255) {     // the running values now hold the grand totals
+        *a.count_out = oc;
+        if (a.want_out) {
+            a.eoff[oc] = oo;
+            if (a.msgs_out) *a.msgs_out = oo;
+        }
+        if (a.want_in) {
+            a.ioff[oc] = oi;
+            if (a.isum_out) *a.isum_out = oi;
         }
     }
 }
@@ -202,26 +230,55 @@ void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l) {
                        c->eoff[l - 1], c->out_meta, c->out_pool, c->bm[l]);
 }
 
-// bitmap of layer l, merged with S, V_added (and A_{l-1} when self_term) -> list[l], eoff[l], ctr->a[l], ctr->m[l+1]
-void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool want_deg, bool accumulate_rep) {
+// bitmap of layer l, merged with S, V_added (and A_{l-1} when self_term) -> list[l], ctr->a[l];
+// want_out: eoff[l] and ctr->m[l+1] (the next hop's edge walk); want_in: ioff[l], ctr->isum[l], wrank[l]
+void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool want_out, bool want_in,
+                                bool accumulate_rep) {
     uint32_t nb = rp_div_up(c->n_words, 256);
-    hipLaunchKernelGGL(k_frontier_count, dim3(nb), dim3(256), 0, c->stream, c->bm[l],
-                       self_term ? c->bm[l - 1] : (const uint32_t *)nullptr, c->bm_sink, c->bm_vadd, c->alive,
-                       c->n_words, c->out_meta, want_deg ? 1 : 0, c->part_cnt, c->part_deg,
-                       accumulate_rep ? c->rep[l] : (uint32_t *)nullptr, &c->ctr->touched[l]);
-    hipLaunchKernelGGL(k_frontier_emit, dim3(nb), dim3(256), 0, c->stream, c->bm[l], c->n_words, c->out_meta,
-                       want_deg ? 1 : 0, c->part_cnt, c->part_deg, c->list[l], c->eoff[l], &c->ctr->a[l],
-                       (want_deg && l < RIPPLE_MAX_LAYERS) ? &c->ctr->m[l + 1] : (uint32_t *)nullptr);
+    CompactArgs a;
+    a.bm = c->bm[l];
+    a.bm_prev = self_term ? c->bm[l - 1] : nullptr;
+    a.bm_sink = c->bm_sink;
+    a.bm_vadd = c->bm_vadd;
+    a.alive = c->alive;
+    a.n_words = c->n_words;
+    a.out_meta = c->out_meta;
+    a.in_meta = c->in_meta;
+    a.want_out = want_out ? 1 : 0;
+    a.want_in = want_in ? 1 : 0;
+    a.part_cnt = c->part_cnt;
+    a.part_out = c->part_deg;
+    a.part_in = c->part_ideg;
+    a.rep = accumulate_rep ? c->rep[l] : nullptr;
+    a.touched_out = &c->ctr->touched[l];
+    a.list = c->list[l];
+    a.eoff = c->eoff[l];
+    a.ioff = c->ioff[l];
+    a.wrank = c->wrank[l];
+    a.count_out = &c->ctr->a[l];
+    a.msgs_out = (l < RIPPLE_MAX_LAYERS) ? &c->ctr->m[l + 1] : nullptr;
+    a.isum_out = &c->ctr->isum[l];
+    hipLaunchKernelGGL(k_frontier_count, dim3(nb), dim3(256), 0, c->stream, a);
+    hipLaunchKernelGGL(k_frontier_emit, dim3(nb), dim3(256), 0, c->stream, a);
 }
 
 // any bitmap & alive -> ascending list in `out_list`, count in *count_d (device)
 void rp_launch_bitmap_to_list(ripple_ctx *c, uint32_t *bitmap, uint32_t *out_list, uint32_t *count_d) {
     uint32_t nb = rp_div_up(c->n_words, 256);
-    hipLaunchKernelGGL(k_frontier_count, dim3(nb), dim3(256), 0, c->stream, bitmap, (const uint32_t *)nullptr,
-                       (const uint32_t *)nullptr, (const uint32_t *)nullptr, c->alive, c->n_words, c->out_meta, 0,
-                       c->part_cnt, c->part_deg, (uint32_t *)nullptr, (uint32_t *)nullptr);
-    hipLaunchKernelGGL(k_frontier_emit, dim3(nb), dim3(256), 0, c->stream, bitmap, c->n_words, c->out_meta, 0,
-                       c->part_cnt, c->part_deg, out_list, (uint32_t *)nullptr, count_d, (uint32_t *)nullptr);
+    CompactArgs a;
+    memset(&a, 0, sizeof(a));
+    a.bm = bitmap;
+    a.alive = c->alive;
+    a.n_words = c->n_words;
+    a.out_meta = c->out_meta;
+    a.in_meta = c->in_meta;
+    a.part_cnt = c->part_cnt;
+    a.part_out = c->part_deg;
+    a.part_in = c->part_ideg;
+    a.list = out_list;
+    a.count_out = count_d;
+    hipLaunchKernelGGL(k_frontier_count, dim3(nb), dim3(256), 0, c->stream, a);
+    hipLaunchKernelGGL(k_frontier_emit, dim3(nb), dim3(256), 0, c->stream, a);
 }
 
 void rp_launch_list_eoff(ripple_ctx *c, uint32_t l) {

@@ -14,12 +14,14 @@ void rp_launch_mutate(ripple_ctx *c, uint32_t n_ops, bool has_vertex_del, bool h
 
 // frontier.hip
 void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l);
-void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool want_deg, bool accumulate_rep);
+void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool want_out, bool want_in,
+                                bool accumulate_rep);
 void rp_launch_bitmap_to_list(ripple_ctx *c, uint32_t *bitmap, uint32_t *out_list, uint32_t *count_d);
 void rp_launch_list_eoff(ripple_ctx *c, uint32_t l);
 
 // scatter.hip
-void rp_launch_scatter_push(ripple_ctx *c, uint32_t l);
+void rp_launch_scatter_push(ripple_ctx *c, uint32_t l, bool may_pull);
+void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l);
 void rp_launch_pull_all(ripple_ctx *c, uint32_t l);
 
 // transform.hip

@@ -24,11 +24,25 @@ __device__ __forceinline__ uint32_t seg_search2(const uint32_t *off, uint32_t lo
 }
 
 #define PUSH_CHUNK 64
+#define PULL_CHUNK 256
+
+// Direction of hop l, decided on the device from the hop's own counters so that no host
+// round trip is needed: pulling scans every in-edge of A_l (index + dirty-bit probe, ~8 bytes
+// each) but gathers each message once without atomics; pushing touches only the messages but
+// pays a read-modify-write per message.
+__device__ __forceinline__ bool rp_use_pull(const DevCtr *ctr, uint32_t l, uint32_t d, int mode, int ratio) {
+    if (mode == 2) return true;
+    if (mode == 1) return false;
+    const unsigned long long m = ctr->m[l], in_edges = ctr->isum[l];
+    return m > 0 && m * d * 4ull * (unsigned long long)ratio >= 8ull * in_edges;
+}
 
 template <int NJ>
 __global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, const uint32_t *count_ptr,
                                                       const uint32_t *eoff, const float *D, uint32_t d,
-                                                      const uint2 *out_meta, const uint32_t *out_pool, float *X) {
+                                                      const uint2 *out_meta, const uint32_t *out_pool, float *X,
+                                                      const DevCtr *ctr, uint32_t l, int may_pull, int mode, int ratio) {
+    if (may_pull && rp_use_pull(ctr, l, d, mode, ratio)) return;
     const uint32_t count = *count_ptr;
     if (count == 0) return;
     const int lane = rp_lane();
@@ -73,19 +87,145 @@ __global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, cons
     }
 }
 
-void rp_launch_scatter_push(ripple_ctx *c, uint32_t l) {
+void rp_launch_scatter_push(ripple_ctx *c, uint32_t l, bool may_pull) {
     const uint32_t d = c->d[l - 1];
     const float *D = c->D[(l - 1) & 1];
     dim3 grid(c->n_cu * 8), block(256);
 #define PUSH_CASE(NJ)                                                                                         \
     hipLaunchKernelGGL(k_scatter_push<NJ>, grid, block, 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],      \
-                       c->eoff[l - 1], D, d, c->out_meta, c->out_pool, c->X[l])
+                       c->eoff[l - 1], D, d, c->out_meta, c->out_pool, c->X[l], c->ctr, l, may_pull ? 1 : 0,          \
+                       c->opt_scatter, c->opt_pull_ratio)
     if (d <= 64) PUSH_CASE(1);
     else if (d <= 128) PUSH_CASE(2);
     else if (d <= 256) PUSH_CASE(4);
     else if (d <= 512) PUSH_CASE(8);
     else PUSH_CASE(16);
 #undef PUSH_CASE
+}
+
+// ---------------------------------------------------------------------------------
+// pull: segmented reduction over the in-rows of A_l, keeping only dirty sources
+// ---------------------------------------------------------------------------------
+struct PullArgs {
+    const uint32_t *list;          // A_l
+    const uint32_t *count_ptr;
+    const uint32_t *ioff;          // in-degree prefix over A_l
+    const uint2 *in_meta;
+    const uint32_t *in_pool;
+    const uint32_t *bm_prev;       // A_{l-1} as bitmap
+    const uint32_t *wrank_prev;    // rank of each bitmap word's first vertex in A_{l-1}
+    const float *D;                // delta rows of A_{l-1}, row = rank
+    uint32_t d;
+    float *X;
+    const DevCtr *ctr;
+    uint32_t l;
+    int mode, ratio;
+};
+
+template <int NJ>
+__global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
+    if (!rp_use_pull(a.ctr, a.l, a.d, a.mode, a.ratio)) return;
+    const uint32_t count = *a.count_ptr;
+    if (count == 0) return;
+    const int lane = rp_lane();
+    const uint32_t d = a.d;
+    const uint32_t total = a.ioff[count];
+    const uint32_t n_chunks = (total + PULL_CHUNK - 1) / PULL_CHUNK;
+    const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    for (uint32_t c = gw; c < n_chunks; c += nw) {
+        const uint32_t e0 = c * PULL_CHUNK, e1 = min(total, e0 + PULL_CHUNK);
+        const uint32_t i_lo = seg_search2(a.ioff, 0, count - 1, e0);
+        const uint32_t i_hi = seg_search2(a.ioff, i_lo, count - 1, e1 - 1);
+        uint32_t cur = i_lo;
+        float acc[NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
+        for (uint32_t eb = e0; eb < e1; eb += 64) {
+            const uint32_t e = eb + lane;
+            const bool valid = e < e1;
+            uint32_t my_i = 0, slot = 0;
+            bool dirty = false;
+            if (valid) {
+                my_i = seg_search2(a.ioff, i_lo, i_hi, e);
+                const uint32_t u = a.in_pool[a.in_meta[a.list[my_i]].x + (e - a.ioff[my_i])];
+                const uint32_t word = a.bm_prev[u >> 5];
+                dirty = (word >> (u & 31)) & 1u;
+                if (dirty) slot = a.wrank_prev[u >> 5] + __popc(word & ((1u << (u & 31)) - 1u));
+            }
+            unsigned long long mask = __ballot(dirty);
+            while (mask) {
+                int kk[4];
+                int n = 0;
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    kk[t] = 0;
+                    if (mask) {
+                        kk[t] = __ffsll((long long)mask) - 1;
+                        mask &= mask - 1;
+                        n = t + 1;
+                    }
+                }
+                float r[4][NJ];
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    const uint32_t sk = __shfl(slot, kk[t]);
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) {
+                        const uint32_t col = lane + 64 * j;
+                        r[t][j] = (t < n && col < d) ? a.D[(size_t)sk * d + col] : 0.0f;
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < 4; ++t) {
+                    if (t < n) {
+                        const uint32_t ik = __shfl(my_i, kk[t]);
+                        if (ik != cur) {                     // the destination changes: flush its partial sum
+                            float *xr = a.X + (size_t)a.list[cur] * d;
+#pragma unroll
+                            for (int j = 0; j < NJ; ++j) {
+                                const uint32_t col = lane + 64 * j;
+                                if (col < d && acc[j] != 0.0f) unsafeAtomicAdd(&xr[col], acc[j]);
+                                acc[j] = 0.0f;
+                            }
+                            cur = ik;
+                        }
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j) acc[j] += r[t][j];
+                    }
+                }
+            }
+        }
+        float *xr = a.X + (size_t)a.list[cur] * d;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const uint32_t col = lane + 64 * j;
+            if (col < d && acc[j] != 0.0f) unsafeAtomicAdd(&xr[col], acc[j]);
+        }
+    }
+}
+
+void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l) {
+    PullArgs a;
+    a.list = c->list[l];
+    a.count_ptr = &c->ctr->a[l];
+    a.ioff = c->ioff[l];
+    a.in_meta = c->in_meta;
+    a.in_pool = c->in_pool;
+    a.bm_prev = c->bm[l - 1];
+    a.wrank_prev = c->wrank[l - 1];
+    a.D = c->D[(l - 1) & 1];
+    a.d = c->d[l - 1];
+    a.X = c->X[l];
+    a.ctr = c->ctr;
+    a.l = l;
+    a.mode = c->opt_scatter;
+    a.ratio = c->opt_pull_ratio;
+    dim3 grid(c->n_cu * 8), block(256);
+    if (a.d <= 64) hipLaunchKernelGGL(k_scatter_pull<1>, grid, block, 0, c->stream, a);
+    else if (a.d <= 128) hipLaunchKernelGGL(k_scatter_pull<2>, grid, block, 0, c->stream, a);
+    else if (a.d <= 256) hipLaunchKernelGGL(k_scatter_pull<4>, grid, block, 0, c->stream, a);
+    else if (a.d <= 512) hipLaunchKernelGGL(k_scatter_pull<8>, grid, block, 0, c->stream, a);
+    else hipLaunchKernelGGL(k_scatter_pull<16>, grid, block, 0, c->stream, a);
 }
 
 // ---------------------------------------------------------------------------------

@@ -54,6 +54,27 @@ def test_vertex_additions_and_deletions(kind, widths):
         pair.close()
 
 
+@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("kind,widths", [("sage_mean", (16, 40, 24, 10)), ("gcn_sum", (100, 256, 70)),
+                                         ("gin_sum", (16, 32, 12, 6))])
+def test_push_and_pull_scatter_agree_with_oracle(mode, kind, widths):
+    """Both directions of the delta aggregation (float atomics from the sources; segmented
+    reduction over the destinations' in-rows) must give the same result."""
+    print("case scatter mode", mode, kind, flush=True)
+    pair, graph = make_pair(n=900, e=9000, d0=widths[0], kind=kind, widths=widths, seed=51, slack=128)
+    rp.ripple_set_option(pair.ctx, rp.OPT_SCATTER_MODE, mode)
+    stream = make_stream(pair, graph, MIXV, 53)
+    try:
+        for b, bs in enumerate([3, 40, 200]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload)
+        pair.check_graph()
+        pair.check_aggregates()
+    finally:
+        pair.close()
+
+
 def test_tiny_config_batches():
     cfg = ri.get_config("tiny_gcn_sum")
     print("case tiny config", flush=True)
