@@ -205,48 +205,86 @@ def _act(name: str, z: np.ndarray) -> np.ndarray:
     raise ValueError(name)
 
 
-def aggregate(state: GraphState, h_prev: np.ndarray, agg: str) -> np.ndarray:
-    """Eq. (1): x_v = AGG over in-neighbours u of v of h_prev[u] (Table 1)."""
+def in_adjacency(state: GraphState) -> sp.csr_matrix:
+    """Sparse matrix with a 1 at (v, u) for every edge u -> v: row v lists v's in-neighbours."""
     src, dst = state.edges()
-    a_in = sp.csr_matrix((np.ones(src.size), (dst, src)), shape=(state.cap, state.cap))
-    x = a_in @ h_prev                                            # sum over in-neighbours
+    return sp.csr_matrix((np.ones(src.size), (dst, src)), shape=(state.cap, state.cap))
+
+
+def aggregate(a_in: sp.csr_matrix, h_prev: np.ndarray, agg: str, rows=None) -> np.ndarray:
+    """Eq. (1): x_v = AGG over in-neighbours u of v of h_prev[u] (Table 1), for all v or for `rows`."""
+    a = a_in if rows is None else a_in[rows]
+    x = a @ h_prev                                               # sum over in-neighbours
     if agg == "mean":
-        deg = np.bincount(dst, minlength=state.cap).astype(np.float64)
+        deg = np.asarray(a.getnnz(axis=1), dtype=np.float64)     # in-degree
         x = x / np.maximum(deg, 1.0)[:, None]                    # empty neighbourhood: 0
     elif agg != "sum":
         raise ValueError(agg)
     return x
 
 
-def layer_forward(state: GraphState, layer: dict, h_prev: np.ndarray) -> np.ndarray:
-    """Eq. (2): h_v = act(UPDATE(h_prev[v], x_v)) for every live vertex; dead rows are 0."""
+def layer_rows(state: GraphState, layer: dict, h_prev: np.ndarray, a_in: sp.csr_matrix, rows=None) -> np.ndarray:
+    """Eq. (2): h_v = act(UPDATE(h_prev[v], x_v)) for all vertices or for `rows`; dead rows are 0."""
     d_in = layer["d_in"]
-    x = aggregate(state, h_prev, layer["agg"])
+    x = aggregate(a_in, h_prev, layer["agg"], rows)
+    own = h_prev if rows is None else h_prev[rows]
     w0 = np.asarray(layer["W0"], dtype=np.float64)
     b0 = np.asarray(layer["b0"], dtype=np.float64)
     if layer["self"] == "none":
         z = x @ w0 + b0
     elif layer["self"] == "concat":
-        z = h_prev @ w0[:d_in] + x @ w0[d_in:] + b0
+        z = own @ w0[:d_in] + x @ w0[d_in:] + b0
     elif layer["self"] == "add":
-        z = ((1.0 + layer["eps"]) * h_prev + x) @ w0 + b0
+        z = ((1.0 + layer["eps"]) * own + x) @ w0 + b0
     else:
         raise ValueError(layer["self"])
     if layer["d_hidden"]:
         z = _act(layer["act_inner"], z)
         z = z @ np.asarray(layer["W1"], dtype=np.float64) + np.asarray(layer["b1"], dtype=np.float64)
     h = _act(layer["act_out"], z)
-    h[~state.alive] = 0.0
+    alive = state.alive if rows is None else state.alive[rows]
+    h[~alive] = 0.0
     return h
+
+
+def layer_forward(state: GraphState, layer: dict, h_prev: np.ndarray) -> np.ndarray:
+    return layer_rows(state, layer, h_prev, in_adjacency(state))
 
 
 def full_recompute(state: GraphState, model) -> list:
     """All embeddings of all layers on the current graph: [H^0, H^1, ..., H^L]."""
     hs = [state.h0.copy()]
     hs[0][~state.alive] = 0.0
+    a_in = in_adjacency(state)
     for layer in model:
-        hs.append(layer_forward(state, layer, hs[-1]))
+        hs.append(layer_rows(state, layer, hs[-1], a_in))
     return hs
+
+
+def recompute_rows(state: GraphState, model, targets) -> list:
+    """Final-layer rows of `targets`, computed from the features through their in-neighbourhood
+    only (the vertex's computational graph, Sec. 1.1, evaluated layer by layer): the rows needed
+    at layer l-1 are the in-neighbours of the rows needed at layer l, plus those rows themselves
+    when the layer reads the vertex's own embedding. Returns, per layer l = 0..L, a pair
+    (sorted row ids, their embeddings); used where recomputing everything is too slow."""
+    a_in = in_adjacency(state)
+    L = len(model)
+    need = [None] * (L + 1)
+    need[L] = np.unique(np.asarray(targets, dtype=np.int64))
+    for l in range(L, 0, -1):
+        nbrs = np.unique(a_in[need[l]].indices)
+        need[l - 1] = np.union1d(nbrs, need[l]) if model[l - 1]["self"] != "none" else nbrs
+    h = np.zeros_like(state.h0)
+    h[need[0]] = state.h0[need[0]]
+    h[~state.alive] = 0.0
+    out = [(need[0], h[need[0]].copy())]
+    for l in range(1, L + 1):
+        rows = need[l]
+        vals = layer_rows(state, model[l - 1], h, a_in, rows)
+        h = np.zeros((state.cap, model[l - 1]["d_out"]))
+        h[rows] = vals
+        out.append((rows, vals))
+    return out
 
 
 # --------------------------------------------------------------------------

@@ -1,0 +1,160 @@
+"""Parity at the benchmark configurations' real sizes, and drift over long
+update sequences (the library accumulates into cached sums; the oracle
+recomputes from scratch every time)."""
+import time
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2601_12347_amd as rp
+import ripple_inputs as ri
+from harness import config_pair, TOL
+
+pytestmark = pytest.mark.gpu
+
+
+def test_sparse_sage_mean_all_batch_sizes():
+    cfg = ri.get_config("sparse_sage_mean")
+    print("case", cfg.name, flush=True)
+    pair, stream = config_pair(cfg)
+    try:
+        pair.check_embeddings()
+        for bs in cfg.batch_sizes:
+            for rep in range(2):
+                print(" batch size", bs, rep, flush=True)
+                ops, payload, _ = stream.next_batch(bs)
+                res, _, _ = pair.step(ops, payload)
+        pair.check_graph()
+        pair.check_aggregates()
+    finally:
+        pair.close()
+
+
+def test_sparse_gin_sum_with_vertex_operations():
+    cfg = ri.get_config("sparse_gin_sum")
+    print("case", cfg.name, flush=True)
+    pair, stream = config_pair(cfg)
+    try:
+        for b in range(3):
+            print(" batch", b, flush=True)
+            ops, payload, n_upd = stream.next_batch(cfg.batch_sizes[0])
+            assert n_upd == 1000 and len(ops) == 1000 + 50 * 8
+            pair.step(ops, payload)
+        pair.check_graph()
+        pair.check_aggregates()
+    finally:
+        pair.close()
+
+
+def test_drift_over_1000_batches_tiny():
+    """1,000 consecutive batches; compared with from-scratch recomputation at checkpoints."""
+    cfg = ri.get_config("tiny_gcn_sum")
+    print("case drift", cfg.name, flush=True)
+    pair, stream = config_pair(cfg)
+    try:
+        worst = 0.0
+        for b in range(1, 1001):
+            ops, payload, _ = stream.next_batch(cfg.batch_sizes[0])
+            rec = pair.ora.apply_batch(ops, payload)
+            res = rp.ripple_apply_updates(pair.ctx, ops, payload)
+            assert res.n_applied == int(rec.accepted.sum())
+            if b in (1, 10, 100, 500, 1000):
+                errs, _ = pair.check_embeddings()
+                worst = max(worst, max(errs))
+                print(f"  batch {b}: max rel err per layer {['%.2e' % e for e in errs]}", flush=True)
+        pair.check_graph()
+        pair.check_aggregates()
+        assert worst <= TOL["f32"]
+    finally:
+        pair.close()
+
+
+def test_drift_bf16_store_sparse_graph():
+    """bfloat16 embeddings with float32 cached sums: error stays bounded over many batches."""
+    cfg = ri.get_config("sparse_gin_sum")            # the graph and stream (with vertex operations) of config 3
+    src, dst, out_law, in_law = ri.chung_lu_graph(cfg.n, cfg.e, cfg.gamma, cfg.top_share, cfg.graph_seed)
+    feats = ri.features(cfg.n, 100, cfg.feat_seed)
+    model = ri.make_model("gcn_sum", (100, 256, 256, 47), cfg.weight_seed)
+    from harness import Pair
+    print("case drift bf16", flush=True)
+    pair = Pair(cfg.n, cfg.vertex_capacity, src, dst, feats, model, store="bf16", edge_capacity=cfg.edge_capacity)
+    mix = {"edge_add": 0.49, "edge_del": 0.294, "feat": 0.196, "vadd": 0.01, "vdel": 0.01}
+    stream = ri.UpdateStream(cfg.n, cfg.vertex_capacity, src, dst, out_law, in_law, 100, mix, 77)
+    try:
+        for b in range(1, 101):
+            ops, payload, _ = stream.next_batch(1000)
+            rec = pair.ora.apply_batch(ops, payload)
+            res = rp.ripple_apply_updates(pair.ctx, ops, payload)
+            assert res.n_applied == int(rec.accepted.sum())
+            if b in (1, 10, 100):
+                errs, _ = pair.check_embeddings()
+                print(f"  batch {b}: max rel err per layer {['%.2e' % e for e in errs]}", flush=True)
+        pair.check_graph()
+        pair.check_aggregates(tol=1e-3)
+    finally:
+        pair.close()
+
+
+@pytest.fixture(scope="module")
+def dense_graph():
+    cfg = ri.get_config("dense_sage_mean")
+    t0 = time.time()
+    g = ri.chung_lu_graph(cfg.n, cfg.e, cfg.gamma, cfg.top_share, cfg.graph_seed)
+    print(f" dense graph generated in {time.time() - t0:.0f}s", flush=True)
+    return g
+
+
+@pytest.mark.parametrize("name", ["dense_sage_mean", "dense_gcn_sum_bf16"])
+def test_dense_configs_sampled_rows(dense_graph, name):
+    """Full-size graph, the batch size the benchmark times; the oracle recomputes a sample of
+    final-layer rows through their in-neighbourhood cones (recomputing all 2.4M rows of every
+    layer in fp64 takes minutes), and the affected sets are compared in full."""
+    cfg = ri.get_config(name)
+    src, dst, out_law, in_law = dense_graph
+    feats = ri.features(cfg.n, cfg.d0, cfg.feat_seed)
+    model = ri.make_model(cfg.model, cfg.widths, cfg.weight_seed)
+    print("case", name, flush=True)
+    t0 = time.time()
+    ctx = rp.ripple_init_graph(cfg.n, cfg.vertex_capacity, src, dst, feats, store=cfg.store,
+                               edge_capacity=cfg.edge_capacity)
+    try:
+        rp.ripple_load_model(ctx, model)
+        rp.ripple_full_infer(ctx)
+        print(f"  gpu bootstrap {time.time() - t0:.0f}s", flush=True)
+        stream = ri.UpdateStream(cfg.n, cfg.vertex_capacity, src, dst, out_law, in_law, cfg.d0, cfg.mix,
+                                 cfg.stream_seed)
+        ora = oracle.GraphState(cfg.n, cfg.vertex_capacity, src, dst, feats)
+        print(f"  oracle state {time.time() - t0:.0f}s", flush=True)
+        bs = max(cfg.batch_sizes)
+        ops, payload, _ = stream.next_batch(bs)
+        rec = ora.apply_batch(ops, payload)
+        res = rp.ripple_apply_updates(ctx, ops, payload)
+        assert res.n_applied == int(rec.accepted.sum()) and res.n_rejected == 0
+        assert res.n_edges == ora.n_edges()
+        sets = oracle.affected_sets(ora, rec, model)
+        print(f"  oracle sets {time.time() - t0:.0f}s sizes {[len(s) for s in sets]}", flush=True)
+        L = len(model)
+        for l in range(L + 1):
+            got, n = rp.ripple_get_affected(ctx, l, cfg.vertex_capacity)
+            assert n == len(sets[l]) and np.array_equal(got.astype(np.int64), sets[l]), f"affected set {l}"
+        rng = np.random.default_rng(5)
+        targets = np.unique(np.concatenate([rng.choice(sets[L], size=120, replace=False),
+                                            np.asarray(sorted(rec.sinks))[:40],
+                                            np.asarray(sorted(rec.feat))[:20]]))
+        cone = oracle.recompute_rows(ora, model, targets)
+        print(f"  oracle cone {time.time() - t0:.0f}s rows per layer {[len(r) for r, _ in cone]}", flush=True)
+        tol = TOL[cfg.store]
+        for l in range(L + 1):
+            rows, want = cone[l]
+            if len(rows) > 200_000:                      # compare a slice of the huge lower layers
+                pick = rng.choice(len(rows), size=200_000, replace=False)
+                rows, want = rows[pick], want[pick]
+            got = rp.ripple_get_embeddings(ctx, l, cfg.widths[l], ids=rows.astype(np.uint32))
+            norm = np.abs(want).max(axis=1)
+            tau = norm.mean()
+            err = (np.abs(got - want).max(axis=1) / np.maximum(norm, tau)).max()
+            print(f"  layer {l}: {len(rows)} rows, max rel err {err:.2e}", flush=True)
+            assert err <= tol, (l, err)
+    finally:
+        rp.ripple_destroy(ctx)

@@ -251,6 +251,24 @@ def test_affected_set_equals_rows_that_change(kind, seed):
                 assert changed <= set(sets[l].tolist()), (l, kind)
 
 
+@pytest.mark.parametrize("kind", ["gcn_sum", "sage_mean", "gin_sum"])
+def test_cone_recompute_equals_bruteforce_and_full(kind):
+    st, model, src, dst, feats = small_case(51, n=80, e=400, kind=kind)
+    full = oracle.full_recompute(st, model)
+    targets = [3, 17, 42, 79, st.cap - 1]
+    cone = oracle.recompute_rows(st, model, targets)
+    rows, vals = cone[-1]
+    assert rows.tolist() == sorted(targets)
+    nbrs = in_lists(st.cap, src, dst)
+    memo = {}
+    for r, val in zip(rows, vals):
+        want = embed(int(r), len(model), model, st.h0, nbrs, st.alive, memo)
+        np.testing.assert_allclose(val, want, rtol=1e-12, atol=1e-12)
+    for l in range(len(model) + 1):
+        r, v = cone[l]
+        np.testing.assert_allclose(v, full[l][r], rtol=1e-12, atol=1e-12)
+
+
 def test_apply_batch_validation_in_array_order():
     st, model, src, dst, feats = small_case(41)
     n = len(feats)
