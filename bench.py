@@ -102,6 +102,7 @@ def main():
     ap.add_argument("--cpu-scale", type=int, default=0, help="oracle sample is a 1/scale graph (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--scatter-mode", type=int, default=0)
+    ap.add_argument("--pull-ratio", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three 1 GiB device-to-device copies (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -140,6 +141,8 @@ def main():
     log(f"[bench] {len(batches)} batches of {bs} updates staged in HBM in {time.time() - t0:.1f}s")
 
     rp.ripple_set_option(ctx, rp.OPT_SCATTER_MODE, args.scatter_mode)
+    if args.pull_ratio:
+        rp.ripple_set_option(ctx, rp.OPT_PULL_RATIO, args.pull_ratio)
     if args.calibrate_copy:
         a = torch.zeros(1 << 28, dtype=torch.float32, device="cuda")        # 1 GiB read + 1 GiB written per copy
         b = torch.empty_like(a)

@@ -118,7 +118,7 @@ typedef struct {
 typedef enum {
     RIPPLE_OPT_TIMING = 0,        /* 0/1: record HIP events around every kernel class (default 0) */
     RIPPLE_OPT_SCATTER_MODE = 1,  /* 0 auto per layer, 1 push (float atomics), 2 pull (segmented reduction over in-rows) */
-    RIPPLE_OPT_PULL_RATIO = 2     /* auto mode pulls when messages * row_bytes * ratio >= 8 * scanned in-edges (default 1) */
+    RIPPLE_OPT_PULL_RATIO = 2     /* auto mode pulls when messages * row_bytes * ratio >= 8 * scanned in-edges (default 2) */
 } ripple_option;
 
 /* Build the graph store and upload features (the state the paper's Sec. 3.1

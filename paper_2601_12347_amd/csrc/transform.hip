@@ -6,15 +6,20 @@
 //     D^l[slot] = h_new - H^l[v],   H^l[v] = h_new
 // so that the next hop can forward the delta (Sec. 3.3.3).
 //
-// Tiling: a workgroup of four wavefronts computes a (WM*64) x (WN*64) output
-// tile; each wavefront owns a 64 x 64 block as 2 x 2 MFMA 32x32x2 (fp32)
-// accumulators. K is consumed in slices of 32 staged through LDS: the gathered
-// rows (A) once per slice, the weight slice (B) from the L2-resident padded
-// weight matrix.
+// Tiling: a workgroup of four wavefronts computes a (WAVES_M*TM*32) x (WAVES_N*TN*32)
+// output tile; each wavefront owns TM x TN MFMA 32x32x2 (fp32) accumulators. K is
+// consumed in slices of 32 staged through LDS. Later slices are already on their
+// way from memory into registers while the matrix cores work on the current one:
+// the weight slice (an L2 hit) one step ahead, the gathered rows (HBM latency)
+// STAGES steps ahead. The fetch is branch-free (addresses are clamped, the row
+// mode is a template parameter) and touches no loaded value, so nothing waits on
+// memory until the registers are written to LDS; scaling, the SAGE/GIN combination
+// and zero padding are applied at that point.
 #include "common.h"
 #include "kernels.h"
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
 
 struct TArgs {
     const uint32_t *list;          // slot -> vertex id
@@ -40,66 +45,136 @@ struct TArgs {
     int store;                     // 0 fp32, 1 bf16 embeddings
 };
 
-__device__ __forceinline__ float ld_h(const void *H, int store, size_t idx) {
-    return store ? __bfloat162float(((const __hip_bfloat16 *)H)[idx]) : ((const float *)H)[idx];
-}
-
-__device__ __forceinline__ float load_a1(const TArgs &a, uint32_t v, uint32_t slot, float scale, uint32_t k) {
-    if (k >= a.K) return 0.0f;
-    switch (a.a_mode) {
-    case 0: return a.X[(size_t)v * a.d_in + k] * scale;
-    case 1:
-        return (k < a.d_in) ? ld_h(a.Hprev, a.store, (size_t)v * a.d_in + k)
-                            : a.X[(size_t)v * a.d_in + (k - a.d_in)] * scale;
-    case 2: return a.one_plus_eps * ld_h(a.Hprev, a.store, (size_t)v * a.d_in + k) + a.X[(size_t)v * a.d_in + k] * scale;
-    default: return a.tmp_in[(size_t)slot * a.tmp_ld + k];
-    }
-}
-
-__device__ __forceinline__ float4 ld_h4(const void *H, int store, size_t idx) {
-    if (store) {
-        const ushort4 r = *(const ushort4 *)((const __hip_bfloat16 *)H + idx);
-        return make_float4(__uint_as_float((uint32_t)r.x << 16), __uint_as_float((uint32_t)r.y << 16),
-                           __uint_as_float((uint32_t)r.z << 16), __uint_as_float((uint32_t)r.w << 16));
-    }
-    return *(const float4 *)((const float *)H + idx);
-}
-
-// four consecutive k (k % 4 == 0); requires d_in % 4 == 0 and tmp_ld % 4 == 0
-__device__ __forceinline__ float4 load_a4(const TArgs &a, uint32_t v, uint32_t slot, float scale, uint32_t k) {
-    if (k >= a.K) return make_float4(0.f, 0.f, 0.f, 0.f);
-    switch (a.a_mode) {
-    case 0: {
-        float4 x = *(const float4 *)(a.X + (size_t)v * a.d_in + k);
-        return make_float4(x.x * scale, x.y * scale, x.z * scale, x.w * scale);
-    }
-    case 1: {
-        if (k < a.d_in) return ld_h4(a.Hprev, a.store, (size_t)v * a.d_in + k);
-        float4 x = *(const float4 *)(a.X + (size_t)v * a.d_in + (k - a.d_in));
-        return make_float4(x.x * scale, x.y * scale, x.z * scale, x.w * scale);
-    }
-    case 2: {
-        float4 h = ld_h4(a.Hprev, a.store, (size_t)v * a.d_in + k);
-        float4 x = *(const float4 *)(a.X + (size_t)v * a.d_in + k);
-        const float e = a.one_plus_eps;
-        return make_float4(e * h.x + x.x * scale, e * h.y + x.y * scale, e * h.z + x.z * scale, e * h.w + x.w * scale);
-    }
-    default: return *(const float4 *)(a.tmp_in + (size_t)slot * a.tmp_ld + k);
-    }
-}
-
 #define T_BK 32
 
-template <int WM, int WN, bool VEC>
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// Raw 16 (or 8) bytes for four consecutive k of one gathered row; no arithmetic on the data.
+// MODE 1 with bf16 embeddings and MODE 2 need two sources (p: own embedding, q: aggregate).
+template <int MODE, int STORE>
+__device__ __forceinline__ void fetch_raw(const TArgs &a, uint32_t v, uint32_t slot, uint32_t k, floatx4 &p, floatx4 &q) {
+    const uint32_t kc = min(k, a.K - 4u);                     // stay inside the row; padding is zeroed later
+    const size_t row = (size_t)v * a.d_in;
+    if (MODE == 0) {
+        p = *(const floatx4 *)(a.X + row + kc);
+    } else if (MODE == 3) {
+        p = *(const floatx4 *)(a.tmp_in + (size_t)slot * a.tmp_ld + kc);
+    } else if (MODE == 2) {
+        q = *(const floatx4 *)(a.X + row + kc);
+        if (STORE) {
+            const uint2 r = *(const uint2 *)((const __hip_bfloat16 *)a.Hprev + row + kc);
+            p.x = __uint_as_float(r.x);
+            p.y = __uint_as_float(r.y);
+        } else {
+            p = *(const floatx4 *)((const float *)a.Hprev + row + kc);
+        }
+    } else {                                                  // MODE 1: k < d_in own embedding, else aggregate
+        if (STORE) {
+            const uint32_t kh = min(kc, a.d_in - 4u), kx = kc >= a.d_in ? kc - a.d_in : 0u;
+            const uint2 r = *(const uint2 *)((const __hip_bfloat16 *)a.Hprev + row + kh);
+            p.x = __uint_as_float(r.x);
+            p.y = __uint_as_float(r.y);
+            q = *(const floatx4 *)(a.X + row + kx);
+        } else {
+            const float *src = (kc < a.d_in) ? (const float *)a.Hprev + row + kc : a.X + row + (kc - a.d_in);
+            p = *(const floatx4 *)src;
+        }
+    }
+}
+
+template <int MODE, int STORE>
+__device__ __forceinline__ floatx4 finish_raw(const TArgs &a, floatx4 p, floatx4 q, uint32_t k, float scale) {
+    floatx4 h = p;
+    if (STORE && (MODE == 1 || MODE == 2)) {
+        const uint32_t w0 = __float_as_uint(p.x), w1 = __float_as_uint(p.y);
+        h.x = bf_lo(w0);
+        h.y = bf_hi(w0);
+        h.z = bf_lo(w1);
+        h.w = bf_hi(w1);
+    }
+    floatx4 r;
+    if (MODE == 0) {
+        r = p * scale;
+    } else if (MODE == 3) {
+        r = p;
+    } else if (MODE == 2) {
+        r = h * a.one_plus_eps + q * scale;
+    } else {
+        const floatx4 x = STORE ? q : p;
+        r = (k < a.d_in) ? h : x * scale;
+    }
+    if (k >= a.K) r = (floatx4)(0.0f);
+    return r;
+}
+
+// Bias, activation, delta against the stored row, store. The old rows are read in batches of
+// TN*16 loads before anything is written: a load may not move above an earlier store to the same
+// array, so interleaving them would pay one memory round trip per element.
+template <int TM, int TN>
+__device__ __forceinline__ void epilogue(const TArgs &a, floatx16 (&acc)[TM][TN], const uint32_t *s_vtx, uint32_t row0,
+                                         uint32_t count, uint32_t n0, int wm, int wn, int lane) {
+#pragma unroll
+    for (int sm = 0; sm < TM; ++sm) {
+        float old[TN][16];
+        if (a.out_mode != 0) {
+#pragma unroll
+            for (int sn = 0; sn < TN; ++sn) {
+                const uint32_t col = n0 + (wn * TN + sn) * 32 + (lane & 31);
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int lr = (wm * TM + sm) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                    float o = 0.0f;
+                    if (col < a.N && row0 + lr < count) {
+                        const size_t hidx = (size_t)s_vtx[lr] * a.N + col;
+                        o = a.store ? __bfloat162float(((const __hip_bfloat16 *)a.Hout)[hidx]) : ((const float *)a.Hout)[hidx];
+                    }
+                    old[sn][r] = o;
+                }
+            }
+        }
+#pragma unroll
+        for (int sn = 0; sn < TN; ++sn) {
+            const uint32_t col = n0 + (wn * TN + sn) * 32 + (lane & 31);
+            if (col >= a.N) continue;
+            const float bias = a.bias[col];
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int lr = (wm * TM + sm) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                const uint32_t slot = row0 + lr;
+                if (slot >= count) continue;
+                float z = acc[sm][sn][r] + bias;
+                if (a.act == RIPPLE_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+                if (a.out_mode == 0) {
+                    a.tmp_out[(size_t)slot * a.tmp_out_ld + col] = z;
+                } else {
+                    const size_t hidx = (size_t)s_vtx[lr] * a.N + col;
+                    if (a.store) {
+                        const __hip_bfloat16 zr = __float2bfloat16(z);
+                        z = __bfloat162float(zr);
+                        ((__hip_bfloat16 *)a.Hout)[hidx] = zr;
+                    } else {
+                        ((float *)a.Hout)[hidx] = z;
+                    }
+                    if (a.D) a.D[(size_t)slot * a.N + col] = z - old[sn][r];
+                }
+            }
+        }
+    }
+}
+
+template <int WAVES_M, int WAVES_N, int TM, int TN, int STAGES, int MODE, int STORE>
 __global__ __launch_bounds__(256) void k_transform_f32(TArgs a) {
-    constexpr int BM = WM * 64, BN = WN * 64;
+    constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
+    constexpr int NA = BM / 32, NB = BN / 32;              // float4 per thread per slice (A, B)
+    constexpr bool TWO = (MODE == 2) || (MODE == 1 && STORE == 1);
     __shared__ float As[BM][T_BK + 1];
     __shared__ float Bs[T_BK][BN];
     __shared__ uint32_t s_vtx[BM];
     __shared__ float s_scale[BM];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / WN, wn = wave % WN;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
     const uint32_t count = *a.count_ptr;
     const uint32_t n_tiles = (count + BM - 1) / BM;
     const uint32_t n0 = blockIdx.y * BN;
@@ -107,6 +182,153 @@ __global__ __launch_bounds__(256) void k_transform_f32(TArgs a) {
     for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
         const uint32_t row0 = tile * BM;
         __syncthreads();                                   // previous tile's epilogue has read s_vtx
+        for (int r = tid; r < BM; r += 256) {
+            uint32_t slot = row0 + r;
+            uint32_t v = 0;                                // rows past the end read vertex 0; never stored
+            float sc = 1.0f;
+            if (slot < count) {
+                v = a.list[slot];
+                if (a.mean) {
+                    uint32_t deg = a.in_meta[v].y;
+                    sc = 1.0f / (float)(deg > 1u ? deg : 1u);
+                }
+            }
+            s_vtx[r] = v;
+            s_scale[r] = sc;
+        }
+        __syncthreads();
+
+        floatx16 acc[TM][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+        // per-thread row coordinates of its NA float4 of every slice
+        uint32_t my_v[NA], my_slot[NA];
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            const int r = (tid + i * 256) / (T_BK / 4);
+            my_v[i] = s_vtx[r];
+            my_slot[i] = min(row0 + r, count - 1u);
+        }
+        const uint32_t c4a = (tid % (T_BK / 4)) * 4;       // (tid + i*256) % 8 is the same for every i
+
+        floatx4 ra[STAGES][NA], rq[TWO ? STAGES : 1][TWO ? NA : 1], rb[NB];
+#pragma unroll
+        for (int st = 0; st < STAGES; ++st)
+#pragma unroll
+            for (int i = 0; i < NA; ++i) {
+                floatx4 q = (floatx4)(0.0f);
+                fetch_raw<MODE, STORE>(a, my_v[i], my_slot[i], (uint32_t)st * T_BK + c4a, ra[st][i], q);
+                if constexpr (TWO) rq[st][i] = q;
+            }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int idx = tid + i * 256;
+            const int kr = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
+            rb[i] = *(const floatx4 *)(a.W + (size_t)kr * a.Npad + n0 + c4);
+        }
+
+        for (uint32_t k0 = 0; k0 < a.Kpad; k0 += T_BK) {
+            __syncthreads();                               // the matrix cores are done with the previous slice
+#pragma unroll
+            for (int i = 0; i < NA; ++i) {
+                const int r = (tid + i * 256) / (T_BK / 4);
+                floatx4 q = (floatx4)(0.0f);
+                if constexpr (TWO) q = rq[0][i];
+                const floatx4 val = finish_raw<MODE, STORE>(a, ra[0][i], q, k0 + c4a, s_scale[r]);
+                As[r][c4a + 0] = val.x;
+                As[r][c4a + 1] = val.y;
+                As[r][c4a + 2] = val.z;
+                As[r][c4a + 3] = val.w;
+            }
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                const int idx = tid + i * 256;
+                const int kr = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
+                *(floatx4 *)&Bs[kr][c4] = rb[i];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int st = 0; st + 1 < STAGES; ++st)
+#pragma unroll
+                for (int i = 0; i < NA; ++i) {
+                    ra[st][i] = ra[st + 1][i];
+                    if constexpr (TWO) rq[st][i] = rq[st + 1][i];
+                }
+            // memory returns loads in order: the weights (needed one step from now) are requested
+            // before the rows (needed STAGES steps from now), so waiting for them leaves the rows in flight
+            {                                              // weights of the next slice (last step re-reads its own: in bounds)
+                const uint32_t kb = min(k0 + T_BK, a.Kpad - T_BK);
+#pragma unroll
+                for (int i = 0; i < NB; ++i) {
+                    const int idx = tid + i * 256;
+                    const int kr = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
+                    rb[i] = *(const floatx4 *)(a.W + (size_t)(kb + kr) * a.Npad + n0 + c4);
+                }
+            }
+            {                                              // rows of the slice STAGES steps ahead (clamped: harmless past the end)
+                const uint32_t kn = k0 + STAGES * T_BK + c4a;
+#pragma unroll
+                for (int i = 0; i < NA; ++i) {
+                    floatx4 q = (floatx4)(0.0f);
+                    fetch_raw<MODE, STORE>(a, my_v[i], my_slot[i], kn, ra[STAGES - 1][i], q);
+                    if constexpr (TWO) rq[STAGES - 1][i] = q;
+                }
+            }
+#pragma unroll
+            for (int kk = 0; kk < T_BK; kk += 2) {
+                const int kq = kk + (lane >> 5);
+                float av[TM], bv[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i) av[i] = As[(wm * TM + i) * 32 + (lane & 31)][kq];
+#pragma unroll
+                for (int j = 0; j < TN; ++j) bv[j] = Bs[kq][(wn * TN + j) * 32 + (lane & 31)];
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+            }
+        }
+        epilogue<TM, TN>(a, acc, s_vtx, row0, count, n0, wm, wn, lane);
+    }
+}
+
+// Fallback for row widths that are not multiples of 4 (no 16-byte loads): same tiling, scalar
+// gathers, no prefetch.
+__device__ __forceinline__ float load_a1(const TArgs &a, uint32_t v, uint32_t slot, float scale, uint32_t k) {
+    if (k >= a.K) return 0.0f;
+    switch (a.a_mode) {
+    case 0: return a.X[(size_t)v * a.d_in + k] * scale;
+    case 1:
+        return (k < a.d_in) ? rp_load_h(a.Hprev, a.store, (size_t)v * a.d_in + k)
+                            : a.X[(size_t)v * a.d_in + (k - a.d_in)] * scale;
+    case 2:
+        return a.one_plus_eps * rp_load_h(a.Hprev, a.store, (size_t)v * a.d_in + k) + a.X[(size_t)v * a.d_in + k] * scale;
+    default: return a.tmp_in[(size_t)slot * a.tmp_ld + k];
+    }
+}
+
+template <int WAVES_M, int WAVES_N>
+__global__ __launch_bounds__(256) void k_transform_generic(TArgs a) {
+    constexpr int TM = 2, TN = 2;
+    constexpr int BM = WAVES_M * 64, BN = WAVES_N * 64;
+    __shared__ float As[BM][T_BK + 1];
+    __shared__ float Bs[T_BK][BN];
+    __shared__ uint32_t s_vtx[BM];
+    __shared__ float s_scale[BM];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const uint32_t count = *a.count_ptr;
+    const uint32_t n_tiles = (count + BM - 1) / BM;
+    const uint32_t n0 = blockIdx.y * BN;
+    for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint32_t row0 = tile * BM;
+        __syncthreads();
         for (int r = tid; r < BM; r += 256) {
             uint32_t slot = row0 + r;
             uint32_t v = 0;
@@ -122,109 +344,78 @@ __global__ __launch_bounds__(256) void k_transform_f32(TArgs a) {
             s_scale[r] = sc;
         }
         __syncthreads();
-
-        floatx16 acc[2][2];
+        floatx16 acc[TM][TN];
 #pragma unroll
-        for (int i = 0; i < 2; ++i)
+        for (int i = 0; i < TM; ++i)
 #pragma unroll
-            for (int j = 0; j < 2; ++j)
+            for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
-
         for (uint32_t k0 = 0; k0 < a.Kpad; k0 += T_BK) {
-            // stage A: BM rows x 32 k
-            for (int idx = tid; idx < BM * (T_BK / 4); idx += 256) {
-                const int r = idx / (T_BK / 4), c4 = (idx % (T_BK / 4)) * 4;
+            for (int idx = tid; idx < BM * T_BK; idx += 256) {
+                const int r = idx / T_BK, k = idx % T_BK;
                 const uint32_t slot = row0 + r;
-                float4 val = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (slot < count) {
-                    if (VEC) {
-                        val = load_a4(a, s_vtx[r], slot, s_scale[r], k0 + c4);
-                    } else {
-                        val.x = load_a1(a, s_vtx[r], slot, s_scale[r], k0 + c4 + 0);
-                        val.y = load_a1(a, s_vtx[r], slot, s_scale[r], k0 + c4 + 1);
-                        val.z = load_a1(a, s_vtx[r], slot, s_scale[r], k0 + c4 + 2);
-                        val.w = load_a1(a, s_vtx[r], slot, s_scale[r], k0 + c4 + 3);
-                    }
-                }
-                As[r][c4 + 0] = val.x;
-                As[r][c4 + 1] = val.y;
-                As[r][c4 + 2] = val.z;
-                As[r][c4 + 3] = val.w;
+                As[r][k] = (slot < count) ? load_a1(a, s_vtx[r], slot, s_scale[r], k0 + k) : 0.0f;
             }
-            // stage B: 32 k x BN columns of the padded weights
             for (int idx = tid; idx < T_BK * (BN / 4); idx += 256) {
                 const int kr = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
-                const float4 w = *(const float4 *)(a.W + (size_t)(k0 + kr) * a.Npad + n0 + c4);
-                *(float4 *)&Bs[kr][c4] = w;
+                *(float4 *)&Bs[kr][c4] = *(const float4 *)(a.W + (size_t)(k0 + kr) * a.Npad + n0 + c4);
             }
             __syncthreads();
 #pragma unroll
             for (int kk = 0; kk < T_BK; kk += 2) {
                 const int kq = kk + (lane >> 5);
-                const float a0 = As[wm * 64 + (lane & 31)][kq];
-                const float a1 = As[wm * 64 + 32 + (lane & 31)][kq];
-                const float b0 = Bs[kq][wn * 64 + (lane & 31)];
-                const float b1 = Bs[kq][wn * 64 + 32 + (lane & 31)];
-                acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-                acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-                acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-                acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+                float av[TM], bv[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i) av[i] = As[(wm * TM + i) * 32 + (lane & 31)][kq];
+#pragma unroll
+                for (int j = 0; j < TN; ++j) bv[j] = Bs[kq][(wn * TN + j) * 32 + (lane & 31)];
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
             }
             __syncthreads();
         }
-
-        // epilogue: bias, activation, delta against the stored row, store
-#pragma unroll
-        for (int sm = 0; sm < 2; ++sm)
-#pragma unroll
-            for (int sn = 0; sn < 2; ++sn) {
-                const uint32_t col = n0 + wn * 64 + sn * 32 + (lane & 31);
-                if (col >= a.N) continue;
-                const float bias = a.bias[col];
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int lr = wm * 64 + sm * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                    const uint32_t slot = row0 + lr;
-                    if (slot >= count) continue;
-                    float z = acc[sm][sn][r] + bias;
-                    if (a.act == RIPPLE_ACT_RELU) z = z > 0.0f ? z : 0.0f;
-                    if (a.out_mode == 0) {
-                        a.tmp_out[(size_t)slot * a.tmp_out_ld + col] = z;
-                    } else {
-                        const size_t hidx = (size_t)s_vtx[lr] * a.N + col;
-                        float old;
-                        if (a.store) {
-                            __hip_bfloat16 *h = (__hip_bfloat16 *)a.Hout;
-                            old = __bfloat162float(h[hidx]);
-                            const __hip_bfloat16 zr = __float2bfloat16(z);
-                            z = __bfloat162float(zr);
-                            h[hidx] = zr;
-                        } else {
-                            float *h = (float *)a.Hout;
-                            old = h[hidx];
-                            h[hidx] = z;
-                        }
-                        if (a.D) a.D[(size_t)slot * a.N + col] = z - old;
-                    }
-                }
-            }
+        epilogue<TM, TN>(a, acc, s_vtx, row0, count, n0, wm, wn, lane);
     }
 }
 
-template <bool VEC>
-static void launch_t(ripple_ctx *c, const TArgs &a) {
+template <int MODE, int STORE>
+static void launch_fast(ripple_ctx *c, const TArgs &a) {
     const uint32_t gx = c->n_cu * 2;
-    if (a.Npad >= 256 || a.Npad == 192) {
-        dim3 grid(gx, rp_div_up(a.Npad, 256));
-        hipLaunchKernelGGL((k_transform_f32<1, 4, VEC>), grid, dim3(256), 0, c->stream, a);
+    if (a.Npad >= 256) {
+        hipLaunchKernelGGL((k_transform_f32<1, 4, 2, 2, 3, MODE, STORE>), dim3(gx, a.Npad / 256), dim3(256), 0, c->stream, a);
     } else if (a.Npad == 128) {
-        dim3 grid(gx, 1);
-        hipLaunchKernelGGL((k_transform_f32<2, 2, VEC>), grid, dim3(256), 0, c->stream, a);
+        hipLaunchKernelGGL((k_transform_f32<2, 2, 2, 2, 3, MODE, STORE>), dim3(gx, 1), dim3(256), 0, c->stream, a);
     } else {
-        dim3 grid(gx, 1);
-        hipLaunchKernelGGL((k_transform_f32<4, 1, VEC>), grid, dim3(256), 0, c->stream, a);
+        hipLaunchKernelGGL((k_transform_f32<4, 1, 1, 2, 3, MODE, STORE>), dim3(gx, 1), dim3(256), 0, c->stream, a);
     }
+}
+
+static void launch_t(ripple_ctx *c, const TArgs &a, bool vec_ok) {
+    const uint32_t gx = c->n_cu * 2;
+    if (!vec_ok || a.K < 4) {
+        if (a.Npad >= 256) hipLaunchKernelGGL((k_transform_generic<1, 4>), dim3(gx, a.Npad / 256), dim3(256), 0, c->stream, a);
+        else if (a.Npad == 128) hipLaunchKernelGGL((k_transform_generic<2, 2>), dim3(gx, 1), dim3(256), 0, c->stream, a);
+        else hipLaunchKernelGGL((k_transform_generic<4, 1>), dim3(gx, 1), dim3(256), 0, c->stream, a);
+        return;
+    }
+#define T_CASE(M)                                            \
+    case M:                                                  \
+        if (a.store) launch_fast<M, 1>(c, a);                \
+        else launch_fast<M, 0>(c, a);                        \
+        break;
+    switch (a.a_mode) {
+        T_CASE(0)
+        T_CASE(1)
+        T_CASE(2)
+    default:
+        launch_fast<3, 0>(c, a);                             // compact fp32 rows: storage type plays no part in the gather
+        break;
+    }
+#undef T_CASE
 }
 
 // Re-apply layer l (1-based) to the vertices in `list` (count on the device).
@@ -258,8 +449,7 @@ void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const 
         a.Npad = ly.N0pad;
         a.act = (int)ly.act_out;
         a.out_mode = 1;
-        if (vec_in) launch_t<true>(c, a);
-        else launch_t<false>(c, a);
+        launch_t(c, a, vec_in);
         return;
     }
     // two-stage update: hidden = act_inner(row W0 + b0) -> tmp, then h = act_out(hidden W1 + b1)
@@ -276,8 +466,7 @@ void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const 
     s1.tmp_out_ld = ly.d_hidden;
     s1.Hout = nullptr;
     s1.D = nullptr;
-    if (vec_in) launch_t<true>(c, s1);
-    else launch_t<false>(c, s1);
+    launch_t(c, s1, vec_in);
     TArgs s2 = a;
     s2.a_mode = 3;
     s2.tmp_in = c->tmp;
@@ -291,6 +480,5 @@ void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const 
     s2.Npad = ly.N1pad;
     s2.act = (int)ly.act_out;
     s2.out_mode = 1;
-    if (ly.d_hidden % 4 == 0) launch_t<true>(c, s2);
-    else launch_t<false>(c, s2);
+    launch_t(c, s2, ly.d_hidden % 4 == 0);
 }
