@@ -35,12 +35,20 @@ __global__ __launch_bounds__(256) void k_frontier_mark(const uint32_t *list, con
         uint32_t e0 = c * MARK_CHUNK, e1 = min(M, e0 + MARK_CHUNK);
         uint32_t i_lo = seg_search(eoff, 0, count - 1, e0);
         uint32_t i_hi = seg_search(eoff, i_lo, count - 1, e1 - 1);
-        for (uint32_t e = e0 + lane; e < e1; e += 64) {
-            uint32_t i = seg_search(eoff, i_lo, i_hi, e);
-            uint32_t u = list[i];
-            uint32_t v = out_pool[out_meta[u].x + (e - eoff[i])];
-            rp_set_bit(bm, v);
+        // four independent edges per lane: their dependent load chains overlap
+        uint32_t v[MARK_CHUNK / 64];
+#pragma unroll
+        for (int t = 0; t < MARK_CHUNK / 64; ++t) {
+            const uint32_t e = e0 + lane + 64 * t;
+            v[t] = 0xFFFFFFFFu;
+            if (e < e1) {
+                const uint32_t i = (i_lo == i_hi) ? i_lo : seg_search(eoff, i_lo, i_hi, e);
+                v[t] = out_pool[out_meta[list[i]].x + (e - eoff[i])];
+            }
         }
+#pragma unroll
+        for (int t = 0; t < MARK_CHUNK / 64; ++t)
+            if (v[t] != 0xFFFFFFFFu) rp_set_bit(bm, v[t]);
     }
 }
 
@@ -226,7 +234,7 @@ __global__ __launch_bounds__(1024) void k_list_eoff(const uint32_t *list, const 
 }
 
 void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l) {
-    hipLaunchKernelGGL(k_frontier_mark, dim3(c->n_cu * 4), dim3(256), 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],
+    hipLaunchKernelGGL(k_frontier_mark, dim3(c->n_cu * 8), dim3(256), 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],
                        c->eoff[l - 1], c->out_meta, c->out_pool, c->bm[l]);
 }
 
