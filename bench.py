@@ -31,31 +31,40 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_work(st, model, widths, store, L):
+def algorithmic_work(st, model, widths, store, L, layer_info):
     """Per (phase, layer): algorithmic bytes and flops summed over the timed batches.
 
-    scatter(l):   every delta row once, the out-row index pairs and column ids once, and each
-                  distinct destination row of X^l read and written once;
-    frontier(l):  index pairs + column ids of the walked out-rows, the list written, the
-                  bitmap words read and written;
+    scatter(l):   every message row (delta, or projected delta) once, the walked rows' index
+                  pairs and column ids once, and each distinct destination row of the cached
+                  aggregate read and written once;
+    frontier(l):  index pairs + column ids of the walked out-rows, the list written;
     transform(l): per dirty row the gathered input row, old H read, new H and delta written;
-                  flops 2*K*d_out per row (plus the hidden stage for two-stage updates).
+                  flops 2*K*d_out per row (plus the hidden stage for two-stage updates). For
+                  project-first layers the projection of the hop's deltas (a_{l-1} rows) is
+                  part of this class and the row transform reads h_self and the projected aggregate.
     """
     s_h = 2 if store == "bf16" else 4
     out = {}
     for l in range(1, L + 1):
         lay = model[l - 1]
         d_prev, d_out = widths[l - 1], widths[l]
+        w_agg, projected = layer_info[l]
         a_prev, a_l, m_l, t_l = st.rows[l - 1], st.rows[l], st.msgs[l], st.touched[l]
-        out[("scatter", l)] = dict(bytes=a_prev * d_prev * 4 + 8 * a_prev + 4 * m_l + 2 * t_l * d_prev * 4, flops=m_l * d_prev)
+        out[("scatter", l)] = dict(bytes=a_prev * w_agg * 4 + 8 * a_prev + 4 * m_l + 2 * t_l * w_agg * 4, flops=m_l * w_agg)
         out[("frontier", l)] = dict(bytes=8 * a_prev + 4 * m_l + 4 * a_l, flops=0)
-        k = lay["d_in"] * (2 if lay["self"] == "concat" else 1)
-        if lay["d_hidden"]:
-            flops = 2 * a_l * (k * lay["d_hidden"] + lay["d_hidden"] * d_out)
+        self_w = lay["d_in"] if lay["self"] != "none" else 0
+        out_bytes = d_out * s_h * 2 + (d_out * 4 if l < L else 0) + 4
+        if projected:
+            flops = 2 * a_l * self_w * d_out + 2 * a_prev * d_prev * d_out
+            nbytes = a_l * (self_w * s_h + w_agg * 4 + out_bytes) + a_prev * (d_prev * 4 + w_agg * 4)
         else:
-            flops = 2 * a_l * k * d_out
-        in_bytes = lay["d_in"] * 4 + (lay["d_in"] * s_h if lay["self"] != "none" else 0)
-        out[("transform", l)] = dict(bytes=a_l * (in_bytes + d_out * s_h * 2 + (d_out * 4 if l < L else 0) + 4), flops=flops)
+            k = lay["d_in"] + self_w if lay["self"] == "concat" else lay["d_in"]
+            if lay["d_hidden"]:
+                flops = 2 * a_l * (k * lay["d_hidden"] + lay["d_hidden"] * d_out)
+            else:
+                flops = 2 * a_l * k * d_out
+            nbytes = a_l * (lay["d_in"] * 4 + self_w * s_h + out_bytes)
+        out[("transform", l)] = dict(bytes=nbytes, flops=flops)
     return out
 
 
@@ -175,11 +184,12 @@ def main():
     rp.ripple_set_option(ctx, rp.OPT_TIMING, 0)
 
     L = len(model)
-    work = algorithmic_work(st, model, cfg.widths, cfg.store, L)
+    layer_info = {l: rp.ripple_get_layer_info(ctx, l) for l in range(1, L + 1)}
+    work = algorithmic_work(st, model, cfg.widths, cfg.store, L, layer_info)
     phase_idx = {"frontier": 2, "scatter": 3, "transform": 5}
     kernels = {}
     for (ph, l), w in work.items():
-        ms = st.ms[phase_idx[ph]][l]
+        ms = st.ms[phase_idx[ph]][l] + (st.ms[6][l] if ph == "transform" else 0.0)   # 6: projection of the deltas
         n_launch = st.launches[phase_idx[ph]][l]
         if not n_launch or ms <= 0:
             continue
@@ -223,6 +233,7 @@ def main():
         "per_batch": {"a_l": [st.rows[l] / max(st.batches, 1) for l in range(L + 1)],
                       "messages_l": [st.msgs[l] / max(st.batches, 1) for l in range(L + 1)],
                       "phase_ms": other},
+        "aggregate_width": {f"l{l}": layer_info[l][0] for l in layer_info},
         "kernels": kernels,
         "roofline": roofline,
     }

@@ -118,7 +118,9 @@ typedef struct {
 typedef enum {
     RIPPLE_OPT_TIMING = 0,        /* 0/1: record HIP events around every kernel class (default 0) */
     RIPPLE_OPT_SCATTER_MODE = 1,  /* 0 auto per layer, 1 push (float atomics), 2 pull (segmented reduction over in-rows) */
-    RIPPLE_OPT_PULL_RATIO = 2     /* auto mode pulls when messages * row_bytes * ratio >= 8 * scanned in-edges (default 2) */
+    RIPPLE_OPT_PULL_RATIO = 2,    /* auto mode pulls when messages * row_bytes * ratio >= 8 * scanned in-edges (default 2) */
+    RIPPLE_OPT_PROJECT_FIRST = 3  /* 0/1 (default 1), before load_model: layers with one linear map and d_out <= d_in/2
+                                     cache sum_u H[u] W_neigh instead of sum_u H[u] and scatter d_out-wide messages */
 } ripple_option;
 
 /* Build the graph store and upload features (the state the paper's Sec. 3.1
@@ -158,11 +160,16 @@ ripple_status ripple_apply_updates(ripple_ctx *ctx, const ripple_update *ops, ui
 ripple_status ripple_get_embeddings(ripple_ctx *ctx, uint32_t layer, const uint32_t *ids,
                                     uint32_t n_ids, float *out);
 
-/* Same for the cached un-normalised neighbourhood sums X^layer, layer = 1..L
- * (width d_{layer-1}); used to check the invariant X^l[v] = sum of H^{l-1} over
- * v's in-neighbours. */
+/* Same for the cached un-normalised neighbourhood sums X^layer, layer = 1..L; used to
+ * check the invariant X^l[v] = sum of H^{l-1} over v's in-neighbours. The row width is
+ * d_{layer-1}, except for project-first layers (see ripple_get_layer_info), whose rows hold
+ * sum of H^{l-1}[u] W_neigh and are d_layer wide. */
 ripple_status ripple_get_aggregates(ripple_ctx *ctx, uint32_t layer, const uint32_t *ids,
                                     uint32_t n_ids, float *out);
+
+/* Width of layer's cached aggregate rows and whether the layer is handled project-first
+ * (either output pointer may be NULL). */
+ripple_status ripple_get_layer_info(ripple_ctx *ctx, uint32_t layer, uint32_t *aggregate_width, int *projected);
 
 /* Vertices the last batch could affect at `layer` (0..L), ascending, into
  * ids_out (host, room for cap ids); *n_out receives the set size even when it

@@ -22,14 +22,14 @@ STATUS_NAMES = ["RIPPLE_OK", "RIPPLE_EINVAL", "RIPPLE_ESTATE", "RIPPLE_ECAPACITY
 RIPPLE_MAX_LAYERS = 8
 RIPPLE_N_PHASES = 8
 PHASES = ["ingest", "struct", "frontier", "scatter", "compact", "transform", "other", "total"]
-OPT_TIMING, OPT_SCATTER_MODE, OPT_PULL_RATIO = 0, 1, 2
+OPT_TIMING, OPT_SCATTER_MODE, OPT_PULL_RATIO, OPT_PROJECT_FIRST = 0, 1, 2, 3
 AGG = {"sum": 0, "mean": 1}
 SELF = {"none": 0, "concat": 1, "add": 2}
 ACT = {"none": 0, "relu": 1}
 STORE = {"f32": 0, "bf16": 1}
 
 EXPORTS = ["ripple_init_graph", "ripple_load_model", "ripple_full_infer", "ripple_apply_updates",
-           "ripple_get_embeddings", "ripple_get_aggregates", "ripple_get_affected", "ripple_export_edges",
+           "ripple_get_embeddings", "ripple_get_aggregates", "ripple_get_layer_info", "ripple_get_affected", "ripple_export_edges",
            "ripple_get_degrees", "ripple_compact", "ripple_set_option", "ripple_get_stats",
            "ripple_destroy", "ripple_last_error"]
 
@@ -91,6 +91,7 @@ def load_library():
     lib.ripple_apply_updates.argtypes = [vp, vp, u32, vp, u32, C.POINTER(BatchResult)]
     lib.ripple_get_embeddings.argtypes = [vp, u32, vp, u32, vp]
     lib.ripple_get_aggregates.argtypes = [vp, u32, vp, u32, vp]
+    lib.ripple_get_layer_info.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(C.c_int)]
     lib.ripple_get_affected.argtypes = [vp, u32, vp, u32, C.POINTER(u32)]
     lib.ripple_export_edges.argtypes = [vp, C.c_int, vp, vp, u64, C.POINTER(u64)]
     lib.ripple_get_degrees.argtypes = [vp, C.c_int, vp, vp]
@@ -207,6 +208,13 @@ def ripple_get_embeddings(ctx, layer, width, ids=None, n_rows=None, out=None):
 
 def ripple_get_aggregates(ctx, layer, width, ids=None, n_rows=None, out=None):
     return _get_rows(load_library().ripple_get_aggregates, ctx, layer, ids, n_rows, width, out)
+
+
+def ripple_get_layer_info(ctx, layer):
+    """(width of the cached aggregate rows, handled project-first?)"""
+    w, p = C.c_uint32(), C.c_int()
+    _check(ctx, load_library().ripple_get_layer_info(ctx, layer, C.byref(w), C.byref(p)))
+    return w.value, bool(p.value)
 
 
 def ripple_get_affected(ctx, layer, cap):

@@ -234,7 +234,7 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
     hipStreamSynchronize(c->stream);
     void *ptrs[] = {c->out_meta, c->in_meta, c->out_capv, c->in_capv, c->vstate, c->pend_out, c->pend_in, c->dead_out,
                     c->dead_in, c->out_pool, c->in_pool, c->alive, c->part_cnt, c->part_deg, c->part_ideg, c->ioff[0], c->wrank[0], c->ctr, c->D[0], c->D[1],
-                    c->tmp, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ops_d, c->payload_d,
+                    c->tmp, c->PD, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ops_d, c->payload_d,
                     c->op_status, c->op_pos_out, c->op_pos_in, c->touch_out, c->touch_in, c->exp_kind, c->exp_a,
                     c->exp_b, c->st_src, c->st_dst, c->st_sign, c->gather_d, c->gather_ids};
     for (void *p : ptrs)
@@ -245,7 +245,7 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
     }
     for (uint32_t l = 0; l < c->L; ++l) {
         LayerDev &ly = c->layers[l];
-        void *w[] = {ly.W0, ly.b0, ly.W1, ly.b1, ly.W0h, ly.W1h};
+        void *w[] = {ly.W0, ly.b0, ly.W1, ly.b1, ly.W0h, ly.W1h, ly.bzero, (ly.Wn != ly.W0) ? ly.Wn : nullptr};
         for (void *p : w)
             if (p) hipFree(p);
     }
@@ -311,6 +311,18 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
         ly.K0pad = rp_round_up(ly.K, 32);
         ly.N0pad = pad_n(n0);
         RP_TRY(upload_padded(c, s.W0, s.b0, ly.K, n0, ly.K0pad, ly.N0pad, &ly.W0, &ly.b0));
+        // project first where the single linear map shrinks the row at least by half
+        ly.proj = (c->opt_project && s.d_hidden == 0 && s.self_mode != RIPPLE_SELF_ADD && 2 * s.d_out <= s.d_in) ? 1u : 0u;
+        if (ly.proj) {
+            std::vector<float> zeros(ly.N0pad, 0.0f);
+            if (s.self_mode == RIPPLE_SELF_CONCAT) {           // rows d_in .. 2 d_in - 1 of W0
+                RP_TRY(upload_padded(c, s.W0 + (size_t)s.d_in * s.d_out, zeros.data(), s.d_in, s.d_out,
+                                     rp_round_up(s.d_in, 32), ly.N0pad, &ly.Wn, &ly.bzero));
+            } else {
+                ly.Wn = ly.W0;
+                RP_TRY(dev_alloc(c, &ly.bzero, (size_t)ly.N0pad, true));
+            }
+        }
         if (s.d_hidden) {
             ly.K1pad = rp_round_up(s.d_hidden, 32);
             ly.N1pad = pad_n(s.d_out);
@@ -327,11 +339,19 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
         if (hipMalloc(&h, bytes) != hipSuccess) return fail(c, RIPPLE_ENOMEM, "device allocation of H failed");
         c->H[l] = h;
         RP_HIP(c, hipMemsetAsync(h, 0, bytes, c->stream));
-        RP_TRY(dev_alloc(c, &c->X[l], n * c->d[l - 1], true));
+        c->xw[l] = c->layers[l - 1].proj ? c->d[l] : c->d[l - 1];
+        RP_TRY(dev_alloc(c, &c->X[l], n * c->xw[l], true));
     }
     RP_TRY(dev_alloc(c, &c->D[0], n * c->dmax, false));
     RP_TRY(dev_alloc(c, &c->D[1], n * c->dmax, false));
     if (c->hmax) RP_TRY(dev_alloc(c, &c->tmp, n * c->hmax, false));
+    {
+        uint32_t pw = 0;
+        for (uint32_t l = 1; l <= c->L; ++l)
+            if (c->layers[l - 1].proj) pw = std::max(pw, c->d[l]);
+        c->pd_ld = rp_round_up(pw, 16);                  // rows start on 64-byte boundaries
+        if (pw) RP_TRY(dev_alloc(c, &c->PD, n * c->pd_ld, true));
+    }
     // bitmaps: layers 0..L, then S, then V_added, contiguous; reporting copies separately
     uint32_t *bmall = nullptr, *repall = nullptr, *lists = nullptr, *eoffs = nullptr, *ioffs = nullptr, *wranks = nullptr;
     RP_TRY(dev_alloc(c, &bmall, (size_t)c->n_words * (c->L + 3), true));
@@ -367,6 +387,7 @@ extern "C" ripple_status ripple_full_infer(ripple_ctx *c) {
                        c->n_words);
     rp_launch_bitmap_to_list(c, c->bm[0], c->all_list, &c->ctr->a[0]);
     for (uint32_t l = 1; l <= c->L; ++l) {
+        if (c->layers[l - 1].proj) rp_launch_project(c, l, c->all_list, &c->ctr->a[0], false);
         rp_launch_pull_all(c, l);
         rp_launch_transform(c, l, c->all_list, &c->ctr->a[0], false);
     }
@@ -550,6 +571,11 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
         t = rp_timer_begin(c);
         rp_launch_frontier_compact(c, l, layer_self(c, l), l < c->L, true, multi);
         rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l);
+        if (c->layers[l - 1].proj) {                   // multiply the deltas by W_neigh before they travel
+            t = rp_timer_begin(c);
+            rp_launch_project(c, l, c->list[l - 1], &c->ctr->a[l - 1], true);
+            rp_timer_end(c, t, RIPPLE_PH_OTHER, (int)l);
+        }
         t = rp_timer_begin(c);
         if (c->opt_scatter != 2 || !may_pull) rp_launch_scatter_push(c, l, may_pull);
         if (may_pull) rp_launch_scatter_pull(c, l);
@@ -778,7 +804,17 @@ extern "C" ripple_status ripple_get_aggregates(ripple_ctx *c, uint32_t layer, co
     if (!c) return RIPPLE_EINVAL;
     if (c->state < 3) return fail(c, RIPPLE_ESTATE, "aggregates not computed yet");
     if (layer == 0 || layer > c->L) return fail(c, RIPPLE_EINVAL, "layer out of range");
-    return gather_rows(c, c->X[layer], 0, c->d[layer - 1], ids, n_ids, out);
+    return gather_rows(c, c->X[layer], 0, c->xw[layer], ids, n_ids, out);
+}
+
+extern "C" ripple_status ripple_get_layer_info(ripple_ctx *c, uint32_t layer, uint32_t *aggregate_width,
+                                                int *projected) {
+    if (!c) return RIPPLE_EINVAL;
+    if (c->state < 2) return fail(c, RIPPLE_ESTATE, "no model loaded");
+    if (layer == 0 || layer > c->L) return fail(c, RIPPLE_EINVAL, "layer out of range");
+    if (aggregate_width) *aggregate_width = c->xw[layer];
+    if (projected) *projected = (int)c->layers[layer - 1].proj;
+    return RIPPLE_OK;
 }
 
 extern "C" ripple_status ripple_get_affected(ripple_ctx *c, uint32_t layer, uint32_t *ids_out, uint32_t cap,
@@ -877,6 +913,10 @@ extern "C" ripple_status ripple_set_option(ripple_ctx *c, int option, int64_t va
     case RIPPLE_OPT_SCATTER_MODE:
         if (value < 0 || value > 2) return fail(c, RIPPLE_EINVAL, "scatter mode must be 0, 1 or 2");
         c->opt_scatter = (int)value;
+        return RIPPLE_OK;
+    case RIPPLE_OPT_PROJECT_FIRST:
+        if (c->state != 1) return fail(c, RIPPLE_ESTATE, "project-first must be chosen before load_model");
+        c->opt_project = value ? 1 : 0;
         return RIPPLE_OK;
     case RIPPLE_OPT_PULL_RATIO:
         if (value < 1 || value > 1024) return fail(c, RIPPLE_EINVAL, "pull ratio must be in 1..1024");

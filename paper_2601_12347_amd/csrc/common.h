@@ -53,6 +53,10 @@ struct LayerDev {
     float *W0, *b0, *W1, *b1;
     __hip_bfloat16 *W0h, *W1h;                // bf16 copies (bf16 store only)
     uint32_t K0pad, N0pad, K1pad, N1pad;
+    // project-first layers: the cached aggregate holds sum_u H[u] W_neigh (d_out wide)
+    uint32_t proj;
+    float *Wn;                                // neighbour weights padded to [roundup(d_in,32) x N0pad] (may alias W0)
+    float *bzero;                             // N0pad zeros
 };
 
 struct PhaseTimer;
@@ -85,6 +89,9 @@ struct ripple_ctx {
     float *X[RIPPLE_MAX_LAYERS + 1] = {nullptr};
     float *D[2] = {nullptr, nullptr};                   // compact delta rows, ping-pong
     float *tmp = nullptr;                               // hidden activations of two-stage updates
+    float *PD = nullptr;                                // projected rows of project-first layers
+    uint32_t xw[RIPPLE_MAX_LAYERS + 1] = {0};           // width of X^l (d_{l-1}, or d_l when projected)
+    uint32_t pd_ld = 0;                                 // row stride of PD (64-byte multiple)
 
     // frontier
     uint32_t *bm[RIPPLE_MAX_LAYERS + 1] = {nullptr};    // dirty bitmap per layer
@@ -128,6 +135,7 @@ struct ripple_ctx {
     // options
     int opt_timing = 0;
     int opt_scatter = 0;
+    int opt_project = 1;                        // allow project-first layers (read by load_model)
     int opt_pull_ratio = 2;                     // pull when messages * width * ratio >= scanned in-edges
     ripple_stats stats;
     PhaseTimer *timer = nullptr;

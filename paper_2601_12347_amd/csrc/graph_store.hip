@@ -267,8 +267,11 @@ struct MutArgs {
     int store;
     uint32_t L;
     uint32_t d[RIPPLE_MAX_LAYERS + 1];
+    uint32_t xw[RIPPLE_MAX_LAYERS + 1];          // width of X^l
     void *H[RIPPLE_MAX_LAYERS + 1];
     float *X[RIPPLE_MAX_LAYERS + 1];
+    const float *Wn[RIPPLE_MAX_LAYERS + 1];      // project-first layers: neighbour weights (row stride wn_ld), else null
+    uint32_t wn_ld[RIPPLE_MAX_LAYERS + 1];
 };
 
 __device__ __forceinline__ void touch_row(const MutArgs &a, uint32_t x, uint32_t bit) {
@@ -556,7 +559,7 @@ __global__ __launch_bounds__(256) void k_apply_vertices(MutArgs a) {
                     else ((float *)a.H[l])[idx] = 0.0f;
                 }
                 if (l >= 1) {
-                    uint32_t dp = a.d[l - 1];
+                    uint32_t dp = a.xw[l];
                     for (uint32_t c = lane; c < dp; c += 64) a.X[l][(size_t)w * dp + c] = 0.0f;
                 }
             }
@@ -663,9 +666,29 @@ __global__ __launch_bounds__(256) void k_struct_scatter(MutArgs a) {
         uint32_t u = a.st_src[e], v = a.st_dst[e];
         float sg = a.st_sign[e];
         uint32_t dp = a.d[l - 1];
-        for (uint32_t c = lane; c < dp; c += 64) {
-            float val = rp_load_h(a.H[l - 1], a.store, (size_t)u * dp + c);
-            if (val != 0.0f) unsafeAtomicAdd(&a.X[l][(size_t)v * dp + c], sg * val);
+        if (a.Wn[l] == nullptr) {
+            for (uint32_t c = lane; c < dp; c += 64) {
+                float val = rp_load_h(a.H[l - 1], a.store, (size_t)u * dp + c);
+                if (val != 0.0f) unsafeAtomicAdd(&a.X[l][(size_t)v * dp + c], sg * val);
+            }
+        } else {                                             // project-first layer: add sign * (H_old[u] W_neigh)
+            const uint32_t dn = a.xw[l];
+            const float *W = a.Wn[l];
+            const uint32_t ld = a.wn_ld[l];
+            for (uint32_t c0 = 0; c0 < dn; c0 += 64) {
+                const uint32_t c = c0 + lane;
+                float sum = 0.0f;
+                for (uint32_t k0 = 0; k0 < dp; k0 += 64) {
+                    const uint32_t kk = k0 + lane;
+                    const float hv = (kk < dp) ? rp_load_h(a.H[l - 1], a.store, (size_t)u * dp + kk) : 0.0f;
+                    const uint32_t kn = min(64u, dp - k0);
+                    for (uint32_t j = 0; j < kn; ++j) {
+                        const float hk = __shfl(hv, (int)j);
+                        if (c < dn) sum += hk * W[(size_t)(k0 + j) * ld + c];
+                    }
+                }
+                if (c < dn && sum != 0.0f) unsafeAtomicAdd(&a.X[l][(size_t)v * dn + c], sg * sum);
+            }
         }
     }
 }
@@ -735,8 +758,12 @@ static MutArgs make_args(ripple_ctx *c, uint32_t n_ops) {
     a.L = c->L;
     for (uint32_t l = 0; l <= RIPPLE_MAX_LAYERS; ++l) {
         a.d[l] = c->d[l];
+        a.xw[l] = c->xw[l];
         a.H[l] = c->H[l];
         a.X[l] = c->X[l];
+        const bool proj = l >= 1 && l <= c->L && c->layers[l - 1].proj;
+        a.Wn[l] = proj ? c->layers[l - 1].Wn : nullptr;
+        a.wn_ld[l] = proj ? c->layers[l - 1].N0pad : 0;
     }
     return a;
 }

@@ -39,7 +39,7 @@ __device__ __forceinline__ bool rp_use_pull(const DevCtr *ctr, uint32_t l, uint3
 
 template <int NJ>
 __global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, const uint32_t *count_ptr,
-                                                      const uint32_t *eoff, const float *D, uint32_t d,
+                                                      const uint32_t *eoff, const float *D, uint32_t ldd, uint32_t d,
                                                       const uint2 *out_meta, const uint32_t *out_pool, float *X,
                                                       const DevCtr *ctr, uint32_t l, int may_pull, int mode, int ratio) {
     if (may_pull && rp_use_pull(ctr, l, d, mode, ratio)) return;
@@ -71,7 +71,7 @@ __global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, cons
 #pragma unroll
                 for (int j = 0; j < NJ; ++j) {
                     uint32_t col = lane + 64 * j;
-                    dreg[j] = (col < d) ? D[(size_t)ik * d + col] : 0.0f;
+                    dreg[j] = (col < d) ? D[(size_t)ik * ldd + col] : 0.0f;
                     any |= dreg[j] != 0.0f;
                 }
                 nz = __ballot(any) != 0ull;
@@ -88,12 +88,14 @@ __global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, cons
 }
 
 void rp_launch_scatter_push(ripple_ctx *c, uint32_t l, bool may_pull) {
-    const uint32_t d = c->d[l - 1];
-    const float *D = c->D[(l - 1) & 1];
+    const bool proj = c->layers[l - 1].proj != 0;           // project-first: messages are already d_out wide
+    const uint32_t d = c->xw[l];
+    const float *D = proj ? c->PD : c->D[(l - 1) & 1];
+    const uint32_t ldd = proj ? c->pd_ld : d;
     dim3 grid(c->n_cu * 8), block(256);
 #define PUSH_CASE(NJ)                                                                                         \
     hipLaunchKernelGGL(k_scatter_push<NJ>, grid, block, 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],      \
-                       c->eoff[l - 1], D, d, c->out_meta, c->out_pool, c->X[l], c->ctr, l, may_pull ? 1 : 0,          \
+                       c->eoff[l - 1], D, ldd, d, c->out_meta, c->out_pool, c->X[l], c->ctr, l, may_pull ? 1 : 0,          \
                        c->opt_scatter, c->opt_pull_ratio)
     if (d <= 64) PUSH_CASE(1);
     else if (d <= 128) PUSH_CASE(2);
@@ -115,6 +117,7 @@ struct PullArgs {
     const uint32_t *bm_prev;       // A_{l-1} as bitmap
     const uint32_t *wrank_prev;    // rank of each bitmap word's first vertex in A_{l-1}
     const float *D;                // delta rows of A_{l-1}, row = rank
+    uint32_t ldd;                  // their row stride
     uint32_t d;
     float *X;
     const DevCtr *ctr;
@@ -127,6 +130,8 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
     if (!rp_use_pull(a.ctr, a.l, a.d, a.mode, a.ratio)) return;
     const uint32_t count = *a.count_ptr;
     if (count == 0) return;
+    constexpr int G = (NJ >= 8) ? 2 : 16 / NJ;              // delta rows gathered per round trip
+    constexpr int T = PULL_CHUNK / 64;                      // in-edges examined per lane and chunk
     const int lane = rp_lane();
     const uint32_t d = a.d;
     const uint32_t total = a.ioff[count];
@@ -136,49 +141,57 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
         const uint32_t e0 = c * PULL_CHUNK, e1 = min(total, e0 + PULL_CHUNK);
         const uint32_t i_lo = seg_search2(a.ioff, 0, count - 1, e0);
         const uint32_t i_hi = seg_search2(a.ioff, i_lo, count - 1, e1 - 1);
+        // every lane resolves its T in-edges first (independent load chains), then the
+        // wavefront walks the dirty ones in edge order
+        uint32_t my_i[T], slot[T];
+        bool dirty[T];
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const uint32_t e = e0 + 64 * t + lane;
+            my_i[t] = 0;
+            slot[t] = 0;
+            dirty[t] = false;
+            if (e < e1) {
+                my_i[t] = (i_lo == i_hi) ? i_lo : seg_search2(a.ioff, i_lo, i_hi, e);
+                const uint32_t u = a.in_pool[a.in_meta[a.list[my_i[t]]].x + (e - a.ioff[my_i[t]])];
+                const uint32_t word = a.bm_prev[u >> 5];
+                dirty[t] = (word >> (u & 31)) & 1u;
+                if (dirty[t]) slot[t] = a.wrank_prev[u >> 5] + __popc(word & ((1u << (u & 31)) - 1u));
+            }
+        }
         uint32_t cur = i_lo;
         float acc[NJ];
 #pragma unroll
         for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
-        for (uint32_t eb = e0; eb < e1; eb += 64) {
-            const uint32_t e = eb + lane;
-            const bool valid = e < e1;
-            uint32_t my_i = 0, slot = 0;
-            bool dirty = false;
-            if (valid) {
-                my_i = seg_search2(a.ioff, i_lo, i_hi, e);
-                const uint32_t u = a.in_pool[a.in_meta[a.list[my_i]].x + (e - a.ioff[my_i])];
-                const uint32_t word = a.bm_prev[u >> 5];
-                dirty = (word >> (u & 31)) & 1u;
-                if (dirty) slot = a.wrank_prev[u >> 5] + __popc(word & ((1u << (u & 31)) - 1u));
-            }
-            unsigned long long mask = __ballot(dirty);
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            unsigned long long mask = __ballot(dirty[t]);
             while (mask) {
-                int kk[4];
+                int kk[G];
                 int n = 0;
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    kk[t] = 0;
+                for (int g = 0; g < G; ++g) {
+                    kk[g] = 0;
                     if (mask) {
-                        kk[t] = __ffsll((long long)mask) - 1;
+                        kk[g] = __ffsll((long long)mask) - 1;
                         mask &= mask - 1;
-                        n = t + 1;
+                        n = g + 1;
                     }
                 }
-                float r[4][NJ];
+                float r[G][NJ];
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    const uint32_t sk = __shfl(slot, kk[t]);
+                for (int g = 0; g < G; ++g) {
+                    const uint32_t sk = __shfl(slot[t], kk[g]);
 #pragma unroll
                     for (int j = 0; j < NJ; ++j) {
                         const uint32_t col = lane + 64 * j;
-                        r[t][j] = (t < n && col < d) ? a.D[(size_t)sk * d + col] : 0.0f;
+                        r[g][j] = (g < n && col < d) ? a.D[(size_t)sk * a.ldd + col] : 0.0f;
                     }
                 }
 #pragma unroll
-                for (int t = 0; t < 4; ++t) {
-                    if (t < n) {
-                        const uint32_t ik = __shfl(my_i, kk[t]);
+                for (int g = 0; g < G; ++g) {
+                    if (g < n) {
+                        const uint32_t ik = __shfl(my_i[t], kk[g]);
                         if (ik != cur) {                     // the destination changes: flush its partial sum
                             float *xr = a.X + (size_t)a.list[cur] * d;
 #pragma unroll
@@ -190,7 +203,7 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
                             cur = ik;
                         }
 #pragma unroll
-                        for (int j = 0; j < NJ; ++j) acc[j] += r[t][j];
+                        for (int j = 0; j < NJ; ++j) acc[j] += r[g][j];
                     }
                 }
             }
@@ -213,8 +226,9 @@ void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l) {
     a.in_pool = c->in_pool;
     a.bm_prev = c->bm[l - 1];
     a.wrank_prev = c->wrank[l - 1];
-    a.D = c->D[(l - 1) & 1];
-    a.d = c->d[l - 1];
+    a.D = c->layers[l - 1].proj ? c->PD : c->D[(l - 1) & 1];
+    a.d = c->xw[l];
+    a.ldd = c->layers[l - 1].proj ? c->pd_ld : a.d;
     a.X = c->X[l];
     a.ctr = c->ctr;
     a.l = l;
@@ -233,7 +247,7 @@ void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l) {
 // ---------------------------------------------------------------------------------
 template <int NJ, int STORE>
 __global__ __launch_bounds__(256) void k_pull_all(const uint2 *in_meta, const uint32_t *in_pool, uint32_t n_cap,
-                                                  const void *Hprev, uint32_t d, float *X) {
+                                                  const void *Hprev, uint32_t lds, uint32_t d, float *X) {
     const int lane = rp_lane();
     const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
     for (uint32_t v = gw; v < n_cap; v += nw) {
@@ -251,7 +265,7 @@ __global__ __launch_bounds__(256) void k_pull_all(const uint2 *in_meta, const ui
                 for (int j = 0; j < NJ; ++j) {
                     uint32_t col = lane + 64 * j;
                     if (col < d) {
-                        size_t idx = (size_t)u * d + col;
+                        size_t idx = (size_t)u * lds + col;
                         acc[j] += STORE ? __bfloat162float(((const __hip_bfloat16 *)Hprev)[idx])
                                         : ((const float *)Hprev)[idx];
                     }
@@ -266,17 +280,23 @@ __global__ __launch_bounds__(256) void k_pull_all(const uint2 *in_meta, const ui
     }
 }
 
+// X^l[v] = sum over v's in-row of the previous layer's rows (of their projections, kept in PD,
+// for project-first layers)
 void rp_launch_pull_all(ripple_ctx *c, uint32_t l) {
-    const uint32_t d = c->d[l - 1];
+    const bool proj = c->layers[l - 1].proj != 0;
+    const uint32_t d = c->xw[l];
+    const void *src = proj ? (const void *)c->PD : c->H[l - 1];
+    const int store = proj ? 0 : c->store;
+    const uint32_t lds = proj ? c->pd_ld : d;
     dim3 grid(c->n_cu * 16), block(256);
 #define PULL_CASE(NJ)                                                                                          \
     do {                                                                                                       \
-        if (c->store)                                                                                          \
+        if (store)                                                                                             \
             hipLaunchKernelGGL((k_pull_all<NJ, 1>), grid, block, 0, c->stream, c->in_meta, c->in_pool, c->n_cap, \
-                               c->H[l - 1], d, c->X[l]);                                                       \
+                               src, lds, d, c->X[l]);                                                          \
         else                                                                                                   \
             hipLaunchKernelGGL((k_pull_all<NJ, 0>), grid, block, 0, c->stream, c->in_meta, c->in_pool, c->n_cap, \
-                               c->H[l - 1], d, c->X[l]);                                                       \
+                               src, lds, d, c->X[l]);                                                          \
     } while (0)
     if (d <= 64) PULL_CASE(1);
     else if (d <= 128) PULL_CASE(2);

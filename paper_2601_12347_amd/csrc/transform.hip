@@ -15,6 +15,12 @@
 // mode is a template parameter) and touches no loaded value, so nothing waits on
 // memory until the registers are written to LDS; scaling, the SAGE/GIN combination
 // and zero padding are applied at that point.
+//
+// Layers whose output is much narrower than their input (the classifier layer) are
+// handled "project first": aggregation and the linear map commute, so the deltas are
+// multiplied by the neighbour weights before they are scattered, the cached aggregate
+// holds sum_u H[u] W_neigh (d_out wide), and the row transform only adds it
+// (scaled for mean) to h_self W_self + b in the epilogue.
 #include "common.h"
 #include "kernels.h"
 
@@ -24,7 +30,7 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));   // native vector: s
 struct TArgs {
     const uint32_t *list;          // slot -> vertex id
     const uint32_t *count_ptr;     // number of slots (device)
-    int a_mode;                    // 0 x | 1 [h_self | x] | 2 (1+eps) h_self + x | 3 compact rows of tmp_in
+    int a_mode;                    // 0 x | 1 [h_self | x] | 2 (1+eps) h_self + x | 3 compact rows of tmp_in | 4 h_self
     const void *Hprev;
     const float *X;
     const uint2 *in_meta;
@@ -37,7 +43,8 @@ struct TArgs {
     const float *bias;             // [Npad]
     uint32_t K, Kpad, N, Npad;
     int act;
-    int out_mode;                  // 0 write act(z) to tmp_out[slot] | 1 update H, emit delta
+    int out_mode;                  // 0 write act(z) to tmp_out[slot] | 1 update H, emit delta | 2 write to tmp_out[vertex]
+    const float *addend;           // projected aggregate [vertex x N] added (times the mean scale) before the activation, or null
     float *tmp_out;
     uint32_t tmp_out_ld;
     void *Hout;
@@ -60,6 +67,14 @@ __device__ __forceinline__ void fetch_raw(const TArgs &a, uint32_t v, uint32_t s
         p = *(const floatx4 *)(a.X + row + kc);
     } else if (MODE == 3) {
         p = *(const floatx4 *)(a.tmp_in + (size_t)slot * a.tmp_ld + kc);
+    } else if (MODE == 4) {
+        if (STORE) {
+            const uint2 r = *(const uint2 *)((const __hip_bfloat16 *)a.Hprev + row + kc);
+            p.x = __uint_as_float(r.x);
+            p.y = __uint_as_float(r.y);
+        } else {
+            p = *(const floatx4 *)((const float *)a.Hprev + row + kc);
+        }
     } else if (MODE == 2) {
         q = *(const floatx4 *)(a.X + row + kc);
         if (STORE) {
@@ -86,7 +101,7 @@ __device__ __forceinline__ void fetch_raw(const TArgs &a, uint32_t v, uint32_t s
 template <int MODE, int STORE>
 __device__ __forceinline__ floatx4 finish_raw(const TArgs &a, floatx4 p, floatx4 q, uint32_t k, float scale) {
     floatx4 h = p;
-    if (STORE && (MODE == 1 || MODE == 2)) {
+    if (STORE && (MODE == 1 || MODE == 2 || MODE == 4)) {
         const uint32_t w0 = __float_as_uint(p.x), w1 = __float_as_uint(p.y);
         h.x = bf_lo(w0);
         h.y = bf_hi(w0);
@@ -98,6 +113,8 @@ __device__ __forceinline__ floatx4 finish_raw(const TArgs &a, floatx4 p, floatx4
         r = p * scale;
     } else if (MODE == 3) {
         r = p;
+    } else if (MODE == 4) {
+        r = h;
     } else if (MODE == 2) {
         r = h * a.one_plus_eps + q * scale;
     } else {
@@ -108,29 +125,32 @@ __device__ __forceinline__ floatx4 finish_raw(const TArgs &a, floatx4 p, floatx4
     return r;
 }
 
-// Bias, activation, delta against the stored row, store. The old rows are read in batches of
-// TN*16 loads before anything is written: a load may not move above an earlier store to the same
-// array, so interleaving them would pay one memory round trip per element.
+// Bias, (projected aggregate,) activation, delta against the stored row, store. Everything that
+// is read (old rows, aggregate rows) is read in batches of TN*16 loads before anything is written:
+// a load may not move above an earlier store to the same array, so interleaving them would pay one
+// memory round trip per element.
 template <int TM, int TN>
-__device__ __forceinline__ void epilogue(const TArgs &a, floatx16 (&acc)[TM][TN], const uint32_t *s_vtx, uint32_t row0,
-                                         uint32_t count, uint32_t n0, int wm, int wn, int lane) {
+__device__ __forceinline__ void epilogue(const TArgs &a, floatx16 (&acc)[TM][TN], const uint32_t *s_vtx,
+                                         const float *s_scale, uint32_t row0, uint32_t count, uint32_t n0, int wm, int wn,
+                                         int lane) {
 #pragma unroll
     for (int sm = 0; sm < TM; ++sm) {
-        float old[TN][16];
-        if (a.out_mode != 0) {
+        float old[TN][16], add[TN][16];
 #pragma unroll
-            for (int sn = 0; sn < TN; ++sn) {
-                const uint32_t col = n0 + (wn * TN + sn) * 32 + (lane & 31);
+        for (int sn = 0; sn < TN; ++sn) {
+            const uint32_t col = n0 + (wn * TN + sn) * 32 + (lane & 31);
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int lr = (wm * TM + sm) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
-                    float o = 0.0f;
-                    if (col < a.N && row0 + lr < count) {
-                        const size_t hidx = (size_t)s_vtx[lr] * a.N + col;
+            for (int r = 0; r < 16; ++r) {
+                const int lr = (wm * TM + sm) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                float o = 0.0f, ad = 0.0f;
+                if (col < a.N && row0 + lr < count) {
+                    const size_t hidx = (size_t)s_vtx[lr] * a.N + col;
+                    if (a.out_mode == 1)
                         o = a.store ? __bfloat162float(((const __hip_bfloat16 *)a.Hout)[hidx]) : ((const float *)a.Hout)[hidx];
-                    }
-                    old[sn][r] = o;
+                    if (a.addend) ad = a.addend[hidx] * s_scale[lr];
                 }
+                old[sn][r] = o;
+                add[sn][r] = ad;
             }
         }
 #pragma unroll
@@ -143,10 +163,12 @@ __device__ __forceinline__ void epilogue(const TArgs &a, floatx16 (&acc)[TM][TN]
                 const int lr = (wm * TM + sm) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
                 const uint32_t slot = row0 + lr;
                 if (slot >= count) continue;
-                float z = acc[sm][sn][r] + bias;
+                float z = acc[sm][sn][r] + bias + add[sn][r];
                 if (a.act == RIPPLE_ACT_RELU) z = z > 0.0f ? z : 0.0f;
                 if (a.out_mode == 0) {
                     a.tmp_out[(size_t)slot * a.tmp_out_ld + col] = z;
+                } else if (a.out_mode == 2) {
+                    a.tmp_out[(size_t)s_vtx[lr] * a.tmp_out_ld + col] = z;
                 } else {
                     const size_t hidx = (size_t)s_vtx[lr] * a.N + col;
                     if (a.store) {
@@ -160,6 +182,37 @@ __device__ __forceinline__ void epilogue(const TArgs &a, floatx16 (&acc)[TM][TN]
                 }
             }
         }
+    }
+}
+
+// GraphConv handled project-first has no matrix product left per row: h = act(Y[v] * scale + b).
+__global__ void k_transform_addend_only(TArgs a) {
+    const uint32_t count = *a.count_ptr;
+    const size_t total = (size_t)count * a.N, stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
+        const uint32_t slot = (uint32_t)(i / a.N), col = (uint32_t)(i % a.N);
+        const uint32_t v = a.list[slot];
+        float sc = 1.0f;
+        if (a.mean) {
+            const uint32_t deg = a.in_meta[v].y;
+            sc = 1.0f / (float)(deg > 1u ? deg : 1u);
+        }
+        const size_t hidx = (size_t)v * a.N + col;
+        float z = a.addend[hidx] * sc + a.bias[col];
+        if (a.act == RIPPLE_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+        float old;
+        if (a.store) {
+            __hip_bfloat16 *h = (__hip_bfloat16 *)a.Hout;
+            old = __bfloat162float(h[hidx]);
+            const __hip_bfloat16 zr = __float2bfloat16(z);
+            z = __bfloat162float(zr);
+            h[hidx] = zr;
+        } else {
+            float *h = (float *)a.Hout;
+            old = h[hidx];
+            h[hidx] = z;
+        }
+        if (a.D) a.D[(size_t)slot * a.N + col] = z - old;
     }
 }
 
@@ -294,7 +347,7 @@ __global__ __launch_bounds__(256) void k_transform_f32(TArgs a) {
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
             }
         }
-        epilogue<TM, TN>(a, acc, s_vtx, row0, count, n0, wm, wn, lane);
+        epilogue<TM, TN>(a, acc, s_vtx, s_scale, row0, count, n0, wm, wn, lane);
     }
 }
 
@@ -309,6 +362,7 @@ __device__ __forceinline__ float load_a1(const TArgs &a, uint32_t v, uint32_t sl
                             : a.X[(size_t)v * a.d_in + (k - a.d_in)] * scale;
     case 2:
         return a.one_plus_eps * rp_load_h(a.Hprev, a.store, (size_t)v * a.d_in + k) + a.X[(size_t)v * a.d_in + k] * scale;
+    case 4: return rp_load_h(a.Hprev, a.store, (size_t)v * a.d_in + k);
     default: return a.tmp_in[(size_t)slot * a.tmp_ld + k];
     }
 }
@@ -378,7 +432,7 @@ __global__ __launch_bounds__(256) void k_transform_generic(TArgs a) {
             }
             __syncthreads();
         }
-        epilogue<TM, TN>(a, acc, s_vtx, row0, count, n0, wm, wn, lane);
+        epilogue<TM, TN>(a, acc, s_vtx, s_scale, row0, count, n0, wm, wn, lane);
     }
 }
 
@@ -411,6 +465,7 @@ static void launch_t(ripple_ctx *c, const TArgs &a, bool vec_ok) {
         T_CASE(0)
         T_CASE(1)
         T_CASE(2)
+        T_CASE(4)
     default:
         launch_fast<3, 0>(c, a);                             // compact fp32 rows: storage type plays no part in the gather
         break;
@@ -418,9 +473,7 @@ static void launch_t(ripple_ctx *c, const TArgs &a, bool vec_ok) {
 #undef T_CASE
 }
 
-// Re-apply layer l (1-based) to the vertices in `list` (count on the device).
-// emit_delta: write D^l (into the ping-pong buffer of parity l) for the next hop.
-void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool emit_delta) {
+static TArgs base_args(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d) {
     const LayerDev &ly = c->layers[l - 1];
     TArgs a;
     a.list = list;
@@ -435,31 +488,78 @@ void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const 
     a.tmp_ld = 0;
     a.store = c->store;
     a.Hout = c->H[l];
-    a.D = emit_delta ? c->D[l & 1] : nullptr;
+    a.D = nullptr;
     a.tmp_out = nullptr;
     a.tmp_out_ld = 0;
+    a.addend = nullptr;
+    a.a_mode = 0;
+    a.out_mode = 1;
+    a.act = 0;
+    a.W = ly.W0;
+    a.bias = ly.b0;
+    a.K = ly.K;
+    a.Kpad = ly.K0pad;
+    a.N = ly.d_out;
+    a.Npad = ly.N0pad;
+    return a;
+}
+
+// Project-first layers: P = rows * W_neigh, no bias, no activation.
+//   from_deltas: rows are the compact delta rows D^{l-1} of A_{l-1}; P[slot] goes to c->PD
+//   otherwise:   rows are H^{l-1}[v] for the listed vertices; P[v] goes to c->PD (bootstrap)
+void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool from_deltas) {
+    const LayerDev &ly = c->layers[l - 1];
+    TArgs a = base_args(c, l, list, count_d);
+    a.mean = 0;
+    a.W = ly.Wn;
+    a.bias = ly.bzero;
+    a.K = ly.d_in;
+    a.Kpad = rp_round_up(ly.d_in, 32);
+    a.act = RIPPLE_ACT_NONE;
+    a.tmp_out = c->PD;
+    a.tmp_out_ld = c->pd_ld;
+    a.Hout = nullptr;
+    if (from_deltas) {
+        a.a_mode = 3;
+        a.tmp_in = c->D[(l - 1) & 1];
+        a.tmp_ld = ly.d_in;
+        a.out_mode = 0;
+    } else {
+        a.a_mode = 4;
+        a.out_mode = 2;
+    }
+    launch_t(c, a, ly.d_in % 4 == 0);
+}
+
+// Re-apply layer l (1-based) to the vertices in `list` (count on the device).
+// emit_delta: write D^l (into the ping-pong buffer of parity l) for the next hop.
+void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool emit_delta) {
+    const LayerDev &ly = c->layers[l - 1];
+    TArgs a = base_args(c, l, list, count_d);
+    a.D = emit_delta ? c->D[l & 1] : nullptr;
     a.a_mode = (ly.self_mode == RIPPLE_SELF_NONE) ? 0 : (ly.self_mode == RIPPLE_SELF_CONCAT ? 1 : 2);
     const bool vec_in = (ly.d_in % 4 == 0);
-    if (ly.d_hidden == 0) {
-        a.W = ly.W0;
-        a.bias = ly.b0;
-        a.K = ly.K;
-        a.Kpad = ly.K0pad;
-        a.N = ly.d_out;
-        a.Npad = ly.N0pad;
+    if (ly.proj) {                               // aggregate already multiplied by W_neigh: add it in the epilogue
+        a.addend = c->X[l];
         a.act = (int)ly.act_out;
-        a.out_mode = 1;
+        if (ly.self_mode == RIPPLE_SELF_NONE) {
+            hipLaunchKernelGGL(k_transform_addend_only, dim3(c->n_cu * 8), dim3(256), 0, c->stream, a);
+            return;
+        }
+        a.a_mode = 4;                            // h_self * W_self: the first d_in rows of W0
+        a.K = ly.d_in;
+        a.Kpad = rp_round_up(ly.d_in, 32);
+        launch_t(c, a, vec_in);
+        return;
+    }
+    if (ly.d_hidden == 0) {
+        a.act = (int)ly.act_out;
         launch_t(c, a, vec_in);
         return;
     }
     // two-stage update: hidden = act_inner(row W0 + b0) -> tmp, then h = act_out(hidden W1 + b1)
     TArgs s1 = a;
-    s1.W = ly.W0;
-    s1.bias = ly.b0;
-    s1.K = ly.K;
-    s1.Kpad = ly.K0pad;
     s1.N = ly.d_hidden;
-    s1.Npad = ly.N0pad;
     s1.act = (int)ly.act_inner;
     s1.out_mode = 0;
     s1.tmp_out = c->tmp;

@@ -11,12 +11,14 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}      # max relative error per layer (metric: o
 
 
 class Pair:
-    def __init__(self, n, cap, src, dst, feats, model, store="f32", edge_capacity=None):
+    def __init__(self, n, cap, src, dst, feats, model, store="f32", edge_capacity=None, project_first=True):
         self.n, self.cap, self.model, self.store = n, cap, model, store
         self.widths = [model[0]["d_in"]] + [l["d_out"] for l in model]
         self.L = len(model)
         self.ora = oracle.GraphState(n, cap, src, dst, feats)
         self.ctx = rp.ripple_init_graph(n, cap, src, dst, feats, store=store, edge_capacity=edge_capacity)
+        if not project_first:
+            rp.ripple_set_option(self.ctx, rp.OPT_PROJECT_FIRST, 0)
         rp.ripple_load_model(self.ctx, model)
         rp.ripple_full_infer(self.ctx)
 
@@ -46,9 +48,15 @@ class Pair:
         src, dst = self.ora.edges()
         for l in range(1, self.L + 1):
             h_prev = self.gpu_layer(l - 1).astype(np.float64)
+            width, projected = rp.ripple_get_layer_info(self.ctx, l)
+            if projected:                                     # the layer caches sum_u H[u] W_neigh
+                lay = self.model[l - 1]
+                w = np.asarray(lay["W0"], dtype=np.float64)
+                h_prev = h_prev @ (w[lay["d_in"]:] if lay["self"] == "concat" else w)
+            assert width == h_prev.shape[1]
             want = np.zeros_like(h_prev)
             np.add.at(want, dst, h_prev[src])
-            got = rp.ripple_get_aggregates(self.ctx, l, self.widths[l - 1], n_rows=self.cap)
+            got = rp.ripple_get_aggregates(self.ctx, l, width, n_rows=self.cap)
             err = oracle.max_rel_err(got, want, self.ora.alive)
             assert err <= tol, f"aggregate {l}: {err:.3e}"
 
@@ -92,11 +100,12 @@ class Pair:
 
 
 def make_pair(n=300, e=1500, d0=12, kind="gcn_sum", widths=(12, 20, 8), store="f32", seed=0, slack=64,
-              gamma=2.1, top_share=0.03, edge_capacity=None):
+              gamma=2.1, top_share=0.03, edge_capacity=None, project_first=True):
     src, dst, out_law, in_law = ri.chung_lu_graph(n, e, gamma, top_share, seed)
     feats = ri.features(n, d0, seed + 1)
     model = ri.make_model(kind, widths, seed + 2)
-    pair = Pair(n, n + slack, src, dst, feats, model, store=store, edge_capacity=edge_capacity)
+    pair = Pair(n, n + slack, src, dst, feats, model, store=store, edge_capacity=edge_capacity,
+                project_first=project_first)
     return pair, (src, dst, out_law, in_law)
 
 

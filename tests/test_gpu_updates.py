@@ -75,6 +75,30 @@ def test_push_and_pull_scatter_agree_with_oracle(mode, kind, widths):
         pair.close()
 
 
+@pytest.mark.parametrize("kind,widths,store", [("sage_mean", (16, 40, 24, 10), "f32"), ("gcn_sum", (100, 256, 47), "f32"),
+                                               ("gcn_mean", (32, 64, 12), "bf16")])
+@pytest.mark.parametrize("project_first", [True, False])
+def test_project_first_layers(kind, widths, store, project_first):
+    """Narrow output layers cache sum_u H[u] W_neigh and scatter d_out-wide messages; switching
+    that off must give the same embeddings, and both must match the oracle."""
+    print("case project-first", project_first, kind, store, flush=True)
+    pair, graph = make_pair(n=800, e=7000, d0=widths[0], kind=kind, widths=widths, seed=61, slack=128, store=store,
+                            project_first=project_first)
+    L = len(widths) - 1
+    assert rp.ripple_get_layer_info(pair.ctx, L) == ((widths[-1], True) if project_first else (widths[-2], False))
+    stream = make_stream(pair, graph, MIXV, 63)
+    try:
+        pair.check_aggregates(tol=1e-3 if store == "bf16" else None)
+        for b, bs in enumerate([5, 60, 150]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload)
+        pair.check_graph()
+        pair.check_aggregates(tol=1e-3 if store == "bf16" else None)
+    finally:
+        pair.close()
+
+
 def test_tiny_config_batches():
     cfg = ri.get_config("tiny_gcn_sum")
     print("case tiny config", flush=True)
