@@ -112,6 +112,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--scatter-mode", type=int, default=0)
     ap.add_argument("--pull-ratio", type=int, default=0)
+    ap.add_argument("--no-kernel-timing", action="store_true",
+                    help="leave the library's per-kernel HIP events off (no roofline object; lowest latency)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run three 1 GiB device-to-device copies (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -167,7 +169,7 @@ def main():
 
     for b in batches[:args.warmup]:
         run(b)
-    rp.ripple_set_option(ctx, rp.OPT_TIMING, 1)
+    rp.ripple_set_option(ctx, rp.OPT_TIMING, 0 if args.no_kernel_timing else 1)
     rp.ripple_get_stats(ctx, reset=True)
     torch.cuda.synchronize()
     lat, n_updates, applied = [], 0, 0
