@@ -112,6 +112,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--scatter-mode", type=int, default=0)
     ap.add_argument("--pull-ratio", type=int, default=0)
+    ap.add_argument("--bf16-mfma", type=int, default=1, help="bf16 storage only: 0 = multiply on the fp32 matrix path")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="leave the library's per-kernel HIP events off (no roofline object; lowest latency)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -152,6 +153,7 @@ def main():
     log(f"[bench] {len(batches)} batches of {bs} updates staged in HBM in {time.time() - t0:.1f}s")
 
     rp.ripple_set_option(ctx, rp.OPT_SCATTER_MODE, args.scatter_mode)
+    rp.ripple_set_option(ctx, rp.OPT_BF16_MFMA, args.bf16_mfma)
     if args.pull_ratio:
         rp.ripple_set_option(ctx, rp.OPT_PULL_RATIO, args.pull_ratio)
     if args.calibrate_copy:
@@ -189,6 +191,7 @@ def main():
     layer_info = {l: rp.ripple_get_layer_info(ctx, l) for l in range(1, L + 1)}
     work = algorithmic_work(st, model, cfg.widths, cfg.store, L, layer_info)
     phase_idx = {"frontier": 2, "scatter": 3, "transform": 5}
+    mfma_peak = MFMA_PEAK_TFLOPS["bf16" if (cfg.store == "bf16" and args.bf16_mfma) else "f32"]
     kernels = {}
     for (ph, l), w in work.items():
         ms = st.ms[phase_idx[ph]][l] + (st.ms[6][l] if ph == "transform" else 0.0)   # 6: projection of the deltas
@@ -199,7 +202,7 @@ def main():
                "GBps": w["bytes"] / (ms * 1e-3) / 1e9, "hbm_frac": w["bytes"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
         if ph == "transform":
             ent["TFLOPs"] = w["flops"] / (ms * 1e-3) / 1e12
-            ent["mfma_frac"] = ent["TFLOPs"] / MFMA_PEAK_TFLOPS["f32"]
+            ent["mfma_frac"] = ent["TFLOPs"] / mfma_peak
         kernels[f"{ph}_l{l}"] = ent
     other = {name: st.ms[i][0] / max(st.batches, 1) for i, name in ((0, "ingest"), (1, "struct"), (7, "total"))}
     for l in range(1, L + 1):
@@ -213,9 +216,9 @@ def main():
         w = work[(ph, l)]
         # transform is priced against the matrix-core peak only where its arithmetic intensity
         # clears the ridge (peak flops / peak bytes); otherwise it is HBM-bound
-        ridge = MFMA_PEAK_TFLOPS["f32"] * 1e12 / (HBM_PEAK_GBS * 1e9)
+        ridge = mfma_peak * 1e12 / (HBM_PEAK_GBS * 1e9)
         if ph == "transform" and w["flops"] / max(w["bytes"], 1) >= ridge:
-            roofline = {"kernel": dom, "bound": "mfma", "achieved": k["TFLOPs"], "peak": MFMA_PEAK_TFLOPS["f32"],
+            roofline = {"kernel": dom, "bound": "mfma", "achieved": k["TFLOPs"], "peak": mfma_peak,
                         "unit": "TFLOP/s", "frac": k["mfma_frac"], "traffic": None}
         else:
             roofline = {"kernel": dom, "bound": "hbm", "achieved": k["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -230,7 +233,8 @@ def main():
         "vs_baseline": None, "dtype": "f32" if cfg.store == "f32" else "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: Chung-Lu gamma={cfg.gamma}, {cfg.n} vertices, {cfg.e} edges, "
                                f"widths {'->'.join(map(str, cfg.widths))}, {bs} updates/batch "
-                               f"(50% edge add, 30% edge delete, 20% feature update)",
+                               + ("(50% edge add, 30% edge delete, 20% feature update)" if not cfg.mix.get("vadd") else
+                                  f"({cfg.mix['vadd']:.0%} vertex add, {cfg.mix['vdel']:.0%} vertex delete, rest 50/30/20 edge add/edge delete/feature update)"),
                    "batch_size": bs, "updates_applied": int(applied)},
         "per_batch": {"a_l": [st.rows[l] / max(st.batches, 1) for l in range(L + 1)],
                       "messages_l": [st.msgs[l] / max(st.batches, 1) for l in range(L + 1)],

@@ -311,6 +311,18 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
         ly.K0pad = rp_round_up(ly.K, 32);
         ly.N0pad = pad_n(n0);
         RP_TRY(upload_padded(c, s.W0, s.b0, ly.K, n0, ly.K0pad, ly.N0pad, &ly.W0, &ly.b0));
+        if (c->store == RIPPLE_STORE_BF16) {               // transposed bf16 copy for the bf16 matrix cores
+            std::vector<uint16_t> wt((size_t)ly.N0pad * ly.K0pad, 0);
+            for (uint32_t k = 0; k < ly.K; ++k)
+                for (uint32_t j = 0; j < n0; ++j) {
+                    uint32_t bits;
+                    memcpy(&bits, &s.W0[(size_t)k * n0 + j], 4);
+                    bits += 0x7FFFu + ((bits >> 16) & 1u);      // round to nearest even
+                    wt[(size_t)j * ly.K0pad + k] = (uint16_t)(bits >> 16);
+                }
+            RP_TRY(dev_alloc(c, &ly.W0h, wt.size(), false));
+            RP_HIP(c, hipMemcpy(ly.W0h, wt.data(), wt.size() * 2, hipMemcpyHostToDevice));
+        }
         // project first where the single linear map shrinks the row at least by half
         ly.proj = (c->opt_project && s.d_hidden == 0 && s.self_mode != RIPPLE_SELF_ADD && 2 * s.d_out <= s.d_in) ? 1u : 0u;
         if (ly.proj) {
@@ -913,6 +925,9 @@ extern "C" ripple_status ripple_set_option(ripple_ctx *c, int option, int64_t va
     case RIPPLE_OPT_SCATTER_MODE:
         if (value < 0 || value > 2) return fail(c, RIPPLE_EINVAL, "scatter mode must be 0, 1 or 2");
         c->opt_scatter = (int)value;
+        return RIPPLE_OK;
+    case RIPPLE_OPT_BF16_MFMA:
+        c->opt_bf16_mfma = value ? 1 : 0;
         return RIPPLE_OK;
     case RIPPLE_OPT_PROJECT_FIRST:
         if (c->state != 1) return fail(c, RIPPLE_ESTATE, "project-first must be chosen before load_model");

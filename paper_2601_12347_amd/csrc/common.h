@@ -51,7 +51,7 @@ struct LayerDev {
     float eps;
     // weights padded to [Kpad x Npad] (Kpad multiple of 32, Npad multiple of 64), zero filled
     float *W0, *b0, *W1, *b1;
-    __hip_bfloat16 *W0h, *W1h;                // bf16 copies (bf16 store only)
+    __hip_bfloat16 *W0h, *W1h;                // bf16 copy of W0, transposed [N0pad x K0pad] (bf16 store only); W1h unused
     uint32_t K0pad, N0pad, K1pad, N1pad;
     // project-first layers: the cached aggregate holds sum_u H[u] W_neigh (d_out wide)
     uint32_t proj;
@@ -135,6 +135,7 @@ struct ripple_ctx {
     // options
     int opt_timing = 0;
     int opt_scatter = 0;
+    int opt_bf16_mfma = 1;                      // bf16 storage: multiply on the bf16 matrix cores
     int opt_project = 1;                        // allow project-first layers (read by load_model)
     int opt_pull_ratio = 2;                     // pull when messages * width * ratio >= scanned in-edges
     ripple_stats stats;

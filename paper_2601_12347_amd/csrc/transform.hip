@@ -41,6 +41,8 @@ struct TArgs {
     uint32_t tmp_ld;
     const float *W;                // [Kpad x Npad], zero padded
     const float *bias;             // [Npad]
+    const __hip_bfloat16 *Wt;      // bf16 copy of W, transposed [Npad x Kpad] (k contiguous), or null
+    uint32_t wt_ld;                // its row stride
     uint32_t K, Kpad, N, Npad;
     int act;
     int out_mode;                  // 0 write act(z) to tmp_out[slot] | 1 update H, emit delta | 2 write to tmp_out[vertex]
@@ -436,6 +438,169 @@ __global__ __launch_bounds__(256) void k_transform_generic(TArgs a) {
     }
 }
 
+// ---------------------------------------------------------------------------------
+// bf16 matrix-core variant (embeddings stored in bfloat16): MFMA 32x32x16 bf16 with fp32
+// accumulation. Same tiling, prefetch and epilogue; the gathered rows are rounded to bf16 when
+// they are written to LDS, the weights come from a transposed bf16 copy so that the eight
+// consecutive k a lane feeds into one MFMA are one 16-byte LDS read for both operands.
+// ---------------------------------------------------------------------------------
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+#define TB_LD 40                                            // LDS row stride in bf16 (80 bytes)
+
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    const __hip_bfloat16 a = __float2bfloat16(lo), b = __float2bfloat16(hi);
+    return (uint32_t)__builtin_bit_cast(unsigned short, a) | ((uint32_t)__builtin_bit_cast(unsigned short, b) << 16);
+}
+
+template <int WAVES_M, int WAVES_N, int TM, int TN, int STAGES, int MODE>
+__global__ __launch_bounds__(256) void k_transform_bf16(TArgs a) {
+    constexpr int STORE = 1;
+    constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
+    constexpr int NA = BM / 32, NB = BN / 64;              // per thread per slice: float4 of A, 16-byte chunks of B
+    constexpr bool TWO = (MODE == 2) || (MODE == 1);
+    __shared__ __attribute__((aligned(16))) unsigned short As[BM][TB_LD];
+    __shared__ __attribute__((aligned(16))) unsigned short Bs[BN][TB_LD];
+    __shared__ uint32_t s_vtx[BM];
+    __shared__ float s_scale[BM];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const uint32_t count = *a.count_ptr;
+    const uint32_t n_tiles = (count + BM - 1) / BM;
+    const uint32_t n0 = blockIdx.y * BN;
+
+    for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint32_t row0 = tile * BM;
+        __syncthreads();
+        for (int r = tid; r < BM; r += 256) {
+            uint32_t slot = row0 + r;
+            uint32_t v = 0;
+            float sc = 1.0f;
+            if (slot < count) {
+                v = a.list[slot];
+                if (a.mean) {
+                    uint32_t deg = a.in_meta[v].y;
+                    sc = 1.0f / (float)(deg > 1u ? deg : 1u);
+                }
+            }
+            s_vtx[r] = v;
+            s_scale[r] = sc;
+        }
+        __syncthreads();
+
+        floatx16 acc[TM][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+        uint32_t my_v[NA], my_slot[NA];
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            const int r = (tid + i * 256) / (T_BK / 4);
+            my_v[i] = s_vtx[r];
+            my_slot[i] = min(row0 + r, count - 1u);
+        }
+        const uint32_t c4a = (tid % (T_BK / 4)) * 4;
+
+        floatx4 ra[STAGES][NA], rq[TWO ? STAGES : 1][TWO ? NA : 1];
+        uintx4 rb[NB];
+#pragma unroll
+        for (int st = 0; st < STAGES; ++st)
+#pragma unroll
+            for (int i = 0; i < NA; ++i) {
+                floatx4 q = (floatx4)(0.0f);
+                fetch_raw<MODE, STORE>(a, my_v[i], my_slot[i], (uint32_t)st * T_BK + c4a, ra[st][i], q);
+                if constexpr (TWO) rq[st][i] = q;
+            }
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int idx = tid + i * 256;
+            const int n = idx / 4, kc = (idx % 4) * 8;
+            rb[i] = *(const uintx4 *)(a.Wt + (size_t)(n0 + n) * a.wt_ld + kc);
+        }
+
+        for (uint32_t k0 = 0; k0 < a.Kpad; k0 += T_BK) {
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < NA; ++i) {
+                const int r = (tid + i * 256) / (T_BK / 4);
+                floatx4 q = (floatx4)(0.0f);
+                if constexpr (TWO) q = rq[0][i];
+                const floatx4 val = finish_raw<MODE, STORE>(a, ra[0][i], q, k0 + c4a, s_scale[r]);
+                uint2 pk;
+                pk.x = pack_bf16x2(val.x, val.y);
+                pk.y = pack_bf16x2(val.z, val.w);
+                *(uint2 *)&As[r][c4a] = pk;
+            }
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {
+                const int idx = tid + i * 256;
+                const int n = idx / 4, kc = (idx % 4) * 8;
+                *(uintx4 *)&Bs[n][kc] = rb[i];
+            }
+            __syncthreads();
+#pragma unroll
+            for (int st = 0; st + 1 < STAGES; ++st)
+#pragma unroll
+                for (int i = 0; i < NA; ++i) {
+                    ra[st][i] = ra[st + 1][i];
+                    if constexpr (TWO) rq[st][i] = rq[st + 1][i];
+                }
+            {
+                const uint32_t kb = min(k0 + T_BK, a.Kpad - T_BK);
+#pragma unroll
+                for (int i = 0; i < NB; ++i) {
+                    const int idx = tid + i * 256;
+                    const int n = idx / 4, kc = (idx % 4) * 8;
+                    rb[i] = *(const uintx4 *)(a.Wt + (size_t)(n0 + n) * a.wt_ld + kb + kc);
+                }
+            }
+            {
+                const uint32_t kn = k0 + STAGES * T_BK + c4a;
+#pragma unroll
+                for (int i = 0; i < NA; ++i) {
+                    floatx4 q = (floatx4)(0.0f);
+                    fetch_raw<MODE, STORE>(a, my_v[i], my_slot[i], kn, ra[STAGES - 1][i], q);
+                    if constexpr (TWO) rq[STAGES - 1][i] = q;
+                }
+            }
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh) {
+                const int ko = kh * 16 + (lane >> 5) * 8;
+                bf16x8 av[TM], bv[TN];
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+                    av[i] = __builtin_bit_cast(bf16x8, *(const uintx4 *)&As[(wm * TM + i) * 32 + (lane & 31)][ko]);
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    bv[j] = __builtin_bit_cast(bf16x8, *(const uintx4 *)&Bs[(wn * TN + j) * 32 + (lane & 31)][ko]);
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
+            }
+        }
+        epilogue<TM, TN>(a, acc, s_vtx, s_scale, row0, count, n0, wm, wn, lane);
+    }
+}
+
+template <int MODE>
+static void launch_bf16(ripple_ctx *c, const TArgs &a) {
+    const uint32_t gx = c->n_cu * 2;
+    if (a.Npad >= 256) {
+        hipLaunchKernelGGL((k_transform_bf16<1, 4, 2, 2, 3, MODE>), dim3(gx, a.Npad / 256), dim3(256), 0, c->stream, a);
+    } else if (a.Npad == 128) {
+        hipLaunchKernelGGL((k_transform_bf16<2, 2, 2, 2, 3, MODE>), dim3(gx, 1), dim3(256), 0, c->stream, a);
+    } else {
+        hipLaunchKernelGGL((k_transform_bf16<4, 1, 1, 2, 3, MODE>), dim3(gx, 1), dim3(256), 0, c->stream, a);
+    }
+}
+
 template <int MODE, int STORE>
 static void launch_fast(ripple_ctx *c, const TArgs &a) {
     const uint32_t gx = c->n_cu * 2;
@@ -458,7 +623,8 @@ static void launch_t(ripple_ctx *c, const TArgs &a, bool vec_ok) {
     }
 #define T_CASE(M)                                            \
     case M:                                                  \
-        if (a.store) launch_fast<M, 1>(c, a);                \
+        if (a.store && a.Wt) launch_bf16<M>(c, a);           \
+        else if (a.store) launch_fast<M, 1>(c, a);           \
         else launch_fast<M, 0>(c, a);                        \
         break;
     switch (a.a_mode) {
@@ -496,6 +662,8 @@ static TArgs base_args(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
     a.out_mode = 1;
     a.act = 0;
     a.W = ly.W0;
+    a.Wt = (c->store && c->opt_bf16_mfma) ? ly.W0h : nullptr;   // bf16 storage: bf16 matrix cores
+    a.wt_ld = ly.K0pad;
     a.bias = ly.b0;
     a.K = ly.K;
     a.Kpad = ly.K0pad;
@@ -512,6 +680,7 @@ void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
     TArgs a = base_args(c, l, list, count_d);
     a.mean = 0;
     a.W = ly.Wn;
+    a.Wt = nullptr;                                // deltas of bf16 values need more than 8 mantissa bits: fp32 path
     a.bias = ly.bzero;
     a.K = ly.d_in;
     a.Kpad = rp_round_up(ly.d_in, 32);
@@ -573,6 +742,7 @@ void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const 
     s2.tmp_ld = ly.d_hidden;
     s2.mean = 0;
     s2.W = ly.W1;
+    s2.Wt = nullptr;
     s2.bias = ly.b1;
     s2.K = ly.d_hidden;
     s2.Kpad = ly.K1pad;

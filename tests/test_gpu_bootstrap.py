@@ -36,11 +36,19 @@ def test_bootstrap_wide_layers_span_several_tiles():
         pair.close()
 
 
-def test_bootstrap_bf16_store():
-    print("case bf16", flush=True)
-    pair, _ = make_pair(n=700, e=5000, d0=16, kind="gcn_sum", widths=(16, 64, 24), store="bf16", seed=4)
+@pytest.mark.parametrize("kind,widths", [("gcn_sum", (16, 64, 24)), ("sage_mean", (100, 256, 300, 47)),
+                                         ("gin_sum", (16, 32, 12)), ("gcn_mean", (24, 128, 40))])
+def test_bootstrap_bf16_store(kind, widths):
+    """bfloat16 embeddings: bf16 matrix cores (default) and the fp32 matrix path on the same
+    rounded inputs must both stay within the bf16 tolerance of the fp64 oracle."""
+    print("case bf16", kind, flush=True)
+    pair, _ = make_pair(n=900, e=7000, d0=widths[0], kind=kind, widths=widths, store="bf16", seed=4)
     try:
-        pair.check_embeddings()
+        errs_mfma, want = pair.check_embeddings()
+        rp.ripple_set_option(pair.ctx, rp.OPT_BF16_MFMA, 0)
+        rp.ripple_full_infer(pair.ctx)
+        errs_f32, _ = pair.check_embeddings(want=want)
+        print("  max rel err bf16 mfma", ["%.1e" % e for e in errs_mfma], "fp32 path", ["%.1e" % e for e in errs_f32], flush=True)
     finally:
         pair.close()
 
