@@ -59,6 +59,11 @@ struct TArgs {
 __device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {     // round to nearest even
+    const __hip_bfloat16 a = __float2bfloat16(lo), b = __float2bfloat16(hi);
+    return (uint32_t)__builtin_bit_cast(unsigned short, a) | ((uint32_t)__builtin_bit_cast(unsigned short, b) << 16);
+}
+
 // Raw 16 (or 8) bytes for four consecutive k of one gathered row; no arithmetic on the data.
 // MODE 1 with bf16 embeddings and MODE 2 need two sources (p: own embedding, q: aggregate).
 template <int MODE, int STORE>
@@ -187,6 +192,132 @@ __device__ __forceinline__ void epilogue(const TArgs &a, floatx16 (&acc)[TM][TN]
     }
 }
 
+// Epilogue of the pipelined kernels: the accumulators are first laid out row-major in LDS (over the
+// A/B staging area, which is free by then), so that every thread handles four consecutive columns
+// of a row: 16-byte loads and stores when the row width is a multiple of four, element-wise
+// otherwise. Reads (old row, projected aggregate) of four such groups are issued before any store.
+__device__ __forceinline__ floatx4 ld4(const float *p, bool vec, uint32_t n_valid) {
+    if (vec) return *(const floatx4 *)p;
+    floatx4 r = (floatx4)(0.0f);
+    if (n_valid > 0) r.x = p[0];
+    if (n_valid > 1) r.y = p[1];
+    if (n_valid > 2) r.z = p[2];
+    if (n_valid > 3) r.w = p[3];
+    return r;
+}
+__device__ __forceinline__ void st4(float *p, floatx4 v, bool vec, uint32_t n_valid) {
+    if (vec) {
+        *(floatx4 *)p = v;
+        return;
+    }
+    if (n_valid > 0) p[0] = v.x;
+    if (n_valid > 1) p[1] = v.y;
+    if (n_valid > 2) p[2] = v.z;
+    if (n_valid > 3) p[3] = v.w;
+}
+__device__ __forceinline__ floatx4 ld4_bf16(const __hip_bfloat16 *p, bool vec, uint32_t n_valid) {
+    floatx4 r = (floatx4)(0.0f);
+    if (vec) {
+        const uint2 w = *(const uint2 *)p;
+        r.x = bf_lo(w.x);
+        r.y = bf_hi(w.x);
+        r.z = bf_lo(w.y);
+        r.w = bf_hi(w.y);
+        return r;
+    }
+    if (n_valid > 0) r.x = __bfloat162float(p[0]);
+    if (n_valid > 1) r.y = __bfloat162float(p[1]);
+    if (n_valid > 2) r.z = __bfloat162float(p[2]);
+    if (n_valid > 3) r.w = __bfloat162float(p[3]);
+    return r;
+}
+
+template <int TM, int TN, int BM, int BN>
+__device__ __forceinline__ void epilogue_staged(const TArgs &a, floatx16 (&acc)[TM][TN], float *Cs, const uint32_t *s_vtx,
+                                                const float *s_scale, uint32_t row0, uint32_t count, uint32_t n0, int wm,
+                                                int wn, int tid) {
+    constexpr int C_LD = BN + 4;
+    const int lane = tid & 63;
+    const bool vec = (a.N & 3u) == 0 && (a.out_mode == 1 || (a.tmp_out_ld & 3u) == 0);
+    __syncthreads();                                       // every wavefront is done with the A/B slices
+#pragma unroll
+    for (int sm = 0; sm < TM; ++sm)
+#pragma unroll
+        for (int sn = 0; sn < TN; ++sn)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int lr = (wm * TM + sm) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+                Cs[lr * C_LD + (wn * TN + sn) * 32 + (lane & 31)] = acc[sm][sn][r];
+            }
+    __syncthreads();
+    constexpr int ITER = BM * BN / 4 / 256, U = 4;
+    static_assert(ITER % U == 0, "tile size");
+#pragma unroll 1
+    for (int it0 = 0; it0 < ITER; it0 += U) {
+        floatx4 z[U], old[U], add[U];
+        uint32_t nv[U];                                    // valid columns of the group (0: nothing to do)
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int idx = tid + (it0 + u) * 256;
+            const int r = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
+            const uint32_t col = n0 + c4;
+            nv[u] = (row0 + r < count && col < a.N) ? min(4u, a.N - col) : 0u;
+            z[u] = *(const floatx4 *)&Cs[r * C_LD + c4];
+            old[u] = (floatx4)(0.0f);
+            add[u] = (floatx4)(0.0f);
+            if (nv[u]) {
+                const size_t hidx = (size_t)s_vtx[r] * a.N + col;
+                if (a.out_mode == 1)
+                    old[u] = a.store ? ld4_bf16((const __hip_bfloat16 *)a.Hout + hidx, vec, nv[u])
+                                     : ld4((const float *)a.Hout + hidx, vec, nv[u]);
+                if (a.addend) add[u] = ld4(a.addend + hidx, vec, nv[u]) * s_scale[r];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (!nv[u]) continue;
+            const int idx = tid + (it0 + u) * 256;
+            const int r = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
+            const uint32_t col = n0 + c4, slot = row0 + r;
+            floatx4 v = z[u] + *(const floatx4 *)(a.bias + col) + add[u];     // bias is padded: always 16-byte readable
+            if (a.act == RIPPLE_ACT_RELU) {
+                v.x = v.x > 0.0f ? v.x : 0.0f;
+                v.y = v.y > 0.0f ? v.y : 0.0f;
+                v.z = v.z > 0.0f ? v.z : 0.0f;
+                v.w = v.w > 0.0f ? v.w : 0.0f;
+            }
+            if (a.out_mode == 0) {
+                st4(a.tmp_out + (size_t)slot * a.tmp_out_ld + col, v, vec, nv[u]);
+            } else if (a.out_mode == 2) {
+                st4(a.tmp_out + (size_t)s_vtx[r] * a.tmp_out_ld + col, v, vec, nv[u]);
+            } else {
+                const size_t hidx = (size_t)s_vtx[r] * a.N + col;
+                if (a.store) {
+                    uint2 w;
+                    w.x = pack_bf16x2(v.x, v.y);
+                    w.y = pack_bf16x2(v.z, v.w);
+                    unsigned short *hp = (unsigned short *)a.Hout + hidx;
+                    if (vec) {
+                        *(uint2 *)hp = w;
+                    } else {
+                        if (nv[u] > 0) hp[0] = (unsigned short)(w.x & 0xFFFFu);
+                        if (nv[u] > 1) hp[1] = (unsigned short)(w.x >> 16);
+                        if (nv[u] > 2) hp[2] = (unsigned short)(w.y & 0xFFFFu);
+                        if (nv[u] > 3) hp[3] = (unsigned short)(w.y >> 16);
+                    }
+                    v.x = bf_lo(w.x);
+                    v.y = bf_hi(w.x);
+                    v.z = bf_lo(w.y);
+                    v.w = bf_hi(w.y);
+                } else {
+                    st4((float *)a.Hout + hidx, v, vec, nv[u]);
+                }
+                if (a.D) st4(a.D + (size_t)slot * a.N + col, v - old[u], vec, nv[u]);
+            }
+        }
+    }
+}
+
 // GraphConv handled project-first has no matrix product left per row: h = act(Y[v] * scale + b).
 __global__ void k_transform_addend_only(TArgs a) {
     const uint32_t count = *a.count_ptr;
@@ -223,8 +354,12 @@ __global__ __launch_bounds__(256) void k_transform_f32(TArgs a) {
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
     constexpr int NA = BM / 32, NB = BN / 32;              // float4 per thread per slice (A, B)
     constexpr bool TWO = (MODE == 2) || (MODE == 1 && STORE == 1);
-    __shared__ float As[BM][T_BK + 1];
-    __shared__ float Bs[T_BK][BN];
+    constexpr int A_BYTES = BM * (T_BK + 1) * 4, B_BYTES = T_BK * BN * 4, C_BYTES = BM * (BN + 4) * 4;
+    constexpr int S_BYTES = (A_BYTES + B_BYTES > C_BYTES) ? A_BYTES + B_BYTES : C_BYTES;
+    static_assert(A_BYTES % 16 == 0, "alignment of the weight slice");
+    __shared__ __attribute__((aligned(16))) char smem[S_BYTES];   // A and B slices; reused by the staged epilogue
+    float (*As)[T_BK + 1] = (float (*)[T_BK + 1]) smem;
+    float (*Bs)[BN] = (float (*)[BN])(smem + A_BYTES);
     __shared__ uint32_t s_vtx[BM];
     __shared__ float s_scale[BM];
 
@@ -349,7 +484,7 @@ __global__ __launch_bounds__(256) void k_transform_f32(TArgs a) {
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
             }
         }
-        epilogue<TM, TN>(a, acc, s_vtx, s_scale, row0, count, n0, wm, wn, lane);
+        epilogue_staged<TM, TN, BM, BN>(a, acc, (float *)smem, s_vtx, s_scale, row0, count, n0, wm, wn, tid);
     }
 }
 
@@ -448,19 +583,18 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 #define TB_LD 40                                            // LDS row stride in bf16 (80 bytes)
 
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
-    const __hip_bfloat16 a = __float2bfloat16(lo), b = __float2bfloat16(hi);
-    return (uint32_t)__builtin_bit_cast(unsigned short, a) | ((uint32_t)__builtin_bit_cast(unsigned short, b) << 16);
-}
-
 template <int WAVES_M, int WAVES_N, int TM, int TN, int STAGES, int MODE>
 __global__ __launch_bounds__(256) void k_transform_bf16(TArgs a) {
     constexpr int STORE = 1;
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
     constexpr int NA = BM / 32, NB = BN / 64;              // per thread per slice: float4 of A, 16-byte chunks of B
     constexpr bool TWO = (MODE == 2) || (MODE == 1);
-    __shared__ __attribute__((aligned(16))) unsigned short As[BM][TB_LD];
-    __shared__ __attribute__((aligned(16))) unsigned short Bs[BN][TB_LD];
+    constexpr int A_BYTES = BM * TB_LD * 2, B_BYTES = BN * TB_LD * 2, C_BYTES = BM * (BN + 4) * 4;
+    constexpr int S_BYTES = (A_BYTES + B_BYTES > C_BYTES) ? A_BYTES + B_BYTES : C_BYTES;
+    static_assert(A_BYTES % 16 == 0, "alignment of the weight slice");
+    __shared__ __attribute__((aligned(16))) char smem[S_BYTES];   // A and B slices; reused by the staged epilogue
+    unsigned short (*As)[TB_LD] = (unsigned short (*)[TB_LD]) smem;
+    unsigned short (*Bs)[TB_LD] = (unsigned short (*)[TB_LD])(smem + A_BYTES);
     __shared__ uint32_t s_vtx[BM];
     __shared__ float s_scale[BM];
 
@@ -585,7 +719,7 @@ __global__ __launch_bounds__(256) void k_transform_bf16(TArgs a) {
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
             }
         }
-        epilogue<TM, TN>(a, acc, s_vtx, s_scale, row0, count, n0, wm, wn, lane);
+        epilogue_staged<TM, TN, BM, BN>(a, acc, (float *)smem, s_vtx, s_scale, row0, count, n0, wm, wn, tid);
     }
 }
 
