@@ -50,7 +50,9 @@ def algorithmic_work(st, model, widths, store, L, layer_info):
         d_prev, d_out = widths[l - 1], widths[l]
         w_agg, projected = layer_info[l]
         a_prev, a_l, m_l, t_l = st.rows[l - 1], st.rows[l], st.msgs[l], st.touched[l]
-        out[("scatter", l)] = dict(bytes=a_prev * w_agg * 4 + 8 * a_prev + 4 * m_l + 2 * t_l * w_agg * 4, flops=m_l * w_agg)
+        out[("scatter", l)] = dict(bytes=a_prev * w_agg * 4 + 8 * a_prev + 4 * m_l + 2 * t_l * w_agg * 4, flops=m_l * w_agg,
+                                   # what a cache-less per-message scheme moves: one message row gathered per message
+                                   msg_bytes=m_l * (w_agg * 4 + 4) + 2 * t_l * w_agg * 4)
         out[("frontier", l)] = dict(bytes=8 * a_prev + 4 * m_l + 4 * a_l, flops=0)
         self_w = lay["d_in"] if lay["self"] != "none" else 0
         out_bytes = d_out * s_h * 2 + (d_out * 4 if l < L else 0) + 4
@@ -200,6 +202,9 @@ def main():
             continue
         ent = {"ms_per_launch": ms / n_launch, "launches": int(n_launch),
                "GBps": w["bytes"] / (ms * 1e-3) / 1e9, "hbm_frac": w["bytes"] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+        if ph == "scatter":
+            ent["per_message_GBps"] = w["msg_bytes"] / (ms * 1e-3) / 1e9
+            ent["per_message_hbm_frac"] = ent["per_message_GBps"] / HBM_PEAK_GBS
         if ph == "transform":
             ent["TFLOPs"] = w["flops"] / (ms * 1e-3) / 1e12
             ent["mfma_frac"] = ent["TFLOPs"] / mfma_peak

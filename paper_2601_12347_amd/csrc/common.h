@@ -172,14 +172,23 @@ __device__ __forceinline__ uint32_t rp_row_cap(uint32_t need) {   // capacity gi
     uint32_t c = need + (need >> 1) + 4u;
     return (c + 3u) & ~3u;
 }
-// position of `target` in row[0..len), searched by one wavefront; -1 when absent
+// position of `target` in row[0..len), searched by one wavefront; -1 when absent.
+// Four 64-entry blocks are loaded per round so that long (hub) rows are not paced by one
+// memory round trip per 64 entries.
 __device__ __forceinline__ int rp_wave_find(const uint32_t *row, uint32_t len, uint32_t target) {
     const int lane = rp_lane();
-    for (uint32_t base = 0; base < len; base += 64) {
-        uint32_t i = base + lane;
-        bool hit = (i < len) && (row[i] == target);
-        unsigned long long m = __ballot(hit);
-        if (m) return (int)(base + __ffsll((long long)m) - 1);
+    for (uint32_t base = 0; base < len; base += 256) {
+        uint32_t v[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const uint32_t i = base + 64 * t + lane;
+            v[t] = (i < len) ? row[i] : RP_TOMB;            // a tombstone never equals a vertex id
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const unsigned long long m = __ballot(v[t] == target);
+            if (m) return (int)(base + 64 * t + __ffsll((long long)m) - 1);
+        }
     }
     return -1;
 }
