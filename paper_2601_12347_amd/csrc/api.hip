@@ -463,7 +463,7 @@ struct TouchTable {
 
 struct SubBatch {
     uint32_t begin, end;
-    bool has_vdel, has_vertex_or_feat;
+    bool has_vadd, has_vdel, has_vertex_or_feat;
 };
 
 // Cut the batch where an operation depends on an earlier one of the same piece, so that every
@@ -472,7 +472,7 @@ static void split_batch(const ripple_update *ops, uint32_t n, TouchTable &tt, st
     out.clear();
     tt.reserve((size_t)n * 3 + 16);
     tt.next_generation();
-    SubBatch cur{0, 0, false, false};
+    SubBatch cur{0, 0, false, false, false};
     const uint64_t VKEY = 0x8000000000000000ull;
     for (uint32_t i = 0; i < n; ++i) {
         const ripple_update &op = ops[i];
@@ -501,10 +501,11 @@ static void split_batch(const ripple_update *ops, uint32_t n, TouchTable &tt, st
             if (!conflict) break;
             cur.end = i;                       // close the piece before this operation and start afresh
             out.push_back(cur);
-            cur = SubBatch{i, i, false, false};
+            cur = SubBatch{i, i, false, false, false};
             tt.next_generation();
         }
         if (op.kind == RIPPLE_VERTEX_DEL) cur.has_vdel = true;
+        if (op.kind == RIPPLE_VERTEX_ADD) cur.has_vadd = true;
         if (op.kind >= RIPPLE_VERTEX_ADD) cur.has_vertex_or_feat = true;
     }
     cur.end = n;
@@ -568,15 +569,17 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
     const uint32_t n = sb.end - sb.begin;
     int t = rp_timer_begin(c);
     rp_launch_batch_reset(c);
-    rp_launch_mutate(c, n, sb.has_vdel, sb.has_vertex_or_feat);
+    rp_launch_mutate(c, n, sb.has_vadd, sb.has_vdel, sb.has_vertex_or_feat);
     rp_launch_list_eoff(c, 0);
     rp_timer_end(c, t, RIPPLE_PH_INGEST, 0);
     if (multi)
         hipLaunchKernelGGL(k_or_words, dim3(rp_div_up(c->n_words, 256)), dim3(256), 0, c->stream, c->rep[0], c->bm[0],
                            c->n_words);
     for (uint32_t l = 1; l <= c->L; ++l) {
-        // hop 1 always pushes: hop-0 rows are in operation order, not ranked by vertex id
-        const bool may_pull = l >= 2 && c->opt_scatter != 1;
+        // hop 1 always pushes: hop-0 rows are in operation order, not ranked by vertex id. Where the
+        // previous batch pushed with a wide margin the pull kernel is not even enqueued (pushing is
+        // always correct; the prediction only saves a launch).
+        const bool may_pull = l >= 2 && c->opt_scatter != 1 && !(c->opt_scatter == 0 && c->push_margin[l]);
         t = rp_timer_begin(c);
         rp_launch_frontier_mark(c, l);
         rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
@@ -708,6 +711,9 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
         for (uint32_t l = 1; l <= c->L; ++l) {
             msgs[l] += h.m[l];
             tchd[l] += h.touched[l];
+            // pull wins when m * row_bytes * ratio >= 8 * in-edges; remember if push won by a factor of 16
+            const unsigned long long lhs = (unsigned long long)h.m[l] * c->xw[l] * 4ull * (unsigned)c->opt_pull_ratio * 16ull;
+            c->push_margin[l] = lhs < 8ull * h.isum[l];
         }
         if (!multi)
             for (uint32_t l = 0; l <= c->L; ++l) c->last_a[l] = h.a[l];

@@ -38,9 +38,11 @@ struct DevCtr {                      // device-resident counters, one instance p
     uint32_t out_top, in_top;                 // first free pool entry
     uint32_t n_alive;
     uint32_t n_vadd;
-    uint32_t abort_flag;                      // written by k_decide: 0 ok, bit0 pool, bit1 edges, bit2 scratch
+    uint32_t abort_flag;                      // written by k_capacity's last workgroup: 0 ok, bit0 pool, bit1 edges, bit2 scratch
     uint32_t pad0;
     unsigned long long n_edges;
+    uint32_t blocks_done;                     // workgroups of k_capacity that have finished (0 between launches)
+    uint32_t pad2;
     uint32_t error;                           // sticky consistency error seen by a kernel
     uint32_t pad1;
 };
@@ -131,6 +133,7 @@ struct ripple_ctx {
     // last batch's sets (reporting)
     uint32_t last_a[RIPPLE_MAX_LAYERS + 1] = {0};
     bool last_from_rep = false;
+    bool push_margin[RIPPLE_MAX_LAYERS + 1] = {false};  // last batch pushed at this hop by a wide margin
 
     // options
     int opt_timing = 0;

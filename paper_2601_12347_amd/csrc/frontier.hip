@@ -201,6 +201,109 @@ __global__ __launch_bounds__(256) void k_frontier_emit(CompactArgs a) {
     }
 }
 
+// Both passes in one workgroup, for bitmaps of at most SMALL_WORDS words (small graphs: saves
+// two launches per hop, which is most of the hop's time when batches are small).
+#define SMALL_WPT 8
+#define SMALL_WORDS (1024 * SMALL_WPT)
+__global__ __launch_bounds__(1024) void k_frontier_compact_small(CompactArgs a) {
+    __shared__ uint32_t wc[16], wo[16], wi[16], wt[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const uint32_t wpt = (a.n_words + 1023u) / 1024u;      // consecutive words per thread (<= SMALL_WPT)
+    const uint32_t w0 = tid * wpt;
+    uint32_t words[SMALL_WPT];
+    uint32_t cnt = 0, dout = 0, din = 0, tch = 0;
+#pragma unroll
+    for (int k = 0; k < SMALL_WPT; ++k) {
+        words[k] = 0;
+        const uint32_t idx = w0 + k;
+        if ((uint32_t)k < wpt && idx < a.n_words) {
+            const uint32_t live = a.alive[idx];
+            uint32_t w = a.bm[idx] & live;
+            tch += __popc(w);
+            if (a.bm_sink) w |= (a.bm_sink[idx] | a.bm_vadd[idx]) & live;
+            if (a.bm_prev) w |= a.bm_prev[idx] & live;
+            a.bm[idx] = w;
+            if (a.rep && w) a.rep[idx] |= w;
+            words[k] = w;
+            cnt += __popc(w);
+            uint32_t d_o, d_i;
+            word_degrees(a, idx, w, d_o, d_i);
+            dout += d_o;
+            din += d_i;
+        }
+    }
+    uint32_t ic = cnt, io = dout, ii = din, it = tch;
+    for (int o = 1; o < 64; o <<= 1) {
+        uint32_t tc = __shfl_up(ic, o), to = __shfl_up(io, o), ti = __shfl_up(ii, o);
+        if (lane >= o) {
+            ic += tc;
+            io += to;
+            ii += ti;
+        }
+    }
+    for (int o = 32; o > 0; o >>= 1) it += __shfl_down(it, o);
+    if (lane == 63) {
+        wc[wave] = ic;
+        wo[wave] = io;
+        wi[wave] = ii;
+    }
+    if (lane == 0) wt[wave] = it;
+    __syncthreads();
+    uint32_t oc = ic - cnt, oo = io - dout, oi = ii - din;
+    for (int k = 0; k < wave; ++k) {
+        oc += wc[k];
+        oo += wo[k];
+        oi += wi[k];
+    }
+#pragma unroll
+    for (int k = 0; k < SMALL_WPT; ++k) {
+        const uint32_t idx = w0 + k;
+        if ((uint32_t)k < wpt && idx < a.n_words) {
+            if (a.wrank) a.wrank[idx] = oc;
+            uint32_t t = words[k];
+            while (t) {
+                const uint32_t v = idx * 32 + (__ffs(t) - 1);
+                t &= t - 1;
+                a.list[oc] = v;
+                if (a.want_out) {
+                    a.eoff[oc] = oo;
+                    oo += a.out_meta[v].y;
+                }
+                if (a.want_in) {
+                    a.ioff[oc] = oi;
+                    oi += a.in_meta[v].y;
+                }
+                ++oc;
+            }
+        }
+    }
+    if (tid == 1023) {                                     // the last thread ends on the grand totals
+        *a.count_out = oc;
+        if (a.want_out) {
+            a.eoff[oc] = oo;
+            if (a.msgs_out) *a.msgs_out = oo;
+        }
+        if (a.want_in) {
+            a.ioff[oc] = oi;
+            if (a.isum_out) *a.isum_out = oi;
+        }
+    }
+    if (tid == 0 && a.touched_out) {
+        uint32_t t = 0;
+        for (int k = 0; k < 16; ++k) t += wt[k];
+        if (t) atomicAdd(a.touched_out, t);
+    }
+}
+
+static void launch_compact(ripple_ctx *c, const CompactArgs &a) {
+    if (a.n_words <= SMALL_WORDS) {
+        hipLaunchKernelGGL(k_frontier_compact_small, dim3(1), dim3(1024), 0, c->stream, a);
+        return;
+    }
+    uint32_t nb = rp_div_up(a.n_words, 256);
+    launch_compact(c, a);
+}
+
 // out-degree prefix over an arbitrary (unsorted) list, one workgroup; used for hop 0
 __global__ __launch_bounds__(1024) void k_list_eoff(const uint32_t *list, const uint32_t *count_ptr,
                                                     const uint2 *out_meta, uint32_t *eoff, uint32_t *msgs_out) {
@@ -242,7 +345,6 @@ void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l) {
 // want_out: eoff[l] and ctr->m[l+1] (the next hop's edge walk); want_in: ioff[l], ctr->isum[l], wrank[l]
 void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool want_out, bool want_in,
                                 bool accumulate_rep) {
-    uint32_t nb = rp_div_up(c->n_words, 256);
     CompactArgs a;
     a.bm = c->bm[l];
     a.bm_prev = self_term ? c->bm[l - 1] : nullptr;
@@ -266,13 +368,11 @@ void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool 
     a.count_out = &c->ctr->a[l];
     a.msgs_out = (l < RIPPLE_MAX_LAYERS) ? &c->ctr->m[l + 1] : nullptr;
     a.isum_out = &c->ctr->isum[l];
-    hipLaunchKernelGGL(k_frontier_count, dim3(nb), dim3(256), 0, c->stream, a);
-    hipLaunchKernelGGL(k_frontier_emit, dim3(nb), dim3(256), 0, c->stream, a);
+    launch_compact(c, a);
 }
 
 // any bitmap & alive -> ascending list in `out_list`, count in *count_d (device)
 void rp_launch_bitmap_to_list(ripple_ctx *c, uint32_t *bitmap, uint32_t *out_list, uint32_t *count_d) {
-    uint32_t nb = rp_div_up(c->n_words, 256);
     CompactArgs a;
     memset(&a, 0, sizeof(a));
     a.bm = bitmap;
@@ -285,8 +385,7 @@ void rp_launch_bitmap_to_list(ripple_ctx *c, uint32_t *bitmap, uint32_t *out_lis
     a.part_in = c->part_ideg;
     a.list = out_list;
     a.count_out = count_d;
-    hipLaunchKernelGGL(k_frontier_count, dim3(nb), dim3(256), 0, c->stream, a);
-    hipLaunchKernelGGL(k_frontier_emit, dim3(nb), dim3(256), 0, c->stream, a);
+    launch_compact(c, a);
 }
 
 void rp_launch_list_eoff(ripple_ctx *c, uint32_t l) {

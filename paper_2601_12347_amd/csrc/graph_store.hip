@@ -300,10 +300,8 @@ __global__ void k_vertex_validate(MutArgs a) {
             atomicOr(&a.vstate[op.u], VS_DYING);
             atomicAdd(&a.ctr->need_exp, a.out_meta[op.u].y + a.in_meta[op.u].y);
         }
-    } else if (op.kind == RIPPLE_FEAT_UPDATE) {
-        st = rp_bit(a.alive, op.u) ? 1u : 0u;
     } else {
-        return;                                   // edge operations: k_edge_validate
+        return;                                   // edge operations and feature updates: k_edge_validate
     }
     a.status[i] = st;
 }
@@ -313,6 +311,10 @@ __global__ __launch_bounds__(256) void k_edge_validate(MutArgs a) {
     uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
     for (uint32_t i = gw; i < a.n_ops; i += nw) {
         ripple_update op = a.ops[i];
+        if (op.kind == RIPPLE_FEAT_UPDATE) {               // needs the live flag only
+            if (lane == 0) a.status[i] = rp_bit(a.alive, op.u) ? 1u : 0u;
+            continue;
+        }
         if (op.kind != RIPPLE_EDGE_ADD && op.kind != RIPPLE_EDGE_DEL) continue;
         uint32_t u = op.u, v = op.v;
         bool ok = (rp_bit(a.alive, u) || (a.vstate[u] & VS_ADDING)) &&
@@ -355,6 +357,8 @@ __global__ __launch_bounds__(256) void k_edge_validate(MutArgs a) {
     }
 }
 
+// How much pool space relocation will take, then (by the last workgroup to finish) the decision
+// whether the batch may be committed at all.
 __global__ void k_capacity(MutArgs a) {
     uint32_t j = blockIdx.x * blockDim.x + threadIdx.x;
     uint32_t no = min(a.ctr->n_touch_out, a.touch_cap), ni = min(a.ctr->n_touch_in, a.touch_cap);
@@ -367,14 +371,19 @@ __global__ void k_capacity(MutArgs a) {
         uint32_t need = a.in_meta[x].y - a.dead_in[x] + pend;
         if (pend && need > a.in_capv[x]) atomicAdd(&a.ctr->need_in, rp_row_cap(need));
     }
-}
-
-__global__ void k_decide(MutArgs a) {
-    if (blockIdx.x || threadIdx.x) return;
+    __shared__ bool last;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __threadfence();
+        last = atomicAdd(&a.ctr->blocks_done, 1u) == gridDim.x - 1;
+    }
+    __syncthreads();
+    if (!last || threadIdx.x != 0) return;
+    __threadfence();
     DevCtr *c = a.ctr;
+    const uint32_t need_out = atomicAdd(&c->need_out, 0u), need_in = atomicAdd(&c->need_in, 0u);
     uint32_t flag = 0;
-    if ((unsigned long long)c->out_top + c->need_out > a.pool_cap ||
-        (unsigned long long)c->in_top + c->need_in > a.pool_cap)
+    if ((unsigned long long)c->out_top + need_out > a.pool_cap || (unsigned long long)c->in_top + need_in > a.pool_cap)
         flag |= 1u;
     if (c->n_edges + c->n_add > a.e_cap + c->n_del) flag |= 2u;
     if (c->need_exp > a.exp_cap || (unsigned long long)c->n_add + c->n_del + c->need_exp > a.struct_cap ||
@@ -382,6 +391,7 @@ __global__ void k_decide(MutArgs a) {
         flag |= 4u;
     if (c->error) flag |= 8u;
     c->abort_flag = flag;
+    c->blocks_done = 0;
 }
 
 // slot in a global list for every lane with pred, one atomic per wavefront
@@ -681,10 +691,14 @@ __global__ __launch_bounds__(256) void k_struct_scatter(MutArgs a) {
                 for (uint32_t k0 = 0; k0 < dp; k0 += 64) {
                     const uint32_t kk = k0 + lane;
                     const float hv = (kk < dp) ? rp_load_h(a.H[l - 1], a.store, (size_t)u * dp + kk) : 0.0f;
-                    const uint32_t kn = min(64u, dp - k0);
-                    for (uint32_t j = 0; j < kn; ++j) {
-                        const float hk = __shfl(hv, (int)j);
-                        if (c < dn) sum += hk * W[(size_t)(k0 + j) * ld + c];
+                    // rows of W beyond dp exist (zero padding up to a multiple of 32) or meet hk = 0
+                    const uint32_t kn = min(64u, (dp - k0 + 7u) & ~7u);
+                    for (uint32_t j = 0; j < kn; j += 8) {        // eight independent weight loads in flight
+                        float w[8];
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) w[t] = (c < dn) ? W[(size_t)(k0 + j + t) * ld + c] : 0.0f;
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) sum += __shfl(hv, (int)(j + t)) * w[t];
                     }
                 }
                 if (c < dn && sum != 0.0f) unsafeAtomicAdd(&a.X[l][(size_t)v * dn + c], sg * sum);
@@ -776,18 +790,17 @@ void rp_launch_batch_reset(ripple_ctx *c) {
 }
 
 // Enqueue the whole Apply step for the n_ops operations staged in ops_d / payload_d.
-void rp_launch_mutate(ripple_ctx *c, uint32_t n_ops, bool has_vertex_del, bool has_vertex_or_feat) {
+void rp_launch_mutate(ripple_ctx *c, uint32_t n_ops, bool has_vertex_add, bool has_vertex_del, bool has_vertex_or_feat) {
     if (n_ops == 0) return;
     hipStream_t s = c->stream;
     MutArgs a = make_args(c, n_ops);
     uint32_t tb = rp_div_up(n_ops, 256);                              // thread per op
     uint32_t wb = std::min<uint32_t>(rp_div_up(n_ops, 4), c->n_cu * 8);  // wavefront per op
     uint32_t big = c->n_cu * 8;
-    hipLaunchKernelGGL(k_vertex_validate, dim3(tb), dim3(256), 0, s, a);
+    if (has_vertex_add || has_vertex_del) hipLaunchKernelGGL(k_vertex_validate, dim3(tb), dim3(256), 0, s, a);
     hipLaunchKernelGGL(k_edge_validate, dim3(wb), dim3(256), 0, s, a);
     uint32_t touch_threads = 2 * n_ops;                               // validation touches <= n_ops rows per side
     hipLaunchKernelGGL(k_capacity, dim3(rp_div_up(touch_threads, 256)), dim3(256), 0, s, a);
-    hipLaunchKernelGGL(k_decide, dim3(1), dim3(64), 0, s, a);
     if (has_vertex_del) {
         hipLaunchKernelGGL(k_expand_vdel, dim3(wb), dim3(256), 0, s, a);
         hipLaunchKernelGGL(k_expand_apply, dim3(big), dim3(256), 0, s, a);

@@ -10,7 +10,7 @@ ripple_status rp_build_graph(ripple_ctx *c, uint32_t n_vertices, uint64_t n_edge
                              const uint32_t *dst_h);
 ripple_status rp_compact(ripple_ctx *c);
 void rp_launch_batch_reset(ripple_ctx *c);
-void rp_launch_mutate(ripple_ctx *c, uint32_t n_ops, bool has_vertex_del, bool has_vertex_or_feat);
+void rp_launch_mutate(ripple_ctx *c, uint32_t n_ops, bool has_vertex_add, bool has_vertex_del, bool has_vertex_or_feat);
 
 // frontier.hip
 void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l);

@@ -723,31 +723,36 @@ __global__ __launch_bounds__(256) void k_transform_bf16(TArgs a) {
     }
 }
 
+// narrow: few rows expected. One workgroup then covers 128 rows x 64 columns and the columns are
+// spread over blockIdx.y, which shortens the serial chain of matrix-core work per tile fourfold.
 template <int MODE>
-static void launch_bf16(ripple_ctx *c, const TArgs &a) {
+static void launch_bf16(ripple_ctx *c, const TArgs &a, bool narrow) {
     const uint32_t gx = c->n_cu * 2;
-    if (a.Npad >= 256) {
+    if (a.Npad >= 256 && !narrow) {
         hipLaunchKernelGGL((k_transform_bf16<1, 4, 2, 2, 3, MODE>), dim3(gx, a.Npad / 256), dim3(256), 0, c->stream, a);
-    } else if (a.Npad == 128) {
+    } else if (a.Npad == 128 && !narrow) {
         hipLaunchKernelGGL((k_transform_bf16<2, 2, 2, 2, 3, MODE>), dim3(gx, 1), dim3(256), 0, c->stream, a);
     } else {
-        hipLaunchKernelGGL((k_transform_bf16<4, 1, 1, 2, 3, MODE>), dim3(gx, 1), dim3(256), 0, c->stream, a);
+        hipLaunchKernelGGL((k_transform_bf16<4, 1, 1, 2, 3, MODE>), dim3(narrow ? c->n_cu : gx, a.Npad / 64), dim3(256), 0,
+                           c->stream, a);
     }
 }
 
 template <int MODE, int STORE>
-static void launch_fast(ripple_ctx *c, const TArgs &a) {
+static void launch_fast(ripple_ctx *c, const TArgs &a, bool narrow) {
     const uint32_t gx = c->n_cu * 2;
-    if (a.Npad >= 256) {
+    if (a.Npad >= 256 && !narrow) {
         hipLaunchKernelGGL((k_transform_f32<1, 4, 2, 2, 3, MODE, STORE>), dim3(gx, a.Npad / 256), dim3(256), 0, c->stream, a);
-    } else if (a.Npad == 128) {
+    } else if (a.Npad == 128 && !narrow) {
         hipLaunchKernelGGL((k_transform_f32<2, 2, 2, 2, 3, MODE, STORE>), dim3(gx, 1), dim3(256), 0, c->stream, a);
     } else {
-        hipLaunchKernelGGL((k_transform_f32<4, 1, 1, 2, 3, MODE, STORE>), dim3(gx, 1), dim3(256), 0, c->stream, a);
+        hipLaunchKernelGGL((k_transform_f32<4, 1, 1, 2, 3, MODE, STORE>), dim3(narrow ? c->n_cu : gx, a.Npad / 64), dim3(256), 0,
+                           c->stream, a);
     }
 }
 
-static void launch_t(ripple_ctx *c, const TArgs &a, bool vec_ok) {
+static void launch_t(ripple_ctx *c, const TArgs &a, bool vec_ok, uint32_t rows_hint) {
+    const bool narrow = rows_hint < 64u * c->n_cu;
     const uint32_t gx = c->n_cu * 2;
     if (!vec_ok || a.K < 4) {
         if (a.Npad >= 256) hipLaunchKernelGGL((k_transform_generic<1, 4>), dim3(gx, a.Npad / 256), dim3(256), 0, c->stream, a);
@@ -757,9 +762,9 @@ static void launch_t(ripple_ctx *c, const TArgs &a, bool vec_ok) {
     }
 #define T_CASE(M)                                            \
     case M:                                                  \
-        if (a.store && a.Wt) launch_bf16<M>(c, a);           \
-        else if (a.store) launch_fast<M, 1>(c, a);           \
-        else launch_fast<M, 0>(c, a);                        \
+        if (a.store && a.Wt) launch_bf16<M>(c, a, narrow);   \
+        else if (a.store) launch_fast<M, 1>(c, a, narrow);   \
+        else launch_fast<M, 0>(c, a, narrow);                \
         break;
     switch (a.a_mode) {
         T_CASE(0)
@@ -767,7 +772,7 @@ static void launch_t(ripple_ctx *c, const TArgs &a, bool vec_ok) {
         T_CASE(2)
         T_CASE(4)
     default:
-        launch_fast<3, 0>(c, a);                             // compact fp32 rows: storage type plays no part in the gather
+        launch_fast<3, 0>(c, a, narrow);                     // compact fp32 rows: storage type plays no part in the gather
         break;
     }
 #undef T_CASE
@@ -831,7 +836,7 @@ void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
         a.a_mode = 4;
         a.out_mode = 2;
     }
-    launch_t(c, a, ly.d_in % 4 == 0);
+    launch_t(c, a, ly.d_in % 4 == 0, from_deltas ? c->last_a[l - 1] : c->n_cap);
 }
 
 // Re-apply layer l (1-based) to the vertices in `list` (count on the device).
@@ -842,6 +847,8 @@ void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const 
     a.D = emit_delta ? c->D[l & 1] : nullptr;
     a.a_mode = (ly.self_mode == RIPPLE_SELF_NONE) ? 0 : (ly.self_mode == RIPPLE_SELF_CONCAT ? 1 : 2);
     const bool vec_in = (ly.d_in % 4 == 0);
+    // expected row count: the previous batch's (bootstrap passes the list of all live vertices)
+    const uint32_t hint = (list == c->all_list) ? c->n_cap : c->last_a[l];
     if (ly.proj) {                               // aggregate already multiplied by W_neigh: add it in the epilogue
         a.addend = c->X[l];
         a.act = (int)ly.act_out;
@@ -852,12 +859,12 @@ void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const 
         a.a_mode = 4;                            // h_self * W_self: the first d_in rows of W0
         a.K = ly.d_in;
         a.Kpad = rp_round_up(ly.d_in, 32);
-        launch_t(c, a, vec_in);
+        launch_t(c, a, vec_in, hint);
         return;
     }
     if (ly.d_hidden == 0) {
         a.act = (int)ly.act_out;
-        launch_t(c, a, vec_in);
+        launch_t(c, a, vec_in, hint);
         return;
     }
     // two-stage update: hidden = act_inner(row W0 + b0) -> tmp, then h = act_out(hidden W1 + b1)
@@ -869,7 +876,7 @@ void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const 
     s1.tmp_out_ld = ly.d_hidden;
     s1.Hout = nullptr;
     s1.D = nullptr;
-    launch_t(c, s1, vec_in);
+    launch_t(c, s1, vec_in, hint);
     TArgs s2 = a;
     s2.a_mode = 3;
     s2.tmp_in = c->tmp;
@@ -884,5 +891,5 @@ void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const 
     s2.Npad = ly.N1pad;
     s2.act = (int)ly.act_out;
     s2.out_mode = 1;
-    launch_t(c, s2, ly.d_hidden % 4 == 0);
+    launch_t(c, s2, ly.d_hidden % 4 == 0, hint);
 }
