@@ -233,7 +233,7 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
     if (!c) return;
     hipStreamSynchronize(c->stream);
     void *ptrs[] = {c->out_meta, c->in_meta, c->out_capv, c->in_capv, c->vstate, c->pend_out, c->pend_in, c->dead_out,
-                    c->dead_in, c->out_pool, c->in_pool, c->alive, c->part_cnt, c->part_deg, c->part_ideg, c->ioff[0], c->wrank[0], c->ctr, c->D[0], c->D[1],
+                    c->dead_in, c->out_pool, c->in_pool, c->alive, c->part_cnt, c->part_deg, c->part_ideg, c->ioff[0], c->ctr, c->D[0], c->D[1],
                     c->tmp, c->PD, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ops_d, c->payload_d,
                     c->op_status, c->op_pos_out, c->op_pos_in, c->touch_out, c->touch_in, c->exp_kind, c->exp_a,
                     c->exp_b, c->st_src, c->st_dst, c->st_sign, c->gather_d, c->gather_ids};
@@ -365,20 +365,18 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
         if (pw) RP_TRY(dev_alloc(c, &c->PD, n * c->pd_ld, true));
     }
     // bitmaps: layers 0..L, then S, then V_added, contiguous; reporting copies separately
-    uint32_t *bmall = nullptr, *repall = nullptr, *lists = nullptr, *eoffs = nullptr, *ioffs = nullptr, *wranks = nullptr;
+    uint32_t *bmall = nullptr, *repall = nullptr, *lists = nullptr, *eoffs = nullptr, *ioffs = nullptr;
     RP_TRY(dev_alloc(c, &bmall, (size_t)c->n_words * (c->L + 3), true));
     RP_TRY(dev_alloc(c, &repall, (size_t)c->n_words * (c->L + 1), true));
     RP_TRY(dev_alloc(c, &lists, (n + 1) * (c->L + 1), true));
     RP_TRY(dev_alloc(c, &eoffs, (n + 1) * (c->L + 1), true));
     RP_TRY(dev_alloc(c, &ioffs, (n + 1) * (c->L + 1), true));
-    RP_TRY(dev_alloc(c, &wranks, (size_t)c->n_words * (c->L + 1), true));
     for (uint32_t l = 0; l <= c->L; ++l) {
         c->bm[l] = bmall + (size_t)l * c->n_words;
         c->rep[l] = repall + (size_t)l * c->n_words;
         c->list[l] = lists + (size_t)l * (n + 1);
         c->eoff[l] = eoffs + (size_t)l * (n + 1);
         c->ioff[l] = ioffs + (size_t)l * (n + 1);
-        c->wrank[l] = wranks + (size_t)l * c->n_words;
     }
     c->bm_sink = bmall + (size_t)(c->L + 1) * c->n_words;
     c->bm_vadd = bmall + (size_t)(c->L + 2) * c->n_words;

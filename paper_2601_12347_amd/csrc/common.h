@@ -89,7 +89,7 @@ struct ripple_ctx {
     // embeddings and cached sums
     void *H[RIPPLE_MAX_LAYERS + 1] = {nullptr};
     float *X[RIPPLE_MAX_LAYERS + 1] = {nullptr};
-    float *D[2] = {nullptr, nullptr};                   // compact delta rows, ping-pong
+    float *D[2] = {nullptr, nullptr};                   // delta rows D^l[v] (valid for v in A_l), ping-pong
     float *tmp = nullptr;                               // hidden activations of two-stage updates
     float *PD = nullptr;                                // projected rows of project-first layers
     uint32_t xw[RIPPLE_MAX_LAYERS + 1] = {0};           // width of X^l (d_{l-1}, or d_l when projected)
@@ -103,7 +103,6 @@ struct ripple_ctx {
     uint32_t *eoff[RIPPLE_MAX_LAYERS + 1] = {nullptr};  // exclusive scan of out-degrees over A_l, +1 entry
     uint32_t *part_cnt = nullptr, *part_deg = nullptr, *part_ideg = nullptr;  // per-block partial sums
     uint32_t *ioff[RIPPLE_MAX_LAYERS + 1] = {nullptr};  // exclusive scan of in-degrees over A_l, +1 entry
-    uint32_t *wrank[RIPPLE_MAX_LAYERS + 1] = {nullptr}; // list position of the first vertex of each bitmap word
     uint32_t n_part = 0;
     uint32_t *all_list = nullptr;                       // scratch list (live vertices) for full inference
 

@@ -65,7 +65,6 @@ struct CompactArgs {
     uint32_t *rep;                 // reporting union or null
     uint32_t *touched_out;         // += vertices that received a message, or null
     uint32_t *list, *eoff, *ioff;  // outputs
-    uint32_t *wrank;               // per bitmap word: list position of its first vertex, or null
     uint32_t *count_out, *msgs_out, *isum_out;
 };
 
@@ -172,7 +171,6 @@ __global__ __launch_bounds__(256) void k_frontier_emit(CompactArgs a) {
         oo += wo[k];
         oi += wi[k];
     }
-    if (a.wrank && idx < a.n_words) a.wrank[idx] = oc;
     uint32_t t = w;
     while (t) {
         uint32_t v = idx * 32 + (__ffs(t) - 1);
@@ -259,7 +257,6 @@ __global__ __launch_bounds__(1024) void k_frontier_compact_small(CompactArgs a) 
     for (int k = 0; k < SMALL_WPT; ++k) {
         const uint32_t idx = w0 + k;
         if ((uint32_t)k < wpt && idx < a.n_words) {
-            if (a.wrank) a.wrank[idx] = oc;
             uint32_t t = words[k];
             while (t) {
                 const uint32_t v = idx * 32 + (__ffs(t) - 1);
@@ -300,8 +297,9 @@ static void launch_compact(ripple_ctx *c, const CompactArgs &a) {
         hipLaunchKernelGGL(k_frontier_compact_small, dim3(1), dim3(1024), 0, c->stream, a);
         return;
     }
-    uint32_t nb = rp_div_up(a.n_words, 256);
-    launch_compact(c, a);
+    const uint32_t nb = rp_div_up(a.n_words, 256);
+    hipLaunchKernelGGL(k_frontier_count, dim3(nb), dim3(256), 0, c->stream, a);
+    hipLaunchKernelGGL(k_frontier_emit, dim3(nb), dim3(256), 0, c->stream, a);
 }
 
 // out-degree prefix over an arbitrary (unsorted) list, one workgroup; used for hop 0
@@ -342,7 +340,7 @@ void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l) {
 }
 
 // bitmap of layer l, merged with S, V_added (and A_{l-1} when self_term) -> list[l], ctr->a[l];
-// want_out: eoff[l] and ctr->m[l+1] (the next hop's edge walk); want_in: ioff[l], ctr->isum[l], wrank[l]
+// want_out: eoff[l] and ctr->m[l+1] (the next hop's edge walk); want_in: ioff[l], ctr->isum[l]
 void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool want_out, bool want_in,
                                 bool accumulate_rep) {
     CompactArgs a;
@@ -364,7 +362,6 @@ void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool 
     a.list = c->list[l];
     a.eoff = c->eoff[l];
     a.ioff = c->ioff[l];
-    a.wrank = c->wrank[l];
     a.count_out = &c->ctr->a[l];
     a.msgs_out = (l < RIPPLE_MAX_LAYERS) ? &c->ctr->m[l + 1] : nullptr;
     a.isum_out = &c->ctr->isum[l];

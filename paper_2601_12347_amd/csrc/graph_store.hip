@@ -548,7 +548,7 @@ __global__ __launch_bounds__(256) void k_apply_vertices(MutArgs a) {
                     old = h[idx];
                     h[idx] = nv;
                 }
-                a.D0[(size_t)slot * d0 + c] = nv - old;
+                a.D0[idx] = nv - old;
             }
             if (lane == 0) {
                 a.list0[slot] = w;

@@ -67,11 +67,12 @@ __global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, cons
             const uint32_t ik = __shfl(my_i, k), vk = __shfl(my_v, k);
             if (ik != cur) {                                    // same for all lanes
                 cur = ik;
+                const uint32_t uk = list[ik];                   // delta rows are indexed by vertex
                 bool any = false;
 #pragma unroll
                 for (int j = 0; j < NJ; ++j) {
                     uint32_t col = lane + 64 * j;
-                    dreg[j] = (col < d) ? D[(size_t)ik * ldd + col] : 0.0f;
+                    dreg[j] = (col < d) ? D[(size_t)uk * ldd + col] : 0.0f;
                     any |= dreg[j] != 0.0f;
                 }
                 nz = __ballot(any) != 0ull;
@@ -115,8 +116,7 @@ struct PullArgs {
     const uint2 *in_meta;
     const uint32_t *in_pool;
     const uint32_t *bm_prev;       // A_{l-1} as bitmap
-    const uint32_t *wrank_prev;    // rank of each bitmap word's first vertex in A_{l-1}
-    const float *D;                // delta rows of A_{l-1}, row = rank
+    const float *D;                // delta rows, indexed by vertex
     uint32_t ldd;                  // their row stride
     uint32_t d;
     float *X;
@@ -154,9 +154,8 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
             if (e < e1) {
                 my_i[t] = (i_lo == i_hi) ? i_lo : seg_search2(a.ioff, i_lo, i_hi, e);
                 const uint32_t u = a.in_pool[a.in_meta[a.list[my_i[t]]].x + (e - a.ioff[my_i[t]])];
-                const uint32_t word = a.bm_prev[u >> 5];
-                dirty[t] = (word >> (u & 31)) & 1u;
-                if (dirty[t]) slot[t] = a.wrank_prev[u >> 5] + __popc(word & ((1u << (u & 31)) - 1u));
+                dirty[t] = (a.bm_prev[u >> 5] >> (u & 31)) & 1u;
+                slot[t] = u;
             }
         }
         uint32_t cur = i_lo;
@@ -225,7 +224,6 @@ void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l) {
     a.in_meta = c->in_meta;
     a.in_pool = c->in_pool;
     a.bm_prev = c->bm[l - 1];
-    a.wrank_prev = c->wrank[l - 1];
     a.D = c->layers[l - 1].proj ? c->PD : c->D[(l - 1) & 1];
     a.d = c->xw[l];
     a.ldd = c->layers[l - 1].proj ? c->pd_ld : a.d;

@@ -3,7 +3,7 @@
 //     GraphConv  x            GraphSAGE  [h_self | x]        GIN  (1+eps) h_self + x
 // (x = X^l[v], divided by the in-degree for mean), multiply by the weight
 // matrix on the matrix cores, add the bias, apply the activation, and emit
-//     D^l[slot] = h_new - H^l[v],   H^l[v] = h_new
+//     D^l[v] = h_new - H^l[v],   H^l[v] = h_new
 // so that the next hop can forward the delta (Sec. 3.3.3).
 //
 // Tiling: a workgroup of four wavefronts computes a (WAVES_M*TM*32) x (WAVES_N*TN*32)
@@ -50,7 +50,7 @@ struct TArgs {
     float *tmp_out;
     uint32_t tmp_out_ld;
     void *Hout;
-    float *D;                      // compact delta rows [slot x N] or null
+    float *D;                      // delta rows [vertex x N] or null
     int store;                     // 0 fp32, 1 bf16 embeddings
 };
 
@@ -185,7 +185,7 @@ __device__ __forceinline__ void epilogue(const TArgs &a, floatx16 (&acc)[TM][TN]
                     } else {
                         ((float *)a.Hout)[hidx] = z;
                     }
-                    if (a.D) a.D[(size_t)slot * a.N + col] = z - old[sn][r];
+                    if (a.D) a.D[hidx] = z - old[sn][r];
                 }
             }
         }
@@ -312,7 +312,7 @@ __device__ __forceinline__ void epilogue_staged(const TArgs &a, floatx16 (&acc)[
                 } else {
                     st4((float *)a.Hout + hidx, v, vec, nv[u]);
                 }
-                if (a.D) st4(a.D + (size_t)slot * a.N + col, v - old[u], vec, nv[u]);
+                if (a.D) st4(a.D + hidx, v - old[u], vec, nv[u]);
             }
         }
     }
@@ -345,7 +345,7 @@ __global__ void k_transform_addend_only(TArgs a) {
             old = h[hidx];
             h[hidx] = z;
         }
-        if (a.D) a.D[(size_t)slot * a.N + col] = z - old;
+        if (a.D) a.D[hidx] = z - old;
     }
 }
 
@@ -812,8 +812,9 @@ static TArgs base_args(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
 }
 
 // Project-first layers: P = rows * W_neigh, no bias, no activation.
-//   from_deltas: rows are the compact delta rows D^{l-1} of A_{l-1}; P[slot] goes to c->PD
-//   otherwise:   rows are H^{l-1}[v] for the listed vertices; P[v] goes to c->PD (bootstrap)
+//   from_deltas: rows are the delta rows D^{l-1}[v] of the listed vertices
+//   otherwise:   rows are H^{l-1}[v] (bootstrap)
+// P[v] goes to c->PD.
 void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool from_deltas) {
     const LayerDev &ly = c->layers[l - 1];
     TArgs a = base_args(c, l, list, count_d);
@@ -827,14 +828,12 @@ void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
     a.tmp_out = c->PD;
     a.tmp_out_ld = c->pd_ld;
     a.Hout = nullptr;
+    a.out_mode = 2;
     if (from_deltas) {
-        a.a_mode = 3;
-        a.tmp_in = c->D[(l - 1) & 1];
-        a.tmp_ld = ly.d_in;
-        a.out_mode = 0;
+        a.a_mode = 0;                              // rows of an fp32 matrix indexed by vertex, unscaled (mean = 0)
+        a.X = c->D[(l - 1) & 1];
     } else {
         a.a_mode = 4;
-        a.out_mode = 2;
     }
     launch_t(c, a, ly.d_in % 4 == 0, from_deltas ? c->last_a[l - 1] : c->n_cap);
 }

@@ -264,3 +264,20 @@ def test_device_resident_batch():
         assert np.array_equal(out_t.cpu().numpy(), pair.gpu_layer(pair.L))
     finally:
         pair.close()
+
+
+def test_graph_beyond_the_single_workgroup_compaction_limit():
+    """300,000 vertices need more than 8,192 bitmap words, so the frontier lists come from the
+    two-pass (count, then scan and emit) compaction rather than the one-workgroup kernel."""
+    print("case wide bitmap", flush=True)
+    pair, graph = make_pair(n=300000, e=1200000, d0=8, kind="sage_mean", widths=(8, 16, 12), seed=91,
+                            slack=1000, top_share=0.005)
+    stream = make_stream(pair, graph, MIXV, 92)
+    try:
+        for b, bs in enumerate([1, 64, 2000]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload, check=(b == 2))
+        pair.check_aggregates()
+    finally:
+        pair.close()
