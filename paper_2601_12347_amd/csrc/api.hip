@@ -13,7 +13,7 @@
 // ---------------------------------------------------------------------------------
 struct PhaseTimer {
     struct Rec {
-        int phase, layer, e0, e1;
+        int phase, layer, e0, e1, counted;
     };
     std::vector<hipEvent_t> ev;
     std::vector<Rec> recs;
@@ -35,12 +35,13 @@ int rp_timer_begin(ripple_ctx *c) {
     return e;
 }
 
-void rp_timer_end(ripple_ctx *c, int token, int phase, int layer) {
+// counted = false: a second stretch of a phase already recorded for this hop (adds time, not a launch)
+void rp_timer_end(ripple_ctx *c, int token, int phase, int layer, bool counted) {
     if (token < 0) return;
     int e = c->timer->get(c);
     if (e < 0) return;
     hipEventRecord(c->timer->ev[e], c->stream);
-    c->timer->recs.push_back({phase, layer, token, e});
+    c->timer->recs.push_back({phase, layer, token, e, counted ? 1 : 0});
 }
 
 static void timer_collect(ripple_ctx *c) {       // after the stream has been synchronised
@@ -49,7 +50,7 @@ static void timer_collect(ripple_ctx *c) {       // after the stream has been sy
         float ms = 0.f;
         if (hipEventElapsedTime(&ms, t->ev[r.e0], t->ev[r.e1]) == hipSuccess) {
             c->stats.ms[r.phase][r.layer] += ms;
-            c->stats.launches[r.phase][r.layer] += 1;
+            c->stats.launches[r.phase][r.layer] += r.counted;
         }
     }
     t->recs.clear();
@@ -234,7 +235,7 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
     hipStreamSynchronize(c->stream);
     void *ptrs[] = {c->out_meta, c->in_meta, c->out_capv, c->in_capv, c->vstate, c->pend_out, c->pend_in, c->dead_out,
                     c->dead_in, c->out_pool, c->in_pool, c->alive, c->part_cnt, c->part_deg, c->part_ideg, c->ioff[0], c->ctr, c->D[0], c->D[1],
-                    c->tmp, c->PD, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ops_d, c->payload_d,
+                    c->tmp, c->PD, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ioff_all, c->ops_d, c->payload_d,
                     c->op_status, c->op_pos_out, c->op_pos_in, c->touch_out, c->touch_in, c->exp_kind, c->exp_a,
                     c->exp_b, c->st_src, c->st_dst, c->st_sign, c->gather_d, c->gather_ids};
     for (void *p : ptrs)
@@ -381,6 +382,7 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
     c->bm_sink = bmall + (size_t)(c->L + 1) * c->n_words;
     c->bm_vadd = bmall + (size_t)(c->L + 2) * c->n_words;
     RP_TRY(dev_alloc(c, &c->all_list, n + 1, true));
+    RP_TRY(dev_alloc(c, &c->ioff_all, n + 1, true));
     RP_HIP(c, hipStreamSynchronize(c->stream));
     c->state = 2;
     return RIPPLE_OK;
@@ -573,25 +575,37 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
     if (multi)
         hipLaunchKernelGGL(k_or_words, dim3(rp_div_up(c->n_words, 256)), dim3(256), 0, c->stream, c->rep[0], c->bm[0],
                            c->n_words);
+    bool have_all = false;                              // live-vertex list of this piece exists
     for (uint32_t l = 1; l <= c->L; ++l) {
         // hop 1 always pushes: hop-0 rows are in operation order, not ranked by vertex id. Where the
         // previous batch pushed with a wide margin the pull kernel is not even enqueued (pushing is
-        // always correct; the prediction only saves a launch).
+        // always correct; the prediction only saves a launch). The same goes for the discovering
+        // mode: its kernels are enqueued only where the previous batch came near its threshold.
         const bool may_pull = l >= 2 && c->opt_scatter != 1 && !(c->opt_scatter == 0 && c->push_margin[l]);
+        const bool may_disc = may_pull && (c->opt_scatter == 3 || (c->opt_scatter == 0 && c->disc_near[l]));
         t = rp_timer_begin(c);
-        rp_launch_frontier_mark(c, l);
+        if (may_disc && !have_all) {
+            rp_launch_alive_list(c);
+            have_all = true;
+        }
+        rp_launch_frontier_mark(c, l, may_disc);
         rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
-        t = rp_timer_begin(c);
-        rp_launch_frontier_compact(c, l, layer_self(c, l), l < c->L, true, multi);
-        rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l);
         if (c->layers[l - 1].proj) {                   // multiply the deltas by W_neigh before they travel
             t = rp_timer_begin(c);
             rp_launch_project(c, l, c->list[l - 1], &c->ctr->a[l - 1], true);
             rp_timer_end(c, t, RIPPLE_PH_OTHER, (int)l);
         }
+        if (may_disc) {                                // scatters and marks A_l in one scan of all in-rows
+            t = rp_timer_begin(c);
+            rp_launch_scatter_pull(c, l, true, true);
+            rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l, false);
+        }
         t = rp_timer_begin(c);
-        if (c->opt_scatter != 2 || !may_pull) rp_launch_scatter_push(c, l, may_pull);
-        if (may_pull) rp_launch_scatter_pull(c, l);
+        rp_launch_frontier_compact(c, l, layer_self(c, l), l < c->L, true, multi);
+        rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l);
+        t = rp_timer_begin(c);
+        if (c->opt_scatter < 2 || !may_pull) rp_launch_scatter_push(c, l, may_pull, may_disc);
+        if (may_pull) rp_launch_scatter_pull(c, l, false, may_disc);
         rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l);
         t = rp_timer_begin(c);
         rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], l < c->L);
@@ -712,6 +726,7 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
             // pull wins when m * row_bytes * ratio >= 8 * in-edges; remember if push won by a factor of 16
             const unsigned long long lhs = (unsigned long long)h.m[l] * c->xw[l] * 4ull * (unsigned)c->opt_pull_ratio * 16ull;
             c->push_margin[l] = lhs < 8ull * h.isum[l];
+            c->disc_near[l] = (unsigned long long)h.m[l] * 32ull >= h.n_edges;     // threshold: m * 4 >= edges
         }
         if (!multi)
             for (uint32_t l = 0; l <= c->L; ++l) c->last_a[l] = h.a[l];
@@ -840,7 +855,7 @@ extern "C" ripple_status ripple_get_affected(ripple_ctx *c, uint32_t layer, uint
     if (layer > c->L || !n_out || (cap && !ids_out)) return fail(c, RIPPLE_EINVAL, "bad argument");
     hipStream_t s = c->stream;
     uint32_t *bitmap = c->last_from_rep ? c->rep[layer] : c->bm[layer];
-    uint32_t *cnt_d = &c->ctr->pad0;               // spare counter word
+    uint32_t *cnt_d = &c->ctr->n_all;              // free between batches
     rp_launch_bitmap_to_list(c, bitmap, c->all_list, cnt_d);
     uint32_t n = 0;
     RP_HIP(c, hipMemcpyAsync(&n, cnt_d, 4, hipMemcpyDeviceToHost, s));
@@ -927,7 +942,7 @@ extern "C" ripple_status ripple_set_option(ripple_ctx *c, int option, int64_t va
     switch (option) {
     case RIPPLE_OPT_TIMING: c->opt_timing = value ? 1 : 0; return RIPPLE_OK;
     case RIPPLE_OPT_SCATTER_MODE:
-        if (value < 0 || value > 2) return fail(c, RIPPLE_EINVAL, "scatter mode must be 0, 1 or 2");
+        if (value < 0 || value > 3) return fail(c, RIPPLE_EINVAL, "scatter mode must be 0, 1, 2 or 3");
         c->opt_scatter = (int)value;
         return RIPPLE_OK;
     case RIPPLE_OPT_BF16_MFMA:

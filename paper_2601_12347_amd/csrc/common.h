@@ -39,7 +39,7 @@ struct DevCtr {                      // device-resident counters, one instance p
     uint32_t n_alive;
     uint32_t n_vadd;
     uint32_t abort_flag;                      // written by k_capacity's last workgroup: 0 ok, bit0 pool, bit1 edges, bit2 scratch
-    uint32_t pad0;
+    uint32_t n_all;                           // live vertices listed for a discovering hop
     unsigned long long n_edges;
     uint32_t blocks_done;                     // workgroups of k_capacity that have finished (0 between launches)
     uint32_t pad2;
@@ -104,7 +104,8 @@ struct ripple_ctx {
     uint32_t *part_cnt = nullptr, *part_deg = nullptr, *part_ideg = nullptr;  // per-block partial sums
     uint32_t *ioff[RIPPLE_MAX_LAYERS + 1] = {nullptr};  // exclusive scan of in-degrees over A_l, +1 entry
     uint32_t n_part = 0;
-    uint32_t *all_list = nullptr;                       // scratch list (live vertices) for full inference
+    uint32_t *all_list = nullptr;                       // scratch list (live vertices): full inference, discovering hops
+    uint32_t *ioff_all = nullptr;                       // exclusive scan of in-degrees over all_list, +1 entry
 
     // batch staging
     uint32_t ops_cap = 0, feat_cap = 0;
@@ -133,6 +134,7 @@ struct ripple_ctx {
     uint32_t last_a[RIPPLE_MAX_LAYERS + 1] = {0};
     bool last_from_rep = false;
     bool push_margin[RIPPLE_MAX_LAYERS + 1] = {false};  // last batch pushed at this hop by a wide margin
+    bool disc_near[RIPPLE_MAX_LAYERS + 1] = {false};    // last batch's hop was within reach of the discovering mode
 
     // options
     int opt_timing = 0;
@@ -174,6 +176,56 @@ __device__ __forceinline__ uint32_t rp_row_cap(uint32_t need) {   // capacity gi
     uint32_t c = need + (need >> 1) + 4u;
     return (c + 3u) & ~3u;
 }
+// largest i in [lo, hi] with off[i] <= e   (off is non-decreasing, off[lo] <= e)
+__device__ __forceinline__ uint32_t rp_seg_search(const uint32_t *off, uint32_t lo, uint32_t hi, uint32_t e) {
+    while (lo < hi) {
+        const uint32_t mid = (lo + hi + 1) >> 1;
+        if (off[mid] <= e) lo = mid;
+        else hi = mid - 1;
+    }
+    return lo;
+}
+// the same over [lo, last], for an answer expected close to lo: doubling steps, then bisection
+__device__ __forceinline__ uint32_t rp_seg_forward(const uint32_t *off, uint32_t lo, uint32_t last, uint32_t e) {
+    uint32_t step = 1;
+    while (lo + step <= last && off[lo + step] <= e) {
+        lo += step;
+        step <<= 1;
+    }
+    return rp_seg_search(off, lo, min(last, lo + step), e);
+}
+// number of lanes whose value b (ascending over the lanes) is <= e, found with shuffles; to be
+// called by all 64 lanes together
+__device__ __forceinline__ uint32_t rp_count_le(uint32_t b, uint32_t e) {
+    const uint32_t top = __shfl(b, 63);
+    uint32_t lo = 0;                                        // b of every lane below lo is <= e
+#pragma unroll
+    for (int s = 32; s > 0; s >>= 1) {
+        const uint32_t v = __shfl(b, (int)(lo + s - 1));
+        if (v <= e) lo += s;
+    }
+    if (lo == 63 && top <= e) lo = 64;
+    return lo;
+}
+
+// How hop l (1-based) moves its messages, decided on the device from the hop's own counters so
+// that no host round trip is needed. 0 push: walk the out-edges of A_{l-1}, one atomic row update
+// per message. 1 pull: scan the in-rows of A_l (index + dirty-bit probe per in-edge) and gather each
+// message once. 2 discover: when A_{l-1} sends along a large share of all edges nearly every vertex
+// is hit, so the in-rows of all live vertices are scanned once, which both gathers the messages and
+// finds A_l, and the out-edge walk that would have marked A_l is skipped.
+// mode: 0 automatic, 1 push, 2 pull, 3 discover wherever it is allowed.
+#define RP_HOP_PUSH 0
+#define RP_HOP_PULL 1
+#define RP_HOP_DISCOVER 2
+__device__ __forceinline__ int rp_hop_mode(const DevCtr *ctr, uint32_t l, uint32_t d, int mode, int ratio, int allow_disc) {
+    const unsigned long long m = ctr->m[l];
+    if (allow_disc && m > 0 && (mode == 3 || (mode == 0 && m * 4ull >= ctr->n_edges))) return RP_HOP_DISCOVER;
+    if (mode == 1) return RP_HOP_PUSH;
+    if (mode == 2 || mode == 3) return RP_HOP_PULL;
+    return (m > 0 && m * d * 4ull * (unsigned long long)ratio >= 8ull * ctr->isum[l]) ? RP_HOP_PULL : RP_HOP_PUSH;
+}
+
 // position of `target` in row[0..len), searched by one wavefront; -1 when absent.
 // Four 64-entry blocks are loaded per round so that long (hub) rows are not paced by one
 // memory round trip per 64 entries.

@@ -8,33 +8,31 @@
 #include "kernels.h"
 #include <cstring>
 
-// largest i in [lo, hi] with off[i] <= e   (off is non-decreasing, off[lo] <= e)
-__device__ __forceinline__ uint32_t seg_search(const uint32_t *off, uint32_t lo, uint32_t hi, uint32_t e) {
-    while (lo < hi) {
-        uint32_t mid = (lo + hi + 1) >> 1;
-        if (off[mid] <= e) lo = mid;
-        else hi = mid - 1;
-    }
-    return lo;
-}
-
+#define seg_search rp_seg_search
 #define MARK_CHUNK 256
 
-// mark the out-neighbours of every vertex of A_{l-1}
+// mark the out-neighbours of every vertex of A_{l-1}. Every wavefront walks a contiguous run of
+// 256-edge chunks of the flattened out-edge space, so only its first chunk needs a search over the
+// whole list. Nothing to do on a discovering hop (the in-row scan finds A_l).
 __global__ __launch_bounds__(256) void k_frontier_mark(const uint32_t *list, const uint32_t *count_ptr,
                                                        const uint32_t *eoff, const uint2 *out_meta,
-                                                       const uint32_t *out_pool, uint32_t *bm) {
+                                                       const uint32_t *out_pool, uint32_t *bm, const DevCtr *ctr,
+                                                       uint32_t l, uint32_t d, int mode, int ratio, int allow_disc) {
+    if (allow_disc && rp_hop_mode(ctr, l, d, mode, ratio, allow_disc) == RP_HOP_DISCOVER) return;
     const uint32_t count = *count_ptr;
     if (count == 0) return;
     const int lane = rp_lane();
-    const uint32_t gt = blockIdx.x * blockDim.x + threadIdx.x, nt = gridDim.x * blockDim.x;
     const uint32_t M = eoff[count];
     const uint32_t n_chunks = (M + MARK_CHUNK - 1) / MARK_CHUNK;
-    const uint32_t gw = gt >> 6, nw = nt >> 6;
-    for (uint32_t c = gw; c < n_chunks; c += nw) {
-        uint32_t e0 = c * MARK_CHUNK, e1 = min(M, e0 + MARK_CHUNK);
-        uint32_t i_lo = seg_search(eoff, 0, count - 1, e0);
-        uint32_t i_hi = seg_search(eoff, i_lo, count - 1, e1 - 1);
+    const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    const uint32_t per = (n_chunks + nw - 1) / nw;
+    const uint32_t c_begin = min(n_chunks, gw * per), c_end = min(n_chunks, c_begin + per);
+    if (c_begin >= c_end) return;
+    const uint32_t last = count - 1;
+    uint32_t i_lo = rp_seg_search(eoff, 0, last, c_begin * MARK_CHUNK);
+    for (uint32_t c = c_begin; c < c_end; ++c) {
+        const uint32_t e0 = c * MARK_CHUNK, e1 = min(M, e0 + MARK_CHUNK);
+        const uint32_t i_hi = rp_seg_forward(eoff, i_lo, last, e1 - 1);
         // four independent edges per lane: their dependent load chains overlap
         uint32_t v[MARK_CHUNK / 64];
 #pragma unroll
@@ -42,13 +40,14 @@ __global__ __launch_bounds__(256) void k_frontier_mark(const uint32_t *list, con
             const uint32_t e = e0 + lane + 64 * t;
             v[t] = 0xFFFFFFFFu;
             if (e < e1) {
-                const uint32_t i = (i_lo == i_hi) ? i_lo : seg_search(eoff, i_lo, i_hi, e);
+                const uint32_t i = (i_lo == i_hi) ? i_lo : rp_seg_search(eoff, i_lo, i_hi, e);
                 v[t] = out_pool[out_meta[list[i]].x + (e - eoff[i])];
             }
         }
 #pragma unroll
         for (int t = 0; t < MARK_CHUNK / 64; ++t)
             if (v[t] != 0xFFFFFFFFu) rp_set_bit(bm, v[t]);
+        i_lo = rp_seg_forward(eoff, i_hi, last, e1);
     }
 }
 
@@ -334,9 +333,30 @@ __global__ __launch_bounds__(1024) void k_list_eoff(const uint32_t *list, const 
     }
 }
 
-void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l) {
+void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l, bool allow_disc) {
     hipLaunchKernelGGL(k_frontier_mark, dim3(c->n_cu * 8), dim3(256), 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],
-                       c->eoff[l - 1], c->out_meta, c->out_pool, c->bm[l]);
+                       c->eoff[l - 1], c->out_meta, c->out_pool, c->bm[l], c->ctr, l, c->xw[l], c->opt_scatter,
+                       c->opt_pull_ratio, allow_disc ? 1 : 0);
+}
+
+// all live vertices, ascending, in c->all_list (count in ctr->n_all) with the exclusive scan of
+// their in-degrees in c->ioff_all: the work list of a discovering hop
+void rp_launch_alive_list(ripple_ctx *c) {
+    CompactArgs a;
+    memset(&a, 0, sizeof(a));
+    a.bm = c->alive;                               // rewritten with the same bits
+    a.alive = c->alive;
+    a.n_words = c->n_words;
+    a.out_meta = c->out_meta;
+    a.in_meta = c->in_meta;
+    a.want_in = 1;
+    a.part_cnt = c->part_cnt;
+    a.part_out = c->part_deg;
+    a.part_in = c->part_ideg;
+    a.list = c->all_list;
+    a.ioff = c->ioff_all;
+    a.count_out = &c->ctr->n_all;
+    launch_compact(c, a);
 }
 
 // bitmap of layer l, merged with S, V_added (and A_{l-1} when self_term) -> list[l], ctr->a[l];

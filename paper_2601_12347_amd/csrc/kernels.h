@@ -13,15 +13,16 @@ void rp_launch_batch_reset(ripple_ctx *c);
 void rp_launch_mutate(ripple_ctx *c, uint32_t n_ops, bool has_vertex_add, bool has_vertex_del, bool has_vertex_or_feat);
 
 // frontier.hip
-void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l);
+void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l, bool allow_disc);
+void rp_launch_alive_list(ripple_ctx *c);
 void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool want_out, bool want_in,
                                 bool accumulate_rep);
 void rp_launch_bitmap_to_list(ripple_ctx *c, uint32_t *bitmap, uint32_t *out_list, uint32_t *count_d);
 void rp_launch_list_eoff(ripple_ctx *c, uint32_t l);
 
 // scatter.hip
-void rp_launch_scatter_push(ripple_ctx *c, uint32_t l, bool may_pull);
-void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l);
+void rp_launch_scatter_push(ripple_ctx *c, uint32_t l, bool may_pull, bool allow_disc);
+void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow_disc);
 void rp_launch_pull_all(ripple_ctx *c, uint32_t l);
 
 // transform.hip
@@ -30,4 +31,4 @@ void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
 
 // api.hip: HIP-event timing of kernel classes (no-ops unless RIPPLE_OPT_TIMING is on)
 int rp_timer_begin(ripple_ctx *c);
-void rp_timer_end(ripple_ctx *c, int token, int phase, int layer);
+void rp_timer_end(ripple_ctx *c, int token, int phase, int layer, bool counted = true);

@@ -14,35 +14,18 @@
 #include "common.h"
 #include "kernels.h"
 
-__device__ __forceinline__ uint32_t seg_search2(const uint32_t *off, uint32_t lo, uint32_t hi, uint32_t e) {
-    while (lo < hi) {
-        uint32_t mid = (lo + hi + 1) >> 1;
-        if (off[mid] <= e) lo = mid;
-        else hi = mid - 1;
-    }
-    return lo;
-}
+#define seg_search2 rp_seg_search
 
 #define PUSH_CHUNK 64
 #define PULL_CHUNK 256
-
-// Direction of hop l, decided on the device from the hop's own counters so that no host
-// round trip is needed: pulling scans every in-edge of A_l (index + dirty-bit probe, ~8 bytes
-// each) but gathers each message once without atomics; pushing touches only the messages but
-// pays a read-modify-write per message.
-__device__ __forceinline__ bool rp_use_pull(const DevCtr *ctr, uint32_t l, uint32_t d, int mode, int ratio) {
-    if (mode == 2) return true;
-    if (mode == 1) return false;
-    const unsigned long long m = ctr->m[l], in_edges = ctr->isum[l];
-    return m > 0 && m * d * 4ull * (unsigned long long)ratio >= 8ull * in_edges;
-}
 
 template <int NJ>
 __global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, const uint32_t *count_ptr,
                                                       const uint32_t *eoff, const float *D, uint32_t ldd, uint32_t d,
                                                       const uint2 *out_meta, const uint32_t *out_pool, float *X,
-                                                      const DevCtr *ctr, uint32_t l, int may_pull, int mode, int ratio) {
-    if (may_pull && rp_use_pull(ctr, l, d, mode, ratio)) return;
+                                                      const DevCtr *ctr, uint32_t l, int may_pull, int mode, int ratio, int allow_disc) {
+    const int hm = rp_hop_mode(ctr, l, d, mode, ratio, allow_disc);
+    if (hm == RP_HOP_DISCOVER || (may_pull && hm == RP_HOP_PULL)) return;
     const uint32_t count = *count_ptr;
     if (count == 0) return;
     const int lane = rp_lane();
@@ -88,7 +71,7 @@ __global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, cons
     }
 }
 
-void rp_launch_scatter_push(ripple_ctx *c, uint32_t l, bool may_pull) {
+void rp_launch_scatter_push(ripple_ctx *c, uint32_t l, bool may_pull, bool allow_disc) {
     const bool proj = c->layers[l - 1].proj != 0;           // project-first: messages are already d_out wide
     const uint32_t d = c->xw[l];
     const float *D = proj ? c->PD : c->D[(l - 1) & 1];
@@ -97,7 +80,7 @@ void rp_launch_scatter_push(ripple_ctx *c, uint32_t l, bool may_pull) {
 #define PUSH_CASE(NJ)                                                                                         \
     hipLaunchKernelGGL(k_scatter_push<NJ>, grid, block, 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],      \
                        c->eoff[l - 1], D, ldd, d, c->out_meta, c->out_pool, c->X[l], c->ctr, l, may_pull ? 1 : 0,          \
-                       c->opt_scatter, c->opt_pull_ratio)
+                       c->opt_scatter, c->opt_pull_ratio, allow_disc ? 1 : 0)
     if (d <= 64) PUSH_CASE(1);
     else if (d <= 128) PUSH_CASE(2);
     else if (d <= 256) PUSH_CASE(4);
@@ -107,27 +90,35 @@ void rp_launch_scatter_push(ripple_ctx *c, uint32_t l, bool may_pull) {
 }
 
 // ---------------------------------------------------------------------------------
-// pull: segmented reduction over the in-rows of A_l, keeping only dirty sources
+// pull: segmented reduction over in-rows, keeping only the sources that are in A_{l-1}
 // ---------------------------------------------------------------------------------
+// The flattened in-edge space of the listed destinations is cut into 256-edge chunks and every
+// wavefront takes a contiguous run of chunks, so the row of a chunk's first edge follows from the
+// previous chunk instead of a search over the whole list. The 64 rows after that one (vertex, pool
+// position, first edge) sit in registers, one per lane; an edge finds its row with shuffles. The next
+// chunk's rows are requested before the gathers of the current one.
+// DISC = 0: destinations are A_l. DISC = 1 (discovering hop): destinations are all live vertices and
+// those that receive a message are marked in the hop's bitmap.
 struct PullArgs {
-    const uint32_t *list;          // A_l
+    const uint32_t *list;          // destinations, ascending
     const uint32_t *count_ptr;
-    const uint32_t *ioff;          // in-degree prefix over A_l
+    const uint32_t *ioff;          // in-degree prefix over the list
     const uint2 *in_meta;
     const uint32_t *in_pool;
     const uint32_t *bm_prev;       // A_{l-1} as bitmap
+    uint32_t *bm_cur;              // marks of A_l (written when discovering)
     const float *D;                // delta rows, indexed by vertex
     uint32_t ldd;                  // their row stride
     uint32_t d;
     float *X;
     const DevCtr *ctr;
     uint32_t l;
-    int mode, ratio;
+    int mode, ratio, allow_disc;
 };
 
-template <int NJ>
+template <int NJ, int DISC>
 __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
-    if (!rp_use_pull(a.ctr, a.l, a.d, a.mode, a.ratio)) return;
+    if (rp_hop_mode(a.ctr, a.l, a.d, a.mode, a.ratio, a.allow_disc) != (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL)) return;
     const uint32_t count = *a.count_ptr;
     if (count == 0) return;
     constexpr int G = (NJ >= 8) ? 2 : 16 / NJ;              // delta rows gathered per round trip
@@ -137,28 +128,67 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
     const uint32_t total = a.ioff[count];
     const uint32_t n_chunks = (total + PULL_CHUNK - 1) / PULL_CHUNK;
     const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
-    for (uint32_t c = gw; c < n_chunks; c += nw) {
+    const uint32_t per = (n_chunks + nw - 1) / nw;
+    const uint32_t c_begin = min(n_chunks, gw * per), c_end = min(n_chunks, c_begin + per);
+    if (c_begin >= c_end) return;
+    const uint32_t last = count - 1;
+    uint32_t i_lo = rp_seg_search(a.ioff, 0, last, c_begin * PULL_CHUNK);
+    // lane j describes row i_lo + j: destination, pool position of edge e is rbase + e (mod 2^32),
+    // and bnd = first edge of row i_lo + j + 1 (the total beyond the list's end)
+    uint32_t rv, rbase, bnd;
+    {
+        const uint32_t ri = min(last, i_lo + lane);
+        rv = a.list[ri];
+        rbase = a.in_meta[rv].x - a.ioff[ri];
+        bnd = a.ioff[min(count, i_lo + 1 + lane)];
+    }
+    for (uint32_t c = c_begin; c < c_end; ++c) {
         const uint32_t e0 = c * PULL_CHUNK, e1 = min(total, e0 + PULL_CHUNK);
-        const uint32_t i_lo = seg_search2(a.ioff, 0, count - 1, e0);
-        const uint32_t i_hi = seg_search2(a.ioff, i_lo, count - 1, e1 - 1);
-        // every lane resolves its T in-edges first (independent load chains), then the
-        // wavefront walks the dirty ones in edge order
-        uint32_t my_i[T], slot[T];
+        const bool fits = __shfl(bnd, 63) > e1 - 1;         // every row of the chunk is among the 64 held
+        uint32_t my_v[T], my_u[T];
         bool dirty[T];
+        uint32_t i_nx;
+        if (fits) {
 #pragma unroll
-        for (int t = 0; t < T; ++t) {
-            const uint32_t e = e0 + 64 * t + lane;
-            my_i[t] = 0;
-            slot[t] = 0;
-            dirty[t] = false;
-            if (e < e1) {
-                my_i[t] = (i_lo == i_hi) ? i_lo : seg_search2(a.ioff, i_lo, i_hi, e);
-                const uint32_t u = a.in_pool[a.in_meta[a.list[my_i[t]]].x + (e - a.ioff[my_i[t]])];
-                dirty[t] = (a.bm_prev[u >> 5] >> (u & 31)) & 1u;
-                slot[t] = u;
+            for (int t = 0; t < T; ++t) {
+                const uint32_t e = e0 + 64 * t + lane;
+                const int r = (int)min(63u, rp_count_le(bnd, e));
+                my_v[t] = __shfl(rv, r);
+                const uint32_t base = __shfl(rbase, r);
+                my_u[t] = 0;
+                dirty[t] = false;
+                if (e < e1) {
+                    my_u[t] = a.in_pool[base + e];
+                    dirty[t] = (a.bm_prev[my_u[t] >> 5] >> (my_u[t] & 31)) & 1u;
+                }
             }
+            i_nx = min(last, i_lo + rp_count_le(bnd, e1));
+        } else {
+            const uint32_t i_hi = rp_seg_forward(a.ioff, i_lo, last, e1 - 1);
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const uint32_t e = e0 + 64 * t + lane;
+                my_v[t] = 0;
+                my_u[t] = 0;
+                dirty[t] = false;
+                if (e < e1) {
+                    const uint32_t i = rp_seg_search(a.ioff, i_lo, i_hi, e);
+                    my_v[t] = a.list[i];
+                    my_u[t] = a.in_pool[a.in_meta[my_v[t]].x + (e - a.ioff[i])];
+                    dirty[t] = (a.bm_prev[my_u[t] >> 5] >> (my_u[t] & 31)) & 1u;
+                }
+            }
+            i_nx = rp_seg_forward(a.ioff, i_hi, last, e1);
         }
-        uint32_t cur = i_lo;
+        // rows of the next chunk: in flight while this chunk's messages are gathered
+        uint32_t rv_n, rbase_n, bnd_n;
+        {
+            const uint32_t ri = min(last, i_nx + lane);
+            rv_n = a.list[ri];
+            rbase_n = a.in_meta[rv_n].x - a.ioff[ri];
+            bnd_n = a.ioff[min(count, i_nx + 1 + lane)];
+        }
+        uint32_t cur = 0xFFFFFFFFu;                          // destination whose partial sum is held
         float acc[NJ];
 #pragma unroll
         for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
@@ -180,26 +210,29 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
                 float r[G][NJ];
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
-                    const uint32_t sk = __shfl(slot[t], kk[g]);
+                    const uint32_t uk = __shfl(my_u[t], kk[g]);
 #pragma unroll
                     for (int j = 0; j < NJ; ++j) {
                         const uint32_t col = lane + 64 * j;
-                        r[g][j] = (g < n && col < d) ? a.D[(size_t)sk * a.ldd + col] : 0.0f;
+                        r[g][j] = (g < n && col < d) ? a.D[(size_t)uk * a.ldd + col] : 0.0f;
                     }
                 }
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
                     if (g < n) {
-                        const uint32_t ik = __shfl(my_i[t], kk[g]);
-                        if (ik != cur) {                     // the destination changes: flush its partial sum
-                            float *xr = a.X + (size_t)a.list[cur] * d;
+                        const uint32_t vk = __shfl(my_v[t], kk[g]);
+                        if (vk != cur) {                     // the destination changes: flush its partial sum
+                            if (cur != 0xFFFFFFFFu) {
+                                float *xr = a.X + (size_t)cur * d;
 #pragma unroll
-                            for (int j = 0; j < NJ; ++j) {
-                                const uint32_t col = lane + 64 * j;
-                                if (col < d && acc[j] != 0.0f) unsafeAtomicAdd(&xr[col], acc[j]);
-                                acc[j] = 0.0f;
+                                for (int j = 0; j < NJ; ++j) {
+                                    const uint32_t col = lane + 64 * j;
+                                    if (col < d && acc[j] != 0.0f) unsafeAtomicAdd(&xr[col], acc[j]);
+                                    acc[j] = 0.0f;
+                                }
+                                if (DISC && lane == 0) rp_set_bit(a.bm_cur, cur);
                             }
-                            cur = ik;
+                            cur = vk;
                         }
 #pragma unroll
                         for (int j = 0; j < NJ; ++j) acc[j] += r[g][j];
@@ -207,23 +240,33 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
                 }
             }
         }
-        float *xr = a.X + (size_t)a.list[cur] * d;
+        if (cur != 0xFFFFFFFFu) {
+            float *xr = a.X + (size_t)cur * d;
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-            const uint32_t col = lane + 64 * j;
-            if (col < d && acc[j] != 0.0f) unsafeAtomicAdd(&xr[col], acc[j]);
+            for (int j = 0; j < NJ; ++j) {
+                const uint32_t col = lane + 64 * j;
+                if (col < d && acc[j] != 0.0f) unsafeAtomicAdd(&xr[col], acc[j]);
+            }
+            if (DISC && lane == 0) rp_set_bit(a.bm_cur, cur);
         }
+        i_lo = i_nx;
+        rv = rv_n;
+        rbase = rbase_n;
+        bnd = bnd_n;
     }
 }
 
-void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l) {
+// discover = false: pull into A_l (the hop's list). true: scan every live vertex (c->all_list and
+// c->ioff_all must have been produced by rp_launch_alive_list) and mark the receivers in bm[l].
+void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow_disc) {
     PullArgs a;
-    a.list = c->list[l];
-    a.count_ptr = &c->ctr->a[l];
-    a.ioff = c->ioff[l];
+    a.list = discover ? c->all_list : c->list[l];
+    a.count_ptr = discover ? &c->ctr->n_all : &c->ctr->a[l];
+    a.ioff = discover ? c->ioff_all : c->ioff[l];
     a.in_meta = c->in_meta;
     a.in_pool = c->in_pool;
     a.bm_prev = c->bm[l - 1];
+    a.bm_cur = c->bm[l];
     a.D = c->layers[l - 1].proj ? c->PD : c->D[(l - 1) & 1];
     a.d = c->xw[l];
     a.ldd = c->layers[l - 1].proj ? c->pd_ld : a.d;
@@ -232,12 +275,19 @@ void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l) {
     a.l = l;
     a.mode = c->opt_scatter;
     a.ratio = c->opt_pull_ratio;
+    a.allow_disc = allow_disc ? 1 : 0;
     dim3 grid(c->n_cu * 8), block(256);
-    if (a.d <= 64) hipLaunchKernelGGL(k_scatter_pull<1>, grid, block, 0, c->stream, a);
-    else if (a.d <= 128) hipLaunchKernelGGL(k_scatter_pull<2>, grid, block, 0, c->stream, a);
-    else if (a.d <= 256) hipLaunchKernelGGL(k_scatter_pull<4>, grid, block, 0, c->stream, a);
-    else if (a.d <= 512) hipLaunchKernelGGL(k_scatter_pull<8>, grid, block, 0, c->stream, a);
-    else hipLaunchKernelGGL(k_scatter_pull<16>, grid, block, 0, c->stream, a);
+#define PULL_CASE(NJ)                                                                            \
+    do {                                                                                         \
+        if (discover) hipLaunchKernelGGL((k_scatter_pull<NJ, 1>), grid, block, 0, c->stream, a); \
+        else hipLaunchKernelGGL((k_scatter_pull<NJ, 0>), grid, block, 0, c->stream, a);          \
+    } while (0)
+    if (a.d <= 64) PULL_CASE(1);
+    else if (a.d <= 128) PULL_CASE(2);
+    else if (a.d <= 256) PULL_CASE(4);
+    else if (a.d <= 512) PULL_CASE(8);
+    else PULL_CASE(16);
+#undef PULL_CASE
 }
 
 // ---------------------------------------------------------------------------------

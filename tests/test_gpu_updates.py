@@ -54,12 +54,12 @@ def test_vertex_additions_and_deletions(kind, widths):
         pair.close()
 
 
-@pytest.mark.parametrize("mode", [1, 2])
+@pytest.mark.parametrize("mode", [1, 2, 3])
 @pytest.mark.parametrize("kind,widths", [("sage_mean", (16, 40, 24, 10)), ("gcn_sum", (100, 256, 70)),
                                          ("gin_sum", (16, 32, 12, 6))])
 def test_push_and_pull_scatter_agree_with_oracle(mode, kind, widths):
-    """Both directions of the delta aggregation (float atomics from the sources; segmented
-    reduction over the destinations' in-rows) must give the same result."""
+    """Every way of moving the deltas (float atomics from the sources; segmented reduction over
+    the in-rows of A_l; one scan of all in-rows that also finds A_l) must give the same result."""
     print("case scatter mode", mode, kind, flush=True)
     pair, graph = make_pair(n=900, e=9000, d0=widths[0], kind=kind, widths=widths, seed=51, slack=128)
     rp.ripple_set_option(pair.ctx, rp.OPT_SCATTER_MODE, mode)
@@ -274,10 +274,12 @@ def test_graph_beyond_the_single_workgroup_compaction_limit():
                             slack=1000, top_share=0.005)
     stream = make_stream(pair, graph, MIXV, 92)
     try:
-        for b, bs in enumerate([1, 64, 2000]):
+        for b, bs in enumerate([1, 64, 2000, 500]):
             print(" batch", b, bs, flush=True)
+            if b == 3:                                        # live-vertex list through the same two passes
+                rp.ripple_set_option(pair.ctx, rp.OPT_SCATTER_MODE, 3)
             ops, payload, _ = stream.next_batch(bs)
-            pair.step(ops, payload, check=(b == 2))
+            pair.step(ops, payload, check=(b >= 2))
         pair.check_aggregates()
     finally:
         pair.close()
