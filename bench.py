@@ -31,32 +31,44 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def algorithmic_work(st, model, widths, store, L, layer_info):
+def algorithmic_work(st, model, widths, store, L, layer_info, n_edges=0):
     """Per (phase, layer): algorithmic bytes and flops summed over the timed batches.
 
     scatter(l):   every message row (delta, or projected delta) once, the walked rows' index
                   pairs and column ids once, and each distinct destination row of the cached
                   aggregate read and written once;
-    frontier(l):  index pairs + column ids of the walked out-rows, the list written;
+    frontier(l):  index pairs + column ids of the walked out-rows, the list written; not priced
+                  where the hop discovered A_l while scattering (messages * 4 >= edges, the
+                  library's own rule), since no frontier kernel runs there;
     transform(l): per dirty row the gathered input row, old H read, new H and delta written;
                   flops 2*K*d_out per row (plus the hidden stage for two-stage updates). For
                   project-first layers the projection of the hop's deltas (a_{l-1} rows) is
                   part of this class and the row transform reads h_self and the projected aggregate.
+                  Layers with a cached self term multiply h_self W_self on A_{l-1} only.
     """
     s_h = 2 if store == "bf16" else 4
     out = {}
     for l in range(1, L + 1):
         lay = model[l - 1]
         d_prev, d_out = widths[l - 1], widths[l]
-        w_agg, projected = layer_info[l]
+        w_agg, projected, self_cached = layer_info[l]
         a_prev, a_l, m_l, t_l = st.rows[l - 1], st.rows[l], st.msgs[l], st.touched[l]
         out[("scatter", l)] = dict(bytes=a_prev * w_agg * 4 + 8 * a_prev + 4 * m_l + 2 * t_l * w_agg * 4, flops=m_l * w_agg,
                                    # what a cache-less per-message scheme moves: one message row gathered per message
                                    msg_bytes=m_l * (w_agg * 4 + 4) + 2 * t_l * w_agg * 4)
-        out[("frontier", l)] = dict(bytes=8 * a_prev + 4 * m_l + 4 * a_l, flops=0)
+        discovered = l >= 2 and n_edges and m_l * 4 >= n_edges * max(st.batches, 1)
+        if not discovered:
+            out[("frontier", l)] = dict(bytes=8 * a_prev + 4 * m_l + 4 * a_l, flops=0)
         self_w = lay["d_in"] if lay["self"] != "none" else 0
         out_bytes = d_out * s_h * 2 + (d_out * 4 if l < L else 0) + 4
-        if projected:
+        if self_cached:
+            # self term refreshed on A_{l-1} (row in, d_out floats out); per dirty row the cached self
+            # term and the aggregate (projected, or multiplied by W_neigh here) are read
+            flops = 2 * a_prev * self_w * d_out + (2 * a_prev * d_prev * d_out if projected else 2 * a_l * d_prev * d_out)
+            nbytes = a_prev * (self_w * s_h + d_out * 4) + a_l * (d_out * 4 + w_agg * 4 + out_bytes)
+            if projected:
+                nbytes += a_prev * (d_prev * 4 + w_agg * 4)
+        elif projected:
             flops = 2 * a_l * self_w * d_out + 2 * a_prev * d_prev * d_out
             nbytes = a_l * (self_w * s_h + w_agg * 4 + out_bytes) + a_prev * (d_prev * 4 + w_agg * 4)
         else:
@@ -191,7 +203,7 @@ def main():
 
     L = len(model)
     layer_info = {l: rp.ripple_get_layer_info(ctx, l) for l in range(1, L + 1)}
-    work = algorithmic_work(st, model, cfg.widths, cfg.store, L, layer_info)
+    work = algorithmic_work(st, model, cfg.widths, cfg.store, L, layer_info, n_edges=res.n_edges)
     phase_idx = {"frontier": 2, "scatter": 3, "transform": 5}
     mfma_peak = MFMA_PEAK_TFLOPS["bf16" if (cfg.store == "bf16" and args.bf16_mfma) else "f32"]
     kernels = {}
@@ -212,6 +224,8 @@ def main():
     other = {name: st.ms[i][0] / max(st.batches, 1) for i, name in ((0, "ingest"), (1, "struct"), (7, "total"))}
     for l in range(1, L + 1):
         other[f"compact_l{l}"] = st.ms[4][l] / max(st.batches, 1)
+        if st.ms[6][l] > 0:
+            other[f"project_l{l}"] = st.ms[6][l] / max(st.batches, 1)
     dom = max(kernels, key=lambda k: kernels[k]["ms_per_launch"] * kernels[k]["launches"]) if kernels else None
     roofline = None
     if dom:

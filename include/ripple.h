@@ -122,8 +122,10 @@ typedef enum {
     RIPPLE_OPT_PULL_RATIO = 2,    /* auto mode pulls when messages * row_bytes * ratio >= 8 * scanned in-edges (default 2) */
     RIPPLE_OPT_BF16_MFMA = 4,     /* 0/1 (default 1): with bf16 storage, multiply on the bf16 matrix cores (fp32 accumulation);
                                      0 keeps the fp32 matrix path on bf16-rounded inputs */
-    RIPPLE_OPT_PROJECT_FIRST = 3  /* 0/1 (default 1), before load_model: layers with one linear map and d_out <= d_in/2
+    RIPPLE_OPT_PROJECT_FIRST = 3, /* 0/1 (default 1), before load_model: layers with one linear map and d_out <= d_in/2
                                      cache sum_u H[u] W_neigh instead of sum_u H[u] and scatter d_out-wide messages */
+    RIPPLE_OPT_SELF_CACHE = 5     /* 0/1 (default 1), before load_model: layers that concatenate the vertex's own embedding
+                                     (one linear map) keep H[v] W_self per vertex, recomputed only where H[v] changed */
 } ripple_option;
 
 /* Build the graph store and upload features (the state the paper's Sec. 3.1
@@ -170,9 +172,10 @@ ripple_status ripple_get_embeddings(ripple_ctx *ctx, uint32_t layer, const uint3
 ripple_status ripple_get_aggregates(ripple_ctx *ctx, uint32_t layer, const uint32_t *ids,
                                     uint32_t n_ids, float *out);
 
-/* Width of layer's cached aggregate rows and whether the layer is handled project-first
- * (either output pointer may be NULL). */
-ripple_status ripple_get_layer_info(ripple_ctx *ctx, uint32_t layer, uint32_t *aggregate_width, int *projected);
+/* Width of layer's cached aggregate rows and how the layer's linear map is split: *flags bit 0:
+ * handled project-first; bit 1: the self term H^{l-1}[v] W_self is cached per vertex and refreshed
+ * only where H^{l-1} changed (either output pointer may be NULL). */
+ripple_status ripple_get_layer_info(ripple_ctx *ctx, uint32_t layer, uint32_t *aggregate_width, int *flags);
 
 /* Vertices the last batch could affect at `layer` (0..L), ascending, into
  * ids_out (host, room for cap ids); *n_out receives the set size even when it

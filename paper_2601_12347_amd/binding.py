@@ -22,7 +22,7 @@ STATUS_NAMES = ["RIPPLE_OK", "RIPPLE_EINVAL", "RIPPLE_ESTATE", "RIPPLE_ECAPACITY
 RIPPLE_MAX_LAYERS = 8
 RIPPLE_N_PHASES = 8
 PHASES = ["ingest", "struct", "frontier", "scatter", "compact", "transform", "other", "total"]
-OPT_TIMING, OPT_SCATTER_MODE, OPT_PULL_RATIO, OPT_PROJECT_FIRST, OPT_BF16_MFMA = 0, 1, 2, 3, 4
+OPT_TIMING, OPT_SCATTER_MODE, OPT_PULL_RATIO, OPT_PROJECT_FIRST, OPT_BF16_MFMA, OPT_SELF_CACHE = 0, 1, 2, 3, 4, 5
 AGG = {"sum": 0, "mean": 1}
 SELF = {"none": 0, "concat": 1, "add": 2}
 ACT = {"none": 0, "relu": 1}
@@ -211,10 +211,10 @@ def ripple_get_aggregates(ctx, layer, width, ids=None, n_rows=None, out=None):
 
 
 def ripple_get_layer_info(ctx, layer):
-    """(width of the cached aggregate rows, handled project-first?)"""
+    """(width of the cached aggregate rows, handled project-first?, self term cached?)"""
     w, p = C.c_uint32(), C.c_int()
     _check(ctx, load_library().ripple_get_layer_info(ctx, layer, C.byref(w), C.byref(p)))
-    return w.value, bool(p.value)
+    return w.value, bool(p.value & 1), bool(p.value & 2)
 
 
 def ripple_get_affected(ctx, layer, cap):

@@ -246,7 +246,7 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
     }
     for (uint32_t l = 0; l < c->L; ++l) {
         LayerDev &ly = c->layers[l];
-        void *w[] = {ly.W0, ly.b0, ly.W1, ly.b1, ly.W0h, ly.W1h, ly.bzero, (ly.Wn != ly.W0) ? ly.Wn : nullptr};
+        void *w[] = {ly.W0, ly.b0, ly.W1, ly.b1, ly.W0h, ly.W1h, ly.bzero, (ly.Wn != ly.W0) ? ly.Wn : nullptr, ly.PS};
         for (void *p : w)
             if (p) hipFree(p);
     }
@@ -326,7 +326,8 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
         }
         // project first where the single linear map shrinks the row at least by half
         ly.proj = (c->opt_project && s.d_hidden == 0 && s.self_mode != RIPPLE_SELF_ADD && 2 * s.d_out <= s.d_in) ? 1u : 0u;
-        if (ly.proj) {
+        ly.selfc = (c->opt_selfcache && s.d_hidden == 0 && s.self_mode == RIPPLE_SELF_CONCAT) ? 1u : 0u;
+        if (ly.proj || ly.selfc) {
             std::vector<float> zeros(ly.N0pad, 0.0f);
             if (s.self_mode == RIPPLE_SELF_CONCAT) {           // rows d_in .. 2 d_in - 1 of W0
                 RP_TRY(upload_padded(c, s.W0 + (size_t)s.d_in * s.d_out, zeros.data(), s.d_in, s.d_out,
@@ -354,6 +355,7 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
         RP_HIP(c, hipMemsetAsync(h, 0, bytes, c->stream));
         c->xw[l] = c->layers[l - 1].proj ? c->d[l] : c->d[l - 1];
         RP_TRY(dev_alloc(c, &c->X[l], n * c->xw[l], true));
+        if (c->layers[l - 1].selfc) RP_TRY(dev_alloc(c, &c->layers[l - 1].PS, n * c->d[l], true));
     }
     RP_TRY(dev_alloc(c, &c->D[0], n * c->dmax, false));
     RP_TRY(dev_alloc(c, &c->D[1], n * c->dmax, false));
@@ -400,6 +402,7 @@ extern "C" ripple_status ripple_full_infer(ripple_ctx *c) {
     rp_launch_bitmap_to_list(c, c->bm[0], c->all_list, &c->ctr->a[0]);
     for (uint32_t l = 1; l <= c->L; ++l) {
         if (c->layers[l - 1].proj) rp_launch_project(c, l, c->all_list, &c->ctr->a[0], false);
+        if (c->layers[l - 1].selfc) rp_launch_self_project(c, l, c->all_list, &c->ctr->a[0]);
         rp_launch_pull_all(c, l);
         rp_launch_transform(c, l, c->all_list, &c->ctr->a[0], false);
     }
@@ -594,6 +597,11 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
             t = rp_timer_begin(c);
             rp_launch_project(c, l, c->list[l - 1], &c->ctr->a[l - 1], true);
             rp_timer_end(c, t, RIPPLE_PH_OTHER, (int)l);
+        }
+        if (c->layers[l - 1].selfc) {                  // H^{l-1} changed exactly on A_{l-1}
+            t = rp_timer_begin(c);
+            rp_launch_self_project(c, l, c->list[l - 1], &c->ctr->a[l - 1]);
+            rp_timer_end(c, t, RIPPLE_PH_OTHER, (int)l, !c->layers[l - 1].proj);
         }
         if (may_disc) {                                // scatters and marks A_l in one scan of all in-rows
             t = rp_timer_begin(c);
@@ -844,7 +852,7 @@ extern "C" ripple_status ripple_get_layer_info(ripple_ctx *c, uint32_t layer, ui
     if (c->state < 2) return fail(c, RIPPLE_ESTATE, "no model loaded");
     if (layer == 0 || layer > c->L) return fail(c, RIPPLE_EINVAL, "layer out of range");
     if (aggregate_width) *aggregate_width = c->xw[layer];
-    if (projected) *projected = (int)c->layers[layer - 1].proj;
+    if (projected) *projected = (int)(c->layers[layer - 1].proj | (c->layers[layer - 1].selfc << 1));
     return RIPPLE_OK;
 }
 
@@ -944,6 +952,10 @@ extern "C" ripple_status ripple_set_option(ripple_ctx *c, int option, int64_t va
     case RIPPLE_OPT_SCATTER_MODE:
         if (value < 0 || value > 3) return fail(c, RIPPLE_EINVAL, "scatter mode must be 0, 1, 2 or 3");
         c->opt_scatter = (int)value;
+        return RIPPLE_OK;
+    case RIPPLE_OPT_SELF_CACHE:
+        if (c->state != 1) return fail(c, RIPPLE_ESTATE, "the self-projection cache is chosen before load_model");
+        c->opt_selfcache = value ? 1 : 0;
         return RIPPLE_OK;
     case RIPPLE_OPT_BF16_MFMA:
         c->opt_bf16_mfma = value ? 1 : 0;

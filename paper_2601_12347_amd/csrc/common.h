@@ -59,6 +59,10 @@ struct LayerDev {
     uint32_t proj;
     float *Wn;                                // neighbour weights padded to [roundup(d_in,32) x N0pad] (may alias W0)
     float *bzero;                             // N0pad zeros
+    // concat layers with one linear map: PS[v] = H^{l-1}[v] W_self (d_out wide, fp32) is cached and
+    // refreshed only where H^{l-1} changed, so the row transform multiplies the aggregate alone
+    uint32_t selfc;
+    float *PS;
 };
 
 struct PhaseTimer;
@@ -141,6 +145,7 @@ struct ripple_ctx {
     int opt_scatter = 0;
     int opt_bf16_mfma = 1;                      // bf16 storage: multiply on the bf16 matrix cores
     int opt_project = 1;                        // allow project-first layers (read by load_model)
+    int opt_selfcache = 1;                      // allow cached self projections (read by load_model)
     int opt_pull_ratio = 2;                     // pull when messages * width * ratio >= scanned in-edges
     ripple_stats stats;
     PhaseTimer *timer = nullptr;

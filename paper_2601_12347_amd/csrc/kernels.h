@@ -27,6 +27,7 @@ void rp_launch_pull_all(ripple_ctx *c, uint32_t l);
 
 // transform.hip
 void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool emit_delta);
+void rp_launch_self_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d);
 void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool from_deltas);
 
 // api.hip: HIP-event timing of kernel classes (no-ops unless RIPPLE_OPT_TIMING is on)

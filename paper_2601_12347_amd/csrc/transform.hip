@@ -46,7 +46,9 @@ struct TArgs {
     uint32_t K, Kpad, N, Npad;
     int act;
     int out_mode;                  // 0 write act(z) to tmp_out[slot] | 1 update H, emit delta | 2 write to tmp_out[vertex]
-    const float *addend;           // projected aggregate [vertex x N] added (times the mean scale) before the activation, or null
+    const float *addend;           // [vertex x N] rows added before the activation (projected aggregate or cached self term), or null
+    int addend_scaled;             // 1: the addend is an aggregate and takes the mean scale
+    const float *addend2;          // second, unscaled addend (k_transform_addend_only), or null
     float *tmp_out;
     uint32_t tmp_out_ld;
     void *Hout;
@@ -154,7 +156,7 @@ __device__ __forceinline__ void epilogue(const TArgs &a, floatx16 (&acc)[TM][TN]
                     const size_t hidx = (size_t)s_vtx[lr] * a.N + col;
                     if (a.out_mode == 1)
                         o = a.store ? __bfloat162float(((const __hip_bfloat16 *)a.Hout)[hidx]) : ((const float *)a.Hout)[hidx];
-                    if (a.addend) ad = a.addend[hidx] * s_scale[lr];
+                    if (a.addend) ad = a.addend[hidx] * (a.addend_scaled ? s_scale[lr] : 1.0f);
                 }
                 old[sn][r] = o;
                 add[sn][r] = ad;
@@ -270,7 +272,7 @@ __device__ __forceinline__ void epilogue_staged(const TArgs &a, floatx16 (&acc)[
                 if (a.out_mode == 1)
                     old[u] = a.store ? ld4_bf16((const __hip_bfloat16 *)a.Hout + hidx, vec, nv[u])
                                      : ld4((const float *)a.Hout + hidx, vec, nv[u]);
-                if (a.addend) add[u] = ld4(a.addend + hidx, vec, nv[u]) * s_scale[r];
+                if (a.addend) add[u] = ld4(a.addend + hidx, vec, nv[u]) * (a.addend_scaled ? s_scale[r] : 1.0f);
             }
         }
 #pragma unroll
@@ -318,7 +320,8 @@ __device__ __forceinline__ void epilogue_staged(const TArgs &a, floatx16 (&acc)[
     }
 }
 
-// GraphConv handled project-first has no matrix product left per row: h = act(Y[v] * scale + b).
+// Project-first layers have no matrix product left per row: h = act(Y[v] * scale + PS[v] + b), with
+// Y the projected aggregate and PS the cached self term (absent for GraphConv).
 __global__ void k_transform_addend_only(TArgs a) {
     const uint32_t count = *a.count_ptr;
     const size_t total = (size_t)count * a.N, stride = (size_t)gridDim.x * blockDim.x;
@@ -332,6 +335,7 @@ __global__ void k_transform_addend_only(TArgs a) {
         }
         const size_t hidx = (size_t)v * a.N + col;
         float z = a.addend[hidx] * sc + a.bias[col];
+        if (a.addend2) z += a.addend2[hidx];
         if (a.act == RIPPLE_ACT_RELU) z = z > 0.0f ? z : 0.0f;
         float old;
         if (a.store) {
@@ -407,6 +411,13 @@ __global__ __launch_bounds__(256) void k_transform_f32(TArgs a) {
         const uint32_t c4a = (tid % (T_BK / 4)) * 4;       // (tid + i*256) % 8 is the same for every i
 
         floatx4 ra[STAGES][NA], rq[TWO ? STAGES : 1][TWO ? NA : 1], rb[NB];
+        // weights first, as in every step of the loop, so that one wait count fits both ways into it
+#pragma unroll
+        for (int i = 0; i < NB; ++i) {
+            const int idx = tid + i * 256;
+            const int kr = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
+            rb[i] = *(const floatx4 *)(a.W + (size_t)kr * a.Npad + n0 + c4);
+        }
 #pragma unroll
         for (int st = 0; st < STAGES; ++st)
 #pragma unroll
@@ -415,21 +426,22 @@ __global__ __launch_bounds__(256) void k_transform_f32(TArgs a) {
                 fetch_raw<MODE, STORE>(a, my_v[i], my_slot[i], (uint32_t)st * T_BK + c4a, ra[st][i], q);
                 if constexpr (TWO) rq[st][i] = q;
             }
-#pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            const int idx = tid + i * 256;
-            const int kr = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
-            rb[i] = *(const floatx4 *)(a.W + (size_t)kr * a.Npad + n0 + c4);
-        }
+        __builtin_amdgcn_sched_barrier(0);
 
-        for (uint32_t k0 = 0; k0 < a.Kpad; k0 += T_BK) {
+        // The staging registers rotate by unrolling (slot s of step s mod STAGES), not by moves: a move
+        // would have to wait for the load it copies.
+        for (uint32_t kbase = 0; kbase < a.Kpad; kbase += STAGES * T_BK) {
+#pragma unroll
+          for (int s = 0; s < STAGES; ++s) {
+            const uint32_t k0 = kbase + s * T_BK;
+            if (k0 >= a.Kpad) break;
             __syncthreads();                               // the matrix cores are done with the previous slice
 #pragma unroll
             for (int i = 0; i < NA; ++i) {
                 const int r = (tid + i * 256) / (T_BK / 4);
                 floatx4 q = (floatx4)(0.0f);
-                if constexpr (TWO) q = rq[0][i];
-                const floatx4 val = finish_raw<MODE, STORE>(a, ra[0][i], q, k0 + c4a, s_scale[r]);
+                if constexpr (TWO) q = rq[s][i];
+                const floatx4 val = finish_raw<MODE, STORE>(a, ra[s][i], q, k0 + c4a, s_scale[r]);
                 As[r][c4a + 0] = val.x;
                 As[r][c4a + 1] = val.y;
                 As[r][c4a + 2] = val.z;
@@ -442,13 +454,6 @@ __global__ __launch_bounds__(256) void k_transform_f32(TArgs a) {
                 *(floatx4 *)&Bs[kr][c4] = rb[i];
             }
             __syncthreads();
-#pragma unroll
-            for (int st = 0; st + 1 < STAGES; ++st)
-#pragma unroll
-                for (int i = 0; i < NA; ++i) {
-                    ra[st][i] = ra[st + 1][i];
-                    if constexpr (TWO) rq[st][i] = rq[st + 1][i];
-                }
             // memory returns loads in order: the weights (needed one step from now) are requested
             // before the rows (needed STAGES steps from now), so waiting for them leaves the rows in flight
             {                                              // weights of the next slice (last step re-reads its own: in bounds)
@@ -465,10 +470,13 @@ __global__ __launch_bounds__(256) void k_transform_f32(TArgs a) {
 #pragma unroll
                 for (int i = 0; i < NA; ++i) {
                     floatx4 q = (floatx4)(0.0f);
-                    fetch_raw<MODE, STORE>(a, my_v[i], my_slot[i], kn, ra[STAGES - 1][i], q);
-                    if constexpr (TWO) rq[STAGES - 1][i] = q;
+                    fetch_raw<MODE, STORE>(a, my_v[i], my_slot[i], kn, ra[s][i], q);
+                    if constexpr (TWO) rq[s][i] = q;
                 }
             }
+            // keep the requests above the matrix-core work: the scheduler would otherwise sink them to
+            // the end of the step, where nothing is left to hide their latency behind
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int kk = 0; kk < T_BK; kk += 2) {
                 const int kq = kk + (lane >> 5);
@@ -483,6 +491,7 @@ __global__ __launch_bounds__(256) void k_transform_f32(TArgs a) {
                     for (int j = 0; j < TN; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
             }
+          }
         }
         epilogue_staged<TM, TN, BM, BN>(a, acc, (float *)smem, s_vtx, s_scale, row0, count, n0, wm, wn, tid);
     }
@@ -643,6 +652,12 @@ __global__ __launch_bounds__(256) void k_transform_bf16(TArgs a) {
         floatx4 ra[STAGES][NA], rq[TWO ? STAGES : 1][TWO ? NA : 1];
         uintx4 rb[NB];
 #pragma unroll
+        for (int i = 0; i < NB; ++i) {                     // weights first, as in every step of the loop
+            const int idx = tid + i * 256;
+            const int n = idx / 4, kc = (idx % 4) * 8;
+            rb[i] = *(const uintx4 *)(a.Wt + (size_t)(n0 + n) * a.wt_ld + kc);
+        }
+#pragma unroll
         for (int st = 0; st < STAGES; ++st)
 #pragma unroll
             for (int i = 0; i < NA; ++i) {
@@ -650,21 +665,20 @@ __global__ __launch_bounds__(256) void k_transform_bf16(TArgs a) {
                 fetch_raw<MODE, STORE>(a, my_v[i], my_slot[i], (uint32_t)st * T_BK + c4a, ra[st][i], q);
                 if constexpr (TWO) rq[st][i] = q;
             }
-#pragma unroll
-        for (int i = 0; i < NB; ++i) {
-            const int idx = tid + i * 256;
-            const int n = idx / 4, kc = (idx % 4) * 8;
-            rb[i] = *(const uintx4 *)(a.Wt + (size_t)(n0 + n) * a.wt_ld + kc);
-        }
+        __builtin_amdgcn_sched_barrier(0);
 
-        for (uint32_t k0 = 0; k0 < a.Kpad; k0 += T_BK) {
+        for (uint32_t kbase = 0; kbase < a.Kpad; kbase += STAGES * T_BK) {    // staging registers rotate by unrolling
+#pragma unroll
+          for (int s = 0; s < STAGES; ++s) {
+            const uint32_t k0 = kbase + s * T_BK;
+            if (k0 >= a.Kpad) break;
             __syncthreads();
 #pragma unroll
             for (int i = 0; i < NA; ++i) {
                 const int r = (tid + i * 256) / (T_BK / 4);
                 floatx4 q = (floatx4)(0.0f);
-                if constexpr (TWO) q = rq[0][i];
-                const floatx4 val = finish_raw<MODE, STORE>(a, ra[0][i], q, k0 + c4a, s_scale[r]);
+                if constexpr (TWO) q = rq[s][i];
+                const floatx4 val = finish_raw<MODE, STORE>(a, ra[s][i], q, k0 + c4a, s_scale[r]);
                 uint2 pk;
                 pk.x = pack_bf16x2(val.x, val.y);
                 pk.y = pack_bf16x2(val.z, val.w);
@@ -677,13 +691,6 @@ __global__ __launch_bounds__(256) void k_transform_bf16(TArgs a) {
                 *(uintx4 *)&Bs[n][kc] = rb[i];
             }
             __syncthreads();
-#pragma unroll
-            for (int st = 0; st + 1 < STAGES; ++st)
-#pragma unroll
-                for (int i = 0; i < NA; ++i) {
-                    ra[st][i] = ra[st + 1][i];
-                    if constexpr (TWO) rq[st][i] = rq[st + 1][i];
-                }
             {
                 const uint32_t kb = min(k0 + T_BK, a.Kpad - T_BK);
 #pragma unroll
@@ -698,10 +705,11 @@ __global__ __launch_bounds__(256) void k_transform_bf16(TArgs a) {
 #pragma unroll
                 for (int i = 0; i < NA; ++i) {
                     floatx4 q = (floatx4)(0.0f);
-                    fetch_raw<MODE, STORE>(a, my_v[i], my_slot[i], kn, ra[STAGES - 1][i], q);
-                    if constexpr (TWO) rq[STAGES - 1][i] = q;
+                    fetch_raw<MODE, STORE>(a, my_v[i], my_slot[i], kn, ra[s][i], q);
+                    if constexpr (TWO) rq[s][i] = q;
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);             // requests stay above the matrix-core work
 #pragma unroll
             for (int kh = 0; kh < 2; ++kh) {
                 const int ko = kh * 16 + (lane >> 5) * 8;
@@ -718,6 +726,7 @@ __global__ __launch_bounds__(256) void k_transform_bf16(TArgs a) {
                     for (int j = 0; j < TN; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[i], bv[j], acc[i][j], 0, 0, 0);
             }
+          }
         }
         epilogue_staged<TM, TN, BM, BN>(a, acc, (float *)smem, s_vtx, s_scale, row0, count, n0, wm, wn, tid);
     }
@@ -797,6 +806,8 @@ static TArgs base_args(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
     a.tmp_out = nullptr;
     a.tmp_out_ld = 0;
     a.addend = nullptr;
+    a.addend_scaled = 1;
+    a.addend2 = nullptr;
     a.a_mode = 0;
     a.out_mode = 1;
     a.act = 0;
@@ -838,6 +849,25 @@ void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
     launch_t(c, a, ly.d_in % 4 == 0, from_deltas ? c->last_a[l - 1] : c->n_cap);
 }
 
+// Cached self term of layer l: PS[v] = H^{l-1}[v] W_self for the listed vertices (fp32, no bias).
+void rp_launch_self_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d) {
+    const LayerDev &ly = c->layers[l - 1];
+    TArgs a = base_args(c, l, list, count_d);
+    a.mean = 0;
+    a.W = ly.W0;                                   // W_self: the first d_in rows (the kernel zeroes k >= K)
+    a.Wt = nullptr;
+    a.bias = ly.bzero;
+    a.K = ly.d_in;
+    a.Kpad = rp_round_up(ly.d_in, 32);
+    a.act = RIPPLE_ACT_NONE;
+    a.a_mode = 4;
+    a.out_mode = 2;
+    a.tmp_out = ly.PS;
+    a.tmp_out_ld = ly.d_out;
+    a.Hout = nullptr;
+    launch_t(c, a, ly.d_in % 4 == 0, (list == c->all_list) ? c->n_cap : c->last_a[l - 1]);
+}
+
 // Re-apply layer l (1-based) to the vertices in `list` (count on the device).
 // emit_delta: write D^l (into the ping-pong buffer of parity l) for the next hop.
 void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool emit_delta) {
@@ -851,13 +881,26 @@ void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const 
     if (ly.proj) {                               // aggregate already multiplied by W_neigh: add it in the epilogue
         a.addend = c->X[l];
         a.act = (int)ly.act_out;
-        if (ly.self_mode == RIPPLE_SELF_NONE) {
+        if (ly.self_mode == RIPPLE_SELF_NONE || ly.selfc) {
+            a.addend2 = ly.selfc ? ly.PS : nullptr;
             hipLaunchKernelGGL(k_transform_addend_only, dim3(c->n_cu * 8), dim3(256), 0, c->stream, a);
             return;
         }
         a.a_mode = 4;                            // h_self * W_self: the first d_in rows of W0
         a.K = ly.d_in;
         a.Kpad = rp_round_up(ly.d_in, 32);
+        launch_t(c, a, vec_in, hint);
+        return;
+    }
+    if (ly.selfc) {                              // act((x * scale) W_neigh + PS[v] + b)
+        a.a_mode = 0;
+        a.W = ly.Wn;
+        a.Wt = nullptr;
+        a.K = ly.d_in;
+        a.Kpad = rp_round_up(ly.d_in, 32);
+        a.addend = ly.PS;
+        a.addend_scaled = 0;
+        a.act = (int)ly.act_out;
         launch_t(c, a, vec_in, hint);
         return;
     }

@@ -11,7 +11,8 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}      # max relative error per layer (metric: o
 
 
 class Pair:
-    def __init__(self, n, cap, src, dst, feats, model, store="f32", edge_capacity=None, project_first=True):
+    def __init__(self, n, cap, src, dst, feats, model, store="f32", edge_capacity=None, project_first=True,
+                 self_cache=True):
         self.n, self.cap, self.model, self.store = n, cap, model, store
         self.widths = [model[0]["d_in"]] + [l["d_out"] for l in model]
         self.L = len(model)
@@ -19,6 +20,8 @@ class Pair:
         self.ctx = rp.ripple_init_graph(n, cap, src, dst, feats, store=store, edge_capacity=edge_capacity)
         if not project_first:
             rp.ripple_set_option(self.ctx, rp.OPT_PROJECT_FIRST, 0)
+        if not self_cache:
+            rp.ripple_set_option(self.ctx, rp.OPT_SELF_CACHE, 0)
         rp.ripple_load_model(self.ctx, model)
         rp.ripple_full_infer(self.ctx)
 
@@ -48,7 +51,7 @@ class Pair:
         src, dst = self.ora.edges()
         for l in range(1, self.L + 1):
             h_prev = self.gpu_layer(l - 1).astype(np.float64)
-            width, projected = rp.ripple_get_layer_info(self.ctx, l)
+            width, projected, _ = rp.ripple_get_layer_info(self.ctx, l)
             if projected:                                     # the layer caches sum_u H[u] W_neigh
                 lay = self.model[l - 1]
                 w = np.asarray(lay["W0"], dtype=np.float64)
@@ -100,12 +103,12 @@ class Pair:
 
 
 def make_pair(n=300, e=1500, d0=12, kind="gcn_sum", widths=(12, 20, 8), store="f32", seed=0, slack=64,
-              gamma=2.1, top_share=0.03, edge_capacity=None, project_first=True):
+              gamma=2.1, top_share=0.03, edge_capacity=None, project_first=True, self_cache=True):
     src, dst, out_law, in_law = ri.chung_lu_graph(n, e, gamma, top_share, seed)
     feats = ri.features(n, d0, seed + 1)
     model = ri.make_model(kind, widths, seed + 2)
     pair = Pair(n, n + slack, src, dst, feats, model, store=store, edge_capacity=edge_capacity,
-                project_first=project_first)
+                project_first=project_first, self_cache=self_cache)
     return pair, (src, dst, out_law, in_law)
 
 

@@ -85,7 +85,7 @@ def test_project_first_layers(kind, widths, store, project_first):
     pair, graph = make_pair(n=800, e=7000, d0=widths[0], kind=kind, widths=widths, seed=61, slack=128, store=store,
                             project_first=project_first)
     L = len(widths) - 1
-    assert rp.ripple_get_layer_info(pair.ctx, L) == ((widths[-1], True) if project_first else (widths[-2], False))
+    assert rp.ripple_get_layer_info(pair.ctx, L)[:2] == ((widths[-1], True) if project_first else (widths[-2], False))
     stream = make_stream(pair, graph, MIXV, 63)
     try:
         pair.check_aggregates(tol=1e-3 if store == "bf16" else None)
@@ -94,6 +94,30 @@ def test_project_first_layers(kind, widths, store, project_first):
             ops, payload, _ = stream.next_batch(bs)
             pair.step(ops, payload)
         pair.check_graph()
+        pair.check_aggregates(tol=1e-3 if store == "bf16" else None)
+    finally:
+        pair.close()
+
+
+@pytest.mark.parametrize("store", ["f32", "bf16"])
+@pytest.mark.parametrize("self_cache", [True, False])
+@pytest.mark.parametrize("project_first", [True, False])
+def test_cached_self_projection(store, self_cache, project_first):
+    """Layers that concatenate the vertex's own embedding keep H[v] W_self per vertex and refresh it
+    only on A_{l-1}; with the cache switched off the full [h | x] product runs. Both must match the
+    oracle, with and without project-first on the narrow last layer."""
+    print("case self cache", store, self_cache, project_first, flush=True)
+    widths = (20, 48, 36, 12)
+    pair, graph = make_pair(n=700, e=6000, d0=widths[0], kind="sage_mean", widths=widths, seed=71, slack=128,
+                            store=store, project_first=project_first, self_cache=self_cache)
+    for l in range(1, 4):
+        assert rp.ripple_get_layer_info(pair.ctx, l)[2] == self_cache
+    stream = make_stream(pair, graph, MIXV, 73)
+    try:
+        for b, bs in enumerate([4, 70, 160]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload)
         pair.check_aggregates(tol=1e-3 if store == "bf16" else None)
     finally:
         pair.close()
