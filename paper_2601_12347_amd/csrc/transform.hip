@@ -23,6 +23,7 @@
 // (scaled for mean) to h_self W_self + b in the epilogue.
 #include "common.h"
 #include "kernels.h"
+#include <algorithm>
 
 typedef float floatx16 __attribute__((ext_vector_type(16)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));   // native vector: stays in registers
@@ -194,10 +195,7 @@ __device__ __forceinline__ void epilogue(const TArgs &a, floatx16 (&acc)[TM][TN]
     }
 }
 
-// Epilogue of the pipelined kernels: the accumulators are first laid out row-major in LDS (over the
-// A/B staging area, which is free by then), so that every thread handles four consecutive columns
-// of a row: 16-byte loads and stores when the row width is a multiple of four, element-wise
-// otherwise. Reads (old row, projected aggregate) of four such groups are issued before any store.
+// 16-byte (or element-wise, for rows whose width is not a multiple of four) accesses of the epilogues
 __device__ __forceinline__ floatx4 ld4(const float *p, bool vec, uint32_t n_valid) {
     if (vec) return *(const floatx4 *)p;
     floatx4 r = (floatx4)(0.0f);
@@ -234,11 +232,132 @@ __device__ __forceinline__ floatx4 ld4_bf16(const __hip_bfloat16 *p, bool vec, u
     return r;
 }
 
-template <int TM, int TN, int BM, int BN>
+// One round of the staged epilogue: U groups of four consecutive columns per thread. What the round
+// reads and writes is fixed at compile time, so that its loads form one branch-free batch (a branch
+// between two loads makes the second wait for the first):
+//   EPI 0: act(z) goes to tmp_out (by slot or by vertex); nothing is read
+//   EPI 1: H is updated;  EPI 2: H is updated and the delta row written
+//   VEC: 16-byte accesses (row widths that are multiples of four); BF: bf16 embeddings
+template <int BN, int U, bool VEC, int EPI, bool BF>
+struct EpiRound {
+    floatx4 old[U], add[U];
+    uint32_t nv[U];                                        // valid columns of the group (0: nothing to do)
+
+    // request the old row and the addend of round it0 (no stores in here). With VEC, groups that will
+    // not be stored read a valid address all the same (the row of vertex 0 for slots past the end, the
+    // row's last four columns for padded columns), and a missing addend reads the bias instead.
+    __device__ __forceinline__ void load(const TArgs &a, const uint32_t *s_vtx, const float *s_scale, uint32_t row0,
+                                         uint32_t count, uint32_t n0, int tid, int it0) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int idx = tid + (it0 + u) * 256;
+            const int r = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
+            const uint32_t col = n0 + c4;
+            nv[u] = (row0 + r < count && col < a.N) ? min(4u, a.N - col) : 0u;
+            old[u] = (floatx4)(0.0f);
+            add[u] = (floatx4)(0.0f);
+            if (EPI == 0) continue;
+            if (VEC) {
+                const uint32_t lcol = min(col, a.N - 4u);
+                const size_t hidx = (size_t)s_vtx[r] * a.N + lcol;
+                old[u] = BF ? ld4_bf16((const __hip_bfloat16 *)a.Hout + hidx, true, 4) : ld4((const float *)a.Hout + hidx, true, 4);
+                const float *ap = a.addend ? a.addend + hidx : a.bias + lcol;
+                const floatx4 t = ld4(ap, true, 4);
+                const float sc = a.addend ? (a.addend_scaled ? s_scale[r] : 1.0f) : 0.0f;
+                add[u] = a.addend ? t * sc : (floatx4)(0.0f);
+            } else if (nv[u]) {
+                const size_t hidx = (size_t)s_vtx[r] * a.N + col;
+                old[u] = BF ? ld4_bf16((const __hip_bfloat16 *)a.Hout + hidx, false, nv[u])
+                            : ld4((const float *)a.Hout + hidx, false, nv[u]);
+                if (a.addend) add[u] = ld4(a.addend + hidx, false, nv[u]) * (a.addend_scaled ? s_scale[r] : 1.0f);
+            }
+        }
+    }
+
+    // bias, addend, activation, delta, stores
+    __device__ __forceinline__ void finish(const TArgs &a, const float *Cs, const uint32_t *s_vtx, uint32_t row0,
+                                           uint32_t n0, int tid, int it0) const {
+        constexpr int C_LD = BN + 4;
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (!nv[u]) continue;
+            const int idx = tid + (it0 + u) * 256;
+            const int r = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
+            const uint32_t col = n0 + c4, slot = row0 + r;
+            floatx4 v = *(const floatx4 *)&Cs[r * C_LD + c4] + *(const floatx4 *)(a.bias + col) + add[u];   // bias is padded
+            if (a.act == RIPPLE_ACT_RELU) {
+                v.x = v.x > 0.0f ? v.x : 0.0f;
+                v.y = v.y > 0.0f ? v.y : 0.0f;
+                v.z = v.z > 0.0f ? v.z : 0.0f;
+                v.w = v.w > 0.0f ? v.w : 0.0f;
+            }
+            if (EPI == 0) {
+                const size_t orow = (a.out_mode == 0) ? slot : s_vtx[r];
+                st4(a.tmp_out + orow * a.tmp_out_ld + col, v, VEC, nv[u]);
+                continue;
+            }
+            const size_t hidx = (size_t)s_vtx[r] * a.N + col;
+            if (BF) {
+                uint2 w;
+                w.x = pack_bf16x2(v.x, v.y);
+                w.y = pack_bf16x2(v.z, v.w);
+                unsigned short *hp = (unsigned short *)a.Hout + hidx;
+                if (VEC) {
+                    *(uint2 *)hp = w;
+                } else {
+                    if (nv[u] > 0) hp[0] = (unsigned short)(w.x & 0xFFFFu);
+                    if (nv[u] > 1) hp[1] = (unsigned short)(w.x >> 16);
+                    if (nv[u] > 2) hp[2] = (unsigned short)(w.y & 0xFFFFu);
+                    if (nv[u] > 3) hp[3] = (unsigned short)(w.y >> 16);
+                }
+                v.x = bf_lo(w.x);
+                v.y = bf_hi(w.x);
+                v.z = bf_lo(w.y);
+                v.w = bf_hi(w.y);
+            } else {
+                st4((float *)a.Hout + hidx, v, VEC, nv[u]);
+            }
+            if (EPI == 2) st4(a.D + hidx, v - old[u], VEC, nv[u]);
+        }
+    }
+};
+
+// The global reads (old row, addend) run one round ahead of the stores: the first round is requested
+// while the accumulators settle in LDS, each later one before the previous round is finished, so that
+// only one memory round trip per tile is exposed.
+template <int BN, int ITER, int U, bool VEC, int EPI, bool BF>
+__device__ __forceinline__ void epilogue_rounds(const TArgs &a, const float *Cs, const uint32_t *s_vtx, const float *s_scale,
+                                                uint32_t row0, uint32_t count, uint32_t n0, int tid) {
+    EpiRound<BN, U, VEC, EPI, BF> ra, rb;
+    ra.load(a, s_vtx, s_scale, row0, count, n0, tid, 0);
+    __syncthreads();                                       // the tile is in LDS
+#pragma unroll 1
+    for (int it0 = 0; it0 < ITER; it0 += 2 * U) {
+        rb.load(a, s_vtx, s_scale, row0, count, n0, tid, it0 + U);
+        ra.finish(a, Cs, s_vtx, row0, n0, tid, it0);
+        if (it0 + 2 * U < ITER) ra.load(a, s_vtx, s_scale, row0, count, n0, tid, it0 + 2 * U);
+        rb.finish(a, Cs, s_vtx, row0, n0, tid, it0 + U);
+    }
+}
+
+template <int BN, int ITER, int U, bool VEC, bool BF>
+__device__ __forceinline__ void epilogue_pick(const TArgs &a, const float *Cs, const uint32_t *s_vtx, const float *s_scale,
+                                              uint32_t row0, uint32_t count, uint32_t n0, int tid) {
+    if (a.out_mode != 1) epilogue_rounds<BN, ITER, U, VEC, 0, BF>(a, Cs, s_vtx, s_scale, row0, count, n0, tid);
+    else if (a.D) epilogue_rounds<BN, ITER, U, VEC, 2, BF>(a, Cs, s_vtx, s_scale, row0, count, n0, tid);
+    else epilogue_rounds<BN, ITER, U, VEC, 1, BF>(a, Cs, s_vtx, s_scale, row0, count, n0, tid);
+}
+
+// Epilogue of the pipelined kernels: the accumulators are laid out row-major in LDS (over the A/B
+// staging area, which is free by then), so that every thread handles four consecutive columns of a
+// row. An addend is only read when H is updated (out_mode 1).
+template <int TM, int TN, int BM, int BN, bool BF>
 __device__ __forceinline__ void epilogue_staged(const TArgs &a, floatx16 (&acc)[TM][TN], float *Cs, const uint32_t *s_vtx,
                                                 const float *s_scale, uint32_t row0, uint32_t count, uint32_t n0, int wm,
                                                 int wn, int tid) {
     constexpr int C_LD = BN + 4;
+    constexpr int ITER = BM * BN / 4 / 256, U = 4;
+    static_assert(ITER % (2 * U) == 0, "tile size");
     const int lane = tid & 63;
     const bool vec = (a.N & 3u) == 0 && (a.out_mode == 1 || (a.tmp_out_ld & 3u) == 0);
     __syncthreads();                                       // every wavefront is done with the A/B slices
@@ -251,73 +370,8 @@ __device__ __forceinline__ void epilogue_staged(const TArgs &a, floatx16 (&acc)[
                 const int lr = (wm * TM + sm) * 32 + (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
                 Cs[lr * C_LD + (wn * TN + sn) * 32 + (lane & 31)] = acc[sm][sn][r];
             }
-    __syncthreads();
-    constexpr int ITER = BM * BN / 4 / 256, U = 4;
-    static_assert(ITER % U == 0, "tile size");
-#pragma unroll 1
-    for (int it0 = 0; it0 < ITER; it0 += U) {
-        floatx4 z[U], old[U], add[U];
-        uint32_t nv[U];                                    // valid columns of the group (0: nothing to do)
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int idx = tid + (it0 + u) * 256;
-            const int r = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
-            const uint32_t col = n0 + c4;
-            nv[u] = (row0 + r < count && col < a.N) ? min(4u, a.N - col) : 0u;
-            z[u] = *(const floatx4 *)&Cs[r * C_LD + c4];
-            old[u] = (floatx4)(0.0f);
-            add[u] = (floatx4)(0.0f);
-            if (nv[u]) {
-                const size_t hidx = (size_t)s_vtx[r] * a.N + col;
-                if (a.out_mode == 1)
-                    old[u] = a.store ? ld4_bf16((const __hip_bfloat16 *)a.Hout + hidx, vec, nv[u])
-                                     : ld4((const float *)a.Hout + hidx, vec, nv[u]);
-                if (a.addend) add[u] = ld4(a.addend + hidx, vec, nv[u]) * (a.addend_scaled ? s_scale[r] : 1.0f);
-            }
-        }
-#pragma unroll
-        for (int u = 0; u < U; ++u) {
-            if (!nv[u]) continue;
-            const int idx = tid + (it0 + u) * 256;
-            const int r = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
-            const uint32_t col = n0 + c4, slot = row0 + r;
-            floatx4 v = z[u] + *(const floatx4 *)(a.bias + col) + add[u];     // bias is padded: always 16-byte readable
-            if (a.act == RIPPLE_ACT_RELU) {
-                v.x = v.x > 0.0f ? v.x : 0.0f;
-                v.y = v.y > 0.0f ? v.y : 0.0f;
-                v.z = v.z > 0.0f ? v.z : 0.0f;
-                v.w = v.w > 0.0f ? v.w : 0.0f;
-            }
-            if (a.out_mode == 0) {
-                st4(a.tmp_out + (size_t)slot * a.tmp_out_ld + col, v, vec, nv[u]);
-            } else if (a.out_mode == 2) {
-                st4(a.tmp_out + (size_t)s_vtx[r] * a.tmp_out_ld + col, v, vec, nv[u]);
-            } else {
-                const size_t hidx = (size_t)s_vtx[r] * a.N + col;
-                if (a.store) {
-                    uint2 w;
-                    w.x = pack_bf16x2(v.x, v.y);
-                    w.y = pack_bf16x2(v.z, v.w);
-                    unsigned short *hp = (unsigned short *)a.Hout + hidx;
-                    if (vec) {
-                        *(uint2 *)hp = w;
-                    } else {
-                        if (nv[u] > 0) hp[0] = (unsigned short)(w.x & 0xFFFFu);
-                        if (nv[u] > 1) hp[1] = (unsigned short)(w.x >> 16);
-                        if (nv[u] > 2) hp[2] = (unsigned short)(w.y & 0xFFFFu);
-                        if (nv[u] > 3) hp[3] = (unsigned short)(w.y >> 16);
-                    }
-                    v.x = bf_lo(w.x);
-                    v.y = bf_hi(w.x);
-                    v.z = bf_lo(w.y);
-                    v.w = bf_hi(w.y);
-                } else {
-                    st4((float *)a.Hout + hidx, v, vec, nv[u]);
-                }
-                if (a.D) st4(a.D + hidx, v - old[u], vec, nv[u]);
-            }
-        }
-    }
+    if (vec) epilogue_pick<BN, ITER, U, true, BF>(a, Cs, s_vtx, s_scale, row0, count, n0, tid);
+    else epilogue_pick<BN, ITER, U, false, BF>(a, Cs, s_vtx, s_scale, row0, count, n0, tid);
 }
 
 // Project-first layers have no matrix product left per row: h = act(Y[v] * scale + PS[v] + b), with
@@ -354,7 +408,7 @@ __global__ void k_transform_addend_only(TArgs a) {
 }
 
 template <int WAVES_M, int WAVES_N, int TM, int TN, int STAGES, int MODE, int STORE>
-__global__ __launch_bounds__(256) void k_transform_f32(TArgs a) {
+__global__ __launch_bounds__(256, 2) void k_transform_f32(TArgs a) {
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
     constexpr int NA = BM / 32, NB = BN / 32;              // float4 per thread per slice (A, B)
     constexpr bool TWO = (MODE == 2) || (MODE == 1 && STORE == 1);
@@ -477,23 +531,33 @@ __global__ __launch_bounds__(256) void k_transform_f32(TArgs a) {
             // keep the requests above the matrix-core work: the scheduler would otherwise sink them to
             // the end of the step, where nothing is left to hide their latency behind
             __builtin_amdgcn_sched_barrier(0);
+            // operands of the next pair of k are read from LDS before the matrix cores take the
+            // current pair, so that no LDS round trip separates two groups of products
+            float av[2][TM], bv[2][TN];
+#pragma unroll
+            for (int i = 0; i < TM; ++i) av[0][i] = As[(wm * TM + i) * 32 + (lane & 31)][lane >> 5];
+#pragma unroll
+            for (int j = 0; j < TN; ++j) bv[0][j] = Bs[lane >> 5][(wn * TN + j) * 32 + (lane & 31)];
 #pragma unroll
             for (int kk = 0; kk < T_BK; kk += 2) {
-                const int kq = kk + (lane >> 5);
-                float av[TM], bv[TN];
+                const int cur = (kk >> 1) & 1, nxt = cur ^ 1;
+                if (kk + 2 < T_BK) {
+                    const int kq = kk + 2 + (lane >> 5);
 #pragma unroll
-                for (int i = 0; i < TM; ++i) av[i] = As[(wm * TM + i) * 32 + (lane & 31)][kq];
+                    for (int i = 0; i < TM; ++i) av[nxt][i] = As[(wm * TM + i) * 32 + (lane & 31)][kq];
 #pragma unroll
-                for (int j = 0; j < TN; ++j) bv[j] = Bs[kq][(wn * TN + j) * 32 + (lane & 31)];
+                    for (int j = 0; j < TN; ++j) bv[nxt][j] = Bs[kq][(wn * TN + j) * 32 + (lane & 31)];
+                }
+                __builtin_amdgcn_sched_barrier(0);         // the scheduler would move the reads back next to their use
 #pragma unroll
                 for (int i = 0; i < TM; ++i)
 #pragma unroll
                     for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[i], bv[j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][i], bv[cur][j], acc[i][j], 0, 0, 0);
             }
           }
         }
-        epilogue_staged<TM, TN, BM, BN>(a, acc, (float *)smem, s_vtx, s_scale, row0, count, n0, wm, wn, tid);
+        epilogue_staged<TM, TN, BM, BN, STORE != 0>(a, acc, (float *)smem, s_vtx, s_scale, row0, count, n0, wm, wn, tid);
     }
 }
 
@@ -593,7 +657,7 @@ typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 #define TB_LD 40                                            // LDS row stride in bf16 (80 bytes)
 
 template <int WAVES_M, int WAVES_N, int TM, int TN, int STAGES, int MODE>
-__global__ __launch_bounds__(256) void k_transform_bf16(TArgs a) {
+__global__ __launch_bounds__(256, 2) void k_transform_bf16(TArgs a) {
     constexpr int STORE = 1;
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
     constexpr int NA = BM / 32, NB = BN / 64;              // per thread per slice: float4 of A, 16-byte chunks of B
@@ -728,35 +792,46 @@ __global__ __launch_bounds__(256) void k_transform_bf16(TArgs a) {
             }
           }
         }
-        epilogue_staged<TM, TN, BM, BN>(a, acc, (float *)smem, s_vtx, s_scale, row0, count, n0, wm, wn, tid);
+        epilogue_staged<TM, TN, BM, BN, true>(a, acc, (float *)smem, s_vtx, s_scale, row0, count, n0, wm, wn, tid);
     }
 }
 
 // narrow: few rows expected. One workgroup then covers 128 rows x 64 columns and the columns are
 // spread over blockIdx.y, which shortens the serial chain of matrix-core work per tile fourfold.
+// The grid holds about one workgroup per expected tile (a grid-stride loop covers any excess):
+// workgroups that start at different times do not all sit in their memory phase at once, which a
+// grid of resident, persistent workgroups does.
+static uint32_t tile_grid(const ripple_ctx *c, uint32_t rows_hint, uint32_t bm, uint32_t floor_wg) {
+    const uint64_t want = ((uint64_t)rows_hint + rows_hint / 4) / bm + 1;
+    const uint64_t cap = (uint64_t)c->n_cap / bm + 1;
+    return (uint32_t)std::max<uint64_t>(floor_wg, std::min(want, cap));
+}
+
 template <int MODE>
-static void launch_bf16(ripple_ctx *c, const TArgs &a, bool narrow) {
-    const uint32_t gx = c->n_cu * 2;
+static void launch_bf16(ripple_ctx *c, const TArgs &a, bool narrow, uint32_t rows_hint) {
     if (a.Npad >= 256 && !narrow) {
-        hipLaunchKernelGGL((k_transform_bf16<1, 4, 2, 2, 3, MODE>), dim3(gx, a.Npad / 256), dim3(256), 0, c->stream, a);
+        hipLaunchKernelGGL((k_transform_bf16<1, 4, 2, 2, 3, MODE>), dim3(tile_grid(c, rows_hint, 64, c->n_cu * 2), a.Npad / 256),
+                           dim3(256), 0, c->stream, a);
     } else if (a.Npad == 128 && !narrow) {
-        hipLaunchKernelGGL((k_transform_bf16<2, 2, 2, 2, 3, MODE>), dim3(gx, 1), dim3(256), 0, c->stream, a);
-    } else {
-        hipLaunchKernelGGL((k_transform_bf16<4, 1, 1, 2, 3, MODE>), dim3(narrow ? c->n_cu : gx, a.Npad / 64), dim3(256), 0,
+        hipLaunchKernelGGL((k_transform_bf16<2, 2, 2, 2, 3, MODE>), dim3(tile_grid(c, rows_hint, 128, c->n_cu * 2), 1), dim3(256), 0,
                            c->stream, a);
+    } else {
+        hipLaunchKernelGGL((k_transform_bf16<4, 1, 1, 2, 3, MODE>),
+                           dim3(tile_grid(c, rows_hint, 128, narrow ? c->n_cu : c->n_cu * 2), a.Npad / 64), dim3(256), 0, c->stream, a);
     }
 }
 
 template <int MODE, int STORE>
-static void launch_fast(ripple_ctx *c, const TArgs &a, bool narrow) {
-    const uint32_t gx = c->n_cu * 2;
+static void launch_fast(ripple_ctx *c, const TArgs &a, bool narrow, uint32_t rows_hint) {
     if (a.Npad >= 256 && !narrow) {
-        hipLaunchKernelGGL((k_transform_f32<1, 4, 2, 2, 3, MODE, STORE>), dim3(gx, a.Npad / 256), dim3(256), 0, c->stream, a);
+        hipLaunchKernelGGL((k_transform_f32<1, 4, 2, 2, 3, MODE, STORE>), dim3(tile_grid(c, rows_hint, 64, c->n_cu * 2), a.Npad / 256),
+                           dim3(256), 0, c->stream, a);
     } else if (a.Npad == 128 && !narrow) {
-        hipLaunchKernelGGL((k_transform_f32<2, 2, 2, 2, 3, MODE, STORE>), dim3(gx, 1), dim3(256), 0, c->stream, a);
+        hipLaunchKernelGGL((k_transform_f32<2, 2, 2, 2, 3, MODE, STORE>), dim3(tile_grid(c, rows_hint, 128, c->n_cu * 2), 1), dim3(256),
+                           0, c->stream, a);
     } else {
-        hipLaunchKernelGGL((k_transform_f32<4, 1, 1, 2, 3, MODE, STORE>), dim3(narrow ? c->n_cu : gx, a.Npad / 64), dim3(256), 0,
-                           c->stream, a);
+        hipLaunchKernelGGL((k_transform_f32<4, 1, 1, 2, 3, MODE, STORE>),
+                           dim3(tile_grid(c, rows_hint, 128, narrow ? c->n_cu : c->n_cu * 2), a.Npad / 64), dim3(256), 0, c->stream, a);
     }
 }
 
@@ -771,9 +846,9 @@ static void launch_t(ripple_ctx *c, const TArgs &a, bool vec_ok, uint32_t rows_h
     }
 #define T_CASE(M)                                            \
     case M:                                                  \
-        if (a.store && a.Wt) launch_bf16<M>(c, a, narrow);   \
-        else if (a.store) launch_fast<M, 1>(c, a, narrow);   \
-        else launch_fast<M, 0>(c, a, narrow);                \
+        if (a.store && a.Wt) launch_bf16<M>(c, a, narrow, rows_hint);   \
+        else if (a.store) launch_fast<M, 1>(c, a, narrow, rows_hint);   \
+        else launch_fast<M, 0>(c, a, narrow, rows_hint);                \
         break;
     switch (a.a_mode) {
         T_CASE(0)
@@ -781,7 +856,8 @@ static void launch_t(ripple_ctx *c, const TArgs &a, bool vec_ok, uint32_t rows_h
         T_CASE(2)
         T_CASE(4)
     default:
-        launch_fast<3, 0>(c, a, narrow);                     // compact fp32 rows: storage type plays no part in the gather
+        if (a.store) launch_fast<3, 1>(c, a, narrow, rows_hint);   // compact fp32 rows; the storage type only shapes the epilogue
+        else launch_fast<3, 0>(c, a, narrow, rows_hint);
         break;
     }
 #undef T_CASE
