@@ -231,23 +231,34 @@ __device__ __forceinline__ int rp_hop_mode(const DevCtr *ctr, uint32_t l, uint32
     return (m > 0 && m * d * 4ull * (unsigned long long)ratio >= 8ull * ctr->isum[l]) ? RP_HOP_PULL : RP_HOP_PUSH;
 }
 
-// position of `target` in row[0..len), searched by one wavefront; -1 when absent.
-// Four 64-entry blocks are loaded per round so that long (hub) rows are not paced by one
+// position of `target` in row[0..len), searched by one wavefront; -1 when absent. Long (hub) rows
+// are read sixteen 64-entry blocks per round, short ones four, so that a row is not paced by one
 // memory round trip per 64 entries.
-__device__ __forceinline__ int rp_wave_find(const uint32_t *row, uint32_t len, uint32_t target) {
+template <int T>
+__device__ __forceinline__ int rp_wave_find_blocks(const uint32_t *row, uint32_t base, uint32_t len, uint32_t target) {
     const int lane = rp_lane();
-    for (uint32_t base = 0; base < len; base += 256) {
-        uint32_t v[4];
+    uint32_t v[T];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const uint32_t i = base + 64 * t + lane;
-            v[t] = (i < len) ? row[i] : RP_TOMB;            // a tombstone never equals a vertex id
-        }
+    for (int t = 0; t < T; ++t) {
+        const uint32_t i = base + 64 * t + lane;
+        v[t] = (i < len) ? row[i] : RP_TOMB;                // a tombstone never equals a vertex id
+    }
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const unsigned long long m = __ballot(v[t] == target);
-            if (m) return (int)(base + 64 * t + __ffsll((long long)m) - 1);
-        }
+    for (int t = 0; t < T; ++t) {
+        const unsigned long long m = __ballot(v[t] == target);
+        if (m) return (int)(base + 64 * t + __ffsll((long long)m) - 1);
+    }
+    return -1;
+}
+__device__ __forceinline__ int rp_wave_find(const uint32_t *row, uint32_t len, uint32_t target) {
+    uint32_t base = 0;
+    for (; base + 1024 <= len; base += 1024) {
+        const int p = rp_wave_find_blocks<16>(row, base, len, target);
+        if (p >= 0) return p;
+    }
+    for (; base < len; base += 256) {
+        const int p = rp_wave_find_blocks<4>(row, base, len, target);
+        if (p >= 0) return p;
     }
     return -1;
 }

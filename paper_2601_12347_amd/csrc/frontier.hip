@@ -13,7 +13,9 @@
 
 // mark the out-neighbours of every vertex of A_{l-1}. Every wavefront walks a contiguous run of
 // 256-edge chunks of the flattened out-edge space, so only its first chunk needs a search over the
-// whole list. Nothing to do on a discovering hop (the in-row scan finds A_l).
+// whole list; the 64 rows after the chunk's first one are described in registers (one per lane:
+// where the row's edges start in the pool, and the first edge of the next row) and an edge finds its
+// row with shuffles. Nothing to do on a discovering hop (the in-row scan finds A_l).
 __global__ __launch_bounds__(256) void k_frontier_mark(const uint32_t *list, const uint32_t *count_ptr,
                                                        const uint32_t *eoff, const uint2 *out_meta,
                                                        const uint32_t *out_pool, uint32_t *bm, const DevCtr *ctr,
@@ -21,6 +23,7 @@ __global__ __launch_bounds__(256) void k_frontier_mark(const uint32_t *list, con
     if (allow_disc && rp_hop_mode(ctr, l, d, mode, ratio, allow_disc) == RP_HOP_DISCOVER) return;
     const uint32_t count = *count_ptr;
     if (count == 0) return;
+    constexpr int T = MARK_CHUNK / 64;
     const int lane = rp_lane();
     const uint32_t M = eoff[count];
     const uint32_t n_chunks = (M + MARK_CHUNK - 1) / MARK_CHUNK;
@@ -30,24 +33,51 @@ __global__ __launch_bounds__(256) void k_frontier_mark(const uint32_t *list, con
     if (c_begin >= c_end) return;
     const uint32_t last = count - 1;
     uint32_t i_lo = rp_seg_search(eoff, 0, last, c_begin * MARK_CHUNK);
+    uint32_t rbase, bnd;                                    // lane j: row i_lo + j
+    {
+        const uint32_t ri = min(last, i_lo + lane);
+        rbase = out_meta[list[ri]].x - eoff[ri];            // pool position of edge e: rbase + e (mod 2^32)
+        bnd = eoff[min(count, i_lo + 1 + lane)];
+    }
     for (uint32_t c = c_begin; c < c_end; ++c) {
         const uint32_t e0 = c * MARK_CHUNK, e1 = min(M, e0 + MARK_CHUNK);
-        const uint32_t i_hi = rp_seg_forward(eoff, i_lo, last, e1 - 1);
-        // four independent edges per lane: their dependent load chains overlap
-        uint32_t v[MARK_CHUNK / 64];
+        const bool fits = __shfl(bnd, 63) > e1 - 1;         // every row of the chunk is among the 64 held
+        uint32_t v[T];
+        uint32_t i_nx;
+        if (fits) {
 #pragma unroll
-        for (int t = 0; t < MARK_CHUNK / 64; ++t) {
-            const uint32_t e = e0 + lane + 64 * t;
-            v[t] = 0xFFFFFFFFu;
-            if (e < e1) {
-                const uint32_t i = (i_lo == i_hi) ? i_lo : rp_seg_search(eoff, i_lo, i_hi, e);
-                v[t] = out_pool[out_meta[list[i]].x + (e - eoff[i])];
+            for (int t = 0; t < T; ++t) {
+                const uint32_t e = e0 + lane + 64 * t;
+                const int r = (int)min(63u, rp_count_le(bnd, e));
+                const uint32_t base = __shfl(rbase, r);
+                v[t] = (e < e1) ? out_pool[base + e] : 0xFFFFFFFFu;
             }
+            i_nx = min(last, i_lo + rp_count_le(bnd, e1));
+        } else {
+            const uint32_t i_hi = rp_seg_forward(eoff, i_lo, last, e1 - 1);
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const uint32_t e = e0 + lane + 64 * t;
+                v[t] = 0xFFFFFFFFu;
+                if (e < e1) {
+                    const uint32_t i = rp_seg_search(eoff, i_lo, i_hi, e);
+                    v[t] = out_pool[out_meta[list[i]].x + (e - eoff[i])];
+                }
+            }
+            i_nx = rp_seg_forward(eoff, i_hi, last, e1);
+        }
+        uint32_t rbase_n, bnd_n;                            // next chunk's rows, requested before the marks
+        {
+            const uint32_t ri = min(last, i_nx + lane);
+            rbase_n = out_meta[list[ri]].x - eoff[ri];
+            bnd_n = eoff[min(count, i_nx + 1 + lane)];
         }
 #pragma unroll
-        for (int t = 0; t < MARK_CHUNK / 64; ++t)
+        for (int t = 0; t < T; ++t)
             if (v[t] != 0xFFFFFFFFu) rp_set_bit(bm, v[t]);
-        i_lo = rp_seg_forward(eoff, i_hi, last, e1);
+        i_lo = i_nx;
+        rbase = rbase_n;
+        bnd = bnd_n;
     }
 }
 
@@ -78,6 +108,39 @@ __device__ __forceinline__ void word_degrees(const CompactArgs &a, uint32_t idx,
         if (a.want_in) din += a.in_meta[v].y;
     }
 }
+
+// Degrees of the vertices of one bitmap word, all requested before any is used (the loads are
+// unconditional: a vertex that is not in the word reads entry 0 and counts as zero).
+struct WordDeg {
+    uint32_t o[32], i[32];
+    __device__ __forceinline__ void gather(const CompactArgs &a, uint32_t idx, uint32_t w, uint32_t &dout, uint32_t &din) {
+        dout = din = 0;
+#pragma unroll
+        for (int b = 0; b < 32; ++b) {
+            const bool on = (w >> b) & 1u;
+            const uint32_t v = on ? idx * 32 + b : 0u;
+            const uint32_t x = a.out_meta[v].y, y = a.in_meta[v].y;
+            o[b] = (on && a.want_out) ? x : 0u;
+            i[b] = (on && a.want_in) ? y : 0u;
+            dout += o[b];
+            din += i[b];
+        }
+    }
+    // list entries and prefixes of the word's vertices, starting at position oc with running sums oo, oi
+    __device__ __forceinline__ void emit(const CompactArgs &a, uint32_t idx, uint32_t w, uint32_t &oc, uint32_t &oo,
+                                         uint32_t &oi) const {
+#pragma unroll
+        for (int b = 0; b < 32; ++b) {
+            if (!((w >> b) & 1u)) continue;
+            a.list[oc] = idx * 32 + b;
+            if (a.want_out) a.eoff[oc] = oo;
+            if (a.want_in) a.ioff[oc] = oi;
+            oo += o[b];
+            oi += i[b];
+            ++oc;
+        }
+    }
+};
 
 // pass 1: merge the root sets (S, V_added, and the previous hop's set when the layer has a
 // self term) into the layer's bitmap, restrict to live vertices, count vertices and
@@ -147,8 +210,9 @@ __global__ __launch_bounds__(256) void k_frontier_emit(CompactArgs a) {
     pi = sh[8] + sh[9] + sh[10] + sh[11];
     uint32_t idx = blockIdx.x * 256 + tid;
     uint32_t w = (idx < a.n_words) ? a.bm[idx] : 0u;
-    uint32_t cnt = __popc(w), dout, din;
-    word_degrees(a, idx, w, dout, din);
+    uint32_t cnt = __popc(w), dout = 0, din = 0;
+    WordDeg wd;
+    if (w) wd.gather(a, idx, w, dout, din);
     uint32_t ic = cnt, io = dout, ii = din;
     for (int o = 1; o < 64; o <<= 1) {
         uint32_t tc = __shfl_up(ic, o), to = __shfl_up(io, o), ti = __shfl_up(ii, o);
@@ -170,21 +234,7 @@ __global__ __launch_bounds__(256) void k_frontier_emit(CompactArgs a) {
         oo += wo[k];
         oi += wi[k];
     }
-    uint32_t t = w;
-    while (t) {
-        uint32_t v = idx * 32 + (__ffs(t) - 1);
-        t &= t - 1;
-        a.list[oc] = v;
-        if (a.want_out) {
-            a.eoff[oc] = oo;
-            oo += a.out_meta[v].y;
-        }
-        if (a.want_in) {
-            a.ioff[oc] = oi;
-            oi += a.in_meta[v].y;
-        }
-        ++oc;
-    }
+    if (w) wd.emit(a, idx, w, oc, oo, oi);
     if (blockIdx.x == gridDim.x - 1 && tid == 255) {     // the running values now hold the grand totals
         *a.count_out = oc;
         if (a.want_out) {
@@ -255,22 +305,11 @@ __global__ __launch_bounds__(1024) void k_frontier_compact_small(CompactArgs a) 
 #pragma unroll
     for (int k = 0; k < SMALL_WPT; ++k) {
         const uint32_t idx = w0 + k;
-        if ((uint32_t)k < wpt && idx < a.n_words) {
-            uint32_t t = words[k];
-            while (t) {
-                const uint32_t v = idx * 32 + (__ffs(t) - 1);
-                t &= t - 1;
-                a.list[oc] = v;
-                if (a.want_out) {
-                    a.eoff[oc] = oo;
-                    oo += a.out_meta[v].y;
-                }
-                if (a.want_in) {
-                    a.ioff[oc] = oi;
-                    oi += a.in_meta[v].y;
-                }
-                ++oc;
-            }
+        if ((uint32_t)k < wpt && idx < a.n_words && words[k]) {
+            WordDeg wd;
+            uint32_t d_o, d_i;
+            wd.gather(a, idx, words[k], d_o, d_i);
+            wd.emit(a, idx, words[k], oc, oo, oi);
         }
     }
     if (tid == 1023) {                                     // the last thread ends on the grand totals

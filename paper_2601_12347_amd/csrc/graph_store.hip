@@ -604,17 +604,40 @@ __global__ __launch_bounds__(256) void k_cleanup_rows(MutArgs a) {
             uint32_t dead = deadv[x], pend = pendv[x];
             uint32_t len = m.y;
             if (dead && len) {
-                uint32_t w = 0;
-                for (uint32_t base = 0; base < len; base += 64) {
-                    uint32_t i = base + lane;
-                    uint32_t val = (i < len) ? pool[m.x + i] : RP_TOMB;
-                    bool keep = val != RP_TOMB;
-                    unsigned long long mask = __ballot(keep);
-                    uint32_t off = (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-                    if (keep) pool[m.x + w + off] = val;
-                    w += (uint32_t)__popcll(mask);
+                // Rows are unordered, so holes in the part that stays (the first len - dead entries) are
+                // filled from the part that goes. First the live entries of that tail are packed to its
+                // front (it is at most `dead` long), then the head is read sixteen blocks per round and
+                // its k-th hole takes the tail's k-th live entry.
+                const uint32_t keep_len = len - min(dead, len);
+                uint32_t n_tail = 0;                               // live entries packed at keep_len ..
+                for (uint32_t base = keep_len; base < len; base += 64) {
+                    const uint32_t i = base + lane;
+                    const uint32_t val = (i < len) ? pool[m.x + i] : RP_TOMB;
+                    const bool keep = val != RP_TOMB;
+                    const unsigned long long mask = __ballot(keep);
+                    const uint32_t off = (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+                    if (keep) pool[m.x + keep_len + n_tail + off] = val;
+                    n_tail += (uint32_t)__popcll(mask);
                 }
-                len = w;
+                uint32_t filled = 0;                               // holes of the head filled so far
+                for (uint32_t base = 0; base < keep_len && filled < n_tail; base += 1024) {
+                    uint32_t v[16];
+#pragma unroll
+                    for (int t = 0; t < 16; ++t) {
+                        const uint32_t i = base + 64 * t + lane;
+                        v[t] = (i < keep_len) ? pool[m.x + i] : 0u;
+                    }
+#pragma unroll
+                    for (int t = 0; t < 16; ++t) {
+                        const uint32_t i = base + 64 * t + lane;
+                        const bool hole = i < keep_len && v[t] == RP_TOMB;
+                        const unsigned long long mask = __ballot(hole);
+                        const uint32_t k = filled + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+                        if (hole && k < n_tail) pool[m.x + i] = pool[m.x + keep_len + k];
+                        filled += (uint32_t)__popcll(mask);
+                    }
+                }
+                len = keep_len;
             }
             uint32_t need = len + pend;
             if (pend && need > capv[x]) {
@@ -623,7 +646,19 @@ __global__ __launch_bounds__(256) void k_cleanup_rows(MutArgs a) {
                 if (lane == 0) ns = atomicAdd(top, ncap);
                 ns = __shfl(ns, 0);
                 if ((unsigned long long)ns + ncap <= a.pool_cap) {
-                    for (uint32_t i = lane; i < len; i += 64) pool[ns + i] = pool[m.x + i];
+                    for (uint32_t base = 0; base < len; base += 512) {      // eight blocks in flight per round
+                        uint32_t v[8];
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) {
+                            const uint32_t i = base + 64 * t + lane;
+                            v[t] = (i < len) ? pool[m.x + i] : 0u;
+                        }
+#pragma unroll
+                        for (int t = 0; t < 8; ++t) {
+                            const uint32_t i = base + 64 * t + lane;
+                            if (i < len) pool[ns + i] = v[t];
+                        }
+                    }
                     m.x = ns;
                     if (lane == 0) capv[x] = ncap;
                 } else if (lane == 0) {
