@@ -235,8 +235,8 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
     hipStreamSynchronize(c->stream);
     void *ptrs[] = {c->out_meta, c->in_meta, c->out_capv, c->in_capv, c->vstate, c->pend_out, c->pend_in, c->dead_out,
                     c->dead_in, c->out_pool, c->in_pool, c->alive, c->part_cnt, c->part_deg, c->part_ideg, c->ioff[0], c->ctr, c->D[0], c->D[1],
-                    c->tmp, c->PD, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ioff_all, c->ops_d, c->payload_d,
-                    c->op_status, c->op_pos_out, c->op_pos_in, c->touch_out, c->touch_in, c->exp_kind, c->exp_a,
+                    c->tmp, c->PD, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ioff_all, c->mk, c->ops_d, c->payload_d,
+                    c->op_status, c->op_pos_out, c->op_pos_in, c->op_touch, c->touch_out, c->touch_in, c->exp_kind, c->exp_a,
                     c->exp_b, c->st_src, c->st_dst, c->st_sign, c->gather_d, c->gather_ids};
     for (void *p : ptrs)
         if (p) hipFree(p);
@@ -384,6 +384,11 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
     c->bm_sink = bmall + (size_t)(c->L + 1) * c->n_words;
     c->bm_vadd = bmall + (size_t)(c->L + 2) * c->n_words;
     RP_TRY(dev_alloc(c, &c->all_list, n + 1, true));
+    {
+        uint32_t *mkw = nullptr;                         // n_words * 32 bytes
+        RP_TRY(dev_alloc(c, &mkw, (size_t)c->n_words * 8, true));
+        c->mk = (uint8_t *)mkw;
+    }
     RP_TRY(dev_alloc(c, &c->ioff_all, n + 1, true));
     RP_HIP(c, hipStreamSynchronize(c->stream));
     c->state = 2;
@@ -521,7 +526,7 @@ static ripple_status ensure_batch_buffers(ripple_ctx *c, uint32_t n_ops, uint32_
         uint32_t cap = std::max<uint32_t>(std::max<uint32_t>(n_ops, c->ops_cap), 4096);
         cap = rp_round_up(cap + cap / 2, 1024);
         uint32_t exp = std::max<uint32_t>(std::max<uint32_t>(want_exp, c->exp_cap), 1u << 20);
-        void *old[] = {c->ops_d, c->op_status, c->op_pos_out, c->op_pos_in, c->touch_out, c->touch_in, c->exp_kind,
+        void *old[] = {c->ops_d, c->op_status, c->op_pos_out, c->op_pos_in, c->op_touch, c->touch_out, c->touch_in, c->exp_kind,
                        c->exp_a, c->exp_b, c->st_src, c->st_dst, c->st_sign};
         for (void *p : old)
             if (p) hipFree(p);
@@ -530,6 +535,7 @@ static ripple_status ensure_batch_buffers(ripple_ctx *c, uint32_t n_ops, uint32_
         RP_TRY(dev_alloc(c, &c->op_status, cap, true));
         RP_TRY(dev_alloc(c, &c->op_pos_out, cap, true));
         RP_TRY(dev_alloc(c, &c->op_pos_in, cap, true));
+        RP_TRY(dev_alloc(c, &c->op_touch, cap, true));
         RP_TRY(dev_alloc(c, &c->touch_out, (size_t)cap + exp, false));
         RP_TRY(dev_alloc(c, &c->touch_in, (size_t)cap + exp, false));
         RP_TRY(dev_alloc(c, &c->exp_kind, exp, false));

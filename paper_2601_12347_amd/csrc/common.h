@@ -102,6 +102,7 @@ struct ripple_ctx {
     // frontier
     uint32_t *bm[RIPPLE_MAX_LAYERS + 1] = {nullptr};    // dirty bitmap per layer
     uint32_t *bm_sink = nullptr, *bm_vadd = nullptr;    // S and V_added
+    uint8_t *mk = nullptr;                              // one byte per vertex: marks of the hop in progress (zero between hops)
     uint32_t *rep[RIPPLE_MAX_LAYERS + 1] = {nullptr};   // union over sub-batches (reporting)
     uint32_t *list[RIPPLE_MAX_LAYERS + 1] = {nullptr};  // A_l, ascending (l >= 1); op order for l = 0
     uint32_t *eoff[RIPPLE_MAX_LAYERS + 1] = {nullptr};  // exclusive scan of out-degrees over A_l, +1 entry
@@ -116,6 +117,7 @@ struct ripple_ctx {
     ripple_update *ops_d = nullptr;
     float *payload_d = nullptr;
     uint32_t *op_status = nullptr, *op_pos_out = nullptr, *op_pos_in = nullptr;
+    uint32_t *op_touch = nullptr;                        // per operation: accepted / add / first touch of its rows
     uint32_t *touch_out = nullptr, *touch_in = nullptr;  // touched row lists
     uint32_t touch_cap = 0;
     uint32_t exp_cap = 0;

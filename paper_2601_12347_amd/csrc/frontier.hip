@@ -18,7 +18,7 @@
 // row with shuffles. Nothing to do on a discovering hop (the in-row scan finds A_l).
 __global__ __launch_bounds__(256) void k_frontier_mark(const uint32_t *list, const uint32_t *count_ptr,
                                                        const uint32_t *eoff, const uint2 *out_meta,
-                                                       const uint32_t *out_pool, uint32_t *bm, const DevCtr *ctr,
+                                                       const uint32_t *out_pool, uint8_t *mk, const DevCtr *ctr,
                                                        uint32_t l, uint32_t d, int mode, int ratio, int allow_disc) {
     if (allow_disc && rp_hop_mode(ctr, l, d, mode, ratio, allow_disc) == RP_HOP_DISCOVER) return;
     const uint32_t count = *count_ptr;
@@ -74,7 +74,7 @@ __global__ __launch_bounds__(256) void k_frontier_mark(const uint32_t *list, con
         }
 #pragma unroll
         for (int t = 0; t < T; ++t)
-            if (v[t] != 0xFFFFFFFFu) rp_set_bit(bm, v[t]);
+            if (v[t] != 0xFFFFFFFFu) mk[v[t]] = 1;       // plain byte stores: idempotent, no atomics
         i_lo = i_nx;
         rbase = rbase_n;
         bnd = bnd_n;
@@ -82,7 +82,8 @@ __global__ __launch_bounds__(256) void k_frontier_mark(const uint32_t *list, con
 }
 
 struct CompactArgs {
-    uint32_t *bm;                  // the layer's bitmap: out-neighbour marks in, final set out
+    uint32_t *bm;                  // the layer's bitmap: marks in (a discovering hop sets them here), final set out
+    uint8_t *mk;                   // more marks, one byte per vertex (set by the out-edge walk, cleared here), or null
     const uint32_t *bm_prev;       // previous hop's set (layers with a self term) or null
     const uint32_t *bm_sink;       // S or null
     const uint32_t *bm_vadd;       // V_added (read only when bm_sink is set)
@@ -96,6 +97,21 @@ struct CompactArgs {
     uint32_t *list, *eoff, *ioff;  // outputs
     uint32_t *count_out, *msgs_out, *isum_out;
 };
+
+// bitmap word of 32 mark bytes (each 0 or 1); the bytes are cleared again when any was set
+__device__ __forceinline__ uint32_t take_marks(uint8_t *mk, uint32_t idx) {
+    uint4 *p = (uint4 *)(mk + (size_t)idx * 32);
+    const uint4 lo = p[0], hi = p[1];
+    const uint32_t d[8] = {lo.x, lo.y, lo.z, lo.w, hi.x, hi.y, hi.z, hi.w};
+    uint32_t w = 0;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) w |= (((d[k] * 0x00204081u) >> 21) & 0xFu) << (4 * k);   // bytes 0/1 -> four bits
+    if (w) {
+        p[0] = make_uint4(0, 0, 0, 0);
+        p[1] = make_uint4(0, 0, 0, 0);
+    }
+    return w;
+}
 
 __device__ __forceinline__ void word_degrees(const CompactArgs &a, uint32_t idx, uint32_t w, uint32_t &dout,
                                              uint32_t &din) {
@@ -152,7 +168,9 @@ __global__ __launch_bounds__(256) void k_frontier_count(CompactArgs a) {
     uint32_t w = 0, tch = 0;
     if (idx < a.n_words) {
         const uint32_t live = a.alive[idx];
-        w = a.bm[idx] & live;
+        w = a.bm[idx];
+        if (a.mk) w |= take_marks(a.mk, idx);
+        w &= live;
         tch = __popc(w);                         // vertices that received at least one message
         if (a.bm_sink) w |= (a.bm_sink[idx] | a.bm_vadd[idx]) & live;
         if (a.bm_prev) w |= a.bm_prev[idx] & live;
@@ -265,7 +283,9 @@ __global__ __launch_bounds__(1024) void k_frontier_compact_small(CompactArgs a) 
         const uint32_t idx = w0 + k;
         if ((uint32_t)k < wpt && idx < a.n_words) {
             const uint32_t live = a.alive[idx];
-            uint32_t w = a.bm[idx] & live;
+            uint32_t w = a.bm[idx];
+            if (a.mk) w |= take_marks(a.mk, idx);
+            w &= live;
             tch += __popc(w);
             if (a.bm_sink) w |= (a.bm_sink[idx] | a.bm_vadd[idx]) & live;
             if (a.bm_prev) w |= a.bm_prev[idx] & live;
@@ -374,7 +394,7 @@ __global__ __launch_bounds__(1024) void k_list_eoff(const uint32_t *list, const 
 
 void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l, bool allow_disc) {
     hipLaunchKernelGGL(k_frontier_mark, dim3(c->n_cu * 8), dim3(256), 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],
-                       c->eoff[l - 1], c->out_meta, c->out_pool, c->bm[l], c->ctr, l, c->xw[l], c->opt_scatter,
+                       c->eoff[l - 1], c->out_meta, c->out_pool, c->mk, c->ctr, l, c->xw[l], c->opt_scatter,
                        c->opt_pull_ratio, allow_disc ? 1 : 0);
 }
 
@@ -404,6 +424,7 @@ void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool 
                                 bool accumulate_rep) {
     CompactArgs a;
     a.bm = c->bm[l];
+    a.mk = c->mk;
     a.bm_prev = self_term ? c->bm[l - 1] : nullptr;
     a.bm_sink = c->bm_sink;
     a.bm_vadd = c->bm_vadd;

@@ -246,6 +246,8 @@ struct MutArgs {
     uint32_t n_ops;
     const float *payload;
     uint32_t *status, *pos_out, *pos_in;
+    uint32_t *op_touch;                          // bit 0 accepted edge op, 1 it is an add, 2 / 3 first touch of out-row(u) / in-row(v)
+    int defer_touch;                             // large batches: touched-row lists and counts come from k_touch_lists
     uint2 *out_meta, *in_meta;
     uint32_t *out_capv, *in_capv;
     uint32_t *out_pool, *in_pool;
@@ -312,10 +314,16 @@ __global__ __launch_bounds__(256) void k_edge_validate(MutArgs a) {
     for (uint32_t i = gw; i < a.n_ops; i += nw) {
         ripple_update op = a.ops[i];
         if (op.kind == RIPPLE_FEAT_UPDATE) {               // needs the live flag only
-            if (lane == 0) a.status[i] = rp_bit(a.alive, op.u) ? 1u : 0u;
+            if (lane == 0) {
+                a.status[i] = rp_bit(a.alive, op.u) ? 1u : 0u;
+                if (a.defer_touch) a.op_touch[i] = 0;
+            }
             continue;
         }
-        if (op.kind != RIPPLE_EDGE_ADD && op.kind != RIPPLE_EDGE_DEL) continue;
+        if (op.kind != RIPPLE_EDGE_ADD && op.kind != RIPPLE_EDGE_DEL) {
+            if (lane == 0 && a.defer_touch) a.op_touch[i] = 0;
+            continue;
+        }
         uint32_t u = op.u, v = op.v;
         bool ok = (rp_bit(a.alive, u) || (a.vstate[u] & VS_ADDING)) &&
                   (rp_bit(a.alive, v) || (a.vstate[v] & VS_ADDING));
@@ -338,22 +346,92 @@ __global__ __launch_bounds__(256) void k_edge_validate(MutArgs a) {
         }
         if (lane == 0) {
             a.status[i] = st;
+            uint32_t flags = 0;
             if (st) {
-                if (op.kind == RIPPLE_EDGE_ADD) {
+                const bool is_add = op.kind == RIPPLE_EDGE_ADD;
+                if (is_add) {
                     atomicAdd(&a.pend_out[u], 1u);
                     atomicAdd(&a.pend_in[v], 1u);
-                    atomicAdd(&a.ctr->n_add, 1u);
                 } else {
                     a.pos_out[i] = (uint32_t)po;
                     a.pos_in[i] = (uint32_t)pi;
                     atomicAdd(&a.dead_out[u], 1u);
                     atomicAdd(&a.dead_in[v], 1u);
-                    atomicAdd(&a.ctr->n_del, 1u);
                 }
-                touch_row(a, u, VS_TOUCH_OUT);
-                touch_row(a, v, VS_TOUCH_IN);
+                if (a.defer_touch) {
+                    // thousands of wavefronts bumping the same few counters would queue up behind one
+                    // another: only the per-row bits are set here, k_touch_lists builds lists and counts
+                    flags = 1u | (is_add ? 2u : 0u);
+                    if (!(atomicOr(&a.vstate[u], VS_TOUCH_OUT) & VS_TOUCH_OUT)) flags |= 4u;
+                    if (!(atomicOr(&a.vstate[v], VS_TOUCH_IN) & VS_TOUCH_IN)) flags |= 8u;
+                } else {
+                    atomicAdd(is_add ? &a.ctr->n_add : &a.ctr->n_del, 1u);
+                    touch_row(a, u, VS_TOUCH_OUT);
+                    touch_row(a, v, VS_TOUCH_IN);
+                }
             }
+            if (a.defer_touch) a.op_touch[i] = flags;
         }
+    }
+}
+
+// Touched-row lists and accepted add / delete counts of the edge operations, from the flags that
+// k_edge_validate left per operation: one workgroup, block-wide ranks instead of one atomic per row.
+__global__ __launch_bounds__(1024) void k_touch_lists(MutArgs a) {
+    __shared__ uint32_t s_o[16], s_i[16], s_a[16], s_d[16];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    uint32_t base_o = a.ctr->n_touch_out, base_i = a.ctr->n_touch_in;     // nothing else runs meanwhile
+    uint32_t adds = 0, dels = 0;                                            // per wavefront (lane 0 keeps them)
+    for (uint32_t start = 0; start < a.n_ops; start += 1024) {
+        const uint32_t i = start + tid;
+        const uint32_t f = (i < a.n_ops) ? a.op_touch[i] : 0u;
+        const unsigned long long mo = __ballot((f & 4u) != 0), mi = __ballot((f & 8u) != 0);
+        adds += (uint32_t)__popcll(__ballot((f & 3u) == 3u));
+        dels += (uint32_t)__popcll(__ballot((f & 3u) == 1u));
+        if (lane == 0) {
+            s_o[wave] = (uint32_t)__popcll(mo);
+            s_i[wave] = (uint32_t)__popcll(mi);
+        }
+        __syncthreads();
+        uint32_t off_o = 0, off_i = 0, tot_o = 0, tot_i = 0;
+        for (int k = 0; k < 16; ++k) {
+            if (k < wave) {
+                off_o += s_o[k];
+                off_i += s_i[k];
+            }
+            tot_o += s_o[k];
+            tot_i += s_i[k];
+        }
+        const unsigned long long below = (1ull << lane) - 1ull;
+        if (f & 4u) {
+            const uint32_t p = base_o + off_o + (uint32_t)__popcll(mo & below);
+            if (p < a.touch_cap) a.touch_out[p] = a.ops[i].u;
+            else a.ctr->error = 2;
+        }
+        if (f & 8u) {
+            const uint32_t p = base_i + off_i + (uint32_t)__popcll(mi & below);
+            if (p < a.touch_cap) a.touch_in[p] = a.ops[i].v;
+            else a.ctr->error = 2;
+        }
+        base_o += tot_o;
+        base_i += tot_i;
+        __syncthreads();                                    // s_o / s_i are rewritten by the next round
+    }
+    if (lane == 0) {
+        s_a[wave] = adds;
+        s_d[wave] = dels;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        uint32_t ta = 0, td = 0;
+        for (int k = 0; k < 16; ++k) {
+            ta += s_a[k];
+            td += s_d[k];
+        }
+        a.ctr->n_add += ta;
+        a.ctr->n_del += td;
+        a.ctr->n_touch_out = base_o;
+        a.ctr->n_touch_in = base_i;
     }
 }
 
@@ -769,6 +847,8 @@ static MutArgs make_args(ripple_ctx *c, uint32_t n_ops) {
     a.n_ops = n_ops;
     a.payload = c->payload_d;
     a.status = c->op_status;
+    a.op_touch = c->op_touch;
+    a.defer_touch = n_ops > 512 ? 1 : 0;
     a.pos_out = c->op_pos_out;
     a.pos_in = c->op_pos_in;
     a.out_meta = c->out_meta;
@@ -834,6 +914,7 @@ void rp_launch_mutate(ripple_ctx *c, uint32_t n_ops, bool has_vertex_add, bool h
     uint32_t big = c->n_cu * 8;
     if (has_vertex_add || has_vertex_del) hipLaunchKernelGGL(k_vertex_validate, dim3(tb), dim3(256), 0, s, a);
     hipLaunchKernelGGL(k_edge_validate, dim3(wb), dim3(256), 0, s, a);
+    if (a.defer_touch) hipLaunchKernelGGL(k_touch_lists, dim3(1), dim3(1024), 0, s, a);
     uint32_t touch_threads = 2 * n_ops;                               // validation touches <= n_ops rows per side
     hipLaunchKernelGGL(k_capacity, dim3(rp_div_up(touch_threads, 256)), dim3(256), 0, s, a);
     if (has_vertex_del) {

@@ -106,7 +106,7 @@ struct PullArgs {
     const uint2 *in_meta;
     const uint32_t *in_pool;
     const uint32_t *bm_prev;       // A_{l-1} as bitmap
-    uint32_t *bm_cur;              // marks of A_l (written when discovering)
+    uint32_t *bm_cur;              // bitmap of A_l: receivers are marked here when discovering
     const float *D;                // delta rows, indexed by vertex
     uint32_t ldd;                  // their row stride
     uint32_t d;
@@ -230,7 +230,7 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
                                     if (col < d && acc[j] != 0.0f) unsafeAtomicAdd(&xr[col], acc[j]);
                                     acc[j] = 0.0f;
                                 }
-                                if (DISC && lane == 0) rp_set_bit(a.bm_cur, cur);
+                                if (DISC && lane == 0) atomicOr(&a.bm_cur[cur >> 5], 1u << (cur & 31));   // once per receiver and chunk
                             }
                             cur = vk;
                         }
@@ -247,7 +247,7 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
                 const uint32_t col = lane + 64 * j;
                 if (col < d && acc[j] != 0.0f) unsafeAtomicAdd(&xr[col], acc[j]);
             }
-            if (DISC && lane == 0) rp_set_bit(a.bm_cur, cur);
+            if (DISC && lane == 0) atomicOr(&a.bm_cur[cur >> 5], 1u << (cur & 31));   // once per receiver and chunk
         }
         i_lo = i_nx;
         rv = rv_n;
