@@ -188,6 +188,8 @@ extern "C" ripple_status ripple_init_graph(ripple_ctx **out, uint32_t n_vertices
     RP_TRY(dev_alloc(c, &c->pend_in, n, true));
     RP_TRY(dev_alloc(c, &c->dead_out, n, true));
     RP_TRY(dev_alloc(c, &c->dead_in, n, true));
+    RP_TRY(dev_alloc(c, &c->hole_out, n, true));
+    RP_TRY(dev_alloc(c, &c->hole_in, n, true));
     RP_TRY(dev_alloc(c, &c->out_pool, (size_t)pool_cap, false));
     RP_TRY(dev_alloc(c, &c->in_pool, (size_t)pool_cap, false));
     RP_TRY(dev_alloc(c, &c->alive, (size_t)c->n_words, true));
@@ -234,7 +236,7 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
     if (!c) return;
     hipStreamSynchronize(c->stream);
     void *ptrs[] = {c->out_meta, c->in_meta, c->out_capv, c->in_capv, c->vstate, c->pend_out, c->pend_in, c->dead_out,
-                    c->dead_in, c->out_pool, c->in_pool, c->alive, c->part_cnt, c->part_deg, c->part_ideg, c->ioff[0], c->ctr, c->D[0], c->D[1],
+                    c->dead_in, c->hole_out, c->hole_in, c->out_pool, c->in_pool, c->alive, c->part_cnt, c->part_deg, c->part_ideg, c->ioff[0], c->ctr, c->D[0], c->D[1],
                     c->tmp, c->PD, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ioff_all, c->mk, c->ops_d, c->payload_d,
                     c->op_status, c->op_pos_out, c->op_pos_in, c->op_touch, c->touch_out, c->touch_in, c->exp_kind, c->exp_a,
                     c->exp_b, c->st_src, c->st_dst, c->st_sign, c->gather_d, c->gather_ids};

@@ -89,6 +89,7 @@ struct ripple_ctx {
     uint32_t *vstate = nullptr;                         // VS_* bits, zero between batches
     uint32_t *pend_out = nullptr, *pend_in = nullptr;   // appended this batch
     uint32_t *dead_out = nullptr, *dead_in = nullptr;   // tombstones this batch
+    uint32_t *hole_out = nullptr, *hole_in = nullptr;   // where a row's latest tombstone sits
 
     // embeddings and cached sums
     void *H[RIPPLE_MAX_LAYERS + 1] = {nullptr};

@@ -253,6 +253,7 @@ struct MutArgs {
     uint32_t *out_pool, *in_pool;
     uint32_t *alive, *vstate;
     uint32_t *pend_out, *pend_in, *dead_out, *dead_in;
+    uint32_t *hole_out, *hole_in;                // position of a row's latest tombstone (exact when the row has one)
     uint32_t *touch_out, *touch_in;
     uint32_t touch_cap;
     uint32_t *exp_kind, *exp_a, *exp_b;
@@ -550,6 +551,7 @@ __global__ __launch_bounds__(256) void k_expand_apply(MutArgs a) {
             if (lane == 0) {
                 if (p >= 0) {
                     a.in_pool[mi.x + p] = RP_TOMB;
+                    a.hole_in[y] = (uint32_t)p;
                     atomicAdd(&a.dead_in[y], 1u);
                     touch_row(a, y, VS_TOUCH_IN);
                 } else a.ctr->error = 4;
@@ -560,6 +562,7 @@ __global__ __launch_bounds__(256) void k_expand_apply(MutArgs a) {
             if (lane == 0) {
                 if (p >= 0) {
                     a.out_pool[mo.x + p] = RP_TOMB;
+                    a.hole_out[x] = (uint32_t)p;
                     atomicAdd(&a.dead_out[x], 1u);
                     touch_row(a, x, VS_TOUCH_OUT);
                 } else a.ctr->error = 5;
@@ -587,6 +590,8 @@ __global__ __launch_bounds__(256) void k_apply_edges(MutArgs a) {
     if (op.kind == RIPPLE_EDGE_DEL) {
         a.out_pool[a.out_meta[op.u].x + a.pos_out[i]] = RP_TOMB;
         a.in_pool[a.in_meta[op.v].x + a.pos_in[i]] = RP_TOMB;
+        a.hole_out[op.u] = a.pos_out[i];
+        a.hole_in[op.v] = a.pos_in[i];
     }
     if (s < a.struct_cap) {
         a.st_src[s] = op.u;
@@ -681,7 +686,12 @@ __global__ __launch_bounds__(256) void k_cleanup_rows(MutArgs a) {
             uint2 m = meta[x];
             uint32_t dead = deadv[x], pend = pendv[x];
             uint32_t len = m.y;
-            if (dead && len) {
+            const uint32_t hole = is_out ? a.hole_out[x] : a.hole_in[x];
+            if (dead == 1 && len && hole < len && pool[m.x + hole] == RP_TOMB) {
+                // the usual case, one deletion in the row: its position is known, the last entry fills it
+                if (hole != len - 1 && lane == 0) pool[m.x + hole] = pool[m.x + len - 1];
+                len -= 1;
+            } else if (dead && len) {
                 // Rows are unordered, so holes in the part that stays (the first len - dead entries) are
                 // filled from the part that goes. First the live entries of that tail are packed to its
                 // front (it is at most `dead` long), then the head is read sixteen blocks per round and
@@ -847,6 +857,8 @@ static MutArgs make_args(ripple_ctx *c, uint32_t n_ops) {
     a.n_ops = n_ops;
     a.payload = c->payload_d;
     a.status = c->op_status;
+    a.hole_out = c->hole_out;
+    a.hole_in = c->hole_in;
     a.op_touch = c->op_touch;
     a.defer_touch = n_ops > 512 ? 1 : 0;
     a.pos_out = c->op_pos_out;

@@ -376,35 +376,56 @@ __device__ __forceinline__ void epilogue_staged(const TArgs &a, floatx16 (&acc)[
 
 // Project-first layers have no matrix product left per row: h = act(Y[v] * scale + PS[v] + b), with
 // Y the projected aggregate and PS the cached self term (absent for GraphConv).
-__global__ void k_transform_addend_only(TArgs a) {
+template <bool BF>
+__device__ __forceinline__ void addend_only_rows(const TArgs &a) {
+    constexpr int R = 8;                                   // rows per wavefront and round: their loads overlap
     const uint32_t count = *a.count_ptr;
-    const size_t total = (size_t)count * a.N, stride = (size_t)gridDim.x * blockDim.x;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < total; i += stride) {
-        const uint32_t slot = (uint32_t)(i / a.N), col = (uint32_t)(i % a.N);
-        const uint32_t v = a.list[slot];
-        float sc = 1.0f;
-        if (a.mean) {
-            const uint32_t deg = a.in_meta[v].y;
-            sc = 1.0f / (float)(deg > 1u ? deg : 1u);
+    const int lane = threadIdx.x & 63;
+    const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    for (uint32_t s0 = gw * R; s0 < count; s0 += nw * R) {
+        uint32_t v[R];
+        float sc[R];
+#pragma unroll
+        for (int u = 0; u < R; ++u) v[u] = a.list[min(s0 + u, count - 1u)];
+#pragma unroll
+        for (int u = 0; u < R; ++u) {
+            const uint32_t deg = a.in_meta[v[u]].y;        // read in any case: no branch between the loads
+            sc[u] = a.mean ? 1.0f / (float)(deg > 1u ? deg : 1u) : 1.0f;
         }
-        const size_t hidx = (size_t)v * a.N + col;
-        float z = a.addend[hidx] * sc + a.bias[col];
-        if (a.addend2) z += a.addend2[hidx];
-        if (a.act == RIPPLE_ACT_RELU) z = z > 0.0f ? z : 0.0f;
-        float old;
-        if (a.store) {
-            __hip_bfloat16 *h = (__hip_bfloat16 *)a.Hout;
-            old = __bfloat162float(h[hidx]);
-            const __hip_bfloat16 zr = __float2bfloat16(z);
-            z = __bfloat162float(zr);
-            h[hidx] = zr;
-        } else {
-            float *h = (float *)a.Hout;
-            old = h[hidx];
-            h[hidx] = z;
+        const float *p2 = a.addend2 ? a.addend2 : a.addend;
+        const float w2 = a.addend2 ? 1.0f : 0.0f;
+        for (uint32_t col = lane; col < a.N; col += 64) {
+            float y[R], p[R], old[R];
+#pragma unroll
+            for (int u = 0; u < R; ++u) {                  // rows past the end repeat the last one and are not stored
+                const size_t hidx = (size_t)v[u] * a.N + col;
+                y[u] = a.addend[hidx];
+                p[u] = p2[hidx];                           // unconditional: a branch here would serialise the loads
+                old[u] = BF ? __bfloat162float(((const __hip_bfloat16 *)a.Hout)[hidx]) : ((const float *)a.Hout)[hidx];
+            }
+            const float b = a.bias[col];
+#pragma unroll
+            for (int u = 0; u < R; ++u) {
+                if (s0 + u >= count) continue;
+                const size_t hidx = (size_t)v[u] * a.N + col;
+                float z = y[u] * sc[u] + b + (w2 != 0.0f ? p[u] : 0.0f);
+                if (a.act == RIPPLE_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+                if (BF) {
+                    const __hip_bfloat16 zr = __float2bfloat16(z);
+                    z = __bfloat162float(zr);
+                    ((__hip_bfloat16 *)a.Hout)[hidx] = zr;
+                } else {
+                    ((float *)a.Hout)[hidx] = z;
+                }
+                if (a.D) a.D[hidx] = z - old[u];
+            }
         }
-        if (a.D) a.D[hidx] = z - old;
     }
+}
+
+__global__ __launch_bounds__(256) void k_transform_addend_only(TArgs a) {
+    if (a.store) addend_only_rows<true>(a);
+    else addend_only_rows<false>(a);
 }
 
 template <int WAVES_M, int WAVES_N, int TM, int TN, int STAGES, int MODE, int STORE>
