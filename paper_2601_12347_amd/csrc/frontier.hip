@@ -322,15 +322,16 @@ __global__ __launch_bounds__(1024) void k_frontier_compact_small(CompactArgs a) 
         oo += wo[k];
         oi += wi[k];
     }
-#pragma unroll
-    for (int k = 0; k < SMALL_WPT; ++k) {
+#pragma unroll 1
+    for (uint32_t k = 0; k < wpt; ++k) {                   // one copy of the (long, unrolled) word code
         const uint32_t idx = w0 + k;
-        if ((uint32_t)k < wpt && idx < a.n_words && words[k]) {
-            WordDeg wd;
-            uint32_t d_o, d_i;
-            wd.gather(a, idx, words[k], d_o, d_i);
-            wd.emit(a, idx, words[k], oc, oo, oi);
-        }
+        if (idx >= a.n_words) break;
+        const uint32_t w = a.bm[idx];                      // this thread's own store of the first loop
+        if (!w) continue;
+        WordDeg wd;
+        uint32_t d_o, d_i;
+        wd.gather(a, idx, w, d_o, d_i);
+        wd.emit(a, idx, w, oc, oo, oi);
     }
     if (tid == 1023) {                                     // the last thread ends on the grand totals
         *a.count_out = oc;
@@ -350,8 +351,10 @@ __global__ __launch_bounds__(1024) void k_frontier_compact_small(CompactArgs a) 
     }
 }
 
-static void launch_compact(ripple_ctx *c, const CompactArgs &a) {
-    if (a.n_words <= SMALL_WORDS) {
+// expect: how many vertices the list will probably hold. One workgroup writes a long list slowly
+// (its scattered stores all leave through one CU), so the single-launch kernel is kept for short ones.
+static void launch_compact(ripple_ctx *c, const CompactArgs &a, uint32_t expect) {
+    if (a.n_words <= SMALL_WORDS && expect <= 4096) {
         hipLaunchKernelGGL(k_frontier_compact_small, dim3(1), dim3(1024), 0, c->stream, a);
         return;
     }
@@ -415,7 +418,7 @@ void rp_launch_alive_list(ripple_ctx *c) {
     a.list = c->all_list;
     a.ioff = c->ioff_all;
     a.count_out = &c->ctr->n_all;
-    launch_compact(c, a);
+    launch_compact(c, a, c->n_cap);
 }
 
 // bitmap of layer l, merged with S, V_added (and A_{l-1} when self_term) -> list[l], ctr->a[l];
@@ -445,7 +448,7 @@ void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool 
     a.count_out = &c->ctr->a[l];
     a.msgs_out = (l < RIPPLE_MAX_LAYERS) ? &c->ctr->m[l + 1] : nullptr;
     a.isum_out = &c->ctr->isum[l];
-    launch_compact(c, a);
+    launch_compact(c, a, c->last_a[l]);
 }
 
 // any bitmap & alive -> ascending list in `out_list`, count in *count_d (device)
@@ -462,7 +465,7 @@ void rp_launch_bitmap_to_list(ripple_ctx *c, uint32_t *bitmap, uint32_t *out_lis
     a.part_in = c->part_ideg;
     a.list = out_list;
     a.count_out = count_d;
-    launch_compact(c, a);
+    launch_compact(c, a, c->n_cap);
 }
 
 void rp_launch_list_eoff(ripple_ctx *c, uint32_t l) {
