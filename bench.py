@@ -31,6 +31,15 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
+# HBM bytes per launch of the kernel classes of the default workload (dense_sage_mean, 10,000 updates per
+# batch), measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a 1 GiB copy of known size
+# (profiles/hbm_traffic_dense_sage_mean_bs10000_pmc.txt: FETCH_SIZE x 2.0, WRITE_SIZE x 1.0). bench.py cannot run
+# the profiler on itself; for any other workload `traffic` is null.
+MEASURED_TRAFFIC_BYTES = {
+    ("dense_sage_mean", 10000): {"scatter_l3": 19.0e9, "scatter_l2": 6.5e9, "transform_l2": 7.8e9, "transform_l3": 5.6e9},
+}
+
+
 def algorithmic_work(st, model, widths, store, L, layer_info, n_edges=0):
     """Per (phase, layer): algorithmic bytes and flops summed over the timed batches.
 
@@ -242,6 +251,10 @@ def main():
         else:
             roofline = {"kernel": dom, "bound": "hbm", "achieved": k["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": k["hbm_frac"], "traffic": None}
+    measured = MEASURED_TRAFFIC_BYTES.get((cfg.name, bs), {})
+    if roofline and dom in measured and args.scatter_mode == 0:
+        roofline["traffic"] = measured[dom]                 # bytes per launch; traffic / ms_per_launch is the HBM rate
+        roofline["traffic_GBps"] = measured[dom] / (kernels[dom]["ms_per_launch"] * 1e-3) / 1e9
     lat_ms = np.array(lat) * 1e3
     result = {
         "metric": "graph updates/sec (and p50 batch latency), 3-layer GraphSAGE-mean on a 2.45M-vertex/124M-edge graph"
