@@ -135,6 +135,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--scatter-mode", type=int, default=0)
     ap.add_argument("--pull-ratio", type=int, default=0)
+    ap.add_argument("--deterministic", action="store_true", help="bit-reproducible aggregation (RIPPLE_OPT_DETERMINISTIC)")
     ap.add_argument("--bf16-mfma", type=int, default=1, help="bf16 storage only: 0 = multiply on the fp32 matrix path")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="leave the library's per-kernel HIP events off (no roofline object; lowest latency)")
@@ -159,6 +160,8 @@ def main():
     t0 = time.time()
     ctx = rp.ripple_init_graph(cfg.n, cfg.vertex_capacity, src, dst, feats, store=cfg.store,
                                edge_capacity=cfg.edge_capacity)
+    if args.deterministic:
+        rp.ripple_set_option(ctx, rp.OPT_DETERMINISTIC, 1)
     rp.ripple_load_model(ctx, model)
     rp.ripple_full_infer(ctx)
     log(f"[bench] graph store built and bootstrap inference done in {time.time() - t0:.1f}s")
@@ -252,7 +255,7 @@ def main():
             roofline = {"kernel": dom, "bound": "hbm", "achieved": k["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": k["hbm_frac"], "traffic": None}
     measured = MEASURED_TRAFFIC_BYTES.get((cfg.name, bs), {})
-    if roofline and dom in measured and args.scatter_mode == 0:
+    if roofline and dom in measured and args.scatter_mode == 0 and not args.deterministic:
         roofline["traffic"] = measured[dom]                 # bytes per launch; traffic / ms_per_launch is the HBM rate
         roofline["traffic_GBps"] = measured[dom] / (kernels[dom]["ms_per_launch"] * 1e-3) / 1e9
     lat_ms = np.array(lat) * 1e3
@@ -267,7 +270,8 @@ def main():
                                f"widths {'->'.join(map(str, cfg.widths))}, {bs} updates/batch "
                                + ("(50% edge add, 30% edge delete, 20% feature update)" if not cfg.mix.get("vadd") else
                                   f"({cfg.mix['vadd']:.0%} vertex add, {cfg.mix['vdel']:.0%} vertex delete, rest 50/30/20 edge add/edge delete/feature update)"),
-                   "batch_size": bs, "updates_applied": int(applied)},
+                   "batch_size": bs, "updates_applied": int(applied),
+                   **({"aggregation": "deterministic"} if args.deterministic else {})},
         "per_batch": {"a_l": [st.rows[l] / max(st.batches, 1) for l in range(L + 1)],
                       "messages_l": [st.msgs[l] / max(st.batches, 1) for l in range(L + 1)],
                       "phase_ms": other},

@@ -124,8 +124,12 @@ typedef enum {
                                      0 keeps the fp32 matrix path on bf16-rounded inputs */
     RIPPLE_OPT_PROJECT_FIRST = 3, /* 0/1 (default 1), before load_model: layers with one linear map and d_out <= d_in/2
                                      cache sum_u H[u] W_neigh instead of sum_u H[u] and scatter d_out-wide messages */
-    RIPPLE_OPT_SELF_CACHE = 5     /* 0/1 (default 1), before load_model: layers that concatenate the vertex's own embedding
+    RIPPLE_OPT_SELF_CACHE = 5,    /* 0/1 (default 1), before load_model: layers that concatenate the vertex's own embedding
                                      (one linear map) keep H[v] W_self per vertex, recomputed only where H[v] changed */
+    RIPPLE_OPT_DETERMINISTIC = 6  /* 0/1 (default 0), before load_model: every aggregate row is produced by one owner that
+                                     adds its sources in a fixed order (no float atomics; rows with a changed in-edge are
+                                     recomputed from their in-neighbours), so that two runs over the same operations give
+                                     the same bits. Slower; switches project-first off. */
 } ripple_option;
 
 /* Build the graph store and upload features (the state the paper's Sec. 3.1

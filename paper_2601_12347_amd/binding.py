@@ -22,7 +22,7 @@ STATUS_NAMES = ["RIPPLE_OK", "RIPPLE_EINVAL", "RIPPLE_ESTATE", "RIPPLE_ECAPACITY
 RIPPLE_MAX_LAYERS = 8
 RIPPLE_N_PHASES = 8
 PHASES = ["ingest", "struct", "frontier", "scatter", "compact", "transform", "other", "total"]
-OPT_TIMING, OPT_SCATTER_MODE, OPT_PULL_RATIO, OPT_PROJECT_FIRST, OPT_BF16_MFMA, OPT_SELF_CACHE = 0, 1, 2, 3, 4, 5
+OPT_TIMING, OPT_SCATTER_MODE, OPT_PULL_RATIO, OPT_PROJECT_FIRST, OPT_BF16_MFMA, OPT_SELF_CACHE, OPT_DETERMINISTIC = 0, 1, 2, 3, 4, 5, 6
 AGG = {"sum": 0, "mean": 1}
 SELF = {"none": 0, "concat": 1, "add": 2}
 ACT = {"none": 0, "relu": 1}

@@ -327,7 +327,7 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
             RP_HIP(c, hipMemcpy(ly.W0h, wt.data(), wt.size() * 2, hipMemcpyHostToDevice));
         }
         // project first where the single linear map shrinks the row at least by half
-        ly.proj = (c->opt_project && s.d_hidden == 0 && s.self_mode != RIPPLE_SELF_ADD && 2 * s.d_out <= s.d_in) ? 1u : 0u;
+        ly.proj = (c->opt_project && !c->opt_deterministic && s.d_hidden == 0 && s.self_mode != RIPPLE_SELF_ADD && 2 * s.d_out <= s.d_in) ? 1u : 0u;
         ly.selfc = (c->opt_selfcache && s.d_hidden == 0 && s.self_mode == RIPPLE_SELF_CONCAT) ? 1u : 0u;
         if (ly.proj || ly.selfc) {
             std::vector<float> zeros(ly.N0pad, 0.0f);
@@ -410,7 +410,8 @@ extern "C" ripple_status ripple_full_infer(ripple_ctx *c) {
     for (uint32_t l = 1; l <= c->L; ++l) {
         if (c->layers[l - 1].proj) rp_launch_project(c, l, c->all_list, &c->ctr->a[0], false);
         if (c->layers[l - 1].selfc) rp_launch_self_project(c, l, c->all_list, &c->ctr->a[0]);
-        rp_launch_pull_all(c, l);
+        if (c->opt_deterministic) rp_launch_scatter_owner(c, l, true);     // same summation order as the batches use
+        else rp_launch_pull_all(c, l);
         rp_launch_transform(c, l, c->all_list, &c->ctr->a[0], false);
     }
     rp_launch_batch_reset(c);
@@ -587,6 +588,28 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
         hipLaunchKernelGGL(k_or_words, dim3(rp_div_up(c->n_words, 256)), dim3(256), 0, c->stream, c->rep[0], c->bm[0],
                            c->n_words);
     bool have_all = false;                              // live-vertex list of this piece exists
+    if (c->opt_deterministic) {                         // one owner per aggregate row, fixed summation order
+        for (uint32_t l = 1; l <= c->L; ++l) {
+            t = rp_timer_begin(c);
+            rp_launch_frontier_mark(c, l, false);
+            rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
+            t = rp_timer_begin(c);
+            rp_launch_frontier_compact(c, l, layer_self(c, l), l < c->L, true, multi);
+            rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l);
+            if (c->layers[l - 1].selfc) {
+                t = rp_timer_begin(c);
+                rp_launch_self_project(c, l, c->list[l - 1], &c->ctr->a[l - 1]);
+                rp_timer_end(c, t, RIPPLE_PH_OTHER, (int)l);
+            }
+            t = rp_timer_begin(c);
+            rp_launch_scatter_owner(c, l, false);
+            rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l);
+            t = rp_timer_begin(c);
+            rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], l < c->L);
+            rp_timer_end(c, t, RIPPLE_PH_TRANSFORM, (int)l);
+        }
+        return;
+    }
     for (uint32_t l = 1; l <= c->L; ++l) {
         // hop 1 always pushes: hop-0 rows are in operation order, not ranked by vertex id. Where the
         // previous batch pushed with a wide margin the pull kernel is not even enqueued (pushing is
@@ -960,6 +983,10 @@ extern "C" ripple_status ripple_set_option(ripple_ctx *c, int option, int64_t va
     case RIPPLE_OPT_SCATTER_MODE:
         if (value < 0 || value > 3) return fail(c, RIPPLE_EINVAL, "scatter mode must be 0, 1, 2 or 3");
         c->opt_scatter = (int)value;
+        return RIPPLE_OK;
+    case RIPPLE_OPT_DETERMINISTIC:
+        if (c->state != 1) return fail(c, RIPPLE_ESTATE, "the deterministic mode is chosen before load_model");
+        c->opt_deterministic = value ? 1 : 0;
         return RIPPLE_OK;
     case RIPPLE_OPT_SELF_CACHE:
         if (c->state != 1) return fail(c, RIPPLE_ESTATE, "the self-projection cache is chosen before load_model");

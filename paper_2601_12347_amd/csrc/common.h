@@ -149,6 +149,7 @@ struct ripple_ctx {
     int opt_bf16_mfma = 1;                      // bf16 storage: multiply on the bf16 matrix cores
     int opt_project = 1;                        // allow project-first layers (read by load_model)
     int opt_selfcache = 1;                      // allow cached self projections (read by load_model)
+    int opt_deterministic = 0;                  // bit-reproducible aggregation (owner kernels, no float atomics)
     int opt_pull_ratio = 2;                     // pull when messages * width * ratio >= scanned in-edges
     ripple_stats stats;
     PhaseTimer *timer = nullptr;

@@ -8,7 +8,6 @@
 #include "kernels.h"
 #include <cstring>
 
-#define seg_search rp_seg_search
 #define MARK_CHUNK 256
 
 // mark the out-neighbours of every vertex of A_{l-1}. Every wavefront walks a contiguous run of

@@ -935,6 +935,7 @@ void rp_launch_mutate(ripple_ctx *c, uint32_t n_ops, bool has_vertex_add, bool h
     }
     hipLaunchKernelGGL(k_apply_edges, dim3(tb), dim3(256), 0, s, a);
     int t = rp_timer_begin(c);
+    if (!c->opt_deterministic)                     // that mode recomputes the rows with a changed in-edge instead
     hipLaunchKernelGGL(k_struct_scatter, dim3(has_vertex_del ? big : std::min<uint32_t>(big, rp_div_up((uint64_t)n_ops * c->L, 4))),
                        dim3(256), 0, s, a);
     rp_timer_end(c, t, RIPPLE_PH_STRUCT, 0);

@@ -22,6 +22,7 @@ void rp_launch_list_eoff(ripple_ctx *c, uint32_t l);
 
 // scatter.hip
 void rp_launch_scatter_push(ripple_ctx *c, uint32_t l, bool may_pull, bool allow_disc);
+void rp_launch_scatter_owner(ripple_ctx *c, uint32_t l, bool bootstrap);
 void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow_disc);
 void rp_launch_pull_all(ripple_ctx *c, uint32_t l);
 

@@ -14,7 +14,6 @@
 #include "common.h"
 #include "kernels.h"
 
-#define seg_search2 rp_seg_search
 
 #define PUSH_CHUNK 64
 #define PULL_CHUNK 256
@@ -34,12 +33,12 @@ __global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, cons
     const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
     for (uint32_t c = gw; c < n_chunks; c += nw) {
         const uint32_t e0 = c * PUSH_CHUNK, e1 = min(M, e0 + PUSH_CHUNK);
-        const uint32_t i_lo = seg_search2(eoff, 0, count - 1, e0);
-        const uint32_t i_hi = seg_search2(eoff, i_lo, count - 1, e1 - 1);
+        const uint32_t i_lo = rp_seg_search(eoff, 0, count - 1, e0);
+        const uint32_t i_hi = rp_seg_search(eoff, i_lo, count - 1, e1 - 1);
         const uint32_t e = e0 + lane;
         uint32_t my_i = 0, my_v = 0;
         if (e < e1) {
-            my_i = seg_search2(eoff, i_lo, i_hi, e);
+            my_i = rp_seg_search(eoff, i_lo, i_hi, e);
             my_v = out_pool[out_meta[list[my_i]].x + (e - eoff[my_i])];
         }
         const int n_here = (int)(e1 - e0);
@@ -288,6 +287,251 @@ void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow
     else if (a.d <= 512) PULL_CASE(8);
     else PULL_CASE(16);
 #undef PULL_CASE
+}
+
+// ---------------------------------------------------------------------------------
+// deterministic aggregation: one owner per destination, sources in a fixed order
+// ---------------------------------------------------------------------------------
+// Float addition does not commute bit for bit, and neither the atomics of the kernels above nor the
+// order of a row's entries (which depends on the order concurrent appends landed in) is the same
+// from run to run. Here one team (a wavefront; a 16-wavefront workgroup for rows of more than OWN_LONG entries)
+// owns a destination of A_l: it collects the sources that contribute, sorts them by a fixed key,
+// adds their rows in that order and writes the row with plain stores, so the result is a function
+// of the graph and the embeddings alone. Destinations in S (a changed in-edge) or V_added are
+// recomputed from all their in-neighbours' current rows, which needs no pre-batch values and no
+// list of changed edges (the structural scatter is not run in this mode); the others add the delta
+// rows of their dirty in-neighbours.
+// The key is a bijective hash of the vertex id, so that rows longer than the sort buffer can be
+// taken in ascending key ranges of even population whatever the ids look like; if a range still
+// overflows, the row starts over with twice as many ranges.
+#define OWN_LONG 1024u
+
+__device__ __forceinline__ uint32_t own_key(uint32_t x) {       // bijection on 32 bits
+    x ^= x >> 16;
+    x *= 0x7feb352du;
+    x ^= x >> 15;
+    x *= 0x846ca68bu;
+    x ^= x >> 16;
+    return x;
+}
+__device__ __forceinline__ uint32_t own_unkey(uint32_t x) {     // its inverse
+    x ^= x >> 16;
+    x *= 0x43021123u;
+    x ^= (x >> 15) ^ (x >> 30);
+    x *= 0x1d69e2a5u;
+    x ^= x >> 16;
+    return x;
+}
+
+struct OwnerArgs {
+    const uint32_t *list;          // A_l (TEAM 1) or the queue of long rows (TEAM 16)
+    const uint32_t *count_ptr;
+    uint32_t *queue, *queue_count; // long rows met by the TEAM 1 kernel
+    const uint2 *in_meta;
+    const uint32_t *in_pool;
+    const uint32_t *bm_prev;       // A_{l-1}
+    const uint32_t *bm_sink, *bm_vadd;
+    const float *D;                // delta rows of layer l-1, by vertex
+    const void *Hprev;             // H^{l-1}
+    int store;
+    uint32_t d;                    // row width (of D, H^{l-1} and X^l)
+    float *X;
+    DevCtr *ctr;
+};
+
+template <int TEAM>
+__device__ __forceinline__ void own_sync() {
+    if (TEAM == 1) __builtin_amdgcn_wave_barrier();
+    else __syncthreads();
+}
+
+// TEAM wavefronts per destination; CAP keys in LDS per team
+template <int NJ, int TEAM>
+__global__ __launch_bounds__(TEAM == 1 ? 256 : 1024) void k_scatter_owner(OwnerArgs a) {
+    constexpr int G = (NJ <= 2) ? 16 : (NJ <= 4 ? 8 : 4);      // rows in flight per wavefront
+    constexpr uint32_t CAP = (TEAM == 1) ? 1024u : 16384u;
+    constexpr int TT = TEAM * 64;                              // threads per team
+    __shared__ uint32_t s_keys[(TEAM == 1 ? 4 : 1) * CAP];
+    __shared__ uint32_t s_n[4], s_over[4];
+    __shared__ float s_part[(TEAM == 1) ? 1 : TEAM * NJ * 64];
+    const uint32_t count = *a.count_ptr;
+    const int lane = rp_lane(), wave = threadIdx.x >> 6;
+    const int tt = (TEAM == 1) ? lane : (int)threadIdx.x;     // thread within the team
+    const int slot = (TEAM == 1) ? wave : 0;                   // the team's counters
+    uint32_t *buf = s_keys + (TEAM == 1 ? wave * CAP : 0);
+    const uint32_t d = a.d;
+    const uint32_t team = (TEAM == 1) ? ((blockIdx.x * blockDim.x + threadIdx.x) >> 6) : blockIdx.x;
+    const uint32_t n_teams = (TEAM == 1) ? ((gridDim.x * blockDim.x) >> 6) : gridDim.x;
+    for (uint32_t i = team; i < count; i += n_teams) {
+        const uint32_t v = a.list[i];
+        const uint2 m = a.in_meta[v];
+        if (TEAM == 1 && m.y > OWN_LONG) {                     // left to the workgroup kernel
+            if (lane == 0) a.queue[atomicAdd(a.queue_count, 1u)] = v;
+            continue;
+        }
+        const bool recompute = rp_bit(a.bm_sink, v) || rp_bit(a.bm_vadd, v);
+        uint32_t bits = 0;                                     // 2^bits key ranges
+        while (((unsigned long long)(CAP / 4) << bits) < m.y) ++bits;
+        float acc[NJ];
+        for (;;) {                                             // until no range overflows
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
+            bool overflow = false;
+            for (uint32_t r = 0; r < (1u << bits) && !overflow; ++r) {
+                if (tt == 0) {
+                    s_n[slot] = 0;
+                    s_over[slot] = 0;
+                }
+                own_sync<TEAM>();
+                // collect the keys of the contributing sources that fall into range r, four blocks of the row per round
+                for (uint32_t base = 0; base < m.y; base += 4 * TT) {
+                    uint32_t key[4];
+                    bool take[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const uint32_t e = base + q * TT + tt;
+                        take[q] = false;
+                        key[q] = 0;
+                        if (e < m.y) {
+                            const uint32_t u = a.in_pool[m.x + e];
+                            key[q] = own_key(u);
+                            take[q] = (bits == 0 || (key[q] >> (32 - bits)) == r) && (recompute || rp_bit(a.bm_prev, u));
+                        }
+                    }
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const unsigned long long mask = __ballot(take[q]);
+                        if (!mask) continue;
+                        const uint32_t k = (uint32_t)__popcll(mask);
+                        uint32_t pos = 0;
+                        if (lane == 0) pos = atomicAdd(&s_n[slot], k);
+                        pos = __shfl(pos, 0);
+                        if (pos + k > CAP) {
+                            if (lane == 0) s_over[slot] = 1;
+                        } else if (take[q]) {
+                            buf[pos + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull))] = key[q];
+                        }
+                    }
+                }
+                own_sync<TEAM>();
+                const bool over = s_over[slot] != 0;
+                const uint32_t n = s_n[slot];
+                own_sync<TEAM>();                              // everyone has read the counters before they are reset
+                if (over) {
+                    overflow = true;
+                    break;
+                }
+                // ascending sort (bitonic, padded to a power of two)
+                uint32_t p2 = 64;
+                while (p2 < n) p2 <<= 1;
+                for (uint32_t x = n + tt; x < p2; x += TT) buf[x] = 0xFFFFFFFFu;
+                for (uint32_t k2 = 2; k2 <= p2 && n > 1; k2 <<= 1)
+                    for (uint32_t j2 = k2 >> 1; j2 > 0; j2 >>= 1) {
+                        own_sync<TEAM>();
+                        for (uint32_t x = tt; x < p2; x += TT) {
+                            const uint32_t y = x ^ j2;
+                            if (y > x) {
+                                const uint32_t kx = buf[x], ky = buf[y];
+                                if ((kx > ky) == ((x & k2) == 0)) {
+                                    buf[x] = ky;
+                                    buf[y] = kx;
+                                }
+                            }
+                        }
+                    }
+                own_sync<TEAM>();
+                // add the rows in key order: a wavefront takes every TEAM-th one, G in flight
+                float part[NJ];
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) part[j] = 0.0f;
+                for (uint32_t j0 = (uint32_t)(TEAM == 1 ? 0 : wave); j0 < n; j0 += G * TEAM) {
+                    float rr[G][NJ];
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        const uint32_t idx = j0 + g * TEAM;
+                        const uint32_t u = own_unkey(buf[min(idx, n - 1)]);
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j) {
+                            const uint32_t col = lane + 64 * j;
+                            float x = 0.0f;
+                            if (idx < n && col < d)
+                                x = recompute ? rp_load_h(a.Hprev, a.store, (size_t)u * d + col) : a.D[(size_t)u * d + col];
+                            rr[g][j] = x;
+                        }
+                    }
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j) part[j] += rr[g][j];
+                }
+                if (TEAM == 1) {
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) acc[j] += part[j];
+                } else {                                       // the wavefronts' partial sums, always combined in the same order
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) s_part[(wave * NJ + j) * 64 + lane] = part[j];
+                    __syncthreads();
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) {
+                        float t = s_part[j * 64 + lane];
+                        for (int w = 1; w < TEAM; ++w) t += s_part[(w * NJ + j) * 64 + lane];
+                        acc[j] += t;
+                    }
+                }
+                own_sync<TEAM>();
+            }
+            if (!overflow) break;
+            if (++bits > 24) {                                 // cannot happen with distinct ids in a row
+                if (tt == 0) a.ctr->error = 9;
+                break;
+            }
+        }
+        if (TEAM == 1 || wave == 0) {
+            float *xr = a.X + (size_t)v * d;
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const uint32_t col = lane + 64 * j;
+                if (col < d) xr[col] = recompute ? acc[j] : xr[col] + acc[j];
+            }
+        }
+    }
+}
+
+// every destination of A_l by a wavefront, the long rows among them afterwards by a workgroup each.
+// bootstrap: every live vertex (listed in c->all_list, count in ctr->a[0]) is recomputed.
+void rp_launch_scatter_owner(ripple_ctx *c, uint32_t l, bool bootstrap) {
+    OwnerArgs a;
+    a.list = bootstrap ? c->all_list : c->list[l];
+    a.count_ptr = bootstrap ? &c->ctr->a[0] : &c->ctr->a[l];
+    a.queue = bootstrap ? c->list[0] : c->all_list; // scratch that is free at that point
+    a.queue_count = &c->ctr->n_all;
+    a.in_meta = c->in_meta;
+    a.in_pool = c->in_pool;
+    a.bm_prev = c->bm[l - 1];
+    a.bm_sink = bootstrap ? c->alive : c->bm_sink;  // "recompute" for every listed vertex
+    a.bm_vadd = bootstrap ? c->alive : c->bm_vadd;
+    a.D = c->D[(l - 1) & 1];
+    a.Hprev = c->H[l - 1];
+    a.store = c->store;
+    a.d = c->xw[l];
+    a.X = c->X[l];
+    a.ctr = c->ctr;
+    hipMemsetAsync(&c->ctr->n_all, 0, 4, c->stream);
+    OwnerArgs b = a;
+    b.list = a.queue;
+    b.count_ptr = &c->ctr->n_all;
+    dim3 grid(c->n_cu * 8), block(256);
+#define OWN_CASE(NJ)                                                                        \
+    do {                                                                                    \
+        hipLaunchKernelGGL((k_scatter_owner<NJ, 1>), grid, block, 0, c->stream, a);         \
+        hipLaunchKernelGGL((k_scatter_owner<NJ, 16>), dim3(c->n_cu), dim3(1024), 0, c->stream, b); \
+    } while (0)
+    if (a.d <= 64) OWN_CASE(1);
+    else if (a.d <= 128) OWN_CASE(2);
+    else if (a.d <= 256) OWN_CASE(4);
+    else if (a.d <= 512) OWN_CASE(8);
+    else OWN_CASE(16);
+#undef OWN_CASE
 }
 
 // ---------------------------------------------------------------------------------

@@ -307,3 +307,40 @@ def test_graph_beyond_the_single_workgroup_compaction_limit():
         pair.check_aggregates()
     finally:
         pair.close()
+
+
+@pytest.mark.parametrize("kind,widths,store", [("sage_mean", (16, 40, 24, 10), "f32"), ("gcn_sum", (100, 256, 47), "f32"),
+                                               ("gin_sum", (16, 32, 12, 6), "f32"), ("gcn_mean", (32, 64, 12), "bf16")])
+def test_deterministic_mode_is_bit_reproducible(kind, widths, store):
+    """With RIPPLE_OPT_DETERMINISTIC every aggregate row has one owner that adds its sources in a fixed
+    order: two contexts fed the same operations must agree bit for bit after every batch (bootstrap
+    included), and both must match the oracle like the default mode does. The graph has rows longer
+    than a wavefront owns (1,024 entries) and than the sort buffer takes at once, so the workgroup variant and the key ranges run too."""
+    print("case deterministic", kind, store, flush=True)
+    kw = dict(n=20000, e=240000, d0=widths[0], kind=kind, widths=widths, seed=81, slack=256, store=store,
+              top_share=0.04, deterministic=True)
+    pair, graph = make_pair(**kw)
+    twin, _ = make_pair(**kw)
+    deg_in, _ = rp.ripple_get_degrees(pair.ctx, 1, pair.cap)
+    assert deg_in.max() > 4096, "rows that need several key ranges would not be exercised"
+    stream = make_stream(pair, graph, MIXV, 83)
+    try:
+        for l in range(pair.L + 1):
+            assert np.array_equal(pair.gpu_layer(l).view(np.uint32), twin.gpu_layer(l).view(np.uint32)), "bootstrap differs"
+        for b, bs in enumerate([3, 80, 400, 1500]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload, check=(b != 2))
+            rp.ripple_apply_updates(twin.ctx, ops, payload)
+            for l in range(pair.L + 1):
+                assert np.array_equal(pair.gpu_layer(l).view(np.uint32), twin.gpu_layer(l).view(np.uint32)), \
+                    f"layer {l} differs between two runs of batch {b}"
+            for l in range(1, pair.L + 1):
+                w = rp.ripple_get_layer_info(pair.ctx, l)[0]
+                assert np.array_equal(rp.ripple_get_aggregates(pair.ctx, l, w, n_rows=pair.cap).view(np.uint32),
+                                      rp.ripple_get_aggregates(twin.ctx, l, w, n_rows=twin.cap).view(np.uint32))
+        pair.check_graph()
+        pair.check_aggregates(tol=1e-3 if store == "bf16" else None)
+    finally:
+        pair.close()
+        twin.close()
