@@ -16,7 +16,9 @@ vertices the batch can affect at each hop (Sec. 3.2's per-update-type
 description; Sec. 2.2's worked example).
 
 Readings taken where the paper leaves a choice (each is listed in the design doc):
-  * sum / mean as in Table 1; mean of an empty neighbourhood is the zero vector;
+  * sum / mean / weighted sum as in Table 1 (weighted sum: x_v = sum over in-neighbours u of
+    alpha_uv h_u, alpha_uv a per-edge weight fixed when the edge is created; Sec. 3.3.3, "Other
+    linear aggregators"); mean of an empty neighbourhood is the zero vector;
   * GraphConv: h = act(x W + b), no self term (Sec. 3.3.3 example);
     GraphSAGE: h = act(h_self W_self + x W_neigh + b) (Eq. 2's UPDATE takes both);
     GIN: h = act(MLP((1+eps) h_self + x)) (Sec. 6.3.1: GI-S adds the vertex's
@@ -55,15 +57,22 @@ class GraphState:
     10^8 edges.
     """
 
-    def __init__(self, n_vertices: int, vertex_capacity: int, src, dst, feats):
+    def __init__(self, n_vertices: int, vertex_capacity: int, src, dst, feats, weights=None):
         self.cap = int(vertex_capacity)
         self.alive = np.zeros(self.cap, dtype=bool)
         self.alive[:n_vertices] = True
         s = np.asarray(src, dtype=np.int64)
         d = np.asarray(dst, dtype=np.int64)
-        self.base = np.unique(s * self.cap + d)
-        if self.base.size != s.size:
+        keys = s * self.cap + d
+        order = np.argsort(keys, kind="stable")
+        self.base = keys[order]
+        if self.base.size and (np.diff(self.base) == 0).any():
             raise ValueError("initial edge list contains duplicates")
+        self.weighted = weights is not None
+        # per-edge weight alpha_uv (weighted sum): aligned with `base`; later edges in w_late
+        self.base_w = (np.asarray(weights, dtype=np.float64)[order] if self.weighted
+                       else np.ones(self.base.size))
+        self.w_late = {}                            # key u*cap+v -> weight of an edge created after the start
         self.base_t = np.sort(d * self.cap + s)
         self.removed = set()                        # base keys (u*cap+v) no longer present
         self.added_out = {}                         # u -> set of v, edges not in base
@@ -84,8 +93,9 @@ class GraphState:
         key = u * self.cap + v
         return key not in self.removed and self._in_base(key)
 
-    def _insert(self, u: int, v: int):
+    def _insert(self, u: int, v: int, w: float = 1.0):
         key = u * self.cap + v
+        self.w_late[key] = w                        # also overrides the weight a re-created base edge had
         if key in self.removed:
             self.removed.discard(key)
         else:
@@ -94,6 +104,7 @@ class GraphState:
             self.n_added += 1
 
     def _erase(self, u: int, v: int):
+        self.w_late.pop(u * self.cap + v, None)
         if v in self.added_out.get(u, ()):
             self.added_out[u].discard(v)
             self.added_in[v].discard(u)
@@ -111,6 +122,21 @@ class GraphState:
                          dtype=np.int64)
         keys = np.concatenate([self.base[keep], extra])
         return keys // self.cap, keys % self.cap
+
+    def edge_weights(self):
+        """Weights alpha_uv in the order of edges()."""
+        keep = np.ones(self.base.size, dtype=bool)
+        if self.removed:
+            gone = np.fromiter(self.removed, dtype=np.int64, count=len(self.removed))
+            keep[np.searchsorted(self.base, gone)] = False
+        w = self.base_w.copy()
+        for key, val in self.w_late.items():        # a base edge deleted and created again
+            i = int(np.searchsorted(self.base, key))
+            if i < self.base.size and int(self.base[i]) == key:
+                w[i] = val
+        extra = np.array([self.w_late[u * self.cap + v] for u, vs in self.added_out.items() for v in vs],
+                         dtype=np.float64)
+        return np.concatenate([w[keep], extra])
 
     def n_edges(self) -> int:
         return self.base.size - len(self.removed) + self.n_added
@@ -149,7 +175,9 @@ class GraphState:
                     continue
                 present = self.has_edge(u, v)
                 if kind == EDGE_ADD and not present:
-                    self._insert(u, v)
+                    # weighted graphs: the operation's fourth word holds the float32 bits of alpha_uv
+                    w = float(np.array([row], dtype=np.uint32).view(np.float32)[0]) if self.weighted else 1.0
+                    self._insert(u, v, w)
                 elif kind == EDGE_DEL and present:
                     self._erase(u, v)
                 else:
@@ -205,15 +233,29 @@ def _act(name: str, z: np.ndarray) -> np.ndarray:
     raise ValueError(name)
 
 
-def in_adjacency(state: GraphState) -> sp.csr_matrix:
-    """Sparse matrix with a 1 at (v, u) for every edge u -> v: row v lists v's in-neighbours."""
-    src, dst = state.edges()
-    return sp.csr_matrix((np.ones(src.size), (dst, src)), shape=(state.cap, state.cap))
+class InAdjacency:
+    """ones: sparse matrix with a 1 at (v, u) for every edge u -> v (row v lists v's in-neighbours);
+    alpha: the same pattern holding the edge weights alpha_uv (weighted graphs, else None)."""
+
+    def __init__(self, state: GraphState):
+        src, dst = state.edges()
+        shape = (state.cap, state.cap)
+        self.ones = sp.csr_matrix((np.ones(src.size), (dst, src)), shape=shape)
+        self.alpha = sp.csr_matrix((state.edge_weights(), (dst, src)), shape=shape) if state.weighted else None
 
 
-def aggregate(a_in: sp.csr_matrix, h_prev: np.ndarray, agg: str, rows=None) -> np.ndarray:
+def in_adjacency(state: GraphState) -> InAdjacency:
+    return InAdjacency(state)
+
+
+def aggregate(a_in: InAdjacency, h_prev: np.ndarray, agg: str, rows=None) -> np.ndarray:
     """Eq. (1): x_v = AGG over in-neighbours u of v of h_prev[u] (Table 1), for all v or for `rows`."""
-    a = a_in if rows is None else a_in[rows]
+    if agg == "wsum":                                            # sum of alpha_uv h_u
+        if a_in.alpha is None:
+            raise ValueError("weighted sum on a graph without edge weights")
+        a = a_in.alpha if rows is None else a_in.alpha[rows]
+        return a @ h_prev
+    a = a_in.ones if rows is None else a_in.ones[rows]
     x = a @ h_prev                                               # sum over in-neighbours
     if agg == "mean":
         deg = np.asarray(a.getnnz(axis=1), dtype=np.float64)     # in-degree
@@ -223,7 +265,7 @@ def aggregate(a_in: sp.csr_matrix, h_prev: np.ndarray, agg: str, rows=None) -> n
     return x
 
 
-def layer_rows(state: GraphState, layer: dict, h_prev: np.ndarray, a_in: sp.csr_matrix, rows=None) -> np.ndarray:
+def layer_rows(state: GraphState, layer: dict, h_prev: np.ndarray, a_in: InAdjacency, rows=None) -> np.ndarray:
     """Eq. (2): h_v = act(UPDATE(h_prev[v], x_v)) for all vertices or for `rows`; dead rows are 0."""
     d_in = layer["d_in"]
     x = aggregate(a_in, h_prev, layer["agg"], rows)
@@ -272,7 +314,7 @@ def recompute_rows(state: GraphState, model, targets) -> list:
     need = [None] * (L + 1)
     need[L] = np.unique(np.asarray(targets, dtype=np.int64))
     for l in range(L, 0, -1):
-        nbrs = np.unique(a_in[need[l]].indices)
+        nbrs = np.unique(a_in.ones[need[l]].indices)
         need[l - 1] = np.union1d(nbrs, need[l]) if model[l - 1]["self"] != "none" else nbrs
     h = np.zeros_like(state.h0)
     h[need[0]] = state.h0[need[0]]

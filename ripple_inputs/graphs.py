@@ -84,6 +84,11 @@ def features(n: int, d: int, seed: int) -> np.ndarray:
     return np.random.default_rng(seed).standard_normal((n, d), dtype=np.float32)
 
 
+def edge_weights(e: int, seed: int) -> np.ndarray:
+    """Per-edge weights for the weighted-sum workload: uniform in [0.25, 1.75), float32."""
+    return np.random.default_rng(seed).uniform(0.25, 1.75, e).astype(np.float32)
+
+
 @dataclasses.dataclass(frozen=True)
 class Config:
     name: str

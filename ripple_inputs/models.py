@@ -38,7 +38,9 @@ def make_model(kind: str, widths, seed: int, last_act: str = "none"):
             lay.update(agg="sum", self="none", W0=glorot(rng, d_in, d_out), b0=_bias(rng, d_out))
         elif kind == "gcn_mean":
             lay.update(agg="mean", self="none", W0=glorot(rng, d_in, d_out), b0=_bias(rng, d_out))
-        elif kind in ("sage_mean", "sage_sum"):
+        elif kind == "gcn_wsum":
+            lay.update(agg="wsum", self="none", W0=glorot(rng, d_in, d_out), b0=_bias(rng, d_out))
+        elif kind in ("sage_mean", "sage_sum", "sage_wsum"):
             w_self, w_neigh = glorot(rng, d_in, d_out), glorot(rng, d_in, d_out)
             lay.update(agg=kind.split("_")[1], self="concat",
                        W0=np.ascontiguousarray(np.vstack([w_self, w_neigh])), b0=_bias(rng, d_out))

@@ -10,7 +10,8 @@ feature replacement, one vertex delete, or one vertex add together with its
 
 Operation record: uint32 [kind, u, v, feat_row]; edges are (u -> v); vertex
 operations use u; feat_row indexes the batch's payload for VERTEX_ADD and
-FEAT_UPDATE and is 0 otherwise.
+FEAT_UPDATE and is 0 otherwise, except that a weighted stream puts the float32
+bits of the new edge's weight (uniform in [0.25, 1.75)) there for EDGE_ADD.
 """
 from __future__ import annotations
 
@@ -23,12 +24,14 @@ from .graphs import (OP_EDGE_ADD, OP_EDGE_DEL, OP_VERTEX_ADD, OP_VERTEX_DEL,
 class UpdateStream:
     def __init__(self, n: int, vertex_capacity: int, src, dst, out_law: PowerLaw,
                  in_law: PowerLaw, d0: int, mix: dict, seed: int,
-                 edges_per_new_vertex: int = 8):
+                 edges_per_new_vertex: int = 8, weighted: bool = False):
         self.cap = int(vertex_capacity)
         self.d0 = int(d0)
         self.mix = dict(mix)
         self.out_law, self.in_law = out_law, in_law
         self.rng = np.random.default_rng(seed)
+        self.weighted = bool(weighted)
+        self.wrng = np.random.default_rng(seed + 7919)       # its own stream: the operations do not depend on it
         self.epv = int(edges_per_new_vertex)
         s64, d64 = np.asarray(src, np.int64), np.asarray(dst, np.int64)
         self.base = np.sort(s64 * self.cap + d64)            # keyed src-major
@@ -223,6 +226,10 @@ class UpdateStream:
                     self._del_edge(x, u)
                 self.alive[u] = False
         ops_arr = np.asarray(ops, dtype=np.uint32).reshape(-1, 4)
+        if self.weighted:
+            adds = ops_arr[:, 0] == OP_EDGE_ADD
+            w = self.wrng.uniform(0.25, 1.75, int(adds.sum())).astype(np.float32)
+            ops_arr[adds, 3] = w.view(np.uint32)
         payload = (np.stack(rows).astype(np.float32) if rows
                    else np.zeros((0, self.d0), dtype=np.float32))
         return ops_arr, payload, len(groups)

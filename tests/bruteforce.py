@@ -13,8 +13,13 @@ def in_lists(n, src, dst):
     return nbrs
 
 
-def embed(v, l, model, feats, nbrs, alive, memo):
-    """h^l_v as float64 vector."""
+def in_weights(src, dst, w):
+    """{(u, v): alpha_uv} for the weighted sum."""
+    return {(int(s), int(d)): float(x) for s, d, x in zip(list(src), list(dst), list(w))}
+
+
+def embed(v, l, model, feats, nbrs, alive, memo, alpha=None):
+    """h^l_v as float64 vector; alpha: edge weights for layers that aggregate by weighted sum."""
     key = (v, l)
     if key in memo:
         return memo[key]
@@ -27,10 +32,11 @@ def embed(v, l, model, feats, nbrs, alive, memo):
         lay = model[l - 1]
         acc = np.zeros(lay["d_in"])
         for u in nbrs[v]:
-            acc = acc + embed(u, l - 1, model, feats, nbrs, alive, memo)
+            term = embed(u, l - 1, model, feats, nbrs, alive, memo, alpha)
+            acc = acc + (alpha[(u, v)] * term if lay["agg"] == "wsum" else term)
         if lay["agg"] == "mean" and len(nbrs[v]) > 0:
             acc = acc / len(nbrs[v])
-        own = embed(v, l - 1, model, feats, nbrs, alive, memo)
+        own = embed(v, l - 1, model, feats, nbrs, alive, memo, alpha)
         W0 = np.array(lay["W0"], dtype=np.float64)
         b0 = np.array(lay["b0"], dtype=np.float64)
         z = np.array(b0)

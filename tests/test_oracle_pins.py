@@ -7,7 +7,7 @@ import pytest
 
 import oracle
 import ripple_inputs as ri
-from bruteforce import embed, in_lists
+from bruteforce import embed, in_lists, in_weights
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -298,3 +298,73 @@ def test_max_rel_err_metric():
     alive = np.array([True, True, True])
     # row norms 2, 0, 10 -> tau = 4; errors 0.02/4, 0.04/4, 0.5/10
     assert abs(oracle.max_rel_err(got, want, alive) - 0.05) < 1e-15
+
+
+# ---- weighted sum (Table 1, Sec. 3.3.3 "Other linear aggregators") -------------------------------
+def weighted_case(seed, n=36, e=150, d0=5, kind="gcn_wsum", widths=(5, 7, 4)):
+    rng = np.random.default_rng(seed)
+    keys = rng.choice(n * n, size=e, replace=False)
+    src, dst = keys // n, keys % n
+    keep = src != dst
+    src, dst = src[keep], dst[keep]
+    w = rng.uniform(0.25, 1.75, src.size)
+    feats = rng.standard_normal((n, d0))
+    model = ri.make_model(kind, widths, seed + 1)
+    st = oracle.GraphState(n, n + 4, src, dst, feats, weights=w)
+    return st, model, src, dst, w, feats
+
+
+@pytest.mark.parametrize("kind", ["gcn_wsum", "sage_wsum"])
+@pytest.mark.parametrize("seed", [0, 1])
+def test_weighted_sum_equals_vertexwise_bruteforce(kind, seed):
+    st, model, src, dst, w, feats = weighted_case(seed, kind=kind)
+    hs = oracle.full_recompute(st, model)
+    nbrs, alpha = in_lists(st.cap, src, dst), in_weights(src, dst, w)
+    f = np.zeros((st.cap, feats.shape[1]))
+    f[: len(feats)] = feats
+    memo = {}
+    for v in range(st.cap):
+        want = embed(v, len(model), model, f, nbrs, st.alive, memo, alpha)
+        np.testing.assert_allclose(hs[-1][v], want, rtol=1e-12, atol=1e-12)
+
+
+def test_weighted_sum_special_cases():
+    """All weights 1: the plain sum. All weights c on a linear bias-free model: c^L times the plain sum.
+    A mistake that takes alpha_vu for alpha_uv, or weights the self term, fails the brute force above;
+    this one pins the scale."""
+    st, model, src, dst, w, feats = weighted_case(3, kind="gcn_wsum")
+    ones = oracle.GraphState(st.cap - 4, st.cap, src, dst, feats, weights=np.ones(src.size))
+    plain = oracle.GraphState(st.cap - 4, st.cap, src, dst, feats)
+    sum_model = [dict(l, agg="sum") for l in model]
+    for a, b in zip(oracle.full_recompute(ones, model), oracle.full_recompute(plain, sum_model)):
+        np.testing.assert_allclose(a, b, rtol=1e-13, atol=1e-13)
+    lin = [dict(l, act_out="none", b0=np.zeros_like(l["b0"])) for l in model]
+    scaled = oracle.GraphState(st.cap - 4, st.cap, src, dst, feats, weights=np.full(src.size, 0.5))
+    got = oracle.full_recompute(scaled, lin)[-1]
+    want = oracle.full_recompute(plain, [dict(l, agg="sum") for l in lin])[-1] * 0.5 ** len(lin)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
+def test_weighted_sum_after_a_batch():
+    """Edge additions carry their weight in the operation's fourth word; an edge deleted and created
+    again takes the new weight. Checked against the brute force on the resulting weighted edge set."""
+    st, model, src, dst, w, feats = weighted_case(5, kind="sage_wsum")
+    def bits(x):
+        return int(np.array([x], dtype=np.float32).view(np.uint32)[0])
+    s0, d0_ = int(src[0]), int(dst[0])
+    free = next((u, v) for u in range(10) for v in range(10) if u != v and not st.has_edge(u, v))
+    ops = [(ri.OP_EDGE_DEL, s0, d0_, 0), (ri.OP_EDGE_ADD, free[0], free[1], bits(1.5)),
+           (ri.OP_EDGE_ADD, s0, d0_, bits(0.75)), (ri.OP_EDGE_DEL, int(src[1]), int(dst[1]), 0)]
+    rec = st.apply_batch(np.array(ops, dtype=np.uint32), None)
+    assert rec.accepted.all()
+    es, ed = st.edges()
+    ew = st.edge_weights()
+    alpha = in_weights(es, ed, ew)
+    assert alpha[(s0, d0_)] == 0.75 and alpha[free] == 1.5 and (int(src[1]), int(dst[1])) not in alpha
+    assert alpha[(int(src[2]), int(dst[2]))] == pytest.approx(float(w[2]))
+    hs = oracle.full_recompute(st, model)
+    nbrs = in_lists(st.cap, es, ed)
+    memo = {}
+    for v in range(st.cap):
+        want = embed(v, len(model), model, st.h0, nbrs, st.alive, memo, alpha)
+        np.testing.assert_allclose(hs[-1][v], want, rtol=1e-12, atol=1e-12)
