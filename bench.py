@@ -102,8 +102,10 @@ def cpu_baseline(cfg, bs, scale):
     src, dst, out_law, in_law = ri.chung_lu_graph(n, e, cfg.gamma, min(cfg.top_share * scale, 0.05), cfg.graph_seed)
     feats = ri.features(n, cfg.d0, cfg.feat_seed)
     model = ri.make_model(cfg.model, cfg.widths, cfg.weight_seed)
-    stream = ri.UpdateStream(n, n + cfg.vertex_slack, src, dst, out_law, in_law, cfg.d0, cfg.mix, cfg.stream_seed)
-    st = oracle.GraphState(n, n + cfg.vertex_slack, src, dst, feats)
+    stream = ri.UpdateStream(n, n + cfg.vertex_slack, src, dst, out_law, in_law, cfg.d0, cfg.mix, cfg.stream_seed,
+                             weighted=cfg.weighted)
+    st = oracle.GraphState(n, n + cfg.vertex_slack, src, dst, feats,
+                           weights=ri.edge_weights(len(src), cfg.graph_seed + 100) if cfg.weighted else None)
     sample_bs = max(bs // scale, 1)
     ops, payload, n_upd = stream.next_batch(sample_bs)
     t0 = time.perf_counter()
@@ -158,15 +160,20 @@ def main():
     model = ri.make_model(cfg.model, cfg.widths, cfg.weight_seed)
     log(f"[bench] graph {cfg.name}: {cfg.n} vertices, {cfg.e} edges generated in {time.time() - t0:.1f}s")
     t0 = time.time()
-    ctx = rp.ripple_init_graph(cfg.n, cfg.vertex_capacity, src, dst, feats, store=cfg.store,
-                               edge_capacity=cfg.edge_capacity)
+    if cfg.weighted:
+        ctx = rp.ripple_init_graph_weighted(cfg.n, cfg.vertex_capacity, src, dst, ri.edge_weights(len(src), cfg.graph_seed + 100),
+                                            feats, store=cfg.store, edge_capacity=cfg.edge_capacity)
+    else:
+        ctx = rp.ripple_init_graph(cfg.n, cfg.vertex_capacity, src, dst, feats, store=cfg.store,
+                                   edge_capacity=cfg.edge_capacity)
     if args.deterministic:
         rp.ripple_set_option(ctx, rp.OPT_DETERMINISTIC, 1)
     rp.ripple_load_model(ctx, model)
     rp.ripple_full_infer(ctx)
     log(f"[bench] graph store built and bootstrap inference done in {time.time() - t0:.1f}s")
     t0 = time.time()
-    stream = ri.UpdateStream(cfg.n, cfg.vertex_capacity, src, dst, out_law, in_law, cfg.d0, cfg.mix, cfg.stream_seed)
+    stream = ri.UpdateStream(cfg.n, cfg.vertex_capacity, src, dst, out_law, in_law, cfg.d0, cfg.mix, cfg.stream_seed,
+                             weighted=cfg.weighted)
     del src, dst
     batches = []
     for _ in range(args.warmup + args.steps):

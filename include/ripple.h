@@ -60,7 +60,7 @@ typedef struct {
     uint32_t feat_row;   /* row of the batch's feature payload; ignored for edge ops and VERTEX_DEL */
 } ripple_update;         /* 16 bytes */
 
-typedef enum { RIPPLE_AGG_SUM = 0, RIPPLE_AGG_MEAN = 1 } ripple_agg;           /* Table 1 */
+typedef enum { RIPPLE_AGG_SUM = 0, RIPPLE_AGG_MEAN = 1, RIPPLE_AGG_WSUM = 2 } ripple_agg;   /* Table 1 */
 typedef enum {
     RIPPLE_SELF_NONE = 0,    /* GraphConv:  h = act(x W0 + b0)                               */
     RIPPLE_SELF_CONCAT = 1,  /* GraphSAGE:  h = act([h_self | x] W0 + b0), W0 is [2 d_in x .] */
@@ -144,6 +144,16 @@ ripple_status ripple_init_graph(ripple_ctx **out, uint32_t n_vertices, uint32_t 
                                 uint64_t n_edges, uint64_t edge_capacity,
                                 const uint32_t *src, const uint32_t *dst,
                                 const float *features, uint32_t d0, int store, void *hip_stream);
+
+/* The same with a weight alpha_uv per edge (edge_weights: host, float32 [n_edges], borrowed; Table 1's
+ * weighted sum, Sec. 3.3.3 "Other linear aggregators"): layers with RIPPLE_AGG_WSUM aggregate
+ * sum_u alpha_uv h_u, other layers ignore the weights. A weight is fixed when its edge is created: an
+ * EDGE_ADD operation on such a graph carries the float32 bits of alpha_uv in its feat_row word. Weighted
+ * graphs always gather along in-edges (no push kernel) and do not combine with RIPPLE_OPT_DETERMINISTIC. */
+ripple_status ripple_init_graph_weighted(ripple_ctx **out, uint32_t n_vertices, uint32_t vertex_capacity,
+                                         uint64_t n_edges, uint64_t edge_capacity,
+                                         const uint32_t *src, const uint32_t *dst, const float *edge_weights,
+                                         const float *features, uint32_t d0, int store, void *hip_stream);
 
 /* Copy the model to the GPU. layers[0].d_in must equal d0 and widths must chain. */
 ripple_status ripple_load_model(ripple_ctx *ctx, uint32_t n_layers, const ripple_layer_desc *layers);

@@ -23,12 +23,12 @@ RIPPLE_MAX_LAYERS = 8
 RIPPLE_N_PHASES = 8
 PHASES = ["ingest", "struct", "frontier", "scatter", "compact", "transform", "other", "total"]
 OPT_TIMING, OPT_SCATTER_MODE, OPT_PULL_RATIO, OPT_PROJECT_FIRST, OPT_BF16_MFMA, OPT_SELF_CACHE, OPT_DETERMINISTIC = 0, 1, 2, 3, 4, 5, 6
-AGG = {"sum": 0, "mean": 1}
+AGG = {"sum": 0, "mean": 1, "wsum": 2}
 SELF = {"none": 0, "concat": 1, "add": 2}
 ACT = {"none": 0, "relu": 1}
 STORE = {"f32": 0, "bf16": 1}
 
-EXPORTS = ["ripple_init_graph", "ripple_load_model", "ripple_full_infer", "ripple_apply_updates",
+EXPORTS = ["ripple_init_graph", "ripple_init_graph_weighted", "ripple_load_model", "ripple_full_infer", "ripple_apply_updates",
            "ripple_get_embeddings", "ripple_get_aggregates", "ripple_get_layer_info", "ripple_get_affected", "ripple_export_edges",
            "ripple_get_degrees", "ripple_compact", "ripple_set_option", "ripple_get_stats",
            "ripple_destroy", "ripple_last_error"]
@@ -86,6 +86,7 @@ def load_library():
     lib = C.CDLL(LIB_PATH)
     vp, u32, u64 = C.c_void_p, C.c_uint32, C.c_uint64
     lib.ripple_init_graph.argtypes = [C.POINTER(vp), u32, u32, u64, u64, vp, vp, vp, u32, C.c_int, vp]
+    lib.ripple_init_graph_weighted.argtypes = [C.POINTER(vp), u32, u32, u64, u64, vp, vp, vp, vp, u32, C.c_int, vp]
     lib.ripple_load_model.argtypes = [vp, u32, C.POINTER(LayerDesc)]
     lib.ripple_full_infer.argtypes = [vp]
     lib.ripple_apply_updates.argtypes = [vp, vp, u32, vp, u32, C.POINTER(BatchResult)]
@@ -139,12 +140,36 @@ def ripple_init_graph(n_vertices, vertex_capacity, src, dst, features, store="f3
                                _ptr(src), _ptr(dst), _ptr(features), features.shape[1],
                                STORE[store] if isinstance(store, str) else int(store),
                                C.c_void_p(int(hip_stream)))
+    return _checked_ctx(lib, ctx, rc)
+
+
+def _checked_ctx(lib, ctx, rc):
     if rc != RIPPLE_OK:
         text = lib.ripple_last_error(ctx).decode() if ctx else "invalid argument"
         if ctx:
             lib.ripple_destroy(ctx)
         raise RippleError(rc, text)
     return ctx
+
+
+def ripple_init_graph_weighted(n_vertices, vertex_capacity, src, dst, edge_weights, features, store="f32",
+                               edge_capacity=None, hip_stream=0):
+    lib = load_library()
+    src = np.ascontiguousarray(src, dtype=np.uint32)
+    dst = np.ascontiguousarray(dst, dtype=np.uint32)
+    edge_weights = np.ascontiguousarray(edge_weights, dtype=np.float32)
+    features = np.ascontiguousarray(features, dtype=np.float32)
+    if (features.ndim != 2 or features.shape[0] != n_vertices or src.shape != dst.shape
+            or edge_weights.shape != src.shape):
+        raise ValueError("features must be [n_vertices x d0]; src, dst and edge_weights must have equal length")
+    if edge_capacity is None:
+        edge_capacity = int(src.size * 1.25) + 4096
+    ctx = C.c_void_p()
+    rc = lib.ripple_init_graph_weighted(C.byref(ctx), n_vertices, vertex_capacity, src.size, edge_capacity,
+                                        _ptr(src), _ptr(dst), _ptr(edge_weights), _ptr(features), features.shape[1],
+                                        STORE[store] if isinstance(store, str) else int(store),
+                                        C.c_void_p(int(hip_stream)))
+    return _checked_ctx(lib, ctx, rc)
 
 
 def ripple_load_model(ctx, model):

@@ -150,10 +150,9 @@ static ripple_status fail(ripple_ctx *c, ripple_status rc, const char *msg) {
 // ---------------------------------------------------------------------------------
 // init / destroy
 // ---------------------------------------------------------------------------------
-extern "C" ripple_status ripple_init_graph(ripple_ctx **out, uint32_t n_vertices, uint32_t vertex_capacity,
-                                           uint64_t n_edges, uint64_t edge_capacity, const uint32_t *src,
-                                           const uint32_t *dst, const float *features, uint32_t d0, int store,
-                                           void *hip_stream) {
+static ripple_status init_graph(ripple_ctx **out, uint32_t n_vertices, uint32_t vertex_capacity, uint64_t n_edges,
+                                uint64_t edge_capacity, const uint32_t *src, const uint32_t *dst, const float *weights,
+                                const float *features, uint32_t d0, int store, void *hip_stream) {
     if (!out) return RIPPLE_EINVAL;
     *out = nullptr;
     if (vertex_capacity == 0 || n_vertices > vertex_capacity || vertex_capacity > (1u << 31) || d0 == 0 ||
@@ -192,6 +191,7 @@ extern "C" ripple_status ripple_init_graph(ripple_ctx **out, uint32_t n_vertices
     RP_TRY(dev_alloc(c, &c->hole_in, n, true));
     RP_TRY(dev_alloc(c, &c->out_pool, (size_t)pool_cap, false));
     RP_TRY(dev_alloc(c, &c->in_pool, (size_t)pool_cap, false));
+    if (weights) RP_TRY(dev_alloc(c, &c->in_w, (size_t)pool_cap, false));
     RP_TRY(dev_alloc(c, &c->alive, (size_t)c->n_words, true));
     c->n_part = std::max(rp_div_up(n, 1024), rp_div_up(c->n_words, 256)) + 1;
     RP_TRY(dev_alloc(c, &c->part_cnt, (size_t)c->n_part, true));
@@ -221,7 +221,7 @@ extern "C" ripple_status ripple_init_graph(ripple_ctx **out, uint32_t n_vertices
             }
         }
     }
-    RP_TRY(rp_build_graph(c, n_vertices, n_edges, src, dst));
+    RP_TRY(rp_build_graph(c, n_vertices, n_edges, src, dst, weights));
     // counters that persist across batches
     c->ctr_host->n_alive = n_vertices;
     c->ctr_host->n_edges = n_edges;
@@ -232,13 +232,30 @@ extern "C" ripple_status ripple_init_graph(ripple_ctx **out, uint32_t n_vertices
     return RIPPLE_OK;
 }
 
+extern "C" ripple_status ripple_init_graph(ripple_ctx **out, uint32_t n_vertices, uint32_t vertex_capacity,
+                                           uint64_t n_edges, uint64_t edge_capacity, const uint32_t *src,
+                                           const uint32_t *dst, const float *features, uint32_t d0, int store,
+                                           void *hip_stream) {
+    return init_graph(out, n_vertices, vertex_capacity, n_edges, edge_capacity, src, dst, nullptr, features, d0, store,
+                      hip_stream);
+}
+
+extern "C" ripple_status ripple_init_graph_weighted(ripple_ctx **out, uint32_t n_vertices, uint32_t vertex_capacity,
+                                                    uint64_t n_edges, uint64_t edge_capacity, const uint32_t *src,
+                                                    const uint32_t *dst, const float *edge_weights,
+                                                    const float *features, uint32_t d0, int store, void *hip_stream) {
+    if (!edge_weights) return RIPPLE_EINVAL;
+    return init_graph(out, n_vertices, vertex_capacity, n_edges, edge_capacity, src, dst, edge_weights, features, d0,
+                      store, hip_stream);
+}
+
 extern "C" void ripple_destroy(ripple_ctx *c) {
     if (!c) return;
     hipStreamSynchronize(c->stream);
     void *ptrs[] = {c->out_meta, c->in_meta, c->out_capv, c->in_capv, c->vstate, c->pend_out, c->pend_in, c->dead_out,
-                    c->dead_in, c->hole_out, c->hole_in, c->out_pool, c->in_pool, c->alive, c->part_cnt, c->part_deg, c->part_ideg, c->ioff[0], c->ctr, c->D[0], c->D[1],
+                    c->dead_in, c->hole_out, c->hole_in, c->out_pool, c->in_pool, c->in_w, c->alive, c->part_cnt, c->part_deg, c->part_ideg, c->ioff[0], c->ctr, c->D[0], c->D[1],
                     c->tmp, c->PD, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ioff_all, c->mk, c->ops_d, c->payload_d,
-                    c->op_status, c->op_pos_out, c->op_pos_in, c->op_touch, c->touch_out, c->touch_in, c->exp_kind, c->exp_a,
+                    c->op_status, c->op_pos_out, c->op_pos_in, c->op_touch, c->touch_out, c->touch_in, c->exp_kind, c->exp_s, c->exp_a,
                     c->exp_b, c->st_src, c->st_dst, c->st_sign, c->gather_d, c->gather_ids};
     for (void *p : ptrs)
         if (p) hipFree(p);
@@ -288,10 +305,14 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
     uint32_t prev = c->d[0];
     for (uint32_t l = 0; l < n_layers; ++l) {
         const ripple_layer_desc &s = layers[l];
-        if (s.d_in != prev || s.d_out == 0 || s.d_out > 1024 || s.d_hidden > 1024 || s.agg > RIPPLE_AGG_MEAN ||
+        if (s.d_in != prev || s.d_out == 0 || s.d_out > 1024 || s.d_hidden > 1024 || s.agg > RIPPLE_AGG_WSUM ||
             s.self_mode > RIPPLE_SELF_ADD || s.act_inner > RIPPLE_ACT_RELU || s.act_out > RIPPLE_ACT_RELU || !s.W0 ||
             !s.b0 || (s.d_hidden && (!s.W1 || !s.b1)))
             return fail(c, RIPPLE_EINVAL, "bad layer descriptor (widths must chain, dims <= 1024, pointers set)");
+        if (s.agg == RIPPLE_AGG_WSUM && !c->in_w)
+            return fail(c, RIPPLE_EINVAL, "weighted-sum layer on a graph that was built without edge weights");
+        if (s.agg == RIPPLE_AGG_WSUM && c->opt_deterministic)
+            return fail(c, RIPPLE_EINVAL, "the deterministic mode does not take weighted-sum layers");
         prev = s.d_out;
     }
     c->L = n_layers;
@@ -529,7 +550,7 @@ static ripple_status ensure_batch_buffers(ripple_ctx *c, uint32_t n_ops, uint32_
         uint32_t cap = std::max<uint32_t>(std::max<uint32_t>(n_ops, c->ops_cap), 4096);
         cap = rp_round_up(cap + cap / 2, 1024);
         uint32_t exp = std::max<uint32_t>(std::max<uint32_t>(want_exp, c->exp_cap), 1u << 20);
-        void *old[] = {c->ops_d, c->op_status, c->op_pos_out, c->op_pos_in, c->op_touch, c->touch_out, c->touch_in, c->exp_kind,
+        void *old[] = {c->ops_d, c->op_status, c->op_pos_out, c->op_pos_in, c->op_touch, c->touch_out, c->touch_in, c->exp_kind, c->exp_s,
                        c->exp_a, c->exp_b, c->st_src, c->st_dst, c->st_sign};
         for (void *p : old)
             if (p) hipFree(p);
@@ -542,6 +563,7 @@ static ripple_status ensure_batch_buffers(ripple_ctx *c, uint32_t n_ops, uint32_
         RP_TRY(dev_alloc(c, &c->touch_out, (size_t)cap + exp, false));
         RP_TRY(dev_alloc(c, &c->touch_in, (size_t)cap + exp, false));
         RP_TRY(dev_alloc(c, &c->exp_kind, exp, false));
+        RP_TRY(dev_alloc(c, &c->exp_s, exp, false));
         RP_TRY(dev_alloc(c, &c->exp_a, exp, false));
         RP_TRY(dev_alloc(c, &c->exp_b, exp, false));
         RP_TRY(dev_alloc(c, &c->st_src, (size_t)cap + exp, false));
@@ -615,8 +637,10 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
         // previous batch pushed with a wide margin the pull kernel is not even enqueued (pushing is
         // always correct; the prediction only saves a launch). The same goes for the discovering
         // mode: its kernels are enqueued only where the previous batch came near its threshold.
-        const bool may_pull = l >= 2 && c->opt_scatter != 1 && !(c->opt_scatter == 0 && c->push_margin[l]);
-        const bool may_disc = may_pull && (c->opt_scatter == 3 || (c->opt_scatter == 0 && c->disc_near[l]));
+        // Weighted-sum layers gather along in-edges at every hop (the weights are stored with the in-rows only).
+        const bool wsum = c->layers[l - 1].agg == RIPPLE_AGG_WSUM;
+        const bool may_pull = wsum || (l >= 2 && c->opt_scatter != 1 && !(c->opt_scatter == 0 && c->push_margin[l]));
+        const bool may_disc = l >= 2 && may_pull && (c->opt_scatter == 3 || ((c->opt_scatter == 0 || wsum) && c->disc_near[l]));
         t = rp_timer_begin(c);
         if (may_disc && !have_all) {
             rp_launch_alive_list(c);
@@ -643,7 +667,7 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
         rp_launch_frontier_compact(c, l, layer_self(c, l), l < c->L, true, multi);
         rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l);
         t = rp_timer_begin(c);
-        if (c->opt_scatter < 2 || !may_pull) rp_launch_scatter_push(c, l, may_pull, may_disc);
+        if (!wsum && (c->opt_scatter < 2 || !may_pull)) rp_launch_scatter_push(c, l, may_pull, may_disc);
         if (may_pull) rp_launch_scatter_pull(c, l, false, may_disc);
         rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l);
         t = rp_timer_begin(c);

@@ -85,6 +85,7 @@ struct ripple_ctx {
     uint2 *out_meta = nullptr, *in_meta = nullptr;      // {start, len} per vertex
     uint32_t *out_capv = nullptr, *in_capv = nullptr;   // row capacity
     uint32_t *out_pool = nullptr, *in_pool = nullptr;
+    float *in_w = nullptr;                              // edge weights, parallel to in_pool (weighted graphs only)
     uint32_t *alive = nullptr;                          // bitmap
     uint32_t *vstate = nullptr;                         // VS_* bits, zero between batches
     uint32_t *pend_out = nullptr, *pend_in = nullptr;   // appended this batch
@@ -122,7 +123,7 @@ struct ripple_ctx {
     uint32_t *touch_out = nullptr, *touch_in = nullptr;  // touched row lists
     uint32_t touch_cap = 0;
     uint32_t exp_cap = 0;
-    uint32_t *exp_kind = nullptr, *exp_a = nullptr, *exp_b = nullptr;
+    uint32_t *exp_kind = nullptr, *exp_a = nullptr, *exp_b = nullptr, *exp_s = nullptr;
     uint32_t struct_cap = 0;
     uint32_t *st_src = nullptr, *st_dst = nullptr;
     float *st_sign = nullptr;
@@ -166,6 +167,10 @@ struct ripple_ctx {
         }                                                                              \
     } while (0)
 
+// scatter policy of hop l as the kernels see it (see rp_hop_mode)
+static inline int rp_layer_mode(const ripple_ctx *c, uint32_t l) {
+    return c->layers[l - 1].agg == RIPPLE_AGG_WSUM ? 4 : c->opt_scatter;
+}
 static inline uint32_t rp_div_up(uint64_t a, uint64_t b) { return (uint32_t)((a + b - 1) / b); }
 static inline uint32_t rp_round_up(uint32_t a, uint32_t b) { return (a + b - 1) / b * b; }
 
@@ -223,15 +228,16 @@ __device__ __forceinline__ uint32_t rp_count_le(uint32_t b, uint32_t e) {
 // message once. 2 discover: when A_{l-1} sends along a large share of all edges nearly every vertex
 // is hit, so the in-rows of all live vertices are scanned once, which both gathers the messages and
 // finds A_l, and the out-edge walk that would have marked A_l is skipped.
-// mode: 0 automatic, 1 push, 2 pull, 3 discover wherever it is allowed.
+// mode: 0 automatic, 1 push, 2 pull, 3 discover wherever it is allowed, 4 automatic without push (layers whose
+// messages carry an edge weight, which is stored with the in-rows only).
 #define RP_HOP_PUSH 0
 #define RP_HOP_PULL 1
 #define RP_HOP_DISCOVER 2
 __device__ __forceinline__ int rp_hop_mode(const DevCtr *ctr, uint32_t l, uint32_t d, int mode, int ratio, int allow_disc) {
     const unsigned long long m = ctr->m[l];
-    if (allow_disc && m > 0 && (mode == 3 || (mode == 0 && m * 4ull >= ctr->n_edges))) return RP_HOP_DISCOVER;
+    if (allow_disc && m > 0 && (mode == 3 || ((mode == 0 || mode == 4) && m * 4ull >= ctr->n_edges))) return RP_HOP_DISCOVER;
     if (mode == 1) return RP_HOP_PUSH;
-    if (mode == 2 || mode == 3) return RP_HOP_PULL;
+    if (mode >= 2) return RP_HOP_PULL;
     return (m > 0 && m * d * 4ull * (unsigned long long)ratio >= 8ull * ctr->isum[l]) ? RP_HOP_PULL : RP_HOP_PUSH;
 }
 

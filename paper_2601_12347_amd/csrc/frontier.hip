@@ -396,7 +396,7 @@ __global__ __launch_bounds__(1024) void k_list_eoff(const uint32_t *list, const 
 
 void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l, bool allow_disc) {
     hipLaunchKernelGGL(k_frontier_mark, dim3(c->n_cu * 8), dim3(256), 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],
-                       c->eoff[l - 1], c->out_meta, c->out_pool, c->mk, c->ctr, l, c->xw[l], c->opt_scatter,
+                       c->eoff[l - 1], c->out_meta, c->out_pool, c->mk, c->ctr, l, c->xw[l], rp_layer_mode(c, l),
                        c->opt_pull_ratio, allow_disc ? 1 : 0);
 }
 

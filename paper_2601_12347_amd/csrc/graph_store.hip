@@ -115,13 +115,14 @@ __global__ void k_init_meta(const uint32_t *start, uint32_t n_cap, uint2 *meta) 
     if (v < n_cap) meta[v] = make_uint2(start[v], 0u);
 }
 
-__global__ void k_fill_rows(const uint32_t *key, const uint32_t *val, uint64_t n_edges, uint2 *meta,
-                            uint32_t *pool) {
+__global__ void k_fill_rows(const uint32_t *key, const uint32_t *val, const float *wts, uint64_t n_edges,
+                            uint2 *meta, uint32_t *pool, float *wpool) {
     uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
     for (uint64_t e = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_edges; e += stride) {
         uint32_t k = key[e];
         uint32_t p = atomicAdd(&((uint32_t *)meta)[2 * (size_t)k + 1], 1u);
         pool[meta[k].x + p] = val[e];
+        if (wpool) wpool[meta[k].x + p] = wts[e];
     }
 }
 
@@ -136,9 +137,10 @@ __global__ void k_set_alive_prefix(uint32_t *alive, uint32_t n_words, uint32_t n
 }
 
 ripple_status rp_build_graph(ripple_ctx *c, uint32_t n_vertices, uint64_t n_edges, const uint32_t *src_h,
-                             const uint32_t *dst_h) {
+                             const uint32_t *dst_h, const float *w_h) {
     hipStream_t s = c->stream;
     uint32_t *src_d = nullptr, *dst_d = nullptr, *tmp = nullptr, *err_d = nullptr;
+    float *w_d = nullptr;
     size_t eb = (size_t)(n_edges ? n_edges : 1) * sizeof(uint32_t);
     RP_HIP(c, hipMalloc(&src_d, eb));
     RP_HIP(c, hipMalloc(&dst_d, eb));
@@ -148,6 +150,10 @@ ripple_status rp_build_graph(ripple_ctx *c, uint32_t n_vertices, uint64_t n_edge
     if (n_edges) {
         RP_HIP(c, hipMemcpyAsync(src_d, src_h, eb, hipMemcpyHostToDevice, s));
         RP_HIP(c, hipMemcpyAsync(dst_d, dst_h, eb, hipMemcpyHostToDevice, s));
+        if (w_h) {
+            RP_HIP(c, hipMalloc(&w_d, eb));
+            RP_HIP(c, hipMemcpyAsync(w_d, w_h, eb, hipMemcpyHostToDevice, s));
+        }
     }
     uint32_t *deg_out = tmp, *deg_in = tmp + c->n_cap;
     RP_HIP(c, hipMemsetAsync(tmp, 0, (size_t)c->n_cap * 8, s));
@@ -176,14 +182,17 @@ ripple_status rp_build_graph(ripple_ctx *c, uint32_t n_vertices, uint64_t n_edge
         c->err = "edge_capacity too small for the initial graph";
         rc = RIPPLE_ECAPACITY;
     } else if (n_edges) {
-        hipLaunchKernelGGL(k_fill_rows, dim3(gb), dim3(256), 0, s, src_d, dst_d, n_edges, c->out_meta, c->out_pool);
-        hipLaunchKernelGGL(k_fill_rows, dim3(gb), dim3(256), 0, s, dst_d, src_d, n_edges, c->in_meta, c->in_pool);
+        hipLaunchKernelGGL(k_fill_rows, dim3(gb), dim3(256), 0, s, src_d, dst_d, (const float *)nullptr, n_edges,
+                           c->out_meta, c->out_pool, (float *)nullptr);
+        hipLaunchKernelGGL(k_fill_rows, dim3(gb), dim3(256), 0, s, dst_d, src_d, (const float *)w_d, n_edges, c->in_meta,
+                           c->in_pool, w_d ? c->in_w : (float *)nullptr);
     }
     hipMemsetAsync(c->pend_out, 0, (size_t)c->n_cap * 4, s);
     hipMemsetAsync(c->pend_in, 0, (size_t)c->n_cap * 4, s);
     hipStreamSynchronize(s);
     hipFree(src_d);
     hipFree(dst_d);
+    if (w_d) hipFree(w_d);
     hipFree(tmp);
     hipFree(err_d);
     if (rc == RIPPLE_OK) RP_HIP(c, hipGetLastError());
@@ -194,40 +203,49 @@ ripple_status rp_build_graph(ripple_ctx *c, uint32_t n_vertices, uint64_t n_edge
 // compaction: fresh caps, scan, copy every row into a new pool
 // ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void k_copy_rows(uint2 *meta, const uint32_t *new_start, uint32_t n_cap,
-                                                   const uint32_t *old_pool, uint32_t *new_pool) {
+                                                   const uint32_t *old_pool, uint32_t *new_pool, const float *old_w,
+                                                   float *new_w) {
     const int lane = rp_lane();
     uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
     for (uint32_t v = gw; v < n_cap; v += nw) {
         uint2 m = meta[v];
         uint32_t ns = new_start[v];
         for (uint32_t i = lane; i < m.y; i += 64) new_pool[ns + i] = old_pool[m.x + i];
+        if (old_w)
+            for (uint32_t i = lane; i < m.y; i += 64) new_w[ns + i] = old_w[m.x + i];
         if (lane == 0) meta[v] = make_uint2(ns, m.y);
     }
 }
 
-static ripple_status compact_one(ripple_ctx *c, uint2 *meta, uint32_t *capv, uint32_t **pool, uint32_t *top_d,
-                                 uint32_t *scratch_len, uint32_t *scratch_start) {
+static ripple_status compact_one(ripple_ctx *c, uint2 *meta, uint32_t *capv, uint32_t **pool, float **wpool,
+                                 uint32_t *top_d, uint32_t *scratch_len, uint32_t *scratch_start) {
     hipStream_t s = c->stream;
     uint32_t vb = rp_div_up(c->n_cap, 256);
     uint32_t *new_pool = nullptr;
+    float *new_w = nullptr;
     RP_HIP(c, hipMalloc(&new_pool, (size_t)c->pool_cap * 4));
+    if (wpool && *wpool) RP_HIP(c, hipMalloc(&new_w, (size_t)c->pool_cap * 4));
     hipLaunchKernelGGL(k_meta_len, dim3(vb), dim3(256), 0, s, meta, c->n_cap, scratch_len);
     hipLaunchKernelGGL(k_fresh_caps, dim3(vb), dim3(256), 0, s, scratch_len, c->alive, c->n_cap, capv);
     rp_exclusive_scan(s, capv, scratch_start, c->n_cap, c->part_cnt, top_d);
     hipLaunchKernelGGL(k_copy_rows, dim3(c->n_cu * 8), dim3(256), 0, s, meta, scratch_start, c->n_cap, *pool,
-                       new_pool);
+                       new_pool, (const float *)(new_w ? *wpool : nullptr), new_w);
     RP_HIP(c, hipStreamSynchronize(s));
     hipFree(*pool);
     *pool = new_pool;
+    if (new_w) {
+        hipFree(*wpool);
+        *wpool = new_w;
+    }
     return RIPPLE_OK;
 }
 
 ripple_status rp_compact(ripple_ctx *c) {
     // pend_* / dead_* are zero between batches and serve as scratch here
-    ripple_status rc = compact_one(c, c->out_meta, c->out_capv, &c->out_pool, &c->ctr->out_top, c->pend_out,
+    ripple_status rc = compact_one(c, c->out_meta, c->out_capv, &c->out_pool, nullptr, &c->ctr->out_top, c->pend_out,
                                    c->dead_out);
     if (rc != RIPPLE_OK) return rc;
-    rc = compact_one(c, c->in_meta, c->in_capv, &c->in_pool, &c->ctr->in_top, c->pend_in, c->dead_in);
+    rc = compact_one(c, c->in_meta, c->in_capv, &c->in_pool, &c->in_w, &c->ctr->in_top, c->pend_in, c->dead_in);
     if (rc != RIPPLE_OK) return rc;
     hipStream_t s = c->stream;
     RP_HIP(c, hipMemsetAsync(c->pend_out, 0, (size_t)c->n_cap * 4, s));
@@ -251,12 +269,14 @@ struct MutArgs {
     uint2 *out_meta, *in_meta;
     uint32_t *out_capv, *in_capv;
     uint32_t *out_pool, *in_pool;
+    float *in_w;                                 // edge weights parallel to in_pool, or null
     uint32_t *alive, *vstate;
     uint32_t *pend_out, *pend_in, *dead_out, *dead_in;
     uint32_t *hole_out, *hole_in;                // position of a row's latest tombstone (exact when the row has one)
     uint32_t *touch_out, *touch_in;
     uint32_t touch_cap;
     uint32_t *exp_kind, *exp_a, *exp_b;
+    uint32_t *exp_s;                             // structural-list slot of an expanded out-edge (weighted graphs)
     uint32_t exp_cap;
     uint32_t *st_src, *st_dst;
     float *st_sign;
@@ -513,8 +533,9 @@ __global__ __launch_bounds__(256) void k_expand_vdel(MutArgs a) {
                 if (s < a.struct_cap) {
                     a.st_src[s] = w;
                     a.st_dst[s] = y;
-                    a.st_sign[s] = -1.0f;
+                    a.st_sign[s] = -1.0f;                   // times the edge weight: k_expand_apply, which finds the edge in y's in-row
                 }
+                if (a.in_w) a.exp_s[base + j] = s;
                 rp_set_bit(a.bm_sink, y);
             }
         }
@@ -550,6 +571,10 @@ __global__ __launch_bounds__(256) void k_expand_apply(MutArgs a) {
             int p = rp_wave_find(a.in_pool + mi.x, mi.y, x);
             if (lane == 0) {
                 if (p >= 0) {
+                    if (a.in_w) {
+                        const uint32_t slot = a.exp_s[e];
+                        if (slot < a.struct_cap) a.st_sign[slot] = -a.in_w[mi.x + p];
+                    }
                     a.in_pool[mi.x + p] = RP_TOMB;
                     a.hole_in[y] = (uint32_t)p;
                     atomicAdd(&a.dead_in[y], 1u);
@@ -587,16 +612,20 @@ __global__ __launch_bounds__(256) void k_apply_edges(MutArgs a) {
     bool edge = acc && (op.kind == RIPPLE_EDGE_ADD || op.kind == RIPPLE_EDGE_DEL);
     uint32_t s = wave_reserve(&a.ctr->n_struct, edge);
     if (!edge) return;
+    float alpha = 1.0f;                              // the edge's weight (1 on unweighted graphs)
     if (op.kind == RIPPLE_EDGE_DEL) {
+        if (a.in_w) alpha = a.in_w[a.in_meta[op.v].x + a.pos_in[i]];
         a.out_pool[a.out_meta[op.u].x + a.pos_out[i]] = RP_TOMB;
         a.in_pool[a.in_meta[op.v].x + a.pos_in[i]] = RP_TOMB;
         a.hole_out[op.u] = a.pos_out[i];
         a.hole_in[op.v] = a.pos_in[i];
+    } else if (a.in_w) {
+        alpha = __uint_as_float(op.feat_row);       // weighted graphs: EDGE_ADD carries the weight's bits there
     }
     if (s < a.struct_cap) {
         a.st_src[s] = op.u;
         a.st_dst[s] = op.v;
-        a.st_sign[s] = (op.kind == RIPPLE_EDGE_ADD) ? 1.0f : -1.0f;
+        a.st_sign[s] = (op.kind == RIPPLE_EDGE_ADD) ? alpha : -alpha;
     }
     rp_set_bit(a.bm_sink, op.v);
 }
@@ -679,6 +708,7 @@ __global__ __launch_bounds__(256) void k_cleanup_rows(MutArgs a) {
         uint2 *meta = is_out ? a.out_meta : a.in_meta;
         uint32_t *capv = is_out ? a.out_capv : a.in_capv;
         uint32_t *pool = is_out ? a.out_pool : a.in_pool;
+        float *wp = is_out ? nullptr : a.in_w;             // weights travel with the in-row's entries
         uint32_t *deadv = is_out ? a.dead_out : a.dead_in;
         uint32_t *pendv = is_out ? a.pend_out : a.pend_in;
         uint32_t *top = is_out ? &a.ctr->out_top : &a.ctr->in_top;
@@ -689,7 +719,10 @@ __global__ __launch_bounds__(256) void k_cleanup_rows(MutArgs a) {
             const uint32_t hole = is_out ? a.hole_out[x] : a.hole_in[x];
             if (dead == 1 && len && hole < len && pool[m.x + hole] == RP_TOMB) {
                 // the usual case, one deletion in the row: its position is known, the last entry fills it
-                if (hole != len - 1 && lane == 0) pool[m.x + hole] = pool[m.x + len - 1];
+                if (hole != len - 1 && lane == 0) {
+                    pool[m.x + hole] = pool[m.x + len - 1];
+                    if (wp) wp[m.x + hole] = wp[m.x + len - 1];
+                }
                 len -= 1;
             } else if (dead && len) {
                 // Rows are unordered, so holes in the part that stays (the first len - dead entries) are
@@ -701,10 +734,14 @@ __global__ __launch_bounds__(256) void k_cleanup_rows(MutArgs a) {
                 for (uint32_t base = keep_len; base < len; base += 64) {
                     const uint32_t i = base + lane;
                     const uint32_t val = (i < len) ? pool[m.x + i] : RP_TOMB;
+                    const float wv = (wp && i < len) ? wp[m.x + i] : 0.0f;
                     const bool keep = val != RP_TOMB;
                     const unsigned long long mask = __ballot(keep);
                     const uint32_t off = (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-                    if (keep) pool[m.x + keep_len + n_tail + off] = val;
+                    if (keep) {
+                        pool[m.x + keep_len + n_tail + off] = val;
+                        if (wp) wp[m.x + keep_len + n_tail + off] = wv;
+                    }
                     n_tail += (uint32_t)__popcll(mask);
                 }
                 uint32_t filled = 0;                               // holes of the head filled so far
@@ -721,7 +758,10 @@ __global__ __launch_bounds__(256) void k_cleanup_rows(MutArgs a) {
                         const bool hole = i < keep_len && v[t] == RP_TOMB;
                         const unsigned long long mask = __ballot(hole);
                         const uint32_t k = filled + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
-                        if (hole && k < n_tail) pool[m.x + i] = pool[m.x + keep_len + k];
+                        if (hole && k < n_tail) {
+                            pool[m.x + i] = pool[m.x + keep_len + k];
+                            if (wp) wp[m.x + i] = wp[m.x + keep_len + k];
+                        }
                         filled += (uint32_t)__popcll(mask);
                     }
                 }
@@ -747,6 +787,8 @@ __global__ __launch_bounds__(256) void k_cleanup_rows(MutArgs a) {
                             if (i < len) pool[ns + i] = v[t];
                         }
                     }
+                    if (wp)
+                        for (uint32_t i = lane; i < len; i += 64) wp[ns + i] = wp[m.x + i];
                     m.x = ns;
                     if (lane == 0) capv[x] = ncap;
                 } else if (lane == 0) {
@@ -781,8 +823,10 @@ __global__ void k_apply_adds(MutArgs a) {
     if (p < a.out_capv[op.u]) a.out_pool[a.out_meta[op.u].x + p] = op.v;
     else a.ctr->error = 7;
     p = atomicAdd(&((uint32_t *)a.in_meta)[2 * (size_t)op.v + 1], 1u);
-    if (p < a.in_capv[op.v]) a.in_pool[a.in_meta[op.v].x + p] = op.u;
-    else a.ctr->error = 7;
+    if (p < a.in_capv[op.v]) {
+        a.in_pool[a.in_meta[op.v].x + p] = op.u;
+        if (a.in_w) a.in_w[a.in_meta[op.v].x + p] = __uint_as_float(op.feat_row);
+    } else a.ctr->error = 7;
 }
 
 // X^l[v] += sign * H^{l-1}[u] for every changed edge and every layer, taken
@@ -869,6 +913,7 @@ static MutArgs make_args(ripple_ctx *c, uint32_t n_ops) {
     a.in_capv = c->in_capv;
     a.out_pool = c->out_pool;
     a.in_pool = c->in_pool;
+    a.in_w = c->in_w;
     a.alive = c->alive;
     a.vstate = c->vstate;
     a.pend_out = c->pend_out;
@@ -879,6 +924,7 @@ static MutArgs make_args(ripple_ctx *c, uint32_t n_ops) {
     a.touch_in = c->touch_in;
     a.touch_cap = c->touch_cap;
     a.exp_kind = c->exp_kind;
+    a.exp_s = c->exp_s;
     a.exp_a = c->exp_a;
     a.exp_b = c->exp_b;
     a.exp_cap = c->exp_cap;

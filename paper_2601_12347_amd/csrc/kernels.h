@@ -7,7 +7,7 @@
 void rp_exclusive_scan(hipStream_t s, const uint32_t *in, uint32_t *out, uint32_t n, uint32_t *part,
                        uint32_t *total_out);
 ripple_status rp_build_graph(ripple_ctx *c, uint32_t n_vertices, uint64_t n_edges, const uint32_t *src_h,
-                             const uint32_t *dst_h);
+                             const uint32_t *dst_h, const float *w_h);
 ripple_status rp_compact(ripple_ctx *c);
 void rp_launch_batch_reset(ripple_ctx *c);
 void rp_launch_mutate(ripple_ctx *c, uint32_t n_ops, bool has_vertex_add, bool has_vertex_del, bool has_vertex_or_feat);

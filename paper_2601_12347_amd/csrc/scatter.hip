@@ -104,6 +104,7 @@ struct PullArgs {
     const uint32_t *ioff;          // in-degree prefix over the list
     const uint2 *in_meta;
     const uint32_t *in_pool;
+    const float *in_w;             // edge weights parallel to in_pool (weighted-sum layers), or null
     const uint32_t *bm_prev;       // A_{l-1} as bitmap
     uint32_t *bm_cur;              // bitmap of A_l: receivers are marked here when discovering
     const float *D;                // delta rows, indexed by vertex
@@ -115,7 +116,8 @@ struct PullArgs {
     int mode, ratio, allow_disc;
 };
 
-template <int NJ, int DISC>
+// WT = 1: every message is multiplied by its edge's weight (weighted sum, m = alpha (h - h_old), Sec. 3.3.3)
+template <int NJ, int DISC, int WT>
 __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
     if (rp_hop_mode(a.ctr, a.l, a.d, a.mode, a.ratio, a.allow_disc) != (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL)) return;
     const uint32_t count = *a.count_ptr;
@@ -145,6 +147,7 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
         const uint32_t e0 = c * PULL_CHUNK, e1 = min(total, e0 + PULL_CHUNK);
         const bool fits = __shfl(bnd, 63) > e1 - 1;         // every row of the chunk is among the 64 held
         uint32_t my_v[T], my_u[T];
+        float my_w[WT ? T : 1];
         bool dirty[T];
         uint32_t i_nx;
         if (fits) {
@@ -156,8 +159,10 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
                 const uint32_t base = __shfl(rbase, r);
                 my_u[t] = 0;
                 dirty[t] = false;
+                if (WT) my_w[t] = 0.0f;
                 if (e < e1) {
                     my_u[t] = a.in_pool[base + e];
+                    if (WT) my_w[t] = a.in_w[base + e];
                     dirty[t] = (a.bm_prev[my_u[t] >> 5] >> (my_u[t] & 31)) & 1u;
                 }
             }
@@ -169,11 +174,14 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
                 const uint32_t e = e0 + 64 * t + lane;
                 my_v[t] = 0;
                 my_u[t] = 0;
+                if (WT) my_w[t] = 0.0f;
                 dirty[t] = false;
                 if (e < e1) {
                     const uint32_t i = rp_seg_search(a.ioff, i_lo, i_hi, e);
                     my_v[t] = a.list[i];
-                    my_u[t] = a.in_pool[a.in_meta[my_v[t]].x + (e - a.ioff[i])];
+                    const uint32_t pos = a.in_meta[my_v[t]].x + (e - a.ioff[i]);
+                    my_u[t] = a.in_pool[pos];
+                    if (WT) my_w[t] = a.in_w[pos];
                     dirty[t] = (a.bm_prev[my_u[t] >> 5] >> (my_u[t] & 31)) & 1u;
                 }
             }
@@ -233,8 +241,10 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
                             }
                             cur = vk;
                         }
+                        // the weight is fetched again here rather than kept per row in flight (registers)
+                        const float wk = WT ? __shfl(my_w[t], kk[g]) : 1.0f;
 #pragma unroll
-                        for (int j = 0; j < NJ; ++j) acc[j] += r[g][j];
+                        for (int j = 0; j < NJ; ++j) acc[j] += WT ? r[g][j] * wk : r[g][j];
                     }
                 }
             }
@@ -272,14 +282,18 @@ void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow
     a.X = c->X[l];
     a.ctr = c->ctr;
     a.l = l;
-    a.mode = c->opt_scatter;
+    a.mode = rp_layer_mode(c, l);
     a.ratio = c->opt_pull_ratio;
     a.allow_disc = allow_disc ? 1 : 0;
     dim3 grid(c->n_cu * 8), block(256);
-#define PULL_CASE(NJ)                                                                            \
-    do {                                                                                         \
-        if (discover) hipLaunchKernelGGL((k_scatter_pull<NJ, 1>), grid, block, 0, c->stream, a); \
-        else hipLaunchKernelGGL((k_scatter_pull<NJ, 0>), grid, block, 0, c->stream, a);          \
+    const bool wt = c->layers[l - 1].agg == RIPPLE_AGG_WSUM;
+    a.in_w = wt ? c->in_w : nullptr;
+#define PULL_CASE(NJ)                                                                                      \
+    do {                                                                                                   \
+        if (discover && wt) hipLaunchKernelGGL((k_scatter_pull<NJ, 1, 1>), grid, block, 0, c->stream, a);  \
+        else if (discover) hipLaunchKernelGGL((k_scatter_pull<NJ, 1, 0>), grid, block, 0, c->stream, a);   \
+        else if (wt) hipLaunchKernelGGL((k_scatter_pull<NJ, 0, 1>), grid, block, 0, c->stream, a);         \
+        else hipLaunchKernelGGL((k_scatter_pull<NJ, 0, 0>), grid, block, 0, c->stream, a);                 \
     } while (0)
     if (a.d <= 64) PULL_CASE(1);
     else if (a.d <= 128) PULL_CASE(2);
@@ -538,8 +552,8 @@ void rp_launch_scatter_owner(ripple_ctx *c, uint32_t l, bool bootstrap) {
 // bootstrap aggregation: X[v] = sum_{u in in-row(v)} H_prev[u]
 // ---------------------------------------------------------------------------------
 template <int NJ, int STORE>
-__global__ __launch_bounds__(256) void k_pull_all(const uint2 *in_meta, const uint32_t *in_pool, uint32_t n_cap,
-                                                  const void *Hprev, uint32_t lds, uint32_t d, float *X) {
+__global__ __launch_bounds__(256) void k_pull_all(const uint2 *in_meta, const uint32_t *in_pool, const float *in_w,
+                                                  uint32_t n_cap, const void *Hprev, uint32_t lds, uint32_t d, float *X) {
     const int lane = rp_lane();
     const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
     for (uint32_t v = gw; v < n_cap; v += nw) {
@@ -550,16 +564,18 @@ __global__ __launch_bounds__(256) void k_pull_all(const uint2 *in_meta, const ui
         for (uint32_t base = 0; base < m.y; base += 64) {
             const uint32_t i = base + lane;
             const uint32_t my_u = (i < m.y) ? in_pool[m.x + i] : 0u;
+            const float my_w = (in_w && i < m.y) ? in_w[m.x + i] : 1.0f;   // edge weight (weighted-sum layers)
             const int n_here = (int)min(64u, m.y - base);
             for (int k = 0; k < n_here; ++k) {
                 const uint32_t u = __shfl(my_u, k);
+                const float wk = __shfl(my_w, k);
 #pragma unroll
                 for (int j = 0; j < NJ; ++j) {
                     uint32_t col = lane + 64 * j;
                     if (col < d) {
                         size_t idx = (size_t)u * lds + col;
-                        acc[j] += STORE ? __bfloat162float(((const __hip_bfloat16 *)Hprev)[idx])
-                                        : ((const float *)Hprev)[idx];
+                        acc[j] += wk * (STORE ? __bfloat162float(((const __hip_bfloat16 *)Hprev)[idx])
+                                             : ((const float *)Hprev)[idx]);
                     }
                 }
             }
@@ -580,14 +596,15 @@ void rp_launch_pull_all(ripple_ctx *c, uint32_t l) {
     const void *src = proj ? (const void *)c->PD : c->H[l - 1];
     const int store = proj ? 0 : c->store;
     const uint32_t lds = proj ? c->pd_ld : d;
+    const float *w = (c->layers[l - 1].agg == RIPPLE_AGG_WSUM) ? c->in_w : nullptr;
     dim3 grid(c->n_cu * 16), block(256);
 #define PULL_CASE(NJ)                                                                                          \
     do {                                                                                                       \
         if (store)                                                                                             \
-            hipLaunchKernelGGL((k_pull_all<NJ, 1>), grid, block, 0, c->stream, c->in_meta, c->in_pool, c->n_cap, \
+            hipLaunchKernelGGL((k_pull_all<NJ, 1>), grid, block, 0, c->stream, c->in_meta, c->in_pool, w, c->n_cap, \
                                src, lds, d, c->X[l]);                                                          \
         else                                                                                                   \
-            hipLaunchKernelGGL((k_pull_all<NJ, 0>), grid, block, 0, c->stream, c->in_meta, c->in_pool, c->n_cap, \
+            hipLaunchKernelGGL((k_pull_all<NJ, 0>), grid, block, 0, c->stream, c->in_meta, c->in_pool, w, c->n_cap, \
                                src, lds, d, c->X[l]);                                                          \
     } while (0)
     if (d <= 64) PULL_CASE(1);

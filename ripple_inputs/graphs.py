@@ -107,6 +107,7 @@ class Config:
     feat_seed: int = 12348
     weight_seed: int = 12349
     stream_seed: int = 12350
+    weighted: bool = False      # per-edge weights (weighted-sum workloads), seed = graph_seed + 100
 
     @property
     def vertex_capacity(self) -> int:
@@ -139,6 +140,12 @@ CONFIGS = [
     Config("dense_gcn_sum_bf16", 2_449_029, 123_718_280, 2.3, 0.0002, 100, "gcn_sum",
            (100, 256, 256, 47), "bf16", (10000,), _mix_with_vertex_ops(0.01, 0.01),
            1 << 17, stream_seed=12354),
+    # beyond the five of the scope table: the paper's GC-W workload (GraphConv with weighted sum) on the
+    # sparse and dense graphs
+    Config("sparse_gcn_wsum", 169_343, 1_166_243, 2.1, 0.01, 128, "gcn_wsum",
+           (128, 256, 256, 40), "f32", (1000,), _MIX3, 4096, stream_seed=12355, weighted=True),
+    Config("dense_gcn_wsum", 2_449_029, 123_718_280, 2.3, 0.0002, 100, "gcn_wsum",
+           (100, 256, 256, 47), "f32", (10000,), _MIX3, 4096, stream_seed=12356, weighted=True),
 ]
 
 

@@ -12,12 +12,16 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}      # max relative error per layer (metric: o
 
 class Pair:
     def __init__(self, n, cap, src, dst, feats, model, store="f32", edge_capacity=None, project_first=True,
-                 self_cache=True, deterministic=False):
+                 self_cache=True, deterministic=False, weights=None):
         self.n, self.cap, self.model, self.store = n, cap, model, store
         self.widths = [model[0]["d_in"]] + [l["d_out"] for l in model]
         self.L = len(model)
-        self.ora = oracle.GraphState(n, cap, src, dst, feats)
-        self.ctx = rp.ripple_init_graph(n, cap, src, dst, feats, store=store, edge_capacity=edge_capacity)
+        self.ora = oracle.GraphState(n, cap, src, dst, feats, weights=weights)
+        if weights is None:
+            self.ctx = rp.ripple_init_graph(n, cap, src, dst, feats, store=store, edge_capacity=edge_capacity)
+        else:
+            self.ctx = rp.ripple_init_graph_weighted(n, cap, src, dst, weights, feats, store=store,
+                                                     edge_capacity=edge_capacity)
         if not project_first:
             rp.ripple_set_option(self.ctx, rp.OPT_PROJECT_FIRST, 0)
         if not self_cache:
@@ -60,7 +64,10 @@ class Pair:
                 h_prev = h_prev @ (w[lay["d_in"]:] if lay["self"] == "concat" else w)
             assert width == h_prev.shape[1]
             want = np.zeros_like(h_prev)
-            np.add.at(want, dst, h_prev[src])
+            if self.model[l - 1]["agg"] == "wsum":
+                np.add.at(want, dst, h_prev[src] * self.ora.edge_weights()[:, None])
+            else:
+                np.add.at(want, dst, h_prev[src])
             got = rp.ripple_get_aggregates(self.ctx, l, width, n_rows=self.cap)
             err = oracle.max_rel_err(got, want, self.ora.alive)
             assert err <= tol, f"aggregate {l}: {err:.3e}"
@@ -105,26 +112,29 @@ class Pair:
 
 
 def make_pair(n=300, e=1500, d0=12, kind="gcn_sum", widths=(12, 20, 8), store="f32", seed=0, slack=64,
-              gamma=2.1, top_share=0.03, edge_capacity=None, project_first=True, self_cache=True, deterministic=False):
+              gamma=2.1, top_share=0.03, edge_capacity=None, project_first=True, self_cache=True, deterministic=False,
+              weighted=False):
     src, dst, out_law, in_law = ri.chung_lu_graph(n, e, gamma, top_share, seed)
     feats = ri.features(n, d0, seed + 1)
     model = ri.make_model(kind, widths, seed + 2)
+    weights = ri.edge_weights(len(src), seed + 3) if weighted else None
     pair = Pair(n, n + slack, src, dst, feats, model, store=store, edge_capacity=edge_capacity,
-                project_first=project_first, self_cache=self_cache, deterministic=deterministic)
+                project_first=project_first, self_cache=self_cache, deterministic=deterministic, weights=weights)
     return pair, (src, dst, out_law, in_law)
 
 
-def make_stream(pair, graph, mix, seed):
+def make_stream(pair, graph, mix, seed, weighted=False):
     src, dst, out_law, in_law = graph
-    return ri.UpdateStream(pair.n, pair.cap, src, dst, out_law, in_law, pair.widths[0], mix, seed)
+    return ri.UpdateStream(pair.n, pair.cap, src, dst, out_law, in_law, pair.widths[0], mix, seed, weighted=weighted)
 
 
 def config_pair(cfg, store=None):
     src, dst, out_law, in_law = ri.chung_lu_graph(cfg.n, cfg.e, cfg.gamma, cfg.top_share, cfg.graph_seed)
     feats = ri.features(cfg.n, cfg.d0, cfg.feat_seed)
     model = ri.make_model(cfg.model, cfg.widths, cfg.weight_seed)
+    weights = ri.edge_weights(len(src), cfg.graph_seed + 100) if cfg.weighted else None
     pair = Pair(cfg.n, cfg.vertex_capacity, src, dst, feats, model, store=store or cfg.store,
-                edge_capacity=cfg.edge_capacity)
+                edge_capacity=cfg.edge_capacity, weights=weights)
     stream = ri.UpdateStream(cfg.n, cfg.vertex_capacity, src, dst, out_law, in_law, cfg.d0, cfg.mix,
-                             cfg.stream_seed)
+                             cfg.stream_seed, weighted=cfg.weighted)
     return pair, stream

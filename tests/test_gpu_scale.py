@@ -31,6 +31,23 @@ def test_sparse_sage_mean_all_batch_sizes():
         pair.close()
 
 
+def test_sparse_gcn_weighted_sum():
+    """The paper's GC-W workload on the sparse graph: all rows of all layers after every batch."""
+    cfg = ri.get_config("sparse_gcn_wsum")
+    print("case", cfg.name, flush=True)
+    pair, stream = config_pair(cfg)
+    try:
+        pair.check_embeddings()
+        for b, bs in enumerate([10, 1000, 1000]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload)
+        pair.check_graph()
+        pair.check_aggregates()
+    finally:
+        pair.close()
+
+
 def test_sparse_gin_sum_with_vertex_operations():
     cfg = ri.get_config("sparse_gin_sum")
     print("case", cfg.name, flush=True)

@@ -344,3 +344,41 @@ def test_deterministic_mode_is_bit_reproducible(kind, widths, store):
     finally:
         pair.close()
         twin.close()
+
+
+@pytest.mark.parametrize("kind,widths,store", [("gcn_wsum", (100, 256, 47), "f32"), ("sage_wsum", (16, 40, 24, 10), "f32"),
+                                               ("gcn_wsum", (32, 64, 12), "bf16")])
+def test_weighted_sum_aggregation(kind, widths, store):
+    """Table 1's weighted sum (m = alpha (h - h_old), Sec. 3.3.3): every edge has a weight fixed at its
+    creation (initial edges: an array; later ones: in the EDGE_ADD operation). Vertex deletions remove
+    weighted edges, rows are relocated and the pools rebuilt along the way; the cached aggregates must
+    stay sum_u alpha_uv H[u] and the embeddings must match the oracle."""
+    print("case weighted sum", kind, store, flush=True)
+    pair, graph = make_pair(n=1500, e=14000, d0=widths[0], kind=kind, widths=widths, seed=131, slack=256, store=store,
+                            weighted=True, top_share=0.05)
+    stream = make_stream(pair, graph, MIXV, 133, weighted=True)
+    tol = 1e-3 if store == "bf16" else None
+    try:
+        pair.check_aggregates(tol=tol)
+        for b, bs in enumerate([2, 50, 300, 40, 600]):
+            print(" batch", b, bs, flush=True)
+            if b == 3:
+                rp.ripple_compact(pair.ctx)                   # the weights move with the rebuilt in-rows
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload)
+            pair.check_aggregates(tol=tol)
+        pair.check_graph()
+    finally:
+        pair.close()
+
+
+def test_weighted_layer_needs_a_weighted_graph():
+    pair, _ = make_pair(n=50, e=200, d0=8, kind="gcn_sum", widths=(8, 6), seed=5)
+    try:
+        ctx = rp.ripple_init_graph(4, 8, np.array([0, 1], dtype=np.uint32), np.array([1, 2], dtype=np.uint32),
+                                   np.zeros((4, 8), dtype=np.float32))
+        with pytest.raises(rp.RippleError):
+            rp.ripple_load_model(ctx, ri.make_model("gcn_wsum", (8, 6), 1))
+        rp.ripple_destroy(ctx)
+    finally:
+        pair.close()
