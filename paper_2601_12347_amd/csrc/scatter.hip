@@ -122,7 +122,9 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
     if (rp_hop_mode(a.ctr, a.l, a.d, a.mode, a.ratio, a.allow_disc) != (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL)) return;
     const uint32_t count = *a.count_ptr;
     if (count == 0) return;
-    constexpr int G = (NJ >= 8) ? 2 : 16 / NJ;              // delta rows gathered per round trip
+    // delta rows gathered per round trip; the weighted one-column kernel takes 12 so that it stays
+    // within 64 registers (eight waves per SIMD), which matters more here than the deeper round
+    constexpr int G = (NJ >= 8) ? 2 : (WT && NJ == 1) ? 12 : 16 / NJ;
     constexpr int T = PULL_CHUNK / 64;                      // in-edges examined per lane and chunk
     const int lane = rp_lane();
     const uint32_t d = a.d;
