@@ -19,6 +19,12 @@ Readings taken where the paper leaves a choice (each is listed in the design doc):
   * sum / mean / weighted sum as in Table 1 (weighted sum: x_v = sum over in-neighbours u of
     alpha_uv h_u, alpha_uv a per-edge weight fixed when the edge is created; Sec. 3.3.3, "Other
     linear aggregators"); mean of an empty neighbourhood is the zero vector;
+  * max / min as in Table 1, element by element over the in-neighbours' rows; an empty
+    neighbourhood gives the zero vector. The paper's hybrid treatment of these aggregators
+    (Sec. 3.4.2: leave unchanged / update incrementally / recompute) reaches the recomputed
+    values exactly, so the oracle is again the definition; which vertices a pruned propagation
+    visits is not unique, so for these layers the topological sets are an upper bound and the
+    rows whose value really changes a lower bound of what an implementation may report;
   * GraphConv: h = act(x W + b), no self term (Sec. 3.3.3 example);
     GraphSAGE: h = act(h_self W_self + x W_neigh + b) (Eq. 2's UPDATE takes both);
     GIN: h = act(MLP((1+eps) h_self + x)) (Sec. 6.3.1: GI-S adds the vertex's
@@ -33,7 +39,9 @@ Readings taken where the paper leaves a choice (each is listed in the design doc):
 Parity pins (tests/test_oracle_*.py): brute-force per-vertex neighbourhood
 recursion on small graphs, the closed form (A^T)^L H W1..WL for the linear
 case, the all-ones mean fixed point, isolated vertices, the paper's worked
-edge-addition example for the affected sets, and planted-mistake checks.
+edge-addition example for the affected sets, planted-mistake checks; for max / min the
+brute force, the values printed with the paper's three max cases, max(h) = -min(-h),
+min <= mean <= max, and the one-in-neighbour graph where every aggregator agrees.
 The numeric values of the paper's own runs are unpinned: it prints none.
 """
 from __future__ import annotations
@@ -256,6 +264,8 @@ def aggregate(a_in: InAdjacency, h_prev: np.ndarray, agg: str, rows=None) -> np.
         a = a_in.alpha if rows is None else a_in.alpha[rows]
         return a @ h_prev
     a = a_in.ones if rows is None else a_in.ones[rows]
+    if agg in ("max", "min"):                                    # element-wise extreme (Table 1; Sec. 3.4.2)
+        return _extreme(a, h_prev, np.maximum if agg == "max" else np.minimum)
     x = a @ h_prev                                               # sum over in-neighbours
     if agg == "mean":
         deg = np.asarray(a.getnnz(axis=1), dtype=np.float64)     # in-degree
@@ -263,6 +273,32 @@ def aggregate(a_in: InAdjacency, h_prev: np.ndarray, agg: str, rows=None) -> np.
     elif agg != "sum":
         raise ValueError(agg)
     return x
+
+
+SLAB_ELEMENTS = 1 << 26          # numbers gathered at a time by the max / min aggregation
+
+
+def _extreme(a, h_prev: np.ndarray, op) -> np.ndarray:
+    """Row v of the result: op reduced element by element over the rows h_prev[u] of v's
+    in-neighbours u (the column indices of row v of `a`); a vertex without in-neighbours gets 0.
+    Rows are taken in slabs so that the gathered neighbour rows stay bounded in memory."""
+    a = a.tocsr()
+    indptr, indices = a.indptr, a.indices
+    out = np.zeros((a.shape[0], h_prev.shape[1]))
+    rows = np.flatnonzero(np.diff(indptr) > 0)                   # rows with at least one in-neighbour
+    budget = max(1, SLAB_ELEMENTS // max(1, h_prev.shape[1]))    # gathered neighbour rows per slab
+    i = 0
+    while i < rows.size:
+        lo = indptr[rows[i]]
+        j = int(np.searchsorted(indptr[rows + 1], lo + budget, side="right"))
+        j = max(j, i + 1)
+        take = rows[i:j]
+        hi = indptr[take[-1] + 1]
+        gathered = h_prev[indices[lo:hi]]
+        # consecutive non-empty rows are adjacent in `indices`, so each segment ends where the next starts
+        out[take] = op.reduceat(gathered, indptr[take] - lo, axis=0)
+        i = j
+    return out
 
 
 def layer_rows(state: GraphState, layer: dict, h_prev: np.ndarray, a_in: InAdjacency, rows=None) -> np.ndarray:

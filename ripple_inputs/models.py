@@ -2,7 +2,7 @@
 
 A model is a list of per-layer dicts. Keys:
   d_in, d_hidden (0 = single linear map), d_out,
-  agg  'sum' | 'mean',
+  agg  'sum' | 'mean' | 'wsum' (needs edge weights) | 'max' | 'min',
   self 'none' | 'concat' (GraphSAGE: rows [0,d_in) of W0 multiply the vertex's
        own embedding, rows [d_in,2*d_in) the aggregate) | 'add' (GIN:
        (1+eps)*own + aggregate),
@@ -38,9 +38,11 @@ def make_model(kind: str, widths, seed: int, last_act: str = "none"):
             lay.update(agg="sum", self="none", W0=glorot(rng, d_in, d_out), b0=_bias(rng, d_out))
         elif kind == "gcn_mean":
             lay.update(agg="mean", self="none", W0=glorot(rng, d_in, d_out), b0=_bias(rng, d_out))
+        elif kind in ("gcn_max", "gcn_min"):
+            lay.update(agg=kind.split("_")[1], self="none", W0=glorot(rng, d_in, d_out), b0=_bias(rng, d_out))
         elif kind == "gcn_wsum":
             lay.update(agg="wsum", self="none", W0=glorot(rng, d_in, d_out), b0=_bias(rng, d_out))
-        elif kind in ("sage_mean", "sage_sum", "sage_wsum"):
+        elif kind in ("sage_mean", "sage_sum", "sage_wsum", "sage_max", "sage_min"):
             w_self, w_neigh = glorot(rng, d_in, d_out), glorot(rng, d_in, d_out)
             lay.update(agg=kind.split("_")[1], self="concat",
                        W0=np.ascontiguousarray(np.vstack([w_self, w_neigh])), b0=_bias(rng, d_out))

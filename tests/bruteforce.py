@@ -31,8 +31,18 @@ def embed(v, l, model, feats, nbrs, alive, memo, alpha=None):
     else:
         lay = model[l - 1]
         acc = np.zeros(lay["d_in"])
+        first = True
         for u in nbrs[v]:
             term = embed(u, l - 1, model, feats, nbrs, alive, memo, alpha)
+            if lay["agg"] in ("max", "min"):          # element by element, plain comparisons
+                if first:
+                    acc = np.array(term, dtype=np.float64)
+                else:
+                    for k in range(lay["d_in"]):
+                        if (term[k] > acc[k]) if lay["agg"] == "max" else (term[k] < acc[k]):
+                            acc[k] = term[k]
+                first = False
+                continue
             acc = acc + (alpha[(u, v)] * term if lay["agg"] == "wsum" else term)
         if lay["agg"] == "mean" and len(nbrs[v]) > 0:
             acc = acc / len(nbrs[v])

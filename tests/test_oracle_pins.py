@@ -368,3 +368,80 @@ def test_weighted_sum_after_a_batch():
     for v in range(st.cap):
         want = embed(v, len(model), model, st.h0, nbrs, st.alive, memo, alpha)
         np.testing.assert_allclose(hs[-1][v], want, rtol=1e-12, atol=1e-12)
+
+
+# ---- max / min aggregation (Table 1, Sec. 3.4.2 "Monotonic Aggregation Functions") ----------------
+@pytest.mark.parametrize("kind", ["gcn_max", "gcn_min", "sage_max"])
+@pytest.mark.parametrize("seed", [0, 1])
+def test_extreme_aggregation_equals_vertexwise_bruteforce(kind, seed, monkeypatch):
+    st, model, src, dst, feats = small_case(seed, kind=kind)
+    if seed == 1:
+        monkeypatch.setattr(oracle.ripple_oracle, "SLAB_ELEMENTS", 64)    # many slabs of a few rows each
+    hs = oracle.full_recompute(st, model)
+    nbrs = in_lists(st.cap, src, dst)
+    f = np.zeros((st.cap, feats.shape[1]))
+    f[: len(feats)] = feats
+    memo = {}
+    for l in range(len(model) + 1):
+        for v in range(st.cap):
+            want = embed(v, l, model, f, nbrs, st.alive, memo)
+            np.testing.assert_allclose(hs[l][v], want, rtol=1e-12, atol=1e-12)
+
+
+def test_max_cases_of_the_paper():
+    """The values printed with the three cases of Sec. 3.4.2 (tests/golden/max_cases.txt)."""
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "max_cases.txt")) if l.strip() and not l.startswith("#")]
+    assert [r[5] for r in rows] == ["unchanged", "incremental", "recompute"]
+    for b, c_old, c_new, a_before, a_after, _ in rows:
+        # vertices: 0 = A, 1 = B, 2 = C; edges B -> A and C -> A
+        for c_val, want in ((c_old, a_before), (c_new, a_after)):
+            feats = np.array([[0.0], [float(b)], [float(c_val)]])
+            st = oracle.GraphState(3, 3, np.array([1, 2]), np.array([0, 0]), feats)
+            x = oracle.aggregate(oracle.in_adjacency(st), st.h0, "max")
+            assert x[0, 0] == float(want)
+            assert x[1, 0] == 0.0 and x[2, 0] == 0.0            # no in-neighbours: 0
+
+
+def test_extreme_aggregation_identities():
+    st, model, src, dst, feats = small_case(4, kind="gcn_max")
+    a_in = oracle.in_adjacency(st)
+    h = np.random.default_rng(9).standard_normal((st.cap, 6))
+    mx, mn = oracle.aggregate(a_in, h, "max"), oracle.aggregate(a_in, h, "min")
+    mean = oracle.aggregate(a_in, h, "mean")
+    np.testing.assert_array_equal(mx, -oracle.aggregate(a_in, -h, "min"))       # duality
+    has = np.asarray(a_in.ones.getnnz(axis=1)) > 0
+    assert (mn[has] <= mean[has] + 1e-15).all() and (mean[has] <= mx[has] + 1e-15).all()
+    assert (mx[~has] == 0).all() and (mn[~has] == 0).all() and (~has).any()
+    # every value of the result is one of the neighbours' values, and none of them exceeds it
+    nbrs = in_lists(st.cap, src, dst)
+    for v in np.flatnonzero(has)[:10]:
+        block = h[nbrs[v]]
+        assert (block <= mx[v]).all() and (block >= mn[v]).all()
+        assert all(mx[v, k] in block[:, k] and mn[v, k] in block[:, k] for k in range(6))
+    # one in-neighbour each (a cycle): max = min = sum = mean = the predecessor's row
+    n = 12
+    cyc = oracle.GraphState(n, n, np.arange(n), (np.arange(n) + 1) % n, h[:n])
+    a_c = oracle.in_adjacency(cyc)
+    want = np.roll(h[:n], 1, axis=0)
+    for agg in ("max", "min", "sum", "mean"):
+        np.testing.assert_array_equal(oracle.aggregate(a_c, h[:n], agg), want)
+
+
+def test_max_after_a_batch_with_all_update_kinds():
+    st, model, src, dst, feats = small_case(11, kind="sage_max")
+    n = len(feats)
+    rng = np.random.default_rng(5)
+    payload = rng.standard_normal((2, feats.shape[1]))
+    free = next((u, v) for u in range(10) for v in range(10) if u != v and not st.has_edge(u, v))
+    ops = [(ri.OP_EDGE_DEL, int(src[0]), int(dst[0]), 0), (ri.OP_EDGE_ADD, free[0], free[1], 0),
+           (ri.OP_FEAT_UPDATE, 5, 0, 0), (ri.OP_VERTEX_ADD, n, 0, 1), (ri.OP_EDGE_ADD, n, 4, 0),
+           (ri.OP_EDGE_ADD, 6, n, 0), (ri.OP_VERTEX_DEL, 9, 0, 0)]
+    rec = st.apply_batch(np.array(ops, dtype=np.uint32), payload)
+    assert rec.accepted.all()
+    hs = oracle.full_recompute(st, model)
+    es, ed = st.edges()
+    nbrs = in_lists(st.cap, es, ed)
+    memo = {}
+    for v in range(st.cap):
+        want = embed(v, len(model), model, st.h0, nbrs, st.alive, memo)
+        np.testing.assert_allclose(hs[-1][v], want, rtol=1e-12, atol=1e-12)
