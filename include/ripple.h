@@ -60,7 +60,10 @@ typedef struct {
     uint32_t feat_row;   /* row of the batch's feature payload; ignored for edge ops and VERTEX_DEL */
 } ripple_update;         /* 16 bytes */
 
-typedef enum { RIPPLE_AGG_SUM = 0, RIPPLE_AGG_MEAN = 1, RIPPLE_AGG_WSUM = 2 } ripple_agg;   /* Table 1 */
+typedef enum {
+    RIPPLE_AGG_SUM = 0, RIPPLE_AGG_MEAN = 1, RIPPLE_AGG_WSUM = 2,   /* linear (Table 1, Sec. 3.3.3) */
+    RIPPLE_AGG_MAX = 3, RIPPLE_AGG_MIN = 4                          /* monotonic (Table 1, Sec. 3.4.2) */
+} ripple_agg;
 typedef enum {
     RIPPLE_SELF_NONE = 0,    /* GraphConv:  h = act(x W0 + b0)                               */
     RIPPLE_SELF_CONCAT = 1,  /* GraphSAGE:  h = act([h_self | x] W0 + b0), W0 is [2 d_in x .] */
@@ -74,7 +77,13 @@ typedef enum { RIPPLE_STORE_F32 = 0, RIPPLE_STORE_BF16 = 1 } ripple_store;
  * layer's embeddings of the vertex's in-neighbours. With d_hidden == 0 the
  * update is one linear map W0 [K x d_out], K = d_in (2*d_in for SELF_CONCAT);
  * with d_hidden > 0 it is W0 [K x d_hidden], act_inner, W1 [d_hidden x d_out].
- * act_out is applied last. Weights and biases are float32 host arrays. */
+ * act_out is applied last. Weights and biases are float32 host arrays.
+ * RIPPLE_AGG_MAX / RIPPLE_AGG_MIN take the element-wise extreme over the in-neighbours' rows (zero
+ * for a vertex without in-neighbours) and are maintained with the hybrid scheme of Sec. 3.4.2: a
+ * vertex that hears from a changed in-neighbour keeps its aggregate, raises it from the message, or
+ * recomputes it from all its in-neighbours; a vertex whose in-edges changed always recomputes. Such
+ * layers are not handled project-first and are refused in the deterministic mode (they need none:
+ * their result does not depend on any order). */
 typedef struct {
     uint32_t d_in, d_hidden, d_out;
     uint32_t agg;          /* ripple_agg  */
@@ -100,6 +109,11 @@ typedef struct {
     uint32_t affected[RIPPLE_MAX_LAYERS + 1];     /* a_l = |A_l|, l = 0..L (Sec. 3.5)            */
     uint64_t messages[RIPPLE_MAX_LAYERS + 1];     /* delta messages sent into layer l (index 0 unused) */
     uint32_t n_structural;                        /* added/removed edges incl. those of deleted vertices */
+    /* max / min layers only (Sec. 3.4.2): vertices that received a message or had an in-edge changed at
+     * hop l, split by what was done with them; unchanged ones are not in A_l and send nothing on */
+    uint32_t mono_unchanged[RIPPLE_MAX_LAYERS + 1];
+    uint32_t mono_incremental[RIPPLE_MAX_LAYERS + 1];
+    uint32_t mono_recomputed[RIPPLE_MAX_LAYERS + 1];
 } ripple_batch_result;
 
 /* Accumulated per-kernel-class timing and work counters (RIPPLE_OPT_TIMING). */
@@ -193,7 +207,10 @@ ripple_status ripple_get_layer_info(ripple_ctx *ctx, uint32_t layer, uint32_t *a
 
 /* Vertices the last batch could affect at `layer` (0..L), ascending, into
  * ids_out (host, room for cap ids); *n_out receives the set size even when it
- * exceeds cap (then only cap ids are written). */
+ * exceeds cap (then only cap ids are written). At and below a max / min layer the
+ * set is pruned (Sec. 3.4.2): it holds the vertices whose aggregate changed (plus
+ * created vertices and, for layers with a self term, the previous hop's set), a
+ * subset of the topological set and a superset of the rows whose value changed. */
 ripple_status ripple_get_affected(ripple_ctx *ctx, uint32_t layer, uint32_t *ids_out, uint32_t cap,
                                   uint32_t *n_out);
 

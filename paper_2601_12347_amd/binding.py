@@ -23,7 +23,7 @@ RIPPLE_MAX_LAYERS = 8
 RIPPLE_N_PHASES = 8
 PHASES = ["ingest", "struct", "frontier", "scatter", "compact", "transform", "other", "total"]
 OPT_TIMING, OPT_SCATTER_MODE, OPT_PULL_RATIO, OPT_PROJECT_FIRST, OPT_BF16_MFMA, OPT_SELF_CACHE, OPT_DETERMINISTIC = 0, 1, 2, 3, 4, 5, 6
-AGG = {"sum": 0, "mean": 1, "wsum": 2}
+AGG = {"sum": 0, "mean": 1, "wsum": 2, "max": 3, "min": 4}
 SELF = {"none": 0, "concat": 1, "add": 2}
 ACT = {"none": 0, "relu": 1}
 STORE = {"f32": 0, "bf16": 1}
@@ -53,7 +53,10 @@ class BatchResult(C.Structure):
                 ("n_edges", C.c_uint64),
                 ("affected", C.c_uint32 * (RIPPLE_MAX_LAYERS + 1)),
                 ("messages", C.c_uint64 * (RIPPLE_MAX_LAYERS + 1)),
-                ("n_structural", C.c_uint32)]
+                ("n_structural", C.c_uint32),
+                ("mono_unchanged", C.c_uint32 * (RIPPLE_MAX_LAYERS + 1)),
+                ("mono_incremental", C.c_uint32 * (RIPPLE_MAX_LAYERS + 1)),
+                ("mono_recomputed", C.c_uint32 * (RIPPLE_MAX_LAYERS + 1))]
 
 
 class Stats(C.Structure):

@@ -305,14 +305,14 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
     uint32_t prev = c->d[0];
     for (uint32_t l = 0; l < n_layers; ++l) {
         const ripple_layer_desc &s = layers[l];
-        if (s.d_in != prev || s.d_out == 0 || s.d_out > 1024 || s.d_hidden > 1024 || s.agg > RIPPLE_AGG_WSUM ||
+        if (s.d_in != prev || s.d_out == 0 || s.d_out > 1024 || s.d_hidden > 1024 || s.agg > RIPPLE_AGG_MIN ||
             s.self_mode > RIPPLE_SELF_ADD || s.act_inner > RIPPLE_ACT_RELU || s.act_out > RIPPLE_ACT_RELU || !s.W0 ||
             !s.b0 || (s.d_hidden && (!s.W1 || !s.b1)))
             return fail(c, RIPPLE_EINVAL, "bad layer descriptor (widths must chain, dims <= 1024, pointers set)");
         if (s.agg == RIPPLE_AGG_WSUM && !c->in_w)
             return fail(c, RIPPLE_EINVAL, "weighted-sum layer on a graph that was built without edge weights");
-        if (s.agg == RIPPLE_AGG_WSUM && c->opt_deterministic)
-            return fail(c, RIPPLE_EINVAL, "the deterministic mode does not take weighted-sum layers");
+        if ((s.agg == RIPPLE_AGG_WSUM || s.agg >= RIPPLE_AGG_MAX) && c->opt_deterministic)
+            return fail(c, RIPPLE_EINVAL, "the deterministic mode takes sum and mean layers only");
         prev = s.d_out;
     }
     c->L = n_layers;
@@ -348,7 +348,7 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
             RP_HIP(c, hipMemcpy(ly.W0h, wt.data(), wt.size() * 2, hipMemcpyHostToDevice));
         }
         // project first where the single linear map shrinks the row at least by half
-        ly.proj = (c->opt_project && !c->opt_deterministic && s.d_hidden == 0 && s.self_mode != RIPPLE_SELF_ADD && 2 * s.d_out <= s.d_in) ? 1u : 0u;
+        ly.proj = (c->opt_project && !c->opt_deterministic && s.agg < RIPPLE_AGG_MAX && s.d_hidden == 0 && s.self_mode != RIPPLE_SELF_ADD && 2 * s.d_out <= s.d_in) ? 1u : 0u;
         ly.selfc = (c->opt_selfcache && s.d_hidden == 0 && s.self_mode == RIPPLE_SELF_CONCAT) ? 1u : 0u;
         if (ly.proj || ly.selfc) {
             std::vector<float> zeros(ly.N0pad, 0.0f);
@@ -633,6 +633,29 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
         return;
     }
     for (uint32_t l = 1; l <= c->L; ++l) {
+        if (rp_layer_mono(c, l)) {                     // max / min: keep, raise or recompute, then prune (Sec. 3.4.2)
+            t = rp_timer_begin(c);
+            rp_launch_frontier_mark(c, l, false);
+            rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
+            t = rp_timer_begin(c);
+            rp_launch_candidates(c, l);
+            rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l, false);
+            if (c->layers[l - 1].selfc) {
+                t = rp_timer_begin(c);
+                rp_launch_self_project(c, l, c->list[l - 1], &c->ctr->a[l - 1]);
+                rp_timer_end(c, t, RIPPLE_PH_OTHER, (int)l);
+            }
+            t = rp_timer_begin(c);
+            rp_launch_scatter_mono(c, l);
+            rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l);
+            t = rp_timer_begin(c);
+            rp_launch_frontier_compact(c, l, layer_self(c, l), l < c->L, false, multi, true);
+            rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l);
+            t = rp_timer_begin(c);
+            rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], l < c->L);
+            rp_timer_end(c, t, RIPPLE_PH_TRANSFORM, (int)l);
+            continue;
+        }
         // hop 1 always pushes: hop-0 rows are in operation order, not ranked by vertex id. Where the
         // previous batch pushed with a wide margin the pull kernel is not even enqueued (pushing is
         // always correct; the prediction only saves a launch). The same goes for the discovering
@@ -737,6 +760,7 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
     ripple_status rc = RIPPLE_OK;
     uint32_t applied = 0, rejected = 0, n_struct = 0, compactions = 0;
     uint64_t msgs[RIPPLE_MAX_LAYERS + 1] = {0}, tchd[RIPPLE_MAX_LAYERS + 1] = {0};
+    uint32_t mono[3][RIPPLE_MAX_LAYERS + 1] = {{0}};
     for (size_t p = 0; p < pieces.size() && rc == RIPPLE_OK; ++p) {
         const SubBatch &sb = pieces[p];
         const uint32_t n = sb.end - sb.begin;
@@ -786,6 +810,8 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
         for (uint32_t l = 1; l <= c->L; ++l) {
             msgs[l] += h.m[l];
             tchd[l] += h.touched[l];
+            for (int k = 0; k < 3; ++k) mono[k][l] += h.mono[k][l];
+            c->last_cand[l] = h.mono[0][l] + h.mono[1][l] + h.mono[2][l];
             // pull wins when m * row_bytes * ratio >= 8 * in-edges; remember if push won by a factor of 16
             const unsigned long long lhs = (unsigned long long)h.m[l] * c->xw[l] * 4ull * (unsigned)c->opt_pull_ratio * 16ull;
             c->push_margin[l] = lhs < 8ull * h.isum[l];
@@ -827,6 +853,9 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
         for (uint32_t l = 0; l <= c->L; ++l) {
             res->affected[l] = c->last_a[l];
             res->messages[l] = msgs[l];
+            res->mono_unchanged[l] = mono[0][l];
+            res->mono_incremental[l] = mono[1][l];
+            res->mono_recomputed[l] = mono[2][l];
         }
     }
     return RIPPLE_OK;

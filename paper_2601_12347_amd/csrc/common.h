@@ -40,6 +40,7 @@ struct DevCtr {                      // device-resident counters, one instance p
     uint32_t n_vadd;
     uint32_t abort_flag;                      // written by k_capacity's last workgroup: 0 ok, bit0 pool, bit1 edges, bit2 scratch
     uint32_t n_all;                           // live vertices listed for a discovering hop
+    uint32_t mono[3][RIPPLE_MAX_LAYERS + 1];  // max / min hops: candidates left unchanged / raised from the messages / recomputed
     unsigned long long n_edges;
     uint32_t blocks_done;                     // workgroups of k_capacity that have finished (0 between launches)
     uint32_t pad2;
@@ -140,6 +141,7 @@ struct ripple_ctx {
 
     // last batch's sets (reporting)
     uint32_t last_a[RIPPLE_MAX_LAYERS + 1] = {0};
+    uint32_t last_cand[RIPPLE_MAX_LAYERS + 1] = {0};    // candidates of the last batch's max / min hops (a size hint)
     bool last_from_rep = false;
     bool push_margin[RIPPLE_MAX_LAYERS + 1] = {false};  // last batch pushed at this hop by a wide margin
     bool disc_near[RIPPLE_MAX_LAYERS + 1] = {false};    // last batch's hop was within reach of the discovering mode
@@ -168,6 +170,9 @@ struct ripple_ctx {
     } while (0)
 
 // scatter policy of hop l as the kernels see it (see rp_hop_mode)
+static inline bool rp_layer_mono(const ripple_ctx *c, uint32_t l) {      // layer l (1-based) aggregates with max or min
+    return l >= 1 && l <= c->L && c->layers[l - 1].agg >= RIPPLE_AGG_MAX;
+}
 static inline int rp_layer_mode(const ripple_ctx *c, uint32_t l) {
     return c->layers[l - 1].agg == RIPPLE_AGG_WSUM ? 4 : c->opt_scatter;
 }

@@ -422,13 +422,15 @@ void rp_launch_alive_list(ripple_ctx *c) {
 
 // bitmap of layer l, merged with S, V_added (and A_{l-1} when self_term) -> list[l], ctr->a[l];
 // want_out: eoff[l] and ctr->m[l+1] (the next hop's edge walk); want_in: ioff[l], ctr->isum[l]
+// pruned: bm[l] already is the hop's final set (max / min layers: candidates whose aggregate did not
+// change have been taken out again), so neither marks nor S are merged into it
 void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool want_out, bool want_in,
-                                bool accumulate_rep) {
+                                bool accumulate_rep, bool pruned) {
     CompactArgs a;
     a.bm = c->bm[l];
-    a.mk = c->mk;
+    a.mk = pruned ? nullptr : c->mk;
     a.bm_prev = self_term ? c->bm[l - 1] : nullptr;
-    a.bm_sink = c->bm_sink;
+    a.bm_sink = pruned ? nullptr : c->bm_sink;
     a.bm_vadd = c->bm_vadd;
     a.alive = c->alive;
     a.n_words = c->n_words;
@@ -440,7 +442,7 @@ void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool 
     a.part_out = c->part_deg;
     a.part_in = c->part_ideg;
     a.rep = accumulate_rep ? c->rep[l] : nullptr;
-    a.touched_out = &c->ctr->touched[l];
+    a.touched_out = pruned ? nullptr : &c->ctr->touched[l];
     a.list = c->list[l];
     a.eoff = c->eoff[l];
     a.ioff = c->ioff[l];
@@ -448,6 +450,29 @@ void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool 
     a.msgs_out = (l < RIPPLE_MAX_LAYERS) ? &c->ctr->m[l + 1] : nullptr;
     a.isum_out = &c->ctr->isum[l];
     launch_compact(c, a, c->last_a[l]);
+}
+
+// Candidates of a max / min hop: the vertices marked by the out-edge walk from A_{l-1}, S and V_added,
+// into bm[l] and, ascending, into c->all_list (count in ctr->n_all). The aggregation kernel then
+// clears the bits of those whose aggregate stays as it is.
+void rp_launch_candidates(ripple_ctx *c, uint32_t l) {
+    CompactArgs a;
+    memset(&a, 0, sizeof(a));
+    a.bm = c->bm[l];
+    a.mk = c->mk;
+    a.bm_sink = c->bm_sink;
+    a.bm_vadd = c->bm_vadd;
+    a.alive = c->alive;
+    a.n_words = c->n_words;
+    a.out_meta = c->out_meta;
+    a.in_meta = c->in_meta;
+    a.part_cnt = c->part_cnt;
+    a.part_out = c->part_deg;
+    a.part_in = c->part_ideg;
+    a.touched_out = &c->ctr->touched[l];
+    a.list = c->all_list;
+    a.count_out = &c->ctr->n_all;
+    launch_compact(c, a, c->last_cand[l]);
 }
 
 // any bitmap & alive -> ascending list in `out_list`, count in *count_d (device)

@@ -295,6 +295,8 @@ struct MutArgs {
     float *X[RIPPLE_MAX_LAYERS + 1];
     const float *Wn[RIPPLE_MAX_LAYERS + 1];      // project-first layers: neighbour weights (row stride wn_ld), else null
     uint32_t wn_ld[RIPPLE_MAX_LAYERS + 1];
+    uint32_t mono_mask;                          // bit l: layer l aggregates with max / min (no structural terms)
+    int d0_old;                                  // layer 1 does: D0 receives the old feature row instead of the difference
 };
 
 __device__ __forceinline__ void touch_row(const MutArgs &a, uint32_t x, uint32_t bit) {
@@ -660,7 +662,7 @@ __global__ __launch_bounds__(256) void k_apply_vertices(MutArgs a) {
                     old = h[idx];
                     h[idx] = nv;
                 }
-                a.D0[idx] = nv - old;
+                a.D0[idx] = a.d0_old ? old : nv - old;
             }
             if (lane == 0) {
                 a.list0[slot] = w;
@@ -840,6 +842,7 @@ __global__ __launch_bounds__(256) void k_struct_scatter(MutArgs a) {
     unsigned long long total = (unsigned long long)n * a.L;
     for (unsigned long long t = gw; t < total; t += nw) {
         uint32_t e = (uint32_t)(t / a.L), l = (uint32_t)(t % a.L) + 1;
+        if ((a.mono_mask >> l) & 1u) continue;               // rows with a changed in-edge are recomputed instead
         uint32_t u = a.st_src[e], v = a.st_dst[e];
         float sg = a.st_sign[e];
         uint32_t dp = a.d[l - 1];
@@ -892,6 +895,8 @@ __global__ void k_batch_reset(DevCtr *ctr, uint32_t *bitmaps, size_t n_bitmap_wo
         ctr->need_out = ctr->need_in = 0;
         ctr->n_vadd = 0;
         ctr->abort_flag = 0;
+        for (int k = 0; k < 3; ++k)
+            for (int l = 0; l <= RIPPLE_MAX_LAYERS; ++l) ctr->mono[k][l] = 0;
     }
 }
 
@@ -952,6 +957,10 @@ static MutArgs make_args(ripple_ctx *c, uint32_t n_ops) {
         a.Wn[l] = proj ? c->layers[l - 1].Wn : nullptr;
         a.wn_ld[l] = proj ? c->layers[l - 1].N0pad : 0;
     }
+    a.mono_mask = 0;
+    for (uint32_t l = 1; l <= c->L; ++l)
+        if (rp_layer_mono(c, l)) a.mono_mask |= 1u << l;
+    a.d0_old = rp_layer_mono(c, 1) ? 1 : 0;
     return a;
 }
 

@@ -16,7 +16,8 @@ void rp_launch_mutate(ripple_ctx *c, uint32_t n_ops, bool has_vertex_add, bool h
 void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l, bool allow_disc);
 void rp_launch_alive_list(ripple_ctx *c);
 void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool want_out, bool want_in,
-                                bool accumulate_rep);
+                                bool accumulate_rep, bool pruned = false);
+void rp_launch_candidates(ripple_ctx *c, uint32_t l);
 void rp_launch_bitmap_to_list(ripple_ctx *c, uint32_t *bitmap, uint32_t *out_list, uint32_t *count_d);
 void rp_launch_list_eoff(ripple_ctx *c, uint32_t l);
 
@@ -25,6 +26,7 @@ void rp_launch_scatter_push(ripple_ctx *c, uint32_t l, bool may_pull, bool allow
 void rp_launch_scatter_owner(ripple_ctx *c, uint32_t l, bool bootstrap);
 void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow_disc);
 void rp_launch_pull_all(ripple_ctx *c, uint32_t l);
+void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l);
 
 // transform.hip
 void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool emit_delta);

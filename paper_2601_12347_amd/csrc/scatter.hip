@@ -550,19 +550,226 @@ void rp_launch_scatter_owner(ripple_ctx *c, uint32_t l, bool bootstrap) {
 #undef OWN_CASE
 }
 
+
 // ---------------------------------------------------------------------------------
-// bootstrap aggregation: X[v] = sum_{u in in-row(v)} H_prev[u]
+// max / min aggregation: keep, raise or recompute (Sec. 3.4.2)
+// ---------------------------------------------------------------------------------
+// A message carries the sender's old and new row. One wavefront owns a candidate v (a vertex with a
+// changed in-neighbour or a changed in-edge) and decides, element by element:
+//   * a new value that is at least as good as v's aggregate raises it (incremental case);
+//   * an old value that equalled the aggregate and got worse may have been the one that set it; unless
+//     another message reaches the aggregate again, the row is recomputed from all in-neighbours;
+//   * anything else leaves the element alone.
+// A vertex whose in-edges changed (S, V_added) is always recomputed: a deleted edge's source may have
+// set the extreme and an added one needs no old value. Rows whose aggregate ends up bit-equal to the
+// old one are taken out of the hop's set again, so they are not transformed and send nothing on.
+// There are no atomics on rows and the result does not depend on any order.
+struct MonoArgs {
+    const uint32_t *list;          // candidates, ascending
+    const uint32_t *count_ptr;
+    const uint2 *in_meta;
+    const uint32_t *in_pool;
+    const uint32_t *bm_prev;       // A_{l-1}: the in-neighbours whose row changed
+    const uint32_t *bm_sink, *bm_vadd;
+    uint32_t *bm_cur;              // the candidates on entry, the hop's set on exit
+    const float *Dold;             // pre-batch rows of H^{l-1}, valid on A_{l-1}
+    const void *Hprev;             // current H^{l-1}
+    uint32_t d;
+    float *X;
+    int keep_prev;                 // the layer reads the vertex's own row: members of A_{l-1} stay in the set
+    DevCtr *ctr;
+    uint32_t l;
+};
+
+template <int IS_MIN>
+__device__ __forceinline__ bool mono_better(float a, float b) { return IS_MIN ? a < b : a > b; }
+
+template <int NJ, int IS_MIN, int STORE>
+__global__ __launch_bounds__(256) void k_scatter_mono(MonoArgs a) {
+    constexpr int G = (NJ <= 1) ? 8 : (NJ <= 4 ? 4 : 2);      // senders in flight (two rows each)
+    const uint32_t count = *a.count_ptr;
+    const int lane = rp_lane();
+    const uint32_t d = a.d;
+    const float ident = IS_MIN ? INFINITY : -INFINITY;
+    const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    uint32_t n_same = 0, n_inc = 0, n_rec = 0;
+    for (uint32_t i = gw; i < count; i += nw) {
+        const uint32_t v = a.list[i];
+        const uint2 m = a.in_meta[v];
+        const bool created = rp_bit(a.bm_vadd, v);
+        bool recompute = created || rp_bit(a.bm_sink, v);
+        float xo[NJ], xn[NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const uint32_t col = lane + 64 * j;
+            xo[j] = (col < d) ? a.X[(size_t)v * d + col] : 0.0f;
+            xn[j] = xo[j];
+        }
+        if (!recompute) {
+            float inc[NJ];
+            bool lost[NJ];
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                inc[j] = ident;
+                lost[j] = false;
+            }
+            for (uint32_t base = 0; base < m.y; base += 64) {
+                const uint32_t e = base + lane;
+                const uint32_t my_u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
+                unsigned long long mask = __ballot(e < m.y && rp_bit(a.bm_prev, my_u));
+                while (mask) {
+                    int kk[G];
+                    int n = 0;
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        kk[g] = 0;
+                        if (mask) {
+                            kk[g] = __ffsll((long long)mask) - 1;
+                            mask &= mask - 1;
+                            n = g + 1;
+                        }
+                    }
+                    float ro[G][NJ], rn[G][NJ];
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        const uint32_t u = __shfl(my_u, kk[g]);
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j) {
+                            const uint32_t col = lane + 64 * j;
+                            const bool on = g < n && col < d;
+                            ro[g][j] = on ? a.Dold[(size_t)u * d + col] : 0.0f;
+                            rn[g][j] = on ? rp_load_h(a.Hprev, STORE, (size_t)u * d + col) : 0.0f;
+                        }
+                    }
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        if (g < n) {
+#pragma unroll
+                            for (int j = 0; j < NJ; ++j) {
+                                if (mono_better<IS_MIN>(rn[g][j], inc[j])) inc[j] = rn[g][j];
+                                lost[j] = lost[j] || (ro[g][j] == xo[j] && mono_better<IS_MIN>(ro[g][j], rn[g][j]));
+                            }
+                        }
+                    }
+                }
+            }
+            bool need = false;
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const uint32_t col = lane + 64 * j;
+                // an element that lost its extreme is still right if another message reaches it again
+                if (col < d && lost[j] && mono_better<IS_MIN>(xo[j], inc[j])) need = true;
+                if (mono_better<IS_MIN>(inc[j], xo[j])) xn[j] = inc[j];
+            }
+            recompute = __ballot(need) != 0ull;
+        }
+        if (recompute) {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) xn[j] = ident;
+            for (uint32_t base = 0; base < m.y; base += 64) {
+                const uint32_t e = base + lane;
+                const uint32_t my_u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
+                const int n_here = (int)min(64u, m.y - base);
+                for (int k0 = 0; k0 < n_here; k0 += 2 * G) {
+                    float r[2 * G][NJ];
+#pragma unroll
+                    for (int g = 0; g < 2 * G; ++g) {
+                        const uint32_t u = __shfl(my_u, min(k0 + g, n_here - 1));   // the last one again: harmless for an extreme
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j) {
+                            const uint32_t col = lane + 64 * j;
+                            r[g][j] = (col < d) ? rp_load_h(a.Hprev, STORE, (size_t)u * d + col) : 0.0f;
+                        }
+                    }
+#pragma unroll
+                    for (int g = 0; g < 2 * G; ++g)
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j)
+                            if (mono_better<IS_MIN>(r[g][j], xn[j])) xn[j] = r[g][j];
+                }
+            }
+            if (m.y == 0) {                                    // no in-neighbours: zero
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) xn[j] = 0.0f;
+            }
+        }
+        bool diff = false;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const uint32_t col = lane + 64 * j;
+            if (col < d && xn[j] != xo[j]) diff = true;
+        }
+        const bool changed = __ballot(diff) != 0ull;
+        if (changed) {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const uint32_t col = lane + 64 * j;
+                if (col < d) a.X[(size_t)v * d + col] = xn[j];
+            }
+        } else if (!created && !(a.keep_prev && rp_bit(a.bm_prev, v))) {
+            if (lane == 0) atomicAnd(&a.bm_cur[v >> 5], ~(1u << (v & 31)));
+        }
+        if (recompute) ++n_rec;
+        else if (changed) ++n_inc;
+        else ++n_same;
+    }
+    if (lane == 0) {
+        if (n_same) atomicAdd(&a.ctr->mono[0][a.l], n_same);
+        if (n_inc) atomicAdd(&a.ctr->mono[1][a.l], n_inc);
+        if (n_rec) atomicAdd(&a.ctr->mono[2][a.l], n_rec);
+    }
+}
+
+// candidates in c->all_list / ctr->n_all (rp_launch_candidates); D[(l-1)&1] holds the pre-batch rows of A_{l-1}
+void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l) {
+    MonoArgs a;
+    a.list = c->all_list;
+    a.count_ptr = &c->ctr->n_all;
+    a.in_meta = c->in_meta;
+    a.in_pool = c->in_pool;
+    a.bm_prev = c->bm[l - 1];
+    a.bm_sink = c->bm_sink;
+    a.bm_vadd = c->bm_vadd;
+    a.bm_cur = c->bm[l];
+    a.Dold = c->D[(l - 1) & 1];
+    a.Hprev = c->H[l - 1];
+    a.d = c->xw[l];
+    a.X = c->X[l];
+    a.keep_prev = c->layers[l - 1].self_mode != RIPPLE_SELF_NONE ? 1 : 0;
+    a.ctr = c->ctr;
+    a.l = l;
+    const bool is_min = c->layers[l - 1].agg == RIPPLE_AGG_MIN;
+    dim3 grid(c->n_cu * 8), block(256);
+#define MONO_CASE(NJ)                                                                                       \
+    do {                                                                                                    \
+        if (is_min && c->store) hipLaunchKernelGGL((k_scatter_mono<NJ, 1, 1>), grid, block, 0, c->stream, a);       \
+        else if (is_min) hipLaunchKernelGGL((k_scatter_mono<NJ, 1, 0>), grid, block, 0, c->stream, a);      \
+        else if (c->store) hipLaunchKernelGGL((k_scatter_mono<NJ, 0, 1>), grid, block, 0, c->stream, a);    \
+        else hipLaunchKernelGGL((k_scatter_mono<NJ, 0, 0>), grid, block, 0, c->stream, a);                  \
+    } while (0)
+    if (a.d <= 64) MONO_CASE(1);
+    else if (a.d <= 128) MONO_CASE(2);
+    else if (a.d <= 256) MONO_CASE(4);
+    else if (a.d <= 512) MONO_CASE(8);
+    else MONO_CASE(16);
+#undef MONO_CASE
+}
+
+// ---------------------------------------------------------------------------------
+// bootstrap aggregation: X[v] = sum (op 0), max (1) or min (2) over u in in-row(v) of H_prev[u]
 // ---------------------------------------------------------------------------------
 template <int NJ, int STORE>
 __global__ __launch_bounds__(256) void k_pull_all(const uint2 *in_meta, const uint32_t *in_pool, const float *in_w,
-                                                  uint32_t n_cap, const void *Hprev, uint32_t lds, uint32_t d, float *X) {
+                                                  uint32_t n_cap, const void *Hprev, uint32_t lds, uint32_t d, float *X,
+                                                  int op) {
     const int lane = rp_lane();
     const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
     for (uint32_t v = gw; v < n_cap; v += nw) {
         const uint2 m = in_meta[v];
         float acc[NJ];
+        const float start = (op == 0 || m.y == 0) ? 0.0f : (op == 1 ? -INFINITY : INFINITY);
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
+        for (int j = 0; j < NJ; ++j) acc[j] = start;
         for (uint32_t base = 0; base < m.y; base += 64) {
             const uint32_t i = base + lane;
             const uint32_t my_u = (i < m.y) ? in_pool[m.x + i] : 0u;
@@ -576,8 +783,9 @@ __global__ __launch_bounds__(256) void k_pull_all(const uint2 *in_meta, const ui
                     uint32_t col = lane + 64 * j;
                     if (col < d) {
                         size_t idx = (size_t)u * lds + col;
-                        acc[j] += wk * (STORE ? __bfloat162float(((const __hip_bfloat16 *)Hprev)[idx])
-                                             : ((const float *)Hprev)[idx]);
+                        const float x = STORE ? __bfloat162float(((const __hip_bfloat16 *)Hprev)[idx])
+                                              : ((const float *)Hprev)[idx];
+                        acc[j] = op == 0 ? acc[j] + wk * x : (op == 1 ? fmaxf(acc[j], x) : fminf(acc[j], x));
                     }
                 }
             }
@@ -599,15 +807,16 @@ void rp_launch_pull_all(ripple_ctx *c, uint32_t l) {
     const int store = proj ? 0 : c->store;
     const uint32_t lds = proj ? c->pd_ld : d;
     const float *w = (c->layers[l - 1].agg == RIPPLE_AGG_WSUM) ? c->in_w : nullptr;
+    const int op = c->layers[l - 1].agg == RIPPLE_AGG_MAX ? 1 : (c->layers[l - 1].agg == RIPPLE_AGG_MIN ? 2 : 0);
     dim3 grid(c->n_cu * 16), block(256);
 #define PULL_CASE(NJ)                                                                                          \
     do {                                                                                                       \
         if (store)                                                                                             \
             hipLaunchKernelGGL((k_pull_all<NJ, 1>), grid, block, 0, c->stream, c->in_meta, c->in_pool, w, c->n_cap, \
-                               src, lds, d, c->X[l]);                                                          \
+                               src, lds, d, c->X[l], op);                                                          \
         else                                                                                                   \
             hipLaunchKernelGGL((k_pull_all<NJ, 0>), grid, block, 0, c->stream, c->in_meta, c->in_pool, w, c->n_cap, \
-                               src, lds, d, c->X[l]);                                                          \
+                               src, lds, d, c->X[l], op);                                                          \
     } while (0)
     if (d <= 64) PULL_CASE(1);
     else if (d <= 128) PULL_CASE(2);

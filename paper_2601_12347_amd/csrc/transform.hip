@@ -54,6 +54,7 @@ struct TArgs {
     uint32_t tmp_out_ld;
     void *Hout;
     float *D;                      // delta rows [vertex x N] or null
+    int d_old;                     // D receives the row's old value instead of new - old (the next layer takes max / min)
     int store;                     // 0 fp32, 1 bf16 embeddings
 };
 
@@ -188,7 +189,7 @@ __device__ __forceinline__ void epilogue(const TArgs &a, floatx16 (&acc)[TM][TN]
                     } else {
                         ((float *)a.Hout)[hidx] = z;
                     }
-                    if (a.D) a.D[hidx] = z - old[sn][r];
+                    if (a.D) a.D[hidx] = a.d_old ? old[sn][r] : z - old[sn][r];
                 }
             }
         }
@@ -317,7 +318,7 @@ struct EpiRound {
             } else {
                 st4((float *)a.Hout + hidx, v, VEC, nv[u]);
             }
-            if (EPI == 2) st4(a.D + hidx, v - old[u], VEC, nv[u]);
+            if (EPI == 2) st4(a.D + hidx, a.d_old ? old[u] : v - old[u], VEC, nv[u]);
         }
     }
 };
@@ -417,7 +418,7 @@ __device__ __forceinline__ void addend_only_rows(const TArgs &a) {
                 } else {
                     ((float *)a.Hout)[hidx] = z;
                 }
-                if (a.D) a.D[hidx] = z - old[u];
+                if (a.D) a.D[hidx] = a.d_old ? old[u] : z - old[u];
             }
         }
     }
@@ -900,6 +901,7 @@ static TArgs base_args(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
     a.store = c->store;
     a.Hout = c->H[l];
     a.D = nullptr;
+    a.d_old = 0;
     a.tmp_out = nullptr;
     a.tmp_out_ld = 0;
     a.addend = nullptr;
@@ -971,6 +973,7 @@ void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const 
     const LayerDev &ly = c->layers[l - 1];
     TArgs a = base_args(c, l, list, count_d);
     a.D = emit_delta ? c->D[l & 1] : nullptr;
+    a.d_old = rp_layer_mono(c, l + 1) ? 1 : 0;
     a.a_mode = (ly.self_mode == RIPPLE_SELF_NONE) ? 0 : (ly.self_mode == RIPPLE_SELF_CONCAT ? 1 : 2);
     const bool vec_in = (ly.d_in % 4 == 0);
     // expected row count: the previous batch's (bootstrap passes the list of all live vertices)

@@ -30,6 +30,9 @@ class Pair:
             rp.ripple_set_option(self.ctx, rp.OPT_DETERMINISTIC, 1)
         rp.ripple_load_model(self.ctx, model)
         rp.ripple_full_infer(self.ctx)
+        # first layer (1-based) that aggregates with max / min: from there on the reported sets are pruned
+        mono = [l + 1 for l, lay in enumerate(model) if lay["agg"] in ("max", "min")]
+        self.first_mono = mono[0] if mono else None
 
     def close(self):
         rp.ripple_destroy(self.ctx)
@@ -64,6 +67,11 @@ class Pair:
                 h_prev = h_prev @ (w[lay["d_in"]:] if lay["self"] == "concat" else w)
             assert width == h_prev.shape[1]
             want = np.zeros_like(h_prev)
+            if self.model[l - 1]["agg"] in ("max", "min"):        # the extreme of the stored rows, exactly
+                want = oracle.aggregate(oracle.in_adjacency(self.ora), h_prev, self.model[l - 1]["agg"])
+                got = rp.ripple_get_aggregates(self.ctx, l, width, n_rows=self.cap)
+                assert np.array_equal(got[self.ora.alive], want[self.ora.alive].astype(np.float32)), f"aggregate {l}"
+                continue
             if self.model[l - 1]["agg"] == "wsum":
                 np.add.at(want, dst, h_prev[src] * self.ora.edge_weights()[:, None])
             else:
@@ -89,6 +97,8 @@ class Pair:
     def step(self, ops, payload, check=True, tol=None):
         """Apply one batch on both sides; compare acceptance, affected sets and (optionally) all rows."""
         before = [self.gpu_layer(l) for l in range(self.L + 1)] if check else None
+        pruned = self.first_mono is not None
+        ora_before = oracle.full_recompute(self.ora, self.model) if (pruned and check) else None
         rec = self.ora.apply_batch(ops, payload)
         res = rp.ripple_apply_updates(self.ctx, ops, payload)
         assert res.n_applied == int(rec.accepted.sum()), (res.n_applied, int(rec.accepted.sum()))
@@ -96,16 +106,30 @@ class Pair:
         assert res.n_edges == self.ora.n_edges()
         assert res.n_alive == int(self.ora.alive.sum())
         sets = oracle.affected_sets(self.ora, rec, self.model)
+        got_sets = []
         for l in range(self.L + 1):
             got, n = rp.ripple_get_affected(self.ctx, l, self.cap)
-            assert n == res.affected[l] == len(sets[l]), (l, n, res.affected[l], len(sets[l]))
-            assert np.array_equal(got.astype(np.int64), sets[l]), f"affected set of layer {l} differs"
+            got = got.astype(np.int64)
+            got_sets.append(got)
+            assert n == res.affected[l] == len(got)
+            if pruned and l >= self.first_mono:               # any set between the two bounds is valid
+                assert np.all(np.diff(got) > 0)
+                assert np.isin(got, sets[l]).all(), f"layer {l}: reported vertices outside the topological set"
+            else:
+                assert n == len(sets[l]), (l, n, len(sets[l]))
+                assert np.array_equal(got, sets[l]), f"affected set of layer {l} differs"
+        self.last_topological = sets
         if check:
             errs, want = self.check_embeddings(tol)
+            if pruned:                                        # every row whose value really changes is reported
+                for l in range(self.first_mono, self.L + 1):
+                    scale = max(1e-30, float(np.abs(want[l]).max()))
+                    moved = np.flatnonzero((np.abs(want[l] - ora_before[l]).max(axis=1) > 1e-3 * scale) & self.ora.alive)
+                    assert np.isin(moved, got_sets[l]).all(), f"layer {l}: a changed row is missing from the reported set"
             for l in range(self.L + 1):                       # rows outside A_l keep their bits
                 after = self.gpu_layer(l)
                 clean = np.ones(self.cap, dtype=bool)
-                clean[sets[l]] = False
+                clean[got_sets[l]] = False
                 clean[list(rec.removed)] = False
                 assert np.array_equal(after[clean], before[l][clean]), f"layer {l}: a clean row changed"
         return res, rec, sets

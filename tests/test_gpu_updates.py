@@ -382,3 +382,98 @@ def test_weighted_layer_needs_a_weighted_graph():
         rp.ripple_destroy(ctx)
     finally:
         pair.close()
+
+
+# ---- max / min aggregation (Sec. 3.4.2) ------------------------------------------------------------
+@pytest.mark.parametrize("kind,widths,store", [("gcn_max", (100, 256, 47), "f32"), ("gcn_min", (16, 40, 24, 10), "f32"),
+                                               ("sage_max", (16, 40, 24, 10), "f32"), ("sage_max", (32, 64, 12), "bf16"),
+                                               ("gcn_max", (24, 300, 10), "f32"), ("gcn_max", (3, 4, 3, 2), "f32")])
+def test_max_min_aggregation(kind, widths, store):
+    """Monotonic aggregators: a vertex keeps its aggregate, raises it from the messages or recomputes
+    it, and vertices whose aggregate does not change drop out of the propagation. The cached
+    aggregates must be the exact extreme of the stored rows, the embeddings must match the oracle, the
+    reported sets must lie between the rows that really changed and the topological sets."""
+    print("case max/min", kind, widths, store, flush=True)
+    pair, graph = make_pair(n=1500, e=14000, d0=widths[0], kind=kind, widths=widths, seed=141, slack=256, store=store,
+                            top_share=0.05)
+    stream = make_stream(pair, graph, MIXV, 143)
+    seen = np.zeros(3, dtype=np.int64)
+    pruned_any = False
+    try:
+        pair.check_aggregates()
+        for b, bs in enumerate([2, 50, 300, 40, 600]):
+            print(" batch", b, bs, flush=True)
+            if b == 3:
+                rp.ripple_compact(pair.ctx)
+            ops, payload, _ = stream.next_batch(bs)
+            res, rec, sets = pair.step(ops, payload)
+            pair.check_aggregates()
+            for l in range(1, pair.L + 1):
+                seen += [res.mono_unchanged[l], res.mono_incremental[l], res.mono_recomputed[l]]
+                pruned_any |= res.affected[l] < len(sets[l])
+        pair.check_graph()
+        print(" unchanged / incremental / recomputed:", seen, "pruned:", pruned_any, flush=True)
+        assert seen.sum() > 0
+        if widths[0] <= 4:       # wide rows nearly always lose some element's extreme; narrow ones show every case
+            assert (seen > 0).all(), f"all three cases must occur: {seen}"
+            assert pruned_any, "no propagation was ever pruned"
+    finally:
+        pair.close()
+
+
+def test_max_layer_between_linear_layers():
+    """sum -> max -> mean: what a hop hands on (differences for a linear consumer, the old rows for a
+    max / min consumer) depends on the layer that receives it."""
+    print("case mixed aggregators", flush=True)
+    widths = (16, 40, 24, 10)
+    src, dst, out_law, in_law = ri.chung_lu_graph(1200, 10000, 2.1, 0.04, 151)
+    feats = ri.features(1200, widths[0], 152)
+    model = ri.make_model("sage_mean", widths, 153)
+    model[0]["agg"], model[1]["agg"], model[2]["agg"] = "sum", "max", "mean"
+    from harness import Pair
+    pair = Pair(1200, 1200 + 128, src, dst, feats, model)
+    stream = ri.UpdateStream(1200, 1200 + 128, src, dst, out_law, in_law, widths[0], MIXV, 154)
+    try:
+        for b, bs in enumerate([5, 120, 500]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload)
+            pair.check_aggregates()
+    finally:
+        pair.close()
+
+
+def test_max_with_hub_rows_and_repeated_feature_updates():
+    """In-rows of several thousand entries are recomputed when their extreme goes away; feature updates
+    alone (no structural change) exercise the keep / raise / recompute split on unchanged in-rows."""
+    print("case max hubs", flush=True)
+    pair, graph = make_pair(n=20000, e=240000, d0=24, kind="gcn_max", widths=(24, 48, 12), seed=161, slack=64,
+                            top_share=0.04)
+    feat_only = {"edge_add": 0.0, "edge_del": 0.0, "feat": 1.0, "vadd": 0.0, "vdel": 0.0}
+    stream = make_stream(pair, graph, feat_only, 163)
+    mixed = make_stream(pair, graph, MIX3, 164)
+    try:
+        deg_in, _ = rp.ripple_get_degrees(pair.ctx, 1, pair.cap)
+        assert deg_in.max() > 4096
+        tot = np.zeros(3, dtype=np.int64)
+        for b, bs in enumerate([200, 2000]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            res, _, _ = pair.step(ops, payload)
+            for l in range(1, pair.L + 1):
+                tot += [res.mono_unchanged[l], res.mono_incremental[l], res.mono_recomputed[l]]
+        assert (tot > 0).all(), tot
+        ops, payload, _ = mixed.next_batch(3000)
+        pair.step(ops, payload)
+        pair.check_aggregates()
+    finally:
+        pair.close()
+
+
+def test_max_layers_are_refused_in_deterministic_mode():
+    ctx = rp.ripple_init_graph(4, 8, np.array([0, 1], dtype=np.uint32), np.array([1, 2], dtype=np.uint32),
+                               np.zeros((4, 8), dtype=np.float32))
+    rp.ripple_set_option(ctx, rp.OPT_DETERMINISTIC, 1)
+    with pytest.raises(rp.RippleError):
+        rp.ripple_load_model(ctx, ri.make_model("gcn_max", (8, 6), 1))
+    rp.ripple_destroy(ctx)
