@@ -208,6 +208,7 @@ def main():
     rp.ripple_get_stats(ctx, reset=True)
     torch.cuda.synchronize()
     lat, n_updates, applied = [], 0, 0
+    mono = np.zeros((3, len(model) + 1), dtype=np.int64)      # max / min hops: unchanged, incremental, recomputed
     t_begin = time.perf_counter()
     for b in batches[args.warmup:]:
         t1 = time.perf_counter()
@@ -215,6 +216,8 @@ def main():
         lat.append(time.perf_counter() - t1)
         n_updates += b[4]
         applied += res.n_applied
+        for l in range(len(model) + 1):
+            mono[:, l] += (res.mono_unchanged[l], res.mono_incremental[l], res.mono_recomputed[l])
     torch.cuda.synchronize()
     total = time.perf_counter() - t_begin
     st = rp.ripple_get_stats(ctx, reset=False)
@@ -283,6 +286,9 @@ def main():
                       "messages_l": [st.msgs[l] / max(st.batches, 1) for l in range(L + 1)],
                       "phase_ms": other},
         "aggregate_width": {f"l{l}": layer_info[l][0] for l in layer_info},
+        **({"max_min_split_per_batch": {f"l{l}": dict(zip(("unchanged", "incremental", "recomputed"),
+                                                          (mono[:, l] / max(args.steps, 1)).tolist()))
+                                        for l in range(1, len(model) + 1)}} if mono.any() else {}),
         "kernels": kernels,
         "roofline": roofline,
     }

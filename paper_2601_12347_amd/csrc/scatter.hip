@@ -554,19 +554,26 @@ void rp_launch_scatter_owner(ripple_ctx *c, uint32_t l, bool bootstrap) {
 // ---------------------------------------------------------------------------------
 // max / min aggregation: keep, raise or recompute (Sec. 3.4.2)
 // ---------------------------------------------------------------------------------
-// A message carries the sender's old and new row. One wavefront owns a candidate v (a vertex with a
-// changed in-neighbour or a changed in-edge) and decides, element by element:
+// A message carries the sender's old and new row. The owner of a candidate v (a vertex with a
+// changed in-neighbour or a changed in-edge) decides, element by element:
 //   * a new value that is at least as good as v's aggregate raises it (incremental case);
 //   * an old value that equalled the aggregate and got worse may have been the one that set it; unless
 //     another message reaches the aggregate again, the row is recomputed from all in-neighbours;
 //   * anything else leaves the element alone.
-// A vertex whose in-edges changed (S, V_added) is always recomputed: a deleted edge's source may have
-// set the extreme and an added one needs no old value. Rows whose aggregate ends up bit-equal to the
-// old one are taken out of the hop's set again, so they are not transformed and send nothing on.
-// There are no atomics on rows and the result does not depend on any order.
+// Recomputing is always right, so it is also taken where it is the cheaper way: for a vertex whose
+// in-edges changed (S, V_added: a deleted edge's source may have set the extreme, an added one has no
+// old value), where reading the old and new rows of the changed in-neighbours would cost as much as
+// reading every in-neighbour once, and as soon as one element is known to have lost its extreme.
+// Rows whose aggregate ends up bit-equal to the old one are taken out of the hop's set again, so they
+// are not transformed and send nothing on. There are no atomics on rows and the result does not
+// depend on any order. One wavefront owns a candidate with up to MONO_LONG in-neighbours; longer
+// in-rows are queued and taken by a workgroup each.
+#define MONO_LONG 256u
+
 struct MonoArgs {
-    const uint32_t *list;          // candidates, ascending
+    const uint32_t *list;          // candidates (ascending), or the queue of long rows
     const uint32_t *count_ptr;
+    uint32_t *queue, *queue_count; // candidates with long in-rows, left to the workgroup kernel
     const uint2 *in_meta;
     const uint32_t *in_pool;
     const uint32_t *bm_prev;       // A_{l-1}: the in-neighbours whose row changed
@@ -584,9 +591,109 @@ struct MonoArgs {
 template <int IS_MIN>
 __device__ __forceinline__ bool mono_better(float a, float b) { return IS_MIN ? a < b : a > b; }
 
+// Messages of the in-neighbours `mask` selects among the 64 ids held one per lane in my_u: inc becomes
+// the best new value, lostm (bit j: column lane + 64 j) records elements whose old value equalled the
+// aggregate and got worse. stop_early: return true as soon as such an element is not covered by inc.
+template <int NJ, int IS_MIN, int STORE, int G>
+__device__ __forceinline__ bool mono_messages(const MonoArgs &a, uint32_t my_u, unsigned long long mask, const float *xo,
+                                              float *inc, uint32_t &lostm, bool stop_early) {
+    const int lane = rp_lane();
+    const uint32_t d = a.d;
+    while (mask) {
+        int kk[G];
+        int n = 0;
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            kk[g] = 0;
+            if (mask) {
+                kk[g] = __ffsll((long long)mask) - 1;
+                mask &= mask - 1;
+                n = g + 1;
+            }
+        }
+        float ro[G][NJ], rn[G][NJ];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const uint32_t u = __shfl(my_u, kk[g]);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const uint32_t col = lane + 64 * j;
+                const bool on = g < n && col < d;
+                ro[g][j] = on ? a.Dold[(size_t)u * d + col] : 0.0f;
+                rn[g][j] = on ? rp_load_h(a.Hprev, STORE, (size_t)u * d + col) : 0.0f;
+            }
+        }
+        bool need = false;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                if (g < n) {
+                    if (mono_better<IS_MIN>(rn[g][j], inc[j])) inc[j] = rn[g][j];
+                    if (ro[g][j] == xo[j] && mono_better<IS_MIN>(ro[g][j], rn[g][j])) lostm |= 1u << j;
+                }
+            }
+            if (lane + 64 * j < (int)d && ((lostm >> j) & 1u) && mono_better<IS_MIN>(xo[j], inc[j])) need = true;
+        }
+        if (stop_early && __ballot(need) != 0ull) return true;
+    }
+    return false;
+}
+
+// best value per column over the rows of the `n_here` in-neighbours held one per lane in my_u, taken
+// from lane `first` on in steps of `step`
+template <int NJ, int IS_MIN, int STORE, int G>
+__device__ __forceinline__ void mono_gather(const MonoArgs &a, uint32_t my_u, int n_here, float *xn) {
+    const int lane = rp_lane();
+    const uint32_t d = a.d;
+    for (int k0 = 0; k0 < n_here; k0 += G) {
+        float r[G][NJ];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            const uint32_t u = __shfl(my_u, min(k0 + g, n_here - 1));       // the last one again: harmless for an extreme
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const uint32_t col = lane + 64 * j;
+                r[g][j] = (col < d) ? rp_load_h(a.Hprev, STORE, (size_t)u * d + col) : 0.0f;
+            }
+        }
+#pragma unroll
+        for (int g = 0; g < G; ++g)
+#pragma unroll
+            for (int j = 0; j < NJ; ++j)
+                if (mono_better<IS_MIN>(r[g][j], xn[j])) xn[j] = r[g][j];
+    }
+}
+
+// store the row if it differs from the old one, else take v out of the hop's set; returns "changed"
+template <int NJ>
+__device__ __forceinline__ bool mono_finish(const MonoArgs &a, uint32_t v, bool created, const float *xo, const float *xn) {
+    const int lane = rp_lane();
+    const uint32_t d = a.d;
+    bool diff = false;
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+        const uint32_t col = lane + 64 * j;
+        if (col < d && xn[j] != xo[j]) diff = true;
+    }
+    const bool changed = __ballot(diff) != 0ull;
+    if (changed) {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const uint32_t col = lane + 64 * j;
+            if (col < d) a.X[(size_t)v * d + col] = xn[j];
+        }
+    } else if (!created && !(a.keep_prev && rp_bit(a.bm_prev, v))) {
+        if (lane == 0) atomicAnd(&a.bm_cur[v >> 5], ~(1u << (v & 31)));
+    }
+    return changed;
+}
+
 template <int NJ, int IS_MIN, int STORE>
 __global__ __launch_bounds__(256) void k_scatter_mono(MonoArgs a) {
-    constexpr int G = (NJ <= 1) ? 8 : (NJ <= 4 ? 4 : 2);      // senders in flight (two rows each)
+    constexpr int GC = (NJ <= 1) ? 8 : (NJ <= 2 ? 4 : (NJ <= 4 ? 2 : 1));     // senders in flight (two rows each)
+    constexpr int GR = (NJ <= 1) ? 16 : (NJ <= 16 ? 16 / NJ : 1);             // rows in flight when recomputing
+    constexpr int T = MONO_LONG / 64;
     const uint32_t count = *a.count_ptr;
     const int lane = rp_lane();
     const uint32_t d = a.d;
@@ -596,119 +703,51 @@ __global__ __launch_bounds__(256) void k_scatter_mono(MonoArgs a) {
     for (uint32_t i = gw; i < count; i += nw) {
         const uint32_t v = a.list[i];
         const uint2 m = a.in_meta[v];
+        if (m.y > MONO_LONG) {
+            if (lane == 0) a.queue[atomicAdd(a.queue_count, 1u)] = v;
+            continue;
+        }
         const bool created = rp_bit(a.bm_vadd, v);
-        bool recompute = created || rp_bit(a.bm_sink, v);
         float xo[NJ], xn[NJ];
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
             const uint32_t col = lane + 64 * j;
             xo[j] = (col < d) ? a.X[(size_t)v * d + col] : 0.0f;
-            xn[j] = xo[j];
         }
+        uint32_t my_u[T];
+        unsigned long long dmask[T];
+        uint32_t nd = 0;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const uint32_t e = 64 * t + lane;
+            my_u[t] = (e < m.y) ? a.in_pool[m.x + e] : 0u;
+            dmask[t] = __ballot(e < m.y && rp_bit(a.bm_prev, my_u[t]));
+            nd += (uint32_t)__popcll(dmask[t]);
+        }
+        // reading old and new rows of nd senders against reading m.y rows once
+        bool recompute = created || rp_bit(a.bm_sink, v) || 2 * nd >= m.y;
         if (!recompute) {
             float inc[NJ];
-            bool lost[NJ];
+            uint32_t lostm = 0;
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-                inc[j] = ident;
-                lost[j] = false;
-            }
-            for (uint32_t base = 0; base < m.y; base += 64) {
-                const uint32_t e = base + lane;
-                const uint32_t my_u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
-                unsigned long long mask = __ballot(e < m.y && rp_bit(a.bm_prev, my_u));
-                while (mask) {
-                    int kk[G];
-                    int n = 0;
+            for (int j = 0; j < NJ; ++j) inc[j] = ident;
 #pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        kk[g] = 0;
-                        if (mask) {
-                            kk[g] = __ffsll((long long)mask) - 1;
-                            mask &= mask - 1;
-                            n = g + 1;
-                        }
-                    }
-                    float ro[G][NJ], rn[G][NJ];
+            for (int t = 0; t < T; ++t)
+                if (!recompute && dmask[t])
+                    recompute = mono_messages<NJ, IS_MIN, STORE, GC>(a, my_u[t], dmask[t], xo, inc, lostm, true);
 #pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        const uint32_t u = __shfl(my_u, kk[g]);
-#pragma unroll
-                        for (int j = 0; j < NJ; ++j) {
-                            const uint32_t col = lane + 64 * j;
-                            const bool on = g < n && col < d;
-                            ro[g][j] = on ? a.Dold[(size_t)u * d + col] : 0.0f;
-                            rn[g][j] = on ? rp_load_h(a.Hprev, STORE, (size_t)u * d + col) : 0.0f;
-                        }
-                    }
-#pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        if (g < n) {
-#pragma unroll
-                            for (int j = 0; j < NJ; ++j) {
-                                if (mono_better<IS_MIN>(rn[g][j], inc[j])) inc[j] = rn[g][j];
-                                lost[j] = lost[j] || (ro[g][j] == xo[j] && mono_better<IS_MIN>(ro[g][j], rn[g][j]));
-                            }
-                        }
-                    }
-                }
-            }
-            bool need = false;
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-                const uint32_t col = lane + 64 * j;
-                // an element that lost its extreme is still right if another message reaches it again
-                if (col < d && lost[j] && mono_better<IS_MIN>(xo[j], inc[j])) need = true;
-                if (mono_better<IS_MIN>(inc[j], xo[j])) xn[j] = inc[j];
-            }
-            recompute = __ballot(need) != 0ull;
+            for (int j = 0; j < NJ; ++j) xn[j] = mono_better<IS_MIN>(inc[j], xo[j]) ? inc[j] : xo[j];
         }
         if (recompute) {
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) xn[j] = ident;
-            for (uint32_t base = 0; base < m.y; base += 64) {
-                const uint32_t e = base + lane;
-                const uint32_t my_u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
-                const int n_here = (int)min(64u, m.y - base);
-                for (int k0 = 0; k0 < n_here; k0 += 2 * G) {
-                    float r[2 * G][NJ];
+            for (int j = 0; j < NJ; ++j) xn[j] = (m.y == 0) ? 0.0f : ident;     // no in-neighbours: zero
 #pragma unroll
-                    for (int g = 0; g < 2 * G; ++g) {
-                        const uint32_t u = __shfl(my_u, min(k0 + g, n_here - 1));   // the last one again: harmless for an extreme
-#pragma unroll
-                        for (int j = 0; j < NJ; ++j) {
-                            const uint32_t col = lane + 64 * j;
-                            r[g][j] = (col < d) ? rp_load_h(a.Hprev, STORE, (size_t)u * d + col) : 0.0f;
-                        }
-                    }
-#pragma unroll
-                    for (int g = 0; g < 2 * G; ++g)
-#pragma unroll
-                        for (int j = 0; j < NJ; ++j)
-                            if (mono_better<IS_MIN>(r[g][j], xn[j])) xn[j] = r[g][j];
-                }
-            }
-            if (m.y == 0) {                                    // no in-neighbours: zero
-#pragma unroll
-                for (int j = 0; j < NJ; ++j) xn[j] = 0.0f;
+            for (int t = 0; t < T; ++t) {
+                const int n_here = (int)min(64u, m.y - min(m.y, 64u * t));
+                if (n_here > 0) mono_gather<NJ, IS_MIN, STORE, GR>(a, my_u[t], n_here, xn);
             }
         }
-        bool diff = false;
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) {
-            const uint32_t col = lane + 64 * j;
-            if (col < d && xn[j] != xo[j]) diff = true;
-        }
-        const bool changed = __ballot(diff) != 0ull;
-        if (changed) {
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-                const uint32_t col = lane + 64 * j;
-                if (col < d) a.X[(size_t)v * d + col] = xn[j];
-            }
-        } else if (!created && !(a.keep_prev && rp_bit(a.bm_prev, v))) {
-            if (lane == 0) atomicAnd(&a.bm_cur[v >> 5], ~(1u << (v & 31)));
-        }
+        const bool changed = mono_finish<NJ>(a, v, created, xo, xn);
         if (recompute) ++n_rec;
         else if (changed) ++n_inc;
         else ++n_same;
@@ -720,11 +759,121 @@ __global__ __launch_bounds__(256) void k_scatter_mono(MonoArgs a) {
     }
 }
 
+// One workgroup of TEAM wavefronts per candidate with a long in-row: wavefront w takes the 64-entry
+// blocks w, w + TEAM, ...; the wavefronts' partial results meet in LDS and wavefront 0 finishes the row.
+template <int NJ, int IS_MIN, int STORE, int TEAM>
+__global__ __launch_bounds__(TEAM * 64) void k_scatter_mono_long(MonoArgs a) {
+    constexpr int GC = (NJ <= 1) ? 8 : (NJ <= 2 ? 4 : (NJ <= 4 ? 2 : 1));
+    constexpr int GR = (NJ <= 2) ? 16 : 32 / NJ;               // rows in flight: a long row is paced by round trips
+    __shared__ float s_val[TEAM][NJ * 64];
+    __shared__ uint32_t s_lost[TEAM][64];
+    __shared__ uint32_t s_cnt[TEAM];
+    __shared__ uint32_t s_flag;
+    const uint32_t count = *a.count_ptr;
+    const int lane = rp_lane(), wave = threadIdx.x >> 6;
+    const uint32_t d = a.d;
+    const float ident = IS_MIN ? INFINITY : -INFINITY;
+    for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) {
+        const uint32_t v = a.list[i];
+        const uint2 m = a.in_meta[v];
+        const bool created = rp_bit(a.bm_vadd, v);
+        float xo[NJ], xn[NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const uint32_t col = lane + 64 * j;
+            xo[j] = (col < d) ? a.X[(size_t)v * d + col] : 0.0f;
+        }
+        // how many in-neighbours changed
+        uint32_t nd = 0;
+        for (uint32_t base = 64u * wave; base < m.y; base += 64u * TEAM) {
+            const uint32_t e = base + lane;
+            const uint32_t u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
+            nd += (uint32_t)__popcll(__ballot(e < m.y && rp_bit(a.bm_prev, u)));
+        }
+        if (lane == 0) s_cnt[wave] = nd;
+        __syncthreads();
+        nd = 0;
+        for (int w = 0; w < TEAM; ++w) nd += s_cnt[w];
+        bool recompute = created || rp_bit(a.bm_sink, v) || 2 * nd >= m.y;
+        if (!recompute) {                                      // every wavefront looks at its share of the messages
+            float inc[NJ];
+            uint32_t lostm = 0;
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) inc[j] = ident;
+            for (uint32_t base = 64u * wave; base < m.y; base += 64u * TEAM) {
+                const uint32_t e = base + lane;
+                const uint32_t u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
+                const unsigned long long mask = __ballot(e < m.y && rp_bit(a.bm_prev, u));
+                if (mask) mono_messages<NJ, IS_MIN, STORE, GC>(a, u, mask, xo, inc, lostm, false);
+            }
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) s_val[wave][j * 64 + lane] = inc[j];
+            s_lost[wave][lane] = lostm;
+            __syncthreads();
+            if (wave == 0) {
+                bool need = false;
+                lostm = 0;
+                for (int w = 0; w < TEAM; ++w) lostm |= s_lost[w][lane];
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    float best = s_val[0][j * 64 + lane];
+                    for (int w = 1; w < TEAM; ++w) {
+                        const float x = s_val[w][j * 64 + lane];
+                        if (mono_better<IS_MIN>(x, best)) best = x;
+                    }
+                    if (lane + 64 * j < (int)d && ((lostm >> j) & 1u) && mono_better<IS_MIN>(xo[j], best)) need = true;
+                    xn[j] = mono_better<IS_MIN>(best, xo[j]) ? best : xo[j];
+                }
+                const bool rec = __ballot(need) != 0ull;
+                if (lane == 0) s_flag = rec ? 1u : 0u;
+            }
+            __syncthreads();
+            recompute = s_flag != 0;
+            if (!recompute) {
+                if (wave == 0) {
+                    const bool changed = mono_finish<NJ>(a, v, created, xo, xn);
+                    if (lane == 0) atomicAdd(&a.ctr->mono[changed ? 1 : 0][a.l], 1u);
+                }
+                __syncthreads();                               // the LDS arrays are reused by the next row
+                continue;
+            }
+        }
+        // recompute from all in-neighbours (m.y > MONO_LONG, so the row is not empty)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) xn[j] = ident;
+        for (uint32_t base = 64u * wave; base < m.y; base += 64u * TEAM) {
+            const uint32_t e = base + lane;
+            const uint32_t u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
+            mono_gather<NJ, IS_MIN, STORE, GR>(a, u, (int)min(64u, m.y - base), xn);
+        }
+        __syncthreads();                                       // s_val may still be read by wavefront 0 (classification)
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) s_val[wave][j * 64 + lane] = xn[j];
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                float best = s_val[0][j * 64 + lane];
+                for (int w = 1; w < TEAM; ++w) {
+                    const float x = s_val[w][j * 64 + lane];
+                    if (mono_better<IS_MIN>(x, best)) best = x;
+                }
+                xn[j] = best;
+            }
+            mono_finish<NJ>(a, v, created, xo, xn);
+            if (lane == 0) atomicAdd(&a.ctr->mono[2][a.l], 1u);
+        }
+        __syncthreads();
+    }
+}
+
 // candidates in c->all_list / ctr->n_all (rp_launch_candidates); D[(l-1)&1] holds the pre-batch rows of A_{l-1}
 void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l) {
     MonoArgs a;
     a.list = c->all_list;
     a.count_ptr = &c->ctr->n_all;
+    a.queue = c->list[l];                       // not written before the hop's set is compacted
+    a.queue_count = &c->ctr->n_long;
     a.in_meta = c->in_meta;
     a.in_pool = c->in_pool;
     a.bm_prev = c->bm[l - 1];
@@ -738,21 +887,31 @@ void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l) {
     a.keep_prev = c->layers[l - 1].self_mode != RIPPLE_SELF_NONE ? 1 : 0;
     a.ctr = c->ctr;
     a.l = l;
+    hipMemsetAsync(&c->ctr->n_long, 0, 4, c->stream);
+    MonoArgs b = a;
+    b.list = a.queue;
+    b.count_ptr = &c->ctr->n_long;
     const bool is_min = c->layers[l - 1].agg == RIPPLE_AGG_MIN;
     dim3 grid(c->n_cu * 8), block(256);
-#define MONO_CASE(NJ)                                                                                       \
-    do {                                                                                                    \
-        if (is_min && c->store) hipLaunchKernelGGL((k_scatter_mono<NJ, 1, 1>), grid, block, 0, c->stream, a);       \
-        else if (is_min) hipLaunchKernelGGL((k_scatter_mono<NJ, 1, 0>), grid, block, 0, c->stream, a);      \
-        else if (c->store) hipLaunchKernelGGL((k_scatter_mono<NJ, 0, 1>), grid, block, 0, c->stream, a);    \
-        else hipLaunchKernelGGL((k_scatter_mono<NJ, 0, 0>), grid, block, 0, c->stream, a);                  \
+#define MONO_PAIR(NJ, MN, ST, TEAM)                                                                          \
+    do {                                                                                                     \
+        hipLaunchKernelGGL((k_scatter_mono<NJ, MN, ST>), grid, block, 0, c->stream, a);                      \
+        hipLaunchKernelGGL((k_scatter_mono_long<NJ, MN, ST, TEAM>), dim3(c->n_cu * 2), dim3(TEAM * 64), 0, c->stream, b); \
     } while (0)
-    if (a.d <= 64) MONO_CASE(1);
-    else if (a.d <= 128) MONO_CASE(2);
-    else if (a.d <= 256) MONO_CASE(4);
-    else if (a.d <= 512) MONO_CASE(8);
-    else MONO_CASE(16);
+#define MONO_CASE(NJ, TEAM)                                                                                  \
+    do {                                                                                                     \
+        if (is_min && c->store) MONO_PAIR(NJ, 1, 1, TEAM);                                                   \
+        else if (is_min) MONO_PAIR(NJ, 1, 0, TEAM);                                                          \
+        else if (c->store) MONO_PAIR(NJ, 0, 1, TEAM);                                                        \
+        else MONO_PAIR(NJ, 0, 0, TEAM);                                                                      \
+    } while (0)
+    if (a.d <= 64) MONO_CASE(1, 16);
+    else if (a.d <= 128) MONO_CASE(2, 16);
+    else if (a.d <= 256) MONO_CASE(4, 16);
+    else if (a.d <= 512) MONO_CASE(8, 16);
+    else MONO_CASE(16, 8);
 #undef MONO_CASE
+#undef MONO_PAIR
 }
 
 // ---------------------------------------------------------------------------------

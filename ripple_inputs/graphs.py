@@ -146,6 +146,11 @@ CONFIGS = [
            (128, 256, 256, 40), "f32", (1000,), _MIX3, 4096, stream_seed=12355, weighted=True),
     Config("dense_gcn_wsum", 2_449_029, 123_718_280, 2.3, 0.0002, 100, "gcn_wsum",
            (100, 256, 256, 47), "f32", (10000,), _MIX3, 4096, stream_seed=12356, weighted=True),
+    # the paper's GC-X workload (GraphConv with max aggregation)
+    Config("sparse_gcn_max", 169_343, 1_166_243, 2.1, 0.01, 128, "gcn_max",
+           (128, 256, 256, 40), "f32", (1000,), _MIX3, 4096, stream_seed=12357),
+    Config("dense_gcn_max", 2_449_029, 123_718_280, 2.3, 0.0002, 100, "gcn_max",
+           (100, 256, 256, 47), "f32", (10000,), _MIX3, 4096, stream_seed=12358),
 ]
 
 

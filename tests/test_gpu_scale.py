@@ -48,6 +48,27 @@ def test_sparse_gcn_weighted_sum():
         pair.close()
 
 
+def test_sparse_gcn_max():
+    """The paper's GC-X workload on the sparse graph: all rows of all layers after every batch; the
+    reported sets between the rows that changed and the topological sets."""
+    cfg = ri.get_config("sparse_gcn_max")
+    print("case", cfg.name, flush=True)
+    pair, stream = config_pair(cfg)
+    try:
+        pair.check_embeddings()
+        for b, bs in enumerate([10, 1000, 1000]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            res, _, sets = pair.step(ops, payload)
+            print("  reported", [res.affected[l] for l in range(pair.L + 1)], "topological", [len(s) for s in sets],
+                  "unchanged/incremental/recomputed", [(res.mono_unchanged[l], res.mono_incremental[l], res.mono_recomputed[l])
+                                                       for l in range(1, pair.L + 1)], flush=True)
+        pair.check_graph()
+        pair.check_aggregates()
+    finally:
+        pair.close()
+
+
 def test_sparse_gin_sum_with_vertex_operations():
     cfg = ri.get_config("sparse_gin_sum")
     print("case", cfg.name, flush=True)
@@ -122,7 +143,7 @@ def dense_graph():
     return g
 
 
-@pytest.mark.parametrize("name", ["dense_sage_mean", "dense_gcn_sum_bf16"])
+@pytest.mark.parametrize("name", ["dense_sage_mean", "dense_gcn_sum_bf16", "dense_gcn_max"])
 def test_dense_configs_sampled_rows(dense_graph, name):
     """Full-size graph, the batch size the benchmark times; the oracle recomputes a sample of
     final-layer rows through their in-neighbourhood cones (recomputing all 2.4M rows of every
@@ -152,13 +173,23 @@ def test_dense_configs_sampled_rows(dense_graph, name):
         sets = oracle.affected_sets(ora, rec, model)
         print(f"  oracle sets {time.time() - t0:.0f}s sizes {[len(s) for s in sets]}", flush=True)
         L = len(model)
+        pruned = cfg.model.endswith(("_max", "_min"))
         for l in range(L + 1):
             got, n = rp.ripple_get_affected(ctx, l, cfg.vertex_capacity)
-            assert n == len(sets[l]) and np.array_equal(got.astype(np.int64), sets[l]), f"affected set {l}"
+            if pruned and l >= 1:                        # a valid pruned set lies inside the topological one
+                assert n == len(got) and np.all(np.diff(got.astype(np.int64)) > 0)
+                assert np.isin(got.astype(np.int64), sets[l]).all(), f"affected set {l}"
+                print(f"  layer {l}: reported {n} of {len(sets[l])}; unchanged/incremental/recomputed "
+                      f"{res.mono_unchanged[l]}/{res.mono_incremental[l]}/{res.mono_recomputed[l]}", flush=True)
+            else:
+                assert n == len(sets[l]) and np.array_equal(got.astype(np.int64), sets[l]), f"affected set {l}"
         rng = np.random.default_rng(5)
-        targets = np.unique(np.concatenate([rng.choice(sets[L], size=120, replace=False),
-                                            np.asarray(sorted(rec.sinks))[:40],
-                                            np.asarray(sorted(rec.feat))[:20]]))
+        # (the max / min oracle gathers every neighbour row explicitly: a smaller sample keeps it to seconds;
+        # rows the library pruned are sampled too and must equal the recomputation all the same)
+        k_any, k_sink, k_feat = (24, 8, 4) if pruned else (120, 40, 20)
+        targets = np.unique(np.concatenate([rng.choice(sets[L], size=k_any, replace=False),
+                                            np.asarray(sorted(rec.sinks))[:k_sink],
+                                            np.asarray(sorted(rec.feat))[:k_feat]]))
         cone = oracle.recompute_rows(ora, model, targets)
         print(f"  oracle cone {time.time() - t0:.0f}s rows per layer {[len(r) for r, _ in cone]}", flush=True)
         tol = TOL[cfg.store]
