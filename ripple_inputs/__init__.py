@@ -7,8 +7,8 @@ of the method's arithmetic (no aggregation, no layer math, no affected-set
 logic) and imports neither the oracle nor the GPU package.
 
 The graphs stand in for the paper's datasets (Table 2: Arxiv 169K/1.2M,
-Products 2.5M/123.7M) of which only the shapes are taken: vertex and edge
-counts, feature width, class count. The update mix replaces the paper's
+Products 2.5M/123.7M, Reddit 233K/114.6M) of which only the shapes are taken:
+vertex and edge counts, feature width, class count. The update mix replaces the paper's
 LinkBench-derived mix (Sec. 6.1.2), which is not available.
 """
 from .graphs import (PowerLaw, chung_lu_graph, features, edge_weights, CONFIGS, get_config,

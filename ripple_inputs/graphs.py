@@ -151,6 +151,14 @@ CONFIGS = [
            (128, 256, 256, 40), "f32", (1000,), _MIX3, 4096, stream_seed=12357),
     Config("dense_gcn_max", 2_449_029, 123_718_280, 2.3, 0.0002, 100, "gcn_max",
            (100, 256, 256, 47), "f32", (10000,), _MIX3, 4096, stream_seed=12358),
+    # deeper models (the paper's 4-layer runs, Sec. 6.3.2) and a graph of Reddit's shape (Table 2: 233 K
+    # vertices, 114.6 M edges, 602 features, 41 classes; average in-degree 492)
+    Config("sparse_sage_mean_4layer", 169_343, 1_166_243, 2.1, 0.01, 128, "sage_mean",
+           (128, 256, 256, 256, 40), "f32", (1000,), _MIX3, 4096, stream_seed=12359),
+    Config("dense_sage_mean_4layer", 2_449_029, 123_718_280, 2.3, 0.0002, 100, "sage_mean",
+           (100, 256, 256, 256, 47), "f32", (1000,), _MIX3, 4096, stream_seed=12360),
+    Config("reddit_sage_mean", 232_965, 114_615_892, 2.3, 0.0002, 602, "sage_mean",
+           (602, 256, 256, 41), "f32", (100, 1000), _MIX3, 4096, stream_seed=12361),
 ]
 
 

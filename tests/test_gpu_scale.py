@@ -69,6 +69,25 @@ def test_sparse_gcn_max():
         pair.close()
 
 
+def test_sparse_four_layers():
+    """Four hops (the paper's deeper models, Sec. 6.3.2): all rows of all five layers after every batch."""
+    cfg = ri.get_config("sparse_sage_mean_4layer")
+    print("case", cfg.name, flush=True)
+    pair, stream = config_pair(cfg)
+    try:
+        assert pair.L == 4
+        pair.check_embeddings()
+        for b, bs in enumerate([1, 100, 1000]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            res, _, sets = pair.step(ops, payload)
+            print("  a_l", [len(s) for s in sets], flush=True)
+        pair.check_graph()
+        pair.check_aggregates()
+    finally:
+        pair.close()
+
+
 def test_sparse_gin_sum_with_vertex_operations():
     cfg = ri.get_config("sparse_gin_sum")
     print("case", cfg.name, flush=True)
@@ -204,5 +223,67 @@ def test_dense_configs_sampled_rows(dense_graph, name):
             err = (np.abs(got - want).max(axis=1) / np.maximum(norm, tau)).max()
             print(f"  layer {l}: {len(rows)} rows, max rel err {err:.2e}", flush=True)
             assert err <= tol, (l, err)
+    finally:
+        rp.ripple_destroy(ctx)
+
+
+@pytest.mark.parametrize("name,bs", [("dense_sage_mean_4layer", 1000), ("reddit_sage_mean", 1000)])
+def test_deep_and_reddit_shaped_configs(dense_graph, name, bs):
+    """Four layers on the dense graph, and a graph of Reddit's shape (average in-degree 492, 602
+    features). Affected sets are compared in full. At this density the in-neighbourhood cone of even
+    a handful of final-layer rows is most of the graph, so the rows are checked hop by hop instead:
+    for a sample of A_l the oracle applies layer l (fp64) to the library's own stored H^{l-1}, which
+    an earlier step of the same loop has checked the same way, down to the features."""
+    cfg = ri.get_config(name)
+    if cfg.n == 2_449_029:
+        src, dst, out_law, in_law = dense_graph
+    else:
+        t0 = time.time()
+        src, dst, out_law, in_law = ri.chung_lu_graph(cfg.n, cfg.e, cfg.gamma, cfg.top_share, cfg.graph_seed)
+        print(f" graph generated in {time.time() - t0:.0f}s", flush=True)
+    feats = ri.features(cfg.n, cfg.d0, cfg.feat_seed)
+    model = ri.make_model(cfg.model, cfg.widths, cfg.weight_seed)
+    print("case", name, flush=True)
+    t0 = time.time()
+    ctx = rp.ripple_init_graph(cfg.n, cfg.vertex_capacity, src, dst, feats, store=cfg.store,
+                               edge_capacity=cfg.edge_capacity)
+    try:
+        rp.ripple_load_model(ctx, model)
+        rp.ripple_full_infer(ctx)
+        stream = ri.UpdateStream(cfg.n, cfg.vertex_capacity, src, dst, out_law, in_law, cfg.d0, cfg.mix,
+                                 cfg.stream_seed)
+        ora = oracle.GraphState(cfg.n, cfg.vertex_capacity, src, dst, feats)
+        print(f"  bootstrap and oracle state {time.time() - t0:.0f}s", flush=True)
+        L = len(model)
+        rng = np.random.default_rng(6)
+        for b in range(2):
+            ops, payload, _ = stream.next_batch(bs)
+            rec = ora.apply_batch(ops, payload)
+            res = rp.ripple_apply_updates(ctx, ops, payload)
+            assert res.n_applied == int(rec.accepted.sum()) and res.n_rejected == 0
+            assert res.n_edges == ora.n_edges()
+            sets = oracle.affected_sets(ora, rec, model)
+            for l in range(L + 1):
+                got, n = rp.ripple_get_affected(ctx, l, cfg.vertex_capacity)
+                assert n == len(sets[l]) and np.array_equal(got.astype(np.int64), sets[l]), f"affected set {l}"
+            print(f"  batch {b}: sets {[len(s) for s in sets]} {time.time() - t0:.0f}s", flush=True)
+        a_in = oracle.in_adjacency(ora)
+        touched = np.asarray(sorted(rec.feat), dtype=np.int64)
+        got0 = rp.ripple_get_embeddings(ctx, 0, cfg.widths[0], ids=touched.astype(np.uint32))
+        assert np.array_equal(got0, ora.h0[touched].astype(np.float32))
+        for l in range(1, L + 1):
+            rows = np.unique(np.concatenate([rng.choice(sets[l], size=min(300, len(sets[l])), replace=False),
+                                             np.asarray(sorted(rec.sinks), dtype=np.int64)[:60]]))
+            # the rows of H^{l-1} that layer l reads for this sample, from the library
+            need = np.union1d(np.unique(a_in.ones[rows].indices), rows)
+            h_prev = np.zeros((cfg.vertex_capacity, cfg.widths[l - 1]))
+            h_prev[need] = rp.ripple_get_embeddings(ctx, l - 1, cfg.widths[l - 1], ids=need.astype(np.uint32))
+            want = oracle.layer_rows(ora, model[l - 1], h_prev, a_in, rows)
+            got = rp.ripple_get_embeddings(ctx, l, cfg.widths[l], ids=rows.astype(np.uint32))
+            norm = np.abs(want).max(axis=1)
+            err = (np.abs(got - want).max(axis=1) / np.maximum(norm, norm.mean())).max()
+            print(f"  layer {l}: {len(rows)} rows from {len(need)} inputs, max rel err {err:.2e} {time.time() - t0:.0f}s",
+                  flush=True)
+            assert err <= TOL[cfg.store], (l, err)
     finally:
         rp.ripple_destroy(ctx)
