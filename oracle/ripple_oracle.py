@@ -25,6 +25,13 @@ Readings taken where the paper leaves a choice (each is listed in the design doc):
     values exactly, so the oracle is again the definition; which vertices a pruned propagation
     visits is not unique, so for these layers the topological sets are an upper bound and the
     rows whose value really changes a lower bound of what an implementation may report;
+  * graph attention (Sec. 3.4.1, Eq. 3): the printed score z_uv = a . (W h_u || W h_v) without a
+    non-linearity would make the sink's part cancel in the softmax, against the section's own
+    statement that the coefficient depends on both endpoints; the cited GAT definition is taken:
+    z_uv = LeakyReLU_0.2(a_src . W h_u + a_dst . W h_v), one head, h_v = act(sum_u alpha_uv W h_u + b),
+    act(b) for a vertex without in-neighbours. The hybrid scheme (recompute vertices already in the
+    tree, numerator / denominator deltas for the others) reaches these values, so the oracle is
+    the definition;
   * GraphConv: h = act(x W + b), no self term (Sec. 3.3.3 example);
     GraphSAGE: h = act(h_self W_self + x W_neigh + b) (Eq. 2's UPDATE takes both);
     GIN: h = act(MLP((1+eps) h_self + x)) (Sec. 6.3.1: GI-S adds the vertex's
@@ -41,7 +48,9 @@ recursion on small graphs, the closed form (A^T)^L H W1..WL for the linear
 case, the all-ones mean fixed point, isolated vertices, the paper's worked
 edge-addition example for the affected sets, planted-mistake checks; for max / min the
 brute force, the values printed with the paper's three max cases, max(h) = -min(-h),
-min <= mean <= max, and the one-in-neighbour graph where every aggregator agrees.
+min <= mean <= max, and the one-in-neighbour graph where every aggregator agrees; for attention
+the brute force, zero or sink-side-only attention vectors (= the mean of the projected rows)
+and the one-in-neighbour graph (= the projected row).
 The numeric values of the paper's own runs are unpinned: it prints none.
 """
 from __future__ import annotations
@@ -304,6 +313,8 @@ def _extreme(a, h_prev: np.ndarray, op) -> np.ndarray:
 def layer_rows(state: GraphState, layer: dict, h_prev: np.ndarray, a_in: InAdjacency, rows=None) -> np.ndarray:
     """Eq. (2): h_v = act(UPDATE(h_prev[v], x_v)) for all vertices or for `rows`; dead rows are 0."""
     d_in = layer["d_in"]
+    if layer["agg"] == "attn":
+        return _attention_rows(state, layer, h_prev, a_in, rows)
     x = aggregate(a_in, h_prev, layer["agg"], rows)
     own = h_prev if rows is None else h_prev[rows]
     w0 = np.asarray(layer["W0"], dtype=np.float64)
@@ -320,6 +331,35 @@ def layer_rows(state: GraphState, layer: dict, h_prev: np.ndarray, a_in: InAdjac
         z = _act(layer["act_inner"], z)
         z = z @ np.asarray(layer["W1"], dtype=np.float64) + np.asarray(layer["b1"], dtype=np.float64)
     h = _act(layer["act_out"], z)
+    alive = state.alive if rows is None else state.alive[rows]
+    h[~alive] = 0.0
+    return h
+
+
+LEAKY_SLOPE = 0.2
+
+
+def _attention_rows(state: GraphState, layer: dict, h_prev: np.ndarray, a_in: InAdjacency, rows=None) -> np.ndarray:
+    """Graph attention layer, Eq. (3) (Sec. 3.4.1), single head: with p_u = h_prev[u] W,
+    z_uv = LeakyReLU(a_src . p_u + a_dst . p_v), alpha_uv = exp(z_uv) / sum over v's in-neighbours
+    u' of exp(z_u'v), h_v = act(sum_u alpha_uv p_u + b); a vertex without in-neighbours gets act(b).
+    layer["att"] holds a_src followed by a_dst (d_out numbers each)."""
+    w0 = np.asarray(layer["W0"], dtype=np.float64)
+    b0 = np.asarray(layer["b0"], dtype=np.float64)
+    att = np.asarray(layer["att"], dtype=np.float64)
+    d_out = layer["d_out"]
+    p = h_prev @ w0
+    s_src, s_dst = p @ att[:d_out], p @ att[d_out:]
+    a = (a_in.ones if rows is None else a_in.ones[rows]).tocsr()
+    sinks = np.arange(a.shape[0]) if rows is None else np.asarray(rows)
+    counts = np.diff(a.indptr)
+    z = s_src[a.indices] + np.repeat(s_dst[sinks], counts)      # one entry per in-edge u -> v, grouped by v
+    z = np.where(z > 0, z, LEAKY_SLOPE * z)
+    e = sp.csr_matrix((np.exp(z), a.indices, a.indptr), shape=a.shape)
+    num = e @ p
+    den = np.asarray(e.sum(axis=1)).ravel()
+    x = np.divide(num, den[:, None], out=np.zeros_like(num), where=den[:, None] > 0)
+    h = _act(layer["act_out"], x + b0)
     alive = state.alive if rows is None else state.alive[rows]
     h[~alive] = 0.0
     return h
@@ -351,7 +391,8 @@ def recompute_rows(state: GraphState, model, targets) -> list:
     need[L] = np.unique(np.asarray(targets, dtype=np.int64))
     for l in range(L, 0, -1):
         nbrs = np.unique(a_in.ones[need[l]].indices)
-        need[l - 1] = np.union1d(nbrs, need[l]) if model[l - 1]["self"] != "none" else nbrs
+        own = model[l - 1]["self"] != "none" or model[l - 1]["agg"] == "attn"     # attention scores read the sink's own row
+        need[l - 1] = np.union1d(nbrs, need[l]) if own else nbrs
     h = np.zeros_like(state.h0)
     h[need[0]] = state.h0[need[0]]
     h[~state.alive] = 0.0
@@ -374,7 +415,8 @@ def affected_sets(state_after: GraphState, rec: BatchRecord, model) -> list:
     Hop 0: vertices whose features were written. Hop l: sinks of every changed
     edge (an edge's sink is touched at every hop, Sec. 3.2 and the inbox example
     of Sec. 3.3.2), out-neighbours in the updated graph of hop l-1's set, that
-    set itself when the layer reads the vertex's own previous embedding, and
+    set itself when the layer reads the vertex's own previous embedding (a self term, or
+    attention, where it sets the vertex's scores; Sec. 3.4.1: a vertex of the tree stays in it), and
     created vertices (Sec. 3.2: a new vertex updates its own embeddings);
     deleted vertices are dropped.
     """
@@ -388,7 +430,7 @@ def affected_sets(state_after: GraphState, rec: BatchRecord, model) -> list:
             mask[list(cur)] = True
         nxt = set(dst[mask[src]].tolist())
         nxt |= rec.sinks | rec.added
-        if layer["self"] != "none":
+        if layer["self"] != "none" or layer["agg"] == "attn":   # attention: the vertex's own row sets its scores
             nxt |= cur
         cur = {w for w in nxt if alive[w]}
         out.append(np.array(sorted(cur), dtype=np.int64))

@@ -2,7 +2,8 @@
 
 A model is a list of per-layer dicts. Keys:
   d_in, d_hidden (0 = single linear map), d_out,
-  agg  'sum' | 'mean' | 'wsum' (needs edge weights) | 'max' | 'min',
+  agg  'sum' | 'mean' | 'wsum' (needs edge weights) | 'max' | 'min' | 'attn' (graph attention, one head;
+       extra key att: a_src followed by a_dst, d_out float32 each; self must be 'none'),
   self 'none' | 'concat' (GraphSAGE: rows [0,d_in) of W0 multiply the vertex's
        own embedding, rows [d_in,2*d_in) the aggregate) | 'add' (GIN:
        (1+eps)*own + aggregate),
@@ -40,6 +41,9 @@ def make_model(kind: str, widths, seed: int, last_act: str = "none"):
             lay.update(agg="mean", self="none", W0=glorot(rng, d_in, d_out), b0=_bias(rng, d_out))
         elif kind in ("gcn_max", "gcn_min"):
             lay.update(agg=kind.split("_")[1], self="none", W0=glorot(rng, d_in, d_out), b0=_bias(rng, d_out))
+        elif kind == "gat":                   # single-head graph attention: att = a_src then a_dst (d_out each)
+            lay.update(agg="attn", self="none", W0=glorot(rng, d_in, d_out), b0=_bias(rng, d_out),
+                       att=glorot(rng, 2 * d_out, 1).reshape(-1))
         elif kind == "gcn_wsum":
             lay.update(agg="wsum", self="none", W0=glorot(rng, d_in, d_out), b0=_bias(rng, d_out))
         elif kind in ("sage_mean", "sage_sum", "sage_wsum", "sage_max", "sage_min"):

@@ -30,6 +30,31 @@ def embed(v, l, model, feats, nbrs, alive, memo, alpha=None):
         res = np.array(feats[v], dtype=np.float64)
     else:
         lay = model[l - 1]
+        if lay["agg"] == "attn":                      # Eq. (3) with plain loops
+            import math
+            W0 = np.array(lay["W0"], dtype=np.float64)
+            att = np.array(lay["att"], dtype=np.float64)
+            n_out = lay["d_out"]
+
+            def proj(x):
+                out = np.zeros(n_out)
+                for k in range(lay["d_in"]):
+                    out = out + x[k] * W0[k]
+                return out
+            p_v = proj(embed(v, l - 1, model, feats, nbrs, alive, memo, alpha))
+            t_v = sum(att[n_out + k] * p_v[k] for k in range(n_out))
+            num, den = np.zeros(n_out), 0.0
+            for u in nbrs[v]:
+                p_u = proj(embed(u, l - 1, model, feats, nbrs, alive, memo, alpha))
+                z = sum(att[k] * p_u[k] for k in range(n_out)) + t_v
+                z = z if z > 0 else 0.2 * z
+                num = num + math.exp(z) * p_u
+                den = den + math.exp(z)
+            z = np.array(lay["b0"], dtype=np.float64) + (num / den if den > 0 else 0.0)
+            if lay["act_out"] == "relu":
+                z = np.where(z > 0, z, 0.0)
+            memo[key] = z
+            return z
         acc = np.zeros(lay["d_in"])
         first = True
         for u in nbrs[v]:

@@ -213,12 +213,13 @@ def test_paper_worked_example_vertex_delete_and_feature_update():
     assert c not in es and c not in ed and st.n_edges() == 5
 
 
-@pytest.mark.parametrize("kind", ["gcn_sum", "sage_mean", "gin_sum"])
+@pytest.mark.parametrize("kind", ["gcn_sum", "sage_mean", "gin_sum", "gat"])
 @pytest.mark.parametrize("seed", [0, 1, 2, 3])
 def test_affected_set_equals_rows_that_change(kind, seed):
     """With linear activations and generic real inputs, the rows of H^l that a
     batch really changes are exactly the topological affected set; with ReLU
-    they are a subset of it."""
+    they are a subset of it. (Attention: a vertex of the previous hop's set stays in the
+    set, its score shifts all its coefficients; one without in-neighbours keeps act(b).)"""
     for linear in (True, False):
         st, model, src, dst, feats = small_case(100 + seed, n=60, e=150, kind=kind)
         if linear:
@@ -245,8 +246,14 @@ def test_affected_set_equals_rows_that_change(kind, seed):
         sets = oracle.affected_sets(st, rec, model)
         for l in range(len(model) + 1):
             changed = set(np.nonzero(np.abs(after[l] - before[l]).max(axis=1) > 0)[0].tolist())
-            if linear:
-                assert changed == set(sets[l].tolist()), (l, kind)
+            want = set(sets[l].tolist())
+            if linear and kind == "gat" and l >= 1:
+                # a member of A_{l-1} with no in-neighbour keeps act(b), one with a single in-neighbour
+                # keeps the coefficient 1: its own score cannot move it
+                deg_in = np.bincount(st.edges()[1], minlength=st.cap)
+                assert changed <= want and all(deg_in[w] <= 1 for w in want - changed), (l, sorted(changed ^ want))
+            elif linear:
+                assert changed == want, (l, kind)
             else:
                 assert changed <= set(sets[l].tolist()), (l, kind)
 
@@ -445,3 +452,65 @@ def test_max_after_a_batch_with_all_update_kinds():
     for v in range(st.cap):
         want = embed(v, len(model), model, st.h0, nbrs, st.alive, memo)
         np.testing.assert_allclose(hs[-1][v], want, rtol=1e-12, atol=1e-12)
+
+
+# ---- graph attention (Sec. 3.4.1, Eq. 3) ------------------------------------------------------------
+@pytest.mark.parametrize("seed", [0, 1])
+def test_attention_equals_vertexwise_bruteforce(seed):
+    st, model, src, dst, feats = small_case(seed, kind="gat")
+    hs = oracle.full_recompute(st, model)
+    nbrs = in_lists(st.cap, src, dst)
+    f = np.zeros((st.cap, feats.shape[1]))
+    f[: len(feats)] = feats
+    memo = {}
+    for l in range(len(model) + 1):
+        for v in range(st.cap):
+            want = embed(v, l, model, f, nbrs, st.alive, memo)
+            np.testing.assert_allclose(hs[l][v], want, rtol=1e-11, atol=1e-12)
+
+
+def test_attention_special_cases():
+    st, model, src, dst, feats = small_case(6, kind="gat", widths=(5, 7, 4))
+    # zero attention vectors: every coefficient is 1/deg, the layer is the mean of the projected rows
+    flat = [dict(l, att=np.zeros_like(l["att"])) for l in model]
+    mean = [dict(l, agg="mean") for l in model]
+    for a, b in zip(oracle.full_recompute(st, flat), oracle.full_recompute(st, mean)):
+        np.testing.assert_allclose(a, b, rtol=1e-12, atol=1e-13)
+    # a sink-side vector only: the score is the same for all in-neighbours of a vertex, again the mean
+    d1 = model[0]["d_out"]
+    sink_only = [dict(model[0], att=np.concatenate([np.zeros(d1), model[0]["att"][d1:]]))]
+    np.testing.assert_allclose(oracle.full_recompute(st, sink_only)[1], oracle.full_recompute(st, mean[:1])[1],
+                               rtol=1e-12, atol=1e-13)
+    # one in-neighbour each: the coefficient is 1 whatever the scores are
+    n = 12
+    h = np.random.default_rng(2).standard_normal((n, 5))
+    cyc = oracle.GraphState(n, n, np.arange(n), (np.arange(n) + 1) % n, h)
+    got = oracle.full_recompute(cyc, model[:1])[1]
+    want = np.maximum(np.roll(h, 1, axis=0) @ np.asarray(model[0]["W0"], dtype=np.float64) + model[0]["b0"], 0.0)
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
+    # the source-side vector matters: swapping the halves changes the result
+    swapped = [dict(model[0], att=np.concatenate([model[0]["att"][d1:], model[0]["att"][:d1]]))]
+    assert np.abs(oracle.full_recompute(st, swapped)[1] - oracle.full_recompute(st, model[:1])[1]).max() > 1e-3
+
+
+def test_attention_after_a_batch_with_all_update_kinds():
+    st, model, src, dst, feats = small_case(12, kind="gat")
+    n = len(feats)
+    rng = np.random.default_rng(5)
+    payload = rng.standard_normal((2, feats.shape[1]))
+    free = next((u, v) for u in range(10) for v in range(10) if u != v and not st.has_edge(u, v))
+    ops = [(ri.OP_EDGE_DEL, int(src[0]), int(dst[0]), 0), (ri.OP_EDGE_ADD, free[0], free[1], 0),
+           (ri.OP_FEAT_UPDATE, 5, 0, 0), (ri.OP_VERTEX_ADD, n, 0, 1), (ri.OP_EDGE_ADD, n, 4, 0),
+           (ri.OP_EDGE_ADD, 6, n, 0), (ri.OP_VERTEX_DEL, 9, 0, 0)]
+    rec = st.apply_batch(np.array(ops, dtype=np.uint32), payload)
+    assert rec.accepted.all()
+    hs = oracle.full_recompute(st, model)
+    es, ed = st.edges()
+    nbrs = in_lists(st.cap, es, ed)
+    memo = {}
+    for v in range(st.cap):
+        want = embed(v, len(model), model, st.h0, nbrs, st.alive, memo)
+        np.testing.assert_allclose(hs[-1][v], want, rtol=1e-11, atol=1e-12)
+    # sampled rows through their cones give the same values as the full recomputation
+    cone = oracle.recompute_rows(st, model, [0, 3, 7, n])
+    np.testing.assert_allclose(cone[-1][1], hs[-1][cone[-1][0]], rtol=1e-12, atol=1e-13)
