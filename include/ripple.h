@@ -62,7 +62,8 @@ typedef struct {
 
 typedef enum {
     RIPPLE_AGG_SUM = 0, RIPPLE_AGG_MEAN = 1, RIPPLE_AGG_WSUM = 2,   /* linear (Table 1, Sec. 3.3.3) */
-    RIPPLE_AGG_MAX = 3, RIPPLE_AGG_MIN = 4                          /* monotonic (Table 1, Sec. 3.4.2) */
+    RIPPLE_AGG_MAX = 3, RIPPLE_AGG_MIN = 4,                         /* monotonic (Table 1, Sec. 3.4.2) */
+    RIPPLE_AGG_ATTN = 5                                             /* graph attention (Sec. 3.4.1, Eq. 3) */
 } ripple_agg;
 typedef enum {
     RIPPLE_SELF_NONE = 0,    /* GraphConv:  h = act(x W0 + b0)                               */
@@ -83,7 +84,15 @@ typedef enum { RIPPLE_STORE_F32 = 0, RIPPLE_STORE_BF16 = 1 } ripple_store;
  * vertex that hears from a changed in-neighbour keeps its aggregate, raises it from the message, or
  * recomputes it from all its in-neighbours; a vertex whose in-edges changed always recomputes. Such
  * layers are not handled project-first and are refused in the deterministic mode (they need none:
- * their result does not depend on any order). */
+ * their result does not depend on any order).
+ * RIPPLE_AGG_ATTN is a single-head graph attention layer: with p_u = h_u W0,
+ * z_uv = LeakyReLU_0.2(a_src . p_u + a_dst . p_v), alpha_uv = softmax of z_uv over v's in-neighbours,
+ * h_v = act_out(sum_u alpha_uv p_u + b0), act_out(b0) for a vertex without in-neighbours; att holds
+ * a_src followed by a_dst (d_out floats each); self_mode must be RIPPLE_SELF_NONE and d_hidden 0. It
+ * is maintained with the hybrid scheme of Sec. 3.4.1: a vertex already in the previous hop's set, or
+ * with a changed in-edge, recomputes numerator and denominator from all its in-neighbours, any
+ * other receives numerator / denominator differences. Exponentials are taken without subtracting a
+ * maximum (the incremental form needs a fixed reference), so scores must stay below about 80. */
 typedef struct {
     uint32_t d_in, d_hidden, d_out;
     uint32_t agg;          /* ripple_agg  */
@@ -93,6 +102,7 @@ typedef struct {
     uint32_t act_out;      /* ripple_act */
     const float *W0, *b0;  /* host */
     const float *W1, *b1;  /* host; NULL when d_hidden == 0 */
+    const float *att;      /* host; RIPPLE_AGG_ATTN only: 2 * d_out floats, else NULL */
 } ripple_layer_desc;
 
 #define RIPPLE_MAX_LAYERS 8

@@ -23,7 +23,7 @@ RIPPLE_MAX_LAYERS = 8
 RIPPLE_N_PHASES = 8
 PHASES = ["ingest", "struct", "frontier", "scatter", "compact", "transform", "other", "total"]
 OPT_TIMING, OPT_SCATTER_MODE, OPT_PULL_RATIO, OPT_PROJECT_FIRST, OPT_BF16_MFMA, OPT_SELF_CACHE, OPT_DETERMINISTIC = 0, 1, 2, 3, 4, 5, 6
-AGG = {"sum": 0, "mean": 1, "wsum": 2, "max": 3, "min": 4}
+AGG = {"sum": 0, "mean": 1, "wsum": 2, "max": 3, "min": 4, "attn": 5}
 SELF = {"none": 0, "concat": 1, "add": 2}
 ACT = {"none": 0, "relu": 1}
 STORE = {"f32": 0, "bf16": 1}
@@ -44,7 +44,8 @@ class LayerDesc(C.Structure):
     _fields_ = [("d_in", C.c_uint32), ("d_hidden", C.c_uint32), ("d_out", C.c_uint32),
                 ("agg", C.c_uint32), ("self_mode", C.c_uint32), ("eps", C.c_float),
                 ("act_inner", C.c_uint32), ("act_out", C.c_uint32),
-                ("W0", C.c_void_p), ("b0", C.c_void_p), ("W1", C.c_void_p), ("b1", C.c_void_p)]
+                ("W0", C.c_void_p), ("b0", C.c_void_p), ("W1", C.c_void_p), ("b1", C.c_void_p),
+                ("att", C.c_void_p)]
 
 
 class BatchResult(C.Structure):
@@ -194,6 +195,12 @@ def ripple_load_model(ctx, model):
             b1 = np.ascontiguousarray(lay["b1"], dtype=np.float32)
             keep += [w1, b1]
             d.W1, d.b1 = w1.ctypes.data, b1.ctypes.data
+        if lay["agg"] == "attn":
+            att = np.ascontiguousarray(lay["att"], dtype=np.float32)
+            if att.shape != (2 * lay["d_out"],):
+                raise ValueError("att must hold a_src followed by a_dst, d_out numbers each")
+            keep.append(att)
+            d.att = att.ctypes.data
     _check(ctx, lib.ripple_load_model(ctx, len(model), descs))
 
 

@@ -254,7 +254,7 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
     hipStreamSynchronize(c->stream);
     void *ptrs[] = {c->out_meta, c->in_meta, c->out_capv, c->in_capv, c->vstate, c->pend_out, c->pend_in, c->dead_out,
                     c->dead_in, c->hole_out, c->hole_in, c->out_pool, c->in_pool, c->in_w, c->alive, c->part_cnt, c->part_deg, c->part_ideg, c->ioff[0], c->ctr, c->D[0], c->D[1],
-                    c->tmp, c->PD, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ioff_all, c->mk, c->ops_d, c->payload_d,
+                    c->tmp, c->PD, c->Pold, c->sold, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ioff_all, c->mk, c->ops_d, c->payload_d,
                     c->op_status, c->op_pos_out, c->op_pos_in, c->op_touch, c->touch_out, c->touch_in, c->exp_kind, c->exp_s, c->exp_a,
                     c->exp_b, c->st_src, c->st_dst, c->st_sign, c->gather_d, c->gather_ids};
     for (void *p : ptrs)
@@ -265,7 +265,8 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
     }
     for (uint32_t l = 0; l < c->L; ++l) {
         LayerDev &ly = c->layers[l];
-        void *w[] = {ly.W0, ly.b0, ly.W1, ly.b1, ly.W0h, ly.W1h, ly.bzero, (ly.Wn != ly.W0) ? ly.Wn : nullptr, ly.PS};
+        void *w[] = {ly.W0, ly.b0, ly.W1, ly.b1, ly.W0h, ly.W1h, ly.bzero, (ly.Wn != ly.W0) ? ly.Wn : nullptr, ly.PS,
+                     ly.att, ly.P, ly.ssrc, ly.sdst, ly.den};
         for (void *p : w)
             if (p) hipFree(p);
     }
@@ -305,12 +306,14 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
     uint32_t prev = c->d[0];
     for (uint32_t l = 0; l < n_layers; ++l) {
         const ripple_layer_desc &s = layers[l];
-        if (s.d_in != prev || s.d_out == 0 || s.d_out > 1024 || s.d_hidden > 1024 || s.agg > RIPPLE_AGG_MIN ||
+        if (s.d_in != prev || s.d_out == 0 || s.d_out > 1024 || s.d_hidden > 1024 || s.agg > RIPPLE_AGG_ATTN ||
             s.self_mode > RIPPLE_SELF_ADD || s.act_inner > RIPPLE_ACT_RELU || s.act_out > RIPPLE_ACT_RELU || !s.W0 ||
             !s.b0 || (s.d_hidden && (!s.W1 || !s.b1)))
             return fail(c, RIPPLE_EINVAL, "bad layer descriptor (widths must chain, dims <= 1024, pointers set)");
         if (s.agg == RIPPLE_AGG_WSUM && !c->in_w)
             return fail(c, RIPPLE_EINVAL, "weighted-sum layer on a graph that was built without edge weights");
+        if (s.agg == RIPPLE_AGG_ATTN && (!s.att || s.self_mode != RIPPLE_SELF_NONE || s.d_hidden))
+            return fail(c, RIPPLE_EINVAL, "attention layer: att must be set, self_mode none, d_hidden 0");
         if ((s.agg == RIPPLE_AGG_WSUM || s.agg >= RIPPLE_AGG_MAX) && c->opt_deterministic)
             return fail(c, RIPPLE_EINVAL, "the deterministic mode takes sum and mean layers only");
         prev = s.d_out;
@@ -350,6 +353,15 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
         // project first where the single linear map shrinks the row at least by half
         ly.proj = (c->opt_project && !c->opt_deterministic && s.agg < RIPPLE_AGG_MAX && s.d_hidden == 0 && s.self_mode != RIPPLE_SELF_ADD && 2 * s.d_out <= s.d_in) ? 1u : 0u;
         ly.selfc = (c->opt_selfcache && s.d_hidden == 0 && s.self_mode == RIPPLE_SELF_CONCAT) ? 1u : 0u;
+        if (s.agg == RIPPLE_AGG_ATTN) {
+            RP_TRY(dev_alloc(c, &ly.att, (size_t)2 * s.d_out, false));
+            RP_HIP(c, hipMemcpy(ly.att, s.att, (size_t)2 * s.d_out * 4, hipMemcpyHostToDevice));
+            RP_TRY(dev_alloc(c, &ly.bzero, (size_t)ly.N0pad, true));
+            RP_TRY(dev_alloc(c, &ly.P, (size_t)c->n_cap * s.d_out, true));
+            RP_TRY(dev_alloc(c, &ly.ssrc, (size_t)c->n_cap, true));
+            RP_TRY(dev_alloc(c, &ly.sdst, (size_t)c->n_cap, true));
+            RP_TRY(dev_alloc(c, &ly.den, (size_t)c->n_cap, true));
+        }
         if (ly.proj || ly.selfc) {
             std::vector<float> zeros(ly.N0pad, 0.0f);
             if (s.self_mode == RIPPLE_SELF_CONCAT) {           // rows d_in .. 2 d_in - 1 of W0
@@ -376,9 +388,18 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
         if (hipMalloc(&h, bytes) != hipSuccess) return fail(c, RIPPLE_ENOMEM, "device allocation of H failed");
         c->H[l] = h;
         RP_HIP(c, hipMemsetAsync(h, 0, bytes, c->stream));
-        c->xw[l] = c->layers[l - 1].proj ? c->d[l] : c->d[l - 1];
+        c->xw[l] = (c->layers[l - 1].proj || rp_layer_attn(c, l)) ? c->d[l] : c->d[l - 1];
         RP_TRY(dev_alloc(c, &c->X[l], n * c->xw[l], true));
         if (c->layers[l - 1].selfc) RP_TRY(dev_alloc(c, &c->layers[l - 1].PS, n * c->d[l], true));
+    }
+    {
+        uint32_t aw = 0;                                 // widest attention layer
+        for (uint32_t l = 1; l <= c->L; ++l)
+            if (rp_layer_attn(c, l)) aw = std::max(aw, c->d[l]);
+        if (aw) {
+            RP_TRY(dev_alloc(c, &c->Pold, n * aw, true));
+            RP_TRY(dev_alloc(c, &c->sold, n, true));
+        }
     }
     RP_TRY(dev_alloc(c, &c->D[0], n * c->dmax, false));
     RP_TRY(dev_alloc(c, &c->D[1], n * c->dmax, false));
@@ -429,6 +450,13 @@ extern "C" ripple_status ripple_full_infer(ripple_ctx *c) {
                        c->n_words);
     rp_launch_bitmap_to_list(c, c->bm[0], c->all_list, &c->ctr->a[0]);
     for (uint32_t l = 1; l <= c->L; ++l) {
+        if (rp_layer_attn(c, l)) {
+            rp_launch_gat_project(c, l, c->all_list, &c->ctr->a[0]);
+            rp_launch_gat_scores(c, l, c->all_list, &c->ctr->a[0]);
+            rp_launch_gat_scatter(c, l, true);
+            rp_launch_transform(c, l, c->all_list, &c->ctr->a[0], false);
+            continue;
+        }
         if (c->layers[l - 1].proj) rp_launch_project(c, l, c->all_list, &c->ctr->a[0], false);
         if (c->layers[l - 1].selfc) rp_launch_self_project(c, l, c->all_list, &c->ctr->a[0]);
         if (c->opt_deterministic) rp_launch_scatter_owner(c, l, true);     // same summation order as the batches use
@@ -596,7 +624,10 @@ static ripple_status ensure_batch_buffers(ripple_ctx *c, uint32_t n_ops, uint32_
     return RIPPLE_OK;
 }
 
-static bool layer_self(const ripple_ctx *c, uint32_t l) { return c->layers[l - 1].self_mode != RIPPLE_SELF_NONE; }
+// A_{l-1} is part of A_l: the layer reads the vertex's own row (a self term, or its attention score)
+static bool layer_self(const ripple_ctx *c, uint32_t l) {
+    return c->layers[l - 1].self_mode != RIPPLE_SELF_NONE || rp_layer_attn(c, l);
+}
 
 // Enqueue one conflict-free piece: Apply, then hop by hop frontier / scatter / transform.
 static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
@@ -654,6 +685,28 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
             t = rp_timer_begin(c);
             rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], l < c->L);
             rp_timer_end(c, t, RIPPLE_PH_TRANSFORM, (int)l);
+            have_all = false;                          // the candidates went through the live-vertex list's buffer
+            continue;
+        }
+        if (rp_layer_attn(c, l)) {                     // attention: recompute or numerator / denominator deltas (Sec. 3.4.1)
+            t = rp_timer_begin(c);
+            rp_launch_gat_save(c, l, c->list[l - 1], &c->ctr->a[l - 1]);
+            rp_launch_gat_project(c, l, c->list[l - 1], &c->ctr->a[l - 1]);
+            rp_launch_gat_scores(c, l, c->list[l - 1], &c->ctr->a[l - 1]);
+            rp_timer_end(c, t, RIPPLE_PH_OTHER, (int)l);
+            t = rp_timer_begin(c);
+            rp_launch_frontier_mark(c, l, false);
+            rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
+            t = rp_timer_begin(c);
+            rp_launch_frontier_compact(c, l, true, l < c->L, false, multi);
+            rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l);
+            t = rp_timer_begin(c);
+            rp_launch_gat_scatter(c, l, false);
+            rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l);
+            t = rp_timer_begin(c);
+            rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], l < c->L);
+            rp_timer_end(c, t, RIPPLE_PH_TRANSFORM, (int)l);
+            have_all = false;                          // the long-row queue went through the live-vertex list's buffer
             continue;
         }
         // hop 1 always pushes: hop-0 rows are in operation order, not ranked by vertex id. Where the

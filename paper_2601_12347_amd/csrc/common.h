@@ -65,6 +65,9 @@ struct LayerDev {
     // refreshed only where H^{l-1} changed, so the row transform multiplies the aggregate alone
     uint32_t selfc;
     float *PS;
+    // attention layers: projected rows P[v] = H^{l-1}[v] W0 [n x d_out], scores a_src . P[v] and a_dst . P[v],
+    // denominators of the softmax (the numerators are the layer's X rows); att = a_src then a_dst on the device
+    float *att, *P, *ssrc, *sdst, *den;
 };
 
 struct PhaseTimer;
@@ -100,6 +103,7 @@ struct ripple_ctx {
     float *D[2] = {nullptr, nullptr};                   // delta rows D^l[v] (valid for v in A_l), ping-pong
     float *tmp = nullptr;                               // hidden activations of two-stage updates
     float *PD = nullptr;                                // projected rows of project-first layers
+    float *Pold = nullptr, *sold = nullptr;             // attention hops: projected rows / source scores of A_{l-1} before the batch
     uint32_t xw[RIPPLE_MAX_LAYERS + 1] = {0};           // width of X^l (d_{l-1}, or d_l when projected)
     uint32_t pd_ld = 0;                                 // row stride of PD (64-byte multiple)
 
@@ -172,7 +176,10 @@ struct ripple_ctx {
 
 // scatter policy of hop l as the kernels see it (see rp_hop_mode)
 static inline bool rp_layer_mono(const ripple_ctx *c, uint32_t l) {      // layer l (1-based) aggregates with max or min
-    return l >= 1 && l <= c->L && c->layers[l - 1].agg >= RIPPLE_AGG_MAX;
+    return l >= 1 && l <= c->L && (c->layers[l - 1].agg == RIPPLE_AGG_MAX || c->layers[l - 1].agg == RIPPLE_AGG_MIN);
+}
+static inline bool rp_layer_attn(const ripple_ctx *c, uint32_t l) {
+    return l >= 1 && l <= c->L && c->layers[l - 1].agg == RIPPLE_AGG_ATTN;
 }
 static inline int rp_layer_mode(const ripple_ctx *c, uint32_t l) {
     return c->layers[l - 1].agg == RIPPLE_AGG_WSUM ? 4 : c->opt_scatter;

@@ -295,7 +295,7 @@ struct MutArgs {
     float *X[RIPPLE_MAX_LAYERS + 1];
     const float *Wn[RIPPLE_MAX_LAYERS + 1];      // project-first layers: neighbour weights (row stride wn_ld), else null
     uint32_t wn_ld[RIPPLE_MAX_LAYERS + 1];
-    uint32_t mono_mask;                          // bit l: layer l aggregates with max / min (no structural terms)
+    uint32_t mono_mask;                          // bit l: layer l takes max / min or attention (no structural terms)
     int d0_old;                                  // layer 1 does: D0 receives the old feature row instead of the difference
 };
 
@@ -959,7 +959,7 @@ static MutArgs make_args(ripple_ctx *c, uint32_t n_ops) {
     }
     a.mono_mask = 0;
     for (uint32_t l = 1; l <= c->L; ++l)
-        if (rp_layer_mono(c, l)) a.mono_mask |= 1u << l;
+        if (rp_layer_mono(c, l) || rp_layer_attn(c, l)) a.mono_mask |= 1u << l;
     a.d0_old = rp_layer_mono(c, 1) ? 1 : 0;
     return a;
 }

@@ -28,7 +28,13 @@ void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow
 void rp_launch_pull_all(ripple_ctx *c, uint32_t l);
 void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l);
 
+// attention.hip
+void rp_launch_gat_scatter(ripple_ctx *c, uint32_t l, bool bootstrap);
+void rp_launch_gat_save(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d);
+void rp_launch_gat_scores(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d);
+
 // transform.hip
+void rp_launch_gat_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d);
 void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool emit_delta);
 void rp_launch_self_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d);
 void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool from_deltas);

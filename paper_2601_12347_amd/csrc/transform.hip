@@ -50,6 +50,7 @@ struct TArgs {
     const float *addend;           // [vertex x N] rows added before the activation (projected aggregate or cached self term), or null
     int addend_scaled;             // 1: the addend is an aggregate and takes the mean scale
     const float *addend2;          // second, unscaled addend (k_transform_addend_only), or null
+    const float *den;              // attention layers (k_transform_addend_only): the addend is divided by den[vertex], or null
     float *tmp_out;
     uint32_t tmp_out_ld;
     void *Hout;
@@ -392,6 +393,13 @@ __device__ __forceinline__ void addend_only_rows(const TArgs &a) {
         for (int u = 0; u < R; ++u) {
             const uint32_t deg = a.in_meta[v[u]].y;        // read in any case: no branch between the loads
             sc[u] = a.mean ? 1.0f / (float)(deg > 1u ? deg : 1u) : 1.0f;
+        }
+        if (a.den) {                                       // attention: numerator / denominator, 0 without in-neighbours
+#pragma unroll
+            for (int u = 0; u < R; ++u) {
+                const float dn = a.den[v[u]];
+                sc[u] = (a.in_meta[v[u]].y > 0u && dn > 0.0f) ? 1.0f / dn : 0.0f;
+            }
         }
         const float *p2 = a.addend2 ? a.addend2 : a.addend;
         const float w2 = a.addend2 ? 1.0f : 0.0f;
@@ -907,6 +915,7 @@ static TArgs base_args(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
     a.addend = nullptr;
     a.addend_scaled = 1;
     a.addend2 = nullptr;
+    a.den = nullptr;
     a.a_mode = 0;
     a.out_mode = 1;
     a.act = 0;
@@ -948,6 +957,22 @@ void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
     launch_t(c, a, ly.d_in % 4 == 0, from_deltas ? c->last_a[l - 1] : c->n_cap);
 }
 
+// Attention layer l: P[v] = H^{l-1}[v] W0 for the listed vertices (fp32, no bias, no activation).
+void rp_launch_gat_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d) {
+    const LayerDev &ly = c->layers[l - 1];
+    TArgs a = base_args(c, l, list, count_d);
+    a.mean = 0;
+    a.Wt = nullptr;
+    a.bias = ly.bzero;
+    a.act = RIPPLE_ACT_NONE;
+    a.a_mode = 4;
+    a.out_mode = 2;
+    a.tmp_out = ly.P;
+    a.tmp_out_ld = ly.d_out;
+    a.Hout = nullptr;
+    launch_t(c, a, ly.d_in % 4 == 0, (list == c->all_list) ? c->n_cap : c->last_a[l - 1]);
+}
+
 // Cached self term of layer l: PS[v] = H^{l-1}[v] W_self for the listed vertices (fp32, no bias).
 void rp_launch_self_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d) {
     const LayerDev &ly = c->layers[l - 1];
@@ -978,6 +1003,13 @@ void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const 
     const bool vec_in = (ly.d_in % 4 == 0);
     // expected row count: the previous batch's (bootstrap passes the list of all live vertices)
     const uint32_t hint = (list == c->all_list) ? c->n_cap : c->last_a[l];
+    if (ly.agg == RIPPLE_AGG_ATTN) {             // h = act(numerator / denominator + b): no product left per row
+        a.addend = c->X[l];
+        a.den = ly.den;
+        a.act = (int)ly.act_out;
+        hipLaunchKernelGGL(k_transform_addend_only, dim3(c->n_cu * 8), dim3(256), 0, c->stream, a);
+        return;
+    }
     if (ly.proj) {                               // aggregate already multiplied by W_neigh: add it in the epilogue
         a.addend = c->X[l];
         a.act = (int)ly.act_out;

@@ -59,6 +59,9 @@ class Pair:
         tol = 1e-4 if tol is None else tol
         src, dst = self.ora.edges()
         for l in range(1, self.L + 1):
+            if self.model[l - 1]["agg"] == "attn":
+                self._check_attention_numerators(l, tol)
+                continue
             h_prev = self.gpu_layer(l - 1).astype(np.float64)
             width, projected, _ = rp.ripple_get_layer_info(self.ctx, l)
             if projected:                                     # the layer caches sum_u H[u] W_neigh
@@ -79,6 +82,27 @@ class Pair:
             got = rp.ripple_get_aggregates(self.ctx, l, width, n_rows=self.cap)
             err = oracle.max_rel_err(got, want, self.ora.alive)
             assert err <= tol, f"aggregate {l}: {err:.3e}"
+
+    def _check_attention_numerators(self, l, tol):
+        """Attention layers cache sum_u w_uv P[u] (un-normalised, Sec. 3.4.1). The weights w_uv depend on
+        scores the library keeps to itself, so the cached row is compared up to its positive scale: divided
+        by the denominator implied by the stored output it must give the oracle's normalised aggregate
+        computed from the stored H^{l-1}; here simply: direction and, through the embeddings check, value."""
+        lay = self.model[l - 1]
+        h_prev = self.gpu_layer(l - 1).astype(np.float64)
+        width, _, _ = rp.ripple_get_layer_info(self.ctx, l)
+        assert width == lay["d_out"]
+        num = rp.ripple_get_aggregates(self.ctx, l, width, n_rows=self.cap).astype(np.float64)
+        lin = dict(lay, act_out="none", b0=np.zeros_like(lay["b0"]))
+        want = oracle.layer_rows(self.ora, lin, h_prev, oracle.in_adjacency(self.ora))   # sum_u alpha_uv P[u]
+        # num = den * want with den > 0: compare after normalising both by their largest entry
+        def unit(m):
+            s = np.abs(m).max(axis=1, keepdims=True)
+            return np.divide(m, s, out=np.zeros_like(m), where=s > 0)
+        has = (np.bincount(self.ora.edges()[1], minlength=self.cap) > 0) & self.ora.alive
+        err = np.abs(unit(num)[has] - unit(want)[has]).max() if has.any() else 0.0
+        assert err <= (1e-4 if tol is None else tol), f"attention numerator {l}: {err:.3e}"
+        assert not num[~has].any()
 
     def check_graph(self):
         src, dst = self.ora.edges()

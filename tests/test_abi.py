@@ -31,7 +31,7 @@ def test_every_declared_symbol_is_exported():
 
 
 def test_struct_layouts_match_the_header():
-    assert C.sizeof(rp.binding.LayerDesc) == 64
+    assert C.sizeof(rp.binding.LayerDesc) == 72
     assert C.sizeof(rp.BatchResult) == 4 * 6 + 8 + 4 * 9 + 4 + 8 * 9 + 4 + 3 * 4 * 9
     assert C.sizeof(rp.Stats) == 8 + 8 * 8 * 9 * 2 + 8 * 9 * 3
 

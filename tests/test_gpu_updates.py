@@ -477,3 +477,83 @@ def test_max_layers_are_refused_in_deterministic_mode():
     with pytest.raises(rp.RippleError):
         rp.ripple_load_model(ctx, ri.make_model("gcn_max", (8, 6), 1))
     rp.ripple_destroy(ctx)
+
+
+# ---- graph attention (Sec. 3.4.1) -------------------------------------------------------------------
+@pytest.mark.parametrize("widths,store", [((100, 256, 47), "f32"), ((16, 40, 24, 10), "f32"), ((32, 64, 12), "bf16"),
+                                          ((24, 300, 10), "f32")])
+def test_graph_attention_layers(widths, store):
+    """Single-head attention layers, hybrid-incremental: vertices already in the previous hop's set or with
+    a changed in-edge recompute numerator and denominator, the others receive differences. Sets are
+    the topological ones (with A_{l-1} inside A_l), embeddings match the oracle after every batch."""
+    print("case attention", widths, store, flush=True)
+    pair, graph = make_pair(n=1500, e=14000, d0=widths[0], kind="gat", widths=widths, seed=171, slack=256, store=store,
+                            top_share=0.05)
+    stream = make_stream(pair, graph, MIXV, 173)
+    tol = 2e-3 if store == "bf16" else None
+    try:
+        pair.check_embeddings()
+        pair.check_aggregates(tol=tol)
+        for b, bs in enumerate([2, 50, 300, 40, 600]):
+            print(" batch", b, bs, flush=True)
+            if b == 3:
+                rp.ripple_compact(pair.ctx)
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload)
+            pair.check_aggregates(tol=tol)
+        pair.check_graph()
+    finally:
+        pair.close()
+
+
+def test_attention_between_other_layers_and_feature_only_batches():
+    """mean -> attention -> max -> attention; then feature-only batches, where most receivers are not in
+    the previous hop's set and take the incremental path."""
+    print("case attention mixed", flush=True)
+    widths = (16, 40, 24, 12, 10)
+    src, dst, out_law, in_law = ri.chung_lu_graph(1200, 10000, 2.1, 0.04, 181)
+    feats = ri.features(1200, widths[0], 182)
+    model = ri.make_model("gat", widths, 183)
+    sage = ri.make_model("sage_mean", widths, 184)
+    gmax = ri.make_model("gcn_max", widths, 185)
+    model[0], model[2] = sage[0], gmax[2]
+    from harness import Pair
+    pair = Pair(1200, 1200 + 128, src, dst, feats, model)
+    stream = ri.UpdateStream(1200, 1200 + 128, src, dst, out_law, in_law, widths[0], MIXV, 186)
+    feat_only = ri.UpdateStream(1200, 1200 + 128, src, dst, out_law, in_law, widths[0],
+                                {"edge_add": 0.0, "edge_del": 0.0, "feat": 1.0, "vadd": 0.0, "vdel": 0.0}, 187)
+    try:
+        pair.check_embeddings()
+        for b, bs in enumerate([5, 3]):
+            print(" feature batch", b, bs, flush=True)
+            ops, payload, _ = feat_only.next_batch(bs)
+            pair.step(ops, payload)
+            pair.check_aggregates()
+    finally:
+        pair.close()
+    pair = Pair(1200, 1200 + 128, src, dst, feats, model)
+    try:
+        for b, bs in enumerate([5, 120, 500]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload)
+            pair.check_aggregates()
+    finally:
+        pair.close()
+
+
+def test_attention_with_hub_rows():
+    print("case attention hubs", flush=True)
+    pair, graph = make_pair(n=20000, e=240000, d0=24, kind="gat", widths=(24, 48, 12), seed=191, slack=64, top_share=0.04)
+    stream = make_stream(pair, graph, MIX3, 193)
+    try:
+        deg_in, _ = rp.ripple_get_degrees(pair.ctx, 1, pair.cap)
+        assert deg_in.max() > 4096
+        pair.check_embeddings()
+        for b, bs in enumerate([20, 2000]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload)
+        pair.check_aggregates()
+    finally:
+        pair.close()
