@@ -70,7 +70,11 @@ def algorithmic_work(st, model, widths, store, L, layer_info, n_edges=0):
             out[("frontier", l)] = dict(bytes=8 * a_prev + 4 * m_l + 4 * a_l, flops=0)
         self_w = lay["d_in"] if lay["self"] != "none" else 0
         out_bytes = d_out * s_h * 2 + (d_out * 4 if l < L else 0) + 4
-        if self_cached:
+        if lay["agg"] == "attn":
+            # projection of A_{l-1} (row in, d_out floats out), then per dirty row numerator, denominator, old and new row
+            flops = 2 * a_prev * d_prev * d_out
+            nbytes = a_prev * (d_prev * s_h + d_out * 4) + a_l * (d_out * 4 + 4 + out_bytes)
+        elif self_cached:
             # self term refreshed on A_{l-1} (row in, d_out floats out); per dirty row the cached self
             # term and the aggregate (projected, or multiplied by W_neigh here) are read
             flops = 2 * a_prev * self_w * d_out + (2 * a_prev * d_prev * d_out if projected else 2 * a_l * d_prev * d_out)

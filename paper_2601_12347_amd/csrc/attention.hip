@@ -37,11 +37,11 @@ __device__ __forceinline__ float gat_weight(float s_u, float t_v) {
 // One block of up to 64 in-neighbours (id per lane in my_u, `valid` lanes hold one). recompute: all of them
 // contribute w P[u]; otherwise the changed ones contribute w_new P[u] - w_old Pold[u]. acc: the wavefront's
 // running numerator (column lane + 64 j); returns this lane's share of the denominator.
-template <int NJ, int G>
-__device__ __forceinline__ float gat_block(const GatArgs &a, uint32_t my_u, bool valid, bool recompute, float t_v, float *acc) {
+template <int NJ, int G, bool recompute>
+__device__ __forceinline__ float gat_block(const GatArgs &a, uint32_t my_u, bool valid, float t_v, float *acc) {
     const int lane = rp_lane();
     const uint32_t d = a.d;
-    const bool on = valid && (recompute || rp_bit(a.bm_prev, my_u));
+    const bool on = valid && (recompute || rp_bit(a.bm_prev, my_u));     // rp_bit is not evaluated when recomputing
     float wn = 0.0f, wo = 0.0f;
     if (on) {
         wn = gat_weight(a.ssrc[my_u], t_v);
@@ -60,7 +60,7 @@ __device__ __forceinline__ float gat_block(const GatArgs &a, uint32_t my_u, bool
                 n = g + 1;
             }
         }
-        float rn[G][NJ], ro[G][NJ];
+        float rn[G][NJ], ro[recompute ? 1 : G][NJ];
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             const uint32_t u = __shfl(my_u, kk[g]);
@@ -69,7 +69,7 @@ __device__ __forceinline__ float gat_block(const GatArgs &a, uint32_t my_u, bool
                 const uint32_t col = lane + 64 * j;
                 const bool in = g < n && col < d;
                 rn[g][j] = in ? a.P[(size_t)u * d + col] : 0.0f;
-                ro[g][j] = (in && !recompute) ? a.Pold[(size_t)u * d + col] : 0.0f;
+                if (!recompute) ro[g][j] = in ? a.Pold[(size_t)u * d + col] : 0.0f;
             }
         }
 #pragma unroll
@@ -77,7 +77,7 @@ __device__ __forceinline__ float gat_block(const GatArgs &a, uint32_t my_u, bool
             if (g < n) {
                 const float wnk = __shfl(wn, kk[g]), wok = __shfl(wo, kk[g]);
 #pragma unroll
-                for (int j = 0; j < NJ; ++j) acc[j] += wnk * rn[g][j] - wok * ro[g][j];
+                for (int j = 0; j < NJ; ++j) acc[j] += recompute ? wnk * rn[g][j] : wnk * rn[g][j] - wok * ro[g][j];
             }
         }
     }
@@ -92,7 +92,8 @@ __device__ __forceinline__ float gat_wave_sum(float x) {
 
 template <int NJ>
 __global__ __launch_bounds__(256) void k_gat_scatter(GatArgs a) {
-    constexpr int G = (NJ <= 1) ? 8 : (NJ <= 2 ? 4 : (NJ <= 4 ? 2 : 1));
+    constexpr int G = (NJ <= 1) ? 8 : (NJ <= 2 ? 4 : (NJ <= 4 ? 2 : 1));     // senders in flight (old and new row each)
+    constexpr int GR = (NJ <= 1) ? 16 : (NJ <= 16 ? 16 / NJ : 1);             // rows in flight when recomputing
     const uint32_t count = *a.count_ptr;
     const int lane = rp_lane();
     const uint32_t d = a.d;
@@ -113,7 +114,7 @@ __global__ __launch_bounds__(256) void k_gat_scatter(GatArgs a) {
         for (uint32_t base = 0; base < m.y; base += 64) {
             const uint32_t e = base + lane;
             const uint32_t my_u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
-            dsum += gat_block<NJ, G>(a, my_u, e < m.y, recompute, t_v, acc);
+            dsum += recompute ? gat_block<NJ, GR, true>(a, my_u, e < m.y, t_v, acc) : gat_block<NJ, G, false>(a, my_u, e < m.y, t_v, acc);
         }
         dsum = gat_wave_sum(dsum);
 #pragma unroll
@@ -132,6 +133,7 @@ __global__ __launch_bounds__(256) void k_gat_scatter(GatArgs a) {
 template <int NJ, int TEAM>
 __global__ __launch_bounds__(TEAM * 64) void k_gat_scatter_long(GatArgs a) {
     constexpr int G = (NJ <= 1) ? 8 : (NJ <= 2 ? 4 : (NJ <= 4 ? 2 : 1));
+    constexpr int GR = (NJ <= 2) ? 16 : 32 / NJ;               // a long row is paced by round trips
     __shared__ float s_val[TEAM][NJ * 64];
     __shared__ float s_den[TEAM];
     const uint32_t count = *a.count_ptr;
@@ -149,7 +151,7 @@ __global__ __launch_bounds__(TEAM * 64) void k_gat_scatter_long(GatArgs a) {
         for (uint32_t base = 64u * wave; base < m.y; base += 64u * TEAM) {
             const uint32_t e = base + lane;
             const uint32_t my_u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
-            dsum += gat_block<NJ, G>(a, my_u, e < m.y, recompute, t_v, acc);
+            dsum += recompute ? gat_block<NJ, GR, true>(a, my_u, e < m.y, t_v, acc) : gat_block<NJ, G, false>(a, my_u, e < m.y, t_v, acc);
         }
         dsum = gat_wave_sum(dsum);
 #pragma unroll

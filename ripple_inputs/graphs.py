@@ -159,6 +159,11 @@ CONFIGS = [
            (100, 256, 256, 256, 47), "f32", (1000,), _MIX3, 4096, stream_seed=12360),
     Config("reddit_sage_mean", 232_965, 114_615_892, 2.3, 0.0002, 602, "sage_mean",
            (602, 256, 256, 41), "f32", (100, 1000), _MIX3, 4096, stream_seed=12361),
+    # the paper's GA-A workload (graph attention)
+    Config("sparse_gat", 169_343, 1_166_243, 2.1, 0.01, 128, "gat",
+           (128, 256, 256, 40), "f32", (1000,), _MIX3, 4096, stream_seed=12362),
+    Config("dense_gat", 2_449_029, 123_718_280, 2.3, 0.0002, 100, "gat",
+           (100, 256, 256, 47), "f32", (10000,), _MIX3, 4096, stream_seed=12363),
 ]
 
 

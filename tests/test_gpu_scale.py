@@ -69,6 +69,23 @@ def test_sparse_gcn_max():
         pair.close()
 
 
+def test_sparse_graph_attention():
+    """The paper's GA-A workload on the sparse graph: all rows of all layers after every batch."""
+    cfg = ri.get_config("sparse_gat")
+    print("case", cfg.name, flush=True)
+    pair, stream = config_pair(cfg)
+    try:
+        pair.check_embeddings()
+        for b, bs in enumerate([10, 1000, 1000]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload)
+        pair.check_graph()
+        pair.check_aggregates()
+    finally:
+        pair.close()
+
+
 def test_sparse_four_layers():
     """Four hops (the paper's deeper models, Sec. 6.3.2): all rows of all five layers after every batch."""
     cfg = ri.get_config("sparse_sage_mean_4layer")
@@ -227,7 +244,7 @@ def test_dense_configs_sampled_rows(dense_graph, name):
         rp.ripple_destroy(ctx)
 
 
-@pytest.mark.parametrize("name,bs", [("dense_sage_mean_4layer", 1000), ("reddit_sage_mean", 1000)])
+@pytest.mark.parametrize("name,bs", [("dense_sage_mean_4layer", 1000), ("reddit_sage_mean", 1000), ("dense_gat", 10000)])
 def test_deep_and_reddit_shaped_configs(dense_graph, name, bs):
     """Four layers on the dense graph, and a graph of Reddit's shape (average in-degree 492, 602
     features). Affected sets are compared in full. At this density the in-neighbourhood cone of even
