@@ -144,6 +144,40 @@ def test_drift_over_1000_batches_tiny():
         pair.close()
 
 
+@pytest.mark.parametrize("kind", ["gat", "gcn_max", "gcn_wsum"])
+def test_drift_of_the_other_aggregators(kind):
+    """400 consecutive batches on a small graph. Attention numerators and denominators and weighted sums are
+    patched with differences batch after batch (rounding could pile up); max / min aggregates are exact
+    selections and must not drift at all."""
+    cfg = ri.get_config("tiny_gcn_sum")
+    src, dst, out_law, in_law = ri.chung_lu_graph(cfg.n, cfg.e, cfg.gamma, cfg.top_share, cfg.graph_seed)
+    feats = ri.features(cfg.n, cfg.d0, cfg.feat_seed)
+    model = ri.make_model(kind, cfg.widths, cfg.weight_seed)
+    weighted = kind == "gcn_wsum"
+    weights = ri.edge_weights(len(src), 7) if weighted else None
+    from harness import Pair
+    print("case drift", kind, flush=True)
+    pair = Pair(cfg.n, cfg.vertex_capacity, src, dst, feats, model, edge_capacity=cfg.edge_capacity, weights=weights)
+    mix = {"edge_add": 0.39, "edge_del": 0.29, "feat": 0.3, "vadd": 0.01, "vdel": 0.01}
+    stream = ri.UpdateStream(cfg.n, cfg.vertex_capacity, src, dst, out_law, in_law, cfg.d0, mix, 99, weighted=weighted)
+    try:
+        worst = 0.0
+        for b in range(1, 401):
+            ops, payload, _ = stream.next_batch(60)
+            rec = pair.ora.apply_batch(ops, payload)
+            res = rp.ripple_apply_updates(pair.ctx, ops, payload)
+            assert res.n_applied == int(rec.accepted.sum())
+            if b in (1, 10, 100, 400):
+                errs, _ = pair.check_embeddings()
+                worst = max(worst, max(errs))
+                print(f"  batch {b}: max rel err per layer {['%.2e' % e for e in errs]}", flush=True)
+        pair.check_graph()
+        pair.check_aggregates()
+        assert worst <= TOL["f32"]
+    finally:
+        pair.close()
+
+
 def test_drift_bf16_store_sparse_graph():
     """bfloat16 embeddings with float32 cached sums: error stays bounded over many batches."""
     cfg = ri.get_config("sparse_gin_sum")            # the graph and stream (with vertex operations) of config 3
