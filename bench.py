@@ -142,6 +142,8 @@ def main():
     ap.add_argument("--scatter-mode", type=int, default=0)
     ap.add_argument("--pull-ratio", type=int, default=0)
     ap.add_argument("--deterministic", action="store_true", help="bit-reproducible aggregation (RIPPLE_OPT_DETERMINISTIC)")
+    ap.add_argument("--split-mfma", type=int, default=-1,
+                    help="fp32 storage: 1 = products on the bf16 matrix cores with operands split in three, 0 = fp32 matrix path")
     ap.add_argument("--bf16-mfma", type=int, default=1, help="bf16 storage only: 0 = multiply on the fp32 matrix path")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="leave the library's per-kernel HIP events off (no roofline object; lowest latency)")
@@ -172,6 +174,8 @@ def main():
                                    edge_capacity=cfg.edge_capacity)
     if args.deterministic:
         rp.ripple_set_option(ctx, rp.OPT_DETERMINISTIC, 1)
+    if args.split_mfma >= 0:
+        rp.ripple_set_option(ctx, rp.OPT_SPLIT_MFMA, args.split_mfma)
     rp.ripple_load_model(ctx, model)
     rp.ripple_full_infer(ctx)
     log(f"[bench] graph store built and bootstrap inference done in {time.time() - t0:.1f}s")

@@ -266,6 +266,7 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
     for (uint32_t l = 0; l < c->L; ++l) {
         LayerDev &ly = c->layers[l];
         void *w[] = {ly.W0, ly.b0, ly.W1, ly.b1, ly.W0h, ly.W1h, ly.bzero, (ly.Wn != ly.W0) ? ly.Wn : nullptr, ly.PS,
+                     ly.W0s, ly.W1s, (ly.Wns != ly.W0s) ? ly.Wns : nullptr,
                      ly.att, ly.P, ly.ssrc, ly.sdst, ly.den};
         for (void *p : w)
             if (p) hipFree(p);
@@ -287,11 +288,33 @@ extern "C" const char *ripple_last_error(const ripple_ctx *c) { return c ? c->er
 // ---------------------------------------------------------------------------------
 static uint32_t pad_n(uint32_t n) { return n <= 64 ? 64u : (n <= 128 ? 128u : rp_round_up(n, 256)); }
 
+// planes (optional): the padded matrix as three transposed bf16 matrices [Npad x Kpad] whose sum is W exactly
+// (leading, middle and last 8 significant bits of every weight), for the split products on the bf16 matrix cores
 static ripple_status upload_padded(ripple_ctx *c, const float *w, const float *b, uint32_t K, uint32_t N,
-                                   uint32_t Kpad, uint32_t Npad, float **W_d, float **b_d) {
+                                   uint32_t Kpad, uint32_t Npad, float **W_d, float **b_d,
+                                   unsigned short **planes = nullptr) {
     std::vector<float> wp((size_t)Kpad * Npad, 0.0f), bp(Npad, 0.0f);
     for (uint32_t k = 0; k < K; ++k) memcpy(&wp[(size_t)k * Npad], &w[(size_t)k * N], (size_t)N * 4);
     memcpy(bp.data(), b, (size_t)N * 4);
+    if (planes) {
+        const size_t plane = (size_t)Npad * Kpad;
+        std::vector<uint16_t> pl(3 * plane, 0);
+        for (uint32_t k = 0; k < K; ++k)
+            for (uint32_t j = 0; j < N; ++j) {
+                float x = wp[(size_t)k * Npad + j];
+                for (int p = 0; p < 3; ++p) {
+                    uint32_t bits;
+                    memcpy(&bits, &x, 4);
+                    bits &= 0xFFFF0000u;
+                    float head;
+                    memcpy(&head, &bits, 4);
+                    pl[p * plane + (size_t)j * Kpad + k] = (uint16_t)(bits >> 16);
+                    x -= head;                         // exact
+                }
+            }
+        RP_TRY(dev_alloc(c, planes, pl.size(), false));
+        RP_HIP(c, hipMemcpy(*planes, pl.data(), pl.size() * 2, hipMemcpyHostToDevice));
+    }
     RP_TRY(dev_alloc(c, W_d, wp.size(), false));
     RP_TRY(dev_alloc(c, b_d, bp.size(), false));
     RP_HIP(c, hipMemcpy(*W_d, wp.data(), wp.size() * 4, hipMemcpyHostToDevice));
@@ -337,7 +360,8 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
         uint32_t n0 = s.d_hidden ? s.d_hidden : s.d_out;
         ly.K0pad = rp_round_up(ly.K, 32);
         ly.N0pad = pad_n(n0);
-        RP_TRY(upload_padded(c, s.W0, s.b0, ly.K, n0, ly.K0pad, ly.N0pad, &ly.W0, &ly.b0));
+        const bool split = c->store == RIPPLE_STORE_F32 && c->opt_split;
+        RP_TRY(upload_padded(c, s.W0, s.b0, ly.K, n0, ly.K0pad, ly.N0pad, &ly.W0, &ly.b0, split ? &ly.W0s : nullptr));
         if (c->store == RIPPLE_STORE_BF16) {               // transposed bf16 copy for the bf16 matrix cores
             std::vector<uint16_t> wt((size_t)ly.N0pad * ly.K0pad, 0);
             for (uint32_t k = 0; k < ly.K; ++k)
@@ -366,16 +390,19 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
             std::vector<float> zeros(ly.N0pad, 0.0f);
             if (s.self_mode == RIPPLE_SELF_CONCAT) {           // rows d_in .. 2 d_in - 1 of W0
                 RP_TRY(upload_padded(c, s.W0 + (size_t)s.d_in * s.d_out, zeros.data(), s.d_in, s.d_out,
-                                     rp_round_up(s.d_in, 32), ly.N0pad, &ly.Wn, &ly.bzero));
+                                     rp_round_up(s.d_in, 32), ly.N0pad, &ly.Wn, &ly.bzero, split ? &ly.Wns : nullptr));
+                ly.Wns_ld = rp_round_up(s.d_in, 32);
             } else {
                 ly.Wn = ly.W0;
+                ly.Wns = ly.W0s;
+                ly.Wns_ld = ly.K0pad;
                 RP_TRY(dev_alloc(c, &ly.bzero, (size_t)ly.N0pad, true));
             }
         }
         if (s.d_hidden) {
             ly.K1pad = rp_round_up(s.d_hidden, 32);
             ly.N1pad = pad_n(s.d_out);
-            RP_TRY(upload_padded(c, s.W1, s.b1, s.d_hidden, s.d_out, ly.K1pad, ly.N1pad, &ly.W1, &ly.b1));
+            RP_TRY(upload_padded(c, s.W1, s.b1, s.d_hidden, s.d_out, ly.K1pad, ly.N1pad, &ly.W1, &ly.b1, split ? &ly.W1s : nullptr));
         }
         c->d[l + 1] = s.d_out;
         c->dmax = std::max(c->dmax, s.d_out);
@@ -1097,6 +1124,10 @@ extern "C" ripple_status ripple_set_option(ripple_ctx *c, int option, int64_t va
     case RIPPLE_OPT_SELF_CACHE:
         if (c->state != 1) return fail(c, RIPPLE_ESTATE, "the self-projection cache is chosen before load_model");
         c->opt_selfcache = value ? 1 : 0;
+        return RIPPLE_OK;
+    case RIPPLE_OPT_SPLIT_MFMA:
+        if (c->state != 1) return fail(c, RIPPLE_ESTATE, "RIPPLE_OPT_SPLIT_MFMA must be set before load_model");
+        c->opt_split = value ? 1 : 0;
         return RIPPLE_OK;
     case RIPPLE_OPT_BF16_MFMA:
         c->opt_bf16_mfma = value ? 1 : 0;

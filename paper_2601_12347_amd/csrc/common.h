@@ -68,6 +68,9 @@ struct LayerDev {
     // attention layers: projected rows P[v] = H^{l-1}[v] W0 [n x d_out], scores a_src . P[v] and a_dst . P[v],
     // denominators of the softmax (the numerators are the layer's X rows); att = a_src then a_dst on the device
     float *att, *P, *ssrc, *sdst, *den;
+    // fp32 storage: W0, Wn, W1 as three transposed bf16 planes each (their sum is the matrix), or null
+    unsigned short *W0s, *Wns, *W1s;
+    uint32_t Wns_ld;                          // row stride of the Wn planes (those of W0: K0pad, of W1: K1pad)
 };
 
 struct PhaseTimer;
@@ -157,6 +160,7 @@ struct ripple_ctx {
     int opt_bf16_mfma = 1;                      // bf16 storage: multiply on the bf16 matrix cores
     int opt_project = 1;                        // allow project-first layers (read by load_model)
     int opt_selfcache = 1;                      // allow cached self projections (read by load_model)
+    int opt_split = 0;                          // fp32 storage: products on the bf16 matrix cores, operands split in three (read by load_model)
     int opt_deterministic = 0;                  // bit-reproducible aggregation (owner kernels, no float atomics)
     int opt_pull_ratio = 2;                     // pull when messages * width * ratio >= scanned in-edges
     ripple_stats stats;

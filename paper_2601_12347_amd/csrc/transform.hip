@@ -43,6 +43,8 @@ struct TArgs {
     const float *W;                // [Kpad x Npad], zero padded
     const float *bias;             // [Npad]
     const __hip_bfloat16 *Wt;      // bf16 copy of W, transposed [Npad x Kpad] (k contiguous), or null
+    const unsigned short *Ws;      // fp32 storage: W as three transposed bf16 planes (W = plane 0 + plane 1 + plane 2), or null
+    size_t ws_plane;               // elements per plane
     uint32_t wt_ld;                // its row stride
     uint32_t K, Kpad, N, Npad;
     int act;
@@ -851,6 +853,202 @@ static void launch_bf16(ripple_ctx *c, const TArgs &a, bool narrow, uint32_t row
     }
 }
 
+// fp32 embeddings on the bf16 matrix cores: every fp32 number is the exact sum of three bf16 numbers
+// (its leading 8 significant bits, the next 8, the last 8), so a product a b is the sum of nine bf16
+// products; the six largest (a1 b1, a1 b2, a2 b1, a2 b2, a1 b3, a3 b1) are kept, each exact in the
+// fp32 accumulator, and what is dropped is below 2^-24 |a b|. Six bf16 products cost 3/8 of one fp32
+// product on this chip (the bf16 rate is sixteen times the fp32 rate), which leaves the kernel bound by
+// the gathered rows rather than by the matrix cores. Rows are split as they enter LDS, the weights
+// come from three transposed bf16 planes made when the model is loaded.
+__device__ __forceinline__ void split3(float a, float &a1, float &a2, float &a3) {
+    a1 = __uint_as_float(__float_as_uint(a) & 0xFFFF0000u);
+    const float r = a - a1;                                   // exact: the low 16 bits of the significand
+    a2 = __uint_as_float(__float_as_uint(r) & 0xFFFF0000u);
+    a3 = r - a2;                                              // exact, at most 8 significant bits
+}
+__device__ __forceinline__ uint32_t pack_hi16(float lo, float hi) {       // the two values are bf16-representable
+    return (__float_as_uint(lo) >> 16) | (__float_as_uint(hi) & 0xFFFF0000u);
+}
+
+template <int WAVES_M, int WAVES_N, int TM, int TN, int STAGES, int MODE>
+__global__ __launch_bounds__(256, 2) void k_transform_split(TArgs a) {
+    constexpr int STORE = 0;
+    constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
+    constexpr int NA = BM / 32, NB = BN / 64;              // per thread per slice: float4 of A, 16-byte chunks of B per plane
+    constexpr bool TWO = (MODE == 2);
+    constexpr int A_BYTES = BM * TB_LD * 2, B_BYTES = BN * TB_LD * 2, C_BYTES = BM * (BN + 4) * 4;
+    constexpr int PB = 3;                                  // weight planes
+    constexpr int S_BYTES = (3 * A_BYTES + PB * B_BYTES > C_BYTES) ? 3 * A_BYTES + PB * B_BYTES : C_BYTES;
+    static_assert(A_BYTES % 16 == 0 && B_BYTES % 16 == 0, "alignment of the planes");
+    __shared__ __attribute__((aligned(16))) char smem[S_BYTES];   // three A and three B planes; reused by the staged epilogue
+    typedef unsigned short (*plane_t)[TB_LD];
+    plane_t As[3], Bs[PB];
+#pragma unroll
+    for (int p = 0; p < 3; ++p) As[p] = (plane_t)(smem + p * A_BYTES);
+#pragma unroll
+    for (int p = 0; p < PB; ++p) Bs[p] = (plane_t)(smem + 3 * A_BYTES + p * B_BYTES);
+    __shared__ uint32_t s_vtx[BM];
+    __shared__ float s_scale[BM];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WAVES_N, wn = wave % WAVES_N;
+    const uint32_t count = *a.count_ptr;
+    const uint32_t n_tiles = (count + BM - 1) / BM;
+    const uint32_t n0 = blockIdx.y * BN;
+
+    for (uint32_t tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const uint32_t row0 = tile * BM;
+        __syncthreads();
+        for (int r = tid; r < BM; r += 256) {
+            uint32_t slot = row0 + r;
+            uint32_t v = 0;
+            float sc = 1.0f;
+            if (slot < count) {
+                v = a.list[slot];
+                if (a.mean) {
+                    uint32_t deg = a.in_meta[v].y;
+                    sc = 1.0f / (float)(deg > 1u ? deg : 1u);
+                }
+            }
+            s_vtx[r] = v;
+            s_scale[r] = sc;
+        }
+        __syncthreads();
+
+        floatx16 acc[TM][TN];
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[i][j][r] = 0.0f;
+
+        uint32_t my_v[NA], my_slot[NA];
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            const int r = (tid + i * 256) / (T_BK / 4);
+            my_v[i] = s_vtx[r];
+            my_slot[i] = min(row0 + r, count - 1u);
+        }
+        const uint32_t c4a = (tid % (T_BK / 4)) * 4;
+
+        floatx4 ra[STAGES][NA], rq[TWO ? STAGES : 1][TWO ? NA : 1];
+        uintx4 rb[PB][NB];
+#pragma unroll
+        for (int p = 0; p < PB; ++p)
+#pragma unroll
+            for (int i = 0; i < NB; ++i) {                 // weights first, as in every step of the loop
+                const int idx = tid + i * 256;
+                const int n = idx / 4, kc = (idx % 4) * 8;
+                rb[p][i] = *(const uintx4 *)(a.Ws + p * a.ws_plane + (size_t)(n0 + n) * a.wt_ld + kc);
+            }
+#pragma unroll
+        for (int st = 0; st < STAGES; ++st)
+#pragma unroll
+            for (int i = 0; i < NA; ++i) {
+                floatx4 q = (floatx4)(0.0f);
+                fetch_raw<MODE, STORE>(a, my_v[i], my_slot[i], (uint32_t)st * T_BK + c4a, ra[st][i], q);
+                if constexpr (TWO) rq[st][i] = q;
+            }
+        __builtin_amdgcn_sched_barrier(0);
+
+        for (uint32_t kbase = 0; kbase < a.Kpad; kbase += STAGES * T_BK) {    // staging registers rotate by unrolling
+#pragma unroll
+          for (int s = 0; s < STAGES; ++s) {
+            const uint32_t k0 = kbase + s * T_BK;
+            if (k0 >= a.Kpad) break;
+            __syncthreads();
+#pragma unroll
+            for (int i = 0; i < NA; ++i) {
+                const int r = (tid + i * 256) / (T_BK / 4);
+                floatx4 q = (floatx4)(0.0f);
+                if constexpr (TWO) q = rq[s][i];
+                const floatx4 val = finish_raw<MODE, STORE>(a, ra[s][i], q, k0 + c4a, s_scale[r]);
+                float x1[4], x2[4], x3[4];
+                split3(val.x, x1[0], x2[0], x3[0]);
+                split3(val.y, x1[1], x2[1], x3[1]);
+                split3(val.z, x1[2], x2[2], x3[2]);
+                split3(val.w, x1[3], x2[3], x3[3]);
+                *(uint2 *)&As[0][r][c4a] = make_uint2(pack_hi16(x1[0], x1[1]), pack_hi16(x1[2], x1[3]));
+                *(uint2 *)&As[1][r][c4a] = make_uint2(pack_hi16(x2[0], x2[1]), pack_hi16(x2[2], x2[3]));
+                *(uint2 *)&As[2][r][c4a] = make_uint2(pack_hi16(x3[0], x3[1]), pack_hi16(x3[2], x3[3]));
+            }
+#pragma unroll
+            for (int p = 0; p < PB; ++p)
+#pragma unroll
+                for (int i = 0; i < NB; ++i) {
+                    const int idx = tid + i * 256;
+                    const int n = idx / 4, kc = (idx % 4) * 8;
+                    *(uintx4 *)&Bs[p][n][kc] = rb[p][i];
+                }
+            __syncthreads();
+            {
+                const uint32_t kb = min(k0 + T_BK, a.Kpad - T_BK);
+#pragma unroll
+                for (int p = 0; p < PB; ++p)
+#pragma unroll
+                    for (int i = 0; i < NB; ++i) {
+                        const int idx = tid + i * 256;
+                        const int n = idx / 4, kc = (idx % 4) * 8;
+                        rb[p][i] = *(const uintx4 *)(a.Ws + p * a.ws_plane + (size_t)(n0 + n) * a.wt_ld + kb + kc);
+                    }
+            }
+            {
+                const uint32_t kn = k0 + STAGES * T_BK + c4a;
+#pragma unroll
+                for (int i = 0; i < NA; ++i) {
+                    floatx4 q = (floatx4)(0.0f);
+                    fetch_raw<MODE, STORE>(a, my_v[i], my_slot[i], kn, ra[s][i], q);
+                    if constexpr (TWO) rq[s][i] = q;
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);             // requests stay above the matrix-core work
+#pragma unroll
+            for (int kh = 0; kh < 2; ++kh) {
+                const int ko = kh * 16 + (lane >> 5) * 8;
+                bf16x8 av[3][TM];
+#pragma unroll
+                for (int p = 0; p < 3; ++p)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+                        av[p][i] = __builtin_bit_cast(bf16x8, *(const uintx4 *)&As[p][(wm * TM + i) * 32 + (lane & 31)][ko]);
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {               // one column block's three planes at a time (registers)
+                    bf16x8 bv[PB];
+#pragma unroll
+                    for (int p = 0; p < PB; ++p)
+                        bv[p] = __builtin_bit_cast(bf16x8, *(const uintx4 *)&Bs[p][(wn * TN + j) * 32 + (lane & 31)][ko]);
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) {           // smallest terms first
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[2][i], bv[0], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[0][i], bv[2], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[1][i], bv[1], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[1][i], bv[0], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[0][i], bv[1], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av[0][i], bv[0], acc[i][j], 0, 0, 0);
+                    }
+                }
+            }
+          }
+        }
+        epilogue_staged<TM, TN, BM, BN, false>(a, acc, (float *)smem, s_vtx, s_scale, row0, count, n0, wm, wn, tid);
+    }
+}
+
+template <int MODE>
+static void launch_split(ripple_ctx *c, const TArgs &a, bool narrow, uint32_t rows_hint) {
+    if (a.Npad >= 256 && !narrow) {
+        hipLaunchKernelGGL((k_transform_split<1, 4, 2, 2, 3, MODE>), dim3(tile_grid(c, rows_hint, 64, c->n_cu * 2), a.Npad / 256),
+                           dim3(256), 0, c->stream, a);
+    } else if (a.Npad == 128 && !narrow) {
+        hipLaunchKernelGGL((k_transform_split<2, 2, 2, 2, 3, MODE>), dim3(tile_grid(c, rows_hint, 128, c->n_cu * 2), 1), dim3(256), 0,
+                           c->stream, a);
+    } else {
+        hipLaunchKernelGGL((k_transform_split<4, 1, 1, 2, 3, MODE>),
+                           dim3(tile_grid(c, rows_hint, 128, narrow ? c->n_cu : c->n_cu * 2), a.Npad / 64), dim3(256), 0, c->stream, a);
+    }
+}
+
 template <int MODE, int STORE>
 static void launch_fast(ripple_ctx *c, const TArgs &a, bool narrow, uint32_t rows_hint) {
     if (a.Npad >= 256 && !narrow) {
@@ -878,6 +1076,7 @@ static void launch_t(ripple_ctx *c, const TArgs &a, bool vec_ok, uint32_t rows_h
     case M:                                                  \
         if (a.store && a.Wt) launch_bf16<M>(c, a, narrow, rows_hint);   \
         else if (a.store) launch_fast<M, 1>(c, a, narrow, rows_hint);   \
+        else if (a.Ws) launch_split<M>(c, a, narrow, rows_hint);        \
         else launch_fast<M, 0>(c, a, narrow, rows_hint);                \
         break;
     switch (a.a_mode) {
@@ -887,6 +1086,7 @@ static void launch_t(ripple_ctx *c, const TArgs &a, bool vec_ok, uint32_t rows_h
         T_CASE(4)
     default:
         if (a.store) launch_fast<3, 1>(c, a, narrow, rows_hint);   // compact fp32 rows; the storage type only shapes the epilogue
+        else if (a.Ws) launch_split<3>(c, a, narrow, rows_hint);
         else launch_fast<3, 0>(c, a, narrow, rows_hint);
         break;
     }
@@ -922,6 +1122,8 @@ static TArgs base_args(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
     a.W = ly.W0;
     a.Wt = (c->store && c->opt_bf16_mfma) ? ly.W0h : nullptr;   // bf16 storage: bf16 matrix cores
     a.wt_ld = ly.K0pad;
+    a.Ws = ly.W0s;                                 // fp32 storage with split products, else null
+    a.ws_plane = (size_t)ly.N0pad * ly.K0pad;
     a.bias = ly.b0;
     a.K = ly.K;
     a.Kpad = ly.K0pad;
@@ -940,6 +1142,9 @@ void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
     a.mean = 0;
     a.W = ly.Wn;
     a.Wt = nullptr;                                // deltas of bf16 values need more than 8 mantissa bits: fp32 path
+    a.Ws = ly.Wns;
+    a.wt_ld = ly.Wns_ld;
+    a.ws_plane = (size_t)ly.N0pad * ly.Wns_ld;
     a.bias = ly.bzero;
     a.K = ly.d_in;
     a.Kpad = rp_round_up(ly.d_in, 32);
@@ -1028,6 +1233,9 @@ void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const 
         a.a_mode = 0;
         a.W = ly.Wn;
         a.Wt = nullptr;
+        a.Ws = ly.Wns;
+        a.wt_ld = ly.Wns_ld;
+        a.ws_plane = (size_t)ly.N0pad * ly.Wns_ld;
         a.K = ly.d_in;
         a.Kpad = rp_round_up(ly.d_in, 32);
         a.addend = ly.PS;
@@ -1058,6 +1266,9 @@ void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const 
     s2.mean = 0;
     s2.W = ly.W1;
     s2.Wt = nullptr;
+    s2.Ws = ly.W1s;
+    s2.wt_ld = ly.K1pad;
+    s2.ws_plane = (size_t)ly.N1pad * ly.K1pad;
     s2.bias = ly.b1;
     s2.K = ly.d_hidden;
     s2.Kpad = ly.K1pad;

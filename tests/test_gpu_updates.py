@@ -557,3 +557,30 @@ def test_attention_with_hub_rows():
         pair.check_aggregates()
     finally:
         pair.close()
+
+
+@pytest.mark.parametrize("kind,widths", [("sage_mean", (100, 256, 256, 47)), ("gin_sum", (32, 64, 40, 10)), ("gat", (64, 128, 16)),
+                                         ("gcn_sum", (128, 130, 70))])
+def test_split_products_on_the_bf16_matrix_cores(kind, widths):
+    """fp32 operands split exactly into three bf16 numbers, six partial products per product: the rows must
+    match the oracle like the fp32 matrix path does, and the two paths must agree far below the tolerance."""
+    print("case split products", kind, widths, flush=True)
+    pair, graph = make_pair(n=3000, e=30000, d0=widths[0], kind=kind, widths=widths, seed=201, slack=128, split=True)
+    twin, _ = make_pair(n=3000, e=30000, d0=widths[0], kind=kind, widths=widths, seed=201, slack=128, split=False)
+    stream = make_stream(pair, graph, MIXV, 203)
+    try:
+        pair.check_embeddings()
+        for b, bs in enumerate([4, 200, 900]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload)
+            rp.ripple_apply_updates(twin.ctx, ops, payload)
+            for l in range(1, pair.L + 1):
+                a, b2 = pair.gpu_layer(l).astype(np.float64), twin.gpu_layer(l).astype(np.float64)
+                scale = np.abs(b2).max()
+                assert np.abs(a - b2).max() <= 2e-6 * scale, (l, np.abs(a - b2).max() / scale)
+                print("   layer", l, "split vs fp32 path: %.2e" % (np.abs(a - b2).max() / scale), flush=True)
+        pair.check_aggregates()
+    finally:
+        pair.close()
+        twin.close()
