@@ -584,3 +584,67 @@ def test_split_products_on_the_bf16_matrix_cores(kind, widths):
     finally:
         pair.close()
         twin.close()
+
+
+@pytest.mark.parametrize("kind,mode", [("gcn_sum", 1), ("gcn_sum", 2), ("sage_mean", 0), ("gin_sum", 0), ("gcn_max", 0),
+                                       ("gat", 0), ("gcn_wsum", 0)])
+def test_maximum_row_widths(kind, mode):
+    """Rows of 1024 floats (the largest the library takes) and of 400: the 16- and 8-column-block
+    instantiations of every scatter kernel, products with K up to 2048 and N above 256, hidden width 1024."""
+    print("case maximum widths", kind, mode, flush=True)
+    widths = (1024, 400, 1024)
+    weighted = kind == "gcn_wsum"
+    pair, graph = make_pair(n=700, e=6000, d0=widths[0], kind=kind, widths=widths, seed=221, slack=64, top_share=0.08,
+                            weighted=weighted)
+    if kind == "gin_sum":
+        assert pair.model[0]["d_hidden"] == 256
+    stream = make_stream(pair, graph, MIXV, 223, weighted=weighted)
+    try:
+        rp.ripple_set_option(pair.ctx, rp.OPT_SCATTER_MODE, mode)
+        pair.check_embeddings()
+        for b, bs in enumerate([3, 120, 400]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload)
+        pair.check_aggregates()
+        pair.check_graph()
+    finally:
+        pair.close()
+
+
+def test_gin_with_the_widest_hidden_layer():
+    print("case gin hidden 1024", flush=True)
+    src, dst, out_law, in_law = ri.chung_lu_graph(600, 5000, 2.1, 0.05, 231)
+    feats = ri.features(600, 48, 232)
+    model = ri.make_model("gin_sum", (48, 64, 12), 233)
+    rng = np.random.default_rng(234)
+    for lay in model:                                  # widen the inner layer to the limit
+        lay["d_hidden"] = 1024
+        lay["W0"], lay["b0"] = ri.glorot(rng, lay["d_in"], 1024), rng.uniform(-0.1, 0.1, 1024).astype(np.float32)
+        lay["W1"] = ri.glorot(rng, 1024, lay["d_out"])
+    from harness import Pair
+    pair = Pair(600, 664, src, dst, feats, model)
+    stream = ri.UpdateStream(600, 664, src, dst, out_law, in_law, 48, MIXV, 235)
+    try:
+        pair.check_embeddings()
+        for bs in (5, 200):
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload)
+    finally:
+        pair.close()
+
+
+def test_maximum_row_widths_deterministic_mode():
+    print("case maximum widths, deterministic", flush=True)
+    widths = (1024, 400, 1024)
+    pair, graph = make_pair(n=700, e=6000, d0=widths[0], kind="sage_mean", widths=widths, seed=241, slack=64, top_share=0.08,
+                            deterministic=True)
+    stream = make_stream(pair, graph, MIXV, 243)
+    try:
+        pair.check_embeddings()
+        for bs in (3, 300):
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload)
+        pair.check_aggregates()
+    finally:
+        pair.close()
