@@ -648,3 +648,52 @@ def test_maximum_row_widths_deterministic_mode():
         pair.check_aggregates()
     finally:
         pair.close()
+
+
+@pytest.mark.parametrize("kind", ["gcn_max", "gcn_min", "gat", "gcn_wsum", "gcn_mean", "sage_max"])
+def test_degenerate_neighbourhoods(kind):
+    """A graph without any edge at the start, a vertex that gains its first and loses its last
+    in-neighbour, self-loops, an identical feature rewrite, an empty batch, and a batch in which every
+    operation is rejected: the cases where an aggregate is empty, a denominator is zero or nothing moves."""
+    print("case degenerate", kind, flush=True)
+    n, d0 = 40, 6
+    weighted = kind == "gcn_wsum"
+    feats = ri.features(n, d0, 251)
+    model = ri.make_model(kind, (d0, 9, 5), 252)
+    from harness import Pair
+    none = np.zeros(0, dtype=np.uint32)
+    pair = Pair(n, n + 8, none, none, feats, model, weights=np.zeros(0, dtype=np.float32) if weighted else None)
+
+    def w(x):                                           # weight word of an EDGE_ADD on a weighted graph
+        return int(np.array([x], dtype=np.float32).view(np.uint32)[0]) if weighted else 0
+    try:
+        pair.check_embeddings()                         # every aggregate is empty
+        steps = [
+            [(ri.OP_EDGE_ADD, 1, 0, w(0.5))],                                   # first in-neighbour of 0
+            [(ri.OP_EDGE_ADD, 2, 0, w(1.5)), (ri.OP_EDGE_ADD, 0, 0, w(0.75)), (ri.OP_EDGE_ADD, 0, 3, w(1.0))],   # a self-loop
+            [(ri.OP_FEAT_UPDATE, 1, 0, 0), (ri.OP_FEAT_UPDATE, 0, 0, 1)],
+            [(ri.OP_EDGE_DEL, 1, 0, 0), (ri.OP_EDGE_DEL, 2, 0, 0)],             # only the self-loop feeds 0 now
+            [(ri.OP_EDGE_DEL, 0, 0, 0)],                                        # 0 loses its last in-neighbour
+            [(ri.OP_EDGE_DEL, 0, 0, 0), (ri.OP_EDGE_ADD, 0, 3, w(1.0)), (ri.OP_FEAT_UPDATE, n + 2, 0, 0),
+             (ri.OP_VERTEX_DEL, n + 3, 0, 0)],                                  # all rejected
+            [(ri.OP_VERTEX_ADD, n, 0, 0), (ri.OP_EDGE_ADD, n, 3, w(0.25)), (ri.OP_EDGE_ADD, 3, n, w(1.25))],
+            [(ri.OP_VERTEX_DEL, 3, 0, 0)],                                      # n and 0 lose their neighbour again
+        ]
+        rng = np.random.default_rng(253)
+        for i, ops in enumerate(steps):
+            print(" step", i, flush=True)
+            payload = rng.standard_normal((2, d0)).astype(np.float32)
+            res, rec, _ = pair.step(np.array(ops, dtype=np.uint32), payload)
+            if i == 5:
+                assert res.n_applied == 0 and res.n_rejected == 4
+            pair.check_aggregates()
+        same = pair.gpu_layer(0)[[0]].copy()            # a feature rewrite with the identical row
+        before = [pair.gpu_layer(l) for l in range(pair.L + 1)]
+        pair.step(np.array([(ri.OP_FEAT_UPDATE, 0, 0, 0)], dtype=np.uint32), same)
+        for l in range(pair.L + 1):
+            assert np.array_equal(before[l], pair.gpu_layer(l))
+        res = rp.ripple_apply_updates(pair.ctx, np.zeros((0, 4), np.uint32), None)
+        assert list(res.affected[: pair.L + 1]) == [0] * (pair.L + 1)
+        pair.check_graph()
+    finally:
+        pair.close()
