@@ -138,9 +138,10 @@ def test_tiny_config_batches():
         pair.close()
 
 
-def test_conflicting_operations_keep_array_order():
-    print("case conflicts", flush=True)
-    pair, graph = make_pair(n=200, e=900, d0=8, kind="sage_mean", widths=(8, 16, 6), seed=17)
+@pytest.mark.parametrize("kind", ["sage_mean", "gcn_max", "sage_max", "gat", "gin_sum"])
+def test_conflicting_operations_keep_array_order(kind):
+    print("case conflicts", kind, flush=True)
+    pair, graph = make_pair(n=200, e=900, d0=8, kind=kind, widths=(8, 16, 6), seed=17)
     src, dst = graph[0], graph[1]
     u, v = int(src[0]), int(dst[0])
     n = pair.n
