@@ -150,7 +150,7 @@ typedef enum {
                                      cache sum_u H[u] W_neigh instead of sum_u H[u] and scatter d_out-wide messages */
     RIPPLE_OPT_SELF_CACHE = 5,    /* 0/1 (default 1), before load_model: layers that concatenate the vertex's own embedding
                                      (one linear map) keep H[v] W_self per vertex, recomputed only where H[v] changed */
-    RIPPLE_OPT_SPLIT_MFMA = 7,    /* 0/1, before load_model, fp32 storage only: the dense products run on the bf16 matrix
+    RIPPLE_OPT_SPLIT_MFMA = 7,    /* 0/1 (default 0), before load_model, fp32 storage only: the dense products run on the bf16 matrix
                                      cores with every fp32 operand split exactly into three bf16 numbers and the six
                                      largest of the nine partial products kept (what is dropped is below 2^-24 of a
                                      product); results agree with the fp32 matrix path to rounding */

@@ -1,6 +1,7 @@
 """Parity at the benchmark configurations' real sizes, and drift over long
 update sequences (the library accumulates into cached sums; the oracle
 recomputes from scratch every time)."""
+import os
 import time
 
 import numpy as np
@@ -213,6 +214,35 @@ def dense_graph():
     return g
 
 
+def cone_check(ctx, ora, cfg, model, rec, sets, rng, pruned, t0):
+    """A sample of final-layer rows (affected ones, sinks of changed edges, updated vertices) recomputed
+    by the oracle through their in-neighbourhood cones and compared layer by layer."""
+    L = len(model)
+    # (the max / min oracle gathers every neighbour row explicitly: a smaller sample keeps it to seconds;
+    # rows the library pruned are sampled too and must equal the recomputation all the same)
+    k_any, k_sink, k_feat = (24, 8, 4) if pruned else (120, 40, 20)
+    targets = np.unique(np.concatenate([rng.choice(sets[L], size=k_any, replace=False),
+                                        np.asarray(sorted(rec.sinks))[:k_sink],
+                                        np.asarray(sorted(rec.feat))[:k_feat]]))
+    cone = oracle.recompute_rows(ora, model, targets)
+    print(f"  oracle cone {time.time() - t0:.0f}s rows per layer {[len(r) for r, _ in cone]}", flush=True)
+    tol = TOL[cfg.store]
+    worst = 0.0
+    for l in range(L + 1):
+        rows, want = cone[l]
+        if len(rows) > 200_000:                      # compare a slice of the huge lower layers
+            pick = rng.choice(len(rows), size=200_000, replace=False)
+            rows, want = rows[pick], want[pick]
+        got = rp.ripple_get_embeddings(ctx, l, cfg.widths[l], ids=rows.astype(np.uint32))
+        norm = np.abs(want).max(axis=1)
+        tau = norm.mean()
+        err = (np.abs(got - want).max(axis=1) / np.maximum(norm, tau)).max()
+        print(f"  layer {l}: {len(rows)} rows, max rel err {err:.2e}", flush=True)
+        assert err <= tol, (l, err)
+        worst = max(worst, err)
+    return worst
+
+
 @pytest.mark.parametrize("name", ["dense_sage_mean", "dense_gcn_sum_bf16", "dense_gcn_max"])
 def test_dense_configs_sampled_rows(dense_graph, name):
     """Full-size graph, the batch size the benchmark times; the oracle recomputes a sample of
@@ -254,26 +284,7 @@ def test_dense_configs_sampled_rows(dense_graph, name):
             else:
                 assert n == len(sets[l]) and np.array_equal(got.astype(np.int64), sets[l]), f"affected set {l}"
         rng = np.random.default_rng(5)
-        # (the max / min oracle gathers every neighbour row explicitly: a smaller sample keeps it to seconds;
-        # rows the library pruned are sampled too and must equal the recomputation all the same)
-        k_any, k_sink, k_feat = (24, 8, 4) if pruned else (120, 40, 20)
-        targets = np.unique(np.concatenate([rng.choice(sets[L], size=k_any, replace=False),
-                                            np.asarray(sorted(rec.sinks))[:k_sink],
-                                            np.asarray(sorted(rec.feat))[:k_feat]]))
-        cone = oracle.recompute_rows(ora, model, targets)
-        print(f"  oracle cone {time.time() - t0:.0f}s rows per layer {[len(r) for r, _ in cone]}", flush=True)
-        tol = TOL[cfg.store]
-        for l in range(L + 1):
-            rows, want = cone[l]
-            if len(rows) > 200_000:                      # compare a slice of the huge lower layers
-                pick = rng.choice(len(rows), size=200_000, replace=False)
-                rows, want = rows[pick], want[pick]
-            got = rp.ripple_get_embeddings(ctx, l, cfg.widths[l], ids=rows.astype(np.uint32))
-            norm = np.abs(want).max(axis=1)
-            tau = norm.mean()
-            err = (np.abs(got - want).max(axis=1) / np.maximum(norm, tau)).max()
-            print(f"  layer {l}: {len(rows)} rows, max rel err {err:.2e}", flush=True)
-            assert err <= tol, (l, err)
+        cone_check(ctx, ora, cfg, model, rec, sets, rng, pruned, t0)
     finally:
         rp.ripple_destroy(ctx)
 
@@ -336,5 +347,49 @@ def test_deep_and_reddit_shaped_configs(dense_graph, name, bs):
             print(f"  layer {l}: {len(rows)} rows from {len(need)} inputs, max rel err {err:.2e} {time.time() - t0:.0f}s",
                   flush=True)
             assert err <= TOL[cfg.store], (l, err)
+    finally:
+        rp.ripple_destroy(ctx)
+
+
+@pytest.mark.skipif(os.environ.get("RIPPLE_LONG_TESTS") != "1",
+                    reason="about ten minutes: 1,000 consecutive batches at full size; set RIPPLE_LONG_TESTS=1")
+def test_dense_bf16_1000_consecutive_batches(dense_graph):
+    """The fifth configuration as stated: 1,000 consecutive batches of 10,000 updates (2% vertex additions and
+    deletions) on the 2.45 M-vertex graph with bf16 storage. Counts are compared after every batch; at
+    batches 1, 10, 100 and 1,000 the affected sets are compared in full and sampled rows against the
+    oracle's recomputation, so drift of the cached sums would show."""
+    cfg = ri.get_config("dense_gcn_sum_bf16")
+    src, dst, out_law, in_law = dense_graph
+    feats = ri.features(cfg.n, cfg.d0, cfg.feat_seed)
+    model = ri.make_model(cfg.model, cfg.widths, cfg.weight_seed)
+    print("case long run", cfg.name, flush=True)
+    t0 = time.time()
+    ctx = rp.ripple_init_graph(cfg.n, cfg.vertex_capacity, src, dst, feats, store=cfg.store, edge_capacity=cfg.edge_capacity)
+    try:
+        rp.ripple_load_model(ctx, model)
+        rp.ripple_full_infer(ctx)
+        stream = ri.UpdateStream(cfg.n, cfg.vertex_capacity, src, dst, out_law, in_law, cfg.d0, cfg.mix, cfg.stream_seed)
+        ora = oracle.GraphState(cfg.n, cfg.vertex_capacity, src, dst, feats)
+        rng = np.random.default_rng(8)
+        lat, compactions = [], 0
+        for b in range(1, 1001):
+            ops, payload, _ = stream.next_batch(10000)
+            rec = ora.apply_batch(ops, payload)
+            t1 = time.perf_counter()
+            res = rp.ripple_apply_updates(ctx, ops, payload)
+            lat.append(time.perf_counter() - t1)
+            compactions += res.n_compactions
+            assert res.n_applied == int(rec.accepted.sum()) and res.n_edges == ora.n_edges()
+            assert res.n_alive == int(ora.alive.sum())
+            if b % 50 == 0:
+                print(f"  batch {b}: {time.time() - t0:.0f}s, median {np.median(lat) * 1e3:.2f} ms per batch (host buffers), "
+                      f"{compactions} compactions", flush=True)
+            if b in (1, 10, 100, 1000):
+                sets = oracle.affected_sets(ora, rec, model)
+                for l in range(len(model) + 1):
+                    got, n = rp.ripple_get_affected(ctx, l, cfg.vertex_capacity)
+                    assert n == len(sets[l]) and np.array_equal(got.astype(np.int64), sets[l]), f"affected set {l}"
+                print(f"  batch {b}: sets {[len(x) for x in sets]}", flush=True)
+                cone_check(ctx, ora, cfg, model, rec, sets, rng, False, t0)
     finally:
         rp.ripple_destroy(ctx)
