@@ -273,7 +273,7 @@ def main():
             roofline = {"kernel": dom, "bound": "hbm", "achieved": k["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
                         "frac": k["hbm_frac"], "traffic": None}
     measured = MEASURED_TRAFFIC_BYTES.get((cfg.name, bs), {})
-    if roofline and dom in measured and args.scatter_mode == 0 and not args.deterministic:
+    if roofline and dom in measured and args.scatter_mode == 0 and not args.deterministic and args.split_mfma <= 0:
         roofline["traffic"] = measured[dom]                 # bytes per launch; traffic / ms_per_launch is the HBM rate
         roofline["traffic_GBps"] = measured[dom] / (kernels[dom]["ms_per_launch"] * 1e-3) / 1e9
     lat_ms = np.array(lat) * 1e3
