@@ -244,6 +244,16 @@ ripple_status ripple_compact(ripple_ctx *ctx);
 ripple_status ripple_set_option(ripple_ctx *ctx, int option, int64_t value);
 ripple_status ripple_get_stats(ripple_ctx *ctx, ripple_stats *out, int reset);
 
+/* Host only, no GPU and no context needed: how ripple_apply_updates cuts a batch (host array) into pieces
+ * whose operations do not depend on one another, so that each piece can be applied in parallel with
+ * the result of applying it in array order (operations of a batch take effect in array order; the
+ * paper batches updates and applies them, Sec. 3.1, without saying more). piece_end (host, room for cap
+ * entries) receives, per piece, the index one past its last operation; *n_pieces the number of pieces
+ * even when it exceeds cap. An operation with an unknown kind, a vertex id >= vertex_capacity or a
+ * payload row >= n_feat_rows makes the call return RIPPLE_EINVAL, as it does in ripple_apply_updates. */
+ripple_status ripple_plan_batch(const ripple_update *ops, uint32_t n_ops, uint32_t vertex_capacity,
+                                uint32_t n_feat_rows, uint32_t *piece_end, uint32_t cap, uint32_t *n_pieces);
+
 void ripple_destroy(ripple_ctx *ctx);
 const char *ripple_last_error(const ripple_ctx *ctx);   /* never NULL; "" when ctx is NULL */
 

@@ -31,7 +31,7 @@ STORE = {"f32": 0, "bf16": 1}
 
 EXPORTS = ["ripple_init_graph", "ripple_init_graph_weighted", "ripple_load_model", "ripple_full_infer", "ripple_apply_updates",
            "ripple_get_embeddings", "ripple_get_aggregates", "ripple_get_layer_info", "ripple_get_affected", "ripple_export_edges",
-           "ripple_get_degrees", "ripple_compact", "ripple_set_option", "ripple_get_stats",
+           "ripple_get_degrees", "ripple_compact", "ripple_set_option", "ripple_get_stats", "ripple_plan_batch",
            "ripple_destroy", "ripple_last_error"]
 
 
@@ -104,6 +104,7 @@ def load_library():
     lib.ripple_compact.argtypes = [vp]
     lib.ripple_set_option.argtypes = [vp, C.c_int, C.c_int64]
     lib.ripple_get_stats.argtypes = [vp, C.POINTER(Stats), C.c_int]
+    lib.ripple_plan_batch.argtypes = [vp, u32, u32, u32, vp, u32, C.POINTER(u32)]
     lib.ripple_destroy.argtypes = [vp]
     lib.ripple_destroy.restype = None
     lib.ripple_last_error.argtypes = [vp]
@@ -288,6 +289,18 @@ def ripple_get_stats(ctx, reset=False):
     st = Stats()
     _check(ctx, load_library().ripple_get_stats(ctx, C.byref(st), 1 if reset else 0))
     return st
+
+
+def ripple_plan_batch(ops, vertex_capacity, n_feat_rows):
+    """Ends (exclusive) of the conflict-free pieces ripple_apply_updates would cut `ops` into; host only."""
+    ops = np.ascontiguousarray(ops, dtype=np.uint32).reshape(-1, 4)
+    ends = np.zeros(max(len(ops), 1), dtype=np.uint32)
+    n = C.c_uint32(0)
+    rc = load_library().ripple_plan_batch(_ptr(ops) if len(ops) else None, len(ops), int(vertex_capacity),
+                                          int(n_feat_rows), _ptr(ends), len(ends), C.byref(n))
+    if rc != RIPPLE_OK:
+        raise RippleError(rc, "ripple_plan_batch")
+    return ends[: n.value].tolist()
 
 
 def ripple_destroy(ctx):

@@ -599,6 +599,32 @@ static void split_batch(const ripple_update *ops, uint32_t n, TouchTable &tt, st
     if (cur.end > cur.begin || out.empty()) out.push_back(cur);
 }
 
+static bool ops_in_range(const ripple_update *ops, uint32_t n_ops, uint32_t n_cap, uint32_t n_feat_rows) {
+    for (uint32_t i = 0; i < n_ops; ++i) {
+        const ripple_update &op = ops[i];
+        bool bad = op.kind > RIPPLE_FEAT_UPDATE || op.u >= n_cap;
+        if (!bad && op.kind <= RIPPLE_EDGE_DEL) bad = op.v >= n_cap;
+        if (!bad && (op.kind == RIPPLE_VERTEX_ADD || op.kind == RIPPLE_FEAT_UPDATE)) bad = op.feat_row >= n_feat_rows;
+        if (bad) return false;
+    }
+    return true;
+}
+
+extern "C" ripple_status ripple_plan_batch(const ripple_update *ops, uint32_t n_ops, uint32_t vertex_capacity,
+                                           uint32_t n_feat_rows, uint32_t *piece_end, uint32_t cap, uint32_t *n_pieces) {
+    if ((n_ops && !ops) || !n_pieces || (cap && !piece_end)) return RIPPLE_EINVAL;
+    if (!ops_in_range(ops, n_ops, vertex_capacity, n_feat_rows)) return RIPPLE_EINVAL;
+    *n_pieces = 0;
+    if (n_ops == 0) return RIPPLE_OK;
+    TouchTable tt;
+    std::vector<SubBatch> pieces;
+    split_batch(ops, n_ops, tt, pieces);
+    for (size_t p = 0; p < pieces.size(); ++p)
+        if (p < cap) piece_end[p] = pieces[p].end;
+    *n_pieces = (uint32_t)pieces.size();
+    return RIPPLE_OK;
+}
+
 static ripple_status ensure_batch_buffers(ripple_ctx *c, uint32_t n_ops, uint32_t n_feat, uint32_t want_exp) {
     if (n_ops > c->ops_cap || want_exp > c->exp_cap) {
         RP_HIP(c, hipStreamSynchronize(c->stream));
@@ -799,13 +825,8 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
         RP_HIP(c, hipStreamSynchronize(s));
         hops = c->ops_pin;
     }
-    for (uint32_t i = 0; i < n_ops; ++i) {
-        const ripple_update &op = hops[i];
-        bool bad = op.kind > RIPPLE_FEAT_UPDATE || op.u >= c->n_cap;
-        if (!bad && op.kind <= RIPPLE_EDGE_DEL) bad = op.v >= c->n_cap;
-        if (!bad && (op.kind == RIPPLE_VERTEX_ADD || op.kind == RIPPLE_FEAT_UPDATE)) bad = op.feat_row >= n_feat_rows;
-        if (bad) return fail(c, RIPPLE_EINVAL, "operation with unknown kind, vertex id or payload row out of range");
-    }
+    if (!ops_in_range(hops, n_ops, c->n_cap, n_feat_rows))
+        return fail(c, RIPPLE_EINVAL, "operation with unknown kind, vertex id or payload row out of range");
     if (n_ops == 0) {                              // nothing to do: the affected sets become empty
         rp_launch_batch_reset(c);
         RP_HIP(c, hipMemcpyAsync(c->ctr_host, c->ctr, sizeof(DevCtr), hipMemcpyDeviceToHost, s));
