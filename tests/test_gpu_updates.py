@@ -698,3 +698,32 @@ def test_degenerate_neighbourhoods(kind):
         pair.check_graph()
     finally:
         pair.close()
+
+
+@pytest.mark.parametrize("kinds,widths", [(("sage_mean", "gcn_max", "gcn_mean"), (64, 16, 12, 6)),      # project-first, then max
+                                          (("gcn_sum", "gcn_min", "gat"), (10, 7, 5, 3)),             # odd widths: generic products
+                                          (("gat", "gcn_sum", "gcn_max"), (9, 6, 7, 5)),
+                                          (("gin_sum", "gcn_max", "sage_mean"), (12, 20, 8, 6))])
+def test_mixed_layer_kinds_hand_over_the_right_rows(kinds, widths):
+    """What layer l writes for the next hop (differences, or the old rows when the next layer takes max / min)
+    comes from whichever kernel finishes layer l: the tiled product, the generic product for odd widths,
+    the element-wise update of project-first and attention layers, or the second stage of a two-stage
+    update."""
+    print("case mixed kinds", kinds, widths, flush=True)
+    src, dst, out_law, in_law = ri.chung_lu_graph(900, 8000, 2.1, 0.04, 261)
+    feats = ri.features(900, widths[0], 262)
+    model = [ri.make_model(k, widths, 263 + i)[i] for i, k in enumerate(kinds)]
+    from harness import Pair
+    pair = Pair(900, 900 + 64, src, dst, feats, model)
+    stream = ri.UpdateStream(900, 900 + 64, src, dst, out_law, in_law, widths[0], MIXV, 266)
+    try:
+        if kinds[0] == "sage_mean":
+            assert rp.ripple_get_layer_info(pair.ctx, 1)[1], "the first layer was meant to be handled project-first"
+        pair.check_embeddings()
+        for b, bs in enumerate([4, 90, 350]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload)
+            pair.check_aggregates()
+    finally:
+        pair.close()
