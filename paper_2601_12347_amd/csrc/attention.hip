@@ -36,9 +36,10 @@ __device__ __forceinline__ float gat_weight(float s_u, float t_v) {
 
 // One block of up to 64 in-neighbours (id per lane in my_u, `valid` lanes hold one). recompute: all of them
 // contribute w P[u]; otherwise the changed ones contribute w_new P[u] - w_old Pold[u]. acc: the wavefront's
-// running numerator (column lane + 64 j); returns this lane's share of the denominator.
+// running numerator (column lane + 64 j); returns this lane's share of the denominator and adds the
+// magnitude of what it patched (w_new + w_old) to mag.
 template <int NJ, int G, bool recompute>
-__device__ __forceinline__ float gat_block(const GatArgs &a, uint32_t my_u, bool valid, float t_v, float *acc) {
+__device__ __forceinline__ float gat_block(const GatArgs &a, uint32_t my_u, bool valid, float t_v, float *acc, float &mag) {
     const int lane = rp_lane();
     const uint32_t d = a.d;
     const bool on = valid && (recompute || rp_bit(a.bm_prev, my_u));     // rp_bit is not evaluated when recomputing
@@ -81,8 +82,14 @@ __device__ __forceinline__ float gat_block(const GatArgs &a, uint32_t my_u, bool
             }
         }
     }
+    mag += wn + wo;
     return wn - wo;
 }
+
+// A patched denominator that is tiny against what was added and taken away has lost its small terms
+// (a weight e^z that dropped by many orders of magnitude leaves only rounding residue of itself): such a
+// row is recomputed from all its in-neighbours instead.
+#define GAT_CANCEL 1e-3f
 
 __device__ __forceinline__ float gat_wave_sum(float x) {
 #pragma unroll
@@ -105,18 +112,27 @@ __global__ __launch_bounds__(256) void k_gat_scatter(GatArgs a) {
             if (lane == 0) a.queue[atomicAdd(a.queue_count, 1u)] = v;
             continue;
         }
-        const bool recompute = a.all || rp_bit(a.bm_prev, v) || rp_bit(a.bm_sink, v) || rp_bit(a.bm_vadd, v);
+        bool recompute = a.all || rp_bit(a.bm_prev, v) || rp_bit(a.bm_sink, v) || rp_bit(a.bm_vadd, v);
         const float t_v = a.sdst[v];
         float acc[NJ];
+        float dsum;
+        for (;;) {                                             // a second pass only after a cancelled patch
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
-        float dsum = 0.0f;
-        for (uint32_t base = 0; base < m.y; base += 64) {
-            const uint32_t e = base + lane;
-            const uint32_t my_u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
-            dsum += recompute ? gat_block<NJ, GR, true>(a, my_u, e < m.y, t_v, acc) : gat_block<NJ, G, false>(a, my_u, e < m.y, t_v, acc);
+            for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
+            dsum = 0.0f;
+            float mag = 0.0f;
+            for (uint32_t base = 0; base < m.y; base += 64) {
+                const uint32_t e = base + lane;
+                const uint32_t my_u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
+                dsum += recompute ? gat_block<NJ, GR, true>(a, my_u, e < m.y, t_v, acc, mag)
+                                  : gat_block<NJ, G, false>(a, my_u, e < m.y, t_v, acc, mag);
+            }
+            dsum = gat_wave_sum(dsum);
+            if (recompute) break;
+            mag = gat_wave_sum(mag);
+            if (a.den[v] + dsum > GAT_CANCEL * mag) break;
+            recompute = true;
         }
-        dsum = gat_wave_sum(dsum);
 #pragma unroll
         for (int j = 0; j < NJ; ++j) {
             const uint32_t col = lane + 64 * j;
@@ -135,29 +151,45 @@ __global__ __launch_bounds__(TEAM * 64) void k_gat_scatter_long(GatArgs a) {
     constexpr int G = (NJ <= 1) ? 8 : (NJ <= 2 ? 4 : (NJ <= 4 ? 2 : 1));
     constexpr int GR = (NJ <= 2) ? 16 : 32 / NJ;               // a long row is paced by round trips
     __shared__ float s_val[TEAM][NJ * 64];
-    __shared__ float s_den[TEAM];
+    __shared__ float s_den[TEAM], s_mag[TEAM];
     const uint32_t count = *a.count_ptr;
     const int lane = rp_lane(), wave = threadIdx.x >> 6;
     const uint32_t d = a.d;
     for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) {
         const uint32_t v = a.list[i];
         const uint2 m = a.in_meta[v];
-        const bool recompute = a.all || rp_bit(a.bm_prev, v) || rp_bit(a.bm_sink, v) || rp_bit(a.bm_vadd, v);
+        bool recompute = a.all || rp_bit(a.bm_prev, v) || rp_bit(a.bm_sink, v) || rp_bit(a.bm_vadd, v);
         const float t_v = a.sdst[v];
         float acc[NJ];
+        for (;;) {                                             // a second pass only after a cancelled patch
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
-        float dsum = 0.0f;
-        for (uint32_t base = 64u * wave; base < m.y; base += 64u * TEAM) {
-            const uint32_t e = base + lane;
-            const uint32_t my_u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
-            dsum += recompute ? gat_block<NJ, GR, true>(a, my_u, e < m.y, t_v, acc) : gat_block<NJ, G, false>(a, my_u, e < m.y, t_v, acc);
+            for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
+            float dsum = 0.0f, mag = 0.0f;
+            for (uint32_t base = 64u * wave; base < m.y; base += 64u * TEAM) {
+                const uint32_t e = base + lane;
+                const uint32_t my_u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
+                dsum += recompute ? gat_block<NJ, GR, true>(a, my_u, e < m.y, t_v, acc, mag)
+                                  : gat_block<NJ, G, false>(a, my_u, e < m.y, t_v, acc, mag);
+            }
+            dsum = gat_wave_sum(dsum);
+            mag = gat_wave_sum(mag);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) s_val[wave][j * 64 + lane] = acc[j];
+            if (lane == 0) {
+                s_den[wave] = dsum;
+                s_mag[wave] = mag;
+            }
+            __syncthreads();
+            if (recompute) break;
+            float dd = 0.0f, mm = 0.0f;                        // every thread takes the same decision
+            for (int w = 0; w < TEAM; ++w) {
+                dd += s_den[w];
+                mm += s_mag[w];
+            }
+            if (a.den[v] + dd > GAT_CANCEL * mm) break;
+            recompute = true;
+            __syncthreads();                                   // the partial results are overwritten by the second pass
         }
-        dsum = gat_wave_sum(dsum);
-#pragma unroll
-        for (int j = 0; j < NJ; ++j) s_val[wave][j * 64 + lane] = acc[j];
-        if (lane == 0) s_den[wave] = dsum;
-        __syncthreads();
         if (wave == 0) {
             float dd = 0.0f;
             for (int w = 0; w < TEAM; ++w) dd += s_den[w];

@@ -727,3 +727,31 @@ def test_mixed_layer_kinds_hand_over_the_right_rows(kinds, widths):
             pair.check_aggregates()
     finally:
         pair.close()
+
+
+def test_attention_scores_that_drop_by_many_orders_of_magnitude():
+    """Raw exponentials (the paper's numerator / denominator messages) cancel catastrophically when a dominant
+    weight collapses: e^36 taken out of a denominator leaves only rounding residue. Rows whose patched
+    denominator is tiny against what was added and removed are recomputed instead; the result must still
+    match the oracle."""
+    print("case attention cancellation", flush=True)
+    n, d = 400, 4
+    src, dst, out_law, in_law = ri.chung_lu_graph(n, 4000, 2.1, 0.05, 271)
+    feats = ri.features(n, d, 272)
+    model = ri.make_model("gat", (d, d, 3), 273)
+    model[0]["W0"] = np.eye(d, dtype=np.float32)
+    model[0]["att"] = np.array([12.0, 0, 0, 0, 0, 0, 0, 0], dtype=np.float32)      # score = 12 * first feature of the source
+    from harness import Pair
+    pair = Pair(n, n + 16, src, dst, feats, model)
+    feat_only = {"edge_add": 0.0, "edge_del": 0.0, "feat": 1.0, "vadd": 0.0, "vdel": 0.0}
+    stream = ri.UpdateStream(n, n + 16, src, dst, out_law, in_law, d, feat_only, 274)
+    try:
+        pair.check_embeddings()
+        rng = np.random.default_rng(275)
+        for b in range(6):
+            ops, payload, _ = stream.next_batch(30)
+            # push the updated vertices' first feature to the extremes: weights between e^-7 and e^36
+            payload[:, 0] = rng.choice([-3.0, 3.0], size=len(payload))
+            pair.step(ops, payload)
+    finally:
+        pair.close()
