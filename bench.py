@@ -142,6 +142,7 @@ def main():
     ap.add_argument("--scatter-mode", type=int, default=0)
     ap.add_argument("--pull-ratio", type=int, default=0)
     ap.add_argument("--deterministic", action="store_true", help="bit-reproducible aggregation (RIPPLE_OPT_DETERMINISTIC)")
+    ap.add_argument("--sparse-frontier", type=int, default=-1, help="0 = always scan the bitmap for the hop's list")
     ap.add_argument("--split-mfma", type=int, default=-1,
                     help="fp32 storage: 1 = products on the bf16 matrix cores with operands split in three, 0 = fp32 matrix path")
     ap.add_argument("--bf16-mfma", type=int, default=1, help="bf16 storage only: 0 = multiply on the fp32 matrix path")
@@ -194,6 +195,8 @@ def main():
     log(f"[bench] {len(batches)} batches of {bs} updates staged in HBM in {time.time() - t0:.1f}s")
 
     rp.ripple_set_option(ctx, rp.OPT_SCATTER_MODE, args.scatter_mode)
+    if args.sparse_frontier >= 0:
+        rp.ripple_set_option(ctx, rp.OPT_SPARSE_FRONTIER, args.sparse_frontier)
     rp.ripple_set_option(ctx, rp.OPT_BF16_MFMA, args.bf16_mfma)
     if args.pull_ratio:
         rp.ripple_set_option(ctx, rp.OPT_PULL_RATIO, args.pull_ratio)

@@ -154,6 +154,8 @@ typedef enum {
                                      cores with every fp32 operand split exactly into three bf16 numbers and the six
                                      largest of the nine partial products kept (what is dropped is below 2^-24 of a
                                      product); results agree with the fp32 matrix path to rounding */
+    RIPPLE_OPT_SPARSE_FRONTIER = 8, /* 0/1 (default 1): a hop whose set was small in the previous batch enters vertices into
+                                     its list as they are marked instead of scanning the whole bitmap afterwards */
     RIPPLE_OPT_DETERMINISTIC = 6  /* 0/1 (default 0), before load_model: every aggregate row is produced by one owner that
                                      adds its sources in a fixed order (no float atomics; rows with a changed in-edge are
                                      recomputed from their in-neighbours), so that two runs over the same operations give

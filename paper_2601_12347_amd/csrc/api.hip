@@ -678,6 +678,9 @@ static ripple_status ensure_batch_buffers(ripple_ctx *c, uint32_t n_ops, uint32_
 }
 
 // A_{l-1} is part of A_l: the layer reads the vertex's own row (a self term, or its attention score)
+#define SPARSE_MAX_ROWS 4096u
+#define SPARSE_MAX_EDGES 65536u
+
 static bool layer_self(const ripple_ctx *c, uint32_t l) {
     return c->layers[l - 1].self_mode != RIPPLE_SELF_NONE || rp_layer_attn(c, l);
 }
@@ -770,12 +773,17 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
         const bool wsum = c->layers[l - 1].agg == RIPPLE_AGG_WSUM;
         const bool may_pull = wsum || (l >= 2 && c->opt_scatter != 1 && !(c->opt_scatter == 0 && c->push_margin[l]));
         const bool may_disc = l >= 2 && may_pull && (c->opt_scatter == 3 || ((c->opt_scatter == 0 || wsum) && c->disc_near[l]));
+        // a frontier that was small last time (and a batch of about the same size) is listed as it is marked
+        const bool sparse = c->opt_sparse && !multi && !may_disc && c->last_a[l] <= SPARSE_MAX_ROWS &&
+                            c->last_a[l - 1] <= SPARSE_MAX_ROWS && c->last_m[l] <= SPARSE_MAX_EDGES &&
+                            c->last_n_ops && n <= 2 * c->last_n_ops;
         t = rp_timer_begin(c);
         if (may_disc && !have_all) {
             rp_launch_alive_list(c);
             have_all = true;
         }
-        rp_launch_frontier_mark(c, l, may_disc);
+        if (sparse) rp_launch_frontier_sparse(c, l, layer_self(c, l), l < c->L);
+        else rp_launch_frontier_mark(c, l, may_disc);
         rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
         if (c->layers[l - 1].proj) {                   // multiply the deltas by W_neigh before they travel
             t = rp_timer_begin(c);
@@ -792,9 +800,11 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
             rp_launch_scatter_pull(c, l, true, true);
             rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l, false);
         }
-        t = rp_timer_begin(c);
-        rp_launch_frontier_compact(c, l, layer_self(c, l), l < c->L, true, multi);
-        rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l);
+        if (!sparse) {
+            t = rp_timer_begin(c);
+            rp_launch_frontier_compact(c, l, layer_self(c, l), l < c->L, true, multi);
+            rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l);
+        }
         t = rp_timer_begin(c);
         if (!wsum && (c->opt_scatter < 2 || !may_pull)) rp_launch_scatter_push(c, l, may_pull, may_disc);
         if (may_pull) rp_launch_scatter_pull(c, l, false, may_disc);
@@ -911,6 +921,7 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
         for (uint32_t l = 1; l <= c->L; ++l) {
             msgs[l] += h.m[l];
             tchd[l] += h.touched[l];
+            c->last_m[l] = h.m[l];
             for (int k = 0; k < 3; ++k) mono[k][l] += h.mono[k][l];
             c->last_cand[l] = h.mono[0][l] + h.mono[1][l] + h.mono[2][l];
             // pull wins when m * row_bytes * ratio >= 8 * in-edges; remember if push won by a factor of 16
@@ -920,6 +931,7 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
         }
         if (!multi)
             for (uint32_t l = 0; l <= c->L; ++l) c->last_a[l] = h.a[l];
+        c->last_n_ops = multi ? 0u : n;
     }
     c->payload_d = payload_saved;
     if (rc != RIPPLE_OK) return rc;
@@ -1152,6 +1164,9 @@ extern "C" ripple_status ripple_set_option(ripple_ctx *c, int option, int64_t va
         return RIPPLE_OK;
     case RIPPLE_OPT_BF16_MFMA:
         c->opt_bf16_mfma = value ? 1 : 0;
+        return RIPPLE_OK;
+    case RIPPLE_OPT_SPARSE_FRONTIER:
+        c->opt_sparse = value ? 1 : 0;
         return RIPPLE_OK;
     case RIPPLE_OPT_PROJECT_FIRST:
         if (c->state != 1) return fail(c, RIPPLE_ESTATE, "project-first must be chosen before load_model");

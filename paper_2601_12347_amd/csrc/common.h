@@ -149,7 +149,9 @@ struct ripple_ctx {
 
     // last batch's sets (reporting)
     uint32_t last_a[RIPPLE_MAX_LAYERS + 1] = {0};
-    uint32_t last_cand[RIPPLE_MAX_LAYERS + 1] = {0};    // candidates of the last batch's max / min hops (a size hint)
+    uint32_t last_cand[RIPPLE_MAX_LAYERS + 1] = {0};
+    uint32_t last_m[RIPPLE_MAX_LAYERS + 1] = {0};       // messages per hop of the last batch (a size hint)
+    uint32_t last_n_ops = 0;                            // operations of the last single-piece batch    // candidates of the last batch's max / min hops (a size hint)
     bool last_from_rep = false;
     bool push_margin[RIPPLE_MAX_LAYERS + 1] = {false};  // last batch pushed at this hop by a wide margin
     bool disc_near[RIPPLE_MAX_LAYERS + 1] = {false};    // last batch's hop was within reach of the discovering mode
@@ -160,6 +162,7 @@ struct ripple_ctx {
     int opt_bf16_mfma = 1;                      // bf16 storage: multiply on the bf16 matrix cores
     int opt_project = 1;                        // allow project-first layers (read by load_model)
     int opt_selfcache = 1;                      // allow cached self projections (read by load_model)
+    int opt_sparse = 1;                         // small frontiers are listed as they are marked (no bitmap scan)
     int opt_split = 0;                          // fp32 storage: products on the bf16 matrix cores, operands split in three (read by load_model)
     int opt_deterministic = 0;                  // bit-reproducible aggregation (owner kernels, no float atomics)
     int opt_pull_ratio = 2;                     // pull when messages * width * ratio >= scanned in-edges

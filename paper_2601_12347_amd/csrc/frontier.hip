@@ -15,11 +15,46 @@
 // whole list; the 64 rows after the chunk's first one are described in registers (one per lane:
 // where the row's edges start in the pool, and the first edge of the next row) and an edge finds its
 // row with shuffles. Nothing to do on a discovering hop (the in-row scan finds A_l).
-__global__ __launch_bounds__(256) void k_frontier_mark(const uint32_t *list, const uint32_t *count_ptr,
-                                                       const uint32_t *eoff, const uint2 *out_meta,
-                                                       const uint32_t *out_pool, uint8_t *mk, const DevCtr *ctr,
-                                                       uint32_t l, uint32_t d, int mode, int ratio, int allow_disc) {
-    if (allow_disc && rp_hop_mode(ctr, l, d, mode, ratio, allow_disc) == RP_HOP_DISCOVER) return;
+// Small frontiers (SparseArgs given): a marked vertex is entered into the hop's bitmap at once and the
+// first wavefront to do so appends it to the hop's list, so no scan of the whole bitmap is needed
+// afterwards; the list is then in no particular order.
+struct SparseArgs {
+    uint32_t *bm;                  // the hop's bitmap (zero on entry)
+    const uint32_t *alive;
+    uint32_t *list, *count;        // the hop's list and its length (zero on entry)
+    uint32_t *touched;             // += vertices first entered by an out-edge (statistics)
+    // roots merged in by the same kernel: sinks of changed edges, created vertices, the previous hop's set (self term)
+    const uint32_t *st_dst, *n_struct;
+    uint32_t struct_cap;
+    const uint32_t *list0, *count0, *bm_vadd;
+    int self_term;
+};
+
+// to be called by all 64 lanes together
+__device__ __forceinline__ void sparse_enter(const SparseArgs &s, uint32_t v, bool valid, bool from_edge) {
+    bool fresh = false;
+    if (valid && rp_bit(s.alive, v)) {
+        const uint32_t m = 1u << (v & 31);
+        fresh = !(atomicOr(&s.bm[v >> 5], m) & m);
+    }
+    const unsigned long long mask = __ballot(fresh);
+    if (!mask) return;
+    const int lane = rp_lane();
+    const int leader = __ffsll((long long)mask) - 1;
+    const uint32_t k = (uint32_t)__popcll(mask);
+    uint32_t base = 0;
+    if (lane == leader) {
+        base = atomicAdd(s.count, k);
+        if (from_edge && s.touched) atomicAdd(s.touched, k);
+    }
+    base = __shfl(base, leader);
+    if (fresh) s.list[base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull))] = v;
+}
+
+template <bool SPARSE>
+__device__ __forceinline__ void frontier_walk(const uint32_t *list, const uint32_t *count_ptr, const uint32_t *eoff,
+                                              const uint2 *out_meta, const uint32_t *out_pool, uint8_t *mk,
+                                              const SparseArgs &sp) {
     const uint32_t count = *count_ptr;
     if (count == 0) return;
     constexpr int T = MARK_CHUNK / 64;
@@ -72,11 +107,45 @@ __global__ __launch_bounds__(256) void k_frontier_mark(const uint32_t *list, con
             bnd_n = eoff[min(count, i_nx + 1 + lane)];
         }
 #pragma unroll
-        for (int t = 0; t < T; ++t)
-            if (v[t] != 0xFFFFFFFFu) mk[v[t]] = 1;       // plain byte stores: idempotent, no atomics
+        for (int t = 0; t < T; ++t) {
+            if (SPARSE) sparse_enter(sp, v[t], v[t] != 0xFFFFFFFFu, true);
+            else if (v[t] != 0xFFFFFFFFu) mk[v[t]] = 1;  // plain byte stores: idempotent, no atomics
+        }
         i_lo = i_nx;
         rbase = rbase_n;
         bnd = bnd_n;
+    }
+}
+
+__global__ __launch_bounds__(256) void k_frontier_mark(const uint32_t *list, const uint32_t *count_ptr,
+                                                       const uint32_t *eoff, const uint2 *out_meta,
+                                                       const uint32_t *out_pool, uint8_t *mk, const DevCtr *ctr,
+                                                       uint32_t l, uint32_t d, int mode, int ratio, int allow_disc) {
+    if (allow_disc && rp_hop_mode(ctr, l, d, mode, ratio, allow_disc) == RP_HOP_DISCOVER) return;
+    frontier_walk<false>(list, count_ptr, eoff, out_meta, out_pool, mk, SparseArgs());
+}
+
+// the out-edge walk and the roots in one kernel, straight into the hop's bitmap and (unordered) list
+__global__ __launch_bounds__(256) void k_frontier_sparse(const uint32_t *list, const uint32_t *count_ptr,
+                                                         const uint32_t *eoff, const uint2 *out_meta,
+                                                         const uint32_t *out_pool, SparseArgs sp) {
+    frontier_walk<true>(list, count_ptr, eoff, out_meta, out_pool, nullptr, sp);
+    const int lane = rp_lane();
+    const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    const uint32_t n_s = min(*sp.n_struct, sp.struct_cap), n_0 = *sp.count0, n_p = sp.self_term ? *count_ptr : 0u;
+    const uint32_t total = n_s + n_0 + n_p;
+    for (uint32_t base = gw * 64; base < total; base += nw * 64) {
+        const uint32_t i = base + lane;
+        uint32_t v = 0;
+        bool valid = i < total;
+        if (valid) {
+            if (i < n_s) v = sp.st_dst[i];
+            else if (i < n_s + n_0) {
+                v = sp.list0[i - n_s];
+                valid = rp_bit(sp.bm_vadd, v);
+            } else v = list[i - n_s - n_0];
+        }
+        sparse_enter(sp, v, valid, false);
     }
 }
 
@@ -362,35 +431,44 @@ static void launch_compact(ripple_ctx *c, const CompactArgs &a, uint32_t expect)
     hipLaunchKernelGGL(k_frontier_emit, dim3(nb), dim3(256), 0, c->stream, a);
 }
 
-// out-degree prefix over an arbitrary (unsorted) list, one workgroup; used for hop 0
+// degree prefix over an arbitrary (unsorted) list, one workgroup: out-degrees (used for hop 0 and for the
+// lists of small frontiers), and with in_meta given the in-degrees in a second sweep
 __global__ __launch_bounds__(1024) void k_list_eoff(const uint32_t *list, const uint32_t *count_ptr,
-                                                    const uint2 *out_meta, uint32_t *eoff, uint32_t *msgs_out) {
+                                                    const uint2 *out_meta, uint32_t *eoff, uint32_t *msgs_out,
+                                                    const uint2 *in_meta, uint32_t *ioff, uint32_t *isum_out) {
     __shared__ uint32_t ws[16];
     __shared__ uint32_t carry;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t count = *count_ptr;
-    if (tid == 0) carry = 0;
-    __syncthreads();
-    for (uint32_t base = 0; base < count; base += 1024) {
-        uint32_t i = base + tid;
-        uint32_t deg = (i < count) ? out_meta[list[i]].y : 0u;
-        uint32_t inc = deg;
-        for (int o = 1; o < 64; o <<= 1) {
-            uint32_t t = __shfl_up(inc, o);
-            if (lane >= o) inc += t;
+    for (int side = 0; side < 2; ++side) {
+        const uint2 *meta = side ? in_meta : out_meta;
+        uint32_t *off_out = side ? ioff : eoff;
+        uint32_t *total_out = side ? isum_out : msgs_out;
+        if (!meta || !off_out) continue;                   // (kernel arguments: the same for every thread)
+        __syncthreads();
+        if (tid == 0) carry = 0;
+        __syncthreads();
+        for (uint32_t base = 0; base < count; base += 1024) {
+            uint32_t i = base + tid;
+            uint32_t deg = (i < count) ? meta[list[i]].y : 0u;
+            uint32_t inc = deg;
+            for (int o = 1; o < 64; o <<= 1) {
+                uint32_t t = __shfl_up(inc, o);
+                if (lane >= o) inc += t;
+            }
+            if (lane == 63) ws[wave] = inc;
+            __syncthreads();
+            uint32_t off = carry;
+            for (int k = 0; k < wave; ++k) off += ws[k];
+            if (i < count) off_out[i] = off + inc - deg;
+            __syncthreads();
+            if (tid == 1023) carry = off + inc;
+            __syncthreads();
         }
-        if (lane == 63) ws[wave] = inc;
-        __syncthreads();
-        uint32_t off = carry;
-        for (int k = 0; k < wave; ++k) off += ws[k];
-        if (i < count) eoff[i] = off + inc - deg;
-        __syncthreads();
-        if (tid == 1023) carry = off + inc;
-        __syncthreads();
-    }
-    if (tid == 0) {
-        eoff[count] = carry;
-        if (msgs_out) *msgs_out = carry;
+        if (tid == 0) {
+            off_out[count] = carry;
+            if (total_out) *total_out = carry;
+        }
     }
 }
 
@@ -494,5 +572,31 @@ void rp_launch_bitmap_to_list(ripple_ctx *c, uint32_t *bitmap, uint32_t *out_lis
 
 void rp_launch_list_eoff(ripple_ctx *c, uint32_t l) {
     hipLaunchKernelGGL(k_list_eoff, dim3(1), dim3(1024), 0, c->stream, c->list[l], &c->ctr->a[l], c->out_meta,
-                       c->eoff[l], l < RIPPLE_MAX_LAYERS ? &c->ctr->m[l + 1] : (uint32_t *)nullptr);
+                       c->eoff[l], l < RIPPLE_MAX_LAYERS ? &c->ctr->m[l + 1] : (uint32_t *)nullptr,
+                       (const uint2 *)nullptr, (uint32_t *)nullptr, (uint32_t *)nullptr);
+}
+
+// Hop l for a small frontier: out-edge walk from A_{l-1} and the roots (S, V_added, A_{l-1} when self_term)
+// straight into bm[l] and list[l] (unordered), then the degree prefixes over that list. Two launches
+// instead of the walk plus a scan of the whole bitmap.
+void rp_launch_frontier_sparse(ripple_ctx *c, uint32_t l, bool self_term, bool want_out) {
+    SparseArgs sp;
+    sp.bm = c->bm[l];
+    sp.alive = c->alive;
+    sp.list = c->list[l];
+    sp.count = &c->ctr->a[l];
+    sp.touched = &c->ctr->touched[l];
+    sp.st_dst = c->st_dst;
+    sp.n_struct = &c->ctr->n_struct;
+    sp.struct_cap = c->struct_cap;
+    sp.list0 = c->list[0];
+    sp.count0 = &c->ctr->a[0];
+    sp.bm_vadd = c->bm_vadd;
+    sp.self_term = self_term ? 1 : 0;
+    hipLaunchKernelGGL(k_frontier_sparse, dim3(c->n_cu), dim3(256), 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],
+                       c->eoff[l - 1], c->out_meta, c->out_pool, sp);
+    hipLaunchKernelGGL(k_list_eoff, dim3(1), dim3(1024), 0, c->stream, c->list[l], &c->ctr->a[l], c->out_meta,
+                       want_out ? c->eoff[l] : (uint32_t *)nullptr,
+                       (want_out && l < RIPPLE_MAX_LAYERS) ? &c->ctr->m[l + 1] : (uint32_t *)nullptr, c->in_meta, c->ioff[l],
+                       &c->ctr->isum[l]);
 }

@@ -20,6 +20,7 @@ void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool 
 void rp_launch_candidates(ripple_ctx *c, uint32_t l);
 void rp_launch_bitmap_to_list(ripple_ctx *c, uint32_t *bitmap, uint32_t *out_list, uint32_t *count_d);
 void rp_launch_list_eoff(ripple_ctx *c, uint32_t l);
+void rp_launch_frontier_sparse(ripple_ctx *c, uint32_t l, bool self_term, bool want_out);
 
 // scatter.hip
 void rp_launch_scatter_push(ripple_ctx *c, uint32_t l, bool may_pull, bool allow_disc);

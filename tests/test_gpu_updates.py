@@ -755,3 +755,31 @@ def test_attention_scores_that_drop_by_many_orders_of_magnitude():
             pair.step(ops, payload)
     finally:
         pair.close()
+
+
+@pytest.mark.parametrize("kind,widths,weighted", [("sage_mean", (16, 40, 24, 10), False), ("gcn_sum", (100, 256, 47), False),
+                                                  ("gin_sum", (12, 20, 8), False), ("gcn_wsum", (12, 20, 8), True)])
+def test_small_frontiers_listed_while_marking(kind, widths, weighted):
+    """Hops whose sets were small in the previous batch build their list while marking (unordered, no bitmap
+    scan). Small batches of steady size take that path from the second batch on; a much larger batch in
+    between and the batches after it fall back and return to it. Checked like every other batch; the same
+    stream with the option off must report identical sets."""
+    print("case sparse frontier", kind, flush=True)
+    pair, graph = make_pair(n=6000, e=50000, d0=widths[0], kind=kind, widths=widths, seed=281, slack=128, weighted=weighted)
+    twin, _ = make_pair(n=6000, e=50000, d0=widths[0], kind=kind, widths=widths, seed=281, slack=128, weighted=weighted)
+    rp.ripple_set_option(twin.ctx, rp.OPT_SPARSE_FRONTIER, 0)
+    stream = make_stream(pair, graph, MIXV, 283, weighted=weighted)
+    try:
+        for b, bs in enumerate([6, 6, 8, 7, 900, 10, 12, 9, 1, 1, 2]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            res, _, sets = pair.step(ops, payload)
+            rp.ripple_apply_updates(twin.ctx, ops, payload)
+            for l in range(pair.L + 1):
+                assert np.array_equal(rp.ripple_get_affected(twin.ctx, l, twin.cap)[0],
+                                      rp.ripple_get_affected(pair.ctx, l, pair.cap)[0])
+        pair.check_aggregates()
+        pair.check_graph()
+    finally:
+        pair.close()
+        twin.close()
