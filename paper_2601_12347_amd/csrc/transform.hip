@@ -360,8 +360,8 @@ __device__ __forceinline__ void epilogue_staged(const TArgs &a, floatx16 (&acc)[
                                                 const float *s_scale, uint32_t row0, uint32_t count, uint32_t n0, int wm,
                                                 int wn, int tid) {
     constexpr int C_LD = BN + 4;
-    constexpr int ITER = BM * BN / 4 / 256, U = 4;
-    static_assert(ITER % (2 * U) == 0, "tile size");
+    constexpr int ITER = BM * BN / 4 / 256, U = (ITER >= 8) ? 4 : ITER / 2;
+    static_assert(U >= 1 && ITER % (2 * U) == 0, "tile size");
     const int lane = tid & 63;
     const bool vec = (a.N & 3u) == 0 && (a.out_mode == 1 || (a.tmp_out_ld & 3u) == 0);
     __syncthreads();                                       // every wavefront is done with the A/B slices
@@ -1051,6 +1051,17 @@ static void launch_split(ripple_ctx *c, const TArgs &a, bool narrow, uint32_t ro
 
 template <int MODE, int STORE>
 static void launch_fast(ripple_ctx *c, const TArgs &a, bool narrow, uint32_t rows_hint) {
+    if (rows_hint <= 32 && a.Npad % 128 == 0) {
+        // a handful of rows: one 32-row tile, four wavefronts side by side on 32 columns each, so that the
+        // chain of dependent matrix-core operations per K step is a quarter of the 128 x 64 tile's
+        hipLaunchKernelGGL((k_transform_f32<1, 4, 1, 1, 3, MODE, STORE>), dim3(8, a.Npad / 128), dim3(256), 0, c->stream, a);
+        return;
+    }
+    if (rows_hint <= 2048) {                               // few rows: 64 x 64 tiles, one 32 x 32 block per wavefront
+        hipLaunchKernelGGL((k_transform_f32<2, 2, 1, 1, 3, MODE, STORE>), dim3(std::max(8u, rows_hint / 64 + 1), a.Npad / 64),
+                           dim3(256), 0, c->stream, a);
+        return;
+    }
     if (a.Npad >= 256 && !narrow) {
         hipLaunchKernelGGL((k_transform_f32<1, 4, 2, 2, 3, MODE, STORE>), dim3(tile_grid(c, rows_hint, 64, c->n_cu * 2), a.Npad / 256),
                            dim3(256), 0, c->stream, a);
