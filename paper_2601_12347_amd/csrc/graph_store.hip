@@ -861,14 +861,14 @@ __global__ __launch_bounds__(256) void k_struct_scatter(MutArgs a) {
                 for (uint32_t k0 = 0; k0 < dp; k0 += 64) {
                     const uint32_t kk = k0 + lane;
                     const float hv = (kk < dp) ? rp_load_h(a.H[l - 1], a.store, (size_t)u * dp + kk) : 0.0f;
-                    // rows of W beyond dp exist (zero padding up to a multiple of 32) or meet hk = 0
-                    const uint32_t kn = min(64u, (dp - k0 + 7u) & ~7u);
-                    for (uint32_t j = 0; j < kn; j += 8) {        // eight independent weight loads in flight
-                        float w[8];
+                    // rows of W beyond dp exist (zero padding up to a multiple of 32) and meet hv = 0
+                    const uint32_t kn = min(64u, (dp - k0 + 31u) & ~31u);
+                    for (uint32_t j = 0; j < kn; j += 32) {       // 32 independent weight loads in flight (the loop is paced by L2 round trips)
+                        float w[32];
 #pragma unroll
-                        for (int t = 0; t < 8; ++t) w[t] = (c < dn) ? W[(size_t)(k0 + j + t) * ld + c] : 0.0f;
+                        for (int t = 0; t < 32; ++t) w[t] = (c < dn) ? W[(size_t)(k0 + j + t) * ld + c] : 0.0f;
 #pragma unroll
-                        for (int t = 0; t < 8; ++t) sum += __shfl(hv, (int)(j + t)) * w[t];
+                        for (int t = 0; t < 32; ++t) sum += __shfl(hv, (int)(j + t)) * w[t];
                     }
                 }
                 if (c < dn && sum != 0.0f) unsafeAtomicAdd(&a.X[l][(size_t)v * dn + c], sg * sum);
