@@ -431,43 +431,81 @@ static void launch_compact(ripple_ctx *c, const CompactArgs &a, uint32_t expect)
     hipLaunchKernelGGL(k_frontier_emit, dim3(nb), dim3(256), 0, c->stream, a);
 }
 
-// degree prefix over an arbitrary (unsorted) list, one workgroup: out-degrees (used for hop 0 and for the
-// lists of small frontiers), and with in_meta given the in-degrees in a second sweep
+// degree prefixes over an arbitrary (unsorted) list, one workgroup: out-degrees into eoff (hop 0, and the
+// lists of small frontiers) and, with in_meta and ioff given, in-degrees into ioff in the same sweep.
+// Every thread takes four consecutive entries per round, so that a list that turns out long (the
+// small-frontier path is chosen on the previous batch's sizes) costs a quarter of the round trips.
+#define EOFF_PER 4
 __global__ __launch_bounds__(1024) void k_list_eoff(const uint32_t *list, const uint32_t *count_ptr,
                                                     const uint2 *out_meta, uint32_t *eoff, uint32_t *msgs_out,
                                                     const uint2 *in_meta, uint32_t *ioff, uint32_t *isum_out) {
-    __shared__ uint32_t ws[16];
-    __shared__ uint32_t carry;
+    __shared__ uint32_t wo[16], wi[16];
+    __shared__ uint32_t carry_o, carry_i;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const uint32_t count = *count_ptr;
-    for (int side = 0; side < 2; ++side) {
-        const uint2 *meta = side ? in_meta : out_meta;
-        uint32_t *off_out = side ? ioff : eoff;
-        uint32_t *total_out = side ? isum_out : msgs_out;
-        if (!meta || !off_out) continue;                   // (kernel arguments: the same for every thread)
-        __syncthreads();
-        if (tid == 0) carry = 0;
-        __syncthreads();
-        for (uint32_t base = 0; base < count; base += 1024) {
-            uint32_t i = base + tid;
-            uint32_t deg = (i < count) ? meta[list[i]].y : 0u;
-            uint32_t inc = deg;
-            for (int o = 1; o < 64; o <<= 1) {
-                uint32_t t = __shfl_up(inc, o);
-                if (lane >= o) inc += t;
-            }
-            if (lane == 63) ws[wave] = inc;
-            __syncthreads();
-            uint32_t off = carry;
-            for (int k = 0; k < wave; ++k) off += ws[k];
-            if (i < count) off_out[i] = off + inc - deg;
-            __syncthreads();
-            if (tid == 1023) carry = off + inc;
-            __syncthreads();
+    const bool want_o = eoff != nullptr, want_i = in_meta != nullptr && ioff != nullptr;   // kernel arguments: uniform
+    if (tid == 0) {
+        carry_o = 0;
+        carry_i = 0;
+    }
+    __syncthreads();
+    for (uint32_t base = 0; base < count; base += 1024 * EOFF_PER) {
+        const uint32_t i0 = base + tid * EOFF_PER;
+        uint32_t v[EOFF_PER], dgo[EOFF_PER], dgi[EOFF_PER];
+#pragma unroll
+        for (int k = 0; k < EOFF_PER; ++k) v[k] = (i0 + k < count) ? list[i0 + k] : 0u;
+        uint32_t so = 0, si = 0;
+#pragma unroll
+        for (int k = 0; k < EOFF_PER; ++k) {
+            const bool on = i0 + k < count;
+            dgo[k] = (on && want_o) ? out_meta[v[k]].y : 0u;
+            dgi[k] = (on && want_i) ? in_meta[v[k]].y : 0u;
+            so += dgo[k];
+            si += dgi[k];
         }
-        if (tid == 0) {
-            off_out[count] = carry;
-            if (total_out) *total_out = carry;
+        uint32_t inc_o = so, inc_i = si;
+        for (int o = 1; o < 64; o <<= 1) {
+            const uint32_t to = __shfl_up(inc_o, o), ti = __shfl_up(inc_i, o);
+            if (lane >= o) {
+                inc_o += to;
+                inc_i += ti;
+            }
+        }
+        if (lane == 63) {
+            wo[wave] = inc_o;
+            wi[wave] = inc_i;
+        }
+        __syncthreads();
+        uint32_t off_o = carry_o, off_i = carry_i;
+        for (int k = 0; k < wave; ++k) {
+            off_o += wo[k];
+            off_i += wi[k];
+        }
+        uint32_t run_o = off_o + inc_o - so, run_i = off_i + inc_i - si;
+#pragma unroll
+        for (int k = 0; k < EOFF_PER; ++k) {
+            if (i0 + k < count) {
+                if (want_o) eoff[i0 + k] = run_o;
+                if (want_i) ioff[i0 + k] = run_i;
+            }
+            run_o += dgo[k];
+            run_i += dgi[k];
+        }
+        __syncthreads();
+        if (tid == 1023) {
+            carry_o = off_o + inc_o;
+            carry_i = off_i + inc_i;
+        }
+        __syncthreads();
+    }
+    if (tid == 0) {
+        if (want_o) {
+            eoff[count] = carry_o;
+            if (msgs_out) *msgs_out = carry_o;
+        }
+        if (want_i) {
+            ioff[count] = carry_i;
+            if (isum_out) *isum_out = carry_i;
         }
     }
 }
