@@ -783,3 +783,26 @@ def test_small_frontiers_listed_while_marking(kind, widths, weighted):
     finally:
         pair.close()
         twin.close()
+
+
+def test_small_frontier_hint_that_turns_out_wrong():
+    """Single-update batches: after two that touch a leaf, one rewrites the features of the vertex with the
+    most out-neighbours (thousands), so the list-while-marking path, chosen on the previous batch's sizes,
+    has to carry a set far beyond what it was meant for; then back to a leaf."""
+    print("case sparse frontier, wrong hint", flush=True)
+    pair, graph = make_pair(n=20000, e=240000, d0=16, kind="sage_mean", widths=(16, 24, 8), seed=291, slack=64, top_share=0.04)
+    try:
+        deg_out, _ = rp.ripple_get_degrees(pair.ctx, 0, pair.cap)
+        hub = int(np.argmax(deg_out))
+        leaves = [int(v) for v in np.flatnonzero((deg_out > 0) & (deg_out <= 3))[:6]]
+        assert deg_out[hub] > 4096
+        rng = np.random.default_rng(293)
+        for b, v in enumerate([leaves[0], leaves[1], hub, leaves[2], hub, hub, leaves[3]]):
+            print(" batch", b, "vertex", v, "out-degree", int(deg_out[v]), flush=True)
+            ops = np.array([(ri.OP_FEAT_UPDATE, v, 0, 0)], dtype=np.uint32)
+            res, _, sets = pair.step(ops, rng.standard_normal((1, 16)).astype(np.float32))
+            if v == hub:
+                assert res.affected[1] > 4096
+        pair.check_aggregates()
+    finally:
+        pair.close()
