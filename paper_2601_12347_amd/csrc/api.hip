@@ -685,6 +685,14 @@ static bool layer_self(const ripple_ctx *c, uint32_t l) {
     return c->layers[l - 1].self_mode != RIPPLE_SELF_NONE || rp_layer_attn(c, l);
 }
 
+// Hop l's set (and the previous hop's) was small in the previous batch, which was of about this size: the
+// hop lists its vertices while marking them instead of scanning the bitmap. Only a choice between two
+// correct paths.
+static bool small_frontier(const ripple_ctx *c, uint32_t l, uint32_t n_ops, bool multi) {
+    return c->opt_sparse && !multi && c->last_a[l] <= SPARSE_MAX_ROWS && c->last_a[l - 1] <= SPARSE_MAX_ROWS &&
+           c->last_m[l] <= SPARSE_MAX_EDGES && c->last_n_ops && n_ops <= 2 * c->last_n_ops;
+}
+
 // Enqueue one conflict-free piece: Apply, then hop by hop frontier / scatter / transform.
 static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
     const uint32_t n = sb.end - sb.begin;
@@ -750,12 +758,18 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
             rp_launch_gat_project(c, l, c->list[l - 1], &c->ctr->a[l - 1]);
             rp_launch_gat_scores(c, l, c->list[l - 1], &c->ctr->a[l - 1]);
             rp_timer_end(c, t, RIPPLE_PH_OTHER, (int)l);
-            t = rp_timer_begin(c);
-            rp_launch_frontier_mark(c, l, false);
-            rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
-            t = rp_timer_begin(c);
-            rp_launch_frontier_compact(c, l, true, l < c->L, false, multi);
-            rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l);
+            if (small_frontier(c, l, n, multi)) {
+                t = rp_timer_begin(c);
+                rp_launch_frontier_sparse(c, l, true, l < c->L);
+                rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
+            } else {
+                t = rp_timer_begin(c);
+                rp_launch_frontier_mark(c, l, false);
+                rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
+                t = rp_timer_begin(c);
+                rp_launch_frontier_compact(c, l, true, l < c->L, false, multi);
+                rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l);
+            }
             t = rp_timer_begin(c);
             rp_launch_gat_scatter(c, l, false);
             rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l);
@@ -774,9 +788,7 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
         const bool may_pull = wsum || (l >= 2 && c->opt_scatter != 1 && !(c->opt_scatter == 0 && c->push_margin[l]));
         const bool may_disc = l >= 2 && may_pull && (c->opt_scatter == 3 || ((c->opt_scatter == 0 || wsum) && c->disc_near[l]));
         // a frontier that was small last time (and a batch of about the same size) is listed as it is marked
-        const bool sparse = c->opt_sparse && !multi && !may_disc && c->last_a[l] <= SPARSE_MAX_ROWS &&
-                            c->last_a[l - 1] <= SPARSE_MAX_ROWS && c->last_m[l] <= SPARSE_MAX_EDGES &&
-                            c->last_n_ops && n <= 2 * c->last_n_ops;
+        const bool sparse = !may_disc && small_frontier(c, l, n, multi);
         t = rp_timer_begin(c);
         if (may_disc && !have_all) {
             rp_launch_alive_list(c);
