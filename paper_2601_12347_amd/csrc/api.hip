@@ -494,6 +494,8 @@ extern "C" ripple_status ripple_full_infer(ripple_ctx *c) {
     RP_HIP(c, hipStreamSynchronize(c->stream));
     RP_HIP(c, hipGetLastError());
     for (uint32_t l = 0; l <= c->L; ++l) c->last_a[l] = 0;
+    c->hints_valid = false;
+    c->last_n_ops = 0;
     c->last_from_rep = false;
     c->state = 3;
     return RIPPLE_OK;
@@ -944,6 +946,7 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
         if (!multi)
             for (uint32_t l = 0; l <= c->L; ++l) c->last_a[l] = h.a[l];
         c->last_n_ops = multi ? 0u : n;
+        c->hints_valid = !multi;
     }
     c->payload_d = payload_saved;
     if (rc != RIPPLE_OK) return rc;

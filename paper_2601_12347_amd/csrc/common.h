@@ -149,6 +149,7 @@ struct ripple_ctx {
 
     // last batch's sets (reporting)
     uint32_t last_a[RIPPLE_MAX_LAYERS + 1] = {0};
+    bool hints_valid = false;                           // last_a / last_cand describe a batch (not the state after the bootstrap)
     uint32_t last_cand[RIPPLE_MAX_LAYERS + 1] = {0};
     uint32_t last_m[RIPPLE_MAX_LAYERS + 1] = {0};       // messages per hop of the last batch (a size hint)
     uint32_t last_n_ops = 0;                            // operations of the last single-piece batch    // candidates of the last batch's max / min hops (a size hint)
@@ -182,6 +183,9 @@ struct ripple_ctx {
     } while (0)
 
 // scatter policy of hop l as the kernels see it (see rp_hop_mode)
+// |A_l| of the previous batch as a hint for launch shapes (tile sizes, grids, which compaction kernel); before
+// the first batch nothing is known and the shapes for large sets are taken, which are never far off
+static inline uint32_t rp_rows_hint(const ripple_ctx *c, uint32_t l) { return c->hints_valid ? c->last_a[l] : c->n_cap; }
 static inline bool rp_layer_mono(const ripple_ctx *c, uint32_t l) {      // layer l (1-based) aggregates with max or min
     return l >= 1 && l <= c->L && (c->layers[l - 1].agg == RIPPLE_AGG_MAX || c->layers[l - 1].agg == RIPPLE_AGG_MIN);
 }

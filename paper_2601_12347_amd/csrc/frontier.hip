@@ -565,7 +565,7 @@ void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool 
     a.count_out = &c->ctr->a[l];
     a.msgs_out = (l < RIPPLE_MAX_LAYERS) ? &c->ctr->m[l + 1] : nullptr;
     a.isum_out = &c->ctr->isum[l];
-    launch_compact(c, a, c->last_a[l]);
+    launch_compact(c, a, rp_rows_hint(c, l));
 }
 
 // Candidates of a max / min hop: the vertices marked by the out-edge walk from A_{l-1}, S and V_added,
@@ -588,7 +588,7 @@ void rp_launch_candidates(ripple_ctx *c, uint32_t l) {
     a.touched_out = &c->ctr->touched[l];
     a.list = c->all_list;
     a.count_out = &c->ctr->n_all;
-    launch_compact(c, a, c->last_cand[l]);
+    launch_compact(c, a, c->hints_valid ? c->last_cand[l] : c->n_cap);
 }
 
 // any bitmap & alive -> ascending list in `out_list`, count in *count_d (device)

@@ -1054,11 +1054,13 @@ static void launch_fast(ripple_ctx *c, const TArgs &a, bool narrow, uint32_t row
     if (rows_hint <= 32 && a.Npad % 128 == 0) {
         // a handful of rows: one 32-row tile, four wavefronts side by side on 32 columns each, so that the
         // chain of dependent matrix-core operations per K step is a quarter of the 128 x 64 tile's
-        hipLaunchKernelGGL((k_transform_f32<1, 4, 1, 1, 3, MODE, STORE>), dim3(8, a.Npad / 128), dim3(256), 0, c->stream, a);
+        // (the grid does not follow the hint: workgroups without a tile leave at once, and a set that turns out
+        // large still finds the whole chip)
+        hipLaunchKernelGGL((k_transform_f32<1, 4, 1, 1, 3, MODE, STORE>), dim3(c->n_cu / 4, a.Npad / 128), dim3(256), 0, c->stream, a);
         return;
     }
     if (rows_hint <= 2048) {                               // few rows: 64 x 64 tiles, one 32 x 32 block per wavefront
-        hipLaunchKernelGGL((k_transform_f32<2, 2, 1, 1, 3, MODE, STORE>), dim3(std::max(8u, rows_hint / 64 + 1), a.Npad / 64),
+        hipLaunchKernelGGL((k_transform_f32<2, 2, 1, 1, 3, MODE, STORE>), dim3(c->n_cu / 4, a.Npad / 64),
                            dim3(256), 0, c->stream, a);
         return;
     }
@@ -1170,7 +1172,7 @@ void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
     } else {
         a.a_mode = 4;
     }
-    launch_t(c, a, ly.d_in % 4 == 0, from_deltas ? c->last_a[l - 1] : c->n_cap);
+    launch_t(c, a, ly.d_in % 4 == 0, from_deltas ? rp_rows_hint(c, l - 1) : c->n_cap);
 }
 
 // Attention layer l: P[v] = H^{l-1}[v] W0 for the listed vertices (fp32, no bias, no activation).
@@ -1186,7 +1188,7 @@ void rp_launch_gat_project(ripple_ctx *c, uint32_t l, const uint32_t *list, cons
     a.tmp_out = ly.P;
     a.tmp_out_ld = ly.d_out;
     a.Hout = nullptr;
-    launch_t(c, a, ly.d_in % 4 == 0, (list == c->all_list) ? c->n_cap : c->last_a[l - 1]);
+    launch_t(c, a, ly.d_in % 4 == 0, (list == c->all_list) ? c->n_cap : rp_rows_hint(c, l - 1));
 }
 
 // Cached self term of layer l: PS[v] = H^{l-1}[v] W_self for the listed vertices (fp32, no bias).
@@ -1205,7 +1207,7 @@ void rp_launch_self_project(ripple_ctx *c, uint32_t l, const uint32_t *list, con
     a.tmp_out = ly.PS;
     a.tmp_out_ld = ly.d_out;
     a.Hout = nullptr;
-    launch_t(c, a, ly.d_in % 4 == 0, (list == c->all_list) ? c->n_cap : c->last_a[l - 1]);
+    launch_t(c, a, ly.d_in % 4 == 0, (list == c->all_list) ? c->n_cap : rp_rows_hint(c, l - 1));
 }
 
 // Re-apply layer l (1-based) to the vertices in `list` (count on the device).
@@ -1218,7 +1220,7 @@ void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const 
     a.a_mode = (ly.self_mode == RIPPLE_SELF_NONE) ? 0 : (ly.self_mode == RIPPLE_SELF_CONCAT ? 1 : 2);
     const bool vec_in = (ly.d_in % 4 == 0);
     // expected row count: the previous batch's (bootstrap passes the list of all live vertices)
-    const uint32_t hint = (list == c->all_list) ? c->n_cap : c->last_a[l];
+    const uint32_t hint = (list == c->all_list) ? c->n_cap : rp_rows_hint(c, l);
     if (ly.agg == RIPPLE_AGG_ATTN) {             // h = act(numerator / denominator + b): no product left per row
         a.addend = c->X[l];
         a.den = ly.den;
