@@ -731,19 +731,23 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
     }
     for (uint32_t l = 1; l <= c->L; ++l) {
         if (rp_layer_mono(c, l)) {                     // max / min: keep, raise or recompute, then prune (Sec. 3.4.2)
+            const bool listed = small_frontier(c, l, n, multi) && c->last_cand[l] <= SPARSE_MAX_ROWS;
             t = rp_timer_begin(c);
-            rp_launch_frontier_mark(c, l, false);
+            if (listed) rp_launch_candidates_sparse(c, l);
+            else rp_launch_frontier_mark(c, l, false);
             rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
-            t = rp_timer_begin(c);
-            rp_launch_candidates(c, l);
-            rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l, false);
+            if (!listed) {
+                t = rp_timer_begin(c);
+                rp_launch_candidates(c, l);
+                rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l, false);
+            }
             if (c->layers[l - 1].selfc) {
                 t = rp_timer_begin(c);
                 rp_launch_self_project(c, l, c->list[l - 1], &c->ctr->a[l - 1]);
                 rp_timer_end(c, t, RIPPLE_PH_OTHER, (int)l);
             }
             t = rp_timer_begin(c);
-            rp_launch_scatter_mono(c, l);
+            rp_launch_scatter_mono(c, l, listed ? &c->ctr->cand[l] : &c->ctr->n_all);
             rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l);
             t = rp_timer_begin(c);
             rp_launch_frontier_compact(c, l, layer_self(c, l), l < c->L, false, multi, true);

@@ -216,7 +216,7 @@ void rp_launch_gat_scatter(ripple_ctx *c, uint32_t l, bool bootstrap) {
     a.list = bootstrap ? c->all_list : c->list[l];
     a.count_ptr = bootstrap ? &c->ctr->a[0] : &c->ctr->a[l];
     a.queue = bootstrap ? c->list[0] : c->all_list;     // scratch that is free at that point
-    a.queue_count = &c->ctr->n_long;
+    a.queue_count = &c->ctr->n_long[l];
     a.in_meta = c->in_meta;
     a.in_pool = c->in_pool;
     a.bm_prev = c->bm[l - 1];
@@ -231,10 +231,10 @@ void rp_launch_gat_scatter(ripple_ctx *c, uint32_t l, bool bootstrap) {
     a.X = c->X[l];
     a.den = ly.den;
     a.all = bootstrap ? 1 : 0;
-    hipMemsetAsync(&c->ctr->n_long, 0, 4, c->stream);
+    if (bootstrap) hipMemsetAsync(&c->ctr->n_long[l], 0, 4, c->stream);   // a batch starts with it cleared
     GatArgs b = a;
     b.list = a.queue;
-    b.count_ptr = &c->ctr->n_long;
+    b.count_ptr = &c->ctr->n_long[l];
     dim3 grid(c->n_cu * 8), block(256);
 #define GAT_CASE(NJ, TEAM)                                                                                   \
     do {                                                                                                     \

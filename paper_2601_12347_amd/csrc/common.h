@@ -40,7 +40,8 @@ struct DevCtr {                      // device-resident counters, one instance p
     uint32_t n_vadd;
     uint32_t abort_flag;                      // written by k_capacity's last workgroup: 0 ok, bit0 pool, bit1 edges, bit2 scratch
     uint32_t n_all;                           // live vertices listed for a discovering hop
-    uint32_t n_long;                          // max / min hops: candidates with long in-rows queued for the workgroup kernel
+    uint32_t n_long[RIPPLE_MAX_LAYERS + 1];   // max / min and attention hops: vertices with long in-rows queued for the workgroup kernel
+    uint32_t cand[RIPPLE_MAX_LAYERS + 1];     // max / min hops: candidates listed while they were marked (small hops)
     uint32_t mono[3][RIPPLE_MAX_LAYERS + 1];  // max / min hops: candidates left unchanged / raised from the messages / recomputed
     unsigned long long n_edges;
     uint32_t blocks_done;                     // workgroups of k_capacity that have finished (0 between launches)

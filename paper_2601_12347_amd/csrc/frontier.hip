@@ -614,15 +614,12 @@ void rp_launch_list_eoff(ripple_ctx *c, uint32_t l) {
                        (const uint2 *)nullptr, (uint32_t *)nullptr, (uint32_t *)nullptr);
 }
 
-// Hop l for a small frontier: out-edge walk from A_{l-1} and the roots (S, V_added, A_{l-1} when self_term)
-// straight into bm[l] and list[l] (unordered), then the degree prefixes over that list. Two launches
-// instead of the walk plus a scan of the whole bitmap.
-void rp_launch_frontier_sparse(ripple_ctx *c, uint32_t l, bool self_term, bool want_out) {
+static SparseArgs sparse_args(ripple_ctx *c, uint32_t l, uint32_t *list, uint32_t *count, bool self_term) {
     SparseArgs sp;
     sp.bm = c->bm[l];
     sp.alive = c->alive;
-    sp.list = c->list[l];
-    sp.count = &c->ctr->a[l];
+    sp.list = list;
+    sp.count = count;
     sp.touched = &c->ctr->touched[l];
     sp.st_dst = c->st_dst;
     sp.n_struct = &c->ctr->n_struct;
@@ -631,6 +628,22 @@ void rp_launch_frontier_sparse(ripple_ctx *c, uint32_t l, bool self_term, bool w
     sp.count0 = &c->ctr->a[0];
     sp.bm_vadd = c->bm_vadd;
     sp.self_term = self_term ? 1 : 0;
+    return sp;
+}
+
+// Candidates of a small max / min hop, listed while they are marked: the set of rp_launch_candidates in
+// bm[l] and, unordered, in c->all_list, count in ctr->cand[l] (zero since the batch began).
+void rp_launch_candidates_sparse(ripple_ctx *c, uint32_t l) {
+    const SparseArgs sp = sparse_args(c, l, c->all_list, &c->ctr->cand[l], false);
+    hipLaunchKernelGGL(k_frontier_sparse, dim3(c->n_cu), dim3(256), 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],
+                       c->eoff[l - 1], c->out_meta, c->out_pool, sp);
+}
+
+// Hop l for a small frontier: out-edge walk from A_{l-1} and the roots (S, V_added, A_{l-1} when self_term)
+// straight into bm[l] and list[l] (unordered), then the degree prefixes over that list. Two launches
+// instead of the walk plus a scan of the whole bitmap.
+void rp_launch_frontier_sparse(ripple_ctx *c, uint32_t l, bool self_term, bool want_out) {
+    const SparseArgs sp = sparse_args(c, l, c->list[l], &c->ctr->a[l], self_term);
     hipLaunchKernelGGL(k_frontier_sparse, dim3(c->n_cu), dim3(256), 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],
                        c->eoff[l - 1], c->out_meta, c->out_pool, sp);
     hipLaunchKernelGGL(k_list_eoff, dim3(1), dim3(1024), 0, c->stream, c->list[l], &c->ctr->a[l], c->out_meta,

@@ -867,13 +867,13 @@ __global__ __launch_bounds__(TEAM * 64) void k_scatter_mono_long(MonoArgs a) {
     }
 }
 
-// candidates in c->all_list / ctr->n_all (rp_launch_candidates); D[(l-1)&1] holds the pre-batch rows of A_{l-1}
-void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l) {
+// candidates in c->all_list, *count_ptr of them (rp_launch_candidates[_sparse]); D[(l-1)&1] holds the pre-batch rows of A_{l-1}
+void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l, const uint32_t *count_ptr) {
     MonoArgs a;
     a.list = c->all_list;
-    a.count_ptr = &c->ctr->n_all;
+    a.count_ptr = count_ptr;
     a.queue = c->list[l];                       // not written before the hop's set is compacted
-    a.queue_count = &c->ctr->n_long;
+    a.queue_count = &c->ctr->n_long[l];         // zero since the batch began
     a.in_meta = c->in_meta;
     a.in_pool = c->in_pool;
     a.bm_prev = c->bm[l - 1];
@@ -887,10 +887,9 @@ void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l) {
     a.keep_prev = c->layers[l - 1].self_mode != RIPPLE_SELF_NONE ? 1 : 0;
     a.ctr = c->ctr;
     a.l = l;
-    hipMemsetAsync(&c->ctr->n_long, 0, 4, c->stream);
     MonoArgs b = a;
     b.list = a.queue;
-    b.count_ptr = &c->ctr->n_long;
+    b.count_ptr = &c->ctr->n_long[l];
     const bool is_min = c->layers[l - 1].agg == RIPPLE_AGG_MIN;
     dim3 grid(c->n_cu * 8), block(256);
 #define MONO_PAIR(NJ, MN, ST, TEAM)                                                                          \

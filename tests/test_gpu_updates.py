@@ -759,7 +759,8 @@ def test_attention_scores_that_drop_by_many_orders_of_magnitude():
 
 @pytest.mark.parametrize("kind,widths,weighted", [("sage_mean", (16, 40, 24, 10), False), ("gcn_sum", (100, 256, 47), False),
                                                   ("gin_sum", (12, 20, 8), False), ("gcn_wsum", (12, 20, 8), True),
-                                                  ("gat", (12, 20, 8), False)])
+                                                  ("gat", (12, 20, 8), False), ("gcn_max", (12, 20, 8), False),
+                                                  ("sage_min", (12, 20, 8, 6), False)])
 def test_small_frontiers_listed_while_marking(kind, widths, weighted):
     """Hops whose sets were small in the previous batch build their list while marking (unordered, no bitmap
     scan). Small batches of steady size take that path from the second batch on; a much larger batch in
