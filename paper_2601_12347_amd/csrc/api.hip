@@ -254,7 +254,7 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
     hipStreamSynchronize(c->stream);
     void *ptrs[] = {c->out_meta, c->in_meta, c->out_capv, c->in_capv, c->vstate, c->pend_out, c->pend_in, c->dead_out,
                     c->dead_in, c->hole_out, c->hole_in, c->out_pool, c->in_pool, c->in_w, c->alive, c->part_cnt, c->part_deg, c->part_ideg, c->ioff[0], c->ctr, c->D[0], c->D[1],
-                    c->tmp, c->PD, c->Pold, c->sold, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ioff_all, c->mk, c->ops_d, c->payload_d,
+                    c->tmp, c->PD, c->Pold, c->sold, c->seg_v, c->seg_done, c->seg_base, c->seg_r, c->seg_part, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ioff_all, c->mk, c->ops_d, c->payload_d,
                     c->op_status, c->op_pos_out, c->op_pos_in, c->op_touch, c->touch_out, c->touch_in, c->exp_kind, c->exp_s, c->exp_a,
                     c->exp_b, c->st_src, c->st_dst, c->st_sign, c->gather_d, c->gather_ids};
     for (void *p : ptrs)
@@ -426,6 +426,21 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
         if (aw) {
             RP_TRY(dev_alloc(c, &c->Pold, n * aw, true));
             RP_TRY(dev_alloc(c, &c->sold, n, true));
+        }
+    }
+    {
+        uint32_t mw = 0;                                 // widest max / min aggregate
+        for (uint32_t l = 1; l <= c->L; ++l)
+            if (rp_layer_mono(c, l)) mw = std::max(mw, c->xw[l]);
+        if (mw) {                                        // in-rows sum to at most the pool: that bounds rows and segments
+            c->big_cap = (uint32_t)std::min<uint64_t>(c->pool_cap / ROW_SPLIT_MIN + 1, 1u << 30);
+            c->seg_cap = (uint32_t)std::min<uint64_t>(c->pool_cap / ROW_SEG + c->big_cap, 1u << 30);
+            c->seg_ld = rp_round_up(mw, 32);             // partial rows share no 128-byte line
+            RP_TRY(dev_alloc(c, &c->seg_v, c->big_cap, false));
+            RP_TRY(dev_alloc(c, &c->seg_done, c->big_cap, false));
+            RP_TRY(dev_alloc(c, &c->seg_base, c->big_cap, false));
+            RP_TRY(dev_alloc(c, &c->seg_r, c->seg_cap, false));
+            RP_TRY(dev_alloc(c, &c->seg_part, (size_t)c->seg_cap * c->seg_ld, false));
         }
     }
     RP_TRY(dev_alloc(c, &c->D[0], n * c->dmax, false));
@@ -733,7 +748,7 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
         if (rp_layer_mono(c, l)) {                     // max / min: keep, raise or recompute, then prune (Sec. 3.4.2)
             const bool listed = small_frontier(c, l, n, multi) && c->last_cand[l] <= SPARSE_MAX_ROWS;
             t = rp_timer_begin(c);
-            if (listed) rp_launch_candidates_sparse(c, l);
+            if (listed) rp_launch_candidates_sparse(c, l, layer_self(c, l));
             else rp_launch_frontier_mark(c, l, false);
             rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
             if (!listed) {
@@ -747,10 +762,11 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
                 rp_timer_end(c, t, RIPPLE_PH_OTHER, (int)l);
             }
             t = rp_timer_begin(c);
-            rp_launch_scatter_mono(c, l, listed ? &c->ctr->cand[l] : &c->ctr->n_all);
+            rp_launch_scatter_mono(c, l, listed ? &c->ctr->cand[l] : &c->ctr->n_all, listed);
             rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l);
             t = rp_timer_begin(c);
-            rp_launch_frontier_compact(c, l, layer_self(c, l), l < c->L, false, multi, true);
+            if (listed) rp_launch_list_offsets(c, l, l < c->L);  // the aggregation kernels listed what stays
+            else rp_launch_frontier_compact(c, l, layer_self(c, l), l < c->L, false, multi, true);
             rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l);
             t = rp_timer_begin(c);
             rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], l < c->L);

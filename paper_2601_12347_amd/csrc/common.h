@@ -42,6 +42,8 @@ struct DevCtr {                      // device-resident counters, one instance p
     uint32_t n_all;                           // live vertices listed for a discovering hop
     uint32_t n_long[RIPPLE_MAX_LAYERS + 1];   // max / min and attention hops: vertices with long in-rows queued for the workgroup kernel
     uint32_t cand[RIPPLE_MAX_LAYERS + 1];     // max / min hops: candidates listed while they were marked (small hops)
+    uint32_t n_big[RIPPLE_MAX_LAYERS + 1];    // very long in-rows whose recomputation was split into segments
+    uint32_t n_seg[RIPPLE_MAX_LAYERS + 1];    // segments queued for them
     uint32_t mono[3][RIPPLE_MAX_LAYERS + 1];  // max / min hops: candidates left unchanged / raised from the messages / recomputed
     unsigned long long n_edges;
     uint32_t blocks_done;                     // workgroups of k_capacity that have finished (0 between launches)
@@ -49,6 +51,10 @@ struct DevCtr {                      // device-resident counters, one instance p
     uint32_t error;                           // sticky consistency error seen by a kernel
     uint32_t pad1;
 };
+
+#define ROW_SPLIT_MIN 2048u
+#define ROW_SEG 1024u
+#define SEG_NONE 0xffffffffu
 
 struct LayerDev {
     uint32_t d_in, d_hidden, d_out, K;        // K = rows of W0
@@ -107,6 +113,12 @@ struct ripple_ctx {
     float *D[2] = {nullptr, nullptr};                   // delta rows D^l[v] (valid for v in A_l), ping-pong
     float *tmp = nullptr;                               // hidden activations of two-stage updates
     float *PD = nullptr;                                // projected rows of project-first layers
+    // max / min (and attention) hops: in-rows of ROW_SPLIT_MIN entries or more are recomputed in segments of ROW_SEG
+    // entries, one workgroup each. Per split row: vertex, segments finished, first segment; per segment: its row's
+    // slot and its partial result (seg_ld floats)
+    uint32_t *seg_v = nullptr, *seg_done = nullptr, *seg_base = nullptr, *seg_r = nullptr;
+    float *seg_part = nullptr;
+    uint32_t big_cap = 0, seg_cap = 0, seg_ld = 0;
     float *Pold = nullptr, *sold = nullptr;             // attention hops: projected rows / source scores of A_{l-1} before the batch
     uint32_t xw[RIPPLE_MAX_LAYERS + 1] = {0};           // width of X^l (d_{l-1}, or d_l when projected)
     uint32_t pd_ld = 0;                                 // row stride of PD (64-byte multiple)

@@ -631,10 +631,11 @@ static SparseArgs sparse_args(ripple_ctx *c, uint32_t l, uint32_t *list, uint32_
     return sp;
 }
 
-// Candidates of a small max / min hop, listed while they are marked: the set of rp_launch_candidates in
-// bm[l] and, unordered, in c->all_list, count in ctr->cand[l] (zero since the batch began).
-void rp_launch_candidates_sparse(ripple_ctx *c, uint32_t l) {
-    const SparseArgs sp = sparse_args(c, l, c->all_list, &c->ctr->cand[l], false);
+// Candidates of a small max / min hop, listed while they are marked: the set of rp_launch_candidates
+// (with A_{l-1} when the layer has a self term) in bm[l] and, unordered, in c->all_list, count in
+// ctr->cand[l] (zero since the batch began).
+void rp_launch_candidates_sparse(ripple_ctx *c, uint32_t l, bool self_term) {
+    const SparseArgs sp = sparse_args(c, l, c->all_list, &c->ctr->cand[l], self_term);
     hipLaunchKernelGGL(k_frontier_sparse, dim3(c->n_cu), dim3(256), 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],
                        c->eoff[l - 1], c->out_meta, c->out_pool, sp);
 }
@@ -646,6 +647,11 @@ void rp_launch_frontier_sparse(ripple_ctx *c, uint32_t l, bool self_term, bool w
     const SparseArgs sp = sparse_args(c, l, c->list[l], &c->ctr->a[l], self_term);
     hipLaunchKernelGGL(k_frontier_sparse, dim3(c->n_cu), dim3(256), 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],
                        c->eoff[l - 1], c->out_meta, c->out_pool, sp);
+    rp_launch_list_offsets(c, l, want_out);
+}
+
+// degree prefixes over the (unordered) list of hop l
+void rp_launch_list_offsets(ripple_ctx *c, uint32_t l, bool want_out) {
     hipLaunchKernelGGL(k_list_eoff, dim3(1), dim3(1024), 0, c->stream, c->list[l], &c->ctr->a[l], c->out_meta,
                        want_out ? c->eoff[l] : (uint32_t *)nullptr,
                        (want_out && l < RIPPLE_MAX_LAYERS) ? &c->ctr->m[l + 1] : (uint32_t *)nullptr, c->in_meta, c->ioff[l],

@@ -18,7 +18,8 @@ void rp_launch_alive_list(ripple_ctx *c);
 void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool want_out, bool want_in,
                                 bool accumulate_rep, bool pruned = false);
 void rp_launch_candidates(ripple_ctx *c, uint32_t l);
-void rp_launch_candidates_sparse(ripple_ctx *c, uint32_t l);
+void rp_launch_candidates_sparse(ripple_ctx *c, uint32_t l, bool self_term);
+void rp_launch_list_offsets(ripple_ctx *c, uint32_t l, bool want_out);
 void rp_launch_bitmap_to_list(ripple_ctx *c, uint32_t *bitmap, uint32_t *out_list, uint32_t *count_d);
 void rp_launch_list_eoff(ripple_ctx *c, uint32_t l);
 void rp_launch_frontier_sparse(ripple_ctx *c, uint32_t l, bool self_term, bool want_out);
@@ -28,7 +29,7 @@ void rp_launch_scatter_push(ripple_ctx *c, uint32_t l, bool may_pull, bool allow
 void rp_launch_scatter_owner(ripple_ctx *c, uint32_t l, bool bootstrap);
 void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow_disc);
 void rp_launch_pull_all(ripple_ctx *c, uint32_t l);
-void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l, const uint32_t *count_ptr);
+void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l, const uint32_t *count_ptr, bool listed);
 
 // attention.hip
 void rp_launch_gat_scatter(ripple_ctx *c, uint32_t l, bool bootstrap);

@@ -569,6 +569,9 @@ void rp_launch_scatter_owner(ripple_ctx *c, uint32_t l, bool bootstrap) {
 // depend on any order. One wavefront owns a candidate with up to MONO_LONG in-neighbours; longer
 // in-rows are queued and taken by a workgroup each.
 #define MONO_LONG 256u
+#define MONO_DIRTY_LIST 2048u     // changed in-neighbours of a long row remembered between counting and reading them
+#define MONO_EDGE_HITS 1024u      // changed edges of one sink kept as messages; more: recompute
+#define MONO_EDGE_SCAN 32768u     // longest list of changed edges a sink's workgroup searches; longer: recompute
 
 struct MonoArgs {
     const uint32_t *list;          // candidates (ascending), or the queue of long rows
@@ -586,6 +589,16 @@ struct MonoArgs {
     int keep_prev;                 // the layer reads the vertex's own row: members of A_{l-1} stay in the set
     DevCtr *ctr;
     uint32_t l;
+    // the batch's changed edges (source, sink, sign: < 0 deleted), read for sinks with long in-rows
+    const uint32_t *st_src, *st_dst;
+    const float *st_sign;
+    uint32_t struct_cap;
+    const uint32_t *alive;
+    uint32_t *out_list, *out_count; // small hops: the vertices that stay in the hop's set are appended here (or null)
+    // very long rows that are recomputed: split into segments for k_scatter_mono_seg
+    uint32_t *seg_v, *seg_done, *seg_base, *seg_r;
+    float *seg_part;
+    uint32_t big_cap, seg_cap, seg_ld;
 };
 
 template <int IS_MIN>
@@ -640,6 +653,39 @@ __device__ __forceinline__ bool mono_messages(const MonoArgs &a, uint32_t my_u, 
     return false;
 }
 
+// Messages of changed in-edges of one sink, held one per lane (u = source, deleted = the edge went away)
+// for the lanes in `mask`. A deleted edge sends its source's pre-batch row as a value that is gone: where
+// it equalled the aggregate the element may have lost its extreme. An added edge sends the source's
+// current row. Bit 31 of lostm: the pre-batch row is no longer there (the source was removed), recompute.
+template <int NJ, int IS_MIN, int STORE>
+__device__ __forceinline__ void mono_edge_messages(const MonoArgs &a, uint32_t my_u, bool my_deleted,
+                                                   unsigned long long mask, const float *xo, float *inc, uint32_t &lostm) {
+    const int lane = rp_lane();
+    const uint32_t d = a.d;
+    while (mask) {
+        const int k = __ffsll((long long)mask) - 1;
+        mask &= mask - 1;
+        const uint32_t u = __shfl(my_u, k);
+        const bool deleted = __shfl((int)my_deleted, k) != 0;
+        if (deleted && !rp_bit(a.alive, u)) {
+            lostm |= 1u << 31;
+            continue;
+        }
+        const bool from_old = deleted && rp_bit(a.bm_prev, u);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const uint32_t col = lane + 64 * j;
+            if (col >= d) continue;
+            const float r = from_old ? a.Dold[(size_t)u * d + col] : rp_load_h(a.Hprev, STORE, (size_t)u * d + col);
+            if (deleted) {
+                if (r == xo[j]) lostm |= 1u << j;
+            } else if (mono_better<IS_MIN>(r, inc[j])) {
+                inc[j] = r;
+            }
+        }
+    }
+}
+
 // best value per column over the rows of the `n_here` in-neighbours held one per lane in my_u, taken
 // from lane `first` on in steps of `step`
 template <int NJ, int IS_MIN, int STORE, int G>
@@ -650,11 +696,12 @@ __device__ __forceinline__ void mono_gather(const MonoArgs &a, uint32_t my_u, in
         float r[G][NJ];
 #pragma unroll
         for (int g = 0; g < G; ++g) {
-            const uint32_t u = __shfl(my_u, min(k0 + g, n_here - 1));       // the last one again: harmless for an extreme
+            const bool on = k0 + g < n_here;
+            const uint32_t u = __shfl(my_u, min(k0 + g, n_here - 1));
 #pragma unroll
             for (int j = 0; j < NJ; ++j) {
                 const uint32_t col = lane + 64 * j;
-                r[g][j] = (col < d) ? rp_load_h(a.Hprev, STORE, (size_t)u * d + col) : 0.0f;
+                r[g][j] = (on && col < d) ? rp_load_h(a.Hprev, STORE, (size_t)u * d + col) : xn[j];
             }
         }
 #pragma unroll
@@ -683,16 +730,19 @@ __device__ __forceinline__ bool mono_finish(const MonoArgs &a, uint32_t v, bool 
             const uint32_t col = lane + 64 * j;
             if (col < d) a.X[(size_t)v * d + col] = xn[j];
         }
-    } else if (!created && !(a.keep_prev && rp_bit(a.bm_prev, v))) {
+    }
+    if (!changed && !created && !(a.keep_prev && rp_bit(a.bm_prev, v))) {
         if (lane == 0) atomicAnd(&a.bm_cur[v >> 5], ~(1u << (v & 31)));
+    } else if (a.out_list && lane == 0) {
+        a.out_list[atomicAdd(a.out_count, 1u)] = v;
     }
     return changed;
 }
 
 template <int NJ, int IS_MIN, int STORE>
 __global__ __launch_bounds__(256) void k_scatter_mono(MonoArgs a) {
-    constexpr int GC = (NJ <= 1) ? 8 : (NJ <= 2 ? 4 : (NJ <= 4 ? 2 : 1));     // senders in flight (two rows each)
-    constexpr int GR = (NJ <= 1) ? 16 : (NJ <= 16 ? 16 / NJ : 1);             // rows in flight when recomputing
+    constexpr int GC = (NJ <= 4) ? 8 : 32 / NJ;                // senders in flight (two rows each)
+    constexpr int GR = (NJ <= 2) ? 32 : 64 / NJ;               // rows in flight when recomputing: round trips pace a row
     constexpr int T = MONO_LONG / 64;
     const uint32_t count = *a.count_ptr;
     const int lane = rp_lane();
@@ -763,13 +813,19 @@ __global__ __launch_bounds__(256) void k_scatter_mono(MonoArgs a) {
 // blocks w, w + TEAM, ...; the wavefronts' partial results meet in LDS and wavefront 0 finishes the row.
 template <int NJ, int IS_MIN, int STORE, int TEAM>
 __global__ __launch_bounds__(TEAM * 64) void k_scatter_mono_long(MonoArgs a) {
-    constexpr int GC = (NJ <= 1) ? 8 : (NJ <= 2 ? 4 : (NJ <= 4 ? 2 : 1));
-    constexpr int GR = (NJ <= 2) ? 16 : 32 / NJ;               // rows in flight: a long row is paced by round trips
+    constexpr int GC = (NJ <= 4) ? 8 : 32 / NJ;
+    constexpr int GR = (NJ <= 2) ? 32 : 64 / NJ;               // rows in flight: a long row is paced by round trips
     __shared__ float s_val[TEAM][NJ * 64];
     __shared__ uint32_t s_lost[TEAM][64];
-    __shared__ uint32_t s_cnt[TEAM];
+    constexpr int IDS = 4;                                     // blocks of in-neighbour ids in flight while counting
+    __shared__ uint32_t s_dirty[MONO_DIRTY_LIST];              // the changed in-neighbours of the row (while they fit)
+    __shared__ uint32_t s_nd;
     __shared__ uint32_t s_flag;
+    __shared__ uint32_t s_hit[MONO_EDGE_HITS];                 // the sink's entries in the list of changed edges
+    __shared__ uint32_t s_nhit;
+    __shared__ uint32_t s_base, s_slot;
     const uint32_t count = *a.count_ptr;
+    const uint32_t n_st = a.ctr->n_struct;
     const int lane = rp_lane(), wave = threadIdx.x >> 6;
     const uint32_t d = a.d;
     const float ident = IS_MIN ? INFINITY : -INFINITY;
@@ -783,37 +839,90 @@ __global__ __launch_bounds__(TEAM * 64) void k_scatter_mono_long(MonoArgs a) {
             const uint32_t col = lane + 64 * j;
             xo[j] = (col < d) ? a.X[(size_t)v * d + col] : 0.0f;
         }
-        // how many in-neighbours changed
-        uint32_t nd = 0;
-        for (uint32_t base = 64u * wave; base < m.y; base += 64u * TEAM) {
-            const uint32_t e = base + lane;
-            const uint32_t u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
-            nd += (uint32_t)__popcll(__ballot(e < m.y && rp_bit(a.bm_prev, u)));
+        // the in-neighbours that changed: counted, and listed in LDS while they fit (several blocks of ids
+        // are in flight per wavefront: the row is long and each block is two dependent reads)
+        if (threadIdx.x == 0) {
+            s_nd = 0;
+            s_nhit = 0;
         }
-        if (lane == 0) s_cnt[wave] = nd;
         __syncthreads();
-        nd = 0;
-        for (int w = 0; w < TEAM; ++w) nd += s_cnt[w];
-        bool recompute = created || rp_bit(a.bm_sink, v) || 2 * nd >= m.y;
+        for (uint32_t base = 64u * wave; base < m.y; base += 64u * TEAM * IDS) {
+            uint32_t u[IDS];
+            bool dirty[IDS];
+#pragma unroll
+            for (int t = 0; t < IDS; ++t) {
+                const uint32_t e = base + 64u * TEAM * t + lane;
+                u[t] = (e < m.y) ? a.in_pool[m.x + e] : 0u;
+            }
+#pragma unroll
+            for (int t = 0; t < IDS; ++t) {
+                const uint32_t e = base + 64u * TEAM * t + lane;
+                dirty[t] = e < m.y && rp_bit(a.bm_prev, u[t]);
+            }
+#pragma unroll
+            for (int t = 0; t < IDS; ++t) {
+                const unsigned long long mask = __ballot(dirty[t]);
+                if (!mask) continue;
+                uint32_t pos = 0;
+                if (lane == __ffsll((long long)mask) - 1) pos = atomicAdd(&s_nd, (uint32_t)__popcll(mask));
+                pos = __shfl(pos, __ffsll((long long)mask) - 1) + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull));
+                if (dirty[t] && pos < MONO_DIRTY_LIST) s_dirty[pos] = u[t];
+            }
+        }
+        __syncthreads();
+        const uint32_t nd = s_nd;
+        // A sink keeps its long row incremental when its changed edges can be looked up: each becomes a message.
+        bool recompute = created;
+        uint32_t ns = 0;
+        if (!recompute && rp_bit(a.bm_sink, v)) {
+            if (n_st > a.struct_cap || n_st > MONO_EDGE_SCAN) {
+                recompute = true;
+            } else {
+                for (uint32_t s = threadIdx.x; s < n_st; s += TEAM * 64)
+                    if (a.st_dst[s] == v) {
+                        const uint32_t k = atomicAdd(&s_nhit, 1u);
+                        if (k < MONO_EDGE_HITS) s_hit[k] = s;
+                    }
+                __syncthreads();
+                ns = s_nhit;
+                if (ns > MONO_EDGE_HITS) recompute = true;
+            }
+        }
+        if (2 * (nd + ns) >= m.y) recompute = true;            // old and new rows of the senders against every row once
         if (!recompute) {                                      // every wavefront looks at its share of the messages
             float inc[NJ];
             uint32_t lostm = 0;
 #pragma unroll
             for (int j = 0; j < NJ; ++j) inc[j] = ident;
-            for (uint32_t base = 64u * wave; base < m.y; base += 64u * TEAM) {
-                const uint32_t e = base + lane;
-                const uint32_t u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
-                const unsigned long long mask = __ballot(e < m.y && rp_bit(a.bm_prev, u));
-                if (mask) mono_messages<NJ, IS_MIN, STORE, GC>(a, u, mask, xo, inc, lostm, false);
+            if (nd <= MONO_DIRTY_LIST) {
+                for (uint32_t base = 64u * wave; base < nd; base += 64u * TEAM) {
+                    const uint32_t k = base + lane;
+                    const uint32_t u = (k < nd) ? s_dirty[k] : 0u;
+                    mono_messages<NJ, IS_MIN, STORE, GC>(a, u, __ballot(k < nd), xo, inc, lostm, false);
+                }
+            } else {
+                for (uint32_t base = 64u * wave; base < m.y; base += 64u * TEAM) {
+                    const uint32_t e = base + lane;
+                    const uint32_t u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
+                    const unsigned long long mask = __ballot(e < m.y && rp_bit(a.bm_prev, u));
+                    if (mask) mono_messages<NJ, IS_MIN, STORE, GC>(a, u, mask, xo, inc, lostm, false);
+                }
+            }
+            for (uint32_t base = 64u * wave; base < ns; base += 64u * TEAM) {
+                const uint32_t k = base + lane;
+                const uint32_t s = (k < ns) ? s_hit[k] : 0u;
+                const uint32_t u = (k < ns) ? a.st_src[s] : 0u;
+                const bool deleted = (k < ns) && a.st_sign[s] < 0.0f;
+                mono_edge_messages<NJ, IS_MIN, STORE>(a, u, deleted, __ballot(k < ns), xo, inc, lostm);
             }
 #pragma unroll
             for (int j = 0; j < NJ; ++j) s_val[wave][j * 64 + lane] = inc[j];
             s_lost[wave][lane] = lostm;
             __syncthreads();
             if (wave == 0) {
-                bool need = false;
                 lostm = 0;
                 for (int w = 0; w < TEAM; ++w) lostm |= s_lost[w][lane];
+                bool need = (lostm >> 31) != 0;
 #pragma unroll
                 for (int j = 0; j < NJ; ++j) {
                     float best = s_val[0][j * 64 + lane];
@@ -839,6 +948,29 @@ __global__ __launch_bounds__(TEAM * 64) void k_scatter_mono_long(MonoArgs a) {
             }
         }
         // recompute from all in-neighbours (m.y > MONO_LONG, so the row is not empty)
+        if (m.y >= ROW_SPLIT_MIN) {
+            // One compute unit reads a row of many thousand in-neighbours far too slowly: queue its segments,
+            // a workgroup each takes one, the last to finish combines them (k_scatter_mono_seg).
+            const uint32_t nseg = (m.y + ROW_SEG - 1) / ROW_SEG;
+            if (threadIdx.x == 0) {
+                const uint32_t r = atomicAdd(&a.ctr->n_big[a.l], 1u);
+                const uint32_t base = atomicAdd(&a.ctr->n_seg[a.l], nseg);
+                const bool fits = r < a.big_cap && base < a.seg_cap && nseg <= a.seg_cap - base;
+                if (fits) {
+                    a.seg_v[r] = v;
+                    a.seg_done[r] = 0;
+                    a.seg_base[r] = base;
+                }
+                s_base = base;
+                s_slot = fits ? r : SEG_NONE;
+            }
+            __syncthreads();
+            const uint32_t base = s_base, r = s_slot;
+            for (uint32_t k = threadIdx.x; k < nseg; k += TEAM * 64)
+                if (base < a.seg_cap && k < a.seg_cap - base) a.seg_r[base + k] = r;    // SEG_NONE: skipped there
+            __syncthreads();
+            if (r != SEG_NONE) continue;                       // (the capacities cover every row: not expected otherwise)
+        }
 #pragma unroll
         for (int j = 0; j < NJ; ++j) xn[j] = ident;
         for (uint32_t base = 64u * wave; base < m.y; base += 64u * TEAM) {
@@ -867,12 +999,87 @@ __global__ __launch_bounds__(TEAM * 64) void k_scatter_mono_long(MonoArgs a) {
     }
 }
 
+// One workgroup per queued segment of a very long row that is recomputed: the extreme over the segment's
+// ROW_SEG in-neighbours goes to the segment's partial row; the workgroup that finishes a row's last
+// segment takes the extreme over the partial rows and finishes the row.
+template <int NJ, int IS_MIN, int STORE, int TEAM>
+__global__ __launch_bounds__(TEAM * 64) void k_scatter_mono_seg(MonoArgs a) {
+    static_assert(TEAM * 64 == ROW_SEG, "one 64-entry block per wavefront");
+    constexpr int GR = (NJ <= 2) ? 32 : 64 / NJ;
+    __shared__ float s_val[TEAM][NJ * 64];
+    const uint32_t n_seg = min(a.ctr->n_seg[a.l], a.seg_cap);
+    const int lane = rp_lane(), wave = threadIdx.x >> 6;
+    const uint32_t d = a.d;
+    const float ident = IS_MIN ? INFINITY : -INFINITY;
+    for (uint32_t e = blockIdx.x; e < n_seg; e += gridDim.x) {
+        const uint32_t r = a.seg_r[e];
+        if (r == SEG_NONE) continue;
+        const uint32_t v = a.seg_v[r], first = a.seg_base[r];
+        const uint2 m = a.in_meta[v];
+        const uint32_t nseg = (m.y + ROW_SEG - 1) / ROW_SEG;
+        const uint32_t lo = (e - first) * ROW_SEG, hi = min(m.y, lo + ROW_SEG);
+        float xn[NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) xn[j] = ident;
+        const uint32_t b = lo + 64u * wave;
+        if (b < hi) {
+            const uint32_t u = (b + lane < hi) ? a.in_pool[m.x + b + lane] : 0u;
+            mono_gather<NJ, IS_MIN, STORE, GR>(a, u, (int)min(64u, hi - b), xn);
+        }
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) s_val[wave][j * 64 + lane] = xn[j];
+        __syncthreads();
+        if (wave == 0) {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                float best = s_val[0][j * 64 + lane];
+                for (int w = 1; w < TEAM; ++w) {
+                    const float x = s_val[w][j * 64 + lane];
+                    if (mono_better<IS_MIN>(x, best)) best = x;
+                }
+                const uint32_t col = lane + 64 * j;
+                if (col < d) a.seg_part[(size_t)e * a.seg_ld + col] = best;
+            }
+            __threadfence();                                   // the partial row is visible before the count moves
+            uint32_t last = 0;
+            if (lane == 0) last = (atomicAdd(&a.seg_done[r], 1u) == nseg - 1) ? 1u : 0u;
+            last = __shfl(last, 0);
+            if (last) {
+                __threadfence();
+                float xo[NJ];
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    const uint32_t col = lane + 64 * j;
+                    xo[j] = (col < d) ? a.X[(size_t)v * d + col] : 0.0f;
+                    xn[j] = ident;
+                }
+                for (uint32_t k = 0; k < nseg; ++k) {
+                    const float *part = a.seg_part + (size_t)(first + k) * a.seg_ld;
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) {
+                        const uint32_t col = lane + 64 * j;
+                        if (col < d) {                         // written by other compute units: read past this one's cache
+                            const float x = __hip_atomic_load(part + col, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            if (mono_better<IS_MIN>(x, xn[j])) xn[j] = x;
+                        }
+                    }
+                }
+                mono_finish<NJ>(a, v, rp_bit(a.bm_vadd, v), xo, xn);
+                if (lane == 0) atomicAdd(&a.ctr->mono[2][a.l], 1u);
+            }
+        }
+        __syncthreads();
+    }
+}
+
 // candidates in c->all_list, *count_ptr of them (rp_launch_candidates[_sparse]); D[(l-1)&1] holds the pre-batch rows of A_{l-1}
-void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l, const uint32_t *count_ptr) {
+void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l, const uint32_t *count_ptr, bool listed) {
     MonoArgs a;
     a.list = c->all_list;
     a.count_ptr = count_ptr;
-    a.queue = c->list[l];                       // not written before the hop's set is compacted
+    a.queue = listed ? c->eoff[l] : c->list[l]; // neither is written before the hop's set is final
+    a.out_list = listed ? c->list[l] : nullptr;
+    a.out_count = &c->ctr->a[l];                // zero since the batch began
     a.queue_count = &c->ctr->n_long[l];         // zero since the batch began
     a.in_meta = c->in_meta;
     a.in_pool = c->in_pool;
@@ -887,15 +1094,30 @@ void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l, const uint32_t *count_ptr
     a.keep_prev = c->layers[l - 1].self_mode != RIPPLE_SELF_NONE ? 1 : 0;
     a.ctr = c->ctr;
     a.l = l;
+    a.st_src = c->st_src;
+    a.st_dst = c->st_dst;
+    a.st_sign = c->st_sign;
+    a.struct_cap = c->in_w ? 0u : c->struct_cap;   // weighted graphs: the sign carries the weight, sinks recompute
+    a.alive = c->alive;
+    a.seg_v = c->seg_v;
+    a.seg_done = c->seg_done;
+    a.seg_base = c->seg_base;
+    a.seg_r = c->seg_r;
+    a.seg_part = c->seg_part;
+    a.big_cap = c->big_cap;
+    a.seg_cap = c->seg_cap;
+    a.seg_ld = c->seg_ld;
     MonoArgs b = a;
     b.list = a.queue;
     b.count_ptr = &c->ctr->n_long[l];
     const bool is_min = c->layers[l - 1].agg == RIPPLE_AGG_MIN;
-    dim3 grid(c->n_cu * 8), block(256);
+    // few candidates: every workgroup resident at once, so none waits for a slot behind one that holds a long chain of reads
+    dim3 grid(c->n_cu * ((c->hints_valid && c->last_cand[l] <= 8192u) ? 4 : 8)), block(256);
 #define MONO_PAIR(NJ, MN, ST, TEAM)                                                                          \
     do {                                                                                                     \
         hipLaunchKernelGGL((k_scatter_mono<NJ, MN, ST>), grid, block, 0, c->stream, a);                      \
         hipLaunchKernelGGL((k_scatter_mono_long<NJ, MN, ST, TEAM>), dim3(c->n_cu * 2), dim3(TEAM * 64), 0, c->stream, b); \
+        hipLaunchKernelGGL((k_scatter_mono_seg<NJ, MN, ST, 16>), dim3(c->n_cu * 2), dim3(1024), 0, c->stream, b); \
     } while (0)
 #define MONO_CASE(NJ, TEAM)                                                                                  \
     do {                                                                                                     \

@@ -471,6 +471,61 @@ def test_max_with_hub_rows_and_repeated_feature_updates():
         pair.close()
 
 
+@pytest.mark.parametrize("kind", ["gcn_max", "sage_min"])
+def test_max_min_changed_edges_of_a_hub_are_messages(kind):
+    """A sink with thousands of in-neighbours is not re-read for an edge that comes or goes (Sec. 3.4.2): an
+    added edge can only raise the extreme, a deleted one matters only if its source held it. Hand-made
+    batches aimed at the vertex with the longest in-row: additions only, deletions of sources that hold no
+    column's extreme, the deletion of one that does, then changed edges whose sources also change or vanish."""
+    print("case max/min hub sink", kind, flush=True)
+    pair, graph = make_pair(n=20000, e=240000, d0=24, kind=kind, widths=(24, 48, 12), seed=161, slack=64, top_share=0.04)
+    best = np.argmin if kind.endswith("min") else np.argmax
+    rng = np.random.default_rng(167)
+    try:
+        deg_in, _ = rp.ripple_get_degrees(pair.ctx, 1, pair.cap)
+        hub = int(np.argmax(deg_in))
+        assert deg_in[hub] > 4096
+
+        def edge_ops(code, sources):
+            return np.array([(code, int(u), hub, 0) for u in sources], dtype=np.uint32)
+
+        none = np.zeros((0, 24), dtype=np.float32)
+        inn = np.array(sorted(pair.ora.in_neighbours(hub)), dtype=np.int64)
+        outside = np.setdiff1d(np.flatnonzero(pair.ora.alive), np.append(inn, hub))
+        print(" additions", flush=True)
+        res, _, _ = pair.step(edge_ops(ri.OP_EDGE_ADD, rng.choice(outside, 5, replace=False)), none)
+        assert res.mono_recomputed[1] == 0 and res.mono_unchanged[1] + res.mono_incremental[1] == 1
+
+        inn = np.array(sorted(pair.ora.in_neighbours(hub)), dtype=np.int64)
+        holders = np.unique(inn[best(pair.ora.h0[inn], axis=0)])
+        others = np.setdiff1d(inn, holders)
+        print(" deletions that keep every extreme", flush=True)
+        res, _, _ = pair.step(edge_ops(ri.OP_EDGE_DEL, rng.choice(others, 4, replace=False)), none)
+        assert res.mono_recomputed[1] == 0 and res.mono_unchanged[1] == 1 and res.affected[1] == 0
+        print(" deletion of the source that holds a column", flush=True)
+        res, _, _ = pair.step(edge_ops(ri.OP_EDGE_DEL, holders[:1]), none)
+        assert res.mono_recomputed[1] == 1 and res.affected[1] == 1
+
+        print(" changed edges with changed and removed sources", flush=True)
+        inn = np.array(sorted(pair.ora.in_neighbours(hub)), dtype=np.int64)
+        outside = np.setdiff1d(np.flatnonzero(pair.ora.alive), np.append(inn, hub))
+        u_add, u_del, u_gone, u_far = int(outside[3]), int(inn[7]), int(inn[11]), int(inn[13])
+        ops = np.array([(ri.OP_EDGE_ADD, u_add, hub, 0), (ri.OP_FEAT_UPDATE, u_add, 0, 0),
+                        (ri.OP_EDGE_DEL, u_del, hub, 0), (ri.OP_FEAT_UPDATE, u_del, 0, 1)], dtype=np.uint32)
+        pair.step(ops, rng.standard_normal((2, 24)).astype(np.float32))
+        res, _, _ = pair.step(np.array([(ri.OP_VERTEX_DEL, u_gone, 0, 0)], dtype=np.uint32), none)
+        assert res.mono_recomputed[1] >= 1                     # the removed source's row is gone: the hub is re-read
+        # an added edge whose source jumps far beyond every other row: raised, not re-read
+        big = (-50.0 if kind.endswith("min") else 50.0) * np.ones((1, 24), dtype=np.float32)
+        ops = np.array([(ri.OP_EDGE_DEL, u_far, hub, 0), (ri.OP_FEAT_UPDATE, u_far, 0, 0)], dtype=np.uint32)
+        pair.step(ops, big)
+        pair.step(np.array([(ri.OP_EDGE_ADD, u_far, hub, 0)], dtype=np.uint32), none)
+        pair.check_aggregates()
+        pair.check_graph()
+    finally:
+        pair.close()
+
+
 def test_max_layers_are_refused_in_deterministic_mode():
     ctx = rp.ripple_init_graph(4, 8, np.array([0, 1], dtype=np.uint32), np.array([1, 2], dtype=np.uint32),
                                np.zeros((4, 8), dtype=np.float32))
