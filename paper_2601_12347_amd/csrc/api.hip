@@ -433,8 +433,8 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
         for (uint32_t l = 1; l <= c->L; ++l)
             if (rp_layer_mono(c, l)) mw = std::max(mw, c->xw[l]);
         if (mw) {                                        // in-rows sum to at most the pool: that bounds rows and segments
-            c->big_cap = (uint32_t)std::min<uint64_t>(c->pool_cap / ROW_SPLIT_MIN + 1, 1u << 30);
-            c->seg_cap = (uint32_t)std::min<uint64_t>(c->pool_cap / ROW_SEG + c->big_cap, 1u << 30);
+            c->big_cap = (uint32_t)std::min<uint64_t>(c->pool_cap / ROW_SPLIT_MIN + 1, ROW_SEG_MAX);
+            c->seg_cap = (uint32_t)std::min<uint64_t>(c->pool_cap / ROW_SEG + c->big_cap, ROW_SEG_MAX);
             c->seg_ld = rp_round_up(mw, 32);             // partial rows share no 128-byte line
             RP_TRY(dev_alloc(c, &c->seg_v, c->big_cap, false));
             RP_TRY(dev_alloc(c, &c->seg_done, c->big_cap, false));

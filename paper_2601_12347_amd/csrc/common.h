@@ -52,8 +52,9 @@ struct DevCtr {                      // device-resident counters, one instance p
     uint32_t pad1;
 };
 
-#define ROW_SPLIT_MIN 2048u
-#define ROW_SEG 1024u
+#define ROW_SPLIT_MIN 512u
+#define ROW_SEG 512u
+#define ROW_SEG_MAX (1u << 18)           // segments queued at a time; rows that find the queue full are read by one workgroup
 #define SEG_NONE 0xffffffffu
 
 struct LayerDev {

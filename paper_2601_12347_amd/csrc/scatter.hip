@@ -594,6 +594,8 @@ struct MonoArgs {
     const float *st_sign;
     uint32_t struct_cap;
     const uint32_t *alive;
+    uint32_t long_min;             // in-rows longer than this (at most MONO_LONG) go to the workgroup kernel
+    uint32_t split_min;            // in-rows of at least this many entries (at least ROW_SPLIT_MIN) are recomputed in segments
     uint32_t *out_list, *out_count; // small hops: the vertices that stay in the hop's set are appended here (or null)
     // very long rows that are recomputed: split into segments for k_scatter_mono_seg
     uint32_t *seg_v, *seg_done, *seg_base, *seg_r;
@@ -753,7 +755,7 @@ __global__ __launch_bounds__(256) void k_scatter_mono(MonoArgs a) {
     for (uint32_t i = gw; i < count; i += nw) {
         const uint32_t v = a.list[i];
         const uint2 m = a.in_meta[v];
-        if (m.y > MONO_LONG) {
+        if (m.y > a.long_min) {
             if (lane == 0) a.queue[atomicAdd(a.queue_count, 1u)] = v;
             continue;
         }
@@ -947,9 +949,9 @@ __global__ __launch_bounds__(TEAM * 64) void k_scatter_mono_long(MonoArgs a) {
                 continue;
             }
         }
-        // recompute from all in-neighbours (m.y > MONO_LONG, so the row is not empty)
-        if (m.y >= ROW_SPLIT_MIN) {
-            // One compute unit reads a row of many thousand in-neighbours far too slowly: queue its segments,
+        // recompute from all in-neighbours (m.y > long_min, so the row is not empty)
+        if (m.y >= a.split_min) {
+            // One compute unit reads a row of thousands of in-neighbours far too slowly: queue its segments,
             // a workgroup each takes one, the last to finish combines them (k_scatter_mono_seg).
             const uint32_t nseg = (m.y + ROW_SEG - 1) / ROW_SEG;
             if (threadIdx.x == 0) {
@@ -973,10 +975,11 @@ __global__ __launch_bounds__(TEAM * 64) void k_scatter_mono_long(MonoArgs a) {
         }
 #pragma unroll
         for (int j = 0; j < NJ; ++j) xn[j] = ident;
-        for (uint32_t base = 64u * wave; base < m.y; base += 64u * TEAM) {
+        const uint32_t chunk = (m.y <= 16u * 64u) ? 16u : 64u;  // shorter rows in finer pieces: every wavefront reads some
+        for (uint32_t base = chunk * wave; base < m.y; base += chunk * TEAM) {
             const uint32_t e = base + lane;
-            const uint32_t u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
-            mono_gather<NJ, IS_MIN, STORE, GR>(a, u, (int)min(64u, m.y - base), xn);
+            const uint32_t u = ((uint32_t)lane < chunk && e < m.y) ? a.in_pool[m.x + e] : 0u;
+            mono_gather<NJ, IS_MIN, STORE, GR>(a, u, (int)min(chunk, m.y - base), xn);
         }
         __syncthreads();                                       // s_val may still be read by wavefront 0 (classification)
 #pragma unroll
@@ -1075,6 +1078,11 @@ __global__ __launch_bounds__(TEAM * 64) void k_scatter_mono_seg(MonoArgs a) {
 // candidates in c->all_list, *count_ptr of them (rp_launch_candidates[_sparse]); D[(l-1)&1] holds the pre-batch rows of A_{l-1}
 void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l, const uint32_t *count_ptr, bool listed) {
     MonoArgs a;
+    const bool few = c->hints_valid && c->last_cand[l] <= 8192u;
+    // few candidates: one wavefront would read a row of 100+ in-neighbours for tens of microseconds with the chip idle
+    a.long_min = few ? 64u : MONO_LONG;
+    // a full chip is busy whichever workgroup reads a row: only the longest rows are split, so that none is left running alone
+    a.split_min = few ? ROW_SPLIT_MIN : 16u * ROW_SPLIT_MIN;
     a.list = c->all_list;
     a.count_ptr = count_ptr;
     a.queue = listed ? c->eoff[l] : c->list[l]; // neither is written before the hop's set is final
@@ -1112,12 +1120,12 @@ void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l, const uint32_t *count_ptr
     b.count_ptr = &c->ctr->n_long[l];
     const bool is_min = c->layers[l - 1].agg == RIPPLE_AGG_MIN;
     // few candidates: every workgroup resident at once, so none waits for a slot behind one that holds a long chain of reads
-    dim3 grid(c->n_cu * ((c->hints_valid && c->last_cand[l] <= 8192u) ? 4 : 8)), block(256);
+    dim3 grid(c->n_cu * (few ? 4 : 8)), block(256);
 #define MONO_PAIR(NJ, MN, ST, TEAM)                                                                          \
     do {                                                                                                     \
         hipLaunchKernelGGL((k_scatter_mono<NJ, MN, ST>), grid, block, 0, c->stream, a);                      \
         hipLaunchKernelGGL((k_scatter_mono_long<NJ, MN, ST, TEAM>), dim3(c->n_cu * 2), dim3(TEAM * 64), 0, c->stream, b); \
-        hipLaunchKernelGGL((k_scatter_mono_seg<NJ, MN, ST, 16>), dim3(c->n_cu * 2), dim3(1024), 0, c->stream, b); \
+        hipLaunchKernelGGL((k_scatter_mono_seg<NJ, MN, ST, ROW_SEG / 64>), dim3(c->n_cu * 4), dim3(ROW_SEG), 0, c->stream, b); \
     } while (0)
 #define MONO_CASE(NJ, TEAM)                                                                                  \
     do {                                                                                                     \
