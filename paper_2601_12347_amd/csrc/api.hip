@@ -429,9 +429,11 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
         }
     }
     {
-        uint32_t mw = 0;                                 // widest max / min aggregate
-        for (uint32_t l = 1; l <= c->L; ++l)
+        uint32_t mw = 0;                                 // widest max / min aggregate, widest attention numerator and its denominator
+        for (uint32_t l = 1; l <= c->L; ++l) {
             if (rp_layer_mono(c, l)) mw = std::max(mw, c->xw[l]);
+            if (rp_layer_attn(c, l)) mw = std::max(mw, c->d[l] + 1);
+        }
         if (mw) {                                        // in-rows sum to at most the pool: that bounds rows and segments
             c->big_cap = (uint32_t)std::min<uint64_t>(c->pool_cap / ROW_SPLIT_MIN + 1, ROW_SEG_MAX);
             c->seg_cap = (uint32_t)std::min<uint64_t>(c->pool_cap / ROW_SEG + c->big_cap, ROW_SEG_MAX);

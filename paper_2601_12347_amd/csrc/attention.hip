@@ -4,15 +4,19 @@
 // s_src[v] = a_src . P[v] and s_dst[v] = a_dst . P[v], and the un-normalised aggregate: the numerator
 // X[v] = sum_u w_uv P[u] and the denominator den[v] = sum_u w_uv over v's in-neighbours u, with
 // w_uv = exp(LeakyReLU(s_src[u] + s_dst[v])). The row transform is h_v = act(X[v] / den[v] + b).
-// After a batch, a vertex of A_l that is itself in A_{l-1} (its own score moved, so every w_uv did), or
-// whose in-edges changed, recomputes numerator and denominator from all its in-neighbours; any other
-// vertex of A_l receives, per changed in-neighbour u, the message of the paper:
-// <w_new P_new[u] - w_old P_old[u], w_new - w_old>. One owner per destination (a wavefront; a workgroup for long
-// in-rows), no atomics, a fixed order of additions.
+// After a batch, a vertex of A_l that is itself in A_{l-1} (its own score moved, so every w_uv did)
+// recomputes numerator and denominator from all its in-neighbours; any other vertex of A_l receives, per
+// changed in-neighbour u, the message of the paper: <w_new P_new[u] - w_old P_old[u], w_new - w_old>.
+// A vertex whose in-edges changed recomputes if its in-row is short; with a long in-row each changed edge
+// is a message too (its pre-batch weight and row, added or taken away). One owner per destination (a
+// wavefront; a workgroup for long in-rows; a workgroup per 512-entry segment when a very long row is
+// recomputed, the last of them adding the segments up in order), no atomics on rows.
 #include "kernels.h"
 
 #define GAT_SLOPE 0.2f
 #define GAT_LONG 256u
+#define GAT_EDGE_HITS 1024u       // changed edges of one sink kept as messages; more: recompute
+#define GAT_EDGE_SCAN 32768u      // longest list of changed edges a sink's workgroup searches; longer: recompute
 
 struct GatArgs {
     const uint32_t *list;          // A_l, or every live vertex (bootstrap), or the queue of long rows
@@ -27,6 +31,18 @@ struct GatArgs {
     uint32_t d;                    // d_out
     float *X, *den;
     int all;                       // bootstrap: recompute every listed row
+    int few;                       // few rows this hop: latency of the longest row matters, not throughput
+    uint32_t long_min;             // in-rows longer than this (at most GAT_LONG) go to the workgroup kernel
+    uint32_t split_min;            // in-rows of at least this many entries are recomputed in segments (k_gat_scatter_seg)
+    uint32_t *n_big, *n_seg;       // split rows / queued segments of this hop
+    uint32_t *seg_v, *seg_done, *seg_base, *seg_r;
+    float *seg_part;               // per segment: partial numerator (d floats), then the partial denominator
+    uint32_t big_cap, seg_cap, seg_ld;
+    // the batch's changed edges (source, sink, sign: < 0 deleted), read for sinks with long in-rows
+    const uint32_t *st_src, *st_dst;
+    const float *st_sign;
+    const uint32_t *n_struct;
+    uint32_t struct_cap;
 };
 
 __device__ __forceinline__ float gat_weight(float s_u, float t_v) {
@@ -86,6 +102,39 @@ __device__ __forceinline__ float gat_block(const GatArgs &a, uint32_t my_u, bool
     return wn - wo;
 }
 
+// Messages of changed in-edges of one sink whose own score stayed (u = source, sgn = +1 added, -1 deleted,
+// one per valid lane): the edge's weight and row as they were before the batch. For a deleted edge that
+// is what goes away; for an added edge whose source also changed it cancels the old part of the
+// changed-source message, which was never in the sums; for an added edge from an unchanged source it is
+// the edge's contribution itself.
+template <int NJ>
+__device__ __forceinline__ float gat_edge_block(const GatArgs &a, uint32_t my_u, float my_sgn, bool valid, float t_v,
+                                                float *acc, float &mag) {
+    const int lane = rp_lane();
+    const uint32_t d = a.d;
+    bool from_old = false;
+    float w = 0.0f;
+    if (valid) {
+        from_old = rp_bit(a.bm_prev, my_u);
+        w = gat_weight(from_old ? a.sold[my_u] : a.ssrc[my_u], t_v);
+    }
+    unsigned long long mask = __ballot(valid);
+    while (mask) {
+        const int k = __ffsll((long long)mask) - 1;
+        mask &= mask - 1;
+        const uint32_t u = __shfl(my_u, k);
+        const float wk = __shfl(w, k) * __shfl(my_sgn, k);
+        const float *row = (__shfl((int)from_old, k) ? a.Pold : a.P) + (size_t)u * d;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const uint32_t col = lane + 64 * j;
+            if (col < d) acc[j] += wk * row[col];
+        }
+    }
+    mag += w;
+    return w * my_sgn;
+}
+
 // A patched denominator that is tiny against what was added and taken away has lost its small terms
 // (a weight e^z that dropped by many orders of magnitude leaves only rounding residue of itself): such a
 // row is recomputed from all its in-neighbours instead.
@@ -99,8 +148,8 @@ __device__ __forceinline__ float gat_wave_sum(float x) {
 
 template <int NJ>
 __global__ __launch_bounds__(256) void k_gat_scatter(GatArgs a) {
-    constexpr int G = (NJ <= 1) ? 8 : (NJ <= 2 ? 4 : (NJ <= 4 ? 2 : 1));     // senders in flight (old and new row each)
-    constexpr int GR = (NJ <= 1) ? 16 : (NJ <= 16 ? 16 / NJ : 1);             // rows in flight when recomputing
+    constexpr int G = (NJ <= 1) ? 8 : (NJ <= 2 ? 4 : (NJ <= 4 ? 2 : 1));
+    constexpr int GR = (NJ <= 1) ? 16 : (NJ <= 16 ? 16 / NJ : 1);
     const uint32_t count = *a.count_ptr;
     const int lane = rp_lane();
     const uint32_t d = a.d;
@@ -108,7 +157,7 @@ __global__ __launch_bounds__(256) void k_gat_scatter(GatArgs a) {
     for (uint32_t i = gw; i < count; i += nw) {
         const uint32_t v = a.list[i];
         const uint2 m = a.in_meta[v];
-        if (m.y > GAT_LONG) {
+        if (m.y > a.long_min) {
             if (lane == 0) a.queue[atomicAdd(a.queue_count, 1u)] = v;
             continue;
         }
@@ -149,27 +198,113 @@ __global__ __launch_bounds__(256) void k_gat_scatter(GatArgs a) {
 template <int NJ, int TEAM>
 __global__ __launch_bounds__(TEAM * 64) void k_gat_scatter_long(GatArgs a) {
     constexpr int G = (NJ <= 1) ? 8 : (NJ <= 2 ? 4 : (NJ <= 4 ? 2 : 1));
-    constexpr int GR = (NJ <= 2) ? 16 : 32 / NJ;               // a long row is paced by round trips
+    constexpr int GR = (NJ <= 2) ? 16 : 32 / NJ;
+    constexpr int IDS = 4;                                     // blocks of in-neighbour ids in flight while looking for changed ones
     __shared__ float s_val[TEAM][NJ * 64];
     __shared__ float s_den[TEAM], s_mag[TEAM];
+    __shared__ uint32_t s_hit[GAT_EDGE_HITS];                  // the sink's entries in the list of changed edges
+    __shared__ uint32_t s_nhit, s_base, s_slot;
     const uint32_t count = *a.count_ptr;
+    const uint32_t n_st = *a.n_struct;
     const int lane = rp_lane(), wave = threadIdx.x >> 6;
     const uint32_t d = a.d;
     for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) {
         const uint32_t v = a.list[i];
         const uint2 m = a.in_meta[v];
-        bool recompute = a.all || rp_bit(a.bm_prev, v) || rp_bit(a.bm_sink, v) || rp_bit(a.bm_vadd, v);
+        bool recompute = a.all || rp_bit(a.bm_prev, v) || rp_bit(a.bm_vadd, v);
+        // a sink whose own score stayed keeps its long row incremental when its changed edges can be looked up
+        uint32_t ns = 0;
+        if (!recompute && rp_bit(a.bm_sink, v)) {
+            if (n_st > a.struct_cap || n_st > GAT_EDGE_SCAN) {
+                recompute = true;
+            } else {
+                if (threadIdx.x == 0) s_nhit = 0;
+                __syncthreads();
+                for (uint32_t s = threadIdx.x; s < n_st; s += TEAM * 64)
+                    if (a.st_dst[s] == v) {
+                        const uint32_t k = atomicAdd(&s_nhit, 1u);
+                        if (k < GAT_EDGE_HITS) s_hit[k] = s;
+                    }
+                __syncthreads();
+                ns = s_nhit;
+                if (ns > GAT_EDGE_HITS || 2 * ns >= m.y) recompute = true;
+            }
+        }
         const float t_v = a.sdst[v];
         float acc[NJ];
+        bool queued = false;
         for (;;) {                                             // a second pass only after a cancelled patch
+            if (recompute && m.y >= a.split_min) {
+                // One compute unit reads a row of thousands of in-neighbours far too slowly: queue its segments,
+                // a workgroup each takes one, the last to finish adds them up (k_gat_scatter_seg).
+                const uint32_t nseg = (m.y + ROW_SEG - 1) / ROW_SEG;
+                if (threadIdx.x == 0) {
+                    const uint32_t r = atomicAdd(a.n_big, 1u);
+                    const uint32_t base = atomicAdd(a.n_seg, nseg);
+                    const bool fits = r < a.big_cap && base < a.seg_cap && nseg <= a.seg_cap - base;
+                    if (fits) {
+                        a.seg_v[r] = v;
+                        a.seg_done[r] = 0;
+                        a.seg_base[r] = base;
+                    }
+                    s_base = base;
+                    s_slot = fits ? r : SEG_NONE;
+                }
+                __syncthreads();
+                const uint32_t base = s_base, r = s_slot;
+                for (uint32_t k = threadIdx.x; k < nseg; k += TEAM * 64)
+                    if (base < a.seg_cap && k < a.seg_cap - base) a.seg_r[base + k] = r;    // SEG_NONE: skipped there
+                __syncthreads();
+                if (r != SEG_NONE) {                           // (the queue holds every row unless it is capped: then read it here)
+                    queued = true;
+                    break;
+                }
+            }
 #pragma unroll
             for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
             float dsum = 0.0f, mag = 0.0f;
-            for (uint32_t base = 64u * wave; base < m.y; base += 64u * TEAM) {
-                const uint32_t e = base + lane;
-                const uint32_t my_u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
-                dsum += recompute ? gat_block<NJ, GR, true>(a, my_u, e < m.y, t_v, acc, mag)
-                                  : gat_block<NJ, G, false>(a, my_u, e < m.y, t_v, acc, mag);
+            if (recompute) {
+                const uint32_t chunk = (m.y <= 16u * 64u) ? 16u : 64u;   // shorter rows in finer pieces: every wavefront reads some
+                for (uint32_t base = chunk * wave; base < m.y; base += chunk * TEAM) {
+                    const uint32_t e = base + lane;
+                    const bool valid = (uint32_t)lane < chunk && e < m.y;
+                    const uint32_t my_u = valid ? a.in_pool[m.x + e] : 0u;
+                    dsum += gat_block<NJ, GR, true>(a, my_u, valid, t_v, acc, mag);
+                }
+            } else {
+                if (!a.few) {                                  // the chip is full: block after block
+                    for (uint32_t base = 64u * wave; base < m.y; base += 64u * TEAM) {
+                        const uint32_t e = base + lane;
+                        const uint32_t my_u = (e < m.y) ? a.in_pool[m.x + e] : 0u;
+                        dsum += gat_block<NJ, G, false>(a, my_u, e < m.y, t_v, acc, mag);
+                    }
+                } else
+                for (uint32_t base = 64u * wave; base < m.y; base += 64u * TEAM * IDS) {
+                    uint32_t u[IDS];
+                    bool any[IDS];
+#pragma unroll
+                    for (int t = 0; t < IDS; ++t) {
+                        const uint32_t e = base + 64u * TEAM * t + lane;
+                        u[t] = (e < m.y) ? a.in_pool[m.x + e] : 0u;
+                    }
+#pragma unroll
+                    for (int t = 0; t < IDS; ++t) {
+                        const uint32_t e = base + 64u * TEAM * t + lane;
+                        any[t] = __ballot(e < m.y && rp_bit(a.bm_prev, u[t])) != 0ull;
+                    }
+#pragma unroll
+                    for (int t = 0; t < IDS; ++t) {
+                        const uint32_t e = base + 64u * TEAM * t + lane;
+                        if (any[t]) dsum += gat_block<NJ, G, false>(a, u[t], e < m.y, t_v, acc, mag);
+                    }
+                }
+                for (uint32_t base = 64u * wave; base < ns; base += 64u * TEAM) {
+                    const uint32_t k = base + lane;
+                    const uint32_t s = (k < ns) ? s_hit[k] : 0u;
+                    const uint32_t u = (k < ns) ? a.st_src[s] : 0u;
+                    const float sgn = (k < ns && a.st_sign[s] < 0.0f) ? -1.0f : 1.0f;
+                    dsum += gat_edge_block<NJ>(a, u, sgn, k < ns, t_v, acc, mag);
+                }
             }
             dsum = gat_wave_sum(dsum);
             mag = gat_wave_sum(mag);
@@ -190,6 +325,7 @@ __global__ __launch_bounds__(TEAM * 64) void k_gat_scatter_long(GatArgs a) {
             recompute = true;
             __syncthreads();                                   // the partial results are overwritten by the second pass
         }
+        if (queued) continue;
         if (wave == 0) {
             float dd = 0.0f;
             for (int w = 0; w < TEAM; ++w) dd += s_den[w];
@@ -204,6 +340,83 @@ __global__ __launch_bounds__(TEAM * 64) void k_gat_scatter_long(GatArgs a) {
                 }
             }
             if (lane == 0) a.den[v] = recompute ? dd : a.den[v] + dd;
+        }
+        __syncthreads();
+    }
+}
+
+// One workgroup per queued segment of a very long row that is recomputed: numerator and denominator over
+// the segment's ROW_SEG in-neighbours go to the segment's partial row; the workgroup that finishes a row's
+// last segment adds the partial rows up in segment order and stores the row.
+template <int NJ, int TEAM>
+__global__ __launch_bounds__(TEAM * 64) void k_gat_scatter_seg(GatArgs a) {
+    static_assert(TEAM * 64 == ROW_SEG, "one 64-entry block per wavefront");
+    constexpr int GR = (NJ <= 2) ? 32 : 64 / NJ;
+    __shared__ float s_val[TEAM][NJ * 64];
+    __shared__ float s_den[TEAM];
+    const uint32_t n_seg = min(*a.n_seg, a.seg_cap);
+    const int lane = rp_lane(), wave = threadIdx.x >> 6;
+    const uint32_t d = a.d;
+    for (uint32_t e = blockIdx.x; e < n_seg; e += gridDim.x) {
+        const uint32_t r = a.seg_r[e];
+        if (r == SEG_NONE) continue;
+        const uint32_t v = a.seg_v[r], first = a.seg_base[r];
+        const uint2 m = a.in_meta[v];
+        const uint32_t nseg = (m.y + ROW_SEG - 1) / ROW_SEG;
+        const uint32_t lo = (e - first) * ROW_SEG, hi = min(m.y, lo + ROW_SEG);
+        const float t_v = a.sdst[v];
+        float acc[NJ];
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
+        float dsum = 0.0f, mag = 0.0f;
+        const uint32_t b = lo + 64u * wave;
+        if (b < hi) {
+            const bool valid = b + lane < hi;
+            const uint32_t my_u = valid ? a.in_pool[m.x + b + lane] : 0u;
+            dsum = gat_block<NJ, GR, true>(a, my_u, valid, t_v, acc, mag);
+        }
+        dsum = gat_wave_sum(dsum);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) s_val[wave][j * 64 + lane] = acc[j];
+        if (lane == 0) s_den[wave] = dsum;
+        __syncthreads();
+        if (wave == 0) {
+            float *part = a.seg_part + (size_t)e * a.seg_ld;
+            float dd = 0.0f;
+            for (int w = 0; w < TEAM; ++w) dd += s_den[w];
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                float t = 0.0f;
+                for (int w = 0; w < TEAM; ++w) t += s_val[w][j * 64 + lane];
+                const uint32_t col = lane + 64 * j;
+                if (col < d) part[col] = t;
+            }
+            if (lane == 0) part[d] = dd;
+            __threadfence();                                   // the partial row is visible before the count moves
+            uint32_t last = 0;
+            if (lane == 0) last = (atomicAdd(&a.seg_done[r], 1u) == nseg - 1) ? 1u : 0u;
+            last = __shfl(last, 0);
+            if (last) {
+                __threadfence();
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
+                dd = 0.0f;
+                for (uint32_t k = 0; k < nseg; ++k) {          // written by other compute units: read past this one's cache
+                    const float *p = a.seg_part + (size_t)(first + k) * a.seg_ld;
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) {
+                        const uint32_t col = lane + 64 * j;
+                        if (col < d) acc[j] += __hip_atomic_load(p + col, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                    dd += __hip_atomic_load(p + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    const uint32_t col = lane + 64 * j;
+                    if (col < d) a.X[(size_t)v * d + col] = acc[j];
+                }
+                if (lane == 0) a.den[v] = dd;
+            }
         }
         __syncthreads();
     }
@@ -231,15 +444,40 @@ void rp_launch_gat_scatter(ripple_ctx *c, uint32_t l, bool bootstrap) {
     a.X = c->X[l];
     a.den = ly.den;
     a.all = bootstrap ? 1 : 0;
-    if (bootstrap) hipMemsetAsync(&c->ctr->n_long[l], 0, 4, c->stream);   // a batch starts with it cleared
+    const bool few = !bootstrap && c->hints_valid && c->last_a[l] <= 8192u;
+    // few rows: one wavefront would read a row of 100+ in-neighbours, one workgroup a row of thousands, with the chip idle
+    a.few = few ? 1 : 0;
+    a.long_min = few ? 64u : GAT_LONG;
+    a.split_min = few ? ROW_SPLIT_MIN : 64u * ROW_SPLIT_MIN;
+    a.n_big = &c->ctr->n_big[l];
+    a.n_seg = &c->ctr->n_seg[l];
+    a.seg_v = c->seg_v;
+    a.seg_done = c->seg_done;
+    a.seg_base = c->seg_base;
+    a.seg_r = c->seg_r;
+    a.seg_part = c->seg_part;
+    a.big_cap = c->big_cap;
+    a.seg_cap = c->seg_cap;
+    a.seg_ld = c->seg_ld;
+    a.st_src = c->st_src;
+    a.st_dst = c->st_dst;
+    a.st_sign = c->st_sign;
+    a.n_struct = &c->ctr->n_struct;
+    a.struct_cap = (c->in_w || bootstrap) ? 0u : c->struct_cap;   // weighted graphs: the sign carries the weight, sinks recompute
+    if (bootstrap) {                                     // a batch starts with them cleared
+        hipMemsetAsync(&c->ctr->n_long[l], 0, 4, c->stream);
+        hipMemsetAsync(&c->ctr->n_big[l], 0, 4, c->stream);
+        hipMemsetAsync(&c->ctr->n_seg[l], 0, 4, c->stream);
+    }
     GatArgs b = a;
     b.list = a.queue;
     b.count_ptr = &c->ctr->n_long[l];
-    dim3 grid(c->n_cu * 8), block(256);
+    dim3 grid(c->n_cu * (few ? 4 : 8)), block(256);
 #define GAT_CASE(NJ, TEAM)                                                                                   \
     do {                                                                                                     \
         hipLaunchKernelGGL((k_gat_scatter<NJ>), grid, block, 0, c->stream, a);                               \
         hipLaunchKernelGGL((k_gat_scatter_long<NJ, TEAM>), dim3(c->n_cu * 2), dim3(TEAM * 64), 0, c->stream, b); \
+        hipLaunchKernelGGL((k_gat_scatter_seg<NJ, ROW_SEG / 64>), dim3(c->n_cu * 4), dim3(ROW_SEG), 0, c->stream, b); \
     } while (0)
     if (a.d <= 64) GAT_CASE(1, 16);
     else if (a.d <= 128) GAT_CASE(2, 16);

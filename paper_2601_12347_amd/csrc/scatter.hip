@@ -560,14 +560,17 @@ void rp_launch_scatter_owner(ripple_ctx *c, uint32_t l, bool bootstrap) {
 //   * an old value that equalled the aggregate and got worse may have been the one that set it; unless
 //     another message reaches the aggregate again, the row is recomputed from all in-neighbours;
 //   * anything else leaves the element alone.
-// Recomputing is always right, so it is also taken where it is the cheaper way: for a vertex whose
-// in-edges changed (S, V_added: a deleted edge's source may have set the extreme, an added one has no
-// old value), where reading the old and new rows of the changed in-neighbours would cost as much as
-// reading every in-neighbour once, and as soon as one element is known to have lost its extreme.
+// Recomputing is always right, so it is also taken where it is the cheaper way: for a created vertex
+// and for a vertex with a short in-row whose in-edges changed, where reading the old and new rows of
+// the changed in-neighbours would cost as much as reading every in-neighbour once, and as soon as one
+// element is known to have lost its extreme. A vertex with a long in-row whose in-edges changed treats
+// each changed edge as a message: an added edge sends its source's current row (no old value), a deleted
+// one its source's pre-batch row as an old value that is gone.
 // Rows whose aggregate ends up bit-equal to the old one are taken out of the hop's set again, so they
 // are not transformed and send nothing on. There are no atomics on rows and the result does not
-// depend on any order. One wavefront owns a candidate with up to MONO_LONG in-neighbours; longer
-// in-rows are queued and taken by a workgroup each.
+// depend on any order. One wavefront owns a candidate with up to long_min (at most MONO_LONG)
+// in-neighbours; longer in-rows are queued and taken by a workgroup each, and a very long row that has
+// to be recomputed is queued once more, in segments that a workgroup each reads.
 #define MONO_LONG 256u
 #define MONO_DIRTY_LIST 2048u     // changed in-neighbours of a long row remembered between counting and reading them
 #define MONO_EDGE_HITS 1024u      // changed edges of one sink kept as messages; more: recompute
@@ -1082,7 +1085,7 @@ void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l, const uint32_t *count_ptr
     // few candidates: one wavefront would read a row of 100+ in-neighbours for tens of microseconds with the chip idle
     a.long_min = few ? 64u : MONO_LONG;
     // a full chip is busy whichever workgroup reads a row: only the longest rows are split, so that none is left running alone
-    a.split_min = few ? ROW_SPLIT_MIN : 16u * ROW_SPLIT_MIN;
+    a.split_min = few ? ROW_SPLIT_MIN : 64u * ROW_SPLIT_MIN;
     a.list = c->all_list;
     a.count_ptr = count_ptr;
     a.queue = listed ? c->eoff[l] : c->list[l]; // neither is written before the hop's set is final

@@ -526,6 +526,41 @@ def test_max_min_changed_edges_of_a_hub_are_messages(kind):
         pair.close()
 
 
+def test_attention_changed_edges_of_a_hub_are_messages():
+    """Edges that come and go at a vertex with thousands of in-neighbours whose own score stays: numerator
+    and denominator are patched with the edge's pre-batch weight and row (Sec. 3.4.1) instead of re-reading
+    the row; sources that change, appear or vanish in the same batch included. Then the hub's own features
+    change, which recomputes its row (split over several workgroups)."""
+    print("case attention hub sink", flush=True)
+    pair, graph = make_pair(n=20000, e=240000, d0=24, kind="gat", widths=(24, 48, 12), seed=161, slack=64, top_share=0.04)
+    rng = np.random.default_rng(169)
+    try:
+        deg_in, _ = rp.ripple_get_degrees(pair.ctx, 1, pair.cap)
+        hub = int(np.argmax(deg_in))
+        assert deg_in[hub] > 4096
+        none = np.zeros((0, 24), dtype=np.float32)
+        for b in range(3):
+            print(" batch", b, flush=True)
+            inn = np.array(sorted(pair.ora.in_neighbours(hub)), dtype=np.int64)
+            outside = np.setdiff1d(np.flatnonzero(pair.ora.alive), np.append(inn, hub))
+            adds = rng.choice(outside, 4, replace=False)
+            dels = rng.choice(inn, 4, replace=False)
+            ops = [(ri.OP_EDGE_ADD, int(u), hub, 0) for u in adds] + [(ri.OP_EDGE_DEL, int(u), hub, 0) for u in dels]
+            rows = none
+            if b >= 1:                                          # an added and a deleted source change as well
+                ops += [(ri.OP_FEAT_UPDATE, int(adds[0]), 0, 0), (ri.OP_FEAT_UPDATE, int(dels[0]), 0, 1)]
+                rows = rng.standard_normal((2, 24)).astype(np.float32)
+            if b == 2:                                          # and an in-neighbour is removed
+                ops.append((ri.OP_VERTEX_DEL, int(np.setdiff1d(inn, dels)[5]), 0, 0))
+            pair.step(np.array(ops, dtype=np.uint32), rows)
+        print(" the hub itself changes", flush=True)
+        pair.step(np.array([(ri.OP_FEAT_UPDATE, hub, 0, 0)], dtype=np.uint32), rng.standard_normal((1, 24)).astype(np.float32))
+        pair.check_aggregates()
+        pair.check_graph()
+    finally:
+        pair.close()
+
+
 def test_max_layers_are_refused_in_deterministic_mode():
     ctx = rp.ripple_init_graph(4, 8, np.array([0, 1], dtype=np.uint32), np.array([1, 2], dtype=np.uint32),
                                np.zeros((4, 8), dtype=np.float32))
