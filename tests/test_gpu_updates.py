@@ -819,6 +819,33 @@ def test_mixed_layer_kinds_hand_over_the_right_rows(kinds, widths):
         pair.close()
 
 
+def test_weighted_graph_with_max_and_attention_layers_and_hub_rows():
+    """On a weighted graph the list of changed edges carries the weight in its sign field, so max / min and
+    attention layers (which ignore the weights) cannot read "added or deleted" from it: sinks with long
+    in-rows recompute there. Weighted sum first, then max, then attention, hub rows of several thousand
+    entries, small batches (list-while-marking hops) and a large one."""
+    print("case weighted graph, max and attention layers", flush=True)
+    n = 12000
+    src, dst, out_law, in_law = ri.chung_lu_graph(n, 150000, 2.1, 0.05, 301)
+    widths = (16, 24, 12, 6)
+    feats = ri.features(n, widths[0], 302)
+    model = [ri.make_model(k, widths, 303 + i)[i] for i, k in enumerate(("gcn_wsum", "gcn_max", "gat"))]
+    from harness import Pair
+    pair = Pair(n, n + 256, src, dst, feats, model, weights=ri.edge_weights(len(src), 306))
+    stream = ri.UpdateStream(n, n + 256, src, dst, out_law, in_law, widths[0], MIXV, 307, weighted=True)
+    try:
+        deg_in, _ = rp.ripple_get_degrees(pair.ctx, 1, pair.cap)
+        assert deg_in.max() > 2048
+        for b, bs in enumerate([5, 6, 5, 1500, 8]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload)
+        pair.check_aggregates()
+        pair.check_graph()
+    finally:
+        pair.close()
+
+
 def test_attention_scores_that_drop_by_many_orders_of_magnitude():
     """Raw exponentials (the paper's numerator / denominator messages) cancel catastrophically when a dominant
     weight collapses: e^36 taken out of a denominator leaves only rounding residue. Rows whose patched
