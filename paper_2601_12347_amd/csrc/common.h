@@ -237,6 +237,23 @@ __device__ __forceinline__ uint32_t rp_seg_search(const uint32_t *off, uint32_t 
     }
     return lo;
 }
+// The same for a value that all 64 lanes share, found by the wavefront together: 64 probes per round
+// trip instead of one, so a list of up to 4096 rows takes two dependent reads and not twelve. To be
+// called by all 64 lanes.
+__device__ __forceinline__ uint32_t rp_seg_search_wave(const uint32_t *off, uint32_t lo, uint32_t hi, uint32_t e) {
+    const uint32_t lane = (uint32_t)rp_lane();
+    while (hi - lo >= 64u) {
+        const uint32_t step = (hi - lo) / 64u + 1u;        // probes at lo + step, lo + 2 step, ... (clipped to hi)
+        const uint32_t p = min(hi, lo + (lane + 1u) * step);
+        const uint32_t k = (uint32_t)__popcll(__ballot(off[p] <= e));   // the probes that are <= e come first
+        const uint32_t nlo = k ? min(hi, lo + k * step) : lo;
+        const uint32_t nhi = (k == 64u) ? hi : min(hi, lo + (k + 1u) * step) - 1u;
+        lo = nlo;
+        hi = max(nlo, nhi);
+    }
+    const uint32_t p = lo + lane;
+    return lo + (uint32_t)__popcll(__ballot(p <= hi && p > lo && off[p] <= e));
+}
 // the same over [lo, last], for an answer expected close to lo: doubling steps, then bisection
 __device__ __forceinline__ uint32_t rp_seg_forward(const uint32_t *off, uint32_t lo, uint32_t last, uint32_t e) {
     uint32_t step = 1;

@@ -66,7 +66,7 @@ __device__ __forceinline__ void frontier_walk(const uint32_t *list, const uint32
     const uint32_t c_begin = min(n_chunks, gw * per), c_end = min(n_chunks, c_begin + per);
     if (c_begin >= c_end) return;
     const uint32_t last = count - 1;
-    uint32_t i_lo = rp_seg_search(eoff, 0, last, c_begin * MARK_CHUNK);
+    uint32_t i_lo = rp_seg_search_wave(eoff, 0, last, c_begin * MARK_CHUNK);
     uint32_t rbase, bnd;                                    // lane j: row i_lo + j
     {
         const uint32_t ri = min(last, i_lo + lane);

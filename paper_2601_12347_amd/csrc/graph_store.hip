@@ -295,6 +295,7 @@ struct MutArgs {
     float *X[RIPPLE_MAX_LAYERS + 1];
     const float *Wn[RIPPLE_MAX_LAYERS + 1];      // project-first layers: neighbour weights (row stride wn_ld), else null
     uint32_t wn_ld[RIPPLE_MAX_LAYERS + 1];
+    uint32_t kslices;                            // 64-row slices of the widest of those weight matrices (at least 1)
     uint32_t mono_mask;                          // bit l: layer l takes max / min or attention (no structural terms)
     int d0_old;                                  // layer 1 does: D0 receives the old feature row instead of the difference
 };
@@ -839,14 +840,19 @@ __global__ __launch_bounds__(256) void k_struct_scatter(MutArgs a) {
     const int lane = rp_lane();
     uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
     uint32_t n = min(a.ctr->n_struct, a.struct_cap);
-    unsigned long long total = (unsigned long long)n * a.L;
+    // one task per changed edge, layer and 64-row slice of a project-first layer's weights: the slices'
+    // partial products meet in the atomic additions, and no wavefront walks a whole matrix alone
+    const uint32_t per = a.L * a.kslices;
+    unsigned long long total = (unsigned long long)n * per;
     for (unsigned long long t = gw; t < total; t += nw) {
-        uint32_t e = (uint32_t)(t / a.L), l = (uint32_t)(t % a.L) + 1;
+        const uint32_t e = (uint32_t)(t / per), rem = (uint32_t)(t % per);
+        const uint32_t l = rem / a.kslices + 1, ks = rem % a.kslices;
         if ((a.mono_mask >> l) & 1u) continue;               // rows with a changed in-edge are recomputed instead
         uint32_t u = a.st_src[e], v = a.st_dst[e];
         float sg = a.st_sign[e];
         uint32_t dp = a.d[l - 1];
         if (a.Wn[l] == nullptr) {
+            if (ks) continue;
             for (uint32_t c = lane; c < dp; c += 64) {
                 float val = rp_load_h(a.H[l - 1], a.store, (size_t)u * dp + c);
                 if (val != 0.0f) unsafeAtomicAdd(&a.X[l][(size_t)v * dp + c], sg * val);
@@ -855,10 +861,12 @@ __global__ __launch_bounds__(256) void k_struct_scatter(MutArgs a) {
             const uint32_t dn = a.xw[l];
             const float *W = a.Wn[l];
             const uint32_t ld = a.wn_ld[l];
+            const uint32_t k0 = 64u * ks;
+            if (k0 >= dp) continue;
             for (uint32_t c0 = 0; c0 < dn; c0 += 64) {
                 const uint32_t c = c0 + lane;
                 float sum = 0.0f;
-                for (uint32_t k0 = 0; k0 < dp; k0 += 64) {
+                {
                     const uint32_t kk = k0 + lane;
                     const float hv = (kk < dp) ? rp_load_h(a.H[l - 1], a.store, (size_t)u * dp + kk) : 0.0f;
                     // rows of W beyond dp exist (zero padding up to a multiple of 32) and meet hv = 0
@@ -952,6 +960,7 @@ static MutArgs make_args(ripple_ctx *c, uint32_t n_ops) {
     a.pool_cap = c->pool_cap;
     a.store = c->store;
     a.L = c->L;
+    a.kslices = 1;
     for (uint32_t l = 0; l <= RIPPLE_MAX_LAYERS; ++l) {
         a.d[l] = c->d[l];
         a.xw[l] = c->xw[l];
@@ -960,6 +969,7 @@ static MutArgs make_args(ripple_ctx *c, uint32_t n_ops) {
         const bool proj = l >= 1 && l <= c->L && c->layers[l - 1].proj;
         a.Wn[l] = proj ? c->layers[l - 1].Wn : nullptr;
         a.wn_ld[l] = proj ? c->layers[l - 1].N0pad : 0;
+        if (proj) a.kslices = std::max(a.kslices, rp_div_up(c->d[l - 1], 64));
     }
     a.mono_mask = 0;
     for (uint32_t l = 1; l <= c->L; ++l)
@@ -995,7 +1005,7 @@ void rp_launch_mutate(ripple_ctx *c, uint32_t n_ops, bool has_vertex_add, bool h
     hipLaunchKernelGGL(k_apply_edges, dim3(tb), dim3(256), 0, s, a);
     int t = rp_timer_begin(c);
     if (!c->opt_deterministic)                     // that mode recomputes the rows with a changed in-edge instead
-    hipLaunchKernelGGL(k_struct_scatter, dim3(has_vertex_del ? big : std::min<uint32_t>(big, rp_div_up((uint64_t)n_ops * c->L, 4))),
+    hipLaunchKernelGGL(k_struct_scatter, dim3(has_vertex_del ? big : std::min<uint32_t>(big, rp_div_up((uint64_t)n_ops * c->L * a.kslices, 4))),
                        dim3(256), 0, s, a);
     rp_timer_end(c, t, RIPPLE_PH_STRUCT, 0);
     if (has_vertex_or_feat) hipLaunchKernelGGL(k_apply_vertices, dim3(wb), dim3(256), 0, s, a);

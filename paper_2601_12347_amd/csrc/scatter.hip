@@ -33,14 +33,22 @@ __global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, cons
     const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
     for (uint32_t c = gw; c < n_chunks; c += nw) {
         const uint32_t e0 = c * PUSH_CHUNK, e1 = min(M, e0 + PUSH_CHUNK);
-        const uint32_t i_lo = rp_seg_search(eoff, 0, count - 1, e0);
-        const uint32_t i_hi = rp_seg_search(eoff, i_lo, count - 1, e1 - 1);
-        const uint32_t e = e0 + lane;
-        uint32_t my_i = 0, my_v = 0;
-        if (e < e1) {
-            my_i = rp_seg_search(eoff, i_lo, i_hi, e);
-            my_v = out_pool[out_meta[list[my_i]].x + (e - eoff[my_i])];
+        // the chunk's first row by the wavefront together; the 64 rows from there on (vertex, pool position,
+        // end) one per lane, so an edge finds its row with shuffles instead of a chain of dependent reads
+        const uint32_t i_lo = rp_seg_search_wave(eoff, 0, count - 1, e0);
+        const uint32_t ri = min(count - 1, i_lo + (uint32_t)lane);
+        const uint32_t rv = list[ri];
+        const uint32_t rbase = out_meta[rv].x - eoff[ri];      // pool position of edge e: rbase + e (mod 2^32)
+        const uint32_t bnd = eoff[min(count, i_lo + 1u + (uint32_t)lane)];
+        const uint32_t e = min(e0 + (uint32_t)lane, e1 - 1);    // lanes past the chunk repeat its last edge (not used)
+        const uint32_t k = rp_count_le(bnd, e);
+        uint32_t my_i = i_lo + k, my_u = __shfl(rv, (int)min(k, 63u)), pos = __shfl(rbase, (int)min(k, 63u)) + e;
+        if (k >= 64u) {                                         // more than 64 rows in 64 edges (rows without out-edges)
+            my_i = rp_seg_search(eoff, i_lo + 64u, count - 1, e);
+            my_u = list[my_i];
+            pos = out_meta[my_u].x + (e - eoff[my_i]);
         }
+        const uint32_t my_v = out_pool[pos];
         const int n_here = (int)(e1 - e0);
         uint32_t cur = 0xFFFFFFFFu;
         float dreg[NJ];
@@ -49,7 +57,7 @@ __global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, cons
             const uint32_t ik = __shfl(my_i, k), vk = __shfl(my_v, k);
             if (ik != cur) {                                    // same for all lanes
                 cur = ik;
-                const uint32_t uk = list[ik];                   // delta rows are indexed by vertex
+                const uint32_t uk = __shfl(my_u, k);            // delta rows are indexed by vertex
                 bool any = false;
 #pragma unroll
                 for (int j = 0; j < NJ; ++j) {
@@ -135,7 +143,7 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
     const uint32_t c_begin = min(n_chunks, gw * per), c_end = min(n_chunks, c_begin + per);
     if (c_begin >= c_end) return;
     const uint32_t last = count - 1;
-    uint32_t i_lo = rp_seg_search(a.ioff, 0, last, c_begin * PULL_CHUNK);
+    uint32_t i_lo = rp_seg_search_wave(a.ioff, 0, last, c_begin * PULL_CHUNK);
     // lane j describes row i_lo + j: destination, pool position of edge e is rbase + e (mod 2^32),
     // and bnd = first edge of row i_lo + j + 1 (the total beyond the list's end)
     uint32_t rv, rbase, bnd;
