@@ -448,7 +448,8 @@ void rp_launch_gat_scatter(ripple_ctx *c, uint32_t l, bool bootstrap) {
     // few rows: one wavefront would read a row of 100+ in-neighbours, one workgroup a row of thousands, with the chip idle
     a.few = few ? 1 : 0;
     a.long_min = few ? 64u : GAT_LONG;
-    a.split_min = few ? ROW_SPLIT_MIN : 64u * ROW_SPLIT_MIN;
+    const bool some = !bootstrap && c->hints_valid && c->last_a[l] <= 131072u;   // in between: split rows of a few thousand entries
+    a.split_min = few ? ROW_SPLIT_MIN : (some ? 4u : 64u) * ROW_SPLIT_MIN;
     a.n_big = &c->ctr->n_big[l];
     a.n_seg = &c->ctr->n_seg[l];
     a.seg_v = c->seg_v;

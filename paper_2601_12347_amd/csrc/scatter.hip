@@ -1092,8 +1092,10 @@ void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l, const uint32_t *count_ptr
     const bool few = c->hints_valid && c->last_cand[l] <= 8192u;
     // few candidates: one wavefront would read a row of 100+ in-neighbours for tens of microseconds with the chip idle
     a.long_min = few ? 64u : MONO_LONG;
-    // a full chip is busy whichever workgroup reads a row: only the longest rows are split, so that none is left running alone
-    a.split_min = few ? ROW_SPLIT_MIN : 64u * ROW_SPLIT_MIN;
+    // a full chip is busy whichever workgroup reads a row: only the longest rows are split, so that none is left running
+    // alone; in between (up to 128 K candidates) a row of a few thousand entries would still outlast everything else
+    const bool some = c->hints_valid && c->last_cand[l] <= 131072u;
+    a.split_min = few ? ROW_SPLIT_MIN : (some ? 4u : 64u) * ROW_SPLIT_MIN;
     a.list = c->all_list;
     a.count_ptr = count_ptr;
     a.queue = listed ? c->eoff[l] : c->list[l]; // neither is written before the hop's set is final
