@@ -167,12 +167,14 @@ def main():
     model = ri.make_model(cfg.model, cfg.widths, cfg.weight_seed)
     log(f"[bench] graph {cfg.name}: {cfg.n} vertices, {cfg.e} edges generated in {time.time() - t0:.1f}s")
     t0 = time.time()
+    # room for every edge the staged batches can add (a long run of large batches on a small graph outgrows the config's)
+    edge_capacity = max(cfg.edge_capacity, len(src) + (args.warmup + args.steps) * bs + 4096)
     if cfg.weighted:
         ctx = rp.ripple_init_graph_weighted(cfg.n, cfg.vertex_capacity, src, dst, ri.edge_weights(len(src), cfg.graph_seed + 100),
-                                            feats, store=cfg.store, edge_capacity=cfg.edge_capacity)
+                                            feats, store=cfg.store, edge_capacity=edge_capacity)
     else:
         ctx = rp.ripple_init_graph(cfg.n, cfg.vertex_capacity, src, dst, feats, store=cfg.store,
-                                   edge_capacity=cfg.edge_capacity)
+                                   edge_capacity=edge_capacity)
     if args.deterministic:
         rp.ripple_set_option(ctx, rp.OPT_DETERMINISTIC, 1)
     if args.split_mfma >= 0:
