@@ -156,6 +156,10 @@ typedef enum {
                                      product); results agree with the fp32 matrix path to rounding */
     RIPPLE_OPT_SPARSE_FRONTIER = 8, /* 0/1 (default 1): a hop whose set was small in the previous batch enters vertices into
                                      its list as they are marked instead of scanning the whole bitmap afterwards */
+    RIPPLE_OPT_ROW_SEGMENTS = 9,  /* >= 0 (default: what the graph's edge capacity can need, at most 262144): max / min and attention
+                                     layers recompute a very long in-row in 512-entry segments, a workgroup each; this is the
+                                     most segments a hop may have queued at a time. Rows that find the queue full are read by
+                                     one workgroup, as all are with 0. Results do not depend on it (sums: up to rounding order). */
     RIPPLE_OPT_DETERMINISTIC = 6  /* 0/1 (default 0), before load_model: every aggregate row is produced by one owner that
                                      adds its sources in a fixed order (no float atomics; rows with a changed in-edge are
                                      recomputed from their in-neighbours), so that two runs over the same operations give

@@ -25,6 +25,7 @@ PHASES = ["ingest", "struct", "frontier", "scatter", "compact", "transform", "ot
 OPT_TIMING, OPT_SCATTER_MODE, OPT_PULL_RATIO, OPT_PROJECT_FIRST, OPT_BF16_MFMA, OPT_SELF_CACHE, OPT_DETERMINISTIC = 0, 1, 2, 3, 4, 5, 6
 OPT_SPLIT_MFMA = 7
 OPT_SPARSE_FRONTIER = 8
+OPT_ROW_SEGMENTS = 9
 AGG = {"sum": 0, "mean": 1, "wsum": 2, "max": 3, "min": 4, "attn": 5}
 SELF = {"none": 0, "concat": 1, "add": 2}
 ACT = {"none": 0, "relu": 1}

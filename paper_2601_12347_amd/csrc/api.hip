@@ -1205,6 +1205,10 @@ extern "C" ripple_status ripple_set_option(ripple_ctx *c, int option, int64_t va
     case RIPPLE_OPT_SPARSE_FRONTIER:
         c->opt_sparse = value ? 1 : 0;
         return RIPPLE_OK;
+    case RIPPLE_OPT_ROW_SEGMENTS:
+        if (value < 0) return fail(c, RIPPLE_EINVAL, "the number of row segments cannot be negative");
+        c->seg_limit = (uint32_t)std::min<long long>(value, 0xffffffffll);
+        return RIPPLE_OK;
     case RIPPLE_OPT_PROJECT_FIRST:
         if (c->state != 1) return fail(c, RIPPLE_ESTATE, "project-first must be chosen before load_model");
         c->opt_project = value ? 1 : 0;

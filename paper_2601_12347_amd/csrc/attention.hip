@@ -458,7 +458,7 @@ void rp_launch_gat_scatter(ripple_ctx *c, uint32_t l, bool bootstrap) {
     a.seg_r = c->seg_r;
     a.seg_part = c->seg_part;
     a.big_cap = c->big_cap;
-    a.seg_cap = c->seg_cap;
+    a.seg_cap = std::min(c->seg_cap, c->seg_limit);
     a.seg_ld = c->seg_ld;
     a.st_src = c->st_src;
     a.st_dst = c->st_dst;

@@ -120,6 +120,7 @@ struct ripple_ctx {
     uint32_t *seg_v = nullptr, *seg_done = nullptr, *seg_base = nullptr, *seg_r = nullptr;
     float *seg_part = nullptr;
     uint32_t big_cap = 0, seg_cap = 0, seg_ld = 0;
+    uint32_t seg_limit = 0xffffffffu;                   // RIPPLE_OPT_ROW_SEGMENTS: segments a hop may queue (<= seg_cap is used)
     float *Pold = nullptr, *sold = nullptr;             // attention hops: projected rows / source scores of A_{l-1} before the batch
     uint32_t xw[RIPPLE_MAX_LAYERS + 1] = {0};           // width of X^l (d_{l-1}, or d_l when projected)
     uint32_t pd_ld = 0;                                 // row stride of PD (64-byte multiple)

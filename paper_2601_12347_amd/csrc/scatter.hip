@@ -1126,7 +1126,7 @@ void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l, const uint32_t *count_ptr
     a.seg_r = c->seg_r;
     a.seg_part = c->seg_part;
     a.big_cap = c->big_cap;
-    a.seg_cap = c->seg_cap;
+    a.seg_cap = std::min(c->seg_cap, c->seg_limit);
     a.seg_ld = c->seg_ld;
     MonoArgs b = a;
     b.list = a.queue;

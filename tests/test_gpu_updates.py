@@ -471,14 +471,18 @@ def test_max_with_hub_rows_and_repeated_feature_updates():
         pair.close()
 
 
-@pytest.mark.parametrize("kind", ["gcn_max", "sage_min"])
-def test_max_min_changed_edges_of_a_hub_are_messages(kind):
+@pytest.mark.parametrize("kind,segments", [("gcn_max", None), ("sage_min", None), ("gcn_max", 0), ("sage_min", 3)])
+def test_max_min_changed_edges_of_a_hub_are_messages(kind, segments):
     """A sink with thousands of in-neighbours is not re-read for an edge that comes or goes (Sec. 3.4.2): an
     added edge can only raise the extreme, a deleted one matters only if its source held it. Hand-made
     batches aimed at the vertex with the longest in-row: additions only, deletions of sources that hold no
-    column's extreme, the deletion of one that does, then changed edges whose sources also change or vanish."""
-    print("case max/min hub sink", kind, flush=True)
+    column's extreme, the deletion of one that does, then changed edges whose sources also change or vanish.
+    When the hub is recomputed its row is read in segments by several workgroups: also run with that switched
+    off and with room for three segments only (rows that find the queue full are read by one workgroup)."""
+    print("case max/min hub sink", kind, segments, flush=True)
     pair, graph = make_pair(n=20000, e=240000, d0=24, kind=kind, widths=(24, 48, 12), seed=161, slack=64, top_share=0.04)
+    if segments is not None:
+        rp.ripple_set_option(pair.ctx, rp.OPT_ROW_SEGMENTS, segments)
     best = np.argmin if kind.endswith("min") else np.argmax
     rng = np.random.default_rng(167)
     try:
@@ -526,13 +530,16 @@ def test_max_min_changed_edges_of_a_hub_are_messages(kind):
         pair.close()
 
 
-def test_attention_changed_edges_of_a_hub_are_messages():
+@pytest.mark.parametrize("segments", [None, 3])
+def test_attention_changed_edges_of_a_hub_are_messages(segments):
     """Edges that come and go at a vertex with thousands of in-neighbours whose own score stays: numerator
     and denominator are patched with the edge's pre-batch weight and row (Sec. 3.4.1) instead of re-reading
     the row; sources that change, appear or vanish in the same batch included. Then the hub's own features
     change, which recomputes its row (split over several workgroups)."""
-    print("case attention hub sink", flush=True)
+    print("case attention hub sink", segments, flush=True)
     pair, graph = make_pair(n=20000, e=240000, d0=24, kind="gat", widths=(24, 48, 12), seed=161, slack=64, top_share=0.04)
+    if segments is not None:                                # room for three segments: most split rows fall back to one workgroup
+        rp.ripple_set_option(pair.ctx, rp.OPT_ROW_SEGMENTS, segments)
     rng = np.random.default_rng(169)
     try:
         deg_in, _ = rp.ripple_get_degrees(pair.ctx, 1, pair.cap)
