@@ -23,16 +23,18 @@ __global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, cons
                                                       const uint32_t *eoff, const float *D, uint32_t ldd, uint32_t d,
                                                       const uint2 *out_meta, const uint32_t *out_pool, float *X,
                                                       const DevCtr *ctr, uint32_t l, int may_pull, int mode, int ratio, int allow_disc) {
+    constexpr int G = (NJ <= 2) ? 8 : (NJ <= 4 ? 4 : (NJ <= 8 ? 2 : 1));   // edges per round
     const int hm = rp_hop_mode(ctr, l, d, mode, ratio, allow_disc);
     if (hm == RP_HOP_DISCOVER || (may_pull && hm == RP_HOP_PULL)) return;
     const uint32_t count = *count_ptr;
     if (count == 0) return;
     const int lane = rp_lane();
     const uint32_t M = eoff[count];
-    const uint32_t n_chunks = (M + PUSH_CHUNK - 1) / PUSH_CHUNK;
+    const uint32_t chunk = (M <= 16384u) ? 16u : PUSH_CHUNK;   // few messages: spread them over more wavefronts
+    const uint32_t n_chunks = (M + chunk - 1) / chunk;
     const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
     for (uint32_t c = gw; c < n_chunks; c += nw) {
-        const uint32_t e0 = c * PUSH_CHUNK, e1 = min(M, e0 + PUSH_CHUNK);
+        const uint32_t e0 = c * chunk, e1 = min(M, e0 + chunk);
         // the chunk's first row by the wavefront together; the 64 rows from there on (vertex, pool position,
         // end) one per lane, so an edge finds its row with shuffles instead of a chain of dependent reads
         const uint32_t i_lo = rp_seg_search_wave(eoff, 0, count - 1, e0);
@@ -50,29 +52,37 @@ __global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, cons
         }
         const uint32_t my_v = out_pool[pos];
         const int n_here = (int)(e1 - e0);
-        uint32_t cur = 0xFFFFFFFFu;
-        float dreg[NJ];
-        bool nz = false;
-        for (int k = 0; k < n_here; ++k) {
-            const uint32_t ik = __shfl(my_i, k), vk = __shfl(my_v, k);
-            if (ik != cur) {                                    // same for all lanes
-                cur = ik;
-                const uint32_t uk = __shfl(my_u, k);            // delta rows are indexed by vertex
-                bool any = false;
+        // G edges per round: their sources' delta rows are requested together (consecutive edges mostly share
+        // the source: the repeats are cache hits), then the additions go out
+        for (int k0 = 0; k0 < n_here; k0 += G) {
+            float dreg[G][NJ];
+            uint32_t vk[G];
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const int k = min(k0 + g, n_here - 1);
+                const uint32_t uk = __shfl(my_u, k);
+                vk[g] = __shfl(my_v, k);
 #pragma unroll
                 for (int j = 0; j < NJ; ++j) {
-                    uint32_t col = lane + 64 * j;
-                    dreg[j] = (col < d) ? D[(size_t)uk * ldd + col] : 0.0f;
-                    any |= dreg[j] != 0.0f;
+                    const uint32_t col = lane + 64 * j;
+                    dreg[g][j] = (col < d) ? D[(size_t)uk * ldd + col] : 0.0f;
                 }
-                nz = __ballot(any) != 0ull;
             }
-            if (!nz) continue;                                  // an all-zero delta changes nothing
-            float *xr = X + (size_t)vk * d;
 #pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-                uint32_t col = lane + 64 * j;
-                if (col < d) unsafeAtomicAdd(&xr[col], dreg[j]);
+            for (int g = 0; g < G; ++g) {
+                if (k0 + g < n_here) {
+                    bool any = false;
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) any |= dreg[g][j] != 0.0f;
+                    if (__ballot(any) != 0ull) {                // an all-zero delta changes nothing
+                        float *xr = X + (size_t)vk[g] * d;
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j) {
+                            const uint32_t col = lane + 64 * j;
+                            if (col < d) unsafeAtomicAdd(&xr[col], dreg[g][j]);
+                        }
+                    }
+                }
             }
         }
     }
