@@ -51,6 +51,43 @@ __device__ __forceinline__ void sparse_enter(const SparseArgs &s, uint32_t v, bo
     if (fresh) s.list[base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull))] = v;
 }
 
+// The same for T vertices per lane: the T marks go out together and one reservation covers all of them
+// (two round trips instead of 2 T). To be called by all 64 lanes together.
+template <int T>
+__device__ __forceinline__ void sparse_enter_many(const SparseArgs &s, const uint32_t *v, bool from_edge) {
+    bool live[T], fresh[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) live[t] = v[t] != 0xFFFFFFFFu && rp_bit(s.alive, v[t]);
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        fresh[t] = false;
+        if (live[t]) {
+            const uint32_t m = 1u << (v[t] & 31);
+            fresh[t] = !(atomicOr(&s.bm[v[t] >> 5], m) & m);
+        }
+    }
+    unsigned long long mask[T];
+    uint32_t total = 0;
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        mask[t] = __ballot(fresh[t]);
+        total += (uint32_t)__popcll(mask[t]);
+    }
+    if (!total) return;
+    const int lane = rp_lane();
+    uint32_t base = 0;
+    if (lane == 0) {
+        base = atomicAdd(s.count, total);
+        if (from_edge && s.touched) atomicAdd(s.touched, total);
+    }
+    base = __shfl(base, 0);
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        if (fresh[t]) s.list[base + (uint32_t)__popcll(mask[t] & ((1ull << lane) - 1ull))] = v[t];
+        base += (uint32_t)__popcll(mask[t]);
+    }
+}
+
 template <bool SPARSE>
 __device__ __forceinline__ void frontier_walk(const uint32_t *list, const uint32_t *count_ptr, const uint32_t *eoff,
                                               const uint2 *out_meta, const uint32_t *out_pool, uint8_t *mk,
@@ -60,13 +97,15 @@ __device__ __forceinline__ void frontier_walk(const uint32_t *list, const uint32
     constexpr int T = MARK_CHUNK / 64;
     const int lane = rp_lane();
     const uint32_t M = eoff[count];
-    const uint32_t n_chunks = (M + MARK_CHUNK - 1) / MARK_CHUNK;
+    // few out-edges: 64-edge chunks (only the first of a lane's T slots is used) so that more wavefronts share them
+    const uint32_t chunk = (SPARSE && M <= 16384u) ? 64u : (uint32_t)MARK_CHUNK;
+    const uint32_t n_chunks = (M + chunk - 1) / chunk;
     const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
     const uint32_t per = (n_chunks + nw - 1) / nw;
     const uint32_t c_begin = min(n_chunks, gw * per), c_end = min(n_chunks, c_begin + per);
     if (c_begin >= c_end) return;
     const uint32_t last = count - 1;
-    uint32_t i_lo = rp_seg_search_wave(eoff, 0, last, c_begin * MARK_CHUNK);
+    uint32_t i_lo = rp_seg_search_wave(eoff, 0, last, c_begin * chunk);
     uint32_t rbase, bnd;                                    // lane j: row i_lo + j
     {
         const uint32_t ri = min(last, i_lo + lane);
@@ -74,7 +113,7 @@ __device__ __forceinline__ void frontier_walk(const uint32_t *list, const uint32
         bnd = eoff[min(count, i_lo + 1 + lane)];
     }
     for (uint32_t c = c_begin; c < c_end; ++c) {
-        const uint32_t e0 = c * MARK_CHUNK, e1 = min(M, e0 + MARK_CHUNK);
+        const uint32_t e0 = c * chunk, e1 = min(M, e0 + chunk);
         const bool fits = __shfl(bnd, 63) > e1 - 1;         // every row of the chunk is among the 64 held
         uint32_t v[T];
         uint32_t i_nx;
@@ -106,10 +145,12 @@ __device__ __forceinline__ void frontier_walk(const uint32_t *list, const uint32
             rbase_n = out_meta[list[ri]].x - eoff[ri];
             bnd_n = eoff[min(count, i_nx + 1 + lane)];
         }
+        if (SPARSE) {
+            sparse_enter_many<T>(sp, v, true);
+        } else {
 #pragma unroll
-        for (int t = 0; t < T; ++t) {
-            if (SPARSE) sparse_enter(sp, v[t], v[t] != 0xFFFFFFFFu, true);
-            else if (v[t] != 0xFFFFFFFFu) mk[v[t]] = 1;  // plain byte stores: idempotent, no atomics
+            for (int t = 0; t < T; ++t)
+                if (v[t] != 0xFFFFFFFFu) mk[v[t]] = 1;       // plain byte stores: idempotent, no atomics
         }
         i_lo = i_nx;
         rbase = rbase_n;
