@@ -47,7 +47,7 @@ def algorithmic_work(st, model, widths, store, L, layer_info, n_edges=0):
                   pairs and column ids once, and each distinct destination row of the cached
                   aggregate read and written once;
     frontier(l):  index pairs + column ids of the walked out-rows, the list written; not priced
-                  where the hop discovered A_l while scattering (messages * 4 >= edges, the
+                  where the hop discovered A_l while scattering (messages * 8 >= edges, the
                   library's own rule), since no frontier kernel runs there;
     transform(l): per dirty row the gathered input row, old H read, new H and delta written;
                   flops 2*K*d_out per row (plus the hidden stage for two-stage updates). For
@@ -65,7 +65,7 @@ def algorithmic_work(st, model, widths, store, L, layer_info, n_edges=0):
         out[("scatter", l)] = dict(bytes=a_prev * w_agg * 4 + 8 * a_prev + 4 * m_l + 2 * t_l * w_agg * 4, flops=m_l * w_agg,
                                    # what a cache-less per-message scheme moves: one message row gathered per message
                                    msg_bytes=m_l * (w_agg * 4 + 4) + 2 * t_l * w_agg * 4)
-        discovered = l >= 2 and n_edges and m_l * 4 >= n_edges * max(st.batches, 1)
+        discovered = l >= 2 and n_edges and m_l * 8 >= n_edges * max(st.batches, 1)
         if not discovered:
             out[("frontier", l)] = dict(bytes=8 * a_prev + 4 * m_l + 4 * a_l, flops=0)
         self_w = lay["d_in"] if lay["self"] != "none" else 0

@@ -963,7 +963,7 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
             // pull wins when m * row_bytes * ratio >= 8 * in-edges; remember if push won by a factor of 16
             const unsigned long long lhs = (unsigned long long)h.m[l] * c->xw[l] * 4ull * (unsigned)c->opt_pull_ratio * 16ull;
             c->push_margin[l] = lhs < 8ull * h.isum[l];
-            c->disc_near[l] = (unsigned long long)h.m[l] * 32ull >= h.n_edges;     // threshold: m * 4 >= edges
+            c->disc_near[l] = (unsigned long long)h.m[l] * 64ull >= h.n_edges;     // threshold: m * 8 >= edges
         }
         if (!multi)
             for (uint32_t l = 0; l <= c->L; ++l) c->last_a[l] = h.a[l];

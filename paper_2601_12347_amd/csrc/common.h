@@ -291,7 +291,7 @@ __device__ __forceinline__ uint32_t rp_count_le(uint32_t b, uint32_t e) {
 #define RP_HOP_DISCOVER 2
 __device__ __forceinline__ int rp_hop_mode(const DevCtr *ctr, uint32_t l, uint32_t d, int mode, int ratio, int allow_disc) {
     const unsigned long long m = ctr->m[l];
-    if (allow_disc && m > 0 && (mode == 3 || ((mode == 0 || mode == 4) && m * 4ull >= ctr->n_edges))) return RP_HOP_DISCOVER;
+    if (allow_disc && m > 0 && (mode == 3 || ((mode == 0 || mode == 4) && m * 8ull >= ctr->n_edges))) return RP_HOP_DISCOVER;
     if (mode == 1) return RP_HOP_PUSH;
     if (mode >= 2) return RP_HOP_PULL;
     return (m > 0 && m * d * 4ull * (unsigned long long)ratio >= 8ull * ctr->isum[l]) ? RP_HOP_PULL : RP_HOP_PUSH;
