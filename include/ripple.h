@@ -143,7 +143,7 @@ typedef enum {
     RIPPLE_OPT_TIMING = 0,        /* 0/1: record HIP events around every kernel class (default 0) */
     RIPPLE_OPT_SCATTER_MODE = 1,  /* 0 auto per hop, 1 push (float atomics), 2 pull (segmented reduction over the in-rows of A_l),
                                      3 discover from hop 2 on (one scan of all in-rows gathers the messages and finds A_l) */
-    RIPPLE_OPT_PULL_RATIO = 2,    /* auto mode pulls when messages * row_bytes * ratio >= 8 * scanned in-edges (default 2) */
+    RIPPLE_OPT_PULL_RATIO = 2,    /* auto mode pulls when messages * row_bytes * ratio >= 8 * scanned in-edges (default 1) */
     RIPPLE_OPT_BF16_MFMA = 4,     /* 0/1 (default 1): with bf16 storage, multiply on the bf16 matrix cores (fp32 accumulation);
                                      0 keeps the fp32 matrix path on bf16-rounded inputs */
     RIPPLE_OPT_PROJECT_FIRST = 3, /* 0/1 (default 1), before load_model: layers with one linear map and d_out <= d_in/2

@@ -181,7 +181,7 @@ struct ripple_ctx {
     int opt_sparse = 1;                         // small frontiers are listed as they are marked (no bitmap scan)
     int opt_split = 0;                          // fp32 storage: products on the bf16 matrix cores, operands split in three (read by load_model)
     int opt_deterministic = 0;                  // bit-reproducible aggregation (owner kernels, no float atomics)
-    int opt_pull_ratio = 2;                     // pull when messages * width * ratio >= scanned in-edges
+    int opt_pull_ratio = 1;                     // pull when messages * width * ratio >= scanned in-edges
     ripple_stats stats;
     PhaseTimer *timer = nullptr;
     uint32_t n_cu = 256;
