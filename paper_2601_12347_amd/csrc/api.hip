@@ -750,7 +750,7 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
         if (rp_layer_mono(c, l)) {                     // max / min: keep, raise or recompute, then prune (Sec. 3.4.2)
             const bool listed = small_frontier(c, l, n, multi) && c->last_cand[l] <= SPARSE_MAX_ROWS;
             t = rp_timer_begin(c);
-            if (listed) rp_launch_candidates_sparse(c, l, layer_self(c, l));
+            if (listed) rp_launch_candidates_sparse(c, l, layer_self(c, l), RP_MONO_LISTED_LONG);
             else rp_launch_frontier_mark(c, l, false);
             rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
             if (!listed) {

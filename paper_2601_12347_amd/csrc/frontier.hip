@@ -28,34 +28,17 @@ struct SparseArgs {
     uint32_t struct_cap;
     const uint32_t *list0, *count0, *bm_vadd;
     int self_term;
+    // optional second list: vertices with more than long_min in-neighbours are appended there instead
+    const uint2 *in_meta;
+    uint32_t long_min;
+    uint32_t *long_list, *long_count;
 };
 
-// to be called by all 64 lanes together
-__device__ __forceinline__ void sparse_enter(const SparseArgs &s, uint32_t v, bool valid, bool from_edge) {
-    bool fresh = false;
-    if (valid && rp_bit(s.alive, v)) {
-        const uint32_t m = 1u << (v & 31);
-        fresh = !(atomicOr(&s.bm[v >> 5], m) & m);
-    }
-    const unsigned long long mask = __ballot(fresh);
-    if (!mask) return;
-    const int lane = rp_lane();
-    const int leader = __ffsll((long long)mask) - 1;
-    const uint32_t k = (uint32_t)__popcll(mask);
-    uint32_t base = 0;
-    if (lane == leader) {
-        base = atomicAdd(s.count, k);
-        if (from_edge && s.touched) atomicAdd(s.touched, k);
-    }
-    base = __shfl(base, leader);
-    if (fresh) s.list[base + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull))] = v;
-}
-
-// The same for T vertices per lane: the T marks go out together and one reservation covers all of them
-// (two round trips instead of 2 T). To be called by all 64 lanes together.
+// T vertices per lane (0xFFFFFFFF: none): the T marks go out together and one reservation covers all of
+// them (two round trips instead of 2 T). To be called by all 64 lanes together.
 template <int T>
 __device__ __forceinline__ void sparse_enter_many(const SparseArgs &s, const uint32_t *v, bool from_edge) {
-    bool live[T], fresh[T];
+    bool live[T], fresh[T], lng[T];
 #pragma unroll
     for (int t = 0; t < T; ++t) live[t] = v[t] != 0xFFFFFFFFu && rp_bit(s.alive, v[t]);
 #pragma unroll
@@ -66,26 +49,41 @@ __device__ __forceinline__ void sparse_enter_many(const SparseArgs &s, const uin
             fresh[t] = !(atomicOr(&s.bm[v[t] >> 5], m) & m);
         }
     }
-    unsigned long long mask[T];
-    uint32_t total = 0;
+#pragma unroll
+    for (int t = 0; t < T; ++t) lng[t] = fresh[t] && s.long_list && s.in_meta[v[t]].y > s.long_min;
+    unsigned long long mask[T], lmask[T];
+    uint32_t total = 0, ltotal = 0;
 #pragma unroll
     for (int t = 0; t < T; ++t) {
-        mask[t] = __ballot(fresh[t]);
+        mask[t] = __ballot(fresh[t] && !lng[t]);
+        lmask[t] = __ballot(lng[t]);
         total += (uint32_t)__popcll(mask[t]);
+        ltotal += (uint32_t)__popcll(lmask[t]);
     }
-    if (!total) return;
+    if (!(total + ltotal)) return;
     const int lane = rp_lane();
-    uint32_t base = 0;
+    uint32_t base = 0, lbase = 0;
     if (lane == 0) {
-        base = atomicAdd(s.count, total);
-        if (from_edge && s.touched) atomicAdd(s.touched, total);
+        if (total) base = atomicAdd(s.count, total);
+        if (ltotal) lbase = atomicAdd(s.long_count, ltotal);
+        if (from_edge && s.touched) atomicAdd(s.touched, total + ltotal);
     }
     base = __shfl(base, 0);
+    lbase = __shfl(lbase, 0);
+    const unsigned long long below = (1ull << lane) - 1ull;
 #pragma unroll
     for (int t = 0; t < T; ++t) {
-        if (fresh[t]) s.list[base + (uint32_t)__popcll(mask[t] & ((1ull << lane) - 1ull))] = v[t];
+        if (fresh[t] && !lng[t]) s.list[base + (uint32_t)__popcll(mask[t] & below)] = v[t];
+        if (lng[t]) s.long_list[lbase + (uint32_t)__popcll(lmask[t] & below)] = v[t];
         base += (uint32_t)__popcll(mask[t]);
+        lbase += (uint32_t)__popcll(lmask[t]);
     }
+}
+
+// one vertex per valid lane; to be called by all 64 lanes together
+__device__ __forceinline__ void sparse_enter(const SparseArgs &s, uint32_t v, bool valid, bool from_edge) {
+    const uint32_t one[1] = {valid ? v : 0xFFFFFFFFu};
+    sparse_enter_many<1>(s, one, from_edge);
 }
 
 template <bool SPARSE>
@@ -669,14 +667,21 @@ static SparseArgs sparse_args(ripple_ctx *c, uint32_t l, uint32_t *list, uint32_
     sp.count0 = &c->ctr->a[0];
     sp.bm_vadd = c->bm_vadd;
     sp.self_term = self_term ? 1 : 0;
+    sp.in_meta = c->in_meta;
+    sp.long_min = 0;
+    sp.long_list = nullptr;
+    sp.long_count = nullptr;
     return sp;
 }
 
 // Candidates of a small max / min hop, listed while they are marked: the set of rp_launch_candidates
 // (with A_{l-1} when the layer has a self term) in bm[l] and, unordered, in c->all_list, count in
 // ctr->cand[l] (zero since the batch began).
-void rp_launch_candidates_sparse(ripple_ctx *c, uint32_t l, bool self_term) {
-    const SparseArgs sp = sparse_args(c, l, c->all_list, &c->ctr->cand[l], self_term);
+void rp_launch_candidates_sparse(ripple_ctx *c, uint32_t l, bool self_term, uint32_t long_min) {
+    SparseArgs sp = sparse_args(c, l, c->all_list, &c->ctr->cand[l], self_term);
+    sp.long_min = long_min;                              // candidates with longer in-rows: straight into the queue of the
+    sp.long_list = c->eoff[l];                           // workgroup role (free until the hop's set is final), count in
+    sp.long_count = &c->ctr->n_long[l];                  // ctr->n_long[l] (zero since the batch began)
     hipLaunchKernelGGL(k_frontier_sparse, dim3(c->n_cu), dim3(256), 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],
                        c->eoff[l - 1], c->out_meta, c->out_pool, sp);
 }

@@ -18,7 +18,7 @@ void rp_launch_alive_list(ripple_ctx *c);
 void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool want_out, bool want_in,
                                 bool accumulate_rep, bool pruned = false);
 void rp_launch_candidates(ripple_ctx *c, uint32_t l);
-void rp_launch_candidates_sparse(ripple_ctx *c, uint32_t l, bool self_term);
+void rp_launch_candidates_sparse(ripple_ctx *c, uint32_t l, bool self_term, uint32_t long_min);
 void rp_launch_list_offsets(ripple_ctx *c, uint32_t l, bool want_out);
 void rp_launch_bitmap_to_list(ripple_ctx *c, uint32_t *bitmap, uint32_t *out_list, uint32_t *count_d);
 void rp_launch_list_eoff(ripple_ctx *c, uint32_t l);

@@ -762,8 +762,9 @@ __device__ __forceinline__ bool mono_finish(const MonoArgs &a, uint32_t v, bool 
     return changed;
 }
 
+// wavefront gw of nw: the candidates gw, gw + nw, ... of the list
 template <int NJ, int IS_MIN, int STORE>
-__global__ __launch_bounds__(256) void k_scatter_mono(MonoArgs a) {
+__device__ __forceinline__ void mono_wave_role(const MonoArgs &a, uint32_t gw, uint32_t nw) {
     constexpr int GC = (NJ <= 4) ? 8 : 32 / NJ;                // senders in flight (two rows each)
     constexpr int GR = (NJ <= 2) ? 32 : 64 / NJ;               // rows in flight when recomputing: round trips pace a row
     constexpr int T = MONO_LONG / 64;
@@ -771,13 +772,15 @@ __global__ __launch_bounds__(256) void k_scatter_mono(MonoArgs a) {
     const int lane = rp_lane();
     const uint32_t d = a.d;
     const float ident = IS_MIN ? INFINITY : -INFINITY;
-    const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
     uint32_t n_same = 0, n_inc = 0, n_rec = 0;
     for (uint32_t i = gw; i < count; i += nw) {
         const uint32_t v = a.list[i];
         const uint2 m = a.in_meta[v];
         if (m.y > a.long_min) {
-            if (lane == 0) a.queue[atomicAdd(a.queue_count, 1u)] = v;
+            if (lane == 0) {
+                if (a.queue) a.queue[atomicAdd(a.queue_count, 1u)] = v;
+                else a.ctr->error = 9;                          // the long rows were meant to be sorted out already
+            }
             continue;
         }
         const bool created = rp_bit(a.bm_vadd, v);
@@ -832,10 +835,16 @@ __global__ __launch_bounds__(256) void k_scatter_mono(MonoArgs a) {
     }
 }
 
+template <int NJ, int IS_MIN, int STORE>
+__global__ __launch_bounds__(256) void k_scatter_mono(MonoArgs a) {
+    mono_wave_role<NJ, IS_MIN, STORE>(a, (blockIdx.x * blockDim.x + threadIdx.x) >> 6, (gridDim.x * blockDim.x) >> 6);
+}
+
 // One workgroup of TEAM wavefronts per candidate with a long in-row: wavefront w takes the 64-entry
 // blocks w, w + TEAM, ...; the wavefronts' partial results meet in LDS and wavefront 0 finishes the row.
+// Workgroup bid of nb: the rows bid, bid + nb, ... of the queue.
 template <int NJ, int IS_MIN, int STORE, int TEAM>
-__global__ __launch_bounds__(TEAM * 64) void k_scatter_mono_long(MonoArgs a) {
+__device__ __forceinline__ void mono_team_role(const MonoArgs &a, uint32_t bid, uint32_t nb) {
     constexpr int GC = (NJ <= 4) ? 8 : 32 / NJ;
     constexpr int GR = (NJ <= 2) ? 32 : 64 / NJ;               // rows in flight: a long row is paced by round trips
     __shared__ float s_val[TEAM][NJ * 64];
@@ -852,7 +861,7 @@ __global__ __launch_bounds__(TEAM * 64) void k_scatter_mono_long(MonoArgs a) {
     const int lane = rp_lane(), wave = threadIdx.x >> 6;
     const uint32_t d = a.d;
     const float ident = IS_MIN ? INFINITY : -INFINITY;
-    for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) {
+    for (uint32_t i = bid; i < count; i += nb) {
         const uint32_t v = a.list[i];
         const uint2 m = a.in_meta[v];
         const bool created = rp_bit(a.bm_vadd, v);
@@ -1023,6 +1032,24 @@ __global__ __launch_bounds__(TEAM * 64) void k_scatter_mono_long(MonoArgs a) {
     }
 }
 
+template <int NJ, int IS_MIN, int STORE, int TEAM>
+__global__ __launch_bounds__(TEAM * 64) void k_scatter_mono_long(MonoArgs a) {
+    mono_team_role<NJ, IS_MIN, STORE, TEAM>(a, blockIdx.x, gridDim.x);
+}
+
+// Small hops, whose long rows were sorted out while the candidates were listed: both roles in one launch
+// (the first team_blocks workgroups take a queued long row each, the wavefronts of the others a short
+// candidate each), which saves one of the hop's dependent launches.
+template <int NJ, int IS_MIN, int STORE, int TEAM>
+__global__ __launch_bounds__(TEAM * 64) void k_scatter_mono_both(MonoArgs a, MonoArgs b, uint32_t team_blocks) {
+    if (blockIdx.x < team_blocks) {
+        mono_team_role<NJ, IS_MIN, STORE, TEAM>(b, blockIdx.x, team_blocks);
+    } else {
+        const uint32_t wb = blockIdx.x - team_blocks, nwb = gridDim.x - team_blocks;
+        mono_wave_role<NJ, IS_MIN, STORE>(a, (wb * blockDim.x + threadIdx.x) >> 6, (nwb * blockDim.x) >> 6);
+    }
+}
+
 // One workgroup per queued segment of a very long row that is recomputed: the extreme over the segment's
 // ROW_SEG in-neighbours goes to the segment's partial row; the workgroup that finishes a row's last
 // segment takes the extreme over the partial rows and finishes the row.
@@ -1101,14 +1128,15 @@ void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l, const uint32_t *count_ptr
     MonoArgs a;
     const bool few = c->hints_valid && c->last_cand[l] <= 8192u;
     // few candidates: one wavefront would read a row of 100+ in-neighbours for tens of microseconds with the chip idle
-    a.long_min = few ? 64u : MONO_LONG;
+    a.long_min = (few || listed) ? RP_MONO_LISTED_LONG : MONO_LONG;   // (a listed hop's long rows were sorted out with this limit)
     // a full chip is busy whichever workgroup reads a row: only the longest rows are split, so that none is left running
     // alone; in between (up to 128 K candidates) a row of a few thousand entries would still outlast everything else
     const bool some = c->hints_valid && c->last_cand[l] <= 131072u;
     a.split_min = few ? ROW_SPLIT_MIN : (some ? 4u : 64u) * ROW_SPLIT_MIN;
     a.list = c->all_list;
     a.count_ptr = count_ptr;
-    a.queue = listed ? c->eoff[l] : c->list[l]; // neither is written before the hop's set is final
+    // listed: the long rows are in c->eoff[l] already (rp_launch_candidates_sparse), nothing is queued here
+    a.queue = listed ? nullptr : c->list[l];    // not written before the hop's set is final
     a.out_list = listed ? c->list[l] : nullptr;
     a.out_count = &c->ctr->a[l];                // zero since the batch began
     a.queue_count = &c->ctr->n_long[l];         // zero since the batch began
@@ -1139,15 +1167,21 @@ void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l, const uint32_t *count_ptr
     a.seg_cap = std::min(c->seg_cap, c->seg_limit);
     a.seg_ld = c->seg_ld;
     MonoArgs b = a;
-    b.list = a.queue;
+    b.list = listed ? c->eoff[l] : a.queue;
     b.count_ptr = &c->ctr->n_long[l];
     const bool is_min = c->layers[l - 1].agg == RIPPLE_AGG_MIN;
     // few candidates: every workgroup resident at once, so none waits for a slot behind one that holds a long chain of reads
     dim3 grid(c->n_cu * (few ? 4 : 8)), block(256);
 #define MONO_PAIR(NJ, MN, ST, TEAM)                                                                          \
     do {                                                                                                     \
-        hipLaunchKernelGGL((k_scatter_mono<NJ, MN, ST>), grid, block, 0, c->stream, a);                      \
-        hipLaunchKernelGGL((k_scatter_mono_long<NJ, MN, ST, TEAM>), dim3(c->n_cu * 2), dim3(TEAM * 64), 0, c->stream, b); \
+        if (listed) {                                                                                        \
+            /* every workgroup resident at once: half the compute units' worth for each role */              \
+            hipLaunchKernelGGL((k_scatter_mono_both<NJ, MN, ST, TEAM>), dim3(c->n_cu / 2 + (c->n_cu / 2) * (16 / TEAM)), \
+                               dim3(TEAM * 64), 0, c->stream, a, b, c->n_cu / 2);                            \
+        } else {                                                                                             \
+            hipLaunchKernelGGL((k_scatter_mono<NJ, MN, ST>), grid, block, 0, c->stream, a);                  \
+            hipLaunchKernelGGL((k_scatter_mono_long<NJ, MN, ST, TEAM>), dim3(c->n_cu * 2), dim3(TEAM * 64), 0, c->stream, b); \
+        }                                                                                                    \
         hipLaunchKernelGGL((k_scatter_mono_seg<NJ, MN, ST, ROW_SEG / 64>), dim3(c->n_cu * 4), dim3(ROW_SEG), 0, c->stream, b); \
     } while (0)
 #define MONO_CASE(NJ, TEAM)                                                                                  \
