@@ -782,9 +782,10 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
             rp_launch_gat_project(c, l, c->list[l - 1], &c->ctr->a[l - 1]);
             rp_launch_gat_scores(c, l, c->list[l - 1], &c->ctr->a[l - 1]);
             rp_timer_end(c, t, RIPPLE_PH_OTHER, (int)l);
-            if (small_frontier(c, l, n, multi)) {
+            const bool listed = small_frontier(c, l, n, multi);
+            if (listed) {
                 t = rp_timer_begin(c);
-                rp_launch_frontier_sparse(c, l, true, l < c->L);
+                rp_launch_frontier_sparse(c, l, true, l < c->L, RP_MONO_LISTED_LONG);
                 rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
             } else {
                 t = rp_timer_begin(c);
@@ -795,7 +796,7 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
                 rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l);
             }
             t = rp_timer_begin(c);
-            rp_launch_gat_scatter(c, l, false);
+            rp_launch_gat_scatter(c, l, false, listed);
             rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l);
             t = rp_timer_begin(c);
             rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], l < c->L);

@@ -146,19 +146,19 @@ __device__ __forceinline__ float gat_wave_sum(float x) {
     return x;
 }
 
+// wavefront gw of nw: the vertices gw, gw + nw, ... of the list
 template <int NJ>
-__global__ __launch_bounds__(256) void k_gat_scatter(GatArgs a) {
+__device__ __forceinline__ void gat_wave_role(const GatArgs &a, uint32_t gw, uint32_t nw) {
     constexpr int G = (NJ <= 1) ? 8 : (NJ <= 2 ? 4 : (NJ <= 4 ? 2 : 1));
     constexpr int GR = (NJ <= 1) ? 16 : (NJ <= 16 ? 16 / NJ : 1);
     const uint32_t count = *a.count_ptr;
     const int lane = rp_lane();
     const uint32_t d = a.d;
-    const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
     for (uint32_t i = gw; i < count; i += nw) {
         const uint32_t v = a.list[i];
         const uint2 m = a.in_meta[v];
-        if (m.y > a.long_min) {
-            if (lane == 0) a.queue[atomicAdd(a.queue_count, 1u)] = v;
+        if (m.y > a.long_min) {                                // queued here, or already when the hop's vertices were listed
+            if (lane == 0 && a.queue) a.queue[atomicAdd(a.queue_count, 1u)] = v;
             continue;
         }
         bool recompute = a.all || rp_bit(a.bm_prev, v) || rp_bit(a.bm_sink, v) || rp_bit(a.bm_vadd, v);
@@ -194,9 +194,15 @@ __global__ __launch_bounds__(256) void k_gat_scatter(GatArgs a) {
     }
 }
 
-// one workgroup of TEAM wavefronts per long in-row; partial sums meet in LDS and are added in wavefront order
+template <int NJ>
+__global__ __launch_bounds__(256) void k_gat_scatter(GatArgs a) {
+    gat_wave_role<NJ>(a, (blockIdx.x * blockDim.x + threadIdx.x) >> 6, (gridDim.x * blockDim.x) >> 6);
+}
+
+// one workgroup of TEAM wavefronts per long in-row; partial sums meet in LDS and are added in wavefront order.
+// Workgroup bid of nb: the rows bid, bid + nb, ... of the queue.
 template <int NJ, int TEAM>
-__global__ __launch_bounds__(TEAM * 64) void k_gat_scatter_long(GatArgs a) {
+__device__ __forceinline__ void gat_team_role(const GatArgs &a, uint32_t bid, uint32_t nb) {
     constexpr int G = (NJ <= 1) ? 8 : (NJ <= 2 ? 4 : (NJ <= 4 ? 2 : 1));
     constexpr int GR = (NJ <= 2) ? 16 : 32 / NJ;
     constexpr int IDS = 4;                                     // blocks of in-neighbour ids in flight while looking for changed ones
@@ -208,7 +214,7 @@ __global__ __launch_bounds__(TEAM * 64) void k_gat_scatter_long(GatArgs a) {
     const uint32_t n_st = *a.n_struct;
     const int lane = rp_lane(), wave = threadIdx.x >> 6;
     const uint32_t d = a.d;
-    for (uint32_t i = blockIdx.x; i < count; i += gridDim.x) {
+    for (uint32_t i = bid; i < count; i += nb) {
         const uint32_t v = a.list[i];
         const uint2 m = a.in_meta[v];
         bool recompute = a.all || rp_bit(a.bm_prev, v) || rp_bit(a.bm_vadd, v);
@@ -345,6 +351,23 @@ __global__ __launch_bounds__(TEAM * 64) void k_gat_scatter_long(GatArgs a) {
     }
 }
 
+template <int NJ, int TEAM>
+__global__ __launch_bounds__(TEAM * 64) void k_gat_scatter_long(GatArgs a) {
+    gat_team_role<NJ, TEAM>(a, blockIdx.x, gridDim.x);
+}
+
+// Small hops, whose long rows were queued while the hop's vertices were listed: both roles in one launch
+// (the first team_blocks workgroups take a long row each, the wavefronts of the others a short one each).
+template <int NJ, int TEAM>
+__global__ __launch_bounds__(TEAM * 64) void k_gat_scatter_both(GatArgs a, GatArgs b, uint32_t team_blocks) {
+    if (blockIdx.x < team_blocks) {
+        gat_team_role<NJ, TEAM>(b, blockIdx.x, team_blocks);
+    } else {
+        const uint32_t wb = blockIdx.x - team_blocks, nwb = gridDim.x - team_blocks;
+        gat_wave_role<NJ>(a, (wb * blockDim.x + threadIdx.x) >> 6, (nwb * blockDim.x) >> 6);
+    }
+}
+
 // One workgroup per queued segment of a very long row that is recomputed: numerator and denominator over
 // the segment's ROW_SEG in-neighbours go to the segment's partial row; the workgroup that finishes a row's
 // last segment adds the partial rows up in segment order and stores the row.
@@ -423,7 +446,7 @@ __global__ __launch_bounds__(TEAM * 64) void k_gat_scatter_seg(GatArgs a) {
 }
 
 // bootstrap: every live vertex (c->all_list, count in ctr->a[0]) is recomputed
-void rp_launch_gat_scatter(ripple_ctx *c, uint32_t l, bool bootstrap) {
+void rp_launch_gat_scatter(ripple_ctx *c, uint32_t l, bool bootstrap, bool prequeued) {
     const LayerDev &ly = c->layers[l - 1];
     GatArgs a;
     a.list = bootstrap ? c->all_list : c->list[l];
@@ -446,8 +469,8 @@ void rp_launch_gat_scatter(ripple_ctx *c, uint32_t l, bool bootstrap) {
     a.all = bootstrap ? 1 : 0;
     const bool few = !bootstrap && c->hints_valid && c->last_a[l] <= 8192u;
     // few rows: one wavefront would read a row of 100+ in-neighbours, one workgroup a row of thousands, with the chip idle
-    a.few = few ? 1 : 0;
-    a.long_min = few ? 64u : GAT_LONG;
+    a.few = (few || prequeued) ? 1 : 0;
+    a.long_min = (few || prequeued) ? RP_MONO_LISTED_LONG : GAT_LONG;   // (the limit the long rows were queued with)
     const bool some = !bootstrap && c->hints_valid && c->last_a[l] <= 131072u;   // in between: split rows of a few thousand entries
     a.split_min = few ? ROW_SPLIT_MIN : (some ? 4u : 64u) * ROW_SPLIT_MIN;
     a.n_big = &c->ctr->n_big[l];
@@ -472,12 +495,18 @@ void rp_launch_gat_scatter(ripple_ctx *c, uint32_t l, bool bootstrap) {
     }
     GatArgs b = a;
     b.list = a.queue;
+    if (prequeued) a.queue = nullptr;                    // the wavefront role skips the long rows: they are in the queue already
     b.count_ptr = &c->ctr->n_long[l];
     dim3 grid(c->n_cu * (few ? 4 : 8)), block(256);
 #define GAT_CASE(NJ, TEAM)                                                                                   \
     do {                                                                                                     \
-        hipLaunchKernelGGL((k_gat_scatter<NJ>), grid, block, 0, c->stream, a);                               \
-        hipLaunchKernelGGL((k_gat_scatter_long<NJ, TEAM>), dim3(c->n_cu * 2), dim3(TEAM * 64), 0, c->stream, b); \
+        if (prequeued) { /* every workgroup resident at once: half the compute units' worth for each role */ \
+            hipLaunchKernelGGL((k_gat_scatter_both<NJ, TEAM>), dim3(c->n_cu / 2 + (c->n_cu / 2) * (16 / TEAM)),  \
+                               dim3(TEAM * 64), 0, c->stream, a, b, c->n_cu / 2);                            \
+        } else {                                                                                             \
+            hipLaunchKernelGGL((k_gat_scatter<NJ>), grid, block, 0, c->stream, a);                           \
+            hipLaunchKernelGGL((k_gat_scatter_long<NJ, TEAM>), dim3(c->n_cu * 2), dim3(TEAM * 64), 0, c->stream, b); \
+        }                                                                                                    \
         hipLaunchKernelGGL((k_gat_scatter_seg<NJ, ROW_SEG / 64>), dim3(c->n_cu * 4), dim3(ROW_SEG), 0, c->stream, b); \
     } while (0)
     if (a.d <= 64) GAT_CASE(1, 16);

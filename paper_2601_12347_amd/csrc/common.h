@@ -52,7 +52,7 @@ struct DevCtr {                      // device-resident counters, one instance p
     uint32_t pad1;
 };
 
-#define RP_MONO_LISTED_LONG 64u        // small max / min hops: in-rows longer than this are queued for a workgroup while the candidates are listed
+#define RP_MONO_LISTED_LONG 64u        // small max / min and attention hops: in-rows longer than this are queued for a workgroup while the hop's vertices are listed
 #define ROW_SPLIT_MIN 512u
 #define ROW_SEG 512u
 #define ROW_SEG_MAX (1u << 18)           // segments queued at a time; rows that find the queue full are read by one workgroup

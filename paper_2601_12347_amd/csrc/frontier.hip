@@ -32,6 +32,7 @@ struct SparseArgs {
     const uint2 *in_meta;
     uint32_t long_min;
     uint32_t *long_list, *long_count;
+    int long_dup;                  // those vertices are appended to the hop's list as well
 };
 
 // T vertices per lane (0xFFFFFFFF: none): the T marks go out together and one reservation covers all of
@@ -55,7 +56,7 @@ __device__ __forceinline__ void sparse_enter_many(const SparseArgs &s, const uin
     uint32_t total = 0, ltotal = 0;
 #pragma unroll
     for (int t = 0; t < T; ++t) {
-        mask[t] = __ballot(fresh[t] && !lng[t]);
+        mask[t] = __ballot(fresh[t] && (!lng[t] || s.long_dup));
         lmask[t] = __ballot(lng[t]);
         total += (uint32_t)__popcll(mask[t]);
         ltotal += (uint32_t)__popcll(lmask[t]);
@@ -73,7 +74,7 @@ __device__ __forceinline__ void sparse_enter_many(const SparseArgs &s, const uin
     const unsigned long long below = (1ull << lane) - 1ull;
 #pragma unroll
     for (int t = 0; t < T; ++t) {
-        if (fresh[t] && !lng[t]) s.list[base + (uint32_t)__popcll(mask[t] & below)] = v[t];
+        if (fresh[t] && (!lng[t] || s.long_dup)) s.list[base + (uint32_t)__popcll(mask[t] & below)] = v[t];
         if (lng[t]) s.long_list[lbase + (uint32_t)__popcll(lmask[t] & below)] = v[t];
         base += (uint32_t)__popcll(mask[t]);
         lbase += (uint32_t)__popcll(lmask[t]);
@@ -671,6 +672,7 @@ static SparseArgs sparse_args(ripple_ctx *c, uint32_t l, uint32_t *list, uint32_
     sp.long_min = 0;
     sp.long_list = nullptr;
     sp.long_count = nullptr;
+    sp.long_dup = 0;
     return sp;
 }
 
@@ -689,8 +691,16 @@ void rp_launch_candidates_sparse(ripple_ctx *c, uint32_t l, bool self_term, uint
 // Hop l for a small frontier: out-edge walk from A_{l-1} and the roots (S, V_added, A_{l-1} when self_term)
 // straight into bm[l] and list[l] (unordered), then the degree prefixes over that list. Two launches
 // instead of the walk plus a scan of the whole bitmap.
-void rp_launch_frontier_sparse(ripple_ctx *c, uint32_t l, bool self_term, bool want_out) {
-    const SparseArgs sp = sparse_args(c, l, c->list[l], &c->ctr->a[l], self_term);
+// long_min > 0 (attention hops): vertices with more in-neighbours than that are also queued in c->all_list
+// (count in ctr->n_long[l], zero since the batch began) for the workgroup role of the aggregation kernel.
+void rp_launch_frontier_sparse(ripple_ctx *c, uint32_t l, bool self_term, bool want_out, uint32_t long_min) {
+    SparseArgs sp = sparse_args(c, l, c->list[l], &c->ctr->a[l], self_term);
+    if (long_min) {
+        sp.long_min = long_min;
+        sp.long_list = c->all_list;
+        sp.long_count = &c->ctr->n_long[l];
+        sp.long_dup = 1;
+    }
     hipLaunchKernelGGL(k_frontier_sparse, dim3(c->n_cu), dim3(256), 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],
                        c->eoff[l - 1], c->out_meta, c->out_pool, sp);
     rp_launch_list_offsets(c, l, want_out);

@@ -22,7 +22,7 @@ void rp_launch_candidates_sparse(ripple_ctx *c, uint32_t l, bool self_term, uint
 void rp_launch_list_offsets(ripple_ctx *c, uint32_t l, bool want_out);
 void rp_launch_bitmap_to_list(ripple_ctx *c, uint32_t *bitmap, uint32_t *out_list, uint32_t *count_d);
 void rp_launch_list_eoff(ripple_ctx *c, uint32_t l);
-void rp_launch_frontier_sparse(ripple_ctx *c, uint32_t l, bool self_term, bool want_out);
+void rp_launch_frontier_sparse(ripple_ctx *c, uint32_t l, bool self_term, bool want_out, uint32_t long_min = 0);
 
 // scatter.hip
 void rp_launch_scatter_push(ripple_ctx *c, uint32_t l, bool may_pull, bool allow_disc);
@@ -32,7 +32,7 @@ void rp_launch_pull_all(ripple_ctx *c, uint32_t l);
 void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l, const uint32_t *count_ptr, bool listed);
 
 // attention.hip
-void rp_launch_gat_scatter(ripple_ctx *c, uint32_t l, bool bootstrap);
+void rp_launch_gat_scatter(ripple_ctx *c, uint32_t l, bool bootstrap, bool prequeued = false);
 void rp_launch_gat_save(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d);
 void rp_launch_gat_scores(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d);
 
