@@ -15,7 +15,7 @@ embedding of every layer is recomputed from the features with Eq. (1)-(2)
 vertices the batch can affect at each hop (Sec. 3.2's per-update-type
 description; Sec. 2.2's worked example).
 
-Readings taken where the paper leaves a choice (each is listed in the design doc):
+Readings taken where the paper leaves a choice:
   * sum / mean / weighted sum as in Table 1 (weighted sum: x_v = sum over in-neighbours u of
     alpha_uv h_u, alpha_uv a per-edge weight fixed when the edge is created; Sec. 3.3.3, "Other
     linear aggregators"); mean of an empty neighbourhood is the zero vector;
