@@ -424,14 +424,26 @@ __global__ __launch_bounds__(TEAM * 64) void k_gat_scatter_seg(GatArgs a) {
 #pragma unroll
                 for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
                 dd = 0.0f;
-                for (uint32_t k = 0; k < nseg; ++k) {          // written by other compute units: read past this one's cache
-                    const float *p = a.seg_part + (size_t)(first + k) * a.seg_ld;
+                constexpr int GP = (NJ <= 4) ? 8 : 32 / NJ;     // partial rows requested per round trip
+                for (uint32_t k0 = 0; k0 < nseg; k0 += GP) {   // written by other compute units: read past this one's cache
+                    float x[GP][NJ], xd[GP];
 #pragma unroll
-                    for (int j = 0; j < NJ; ++j) {
-                        const uint32_t col = lane + 64 * j;
-                        if (col < d) acc[j] += __hip_atomic_load(p + col, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    for (int g = 0; g < GP; ++g) {
+                        const bool on = k0 + g < nseg;
+                        const float *p = a.seg_part + (size_t)(first + min(k0 + g, nseg - 1)) * a.seg_ld;
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j) {
+                            const uint32_t col = lane + 64 * j;
+                            x[g][j] = (on && col < d) ? __hip_atomic_load(p + col, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0f;
+                        }
+                        xd[g] = on ? __hip_atomic_load(p + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.0f;
                     }
-                    dd += __hip_atomic_load(p + d, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+                    for (int g = 0; g < GP; ++g) {              // in segment order
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j) acc[j] += x[g][j];
+                        dd += xd[g];
+                    }
                 }
 #pragma unroll
                 for (int j = 0; j < NJ; ++j) {

@@ -1104,16 +1104,23 @@ __global__ __launch_bounds__(TEAM * 64) void k_scatter_mono_seg(MonoArgs a) {
                     xo[j] = (col < d) ? a.X[(size_t)v * d + col] : 0.0f;
                     xn[j] = ident;
                 }
-                for (uint32_t k = 0; k < nseg; ++k) {
-                    const float *part = a.seg_part + (size_t)(first + k) * a.seg_ld;
+                constexpr int GP = (NJ <= 4) ? 8 : 32 / NJ;     // partial rows requested per round trip
+                for (uint32_t k0 = 0; k0 < nseg; k0 += GP) {
+                    float x[GP][NJ];
 #pragma unroll
-                    for (int j = 0; j < NJ; ++j) {
-                        const uint32_t col = lane + 64 * j;
-                        if (col < d) {                         // written by other compute units: read past this one's cache
-                            const float x = __hip_atomic_load(part + col, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            if (mono_better<IS_MIN>(x, xn[j])) xn[j] = x;
+                    for (int g = 0; g < GP; ++g) {
+                        const float *part = a.seg_part + (size_t)(first + min(k0 + g, nseg - 1)) * a.seg_ld;
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j) {          // written by other compute units: read past this one's cache
+                            const uint32_t col = lane + 64 * j;
+                            x[g][j] = (col < d) ? __hip_atomic_load(part + col, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : ident;
                         }
                     }
+#pragma unroll
+                    for (int g = 0; g < GP; ++g)
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j)
+                            if (mono_better<IS_MIN>(x[g][j], xn[j])) xn[j] = x[g][j];
                 }
                 mono_finish<NJ>(a, v, rp_bit(a.bm_vadd, v), xo, xn);
                 if (lane == 0) atomicAdd(&a.ctr->mono[2][a.l], 1u);
