@@ -688,7 +688,9 @@ def test_split_products_on_the_bf16_matrix_cores(kind, widths):
                                        ("gat", 0), ("gcn_wsum", 0)])
 def test_maximum_row_widths(kind, mode):
     """Rows of 1024 floats (the largest the library takes) and of 400: the 16- and 8-column-block
-    instantiations of every scatter kernel, products with K up to 2048 and N above 256, hidden width 1024."""
+    instantiations of every scatter kernel, products with K up to 2048 and N above 256, hidden width 1024.
+    A batch of about the size of the one before it takes the small-hop paths (lists built while marking, both
+    aggregation roles of max / min and attention layers in one launch), a much larger one the general ones."""
     print("case maximum widths", kind, mode, flush=True)
     widths = (1024, 400, 1024)
     weighted = kind == "gcn_wsum"
@@ -700,7 +702,7 @@ def test_maximum_row_widths(kind, mode):
     try:
         rp.ripple_set_option(pair.ctx, rp.OPT_SCATTER_MODE, mode)
         pair.check_embeddings()
-        for b, bs in enumerate([3, 120, 400]):
+        for b, bs in enumerate([3, 5, 120, 150, 400]):
             print(" batch", b, bs, flush=True)
             ops, payload, _ = stream.next_batch(bs)
             pair.step(ops, payload)
