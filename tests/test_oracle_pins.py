@@ -260,6 +260,106 @@ def test_affected_set_equals_rows_that_change(kind, seed):
                 assert changed <= set(sets[l].tolist()), (l, kind)
 
 
+def _changed_rows(before, after, alive):
+    """Live rows of a layer that differ at all between two full recomputations."""
+    diff = np.abs(after - before).max(axis=1) > 0
+    return set(np.nonzero(diff & alive)[0].tolist())
+
+
+@pytest.mark.parametrize("kind", ["gcn_sum", "sage_mean", "gin_sum"])
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_affected_set_equals_rows_that_change_with_vertex_operations(kind, seed):
+    """The same pin with created and deleted vertices in the batch (Sec. 3.2, paragraphs on vertex
+    addition and vertex deletion). Linear activations, non-zero biases and generic inputs: a live row
+    changes exactly when the vertex is in the set. A created vertex's rows go from zero to act(b + ...),
+    so it must sit in every set, with or without edges and on layers without a self term; the
+    out-neighbours of a deleted vertex lose a term at every hop; the deleted vertex itself (whose rows
+    become zero) is reported in no set."""
+    st, model, src, dst, feats = small_case(300 + seed, n=60, e=150, kind=kind)
+    for lay in model:
+        lay["act_out"] = "none"
+        lay["act_inner"] = "none"
+    before = oracle.full_recompute(st, model)
+    rng = np.random.default_rng(seed)
+    n, d0 = len(feats), feats.shape[1]
+    iso, src_only, sink_only, both = n, n + 1, n + 2, n + 3          # the four spare ids
+    gone = [int(w) for w in rng.choice(n, size=2, replace=False)]
+    others = [w for w in range(n) if w not in gone]
+    a, b, c, d = (int(w) for w in rng.choice(others, size=4, replace=False))
+    payload = rng.standard_normal((4, d0))
+    ops = [(ri.OP_VERTEX_ADD, iso, 0, 0),                            # isolated
+           (ri.OP_VERTEX_ADD, src_only, 0, 1), (ri.OP_EDGE_ADD, src_only, a, 0),   # only an out-edge
+           (ri.OP_VERTEX_ADD, sink_only, 0, 2), (ri.OP_EDGE_ADD, b, sink_only, 0),  # only an in-edge
+           (ri.OP_VERTEX_ADD, both, 0, 3), (ri.OP_EDGE_ADD, both, c, 0), (ri.OP_EDGE_ADD, d, both, 0),
+           (ri.OP_VERTEX_DEL, gone[0], 0, 0), (ri.OP_VERTEX_DEL, gone[1], 0, 0)]
+    out_of_gone = {w for g in gone for w in st.out_neighbours(g)} - set(gone)
+    rec = st.apply_batch(np.array(ops, dtype=np.uint32), payload)
+    assert rec.accepted.all()
+    after = oracle.full_recompute(st, model)
+    sets = oracle.affected_sets(st, rec, model)
+    for l in range(len(model) + 1):
+        want = set(sets[l].tolist())
+        assert _changed_rows(before[l], after[l], st.alive) == want, (l, kind)
+        assert {iso, src_only, sink_only, both} <= want                # created vertices: every hop
+        assert not (set(gone) & want)                                  # deleted vertices: no hop
+        assert np.all(after[l][gone] == 0)
+        if l >= 1:
+            assert out_of_gone <= want                                 # they lost an in-neighbour
+
+
+def test_isolated_created_vertex_is_alone_in_every_set():
+    """Sec. 3.2, vertex addition: creating a vertex triggers nothing but the update of its own
+    embeddings. With no edges it is the only member of the set at every hop, also on layers
+    without a self term; with only an in-edge it is likewise the only member (it is the sink of the
+    added edge and has nowhere to propagate to); with an out-edge its sink joins from hop 1 on."""
+    for kind in ("gcn_sum", "sage_mean"):
+        st, model, src, dst, feats = small_case(77, kind=kind)
+        n = len(feats)
+        row = np.ones((1, feats.shape[1]))
+        rec = st.apply_batch(np.array([(ri.OP_VERTEX_ADD, n, 0, 0)], dtype=np.uint32), row)
+        assert [s.tolist() for s in oracle.affected_sets(st, rec, model)] == [[n]] * (len(model) + 1)
+        rec = st.apply_batch(np.array([(ri.OP_VERTEX_ADD, n + 1, 0, 0), (ri.OP_EDGE_ADD, 3, n + 1, 0)],
+                                      dtype=np.uint32), row)
+        assert [s.tolist() for s in oracle.affected_sets(st, rec, model)] == [[n + 1]] * (len(model) + 1)
+        rec = st.apply_batch(np.array([(ri.OP_VERTEX_ADD, n + 2, 0, 0), (ri.OP_EDGE_ADD, n + 2, 3, 0)],
+                                      dtype=np.uint32), row)
+        sets = oracle.affected_sets(st, rec, model)
+        assert sets[0].tolist() == [n + 2]
+        assert sets[1].tolist() == [3, n + 2]
+        assert {3, n + 2} | set(st.out_neighbours(3)) <= set(sets[2].tolist())
+
+
+def test_deleted_vertex_is_in_no_set_even_as_an_earlier_sink():
+    """Sec. 3.2, vertex deletion: the incident edges go, then the vertex; what is left to update are its
+    former out-neighbours and what lies downstream of them. The deleted id itself is in no set, also
+    when an earlier operation of the same batch made it the sink of a changed edge, created it, or
+    replaced its features, and also at hops beyond the first."""
+    st, model, src, dst, feats = small_case(78, kind="sage_mean")
+    n = len(feats)
+    victim = int(dst[0])
+    x = next(w for w in range(n) if w != victim and not st.has_edge(w, victim))
+    outs = set(st.out_neighbours(victim)) - {victim}
+    row = np.ones((2, feats.shape[1]))
+    ops = [(ri.OP_EDGE_ADD, x, victim, 0),          # the victim is the sink of a changed edge
+           (ri.OP_FEAT_UPDATE, victim, 0, 0),       # and has its features replaced
+           (ri.OP_VERTEX_ADD, n, 0, 1),             # a vertex created and deleted in one batch
+           (ri.OP_EDGE_ADD, x, n, 0),
+           (ri.OP_VERTEX_DEL, victim, 0, 0),
+           (ri.OP_VERTEX_DEL, n, 0, 0)]
+    rec = st.apply_batch(np.array(ops, dtype=np.uint32), row)
+    assert rec.accepted.all()
+    assert victim in rec.sinks and n in rec.sinks   # the premise: the root sets do name them
+    sets = oracle.affected_sets(st, rec, model)
+    assert sets[0].tolist() == []
+    for l in range(1, len(model) + 1):
+        got = set(sets[l].tolist())
+        assert victim not in got and n not in got, l
+        assert outs <= got, l
+    # downstream of the former out-neighbours at hop 2 (the updated graph's edges)
+    down = {w for o in outs for w in st.out_neighbours(o)}
+    assert down <= set(sets[2].tolist())
+
+
 @pytest.mark.parametrize("kind", ["gcn_sum", "sage_mean", "gin_sum"])
 def test_cone_recompute_equals_bruteforce_and_full(kind):
     st, model, src, dst, feats = small_case(51, n=80, e=400, kind=kind)
