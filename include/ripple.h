@@ -39,7 +39,7 @@ typedef enum {
     RIPPLE_OK = 0,
     RIPPLE_EINVAL = 1,      /* bad argument (null pointer, id out of range, bad enum, bad shape) */
     RIPPLE_ESTATE = 2,      /* call order violated */
-    RIPPLE_ECAPACITY = 3,   /* vertex/edge capacity exceeded; state unchanged */
+    RIPPLE_ECAPACITY = 3,   /* vertex/edge capacity exceeded; the piece of the batch that hit it changed nothing */
     RIPPLE_ENOMEM = 4,      /* device or host allocation failed */
     RIPPLE_EDEVICE = 5      /* a HIP call failed */
 } ripple_status;
@@ -124,6 +124,14 @@ typedef struct {
     uint32_t mono_unchanged[RIPPLE_MAX_LAYERS + 1];
     uint32_t mono_incremental[RIPPLE_MAX_LAYERS + 1];
     uint32_t mono_recomputed[RIPPLE_MAX_LAYERS + 1];
+    /* sum, mean and weighted-sum layers: how hop l moved its messages (Sec. 3.5 compares the costs): 1 pushed
+     * along the out-edges of A_{l-1}, 2 pulled through the in-rows of A_l, 3 one scan of all in-rows that also
+     * found A_l; 0 where no such kernel ran (no messages, other aggregators, deterministic mode). A batch that
+     * was cut into pieces reports its last piece. */
+    uint32_t hop_mode[RIPPLE_MAX_LAYERS + 1];
+    /* operations of the batch, counted from its start, that took effect: n_ops on success; on a capacity or
+     * device error in a batch that had to be cut into pieces, the end of the last piece that went through */
+    uint32_t n_ops_done;
 } ripple_batch_result;
 
 /* Accumulated per-kernel-class timing and work counters (RIPPLE_OPT_TIMING). */
@@ -202,7 +210,13 @@ ripple_status ripple_full_infer(ripple_ctx *ctx);
  * >= vertex_capacity, unknown kinds or feat_row >= n_feat_rows fail the whole
  * call with RIPPLE_EINVAL before anything changes. Then deltas are propagated
  * through all layers. ops: host or device. feat_payload: host or device
- * float32 [n_feat_rows x d0]. res may be NULL. */
+ * float32 [n_feat_rows x d0]. res may be NULL.
+ * A batch whose operations depend on one another (the same edge twice, a vertex used after the batch
+ * deleted it, ...) is cut into pieces that run one after another (ripple_plan_batch shows the cut). If a
+ * piece exceeds the edge capacity, or the adjacency pool even after compaction, that piece changes nothing
+ * and the call returns RIPPLE_ECAPACITY; earlier pieces stay applied and fully propagated, so graph and
+ * embeddings are those of the batch's first res->n_ops_done operations, which res then describes
+ * (n_applied, n_rejected, n_edges, n_alive, affected). A batch that needed no cut is all or nothing. */
 ripple_status ripple_apply_updates(ripple_ctx *ctx, const ripple_update *ops, uint32_t n_ops,
                                    const float *feat_payload, uint32_t n_feat_rows,
                                    ripple_batch_result *res);

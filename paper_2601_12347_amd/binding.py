@@ -60,7 +60,9 @@ class BatchResult(C.Structure):
                 ("n_structural", C.c_uint32),
                 ("mono_unchanged", C.c_uint32 * (RIPPLE_MAX_LAYERS + 1)),
                 ("mono_incremental", C.c_uint32 * (RIPPLE_MAX_LAYERS + 1)),
-                ("mono_recomputed", C.c_uint32 * (RIPPLE_MAX_LAYERS + 1))]
+                ("mono_recomputed", C.c_uint32 * (RIPPLE_MAX_LAYERS + 1)),
+                ("hop_mode", C.c_uint32 * (RIPPLE_MAX_LAYERS + 1)),
+                ("n_ops_done", C.c_uint32)]
 
 
 class Stats(C.Structure):
@@ -225,9 +227,13 @@ def ripple_apply_updates(ctx, ops, payload, n_ops=None, n_feat_rows=None):
         if n_feat_rows == 0:
             payload = None
     res = BatchResult()
-    _check(ctx, lib.ripple_apply_updates(ctx, _ptr(ops) if n_ops else None, n_ops or 0,
-                                         _ptr(payload) if n_feat_rows else None, n_feat_rows or 0,
-                                         C.byref(res)))
+    try:
+        _check(ctx, lib.ripple_apply_updates(ctx, _ptr(ops) if n_ops else None, n_ops or 0,
+                                             _ptr(payload) if n_feat_rows else None, n_feat_rows or 0,
+                                             C.byref(res)))
+    except RippleError as err:
+        err.result = res            # how far the batch got (n_ops_done and the counts of that prefix)
+        raise
     return res
 
 

@@ -852,6 +852,38 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
     }
 }
 
+// Stage, enqueue and wait for one piece; on a full adjacency pool or a full scratch buffer the piece (which
+// aborts on the device before it changes anything) is retried after compaction / growth. On return with
+// RIPPLE_OK the pinned mirror of the counters describes the piece.
+static ripple_status run_piece(ripple_ctx *c, const SubBatch &sb, bool multi, uint32_t *compactions) {
+    hipStream_t s = c->stream;
+    const uint32_t n = sb.end - sb.begin;
+    for (int attempt = 0;; ++attempt) {
+        RP_HIP(c, hipMemcpyAsync(c->ops_d, c->ops_pin + sb.begin, (size_t)n * sizeof(ripple_update),
+                                 hipMemcpyHostToDevice, s));
+        enqueue_piece(c, sb, multi);
+        RP_HIP(c, hipMemcpyAsync(c->ctr_host, c->ctr, sizeof(DevCtr), hipMemcpyDeviceToHost, s));
+        RP_HIP(c, hipStreamSynchronize(s));
+        const DevCtr &h = *c->ctr_host;
+        if (!h.abort_flag) return RIPPLE_OK;
+        if (h.abort_flag & 8u) {
+            c->err = "graph store consistency error " + std::to_string(h.error);
+            return RIPPLE_EDEVICE;
+        }
+        if (h.abort_flag & 2u) return fail(c, RIPPLE_ECAPACITY, "edge capacity exceeded");
+        if (attempt >= 2) return fail(c, RIPPLE_ECAPACITY, "adjacency pool exhausted even after compaction");
+        if (h.abort_flag & 4u) {
+            uint32_t want = h.need_exp + h.need_exp / 2 + 1024;
+            // the caller's payload pointer may sit in payload_d: only the operation-side buffers grow here
+            RP_TRY(ensure_batch_buffers(c, c->ops_cap, 0, want));
+        }
+        if (h.abort_flag & 1u) {
+            ++*compactions;
+            RP_TRY(rp_compact(c));
+        }
+    }
+}
+
 extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update *ops, uint32_t n_ops,
                                               const float *feat_payload, uint32_t n_feat_rows,
                                               ripple_batch_result *res) {
@@ -891,6 +923,8 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
     const bool multi = pieces.size() > 1;
     if (hops != c->ops_pin) memcpy(c->ops_pin, hops, (size_t)n_ops * sizeof(ripple_update));
 
+    if (multi)
+        RP_HIP(c, hipMemsetAsync(c->rep[0], 0, (size_t)c->n_words * (c->L + 1) * 4, s));
     // payload: used in place when it already lives on the device
     float *payload_saved = c->payload_d;
     if (n_feat_rows) {
@@ -902,55 +936,18 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
             RP_HIP(c, hipMemcpyAsync(c->payload_d, c->payload_pin, bytes, hipMemcpyHostToDevice, s));
         }
     }
-    if (multi)
-        RP_HIP(c, hipMemsetAsync(c->rep[0], 0, (size_t)c->n_words * (c->L + 1) * 4, s));
 
     ripple_status rc = RIPPLE_OK;
-    uint32_t applied = 0, rejected = 0, n_struct = 0, compactions = 0;
+    uint32_t applied = 0, rejected = 0, n_struct = 0, compactions = 0, ops_done = 0;
     uint64_t msgs[RIPPLE_MAX_LAYERS + 1] = {0}, tchd[RIPPLE_MAX_LAYERS + 1] = {0};
     uint32_t mono[3][RIPPLE_MAX_LAYERS + 1] = {{0}};
+    uint32_t hop_mode[RIPPLE_MAX_LAYERS + 1] = {0};
     for (size_t p = 0; p < pieces.size() && rc == RIPPLE_OK; ++p) {
         const SubBatch &sb = pieces[p];
         const uint32_t n = sb.end - sb.begin;
-        for (int attempt = 0;; ++attempt) {
-            RP_HIP(c, hipMemcpyAsync(c->ops_d, c->ops_pin + sb.begin, (size_t)n * sizeof(ripple_update),
-                                     hipMemcpyHostToDevice, s));
-            enqueue_piece(c, sb, multi);
-            RP_HIP(c, hipMemcpyAsync(c->ctr_host, c->ctr, sizeof(DevCtr), hipMemcpyDeviceToHost, s));
-            RP_HIP(c, hipStreamSynchronize(s));
-            const DevCtr &h = *c->ctr_host;
-            if (!h.abort_flag) break;
-            if (h.abort_flag & 8u) {
-                c->err = "graph store consistency error " + std::to_string(h.error);
-                rc = RIPPLE_EDEVICE;
-                break;
-            }
-            if (h.abort_flag & 2u) {
-                rc = fail(c, RIPPLE_ECAPACITY, "edge capacity exceeded");
-                break;
-            }
-            if (attempt >= 2) {
-                rc = fail(c, RIPPLE_ECAPACITY, "adjacency pool exhausted even after compaction");
-                break;
-            }
-            if (h.abort_flag & 4u) {
-                uint32_t want = h.need_exp + h.need_exp / 2 + 1024;
-                ripple_status r2 = ensure_batch_buffers(c, c->ops_cap, 0, want);
-                if (r2 != RIPPLE_OK) {
-                    rc = r2;
-                    break;
-                }
-            }
-            if (h.abort_flag & 1u) {
-                ripple_status r2 = rp_compact(c);
-                ++compactions;
-                if (r2 != RIPPLE_OK) {
-                    rc = r2;
-                    break;
-                }
-            }
-        }
+        rc = run_piece(c, sb, multi, &compactions);
         if (rc != RIPPLE_OK) break;
+        ops_done = sb.end;
         const DevCtr &h = *c->ctr_host;
         applied += h.n_applied;
         rejected += h.n_rejected;
@@ -959,6 +956,7 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
             msgs[l] += h.m[l];
             tchd[l] += h.touched[l];
             c->last_m[l] = h.m[l];
+            hop_mode[l] = h.hop_mode[l];
             for (int k = 0; k < 3; ++k) mono[k][l] += h.mono[k][l];
             c->last_cand[l] = h.mono[0][l] + h.mono[1][l] + h.mono[2][l];
             // pull wins when m * row_bytes * ratio >= 8 * in-edges; remember if push won by a factor of 16
@@ -971,8 +969,39 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
         c->last_n_ops = multi ? 0u : n;
         c->hints_valid = !multi;
     }
-    c->payload_d = payload_saved;
-    if (rc != RIPPLE_OK) return rc;
+    c->payload_d = payload_saved;                  // never leave the caller's buffer in the context
+    if (rc != RIPPLE_OK) {
+        // Pieces before the failing one stay applied and fully propagated (the state is that of the batch's
+        // first ops_done operations); the failing piece changed nothing. Say how far the batch got.
+        (void)hipStreamSynchronize(s);
+        c->timer->recs.clear();
+        c->timer->used = 0;
+        c->hints_valid = false;
+        if (res) {
+            res->n_ops = n_ops;
+            res->n_ops_done = ops_done;
+            res->n_applied = applied;
+            res->n_rejected = rejected;
+            res->n_sub_batches = (uint32_t)pieces.size();
+            res->n_compactions = compactions;
+            res->n_structural = n_struct;
+            if (ops_done) {                        // counters of the last piece that went through
+                res->n_alive = c->ctr_host->n_alive;
+                res->n_edges = c->ctr_host->n_edges;
+            }
+        }
+        if (multi && ops_done) {                   // the sets reported are those of the applied pieces
+            for (uint32_t l = 0; l <= c->L; ++l) rp_launch_bitmap_to_list(c, c->rep[l], c->all_list, &c->ctr->a[l]);
+            if (hipMemcpyAsync(c->ctr_host, c->ctr, sizeof(DevCtr), hipMemcpyDeviceToHost, s) == hipSuccess &&
+                hipStreamSynchronize(s) == hipSuccess)
+                for (uint32_t l = 0; l <= c->L; ++l) {
+                    c->last_a[l] = c->ctr_host->a[l];
+                    if (res) res->affected[l] = c->last_a[l];
+                }
+            c->last_from_rep = true;
+        }
+        return rc;
+    }
     RP_HIP(c, hipGetLastError());
     if (multi) {                                   // sizes of the united sets
         for (uint32_t l = 0; l <= c->L; ++l) rp_launch_bitmap_to_list(c, c->rep[l], c->all_list, &c->ctr->a[l]);
@@ -994,6 +1023,7 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
     }
     if (res) {
         res->n_ops = n_ops;
+        res->n_ops_done = n_ops;
         res->n_applied = applied;
         res->n_rejected = rejected;
         res->n_sub_batches = (uint32_t)pieces.size();
@@ -1007,6 +1037,7 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
             res->mono_unchanged[l] = mono[0][l];
             res->mono_incremental[l] = mono[1][l];
             res->mono_recomputed[l] = mono[2][l];
+            res->hop_mode[l] = hop_mode[l];
         }
     }
     return RIPPLE_OK;

@@ -22,12 +22,13 @@ template <int NJ>
 __global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, const uint32_t *count_ptr,
                                                       const uint32_t *eoff, const float *D, uint32_t ldd, uint32_t d,
                                                       const uint2 *out_meta, const uint32_t *out_pool, float *X,
-                                                      const DevCtr *ctr, uint32_t l, int may_pull, int mode, int ratio, int allow_disc) {
+                                                      DevCtr *ctr, uint32_t l, int may_pull, int mode, int ratio, int allow_disc) {
     constexpr int G = (NJ <= 2) ? 8 : (NJ <= 4 ? 4 : (NJ <= 8 ? 2 : 1));   // edges per round
     const int hm = rp_hop_mode(ctr, l, d, mode, ratio, allow_disc);
     if (hm == RP_HOP_DISCOVER || (may_pull && hm == RP_HOP_PULL)) return;
     const uint32_t count = *count_ptr;
     if (count == 0) return;
+    if (blockIdx.x == 0 && threadIdx.x == 0) ctr->hop_mode[l] = 1u + RP_HOP_PUSH;
     const int lane = rp_lane();
     const uint32_t M = eoff[count];
     const uint32_t chunk = (M <= 16384u) ? 16u : PUSH_CHUNK;   // few messages: spread them over more wavefronts
@@ -129,7 +130,7 @@ struct PullArgs {
     uint32_t ldd;                  // their row stride
     uint32_t d;
     float *X;
-    const DevCtr *ctr;
+    DevCtr *ctr;
     uint32_t l;
     int mode, ratio, allow_disc;
 };
@@ -140,6 +141,7 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
     if (rp_hop_mode(a.ctr, a.l, a.d, a.mode, a.ratio, a.allow_disc) != (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL)) return;
     const uint32_t count = *a.count_ptr;
     if (count == 0) return;
+    if (blockIdx.x == 0 && threadIdx.x == 0) a.ctr->hop_mode[a.l] = 1u + (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL);
     // delta rows gathered per round trip; the weighted one-column kernel takes 12 so that it stays
     // within 64 registers (eight waves per SIMD), which matters more here than the deeper round
     constexpr int G = (NJ >= 8) ? 2 : (WT && NJ == 1) ? 12 : 16 / NJ;

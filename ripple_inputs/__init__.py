@@ -11,13 +11,14 @@ Products 2.5M/123.7M, Reddit 233K/114.6M) of which only the shapes are taken:
 vertex and edge counts, feature width, class count. The update mix replaces the paper's
 LinkBench-derived mix (Sec. 6.1.2), which is not available.
 """
-from .graphs import (PowerLaw, chung_lu_graph, features, edge_weights, CONFIGS, get_config,
+from .graphs import (PowerLaw, degree_laws, chung_lu_graph, features, edge_weights, CONFIGS, get_config,
                      OP_EDGE_ADD, OP_EDGE_DEL, OP_VERTEX_ADD, OP_VERTEX_DEL,
                      OP_FEAT_UPDATE)
 from .models import make_model, glorot
 from .updates import UpdateStream
+from .producer import BatchProducer
 
-__all__ = ["PowerLaw", "chung_lu_graph", "features", "edge_weights", "CONFIGS", "get_config",
+__all__ = ["PowerLaw", "degree_laws", "chung_lu_graph", "BatchProducer", "features", "edge_weights", "CONFIGS", "get_config",
            "make_model", "glorot", "UpdateStream",
            "OP_EDGE_ADD", "OP_EDGE_DEL", "OP_VERTEX_ADD", "OP_VERTEX_DEL",
            "OP_FEAT_UPDATE"]

@@ -45,11 +45,33 @@ class PowerLaw:
                 hi = mid
         return float(np.sqrt(lo * hi))
 
-    def draw(self, rng: np.random.Generator, size: int) -> np.ndarray:
-        u = rng.random(size)
+    def _ranks(self, u: np.ndarray) -> np.ndarray:
         x = (u * (self.hi - self.lo) + self.lo) ** (1.0 / self.e) - self.i0
-        r = np.clip(np.floor(x).astype(np.int64), 0, self.n - 1)
-        return self.perm[r]
+        r = np.floor(x).astype(np.int64)
+        np.maximum(r, 0, out=r)
+        np.minimum(r, self.n - 1, out=r)
+        return r
+
+    def draw(self, rng: np.random.Generator, size: int) -> np.ndarray:
+        return self.perm[self._ranks(rng.random(size))]
+
+    def same_shape(self, other: "PowerLaw") -> bool:
+        return (self.n, self.e, self.i0, self.lo, self.hi) == (other.n, other.e, other.i0, other.lo, other.hi)
+
+
+def draw_pair(rng: np.random.Generator, first: PowerLaw, second: PowerLaw, size: int):
+    """The values of first.draw(rng, size) followed by second.draw(rng, size). Two laws of one shape
+    (they differ in their permutation only) share one pass over 2*size uniforms, which saves most of
+    the per-call overhead when size is small."""
+    if not first.same_shape(second):
+        return first.draw(rng, size), second.draw(rng, size)
+    r = first._ranks(rng.random(2 * size))
+    return first.perm[r[:size]], second.perm[r[size:]]
+
+
+def degree_laws(n: int, gamma: float, top_share: float, seed: int):
+    """The out- and in-degree samplers of the graph with this seed."""
+    return PowerLaw(n, gamma, top_share, seed * 7 + 1), PowerLaw(n, gamma, top_share, seed * 7 + 2)
 
 
 def chung_lu_graph(n: int, e: int, gamma: float, top_share: float, seed: int):
@@ -58,8 +80,7 @@ def chung_lu_graph(n: int, e: int, gamma: float, top_share: float, seed: int):
     Returns (src, dst, out_law, in_law): uint32 arrays sorted by (src, dst)
     and the two samplers (the update stream draws new edges from the same law).
     """
-    out_law = PowerLaw(n, gamma, top_share, seed * 7 + 1)
-    in_law = PowerLaw(n, gamma, top_share, seed * 7 + 2)
+    out_law, in_law = degree_laws(n, gamma, top_share, seed)
     rng = np.random.default_rng(seed)
     keys = np.empty(0, dtype=np.int64)
     while keys.size < e:

@@ -18,7 +18,7 @@ from __future__ import annotations
 import numpy as np
 
 from .graphs import (OP_EDGE_ADD, OP_EDGE_DEL, OP_VERTEX_ADD, OP_VERTEX_DEL,
-                     OP_FEAT_UPDATE, PowerLaw)
+                     OP_FEAT_UPDATE, PowerLaw, draw_pair)
 
 
 class UpdateStream:
@@ -128,8 +128,7 @@ class UpdateStream:
 
     def _random_new_edge(self, used, banned):
         while True:
-            us = self.out_law.draw(self.rng, 16)
-            vs = self.in_law.draw(self.rng, 16)
+            us, vs = draw_pair(self.rng, self.out_law, self.in_law, 16)
             for u, v in zip(us.tolist(), vs.tolist()):
                 if u == v or not (self.alive[u] and self.alive[v]):
                     continue

@@ -32,7 +32,7 @@ def test_every_declared_symbol_is_exported():
 
 def test_struct_layouts_match_the_header():
     assert C.sizeof(rp.binding.LayerDesc) == 72
-    assert C.sizeof(rp.BatchResult) == 4 * 6 + 8 + 4 * 9 + 4 + 8 * 9 + 4 + 3 * 4 * 9
+    assert C.sizeof(rp.BatchResult) == 4 * 6 + 8 + 4 * 9 + 4 + 8 * 9 + 4 + 3 * 4 * 9 + 4 * 9 + 4   # the last two: hop_mode, n_ops_done
     assert C.sizeof(rp.Stats) == 8 + 8 * 8 * 9 * 2 + 8 * 9 * 3
 
 

@@ -256,6 +256,45 @@ def test_pool_growth_relocation_and_compaction():
         pair.close()
 
 
+def test_capacity_error_in_a_later_piece_leaves_the_earlier_pieces_applied():
+    """A batch that has to be cut (it touches one edge twice) and whose second piece exceeds the edge
+    capacity: the call reports the capacity error and how many operations took effect; the state is that
+    of exactly those operations, and the next batch goes through."""
+    print("case capacity in second piece", flush=True)
+    pair, graph = make_pair(n=200, e=1200, d0=8, kind="sage_mean", widths=(8, 16, 6), seed=61, edge_capacity=1204)
+    try:
+        free = [(u, v) for u in range(40) for v in range(40, 60) if not pair.ora.has_edge(u, v)]
+        (a0, b0), (a1, b1) = free[0], free[1]
+        first = [(ri.OP_EDGE_ADD, a0, b0, 0), (ri.OP_EDGE_ADD, a1, b1, 0), (ri.OP_FEAT_UPDATE, 7, 0, 0)]
+        second = [(ri.OP_EDGE_DEL, a0, b0, 0)] + [(ri.OP_EDGE_ADD, u, v, 0) for u, v in free[2:12]]
+        ops = np.array(first + second, dtype=np.uint32)
+        payload = np.ones((1, 8), dtype=np.float32)
+        assert rp.ripple_plan_batch(ops, pair.cap, 1) == [len(first), len(ops)]
+        with pytest.raises(rp.RippleError) as ei:
+            rp.ripple_apply_updates(pair.ctx, ops, payload)
+        assert ei.value.status == rp.binding.RIPPLE_ECAPACITY
+        res = ei.value.result
+        assert res.n_ops == len(ops) and res.n_ops_done == len(first) and res.n_sub_batches == 2
+        rec = pair.ora.apply_batch(ops[: res.n_ops_done], payload)
+        assert res.n_applied == int(rec.accepted.sum()) == 3 and res.n_rejected == 0
+        assert res.n_edges == pair.ora.n_edges() == 1202
+        sets = oracle.affected_sets(pair.ora, rec, pair.model)
+        for l in range(pair.L + 1):
+            got, n = rp.ripple_get_affected(pair.ctx, l, pair.cap)
+            assert n == res.affected[l] and np.array_equal(got.astype(np.int64), sets[l]), l
+        pair.check_graph()
+        pair.check_embeddings()
+        pair.check_aggregates()
+        # a device-resident payload must not have been adopted by the context: the next batch (host payload) works
+        stream = make_stream(pair, graph, {"edge_add": 0.0, "edge_del": 0.5, "feat": 0.5, "vadd": 0.0, "vdel": 0.0}, 63)
+        stream._add_edge(a0, b0)
+        stream._add_edge(a1, b1)
+        ops2, payload2, _ = stream.next_batch(20)
+        pair.step(ops2, payload2)
+    finally:
+        pair.close()
+
+
 def test_bf16_store_updates():
     print("case bf16 updates", flush=True)
     pair, graph = make_pair(n=600, e=4000, d0=16, kind="gcn_sum", widths=(16, 64, 24), store="bf16", seed=37)

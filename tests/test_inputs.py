@@ -52,3 +52,30 @@ def test_batch_size_one_draws_every_kind():
         assert n == 1 and len(ops) == 1
         kinds.add(int(ops[0, 0]))
     assert kinds == {ri.OP_EDGE_ADD, ri.OP_EDGE_DEL, ri.OP_FEAT_UPDATE}
+
+
+def test_draw_pair_equals_two_draws():
+    a = ri.PowerLaw(5000, 2.2, 0.01, 3)
+    b = ri.PowerLaw(5000, 2.2, 0.01, 4)
+    from ripple_inputs.graphs import draw_pair
+    r1, r2 = np.random.default_rng(11), np.random.default_rng(11)
+    for size in (1, 16, 33):
+        for _ in range(50):
+            x, y = draw_pair(r1, a, b, size)
+            assert np.array_equal(x, a.draw(r2, size)) and np.array_equal(y, b.draw(r2, size))
+    c = ri.PowerLaw(5000, 2.5, 0.01, 4)                        # another shape: falls back to two draws
+    x, y = draw_pair(r1, a, c, 16)
+    assert np.array_equal(x, a.draw(r2, 16)) and np.array_equal(y, c.draw(r2, 16))
+
+
+def test_producer_process_hands_over_the_same_batches(tmp_path):
+    cfg = ri.get_config("tiny_gcn_sum")
+    src, dst, out_law, in_law = ri.chung_lu_graph(cfg.n, cfg.e, cfg.gamma, cfg.top_share, cfg.graph_seed)
+    stream = ri.UpdateStream(cfg.n, cfg.vertex_capacity, src, dst, out_law, in_law, cfg.d0, cfg.mix, cfg.stream_seed)
+    ri.BatchProducer.save_graph(str(tmp_path), src, dst)
+    with ri.BatchProducer(cfg.name, str(tmp_path), 100, 5) as prod:
+        for _ in range(5):
+            ops, payload, n = stream.next_batch(100)
+            ops2, payload2, n2 = prod.next_batch()
+            assert n == n2 and np.array_equal(ops, ops2) and np.array_equal(payload, payload2)
+            assert ops2.dtype == np.uint32 and payload2.dtype == np.float32
