@@ -248,6 +248,19 @@ ripple_status ripple_get_layer_info(ripple_ctx *ctx, uint32_t layer, uint32_t *a
 ripple_status ripple_get_affected(ripple_ctx *ctx, uint32_t layer, uint32_t *ids_out, uint32_t cap,
                                   uint32_t *n_out);
 
+/* ripple_get_affected for callers that cannot allocate (code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc): the same ascending set, written straight into ids_out (device memory of
+ * the context's GPU, room for cap ids; ids beyond cap are counted but not written) with the set size in
+ * *n_out (device memory, 4 bytes). The call allocates and frees nothing, on the host or on the device: the
+ * block sums of its two-pass compaction live in a static device array of 192 KiB that each GPU the library
+ * runs on holds until the process ends. That bounds the graph: vertex_capacity beyond 134,217,728
+ * (16,384 blocks of 8,192 vertices) returns RIPPLE_EINVAL. All contexts on a GPU share the array, so calls
+ * that overlap on one GPU (two contexts on different streams or host threads) race; calls in sequence do
+ * not, since every call writes the entries it reads. Returns after the context's stream has been
+ * synchronised. */
+ripple_status ripple_get_affected_static(ripple_ctx *ctx, uint32_t layer, uint32_t *ids_out, uint32_t cap,
+                                         uint32_t *n_out);
+
 /* Current edge set read back from the out-adjacency (direction 0) or the
  * in-adjacency (direction 1) as src -> dst pairs, in storage order (host
  * arrays with room for cap edges). */

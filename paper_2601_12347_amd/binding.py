@@ -32,7 +32,8 @@ ACT = {"none": 0, "relu": 1}
 STORE = {"f32": 0, "bf16": 1}
 
 EXPORTS = ["ripple_init_graph", "ripple_init_graph_weighted", "ripple_load_model", "ripple_full_infer", "ripple_apply_updates",
-           "ripple_get_embeddings", "ripple_get_aggregates", "ripple_get_layer_info", "ripple_get_affected", "ripple_export_edges",
+           "ripple_get_embeddings", "ripple_get_aggregates", "ripple_get_layer_info", "ripple_get_affected", "ripple_get_affected_static",
+           "ripple_export_edges",
            "ripple_get_degrees", "ripple_compact", "ripple_set_option", "ripple_get_stats", "ripple_plan_batch",
            "ripple_destroy", "ripple_last_error"]
 
@@ -103,6 +104,7 @@ def load_library():
     lib.ripple_get_aggregates.argtypes = [vp, u32, vp, u32, vp]
     lib.ripple_get_layer_info.argtypes = [vp, u32, C.POINTER(u32), C.POINTER(C.c_int)]
     lib.ripple_get_affected.argtypes = [vp, u32, vp, u32, C.POINTER(u32)]
+    lib.ripple_get_affected_static.argtypes = [vp, u32, vp, u32, vp]
     lib.ripple_export_edges.argtypes = [vp, C.c_int, vp, vp, u64, C.POINTER(u64)]
     lib.ripple_get_degrees.argtypes = [vp, C.c_int, vp, vp]
     lib.ripple_compact.argtypes = [vp]
@@ -267,6 +269,12 @@ def ripple_get_affected(ctx, layer, cap):
     n = C.c_uint32()
     _check(ctx, load_library().ripple_get_affected(ctx, layer, _ptr(out), int(cap), C.byref(n)))
     return out[:min(n.value, int(cap))].copy(), n.value
+
+
+def ripple_get_affected_static(ctx, layer, ids_ptr, cap, n_ptr):
+    """ids_ptr, n_ptr: device pointers (integers) owned by the caller; nothing is allocated by the call."""
+    _check(ctx, load_library().ripple_get_affected_static(ctx, layer, _ptr(int(ids_ptr)) if ids_ptr else None, int(cap),
+                                                          _ptr(int(n_ptr)) if n_ptr else None))
 
 
 def ripple_export_edges(ctx, direction, cap):

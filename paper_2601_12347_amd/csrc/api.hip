@@ -168,6 +168,7 @@ static ripple_status init_graph(ripple_ctx **out, uint32_t n_vertices, uint32_t 
     memset(&c->stats, 0, sizeof(c->stats));
     c->stream = (hipStream_t)hip_stream;
     RP_HIP(c, hipGetDevice(&c->device));
+    RP_TRY(rp_static_scratch_init(c));
     int cu = 0;
     RP_HIP(c, hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, c->device));
     c->n_cu = cu > 0 ? (uint32_t)cu : 256u;
@@ -1138,6 +1139,16 @@ extern "C" ripple_status ripple_get_affected(ripple_ctx *c, uint32_t layer, uint
     uint32_t m = std::min(n, cap);
     if (m) RP_HIP(c, hipMemcpy(ids_out, c->all_list, (size_t)m * 4, hipMemcpyDeviceToHost));
     return RIPPLE_OK;
+}
+
+extern "C" ripple_status ripple_get_affected_static(ripple_ctx *c, uint32_t layer, uint32_t *ids_out, uint32_t cap,
+                                                    uint32_t *n_out) {
+    if (!c) return RIPPLE_EINVAL;
+    if (c->state != 3) return fail(c, RIPPLE_ESTATE, "no batch has been applied");
+    if (layer > c->L || !n_out || (cap && !ids_out)) return fail(c, RIPPLE_EINVAL, "bad argument");
+    if (!is_device_ptr(n_out) || (cap && !is_device_ptr(ids_out)))
+        return fail(c, RIPPLE_EINVAL, "ids_out and n_out must be device memory");
+    return rp_launch_affected_static(c, c->last_from_rep ? c->rep[layer] : c->bm[layer], ids_out, cap, n_out);
 }
 
 extern "C" ripple_status ripple_export_edges(ripple_ctx *c, int direction, uint32_t *src_out, uint32_t *dst_out,

@@ -204,6 +204,7 @@ struct CompactArgs {
     uint32_t *touched_out;         // += vertices that received a message, or null
     uint32_t *list, *eoff, *ioff;  // outputs
     uint32_t *count_out, *msgs_out, *isum_out;
+    uint32_t list_cap;             // entries the list has room for (positions beyond are counted, not written)
 };
 
 // bitmap word of 32 mark bytes (each 0 or 1); the bytes are cleared again when any was set
@@ -256,9 +257,11 @@ struct WordDeg {
 #pragma unroll
         for (int b = 0; b < 32; ++b) {
             if (!((w >> b) & 1u)) continue;
-            a.list[oc] = idx * 32 + b;
-            if (a.want_out) a.eoff[oc] = oo;
-            if (a.want_in) a.ioff[oc] = oi;
+            if (oc < a.list_cap) {
+                a.list[oc] = idx * 32 + b;
+                if (a.want_out) a.eoff[oc] = oo;
+                if (a.want_in) a.ioff[oc] = oi;
+            }
             oo += o[b];
             oi += i[b];
             ++oc;
@@ -561,6 +564,7 @@ void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l, bool allow_disc) {
 void rp_launch_alive_list(ripple_ctx *c) {
     CompactArgs a;
     memset(&a, 0, sizeof(a));
+    a.list_cap = 0xFFFFFFFFu;
     a.bm = c->alive;                               // rewritten with the same bits
     a.alive = c->alive;
     a.n_words = c->n_words;
@@ -605,6 +609,7 @@ void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool 
     a.count_out = &c->ctr->a[l];
     a.msgs_out = (l < RIPPLE_MAX_LAYERS) ? &c->ctr->m[l + 1] : nullptr;
     a.isum_out = &c->ctr->isum[l];
+    a.list_cap = 0xFFFFFFFFu;
     launch_compact(c, a, rp_rows_hint(c, l));
 }
 
@@ -614,6 +619,7 @@ void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool 
 void rp_launch_candidates(ripple_ctx *c, uint32_t l) {
     CompactArgs a;
     memset(&a, 0, sizeof(a));
+    a.list_cap = 0xFFFFFFFFu;
     a.bm = c->bm[l];
     a.mk = c->mk;
     a.bm_sink = c->bm_sink;
@@ -635,6 +641,7 @@ void rp_launch_candidates(ripple_ctx *c, uint32_t l) {
 void rp_launch_bitmap_to_list(ripple_ctx *c, uint32_t *bitmap, uint32_t *out_list, uint32_t *count_d) {
     CompactArgs a;
     memset(&a, 0, sizeof(a));
+    a.list_cap = 0xFFFFFFFFu;
     a.bm = bitmap;
     a.alive = c->alive;
     a.n_words = c->n_words;
@@ -646,6 +653,64 @@ void rp_launch_bitmap_to_list(ripple_ctx *c, uint32_t *bitmap, uint32_t *out_lis
     a.list = out_list;
     a.count_out = count_d;
     launch_compact(c, a, c->n_cap);
+}
+
+// ---------------------------------------------------------------------------------
+// the same compaction without any allocation: block sums in a static device array
+// ---------------------------------------------------------------------------------
+// Per-block partial sums of the two-pass compaction (three arrays of RP_STATIC_BLOCKS entries: vertex
+// counts, and the out- and in-degree sums the first pass writes alongside). One copy per GPU, shared by
+// every context on that GPU and kept until the process ends; every launch writes the entries it reads,
+// so nothing has to be cleared between calls, and calls that overlap on one GPU race on it.
+#define RP_STATIC_BLOCKS 16384u                  // 256 bitmap words = 8192 vertices per block
+static __device__ __align__(256) uint32_t scratch[3 * RP_STATIC_BLOCKS];
+#define RP_MAX_DEVICES 64
+static uint32_t *g_scratch_ptr[RP_MAX_DEVICES] = {nullptr};    // the array's address on each GPU
+
+uint32_t rp_static_max_vertices() { return RP_STATIC_BLOCKS * 256u * 32u; }
+
+// Called by init_graph with the context's device current: looks the array's address up once per GPU.
+ripple_status rp_static_scratch_init(ripple_ctx *c) {
+    if (c->device < 0 || c->device >= RP_MAX_DEVICES) return RIPPLE_OK;      // such a GPU has no no-allocation path
+    if (g_scratch_ptr[c->device]) return RIPPLE_OK;
+    uint32_t *ptr = nullptr;
+    RP_HIP(c, hipGetSymbolAddress((void **)&ptr, HIP_SYMBOL(scratch)));
+    g_scratch_ptr[c->device] = ptr;
+    return RIPPLE_OK;
+}
+
+// bitmap & alive -> ascending ids in ids_out (device, room for cap), set size in *n_out (device). Allocates nothing.
+ripple_status rp_launch_affected_static(ripple_ctx *c, uint32_t *bitmap, uint32_t *ids_out, uint32_t cap,
+                                        uint32_t *n_out) {
+    uint32_t *ptr = (c->device >= 0 && c->device < RP_MAX_DEVICES) ? g_scratch_ptr[c->device] : nullptr;
+    if (!ptr) {
+        c->err = "the static scratch array was not set up for this GPU";
+        return RIPPLE_ESTATE;
+    }
+    const uint32_t nb = rp_div_up(c->n_words, 256);
+    if (nb > RP_STATIC_BLOCKS) {
+        c->err = "vertex capacity " + std::to_string(c->n_cap) + " exceeds what the no-allocation call supports (" +
+                 std::to_string(rp_static_max_vertices()) + ")";
+        return RIPPLE_EINVAL;
+    }
+    CompactArgs a;
+    memset(&a, 0, sizeof(a));
+    a.bm = bitmap;
+    a.alive = c->alive;
+    a.n_words = c->n_words;
+    a.out_meta = c->out_meta;
+    a.in_meta = c->in_meta;
+    a.part_cnt = ptr;
+    a.part_out = ptr + RP_STATIC_BLOCKS;
+    a.part_in = ptr + 2 * RP_STATIC_BLOCKS;
+    a.list = ids_out;
+    a.list_cap = cap;
+    a.count_out = n_out;
+    hipLaunchKernelGGL(k_frontier_count, dim3(nb), dim3(256), 0, c->stream, a);
+    hipLaunchKernelGGL(k_frontier_emit, dim3(nb), dim3(256), 0, c->stream, a);
+    RP_HIP(c, hipGetLastError());
+    RP_HIP(c, hipStreamSynchronize(c->stream));
+    return RIPPLE_OK;
 }
 
 void rp_launch_list_eoff(ripple_ctx *c, uint32_t l) {

@@ -22,6 +22,9 @@ void rp_launch_candidates_sparse(ripple_ctx *c, uint32_t l, bool self_term, uint
 void rp_launch_list_offsets(ripple_ctx *c, uint32_t l, bool want_out);
 void rp_launch_bitmap_to_list(ripple_ctx *c, uint32_t *bitmap, uint32_t *out_list, uint32_t *count_d);
 void rp_launch_list_eoff(ripple_ctx *c, uint32_t l);
+ripple_status rp_static_scratch_init(ripple_ctx *c);
+uint32_t rp_static_max_vertices();
+ripple_status rp_launch_affected_static(ripple_ctx *c, uint32_t *bitmap, uint32_t *ids_out, uint32_t cap, uint32_t *n_out);
 void rp_launch_frontier_sparse(ripple_ctx *c, uint32_t l, bool self_term, bool want_out, uint32_t long_min = 0);
 
 // scatter.hip
