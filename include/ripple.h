@@ -168,6 +168,12 @@ typedef enum {
                                      layers recompute a very long in-row in 512-entry segments, a workgroup each; this is the
                                      most segments a hop may have queued at a time. Rows that find the queue full are read by
                                      one workgroup, as all are with 0. Results do not depend on it (sums: up to rounding order). */
+    RIPPLE_OPT_PACKED_MESSAGES = 10, /* 0/1 (default 1), before load_model: a project-first layer whose rows have 33 to 48 columns
+                                     sends every message as one 128-byte line instead of two (a random gather costs per line
+                                     touched): block floating point, three 19-bit integers and their common power of two per
+                                     8 bytes, so that a number is off by at most 2^-19 of the largest of its three. What the
+                                     rounding takes from a message is carried into the sender's next one: the cached
+                                     aggregates stay the exact sum of what was sent and nothing accumulates. */
     RIPPLE_OPT_DETERMINISTIC = 6  /* 0/1 (default 0), before load_model: every aggregate row is produced by one owner that
                                      adds its sources in a fixed order (no float atomics; rows with a changed in-edge are
                                      recomputed from their in-neighbours), so that two runs over the same operations give
@@ -236,7 +242,8 @@ ripple_status ripple_get_aggregates(ripple_ctx *ctx, uint32_t layer, const uint3
 
 /* Width of layer's cached aggregate rows and how the layer's linear map is split: *flags bit 0:
  * handled project-first; bit 1: the self term H^{l-1}[v] W_self is cached per vertex and refreshed
- * only where H^{l-1} changed (either output pointer may be NULL). */
+ * only where H^{l-1} changed; bit 2: the layer's messages travel packed (RIPPLE_OPT_PACKED_MESSAGES)
+ * (either output pointer may be NULL). */
 ripple_status ripple_get_layer_info(ripple_ctx *ctx, uint32_t layer, uint32_t *aggregate_width, int *flags);
 
 /* Vertices the last batch could affect at `layer` (0..L), ascending, into

@@ -26,6 +26,7 @@ OPT_TIMING, OPT_SCATTER_MODE, OPT_PULL_RATIO, OPT_PROJECT_FIRST, OPT_BF16_MFMA, 
 OPT_SPLIT_MFMA = 7
 OPT_SPARSE_FRONTIER = 8
 OPT_ROW_SEGMENTS = 9
+OPT_PACKED_MESSAGES = 10
 AGG = {"sum": 0, "mean": 1, "wsum": 2, "max": 3, "min": 4, "attn": 5}
 SELF = {"none": 0, "concat": 1, "add": 2}
 ACT = {"none": 0, "relu": 1}
@@ -262,6 +263,13 @@ def ripple_get_layer_info(ctx, layer):
     w, p = C.c_uint32(), C.c_int()
     _check(ctx, load_library().ripple_get_layer_info(ctx, layer, C.byref(w), C.byref(p)))
     return w.value, bool(p.value & 1), bool(p.value & 2)
+
+
+def ripple_layer_packs_messages(ctx, layer):
+    """True when the layer's messages travel as packed 128-byte rows (flag bit 2 of ripple_get_layer_info)."""
+    p = C.c_int()
+    _check(ctx, load_library().ripple_get_layer_info(ctx, layer, None, C.byref(p)))
+    return bool(p.value & 4)
 
 
 def ripple_get_affected(ctx, layer, cap):

@@ -255,7 +255,7 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
     hipStreamSynchronize(c->stream);
     void *ptrs[] = {c->out_meta, c->in_meta, c->out_capv, c->in_capv, c->vstate, c->pend_out, c->pend_in, c->dead_out,
                     c->dead_in, c->hole_out, c->hole_in, c->out_pool, c->in_pool, c->in_w, c->alive, c->part_cnt, c->part_deg, c->part_ideg, c->ioff[0], c->ctr, c->D[0], c->D[1],
-                    c->tmp, c->PD, c->Pold, c->sold, c->seg_v, c->seg_done, c->seg_base, c->seg_r, c->seg_part, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ioff_all, c->mk, c->ops_d, c->payload_d,
+                    c->tmp, c->PD, c->MSG, c->Pold, c->sold, c->seg_v, c->seg_done, c->seg_base, c->seg_r, c->seg_part, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ioff_all, c->mk, c->ops_d, c->payload_d,
                     c->op_status, c->op_pos_out, c->op_pos_in, c->op_touch, c->touch_out, c->touch_in, c->exp_kind, c->exp_s, c->exp_a,
                     c->exp_b, c->st_src, c->st_dst, c->st_sign, c->gather_d, c->gather_ids};
     for (void *p : ptrs)
@@ -268,7 +268,7 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
         LayerDev &ly = c->layers[l];
         void *w[] = {ly.W0, ly.b0, ly.W1, ly.b1, ly.W0h, ly.W1h, ly.bzero, (ly.Wn != ly.W0) ? ly.Wn : nullptr, ly.PS,
                      ly.W0s, ly.W1s, (ly.Wns != ly.W0s) ? ly.Wns : nullptr,
-                     ly.att, ly.P, ly.ssrc, ly.sdst, ly.den};
+                     ly.att, ly.P, ly.ssrc, ly.sdst, ly.den, ly.T};
         for (void *p : w)
             if (p) hipFree(p);
     }
@@ -419,6 +419,10 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
         c->xw[l] = (c->layers[l - 1].proj || rp_layer_attn(c, l)) ? c->d[l] : c->d[l - 1];
         RP_TRY(dev_alloc(c, &c->X[l], n * c->xw[l], true));
         if (c->layers[l - 1].selfc) RP_TRY(dev_alloc(c, &c->layers[l - 1].PS, n * c->d[l], true));
+        if (c->layers[l - 1].proj) {
+            RP_TRY(dev_alloc(c, &c->layers[l - 1].T, n * c->d[l], true));
+            c->layers[l - 1].packed = c->opt_pack ? rp_msg_packed(c->d[l]) : 0u;
+        }
     }
     {
         uint32_t aw = 0;                                 // widest attention layer
@@ -453,8 +457,11 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
         uint32_t pw = 0;
         for (uint32_t l = 1; l <= c->L; ++l)
             if (c->layers[l - 1].proj) pw = std::max(pw, c->d[l]);
-        c->pd_ld = rp_round_up(pw, 16);                  // rows start on 64-byte boundaries
+        c->pd_ld = pw <= 32 ? 32 : rp_round_up(pw, 16);  // up to 32 columns: one 128-byte line per row; else 64-byte multiples
         if (pw) RP_TRY(dev_alloc(c, &c->PD, n * c->pd_ld, true));
+        bool packed = false;
+        for (uint32_t l = 1; l <= c->L; ++l) packed |= c->layers[l - 1].proj && c->layers[l - 1].packed;
+        if (packed) RP_TRY(dev_alloc(c, &c->MSG, n * RP_MSG_WORDS, true));
     }
     // bitmaps: layers 0..L, then S, then V_added, contiguous; reporting copies separately
     uint32_t *bmall = nullptr, *repall = nullptr, *lists = nullptr, *eoffs = nullptr, *ioffs = nullptr;
@@ -502,7 +509,7 @@ extern "C" ripple_status ripple_full_infer(ripple_ctx *c) {
             rp_launch_transform(c, l, c->all_list, &c->ctr->a[0], false);
             continue;
         }
-        if (c->layers[l - 1].proj) rp_launch_project(c, l, c->all_list, &c->ctr->a[0], false);
+        if (c->layers[l - 1].proj) rp_launch_project(c, l, c->all_list, &c->ctr->a[0], true);
         if (c->layers[l - 1].selfc) rp_launch_self_project(c, l, c->all_list, &c->ctr->a[0]);
         if (c->opt_deterministic) rp_launch_scatter_owner(c, l, true);     // same summation order as the batches use
         else rp_launch_pull_all(c, l);
@@ -701,6 +708,10 @@ static ripple_status ensure_batch_buffers(ripple_ctx *c, uint32_t n_ops, uint32_
 #define SPARSE_MAX_ROWS 4096u
 #define SPARSE_MAX_EDGES 65536u
 
+// Hop l + 1 forwards D^l = new - old rows of layer l, unless its layer is handled project-first: that one
+// sends H^l W_neigh minus what it has sent before and never looks at the difference.
+static bool next_reads_delta(const ripple_ctx *c, uint32_t l) { return l < c->L && !c->layers[l].proj; }
+
 static bool layer_self(const ripple_ctx *c, uint32_t l) {
     return c->layers[l - 1].self_mode != RIPPLE_SELF_NONE || rp_layer_attn(c, l);
 }
@@ -742,7 +753,7 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
             rp_launch_scatter_owner(c, l, false);
             rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l);
             t = rp_timer_begin(c);
-            rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], l < c->L);
+            rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], next_reads_delta(c, l));
             rp_timer_end(c, t, RIPPLE_PH_TRANSFORM, (int)l);
         }
         return;
@@ -772,7 +783,7 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
             else rp_launch_frontier_compact(c, l, layer_self(c, l), l < c->L, false, multi, true);
             rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l);
             t = rp_timer_begin(c);
-            rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], l < c->L);
+            rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], next_reads_delta(c, l));
             rp_timer_end(c, t, RIPPLE_PH_TRANSFORM, (int)l);
             have_all = false;                          // the candidates went through the live-vertex list's buffer
             continue;
@@ -800,7 +811,7 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
             rp_launch_gat_scatter(c, l, false, listed);
             rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l);
             t = rp_timer_begin(c);
-            rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], l < c->L);
+            rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], next_reads_delta(c, l));
             rp_timer_end(c, t, RIPPLE_PH_TRANSFORM, (int)l);
             have_all = false;                          // the long-row queue went through the live-vertex list's buffer
             continue;
@@ -823,9 +834,10 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
         if (sparse) rp_launch_frontier_sparse(c, l, layer_self(c, l), l < c->L);
         else rp_launch_frontier_mark(c, l, may_disc);
         rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
-        if (c->layers[l - 1].proj) {                   // multiply the deltas by W_neigh before they travel
+        if (c->layers[l - 1].proj) {                   // what travels is already multiplied by W_neigh
             t = rp_timer_begin(c);
-            rp_launch_project(c, l, c->list[l - 1], &c->ctr->a[l - 1], true);
+            rp_launch_project(c, l, c->list[l - 1], &c->ctr->a[l - 1], false);
+            rp_launch_messages(c, l);
             rp_timer_end(c, t, RIPPLE_PH_OTHER, (int)l);
         }
         if (c->layers[l - 1].selfc) {                  // H^{l-1} changed exactly on A_{l-1}
@@ -848,7 +860,7 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
         if (may_pull) rp_launch_scatter_pull(c, l, false, may_disc);
         rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l);
         t = rp_timer_begin(c);
-        rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], l < c->L);
+        rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], next_reads_delta(c, l));
         rp_timer_end(c, t, RIPPLE_PH_TRANSFORM, (int)l);
     }
 }
@@ -1119,7 +1131,9 @@ extern "C" ripple_status ripple_get_layer_info(ripple_ctx *c, uint32_t layer, ui
     if (c->state < 2) return fail(c, RIPPLE_ESTATE, "no model loaded");
     if (layer == 0 || layer > c->L) return fail(c, RIPPLE_EINVAL, "layer out of range");
     if (aggregate_width) *aggregate_width = c->xw[layer];
-    if (projected) *projected = (int)(c->layers[layer - 1].proj | (c->layers[layer - 1].selfc << 1));
+    if (projected)
+        *projected = (int)(c->layers[layer - 1].proj | (c->layers[layer - 1].selfc << 1) |
+                           ((c->layers[layer - 1].proj && c->layers[layer - 1].packed) ? 4u : 0u));
     return RIPPLE_OK;
 }
 
@@ -1255,6 +1269,10 @@ extern "C" ripple_status ripple_set_option(ripple_ctx *c, int option, int64_t va
     case RIPPLE_OPT_PROJECT_FIRST:
         if (c->state != 1) return fail(c, RIPPLE_ESTATE, "project-first must be chosen before load_model");
         c->opt_project = value ? 1 : 0;
+        return RIPPLE_OK;
+    case RIPPLE_OPT_PACKED_MESSAGES:
+        if (c->state != 1) return fail(c, RIPPLE_ESTATE, "packed messages must be chosen before load_model");
+        c->opt_pack = value ? 1 : 0;
         return RIPPLE_OK;
     case RIPPLE_OPT_PULL_RATIO:
         if (value < 1 || value > 1024) return fail(c, RIPPLE_EINVAL, "pull ratio must be in 1..1024");

@@ -69,6 +69,13 @@ struct LayerDev {
     uint32_t K0pad, N0pad, K1pad, N1pad;
     // project-first layers: the cached aggregate holds sum_u H[u] W_neigh (d_out wide)
     uint32_t proj;
+    // What the receivers of such a layer have been sent so far: T[u] (d_out floats) is the sum of all messages u
+    // has ever sent, so the cached aggregate is X[v] = sum over v's in-neighbours of T[u] at all times. A message
+    // is m = H[u] W_neigh - T[u] in the form it travels in (rounded to 19-bit block floating point when
+    // the row is packed into one 128-byte line) and T[u] += m: what rounding takes away from one message is part
+    // of the next, so nothing accumulates. Changed edges add or remove T[u] itself.
+    float *T;
+    uint32_t packed;                          // 0: messages travel as fp32 rows of PD; 1: as packed rows of MSG
     float *Wn;                                // neighbour weights padded to [roundup(d_in,32) x N0pad] (may alias W0)
     float *bzero;                             // N0pad zeros
     // concat layers with one linear map: PS[v] = H^{l-1}[v] W_self (d_out wide, fp32) is cached and
@@ -115,7 +122,8 @@ struct ripple_ctx {
     float *X[RIPPLE_MAX_LAYERS + 1] = {nullptr};
     float *D[2] = {nullptr, nullptr};                   // delta rows D^l[v] (valid for v in A_l), ping-pong
     float *tmp = nullptr;                               // hidden activations of two-stage updates
-    float *PD = nullptr;                                // projected rows of project-first layers
+    float *PD = nullptr;                                // project-first layers: projected rows, then fp32 messages (by vertex)
+    uint32_t *MSG = nullptr;                            // project-first layers with packed messages: 32 words per vertex
     // max / min (and attention) hops: in-rows of ROW_SPLIT_MIN entries or more are recomputed in segments of ROW_SEG
     // entries, one workgroup each. Per split row: vertex, segments finished, first segment; per segment: its row's
     // slot and its partial result (seg_ld floats)
@@ -184,6 +192,7 @@ struct ripple_ctx {
     int opt_split = 0;                          // fp32 storage: products on the bf16 matrix cores, operands split in three (read by load_model)
     int opt_deterministic = 0;                  // bit-reproducible aggregation (owner kernels, no float atomics)
     int opt_pull_ratio = 1;                     // pull when messages * width * ratio >= scanned in-edges
+    int opt_pack = 1;                           // project-first layers of 33..48 columns send one-line packed messages (read by load_model)
     ripple_stats stats;
     PhaseTimer *timer = nullptr;
     uint32_t n_cu = 256;
@@ -279,6 +288,54 @@ __device__ __forceinline__ uint32_t rp_count_le(uint32_t b, uint32_t e) {
     if (lo == 63 && top <= e) lo = 64;
     return lo;
 }
+
+// ---- packed messages ------------------------------------------------------------------
+// A message row of 33..48 numbers as one 128-byte line of sixteen 8-byte chunks. Chunk c holds columns
+// c, 16 + c and 32 + c as 19-bit two's-complement integers q (bits 0-18, 19-37, 38-56) that share a power of
+// two: the 7-bit code E in bits 57-63 stands for the factor 2^(E - 82) (E = 0: the three numbers are zero). The
+// largest of the three keeps 18 significant bits, so a number is off by at most 2^-19 of the largest in its
+// chunk. A chunk is all a lane needs to decode its three columns: nothing is exchanged between lanes.
+// Magnitudes of 2^63 and above are clipped; below 2^-82 they round to zero.
+#define RP_MSG_WORDS 32u
+#define RP_MSG_QBITS 19
+static inline uint32_t rp_msg_packed(uint32_t d) { return (d > 32u && d <= 48u) ? 1u : 0u; }   // up to 32 floats are one line as they are
+#ifdef __HIPCC__
+__device__ __forceinline__ uint2 rp_msg_encode(float m0, float m1, float m2, float &v0, float &v1, float &v2) {
+    const float big = fmaxf(fabsf(m0), fmaxf(fabsf(m1), fabsf(m2)));
+    int e = 0;
+    (void)frexpf(big, &e);                                  // big < 2^e
+    const int se = max(-81, min(45, e - (RP_MSG_QBITS - 1)));   // the factor is 2^se
+    const bool zero = !(big > 0.0f);
+    const int lim = (1 << (RP_MSG_QBITS - 1)) - 1;
+    const int q0 = zero ? 0 : max(-lim - 1, min(lim, __float2int_rn(ldexpf(m0, -se))));
+    const int q1 = zero ? 0 : max(-lim - 1, min(lim, __float2int_rn(ldexpf(m1, -se))));
+    const int q2 = zero ? 0 : max(-lim - 1, min(lim, __float2int_rn(ldexpf(m2, -se))));
+    const float f = ldexpf(1.0f, se);
+    v0 = (float)q0 * f;                                     // the values the integers stand for (exact products)
+    v1 = (float)q1 * f;
+    v2 = (float)q2 * f;
+    const unsigned long long mask = (1ull << RP_MSG_QBITS) - 1ull;
+    const unsigned long long bits = ((unsigned long long)(uint32_t)q0 & mask) | (((unsigned long long)(uint32_t)q1 & mask) << 19) |
+                                    (((unsigned long long)(uint32_t)q2 & mask) << 38) |
+                                    ((unsigned long long)(zero ? 0u : (uint32_t)(se + 82)) << 57);
+    return make_uint2((uint32_t)bits, (uint32_t)(bits >> 32));
+}
+__device__ __forceinline__ void rp_msg_decode(uint2 c, float &v0, float &v1, float &v2) {
+    const float f = __uint_as_float(((c.y >> 25) + 45u) << 23);           // 2^(E - 82); E = 0 meets q = 0
+    const int q0 = ((int)(c.x << 13)) >> 13;
+    const int q1 = ((int)(__builtin_amdgcn_alignbit(c.y, c.x, 19) << 13)) >> 13;
+    const int q2 = ((int)(c.y << 7)) >> 13;
+    v0 = (float)q0 * f;
+    v1 = (float)q1 * f;
+    v2 = (float)q2 * f;
+}
+// column `col` alone (kernels that give every lane one column)
+__device__ __forceinline__ float rp_msg_decode_col(uint2 c, uint32_t col) {
+    float v0, v1, v2;
+    rp_msg_decode(c, v0, v1, v2);
+    return col < 16u ? v0 : (col < 32u ? v1 : v2);
+}
+#endif
 
 // How hop l (1-based) moves its messages, decided on the device from the hop's own counters so
 // that no host round trip is needed. 0 push: walk the out-edges of A_{l-1}, one atomic row update

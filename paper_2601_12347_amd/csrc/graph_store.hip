@@ -293,9 +293,7 @@ struct MutArgs {
     uint32_t xw[RIPPLE_MAX_LAYERS + 1];          // width of X^l
     void *H[RIPPLE_MAX_LAYERS + 1];
     float *X[RIPPLE_MAX_LAYERS + 1];
-    const float *Wn[RIPPLE_MAX_LAYERS + 1];      // project-first layers: neighbour weights (row stride wn_ld), else null
-    uint32_t wn_ld[RIPPLE_MAX_LAYERS + 1];
-    uint32_t kslices;                            // 64-row slices of the widest of those weight matrices (at least 1)
+    float *T[RIPPLE_MAX_LAYERS + 1];             // project-first layers: what every vertex has sent so far (xw[l] floats per vertex), else null
     uint32_t mono_mask;                          // bit l: layer l takes max / min or attention (no structural terms)
     int d0_old;                                  // layer 1 does: D0 receives the old feature row instead of the difference
 };
@@ -686,6 +684,8 @@ __global__ __launch_bounds__(256) void k_apply_vertices(MutArgs a) {
                 if (l >= 1) {
                     uint32_t dp = a.xw[l];
                     for (uint32_t c = lane; c < dp; c += 64) a.X[l][(size_t)w * dp + c] = 0.0f;
+                    if (a.T[l])                            // a vertex created under this id later has sent nothing yet
+                        for (uint32_t c = lane; c < dp; c += 64) a.T[l][(size_t)w * dp + c] = 0.0f;
                 }
             }
             if (lane == 0) {
@@ -840,46 +840,26 @@ __global__ __launch_bounds__(256) void k_struct_scatter(MutArgs a) {
     const int lane = rp_lane();
     uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
     uint32_t n = min(a.ctr->n_struct, a.struct_cap);
-    // one task per changed edge, layer and 64-row slice of a project-first layer's weights: the slices'
-    // partial products meet in the atomic additions, and no wavefront walks a whole matrix alone
-    const uint32_t per = a.L * a.kslices;
+    // one task per changed edge and layer. A project-first layer's aggregate is the sum of what its in-neighbours
+    // have sent (T), so a changed edge adds or removes T[u] itself
+    const uint32_t per = a.L;
     unsigned long long total = (unsigned long long)n * per;
     for (unsigned long long t = gw; t < total; t += nw) {
-        const uint32_t e = (uint32_t)(t / per), rem = (uint32_t)(t % per);
-        const uint32_t l = rem / a.kslices + 1, ks = rem % a.kslices;
+        const uint32_t e = (uint32_t)(t / per), l = (uint32_t)(t % per) + 1;
         if ((a.mono_mask >> l) & 1u) continue;               // rows with a changed in-edge are recomputed instead
         uint32_t u = a.st_src[e], v = a.st_dst[e];
         float sg = a.st_sign[e];
-        uint32_t dp = a.d[l - 1];
-        if (a.Wn[l] == nullptr) {
-            if (ks) continue;
+        if (a.T[l] == nullptr) {
+            const uint32_t dp = a.d[l - 1];
             for (uint32_t c = lane; c < dp; c += 64) {
                 float val = rp_load_h(a.H[l - 1], a.store, (size_t)u * dp + c);
                 if (val != 0.0f) unsafeAtomicAdd(&a.X[l][(size_t)v * dp + c], sg * val);
             }
-        } else {                                             // project-first layer: add sign * (H_old[u] W_neigh)
+        } else {
             const uint32_t dn = a.xw[l];
-            const float *W = a.Wn[l];
-            const uint32_t ld = a.wn_ld[l];
-            const uint32_t k0 = 64u * ks;
-            if (k0 >= dp) continue;
-            for (uint32_t c0 = 0; c0 < dn; c0 += 64) {
-                const uint32_t c = c0 + lane;
-                float sum = 0.0f;
-                {
-                    const uint32_t kk = k0 + lane;
-                    const float hv = (kk < dp) ? rp_load_h(a.H[l - 1], a.store, (size_t)u * dp + kk) : 0.0f;
-                    // rows of W beyond dp exist (zero padding up to a multiple of 32) and meet hv = 0
-                    const uint32_t kn = min(64u, (dp - k0 + 31u) & ~31u);
-                    for (uint32_t j = 0; j < kn; j += 32) {       // 32 independent weight loads in flight (the loop is paced by L2 round trips)
-                        float w[32];
-#pragma unroll
-                        for (int t = 0; t < 32; ++t) w[t] = (c < dn) ? W[(size_t)(k0 + j + t) * ld + c] : 0.0f;
-#pragma unroll
-                        for (int t = 0; t < 32; ++t) sum += __shfl(hv, (int)(j + t)) * w[t];
-                    }
-                }
-                if (c < dn && sum != 0.0f) unsafeAtomicAdd(&a.X[l][(size_t)v * dn + c], sg * sum);
+            for (uint32_t c = lane; c < dn; c += 64) {
+                const float val = a.T[l][(size_t)u * dn + c];
+                if (val != 0.0f) unsafeAtomicAdd(&a.X[l][(size_t)v * dn + c], sg * val);
             }
         }
     }
@@ -961,16 +941,12 @@ static MutArgs make_args(ripple_ctx *c, uint32_t n_ops) {
     a.pool_cap = c->pool_cap;
     a.store = c->store;
     a.L = c->L;
-    a.kslices = 1;
     for (uint32_t l = 0; l <= RIPPLE_MAX_LAYERS; ++l) {
         a.d[l] = c->d[l];
         a.xw[l] = c->xw[l];
         a.H[l] = c->H[l];
         a.X[l] = c->X[l];
-        const bool proj = l >= 1 && l <= c->L && c->layers[l - 1].proj;
-        a.Wn[l] = proj ? c->layers[l - 1].Wn : nullptr;
-        a.wn_ld[l] = proj ? c->layers[l - 1].N0pad : 0;
-        if (proj) a.kslices = std::max(a.kslices, rp_div_up(c->d[l - 1], 64));
+        a.T[l] = (l >= 1 && l <= c->L && c->layers[l - 1].proj) ? c->layers[l - 1].T : nullptr;
     }
     a.mono_mask = 0;
     for (uint32_t l = 1; l <= c->L; ++l)
@@ -1006,7 +982,7 @@ void rp_launch_mutate(ripple_ctx *c, uint32_t n_ops, bool has_vertex_add, bool h
     hipLaunchKernelGGL(k_apply_edges, dim3(tb), dim3(256), 0, s, a);
     int t = rp_timer_begin(c);
     if (!c->opt_deterministic)                     // that mode recomputes the rows with a changed in-edge instead
-    hipLaunchKernelGGL(k_struct_scatter, dim3(has_vertex_del ? big : std::min<uint32_t>(big, rp_div_up((uint64_t)n_ops * c->L * a.kslices, 4))),
+    hipLaunchKernelGGL(k_struct_scatter, dim3(has_vertex_del ? big : std::min<uint32_t>(big, rp_div_up((uint64_t)n_ops * c->L, 4))),
                        dim3(256), 0, s, a);
     rp_timer_end(c, t, RIPPLE_PH_STRUCT, 0);
     if (has_vertex_or_feat) hipLaunchKernelGGL(k_apply_vertices, dim3(wb), dim3(256), 0, s, a);

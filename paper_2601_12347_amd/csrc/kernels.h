@@ -32,6 +32,7 @@ void rp_launch_scatter_push(ripple_ctx *c, uint32_t l, bool may_pull, bool allow
 void rp_launch_scatter_owner(ripple_ctx *c, uint32_t l, bool bootstrap);
 void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow_disc);
 void rp_launch_pull_all(ripple_ctx *c, uint32_t l);
+void rp_launch_messages(ripple_ctx *c, uint32_t l);
 void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l, const uint32_t *count_ptr, bool listed);
 
 // attention.hip
@@ -43,7 +44,7 @@ void rp_launch_gat_scores(ripple_ctx *c, uint32_t l, const uint32_t *list, const
 void rp_launch_gat_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d);
 void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool emit_delta);
 void rp_launch_self_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d);
-void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool from_deltas);
+void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool bootstrap);
 
 // api.hip: HIP-event timing of kernel classes (no-ops unless RIPPLE_OPT_TIMING is on)
 int rp_timer_begin(ripple_ctx *c);

@@ -18,7 +18,8 @@
 #define PUSH_CHUNK 64
 #define PULL_CHUNK 256
 
-template <int NJ>
+// PK = 1 (NJ = 1 only): the message rows are packed 128-byte lines (D points at them)
+template <int NJ, int PK>
 __global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, const uint32_t *count_ptr,
                                                       const uint32_t *eoff, const float *D, uint32_t ldd, uint32_t d,
                                                       const uint2 *out_meta, const uint32_t *out_pool, float *X,
@@ -58,15 +59,28 @@ __global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, cons
         for (int k0 = 0; k0 < n_here; k0 += G) {
             float dreg[G][NJ];
             uint32_t vk[G];
+            if constexpr (PK) {                              // lane = column: its chunk is lane mod 16
+                uint2 ch[G];
 #pragma unroll
-            for (int g = 0; g < G; ++g) {
-                const int k = min(k0 + g, n_here - 1);
-                const uint32_t uk = __shfl(my_u, k);
-                vk[g] = __shfl(my_v, k);
+                for (int g = 0; g < G; ++g) {
+                    const int k = min(k0 + g, n_here - 1);
+                    const uint32_t uk = __shfl(my_u, k);
+                    vk[g] = __shfl(my_v, k);
+                    ch[g] = *(const uint2 *)((const uint32_t *)D + (size_t)uk * RP_MSG_WORDS + 2u * ((uint32_t)lane & 15u));
+                }
 #pragma unroll
-                for (int j = 0; j < NJ; ++j) {
-                    const uint32_t col = lane + 64 * j;
-                    dreg[g][j] = (col < d) ? D[(size_t)uk * ldd + col] : 0.0f;
+                for (int g = 0; g < G; ++g) dreg[g][0] = ((uint32_t)lane < d) ? rp_msg_decode_col(ch[g], (uint32_t)lane) : 0.0f;
+            } else {
+#pragma unroll
+                for (int g = 0; g < G; ++g) {
+                    const int k = min(k0 + g, n_here - 1);
+                    const uint32_t uk = __shfl(my_u, k);
+                    vk[g] = __shfl(my_v, k);
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) {
+                        const uint32_t col = lane + 64 * j;
+                        dreg[g][j] = (col < d) ? D[(size_t)uk * ldd + col] : 0.0f;
+                    }
                 }
             }
 #pragma unroll
@@ -92,19 +106,23 @@ __global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, cons
 void rp_launch_scatter_push(ripple_ctx *c, uint32_t l, bool may_pull, bool allow_disc) {
     const bool proj = c->layers[l - 1].proj != 0;           // project-first: messages are already d_out wide
     const uint32_t d = c->xw[l];
-    const float *D = proj ? c->PD : c->D[(l - 1) & 1];
+    const bool packed = proj && c->layers[l - 1].packed;
+    const float *D = packed ? (const float *)c->MSG : (proj ? c->PD : c->D[(l - 1) & 1]);
     const uint32_t ldd = proj ? c->pd_ld : d;
     dim3 grid(c->n_cu * 8), block(256);
-#define PUSH_CASE(NJ)                                                                                         \
-    hipLaunchKernelGGL(k_scatter_push<NJ>, grid, block, 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],      \
-                       c->eoff[l - 1], D, ldd, d, c->out_meta, c->out_pool, c->X[l], c->ctr, l, may_pull ? 1 : 0,          \
+#define PUSH_CASE_PK(NJ, PK)                                                                                       \
+    hipLaunchKernelGGL((k_scatter_push<NJ, PK>), grid, block, 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],     \
+                       c->eoff[l - 1], D, ldd, d, c->out_meta, c->out_pool, c->X[l], c->ctr, l, may_pull ? 1 : 0,  \
                        c->opt_scatter, c->opt_pull_ratio, allow_disc ? 1 : 0)
-    if (d <= 64) PUSH_CASE(1);
+#define PUSH_CASE(NJ) PUSH_CASE_PK(NJ, 0)
+    if (packed) PUSH_CASE_PK(1, 1);
+    else if (d <= 64) PUSH_CASE(1);
     else if (d <= 128) PUSH_CASE(2);
     else if (d <= 256) PUSH_CASE(4);
     else if (d <= 512) PUSH_CASE(8);
     else PUSH_CASE(16);
 #undef PUSH_CASE
+#undef PUSH_CASE_PK
 }
 
 // ---------------------------------------------------------------------------------
@@ -135,43 +153,28 @@ struct PullArgs {
     int mode, ratio, allow_disc;
 };
 
-// WT = 1: every message is multiplied by its edge's weight (weighted sum, m = alpha (h - h_old), Sec. 3.3.3)
-template <int NJ, int DISC, int WT>
-__global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
-    if (rp_hop_mode(a.ctr, a.l, a.d, a.mode, a.ratio, a.allow_disc) != (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL)) return;
-    const uint32_t count = *a.count_ptr;
-    if (count == 0) return;
-    if (blockIdx.x == 0 && threadIdx.x == 0) a.ctr->hop_mode[a.l] = 1u + (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL);
-    // delta rows gathered per round trip; the weighted one-column kernel takes 12 so that it stays
-    // within 64 registers (eight waves per SIMD), which matters more here than the deeper round
-    constexpr int G = (NJ >= 8) ? 2 : (WT && NJ == 1) ? 12 : 16 / NJ;
-    constexpr int T = PULL_CHUNK / 64;                      // in-edges examined per lane and chunk
-    const int lane = rp_lane();
-    const uint32_t d = a.d;
-    const uint32_t total = a.ioff[count];
-    const uint32_t n_chunks = (total + PULL_CHUNK - 1) / PULL_CHUNK;
-    const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
-    const uint32_t per = (n_chunks + nw - 1) / nw;
-    const uint32_t c_begin = min(n_chunks, gw * per), c_end = min(n_chunks, c_begin + per);
-    if (c_begin >= c_end) return;
-    const uint32_t last = count - 1;
-    uint32_t i_lo = rp_seg_search_wave(a.ioff, 0, last, c_begin * PULL_CHUNK);
-    // lane j describes row i_lo + j: destination, pool position of edge e is rbase + e (mod 2^32),
-    // and bnd = first edge of row i_lo + j + 1 (the total beyond the list's end)
-    uint32_t rv, rbase, bnd;
-    {
+// The part both pull kernels share: which in-edges a chunk holds. Lane j describes row i_lo + j of the
+// list: destination rv, pool position of edge e is rbase + e (mod 2^32), and bnd = first edge of row
+// i_lo + j + 1 (the total beyond the list's end).
+template <int T, int WT>
+struct PullScan {
+    uint32_t i_lo, rv, rbase, bnd;
+    uint32_t i_nx, rv_n, rbase_n, bnd_n;
+
+    __device__ __forceinline__ void begin(const PullArgs &a, uint32_t count, uint32_t c_begin, int lane) {
+        const uint32_t last = count - 1;
+        i_lo = rp_seg_search_wave(a.ioff, 0, last, c_begin * PULL_CHUNK);
         const uint32_t ri = min(last, i_lo + lane);
         rv = a.list[ri];
         rbase = a.in_meta[rv].x - a.ioff[ri];
         bnd = a.ioff[min(count, i_lo + 1 + lane)];
     }
-    for (uint32_t c = c_begin; c < c_end; ++c) {
-        const uint32_t e0 = c * PULL_CHUNK, e1 = min(total, e0 + PULL_CHUNK);
+    // edge e0 + 64 t + lane of the chunk [e0, e1): its destination, source, weight and whether the source is in
+    // A_{l-1}; then requests the rows of the next chunk, which are in flight while this chunk's messages are gathered
+    __device__ __forceinline__ void chunk(const PullArgs &a, uint32_t count, uint32_t e0, uint32_t e1, int lane,
+                                          uint32_t (&my_v)[T], uint32_t (&my_u)[T], float (&my_w)[WT ? T : 1], bool (&dirty)[T]) {
+        const uint32_t last = count - 1;
         const bool fits = __shfl(bnd, 63) > e1 - 1;         // every row of the chunk is among the 64 held
-        uint32_t my_v[T], my_u[T];
-        float my_w[WT ? T : 1];
-        bool dirty[T];
-        uint32_t i_nx;
         if (fits) {
 #pragma unroll
             for (int t = 0; t < T; ++t) {
@@ -209,14 +212,46 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
             }
             i_nx = rp_seg_forward(a.ioff, i_hi, last, e1);
         }
-        // rows of the next chunk: in flight while this chunk's messages are gathered
-        uint32_t rv_n, rbase_n, bnd_n;
-        {
-            const uint32_t ri = min(last, i_nx + lane);
-            rv_n = a.list[ri];
-            rbase_n = a.in_meta[rv_n].x - a.ioff[ri];
-            bnd_n = a.ioff[min(count, i_nx + 1 + lane)];
-        }
+        const uint32_t ri = min(last, i_nx + lane);
+        rv_n = a.list[ri];
+        rbase_n = a.in_meta[rv_n].x - a.ioff[ri];
+        bnd_n = a.ioff[min(count, i_nx + 1 + lane)];
+    }
+    __device__ __forceinline__ void advance() {
+        i_lo = i_nx;
+        rv = rv_n;
+        rbase = rbase_n;
+        bnd = bnd_n;
+    }
+};
+
+// WT = 1: every message is multiplied by its edge's weight (weighted sum, m = alpha (h - h_old), Sec. 3.3.3)
+template <int NJ, int DISC, int WT>
+__global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
+    if (rp_hop_mode(a.ctr, a.l, a.d, a.mode, a.ratio, a.allow_disc) != (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL)) return;
+    const uint32_t count = *a.count_ptr;
+    if (count == 0) return;
+    if (blockIdx.x == 0 && threadIdx.x == 0) a.ctr->hop_mode[a.l] = 1u + (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL);
+    // delta rows gathered per round trip; the weighted one-column kernel takes 12 so that it stays
+    // within 64 registers (eight waves per SIMD), which matters more here than the deeper round
+    constexpr int G = (NJ >= 8) ? 2 : (WT && NJ == 1) ? 12 : 16 / NJ;
+    constexpr int T = PULL_CHUNK / 64;                      // in-edges examined per lane and chunk
+    const int lane = rp_lane();
+    const uint32_t d = a.d;
+    const uint32_t total = a.ioff[count];
+    const uint32_t n_chunks = (total + PULL_CHUNK - 1) / PULL_CHUNK;
+    const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    const uint32_t per = (n_chunks + nw - 1) / nw;
+    const uint32_t c_begin = min(n_chunks, gw * per), c_end = min(n_chunks, c_begin + per);
+    if (c_begin >= c_end) return;
+    PullScan<T, WT> scan;
+    scan.begin(a, count, c_begin, lane);
+    for (uint32_t c = c_begin; c < c_end; ++c) {
+        const uint32_t e0 = c * PULL_CHUNK, e1 = min(total, e0 + PULL_CHUNK);
+        uint32_t my_v[T], my_u[T];
+        float my_w[WT ? T : 1];
+        bool dirty[T];
+        scan.chunk(a, count, e0, e1, lane, my_v, my_u, my_w, dirty);
         uint32_t cur = 0xFFFFFFFFu;                          // destination whose partial sum is held
         float acc[NJ];
 #pragma unroll
@@ -280,11 +315,138 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
             }
             if (DISC && lane == 0) atomicOr(&a.bm_cur[cur >> 5], 1u << (cur & 31));   // once per receiver and chunk
         }
-        i_lo = i_nx;
-        rv = rv_n;
-        rbase = rbase_n;
-        bnd = bnd_n;
+        scan.advance();
     }
+}
+
+// The same hop for packed message rows (one 128-byte line each, see rp_msg_encode). Decoding a row costs a dozen
+// vector instructions whatever the number of lanes that take part, and a wavefront's instruction rate, not the
+// memory system, is what bounds a one-line gather; so a row is handled by 16 lanes (8 bytes = three columns
+// each) and a wavefront works on four messages, a quad, at a time. The dirty in-edges of a chunk are first
+// compacted (source, destination, weight) into LDS in edge order, i.e. sorted by destination; quad k is entries
+// 4k .. 4k+3, one per 16-lane group. While all four belong to the destination being summed, every group adds its
+// message to its own partial sums. A quad in which the destination changes is taken entry by entry; a change
+// first adds the four groups' partial sums together and sends the row to memory as one 47-lane atomic addition
+// (the atomic units take about three cycles per lane, so the number of such rows, not of instructions, is what
+// counts). The destination and the partial sums carry over from chunk to chunk: a wavefront adds to a row once,
+// however many chunks the row's in-edges span.
+#define PULL4_QUADS 4                                       // quads (16 rows) in flight per wavefront
+template <int DISC, int WT>
+__global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
+    if (rp_hop_mode(a.ctr, a.l, a.d, a.mode, a.ratio, a.allow_disc) != (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL)) return;
+    const uint32_t count = *a.count_ptr;
+    if (count == 0) return;
+    if (blockIdx.x == 0 && threadIdx.x == 0) a.ctr->hop_mode[a.l] = 1u + (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL);
+    constexpr int T = PULL_CHUNK / 64;
+    constexpr uint32_t NONE = 0xFFFFFFFFu;
+    __shared__ uint32_t s_u[4][PULL_CHUNK], s_v[4][PULL_CHUNK];
+    __shared__ float s_w[WT ? 4 : 1][WT ? PULL_CHUNK : 1];
+    const int lane = rp_lane(), wave = threadIdx.x >> 6;
+    const uint32_t grp = (uint32_t)lane >> 4, sub = (uint32_t)lane & 15u;
+    const uint32_t d = a.d;
+    const uint32_t total = a.ioff[count];
+    const uint32_t n_chunks = (total + PULL_CHUNK - 1) / PULL_CHUNK;
+    const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    const uint32_t per = (n_chunks + nw - 1) / nw;
+    const uint32_t c_begin = min(n_chunks, gw * per), c_end = min(n_chunks, c_begin + per);
+    if (c_begin >= c_end) return;
+    const uint32_t *msg = (const uint32_t *)a.D;
+    const uint32_t my_col = 16u * grp + sub;                // the column this lane sends to memory
+    const bool sends = grp < 3u && my_col < d;
+    uint32_t cur = NONE;                                    // destination being summed (the same in all lanes)
+    float acc0 = 0.0f, acc1 = 0.0f, acc2 = 0.0f;            // this group's partial sums of columns sub, 16 + sub, 32 + sub
+    auto flush = [&]() {
+        acc0 += __shfl_xor(acc0, 16);
+        acc1 += __shfl_xor(acc1, 16);
+        acc2 += __shfl_xor(acc2, 16);
+        acc0 += __shfl_xor(acc0, 32);
+        acc1 += __shfl_xor(acc1, 32);
+        acc2 += __shfl_xor(acc2, 32);
+        const float mine = grp == 0u ? acc0 : (grp == 1u ? acc1 : acc2);
+        if (sends && mine != 0.0f) unsafeAtomicAdd(&a.X[(size_t)cur * d + my_col], mine);
+        if (DISC && lane == 0) atomicOr(&a.bm_cur[cur >> 5], 1u << (cur & 31));
+        acc0 = acc1 = acc2 = 0.0f;
+    };
+    PullScan<T, WT> scan;
+    scan.begin(a, count, c_begin, lane);
+    for (uint32_t c = c_begin; c < c_end; ++c) {
+        const uint32_t e0 = c * PULL_CHUNK, e1 = min(total, e0 + PULL_CHUNK);
+        uint32_t my_v[T], my_u[T];
+        float my_w[WT ? T : 1];
+        bool dirty[T];
+        scan.chunk(a, count, e0, e1, lane, my_v, my_u, my_w, dirty);
+        // compact the dirty edges, in edge order
+        uint32_t n = 0;
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const unsigned long long mask = __ballot(dirty[t]);
+            const uint32_t pos = n + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+            if (dirty[t]) {
+                s_u[wave][pos] = my_u[t];
+                s_v[wave][pos] = my_v[t];
+                if (WT) s_w[wave][pos] = my_w[t];
+            }
+            n += (uint32_t)__popcll(mask);
+        }
+        // LDS accesses of one wavefront are executed in order, so the loads below see the stores above without a
+        // workgroup barrier; the fence keeps the compiler from moving them across each other
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const uint32_t n_quads = (n + 3u) >> 2;
+        for (uint32_t k0 = 0; k0 < n_quads; k0 += PULL4_QUADS) {
+            uint32_t vk[PULL4_QUADS];
+            float wk[PULL4_QUADS];
+            uint2 ch[PULL4_QUADS];
+#pragma unroll
+            for (int r = 0; r < PULL4_QUADS; ++r) {          // entries past the list's end repeat its last one: a valid row, not used
+                const uint32_t idx = min(4u * (k0 + r) + grp, n - 1u);
+                const uint32_t uk = s_u[wave][idx];
+                vk[r] = s_v[wave][idx];
+                if (WT) wk[r] = s_w[wave][idx];
+                ch[r] = *(const uint2 *)(msg + (size_t)uk * RP_MSG_WORDS + 2u * sub);
+            }
+#pragma unroll
+            for (int r = 0; r < PULL4_QUADS; ++r) {
+                const uint32_t k = k0 + r;
+                if (k < n_quads) {
+                    float v0, v1, v2;
+                    rp_msg_decode(ch[r], v0, v1, v2);
+                    if (WT) {
+                        v0 *= wk[r];
+                        v1 *= wk[r];
+                        v2 *= wk[r];
+                    }
+                    const uint32_t v_first = (uint32_t)__builtin_amdgcn_readlane((int)vk[r], 0);
+                    const uint32_t v_last = (uint32_t)__builtin_amdgcn_readlane((int)vk[r], 48);
+                    if (4u * k + 3u < n && v_first == cur && v_last == cur) {   // the whole quad goes on
+                        acc0 += v0;
+                        acc1 += v1;
+                        acc2 += v2;
+                    } else {                                 // entry by entry (they are sorted by destination)
+#pragma unroll
+                        for (uint32_t g = 0; g < 4u; ++g) {
+                            if (4u * k + g < n) {
+                                const uint32_t vg = (uint32_t)__builtin_amdgcn_readlane((int)vk[r], 16 * (int)g);
+                                if (vg != cur) {
+                                    if (cur != NONE) flush();
+                                    cur = vg;
+                                }
+                                if (grp == g) {
+                                    acc0 += v0;
+                                    acc1 += v1;
+                                    acc2 += v2;
+                                }
+                            }
+                        }
+                    }
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();                    // the next chunk overwrites the lists
+        scan.advance();
+    }
+    if (cur != NONE) flush();
 }
 
 // discover = false: pull into A_l (the hop's list). true: scan every live vertex (c->all_list and
@@ -298,7 +460,8 @@ void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow
     a.in_pool = c->in_pool;
     a.bm_prev = c->bm[l - 1];
     a.bm_cur = c->bm[l];
-    a.D = c->layers[l - 1].proj ? c->PD : c->D[(l - 1) & 1];
+    const bool packed = c->layers[l - 1].proj && c->layers[l - 1].packed;
+    a.D = packed ? (const float *)c->MSG : (c->layers[l - 1].proj ? c->PD : c->D[(l - 1) & 1]);
     a.d = c->xw[l];
     a.ldd = c->layers[l - 1].proj ? c->pd_ld : a.d;
     a.X = c->X[l];
@@ -317,12 +480,94 @@ void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow
         else if (wt) hipLaunchKernelGGL((k_scatter_pull<NJ, 0, 1>), grid, block, 0, c->stream, a);         \
         else hipLaunchKernelGGL((k_scatter_pull<NJ, 0, 0>), grid, block, 0, c->stream, a);                 \
     } while (0)
-    if (a.d <= 64) PULL_CASE(1);
+    if (packed) {
+        if (discover && wt) hipLaunchKernelGGL((k_scatter_pull4<1, 1>), grid, block, 0, c->stream, a);
+        else if (discover) hipLaunchKernelGGL((k_scatter_pull4<1, 0>), grid, block, 0, c->stream, a);
+        else if (wt) hipLaunchKernelGGL((k_scatter_pull4<0, 1>), grid, block, 0, c->stream, a);
+        else hipLaunchKernelGGL((k_scatter_pull4<0, 0>), grid, block, 0, c->stream, a);
+    } else if (a.d <= 64) PULL_CASE(1);
     else if (a.d <= 128) PULL_CASE(2);
     else if (a.d <= 256) PULL_CASE(4);
     else if (a.d <= 512) PULL_CASE(8);
     else PULL_CASE(16);
 #undef PULL_CASE
+}
+
+// ---------------------------------------------------------------------------------
+// messages of a project-first layer
+// ---------------------------------------------------------------------------------
+// For every vertex u of A_{l-1}: P[u] = H^{l-1}[u] W_neigh has just been written to PD[u]. The message is what
+// the receivers are still missing, m = P[u] - T[u], in the form it travels in: an fp32 row (left in PD[u];
+// T[u] = P[u]) or a packed row (written to MSG[u]; T[u] += the values the packed numbers stand for, so what the
+// rounding took away is part of u's next message). 16 lanes per row, three columns (c, 16 + c, 32 + c) each for
+// packed rows; four rows per wavefront and step, two steps in flight.
+__global__ __launch_bounds__(256) void k_messages(const uint32_t *list, const uint32_t *count_ptr, float *PD, uint32_t ldd,
+                                                  float *T, uint32_t d, uint32_t packed, uint32_t *MSG) {
+    const uint32_t count = *count_ptr;
+    const uint32_t lane = (uint32_t)rp_lane();
+    const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    if (!packed) {                                          // any width: one wavefront per row, element by element
+        constexpr int R = 8;
+        for (uint32_t s0 = gw * R; s0 < count; s0 += nw * R) {
+            uint32_t u[R];
+#pragma unroll
+            for (int r = 0; r < R; ++r) u[r] = list[min(s0 + r, count - 1u)];
+            for (uint32_t col = lane; col < d; col += 64) {
+                float p[R], t[R];
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    p[r] = PD[(size_t)u[r] * ldd + col];
+                    t[r] = T[(size_t)u[r] * d + col];
+                }
+#pragma unroll
+                for (int r = 0; r < R; ++r) {
+                    if (s0 + r >= count) continue;
+                    PD[(size_t)u[r] * ldd + col] = p[r] - t[r];
+                    T[(size_t)u[r] * d + col] = p[r];
+                }
+            }
+        }
+        return;
+    }
+    constexpr int R = 2;
+    const uint32_t grp = lane >> 4, sub = lane & 15u;
+    const bool has1 = 16u + sub < d, has2 = 32u + sub < d;
+    for (uint32_t s0 = gw * 4u * R; s0 < count; s0 += nw * 4u * R) {
+        uint32_t u[R];
+        float p[R][3], t[R][3];
+#pragma unroll
+        for (int r = 0; r < R; ++r) u[r] = list[min(s0 + 4u * r + grp, count - 1u)];
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const float *pr = PD + (size_t)u[r] * ldd;
+            const float *tr = T + (size_t)u[r] * d;
+            p[r][0] = pr[sub];
+            t[r][0] = tr[sub];
+            p[r][1] = has1 ? pr[16u + sub] : 0.0f;
+            t[r][1] = has1 ? tr[16u + sub] : 0.0f;
+            p[r][2] = has2 ? pr[32u + sub] : 0.0f;
+            t[r][2] = has2 ? tr[32u + sub] : 0.0f;
+        }
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            if (s0 + 4u * r + grp >= count) continue;
+            float v0, v1, v2;
+            const uint2 ch = rp_msg_encode(p[r][0] - t[r][0], p[r][1] - t[r][1], p[r][2] - t[r][2], v0, v1, v2);
+            *(uint2 *)(MSG + (size_t)u[r] * RP_MSG_WORDS + 2u * sub) = ch;
+            float *tr = T + (size_t)u[r] * d;
+            tr[sub] = t[r][0] + v0;
+            if (has1) tr[16u + sub] = t[r][1] + v1;
+            if (has2) tr[32u + sub] = t[r][2] + v2;
+        }
+    }
+}
+
+void rp_launch_messages(ripple_ctx *c, uint32_t l) {
+    const LayerDev &ly = c->layers[l - 1];
+    const uint32_t hint = rp_rows_hint(c, l - 1);
+    const uint32_t grid = std::max<uint32_t>(1u, std::min<uint32_t>(c->n_cu * 8, rp_div_up(hint, 4 * 8) + 1));
+    hipLaunchKernelGGL(k_messages, dim3(grid), dim3(256), 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1], c->PD, c->pd_ld,
+                       ly.T, c->xw[l], ly.packed, c->MSG);
 }
 
 // ---------------------------------------------------------------------------------
@@ -1252,14 +1497,14 @@ __global__ __launch_bounds__(256) void k_pull_all(const uint2 *in_meta, const ui
     }
 }
 
-// X^l[v] = sum over v's in-row of the previous layer's rows (of their projections, kept in PD,
+// X^l[v] = sum over v's in-row of the previous layer's rows (of their projections, kept in the layer's T,
 // for project-first layers)
 void rp_launch_pull_all(ripple_ctx *c, uint32_t l) {
     const bool proj = c->layers[l - 1].proj != 0;
     const uint32_t d = c->xw[l];
-    const void *src = proj ? (const void *)c->PD : c->H[l - 1];
+    const void *src = proj ? (const void *)c->layers[l - 1].T : c->H[l - 1];
     const int store = proj ? 0 : c->store;
-    const uint32_t lds = proj ? c->pd_ld : d;
+    const uint32_t lds = d;
     const float *w = (c->layers[l - 1].agg == RIPPLE_AGG_WSUM) ? c->in_w : nullptr;
     const int op = c->layers[l - 1].agg == RIPPLE_AGG_MAX ? 1 : (c->layers[l - 1].agg == RIPPLE_AGG_MIN ? 2 : 0);
     dim3 grid(c->n_cu * 16), block(256);

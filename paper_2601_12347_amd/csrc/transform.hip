@@ -1145,16 +1145,15 @@ static TArgs base_args(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
     return a;
 }
 
-// Project-first layers: P = rows * W_neigh, no bias, no activation.
-//   from_deltas: rows are the delta rows D^{l-1}[v] of the listed vertices
-//   otherwise:   rows are H^{l-1}[v] (bootstrap)
-// P[v] goes to c->PD.
-void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool from_deltas) {
+// Project-first layers: P[v] = H^{l-1}[v] W_neigh for the listed vertices, no bias, no activation.
+//   bootstrap: into the layer's T (what every vertex has sent: the aggregates are then summed from it)
+//   otherwise: into c->PD, from where rp_launch_messages turns the rows into this hop's messages
+void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool bootstrap) {
     const LayerDev &ly = c->layers[l - 1];
     TArgs a = base_args(c, l, list, count_d);
     a.mean = 0;
     a.W = ly.Wn;
-    a.Wt = nullptr;                                // deltas of bf16 values need more than 8 mantissa bits: fp32 path
+    a.Wt = nullptr;                                // messages are differences of such products: fp32 path also for bf16 rows
     a.Ws = ly.Wns;
     a.wt_ld = ly.Wns_ld;
     a.ws_plane = (size_t)ly.N0pad * ly.Wns_ld;
@@ -1162,17 +1161,12 @@ void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
     a.K = ly.d_in;
     a.Kpad = rp_round_up(ly.d_in, 32);
     a.act = RIPPLE_ACT_NONE;
-    a.tmp_out = c->PD;
-    a.tmp_out_ld = c->pd_ld;
+    a.tmp_out = bootstrap ? ly.T : c->PD;
+    a.tmp_out_ld = bootstrap ? ly.d_out : c->pd_ld;
     a.Hout = nullptr;
     a.out_mode = 2;
-    if (from_deltas) {
-        a.a_mode = 0;                              // rows of an fp32 matrix indexed by vertex, unscaled (mean = 0)
-        a.X = c->D[(l - 1) & 1];
-    } else {
-        a.a_mode = 4;
-    }
-    launch_t(c, a, ly.d_in % 4 == 0, from_deltas ? rp_rows_hint(c, l - 1) : c->n_cap);
+    a.a_mode = 4;
+    launch_t(c, a, ly.d_in % 4 == 0, bootstrap ? c->n_cap : rp_rows_hint(c, l - 1));
 }
 
 // Attention layer l: P[v] = H^{l-1}[v] W0 for the listed vertices (fp32, no bias, no activation).

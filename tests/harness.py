@@ -12,7 +12,7 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}      # max relative error per layer (metric: o
 
 class Pair:
     def __init__(self, n, cap, src, dst, feats, model, store="f32", edge_capacity=None, project_first=True,
-                 self_cache=True, deterministic=False, weights=None, split=None):
+                 self_cache=True, deterministic=False, weights=None, split=None, packed=None):
         self.n, self.cap, self.model, self.store = n, cap, model, store
         self.widths = [model[0]["d_in"]] + [l["d_out"] for l in model]
         self.L = len(model)
@@ -30,6 +30,8 @@ class Pair:
             rp.ripple_set_option(self.ctx, rp.OPT_DETERMINISTIC, 1)
         if split is not None:
             rp.ripple_set_option(self.ctx, rp.OPT_SPLIT_MFMA, int(split))
+        if packed is not None:
+            rp.ripple_set_option(self.ctx, rp.OPT_PACKED_MESSAGES, int(packed))
         rp.ripple_load_model(self.ctx, model)
         rp.ripple_full_infer(self.ctx)
         # first layer (1-based) that aggregates with max / min: from there on the reported sets are pruned
@@ -169,14 +171,14 @@ class Pair:
 
 def make_pair(n=300, e=1500, d0=12, kind="gcn_sum", widths=(12, 20, 8), store="f32", seed=0, slack=64,
               gamma=2.1, top_share=0.03, edge_capacity=None, project_first=True, self_cache=True, deterministic=False,
-              weighted=False, split=None):
+              weighted=False, split=None, packed=None):
     src, dst, out_law, in_law = ri.chung_lu_graph(n, e, gamma, top_share, seed)
     feats = ri.features(n, d0, seed + 1)
     model = ri.make_model(kind, widths, seed + 2)
     weights = ri.edge_weights(len(src), seed + 3) if weighted else None
     pair = Pair(n, n + slack, src, dst, feats, model, store=store, edge_capacity=edge_capacity,
                 project_first=project_first, self_cache=self_cache, deterministic=deterministic, weights=weights,
-                split=split)
+                split=split, packed=packed)
     return pair, (src, dst, out_law, in_law)
 
 

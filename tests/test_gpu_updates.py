@@ -75,6 +75,66 @@ def test_push_and_pull_scatter_agree_with_oracle(mode, kind, widths):
         pair.close()
 
 
+PACKED_CASES = [(mode, *case) for case in [("sage_mean", (12, 96, 47), "f32", False), ("gcn_sum", (80, 33), "f32", False),
+                                           ("gcn_wsum", (16, 100, 40), "f32", True), ("gcn_sum", (24, 88, 44), "bf16", False)]
+                for mode in (0, 1, 2, 3) if not (case[3] and mode == 1)]      # weighted layers have no push kernel
+
+
+@pytest.mark.parametrize("mode,kind,widths,store,weighted", PACKED_CASES)
+def test_packed_messages(mode, kind, widths, store, weighted):
+    """Project-first layers of 33 to 47 columns send one-line packed messages (21 to 24-bit block floating point,
+    the rounding error of a message carried into the sender's next one): every way of moving them (push, pull,
+    discovering scan) matches the oracle to the fp32 tolerance, the cached aggregates stay the sum of the
+    projected rows, and a twin context with the option off reports the same sets."""
+    print("case packed messages", mode, kind, widths, store, flush=True)
+    kw = dict(n=700, e=6500, d0=widths[0], kind=kind, widths=widths, seed=131, slack=96, store=store, weighted=weighted)
+    pair, graph = make_pair(**kw)
+    plain, _ = make_pair(packed=False, **kw)
+    L = len(widths) - 1
+    assert rp.ripple_layer_packs_messages(pair.ctx, L) and not rp.ripple_layer_packs_messages(plain.ctx, L)
+    assert rp.ripple_get_layer_info(pair.ctx, L)[:2] == (widths[-1], True)
+    rp.ripple_set_option(pair.ctx, rp.OPT_SCATTER_MODE, mode)
+    rp.ripple_set_option(plain.ctx, rp.OPT_SCATTER_MODE, mode)
+    stream = make_stream(pair, graph, MIXV, 133, weighted=weighted)
+    tol = 1e-3 if store == "bf16" else None
+    try:
+        pair.check_aggregates(tol=tol)
+        for b, bs in enumerate([4, 50, 160, 30, 90]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            res, _, _ = pair.step(ops, payload)
+            res2 = rp.ripple_apply_updates(plain.ctx, ops, payload)
+            assert list(res.affected) == list(res2.affected) and list(res.messages) == list(res2.messages)
+            # against the unpacked twin the rows differ by far less than the tolerance allows
+            a = pair.gpu_layer(L)
+            b_ = plain.gpu_layer(L)
+            scale = max(1e-30, float(np.abs(b_).max()))
+            assert float(np.abs(a - b_).max()) <= (2e-2 if store == "bf16" else 2e-5) * scale
+        pair.check_graph()
+        pair.check_aggregates(tol=tol)
+    finally:
+        pair.close()
+        plain.close()
+
+
+def test_packed_messages_do_not_drift():
+    """300 batches on a small graph: every vertex sends many messages; the cached aggregates of the packed
+    layer must stay the sum of the stored rows' projections (what a message loses to rounding is in the next)."""
+    print("case packed drift", flush=True)
+    pair, graph = make_pair(n=400, e=3600, d0=10, kind="sage_mean", widths=(10, 96, 47), seed=141, slack=800)
+    assert rp.ripple_layer_packs_messages(pair.ctx, 2)
+    stream = make_stream(pair, graph, MIXV, 143)
+    try:
+        for b in range(300):
+            ops, payload, _ = stream.next_batch(40)
+            pair.step(ops, payload, check=(b % 60 == 59))
+        pair.check_aggregates()
+        errs, _ = pair.check_embeddings()
+        print(" errors after 300 batches", ["%.2e" % e for e in errs], flush=True)
+    finally:
+        pair.close()
+
+
 @pytest.mark.parametrize("kind,widths,store", [("sage_mean", (16, 40, 24, 10), "f32"), ("gcn_sum", (100, 256, 47), "f32"),
                                                ("gcn_mean", (32, 64, 12), "bf16")])
 @pytest.mark.parametrize("project_first", [True, False])
