@@ -33,8 +33,9 @@ def log(*a):
 
 # HBM bytes per launch of the kernel classes of the default workload (dense_sage_mean, 10,000 updates per
 # batch), measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and scaled by a 1 GiB copy of known size
-# (profiles/hbm_traffic_dense_sage_mean_bs10000_pmc.txt: FETCH_SIZE x 2.0, WRITE_SIZE x 1.0). bench.py cannot run
+# (FETCH_SIZE x 2.0, WRITE_SIZE x 1.0; the file named below holds commands and raw values). bench.py cannot run
 # the profiler on itself; for any other workload `traffic` is null.
+TRAFFIC_SOURCE = "profiles/hbm_traffic_dense_sage_mean_bs10000_pmc.txt"
 MEASURED_TRAFFIC_BYTES = {
     ("dense_sage_mean", 10000): {"scatter_l3": 19.0e9, "scatter_l2": 6.5e9, "transform_l2": 7.8e9, "transform_l3": 5.6e9},
 }
@@ -60,16 +61,20 @@ def algorithmic_work(st, model, widths, store, L, layer_info, n_edges=0):
     for l in range(1, L + 1):
         lay = model[l - 1]
         d_prev, d_out = widths[l - 1], widths[l]
-        w_agg, projected, self_cached = layer_info[l]
+        w_agg, projected, self_cached = layer_info[l][:3]
+        # a message row: the aggregate's width in fp32, or one 128-byte line where the layer packs its messages
+        row_bytes = 128 if (len(layer_info[l]) > 3 and layer_info[l][3]) else w_agg * 4
         a_prev, a_l, m_l, t_l = st.rows[l - 1], st.rows[l], st.msgs[l], st.touched[l]
-        out[("scatter", l)] = dict(bytes=a_prev * w_agg * 4 + 8 * a_prev + 4 * m_l + 2 * t_l * w_agg * 4, flops=m_l * w_agg,
+        out[("scatter", l)] = dict(bytes=a_prev * row_bytes + 8 * a_prev + 4 * m_l + 2 * t_l * w_agg * 4, flops=m_l * w_agg,
                                    # what a cache-less per-message scheme moves: one message row gathered per message
-                                   msg_bytes=m_l * (w_agg * 4 + 4) + 2 * t_l * w_agg * 4)
+                                   msg_bytes=m_l * (row_bytes + 4) + 2 * t_l * w_agg * 4,
+                                   lines=m_l * ((row_bytes + 127) // 128))
         discovered = l >= 2 and n_edges and m_l * 8 >= n_edges * max(st.batches, 1)
         if not discovered:
             out[("frontier", l)] = dict(bytes=8 * a_prev + 4 * m_l + 4 * a_l, flops=0)
         self_w = lay["d_in"] if lay["self"] != "none" else 0
-        out_bytes = d_out * s_h * 2 + (d_out * 4 if l < L else 0) + 4
+        next_projected = l < L and layer_info[l + 1][1]
+        out_bytes = d_out * s_h * 2 + (d_out * 4 if (l < L and not next_projected) else 0) + 4
         if lay["agg"] == "attn":
             # projection of A_{l-1} (row in, d_out floats out), then per dirty row numerator, denominator, old and new row
             flops = 2 * a_prev * d_prev * d_out
@@ -79,11 +84,11 @@ def algorithmic_work(st, model, widths, store, L, layer_info, n_edges=0):
             # term and the aggregate (projected, or multiplied by W_neigh here) are read
             flops = 2 * a_prev * self_w * d_out + (2 * a_prev * d_prev * d_out if projected else 2 * a_l * d_prev * d_out)
             nbytes = a_prev * (self_w * s_h + d_out * 4) + a_l * (d_out * 4 + w_agg * 4 + out_bytes)
-            if projected:
-                nbytes += a_prev * (d_prev * 4 + w_agg * 4)
+            if projected:                               # rows of A_{l-1} in, message out, running sum read and written
+                nbytes += a_prev * (d_prev * s_h + row_bytes + 2 * w_agg * 4) - a_prev * self_w * s_h   # one pass serves both products
         elif projected:
             flops = 2 * a_l * self_w * d_out + 2 * a_prev * d_prev * d_out
-            nbytes = a_l * (self_w * s_h + w_agg * 4 + out_bytes) + a_prev * (d_prev * 4 + w_agg * 4)
+            nbytes = a_l * (self_w * s_h + w_agg * 4 + out_bytes) + a_prev * (d_prev * s_h + row_bytes + 2 * w_agg * 4)
         else:
             k = lay["d_in"] + self_w if lay["self"] == "concat" else lay["d_in"]
             if lay["d_hidden"]:
@@ -95,39 +100,75 @@ def algorithmic_work(st, model, widths, store, L, layer_info, n_edges=0):
     return out
 
 
-def cpu_baseline(cfg, bs, scale):
-    """The oracle on a 1/scale copy of the workload (same recipe, N/scale vertices, E/scale
-    edges, bs/scale updates): one batch applied and everything recomputed in fp64. Recompute
-    cost is linear in N and E (Sec. 3.5's operation count with a_l = N), so the full-size time
-    per batch is estimated as scale times the sample's."""
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as fh:
+            for line in fh:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def _oracle_batch_seconds(cfg, n, e, top_share, bs, threads):
+    """One batch applied to the oracle's graph, every embedding recomputed (fp64) and the affected sets derived,
+    with the linear-algebra library held to `threads` threads (None: as many as it takes by itself)."""
     import oracle
     import ripple_inputs as ri
-    n, e = max(cfg.n // scale, 64), max(cfg.e // scale, 256)
-    src, dst, out_law, in_law = ri.chung_lu_graph(n, e, cfg.gamma, min(cfg.top_share * scale, 0.05), cfg.graph_seed)
+    from contextlib import nullcontext
+    try:
+        from threadpoolctl import threadpool_limits, threadpool_info
+    except ImportError:
+        threadpool_limits, threadpool_info = None, None
+    src, dst, out_law, in_law = ri.chung_lu_graph(n, e, cfg.gamma, top_share, cfg.graph_seed)
     feats = ri.features(n, cfg.d0, cfg.feat_seed)
     model = ri.make_model(cfg.model, cfg.widths, cfg.weight_seed)
     stream = ri.UpdateStream(n, n + cfg.vertex_slack, src, dst, out_law, in_law, cfg.d0, cfg.mix, cfg.stream_seed,
                              weighted=cfg.weighted)
     st = oracle.GraphState(n, n + cfg.vertex_slack, src, dst, feats,
                            weights=ri.edge_weights(len(src), cfg.graph_seed + 100) if cfg.weighted else None)
+    ops, payload, _ = stream.next_batch(bs)
+    del src, dst, stream
+    limit = threadpool_limits(limits=threads) if (threads and threadpool_limits) else nullcontext()
+    with limit:
+        used = max([p.get("num_threads", 1) for p in threadpool_info()] + [1]) if threadpool_info else (os.cpu_count() or 1)
+        t0 = time.perf_counter()
+        rec = st.apply_batch(ops, payload)
+        oracle.full_recompute(st, model)
+        oracle.affected_sets(st, rec, model)
+        dt = time.perf_counter() - t0
+    return dt, int(used)
+
+
+def cpu_baseline(cfg, bs, scale, full_size=False):
+    """The oracle as it stands, timed on this machine's host cores: one batch applied and everything
+    recomputed in fp64, once with the linear-algebra library on all the threads it takes and once on one.
+    Default: a bounded sample, a 1/scale copy of the workload (same recipe, N/scale vertices, E/scale edges,
+    bs/scale updates); recomputation is linear in N and E (Sec. 3.5's operation count with a_l = N), so the
+    full-size time per batch is the sample's times scale. full_size: the benchmark's own graph and batch
+    (minutes on the dense graph). The sparse aggregation product of the oracle runs on one thread either way."""
+    if full_size:
+        scale = 1
+    n, e = max(cfg.n // scale, 64), max(cfg.e // scale, 256)
+    top = cfg.top_share if scale == 1 else min(cfg.top_share * scale, 0.05)
     sample_bs = max(bs // scale, 1)
-    ops, payload, n_upd = stream.next_batch(sample_bs)
-    t0 = time.perf_counter()
-    rec = st.apply_batch(ops, payload)
-    hs = oracle.full_recompute(st, model)
-    oracle.affected_sets(st, rec, model)
-    dt = time.perf_counter() - t0
-    try:
-        from threadpoolctl import threadpool_info
-        cores = max([p.get("num_threads", 1) for p in threadpool_info()] + [1])
-    except Exception:
-        cores = os.cpu_count() or 1
-    est_full = dt * scale
-    return {"value": bs / est_full, "unit": "updates/s", "cores": int(cores), "kind": "oracle",
-            "sample": f"fp64 full recompute + affected sets for one batch on a 1/{scale}-scale graph of the same "
-                      f"recipe ({n} vertices, {e} edges, {sample_bs} updates): {dt:.2f} s, scaled x{scale} to the "
-                      f"full graph ({est_full:.1f} s per batch of {bs})",
-            "sample_seconds": dt}
+    dt_all, used = _oracle_batch_seconds(cfg, n, e, top, sample_bs, None)
+    dt_one, _ = _oracle_batch_seconds(cfg, n, e, top, sample_bs, 1) if not full_size else (None, 1)
+    est_full = dt_all * scale
+    what = (f"the benchmark's own graph and batch ({n} vertices, {e} edges, {sample_bs} updates): {dt_all:.1f} s"
+            if scale == 1 else
+            f"a 1/{scale}-scale graph of the same recipe ({n} vertices, {e} edges, {sample_bs} updates): {dt_all:.2f} s, "
+            f"scaled x{scale} to the full graph ({est_full:.1f} s per batch of {bs}); an estimate, not a timing of the "
+            f"full-size inputs (--cpu-baseline-full runs those)")
+    out = {"value": bs / est_full, "unit": "updates/s", "cores": used, "kind": "oracle",
+           "sample": "fp64 full recompute + affected sets for one batch on " + what,
+           "sample_seconds": dt_all, "scaled": scale != 1, "cpu_model": cpu_model(), "host_cores": os.cpu_count(),
+           "note": "the dense products use `cores` threads; the sparse aggregation product is single-threaded"}
+    if dt_one is not None:
+        out["value_single_thread"] = bs / (dt_one * scale)
+        out["sample_seconds_single_thread"] = dt_one
+    return out
 
 
 def main():
@@ -139,6 +180,10 @@ def main():
     ap.add_argument("--bs", type=int, default=0, help="updates per batch (default: the config's largest)")
     ap.add_argument("--cpu-scale", type=int, default=0, help="oracle sample is a 1/scale graph (0 = auto)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-baseline-full", action="store_true",
+                    help="time the oracle on the benchmark's own full-size graph and batch instead of the scaled sample (minutes)")
+    ap.add_argument("--no-host-inputs", action="store_true", help="skip the extra batches handed over as host buffers")
+    ap.add_argument("--no-peaks", action="store_true", help="skip measuring the chip's own copy / gather / atomic / matrix-core rates")
     ap.add_argument("--scatter-mode", type=int, default=0)
     ap.add_argument("--pull-ratio", type=int, default=0)
     ap.add_argument("--deterministic", action="store_true", help="bit-reproducible aggregation (RIPPLE_OPT_DETERMINISTIC)")
@@ -192,6 +237,8 @@ def main():
         ops_t = torch.from_numpy(ops.view(np.int32).copy()).cuda()
         pay_t = torch.from_numpy(payload).cuda() if len(payload) else None
         batches.append((ops_t, pay_t, len(ops), len(payload), n_upd))
+    # a few more batches that stay on the host: the same call with operations and feature rows as host buffers
+    host_batches = [] if args.no_host_inputs else [stream.next_batch(bs) for _ in range(min(args.steps, 10))]
     torch.cuda.synchronize()
     del stream
     log(f"[bench] {len(batches)} batches of {bs} updates staged in HBM in {time.time() - t0:.1f}s")
@@ -235,9 +282,14 @@ def main():
     total = time.perf_counter() - t_begin
     st = rp.ripple_get_stats(ctx, reset=False)
     rp.ripple_set_option(ctx, rp.OPT_TIMING, 0)
+    host_lat = []
+    for ops, payload, _ in host_batches:                # not part of `value`: PCIe-inclusive latency of the same call
+        t1 = time.perf_counter()
+        rp.ripple_apply_updates(ctx, ops, payload)
+        host_lat.append(time.perf_counter() - t1)
 
     L = len(model)
-    layer_info = {l: rp.ripple_get_layer_info(ctx, l) for l in range(1, L + 1)}
+    layer_info = {l: rp.ripple_get_layer_info(ctx, l) + (rp.ripple_layer_packs_messages(ctx, l),) for l in range(1, L + 1)}
     work = algorithmic_work(st, model, cfg.widths, cfg.store, L, layer_info, n_edges=res.n_edges)
     phase_idx = {"frontier": 2, "scatter": 3, "transform": 5}
     mfma_peak = MFMA_PEAK_TFLOPS["bf16" if (cfg.store == "bf16" and args.bf16_mfma) else "f32"]
@@ -252,6 +304,7 @@ def main():
         if ph == "scatter":
             ent["per_message_GBps"] = w["msg_bytes"] / (ms * 1e-3) / 1e9
             ent["per_message_hbm_frac"] = ent["per_message_GBps"] / HBM_PEAK_GBS
+            ent["message_lines_per_s"] = w["lines"] / (ms * 1e-3)       # 128-byte lines gathered for messages
         if ph == "transform":
             ent["TFLOPs"] = w["flops"] / (ms * 1e-3) / 1e12
             ent["mfma_frac"] = ent["TFLOPs"] / mfma_peak
@@ -281,13 +334,31 @@ def main():
     if roofline and dom in measured and args.scatter_mode == 0 and not args.deterministic and args.split_mfma <= 0:
         roofline["traffic"] = measured[dom]                 # bytes per launch; traffic / ms_per_launch is the HBM rate
         roofline["traffic_GBps"] = measured[dom] / (kernels[dom]["ms_per_launch"] * 1e-3) / 1e9
+        roofline["traffic_source"] = TRAFFIC_SOURCE + " (rocprofv3 counters of an earlier run of this command, not of this run)"
+    peaks = None
+    if not args.no_peaks:
+        peaks = rp.ripple_measure_peaks()
+        if roofline:                                        # the same achieved figure against what this chip delivers
+            if roofline["bound"] == "hbm":
+                roofline["achievable"] = {"peak": peaks["hbm_copy_gbps"], "unit": "GB/s", "what": "streaming copy measured on this GPU",
+                                          "frac": roofline["achieved"] / peaks["hbm_copy_gbps"]}
+                if dom.startswith("scatter") and "message_lines_per_s" in kernels[dom]:
+                    roofline["achievable"]["gather_lines_per_s"] = peaks["gather_glines"] * 1e9
+                    roofline["achievable"]["gather_frac"] = kernels[dom]["message_lines_per_s"] / (peaks["gather_glines"] * 1e9)
+            else:
+                key = "mfma_bf16_tflops" if mfma_peak > 1000 else "mfma_f32_tflops"
+                roofline["achievable"] = {"peak": peaks[key], "unit": "TFLOP/s", "what": "register-only matrix-core loop measured on this GPU",
+                                          "frac": roofline["achieved"] / peaks[key]}
     lat_ms = np.array(lat) * 1e3
     result = {
         "metric": "graph updates/sec (and p50 batch latency), 3-layer GraphSAGE-mean on a 2.45M-vertex/124M-edge graph"
         if cfg.name == "dense_sage_mean" else f"graph updates/sec, {cfg.name}",
         "value": n_updates / total, "unit": "updates/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": total / max(args.steps, 1) * 1e3, "p50_ms": float(np.percentile(lat_ms, 50)),
-        "p99_ms": float(np.percentile(lat_ms, 99)), "higher_is_better": True, "scaling": "weak",
+        "p99_ms": float(np.percentile(lat_ms, 99)),
+        **({"p50_ms_host_inputs": float(np.percentile(np.array(host_lat) * 1e3, 50)), "host_input_batches": len(host_lat)}
+           if host_lat else {}),
+        "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32" if cfg.store == "f32" else "bf16", "data": "synthetic",
         "config": {"workload": f"{cfg.name}: Chung-Lu gamma={cfg.gamma}, {cfg.n} vertices, {cfg.e} edges, "
                                f"widths {'->'.join(map(str, cfg.widths))}, {bs} updates/batch "
@@ -304,6 +375,7 @@ def main():
                                         for l in range(1, len(model) + 1)}} if mono.any() else {}),
         "kernels": kernels,
         "roofline": roofline,
+        **({"measured_peaks": peaks} if peaks else {}),
     }
     rp.ripple_destroy(ctx)
     del batches
@@ -311,7 +383,7 @@ def main():
     if not args.no_cpu_baseline:
         scale = args.cpu_scale or (16 if cfg.e > 10_000_000 else 1)
         t0 = time.time()
-        result["cpu_baseline"] = cpu_baseline(cfg, bs, scale)
+        result["cpu_baseline"] = cpu_baseline(cfg, bs, scale, full_size=args.cpu_baseline_full)
         log(f"[bench] CPU oracle sample took {time.time() - t0:.1f}s")
     print(json.dumps(result), flush=True)
 

@@ -294,6 +294,21 @@ ripple_status ripple_get_stats(ripple_ctx *ctx, ripple_stats *out, int reset);
 ripple_status ripple_plan_batch(const ripple_update *ops, uint32_t n_ops, uint32_t vertex_capacity,
                                 uint32_t n_feat_rows, uint32_t *piece_end, uint32_t cap, uint32_t *n_pieces);
 
+/* What this GPU reaches on the operations the kernels above are bound by (the cost model of Sec. 3.5 counts
+ * messages and rows; these are the chip's prices for them), measured with plain kernels of known size on the
+ * current device: no context needed. Takes about 50 ms and 2 GiB of device memory, which it frees again. */
+typedef struct {
+    double hbm_copy_gbps;      /* streaming copy of 1 GiB: bytes read + written per second, in 1e9 bytes/s             */
+    double hbm_read_gbps;      /* streaming read of 1 GiB, in 1e9 bytes/s                                              */
+    double gather_glines;      /* gathers of random 128-byte lines from a 512 MiB table, in 1e9 lines/s                */
+    double atomic_gops;        /* float atomic additions to rows of 47 numbers in ascending order, in 1e9 additions/s  */
+    double mfma_f32_tflops;    /* register-only loop of 32x32x2 fp32 matrix-core instructions, in 1e12 flop/s          */
+    double mfma_bf16_tflops;   /* the same with 32x32x16 bf16 instructions                                             */
+    uint32_t compute_units;
+    uint32_t reserved;
+} ripple_peaks;
+ripple_status ripple_measure_peaks(ripple_peaks *out, void *hip_stream);
+
 void ripple_destroy(ripple_ctx *ctx);
 const char *ripple_last_error(const ripple_ctx *ctx);   /* never NULL; "" when ctx is NULL */
 

@@ -36,7 +36,7 @@ EXPORTS = ["ripple_init_graph", "ripple_init_graph_weighted", "ripple_load_model
            "ripple_get_embeddings", "ripple_get_aggregates", "ripple_get_layer_info", "ripple_get_affected", "ripple_get_affected_static",
            "ripple_export_edges",
            "ripple_get_degrees", "ripple_compact", "ripple_set_option", "ripple_get_stats", "ripple_plan_batch",
-           "ripple_destroy", "ripple_last_error"]
+           "ripple_measure_peaks", "ripple_destroy", "ripple_last_error"]
 
 
 class RippleError(RuntimeError):
@@ -76,6 +76,12 @@ class Stats(C.Structure):
                 ("touched", C.c_uint64 * (RIPPLE_MAX_LAYERS + 1))]
 
 
+class Peaks(C.Structure):
+    _fields_ = [("hbm_copy_gbps", C.c_double), ("hbm_read_gbps", C.c_double), ("gather_glines", C.c_double), ("atomic_gops", C.c_double),
+                ("mfma_f32_tflops", C.c_double), ("mfma_bf16_tflops", C.c_double),
+                ("compute_units", C.c_uint32), ("reserved", C.c_uint32)]
+
+
 _lib = None
 
 
@@ -112,6 +118,7 @@ def load_library():
     lib.ripple_set_option.argtypes = [vp, C.c_int, C.c_int64]
     lib.ripple_get_stats.argtypes = [vp, C.POINTER(Stats), C.c_int]
     lib.ripple_plan_batch.argtypes = [vp, u32, u32, u32, vp, u32, C.POINTER(u32)]
+    lib.ripple_measure_peaks.argtypes = [C.POINTER(Peaks), vp]
     lib.ripple_destroy.argtypes = [vp]
     lib.ripple_destroy.restype = None
     lib.ripple_last_error.argtypes = [vp]
@@ -325,6 +332,15 @@ def ripple_plan_batch(ops, vertex_capacity, n_feat_rows):
     if rc != RIPPLE_OK:
         raise RippleError(rc, "ripple_plan_batch")
     return ends[: n.value].tolist()
+
+
+def ripple_measure_peaks(stream=None):
+    """Measured rates of the current GPU as a dict (see ripple_peaks in include/ripple.h)."""
+    p = Peaks()
+    rc = load_library().ripple_measure_peaks(C.byref(p), C.c_void_p(int(stream)) if stream else None)
+    if rc != RIPPLE_OK:
+        raise RippleError(rc, "ripple_measure_peaks")
+    return {name: getattr(p, name) for name, _ in Peaks._fields_ if name != "reserved"}
 
 
 def ripple_destroy(ctx):

@@ -268,7 +268,7 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
         LayerDev &ly = c->layers[l];
         void *w[] = {ly.W0, ly.b0, ly.W1, ly.b1, ly.W0h, ly.W1h, ly.bzero, (ly.Wn != ly.W0) ? ly.Wn : nullptr, ly.PS,
                      ly.W0s, ly.W1s, (ly.Wns != ly.W0s) ? ly.Wns : nullptr,
-                     ly.att, ly.P, ly.ssrc, ly.sdst, ly.den, ly.T};
+                     ly.att, ly.P, ly.ssrc, ly.sdst, ly.den, ly.T, ly.Wc, ly.bzero_c};
         for (void *p : w)
             if (p) hipFree(p);
     }
@@ -400,6 +400,18 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
                 RP_TRY(dev_alloc(c, &ly.bzero, (size_t)ly.N0pad, true));
             }
         }
+        if (ly.proj && ly.selfc && s.d_out <= 64 && s.d_in % 4 == 0 && !split) {
+            const uint32_t kp = rp_round_up(s.d_in, 32);
+            std::vector<float> wc((size_t)kp * 128, 0.0f);
+            for (uint32_t k = 0; k < s.d_in; ++k)
+                for (uint32_t j = 0; j < s.d_out; ++j) {
+                    wc[(size_t)k * 128 + j] = s.W0[(size_t)k * s.d_out + j];                       // W_self
+                    wc[(size_t)k * 128 + 64 + j] = s.W0[(size_t)(s.d_in + k) * s.d_out + j];       // W_neigh
+                }
+            RP_TRY(dev_alloc(c, &ly.Wc, wc.size(), false));
+            RP_HIP(c, hipMemcpy(ly.Wc, wc.data(), wc.size() * 4, hipMemcpyHostToDevice));
+            RP_TRY(dev_alloc(c, &ly.bzero_c, (size_t)128, true));
+        }
         if (s.d_hidden) {
             ly.K1pad = rp_round_up(s.d_hidden, 32);
             ly.N1pad = pad_n(s.d_out);
@@ -509,8 +521,12 @@ extern "C" ripple_status ripple_full_infer(ripple_ctx *c) {
             rp_launch_transform(c, l, c->all_list, &c->ctr->a[0], false);
             continue;
         }
-        if (c->layers[l - 1].proj) rp_launch_project(c, l, c->all_list, &c->ctr->a[0], true);
-        if (c->layers[l - 1].selfc) rp_launch_self_project(c, l, c->all_list, &c->ctr->a[0]);
+        if (rp_has_project_both(c, l)) {
+            rp_launch_project_both(c, l, c->all_list, &c->ctr->a[0], true);
+        } else {
+            if (c->layers[l - 1].proj) rp_launch_project(c, l, c->all_list, &c->ctr->a[0], true);
+            if (c->layers[l - 1].selfc) rp_launch_self_project(c, l, c->all_list, &c->ctr->a[0]);
+        }
         if (c->opt_deterministic) rp_launch_scatter_owner(c, l, true);     // same summation order as the batches use
         else rp_launch_pull_all(c, l);
         rp_launch_transform(c, l, c->all_list, &c->ctr->a[0], false);
@@ -834,13 +850,15 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
         if (sparse) rp_launch_frontier_sparse(c, l, layer_self(c, l), l < c->L);
         else rp_launch_frontier_mark(c, l, may_disc);
         rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
+        const bool both = rp_has_project_both(c, l);
         if (c->layers[l - 1].proj) {                   // what travels is already multiplied by W_neigh
             t = rp_timer_begin(c);
-            rp_launch_project(c, l, c->list[l - 1], &c->ctr->a[l - 1], false);
+            if (both) rp_launch_project_both(c, l, c->list[l - 1], &c->ctr->a[l - 1], false);   // and the self terms in the same pass
+            else rp_launch_project(c, l, c->list[l - 1], &c->ctr->a[l - 1], false);
             rp_launch_messages(c, l);
             rp_timer_end(c, t, RIPPLE_PH_OTHER, (int)l);
         }
-        if (c->layers[l - 1].selfc) {                  // H^{l-1} changed exactly on A_{l-1}
+        if (c->layers[l - 1].selfc && !both) {         // H^{l-1} changed exactly on A_{l-1}
             t = rp_timer_begin(c);
             rp_launch_self_project(c, l, c->list[l - 1], &c->ctr->a[l - 1]);
             rp_timer_end(c, t, RIPPLE_PH_OTHER, (int)l, !c->layers[l - 1].proj);

@@ -82,6 +82,9 @@ struct LayerDev {
     // refreshed only where H^{l-1} changed, so the row transform multiplies the aggregate alone
     uint32_t selfc;
     float *PS;
+    // project-first layers with a cached self term: [W_self | W_neigh] as one matrix [roundup(d_in,32) x 128] (W_neigh
+    // from column 64 on) and 128 zeros, so that one pass over the rows of A_{l-1} yields both products; else null
+    float *Wc, *bzero_c;
     // attention layers: projected rows P[v] = H^{l-1}[v] W0 [n x d_out], scores a_src . P[v] and a_dst . P[v],
     // denominators of the softmax (the numerators are the layer's X rows); att = a_src then a_dst on the device
     float *att, *P, *ssrc, *sdst, *den;

@@ -45,6 +45,8 @@ void rp_launch_gat_project(ripple_ctx *c, uint32_t l, const uint32_t *list, cons
 void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool emit_delta);
 void rp_launch_self_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d);
 void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool bootstrap);
+bool rp_has_project_both(const ripple_ctx *c, uint32_t l);
+void rp_launch_project_both(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool bootstrap);
 
 // api.hip: HIP-event timing of kernel classes (no-ops unless RIPPLE_OPT_TIMING is on)
 int rp_timer_begin(ripple_ctx *c);

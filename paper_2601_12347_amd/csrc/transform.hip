@@ -55,6 +55,12 @@ struct TArgs {
     const float *den;              // attention layers (k_transform_addend_only): the addend is divided by den[vertex], or null
     float *tmp_out;
     uint32_t tmp_out_ld;
+    // two products from one pass over the rows (out_mode 2 only): the weight matrix holds a second block of
+    // columns from split_col on (a multiple of 64); columns [0, N1) go to tmp_out, columns [split_col, N) to
+    // tmp_out2 as its columns 0 .. N - split_col - 1. split_col = 0: one block, N1 = N.
+    uint32_t split_col, N1;
+    float *tmp_out2;
+    uint32_t tmp_out2_ld;
     void *Hout;
     float *D;                      // delta rows [vertex x N] or null
     int d_old;                     // D receives the row's old value instead of new - old (the next layer takes max / min)
@@ -257,7 +263,8 @@ struct EpiRound {
             const int idx = tid + (it0 + u) * 256;
             const int r = idx / (BN / 4), c4 = (idx % (BN / 4)) * 4;
             const uint32_t col = n0 + c4;
-            nv[u] = (row0 + r < count && col < a.N) ? min(4u, a.N - col) : 0u;
+            const uint32_t lim = (a.split_col && col < a.split_col) ? a.N1 : a.N;   // end of the block of columns `col` lies in
+            nv[u] = (row0 + r < count && col < lim) ? min(4u, lim - col) : 0u;
             old[u] = (floatx4)(0.0f);
             add[u] = (floatx4)(0.0f);
             if (EPI == 0) continue;
@@ -297,7 +304,8 @@ struct EpiRound {
             }
             if (EPI == 0) {
                 const size_t orow = (a.out_mode == 0) ? slot : s_vtx[r];
-                st4(a.tmp_out + orow * a.tmp_out_ld + col, v, VEC, nv[u]);
+                if (a.split_col && col >= a.split_col) st4(a.tmp_out2 + orow * a.tmp_out2_ld + (col - a.split_col), v, VEC, nv[u]);
+                else st4(a.tmp_out + orow * a.tmp_out_ld + col, v, VEC, nv[u]);
                 continue;
             }
             const size_t hidx = (size_t)s_vtx[r] * a.N + col;
@@ -363,7 +371,8 @@ __device__ __forceinline__ void epilogue_staged(const TArgs &a, floatx16 (&acc)[
     constexpr int ITER = BM * BN / 4 / 256, U = (ITER >= 8) ? 4 : ITER / 2;
     static_assert(U >= 1 && ITER % (2 * U) == 0, "tile size");
     const int lane = tid & 63;
-    const bool vec = (a.N & 3u) == 0 && (a.out_mode == 1 || (a.tmp_out_ld & 3u) == 0);
+    const bool vec = (a.N & 3u) == 0 && (a.out_mode == 1 || (a.tmp_out_ld & 3u) == 0) &&
+                     (a.split_col == 0 || ((a.N1 & 3u) == 0 && (a.tmp_out2_ld & 3u) == 0));
     __syncthreads();                                       // every wavefront is done with the A/B slices
 #pragma unroll
     for (int sm = 0; sm < TM; ++sm)
@@ -1125,6 +1134,10 @@ static TArgs base_args(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
     a.d_old = 0;
     a.tmp_out = nullptr;
     a.tmp_out_ld = 0;
+    a.split_col = 0;
+    a.N1 = ly.d_out;
+    a.tmp_out2 = nullptr;
+    a.tmp_out2_ld = 0;
     a.addend = nullptr;
     a.addend_scaled = 1;
     a.addend2 = nullptr;
@@ -1167,6 +1180,36 @@ void rp_launch_project(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
     a.out_mode = 2;
     a.a_mode = 4;
     launch_t(c, a, ly.d_in % 4 == 0, bootstrap ? c->n_cap : rp_rows_hint(c, l - 1));
+}
+
+// Layers handled project-first that also cache their self term: both products of H^{l-1}[v], with W_self (into PS)
+// and with W_neigh (into T at the bootstrap, else into c->PD), from one pass over the rows, against the
+// layer's combined weight matrix [W_self | W_neigh] (second block from column 64 on).
+bool rp_has_project_both(const ripple_ctx *c, uint32_t l) { return c->layers[l - 1].Wc != nullptr; }
+
+void rp_launch_project_both(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, bool bootstrap) {
+    const LayerDev &ly = c->layers[l - 1];
+    TArgs a = base_args(c, l, list, count_d);
+    a.mean = 0;
+    a.W = ly.Wc;
+    a.Wt = nullptr;
+    a.Ws = nullptr;
+    a.bias = ly.bzero_c;
+    a.K = ly.d_in;
+    a.Kpad = rp_round_up(ly.d_in, 32);
+    a.N = 64 + ly.d_out;
+    a.Npad = 128;
+    a.act = RIPPLE_ACT_NONE;
+    a.a_mode = 4;
+    a.out_mode = 2;
+    a.Hout = nullptr;
+    a.tmp_out = ly.PS;
+    a.tmp_out_ld = ly.d_out;
+    a.split_col = 64;
+    a.N1 = ly.d_out;
+    a.tmp_out2 = bootstrap ? ly.T : c->PD;
+    a.tmp_out2_ld = bootstrap ? ly.d_out : c->pd_ld;
+    launch_t(c, a, true, bootstrap ? c->n_cap : rp_rows_hint(c, l - 1));
 }
 
 // Attention layer l: P[v] = H^{l-1}[v] W0 for the listed vertices (fp32, no bias, no activation).

@@ -34,6 +34,7 @@ def test_struct_layouts_match_the_header():
     assert C.sizeof(rp.binding.LayerDesc) == 72
     assert C.sizeof(rp.BatchResult) == 4 * 6 + 8 + 4 * 9 + 4 + 8 * 9 + 4 + 3 * 4 * 9 + 4 * 9 + 4   # the last two: hop_mode, n_ops_done
     assert C.sizeof(rp.Stats) == 8 + 8 * 8 * 9 * 2 + 8 * 9 * 3
+    assert C.sizeof(rp.binding.Peaks) == 6 * 8 + 2 * 4
 
 
 def test_null_and_bad_arguments_return_statuses():
@@ -50,5 +51,6 @@ def test_null_and_bad_arguments_return_statuses():
     assert lib.ripple_load_model(None, 1, None) == rp.binding.RIPPLE_EINVAL
     assert lib.ripple_apply_updates(None, None, 0, None, 0, None) == rp.binding.RIPPLE_EINVAL
     assert lib.ripple_get_embeddings(None, 0, None, 0, None) == rp.binding.RIPPLE_EINVAL
+    assert lib.ripple_measure_peaks(None, None) == rp.binding.RIPPLE_EINVAL
     assert lib.ripple_last_error(None) == b""
     lib.ripple_destroy(None)

@@ -110,3 +110,17 @@ def test_call_order_and_argument_errors():
         assert not out[1].any()                                   # id 7 was never created
     finally:
         rp.ripple_destroy(ctx)
+
+
+def test_measured_peaks_are_plausible():
+    """The chip's own rates (streaming copy, random line gathers, float atomics, matrix-core loops) that bench.py
+    prints beside the nominal peaks: each must lie between a loose floor and the published figure."""
+    p = rp.ripple_measure_peaks()
+    print("measured peaks", {k: round(v, 1) for k, v in p.items()}, flush=True)
+    assert 2000.0 < p["hbm_copy_gbps"] < 8000.0
+    assert 2000.0 < p["hbm_read_gbps"] < 8000.0
+    assert 10.0 < p["gather_glines"] < 62.5                  # 62.5e9 lines of 128 bytes per second would be 8 TB/s
+    assert 50.0 < p["atomic_gops"] < 2000.0
+    assert 60.0 < p["mfma_f32_tflops"] < 157.3 * 1.02
+    assert 800.0 < p["mfma_bf16_tflops"] < 2500.0 * 1.02
+    assert p["compute_units"] >= 64
