@@ -41,7 +41,9 @@ typedef enum {
     RIPPLE_ESTATE = 2,      /* call order violated */
     RIPPLE_ECAPACITY = 3,   /* vertex/edge capacity exceeded; the piece of the batch that hit it changed nothing */
     RIPPLE_ENOMEM = 4,      /* device or host allocation failed */
-    RIPPLE_EDEVICE = 5      /* a HIP call failed */
+    RIPPLE_EDEVICE = 5,     /* a HIP call failed */
+    RIPPLE_ERANGE = 6       /* an attention layer's exponentials left the float range (scores above about 88): the call did
+                               its work, but the rows ripple_last_error counts hold non-finite values */
 } ripple_status;
 
 /* The five update types of Sec. 3.1. */
@@ -92,7 +94,9 @@ typedef enum { RIPPLE_STORE_F32 = 0, RIPPLE_STORE_BF16 = 1 } ripple_store;
  * is maintained with the hybrid scheme of Sec. 3.4.1: a vertex already in the previous hop's set, or
  * with a changed in-edge, recomputes numerator and denominator from all its in-neighbours, any
  * other receives numerator / denominator differences. Exponentials are taken without subtracting a
- * maximum (the incremental form needs a fixed reference), so scores must stay below about 80. */
+ * maximum (the incremental form needs a fixed reference), so scores must stay below about 80; a row whose
+ * sums overflow all the same is detected when it is updated, and ripple_full_infer / ripple_apply_updates
+ * then return RIPPLE_ERANGE. */
 typedef struct {
     uint32_t d_in, d_hidden, d_out;
     uint32_t agg;          /* ripple_agg  */

@@ -16,9 +16,9 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libripple.so")
 
-RIPPLE_OK, RIPPLE_EINVAL, RIPPLE_ESTATE, RIPPLE_ECAPACITY, RIPPLE_ENOMEM, RIPPLE_EDEVICE = range(6)
+RIPPLE_OK, RIPPLE_EINVAL, RIPPLE_ESTATE, RIPPLE_ECAPACITY, RIPPLE_ENOMEM, RIPPLE_EDEVICE, RIPPLE_ERANGE = range(7)
 STATUS_NAMES = ["RIPPLE_OK", "RIPPLE_EINVAL", "RIPPLE_ESTATE", "RIPPLE_ECAPACITY", "RIPPLE_ENOMEM",
-                "RIPPLE_EDEVICE"]
+                "RIPPLE_EDEVICE", "RIPPLE_ERANGE"]
 RIPPLE_MAX_LAYERS = 8
 RIPPLE_N_PHASES = 8
 PHASES = ["ingest", "struct", "frontier", "scatter", "compact", "transform", "other", "total"]
@@ -41,7 +41,7 @@ EXPORTS = ["ripple_init_graph", "ripple_init_graph_weighted", "ripple_load_model
 
 class RippleError(RuntimeError):
     def __init__(self, status: int, text: str):
-        super().__init__(f"{STATUS_NAMES[status] if 0 <= status < 6 else status}: {text}")
+        super().__init__(f"{STATUS_NAMES[status] if 0 <= status < len(STATUS_NAMES) else status}: {text}")
         self.status = status
 
 

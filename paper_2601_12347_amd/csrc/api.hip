@@ -503,6 +503,12 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
     return RIPPLE_OK;
 }
 
+static ripple_status range_error(ripple_ctx *c, uint32_t rows) {
+    c->err = "attention exponentials overflowed the float range: " + std::to_string(rows) +
+             " row updates used sums that were not finite (scores must stay below about 88)";
+    return RIPPLE_ERANGE;
+}
+
 // ---------------------------------------------------------------------------------
 // bootstrap inference
 // ---------------------------------------------------------------------------------
@@ -531,14 +537,17 @@ extern "C" ripple_status ripple_full_infer(ripple_ctx *c) {
         else rp_launch_pull_all(c, l);
         rp_launch_transform(c, l, c->all_list, &c->ctr->a[0], false);
     }
+    RP_HIP(c, hipMemcpyAsync(c->ctr_host, c->ctr, sizeof(DevCtr), hipMemcpyDeviceToHost, c->stream));
     rp_launch_batch_reset(c);
     RP_HIP(c, hipStreamSynchronize(c->stream));
     RP_HIP(c, hipGetLastError());
+    const uint32_t range_rows = c->ctr_host->range_rows;
     for (uint32_t l = 0; l <= c->L; ++l) c->last_a[l] = 0;
     c->hints_valid = false;
     c->last_n_ops = 0;
     c->last_from_rep = false;
     c->state = 3;
+    if (range_rows) return range_error(c, range_rows);
     return RIPPLE_OK;
 }
 
@@ -969,7 +978,7 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
     }
 
     ripple_status rc = RIPPLE_OK;
-    uint32_t applied = 0, rejected = 0, n_struct = 0, compactions = 0, ops_done = 0;
+    uint32_t applied = 0, rejected = 0, n_struct = 0, compactions = 0, ops_done = 0, range_rows = 0;
     uint64_t msgs[RIPPLE_MAX_LAYERS + 1] = {0}, tchd[RIPPLE_MAX_LAYERS + 1] = {0};
     uint32_t mono[3][RIPPLE_MAX_LAYERS + 1] = {{0}};
     uint32_t hop_mode[RIPPLE_MAX_LAYERS + 1] = {0};
@@ -983,6 +992,7 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
         applied += h.n_applied;
         rejected += h.n_rejected;
         n_struct += h.n_struct;
+        range_rows += h.range_rows;
         for (uint32_t l = 1; l <= c->L; ++l) {
             msgs[l] += h.m[l];
             tchd[l] += h.touched[l];
@@ -1071,6 +1081,7 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
             res->hop_mode[l] = hop_mode[l];
         }
     }
+    if (range_rows) return range_error(c, range_rows);      // the batch is applied; res describes it
     return RIPPLE_OK;
 }
 

@@ -46,6 +46,7 @@ struct DevCtr {                      // device-resident counters, one instance p
     uint32_t n_seg[RIPPLE_MAX_LAYERS + 1];    // segments queued for them
     uint32_t mono[3][RIPPLE_MAX_LAYERS + 1];  // max / min hops: candidates left unchanged / raised from the messages / recomputed
     uint32_t hop_mode[RIPPLE_MAX_LAYERS + 1]; // 1 + RP_HOP_* of the scatter kernel that moved hop l's messages (0: none ran)
+    uint32_t range_rows;                      // attention layers: rows updated from sums that were not finite
     unsigned long long n_edges;
     uint32_t blocks_done;                     // workgroups of k_capacity that have finished (0 between launches)
     uint32_t pad2;

@@ -888,6 +888,7 @@ __global__ void k_batch_reset(DevCtr *ctr, uint32_t *bitmaps, size_t n_bitmap_wo
         ctr->need_out = ctr->need_in = 0;
         ctr->n_vadd = 0;
         ctr->abort_flag = 0;
+        ctr->range_rows = 0;
         for (int k = 0; k < 3; ++k)
             for (int l = 0; l <= RIPPLE_MAX_LAYERS; ++l) ctr->mono[k][l] = 0;
     }

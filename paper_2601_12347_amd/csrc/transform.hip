@@ -53,6 +53,7 @@ struct TArgs {
     int addend_scaled;             // 1: the addend is an aggregate and takes the mean scale
     const float *addend2;          // second, unscaled addend (k_transform_addend_only), or null
     const float *den;              // attention layers (k_transform_addend_only): the addend is divided by den[vertex], or null
+    uint32_t *range_rows;          // with den: += rows whose numerator or denominator was not finite
     float *tmp_out;
     uint32_t tmp_out_ld;
     // two products from one pass over the rows (out_mode 2 only): the weight matrix holds a second block of
@@ -405,10 +406,14 @@ __device__ __forceinline__ void addend_only_rows(const TArgs &a) {
             const uint32_t deg = a.in_meta[v[u]].y;        // read in any case: no branch between the loads
             sc[u] = a.mean ? 1.0f / (float)(deg > 1u ? deg : 1u) : 1.0f;
         }
+        bool bad[R];
+#pragma unroll
+        for (int u = 0; u < R; ++u) bad[u] = false;
         if (a.den) {                                       // attention: numerator / denominator, 0 without in-neighbours
 #pragma unroll
             for (int u = 0; u < R; ++u) {
                 const float dn = a.den[v[u]];
+                bad[u] = !isfinite(dn) && s0 + u < count;
                 sc[u] = (a.in_meta[v[u]].y > 0u && dn > 0.0f) ? 1.0f / dn : 0.0f;
             }
         }
@@ -429,6 +434,7 @@ __device__ __forceinline__ void addend_only_rows(const TArgs &a) {
                 if (s0 + u >= count) continue;
                 const size_t hidx = (size_t)v[u] * a.N + col;
                 float z = y[u] * sc[u] + b + (w2 != 0.0f ? p[u] : 0.0f);
+                if (a.den && !isfinite(z)) bad[u] = true;      // an overflowed exponential: inf / inf, or inf itself
                 if (a.act == RIPPLE_ACT_RELU) z = z > 0.0f ? z : 0.0f;
                 if (BF) {
                     const __hip_bfloat16 zr = __float2bfloat16(z);
@@ -439,6 +445,12 @@ __device__ __forceinline__ void addend_only_rows(const TArgs &a) {
                 }
                 if (a.D) a.D[hidx] = a.d_old ? old[u] : z - old[u];
             }
+        }
+        if (a.den) {
+            uint32_t n_bad = 0;
+#pragma unroll
+            for (int u = 0; u < R; ++u) n_bad += __ballot(bad[u]) != 0ull ? 1u : 0u;
+            if (n_bad && lane == 0) atomicAdd(a.range_rows, n_bad);
         }
     }
 }
@@ -1142,6 +1154,7 @@ static TArgs base_args(ripple_ctx *c, uint32_t l, const uint32_t *list, const ui
     a.addend_scaled = 1;
     a.addend2 = nullptr;
     a.den = nullptr;
+    a.range_rows = &c->ctr->range_rows;
     a.a_mode = 0;
     a.out_mode = 1;
     a.act = 0;

@@ -355,6 +355,43 @@ def test_capacity_error_in_a_later_piece_leaves_the_earlier_pieces_applied():
         pair.close()
 
 
+def test_attention_scores_beyond_the_float_range_are_reported():
+    """Raw exponentials (no maximum subtracted) overflow for scores above about 88. The oracle (fp64) stays finite;
+    the library must say so instead of handing out non-finite rows as if nothing had happened: scores around 60
+    still match the oracle, scores above 90 make full inference and the next batch return RIPPLE_ERANGE."""
+    print("case attention range", flush=True)
+    n, e, d0, widths = 300, 1800, 8, (8, 12, 6)
+    src, dst, out_law, in_law = ri.chung_lu_graph(n, e, 2.1, 0.03, 151)
+    feats = ri.features(n, d0, 152)
+    for scale, expect_error in ((11.0, False), (40.0, True)):
+        model = ri.make_model("gat", widths, 153)
+        for lay in model:                                   # scores grow with the attention vectors
+            lay["att"] = (np.asarray(lay["att"]) * scale).astype(np.float32)
+        ora = oracle.GraphState(n, n + 16, src, dst, feats)
+        want = oracle.full_recompute(ora, model)
+        assert all(np.isfinite(w).all() for w in want)
+        ctx = rp.ripple_init_graph(n, n + 16, src, dst, feats)
+        try:
+            rp.ripple_load_model(ctx, model)
+            if not expect_error:
+                rp.ripple_full_infer(ctx)
+                got = rp.ripple_get_embeddings(ctx, 2, widths[2], n_rows=n + 16)
+                assert oracle.max_rel_err(got, want[2], ora.alive) <= 1e-4
+                continue
+            with pytest.raises(rp.RippleError) as ei:
+                rp.ripple_full_infer(ctx)
+            assert ei.value.status == rp.binding.RIPPLE_ERANGE and "overflow" in str(ei.value)
+            # the context stays usable, and a batch that touches such rows reports the same
+            ops = np.array([(ri.OP_FEAT_UPDATE, v, 0, i) for i, v in enumerate(range(0, 40))], dtype=np.uint32)
+            payload = ri.features(40, d0, 154)
+            with pytest.raises(rp.RippleError) as ei:
+                rp.ripple_apply_updates(ctx, ops, payload)
+            assert ei.value.status == rp.binding.RIPPLE_ERANGE
+            assert ei.value.result.n_applied == 40          # the batch was applied all the same
+        finally:
+            rp.ripple_destroy(ctx)
+
+
 def test_bf16_store_updates():
     print("case bf16 updates", flush=True)
     pair, graph = make_pair(n=600, e=4000, d0=16, kind="gcn_sum", widths=(16, 64, 24), store="bf16", seed=37)
