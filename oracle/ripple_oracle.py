@@ -38,7 +38,11 @@ Readings taken where the paper leaves a choice:
     own embedding to its in-neighbours');
   * operations of a batch are applied in array order; invalid ones (dead or
     out-of-range endpoint, duplicate edge, missing edge, adding a live vertex,
-    deleting or updating a dead one) are rejected and skipped;
+    deleting or updating a dead one, a new weight for a missing edge or on a graph
+    without weights) are rejected and skipped;
+  * besides the paper's five update types there is a sixth, the replacement of an edge's weight
+    alpha_uv on weighted graphs (the paper keeps weights fixed; with Table 1's weighted sum a new
+    weight changes the sink's aggregate like any other change of the message alpha_uv h_u);
   * a deleted vertex loses all incident edges (Sec. 3.2) and its rows are zero;
   * affected sets are topological: a vertex is affected whether or not its
     value ends up different (Sec. 3.3.1: every vertex of the tree is updated).
@@ -59,7 +63,7 @@ import dataclasses
 import numpy as np
 import scipy.sparse as sp
 
-EDGE_ADD, EDGE_DEL, VERTEX_ADD, VERTEX_DEL, FEAT_UPDATE = 0, 1, 2, 3, 4
+EDGE_ADD, EDGE_DEL, VERTEX_ADD, VERTEX_DEL, FEAT_UPDATE, EDGE_REWEIGHT = 0, 1, 2, 3, 4, 5
 
 
 # --------------------------------------------------------------------------
@@ -199,6 +203,17 @@ class GraphState:
                     self._erase(u, v)
                 else:
                     continue
+                rec.sinks.add(v)
+            elif kind == EDGE_REWEIGHT:
+                # the weight alpha_uv of an existing edge of a weighted graph is replaced (Sec. 3.3.3, "Other linear
+                # aggregators": the message along u -> v is alpha_uv times the embedding, so a new alpha changes
+                # what v aggregates exactly as a changed embedding of u would); v is touched at every hop like the
+                # sink of an added or deleted edge
+                if not (0 <= u < self.cap and 0 <= v < self.cap) or not (self.alive[u] and self.alive[v]):
+                    continue
+                if not self.weighted or not self.has_edge(u, v):
+                    continue
+                self.w_late[u * self.cap + v] = float(np.array([row], dtype=np.uint32).view(np.float32)[0])
                 rec.sinks.add(v)
             elif kind == VERTEX_ADD:
                 if not (0 <= u < self.cap) or self.alive[u] or not (0 <= row < len(payload)):

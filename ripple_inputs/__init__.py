@@ -13,7 +13,7 @@ LinkBench-derived mix (Sec. 6.1.2), which is not available.
 """
 from .graphs import (PowerLaw, degree_laws, chung_lu_graph, features, edge_weights, CONFIGS, get_config,
                      OP_EDGE_ADD, OP_EDGE_DEL, OP_VERTEX_ADD, OP_VERTEX_DEL,
-                     OP_FEAT_UPDATE)
+                     OP_FEAT_UPDATE, OP_EDGE_REWEIGHT)
 from .models import make_model, glorot
 from .updates import UpdateStream
 from .producer import BatchProducer
@@ -21,4 +21,4 @@ from .producer import BatchProducer
 __all__ = ["PowerLaw", "degree_laws", "chung_lu_graph", "BatchProducer", "features", "edge_weights", "CONFIGS", "get_config",
            "make_model", "glorot", "UpdateStream",
            "OP_EDGE_ADD", "OP_EDGE_DEL", "OP_VERTEX_ADD", "OP_VERTEX_DEL",
-           "OP_FEAT_UPDATE"]
+           "OP_FEAT_UPDATE", "OP_EDGE_REWEIGHT"]

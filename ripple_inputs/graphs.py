@@ -14,7 +14,7 @@ from __future__ import annotations
 import dataclasses
 import numpy as np
 
-OP_EDGE_ADD, OP_EDGE_DEL, OP_VERTEX_ADD, OP_VERTEX_DEL, OP_FEAT_UPDATE = 0, 1, 2, 3, 4
+OP_EDGE_ADD, OP_EDGE_DEL, OP_VERTEX_ADD, OP_VERTEX_DEL, OP_FEAT_UPDATE, OP_EDGE_REWEIGHT = 0, 1, 2, 3, 4, 5
 
 
 class PowerLaw:

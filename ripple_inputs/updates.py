@@ -11,14 +11,15 @@ feature replacement, one vertex delete, or one vertex add together with its
 Operation record: uint32 [kind, u, v, feat_row]; edges are (u -> v); vertex
 operations use u; feat_row indexes the batch's payload for VERTEX_ADD and
 FEAT_UPDATE and is 0 otherwise, except that a weighted stream puts the float32
-bits of the new edge's weight (uniform in [0.25, 1.75)) there for EDGE_ADD.
+bits of the new edge's weight (uniform in [0.25, 1.75)) there for EDGE_ADD and of
+the replacement weight for EDGE_REWEIGHT (mix key "reweight", weighted streams only).
 """
 from __future__ import annotations
 
 import numpy as np
 
 from .graphs import (OP_EDGE_ADD, OP_EDGE_DEL, OP_VERTEX_ADD, OP_VERTEX_DEL,
-                     OP_FEAT_UPDATE, PowerLaw, draw_pair)
+                     OP_FEAT_UPDATE, OP_EDGE_REWEIGHT, PowerLaw, draw_pair)
 
 
 class UpdateStream:
@@ -143,7 +144,7 @@ class UpdateStream:
     def counts(self, bs: int) -> dict:
         """Updates of each kind in a batch of `bs`: the mix times bs when that
         is integral for every kind, otherwise a multinomial draw from the mix."""
-        names = ("edge_add", "edge_del", "feat", "vadd", "vdel")
+        names = ("edge_add", "edge_del", "feat", "vadd", "vdel", "reweight")
         exact = [self.mix.get(k, 0.0) * bs for k in names]
         if all(abs(x - round(x)) < 1e-6 for x in exact):
             return {k: int(round(x)) for k, x in zip(names, exact)}
@@ -161,7 +162,7 @@ class UpdateStream:
         if kinds is None:
             c = self.counts(bs)
             kinds = (["vdel"] * c["vdel"] + ["vadd"] * c["vadd"] + ["feat"] * c["feat"] +
-                     ["edge_del"] * c["edge_del"] + ["edge_add"] * c["edge_add"])
+                     ["edge_del"] * c["edge_del"] + ["edge_add"] * c["edge_add"] + ["reweight"] * c["reweight"])
         kinds = sorted(kinds, key=lambda k: {"vdel": 0, "vadd": 1}.get(k, 2))
         banned = set()              # vertices added or deleted by this batch
         used = set()                # edge keys touched by this batch
@@ -206,6 +207,12 @@ class UpdateStream:
                 u, v = self._random_new_edge(used, banned)
                 used.add(u * self.cap + v)
                 groups.append([(OP_EDGE_ADD, u, v, 0)])
+            elif kind == "reweight":                         # weighted streams only: a new weight for an existing edge
+                if not self.weighted:
+                    raise ValueError("edge weights can only be replaced on a weighted stream")
+                u, v = self._random_existing_edge(used, banned)
+                used.add(u * self.cap + v)
+                groups.append([(OP_EDGE_REWEIGHT, u, v, 0)])
             else:
                 raise ValueError(kind)
         order = rng.permutation(len(groups))
@@ -226,7 +233,7 @@ class UpdateStream:
                 self.alive[u] = False
         ops_arr = np.asarray(ops, dtype=np.uint32).reshape(-1, 4)
         if self.weighted:
-            adds = ops_arr[:, 0] == OP_EDGE_ADD
+            adds = (ops_arr[:, 0] == OP_EDGE_ADD) | (ops_arr[:, 0] == OP_EDGE_REWEIGHT)
             w = self.wrng.uniform(0.25, 1.75, int(adds.sum())).astype(np.float32)
             ops_arr[adds, 3] = w.view(np.uint32)
         payload = (np.stack(rows).astype(np.float32) if rows

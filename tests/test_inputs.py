@@ -42,6 +42,26 @@ def test_stream_is_valid_and_nonconflicting():
     assert np.array_equal(st.alive, stream.alive)
 
 
+def test_weighted_stream_with_weight_replacements():
+    cfg = ri.get_config("tiny_gcn_sum")
+    src, dst, out_law, in_law = ri.chung_lu_graph(cfg.n, cfg.e, cfg.gamma, cfg.top_share, 5)
+    feats = ri.features(cfg.n, 8, 6)
+    w = ri.edge_weights(len(src), 8)
+    mix = {"edge_add": 0.3, "edge_del": 0.2, "feat": 0.2, "vadd": 0.0, "vdel": 0.0, "reweight": 0.3}
+    stream = ri.UpdateStream(cfg.n, cfg.vertex_capacity, src, dst, out_law, in_law, 8, mix, 7, weighted=True)
+    st = oracle.GraphState(cfg.n, cfg.vertex_capacity, src, dst, feats, weights=w)
+    seen = 0
+    for b in range(6):
+        ops, payload, n_upd = stream.next_batch(50)
+        assert n_upd == 50
+        seen += int((ops[:, 0] == ri.OP_EDGE_REWEIGHT).sum())
+        rec = st.apply_batch(ops, payload)
+        assert rec.accepted.all(), b
+    assert seen == 6 * 15
+    ew = st.edge_weights()
+    assert ew.min() >= 0.25 and ew.max() < 1.75 and len(ew) == st.n_edges()
+
+
 def test_batch_size_one_draws_every_kind():
     cfg = ri.get_config("tiny_gcn_sum")
     src, dst, out_law, in_law = ri.chung_lu_graph(cfg.n, cfg.e, cfg.gamma, cfg.top_share, 5)

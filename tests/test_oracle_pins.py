@@ -479,6 +479,47 @@ def test_weighted_sum_after_a_batch():
         np.testing.assert_allclose(hs[-1][v], want, rtol=1e-12, atol=1e-12)
 
 
+def test_edge_weight_replacement():
+    """The sixth operation: a new weight for an existing edge of a weighted graph. The result equals the brute
+    force on the re-weighted edge set; the sink is in every affected set and, with linear activations, the
+    rows that change are exactly the sets; on a missing edge, a dead endpoint or an unweighted graph the
+    operation is rejected; a weight replaced twice in one batch ends up with the later value."""
+    def bits(x):
+        return int(np.array([x], dtype=np.float32).view(np.uint32)[0])
+    st, model, src, dst, w, feats = weighted_case(9, kind="gcn_wsum", widths=(5, 7, 6, 4))
+    for lay in model:
+        lay["act_out"] = "none"
+    before = oracle.full_recompute(st, model)
+    (u0, v0), (u1, v1) = (int(src[0]), int(dst[0])), (int(src[5]), int(dst[5]))
+    missing = next((u, v) for u in range(12) for v in range(12) if u != v and not st.has_edge(u, v))
+    ops = [(ri.OP_EDGE_REWEIGHT, u0, v0, bits(1.25)), (ri.OP_EDGE_REWEIGHT, u1, v1, bits(0.5)),
+           (ri.OP_EDGE_REWEIGHT, missing[0], missing[1], bits(1.0)),        # no such edge
+           (ri.OP_EDGE_REWEIGHT, u0, st.cap - 1, bits(1.0)),                  # dead endpoint
+           (ri.OP_EDGE_REWEIGHT, u1, v1, bits(0.625))]                        # again: the later value stays
+    rec = st.apply_batch(np.array(ops, dtype=np.uint32), None)
+    assert rec.accepted.tolist() == [True, True, False, False, True]
+    assert rec.sinks == {v0, v1} and not rec.added and not rec.feat
+    es, ed = st.edges()
+    alpha = in_weights(es, ed, st.edge_weights())
+    assert alpha[(u0, v0)] == 1.25 and alpha[(u1, v1)] == 0.625 and len(alpha) == len(src)
+    after = oracle.full_recompute(st, model)
+    nbrs = in_lists(st.cap, es, ed)
+    memo = {}
+    for v in range(st.cap):
+        want = embed(v, len(model), model, st.h0, nbrs, st.alive, memo, alpha)
+        np.testing.assert_allclose(after[-1][v], want, rtol=1e-12, atol=1e-12)
+    sets = oracle.affected_sets(st, rec, model)
+    assert sets[0].tolist() == []
+    for l in range(1, len(model) + 1):
+        assert {v0, v1} <= set(sets[l].tolist())
+        changed = set(np.nonzero(np.abs(after[l] - before[l]).max(axis=1) > 0)[0].tolist())
+        assert changed == set(sets[l].tolist()), l
+    # a graph without weights has nothing to replace
+    plain, _, s2, d2, _ = small_case(9)
+    rec = plain.apply_batch(np.array([(ri.OP_EDGE_REWEIGHT, int(s2[0]), int(d2[0]), bits(2.0))], dtype=np.uint32), None)
+    assert rec.accepted.tolist() == [False] and not rec.sinks
+
+
 # ---- max / min aggregation (Table 1, Sec. 3.4.2 "Monotonic Aggregation Functions") ----------------
 @pytest.mark.parametrize("kind", ["gcn_max", "gcn_min", "sage_max"])
 @pytest.mark.parametrize("seed", [0, 1])
