@@ -46,20 +46,26 @@ typedef enum {
                                its work, but the rows ripple_last_error counts hold non-finite values */
 } ripple_status;
 
-/* The five update types of Sec. 3.1. */
+/* The five update types of Sec. 3.1, and the replacement of an edge's weight (weighted graphs; Sec. 3.3.3,
+ * "Other linear aggregators": a message is alpha_uv times the source's embedding, so a new alpha_uv reaches
+ * the sink as (alpha_new - alpha_old) h_u). */
 typedef enum {
     RIPPLE_EDGE_ADD = 0,      /* edge u -> v */
     RIPPLE_EDGE_DEL = 1,      /* edge u -> v */
     RIPPLE_VERTEX_ADD = 2,    /* vertex u, features = payload row feat_row */
     RIPPLE_VERTEX_DEL = 3,    /* vertex u and all its incident edges (Sec. 3.2) */
-    RIPPLE_FEAT_UPDATE = 4    /* h^0_u = payload row feat_row */
+    RIPPLE_FEAT_UPDATE = 4,   /* h^0_u = payload row feat_row */
+    RIPPLE_EDGE_REWEIGHT = 5  /* existing edge u -> v of a weighted graph: alpha_uv = the float32 whose bits are in feat_row;
+                                 rejected when the edge is missing or the graph has no weights. The sink is affected at
+                                 every hop, like the sink of an added or deleted edge. */
 } ripple_op_kind;
 
 typedef struct {
     uint32_t kind;       /* ripple_op_kind */
     uint32_t u;
     uint32_t v;          /* sink of an edge op; ignored otherwise */
-    uint32_t feat_row;   /* row of the batch's feature payload; ignored for edge ops and VERTEX_DEL */
+    uint32_t feat_row;   /* row of the batch's feature payload; ignored for EDGE_DEL and VERTEX_DEL; weighted graphs: the
+                            float32 bits of alpha_uv for EDGE_ADD and EDGE_REWEIGHT */
 } ripple_update;         /* 16 bytes */
 
 typedef enum {
@@ -122,7 +128,7 @@ typedef struct {
     uint64_t n_edges;                             /* edges after the batch                       */
     uint32_t affected[RIPPLE_MAX_LAYERS + 1];     /* a_l = |A_l|, l = 0..L (Sec. 3.5)            */
     uint64_t messages[RIPPLE_MAX_LAYERS + 1];     /* delta messages sent into layer l (index 0 unused) */
-    uint32_t n_structural;                        /* added/removed edges incl. those of deleted vertices */
+    uint32_t n_structural;                        /* added / removed / re-weighted edges incl. those of deleted vertices */
     /* max / min layers only (Sec. 3.4.2): vertices that received a message or had an in-edge changed at
      * hop l, split by what was done with them; unchanged ones are not in A_l and send nothing on */
     uint32_t mono_unchanged[RIPPLE_MAX_LAYERS + 1];
@@ -200,14 +206,19 @@ ripple_status ripple_init_graph(ripple_ctx **out, uint32_t n_vertices, uint32_t 
 /* The same with a weight alpha_uv per edge (edge_weights: host, float32 [n_edges], borrowed; Table 1's
  * weighted sum, Sec. 3.3.3 "Other linear aggregators"): layers with RIPPLE_AGG_WSUM aggregate
  * sum_u alpha_uv h_u, other layers ignore the weights. A weight is fixed when its edge is created: an
- * EDGE_ADD operation on such a graph carries the float32 bits of alpha_uv in its feat_row word. Weighted
- * graphs always gather along in-edges (no push kernel) and do not combine with RIPPLE_OPT_DETERMINISTIC. */
+ * EDGE_ADD operation on such a graph carries the float32 bits of alpha_uv in its feat_row word, and
+ * RIPPLE_EDGE_REWEIGHT replaces it later. Weighted graphs always gather along in-edges (no push kernel) and do
+ * not combine with RIPPLE_OPT_DETERMINISTIC. */
 ripple_status ripple_init_graph_weighted(ripple_ctx **out, uint32_t n_vertices, uint32_t vertex_capacity,
                                          uint64_t n_edges, uint64_t edge_capacity,
                                          const uint32_t *src, const uint32_t *dst, const float *edge_weights,
                                          const float *features, uint32_t d0, int store, void *hip_stream);
 
-/* Copy the model to the GPU. layers[0].d_in must equal d0 and widths must chain. */
+/* Copy the model to the GPU: L layers, each an AGGREGATE over the in-neighbours followed by an UPDATE with
+ * learned weights (Sec. 2.1, Eq. 1-2; ripple_layer_desc above says which of Table 1's aggregators and which
+ * update each layer takes). layers: host array of n_layers descriptors whose weight pointers are host memory,
+ * all borrowed for the call; layers[0].d_in must equal d0 and the widths must chain, else RIPPLE_EINVAL.
+ * Allocates every per-layer array (H^l, X^l, caches) at vertex_capacity rows; RIPPLE_ENOMEM when that fails. */
 ripple_status ripple_load_model(ripple_ctx *ctx, uint32_t n_layers, const ripple_layer_desc *layers);
 
 /* Bootstrap: compute X^l and H^l for all layers and all live vertices on the
@@ -215,7 +226,7 @@ ripple_status ripple_load_model(ripple_ctx *ctx, uint32_t n_layers, const ripple
 ripple_status ripple_full_infer(ripple_ctx *ctx);
 
 /* Apply one batch (Sec. 3.3): operations take effect in array order; invalid
- * ones (dead endpoint, existing edge added, missing edge deleted, live vertex
+ * ones (dead endpoint, existing edge added, missing edge deleted or re-weighted, live vertex
  * added, dead vertex deleted/updated) are rejected one by one and counted; ids
  * >= vertex_capacity, unknown kinds or feat_row >= n_feat_rows fail the whole
  * call with RIPPLE_EINVAL before anything changes. Then deltas are propagated
@@ -233,7 +244,9 @@ ripple_status ripple_apply_updates(ripple_ctx *ctx, const ripple_update *ops, ui
 
 /* Rows ids[0..n_ids) of H^layer (layer 0 = features) as float32 into out
  * [n_ids x d_layer] (host or device). ids: host or device, or NULL for rows
- * 0..n_ids-1. Rows of dead vertices are zero. */
+ * 0..n_ids-1. Rows of dead vertices are zero. This is the read side of trigger-based
+ * inference (Sec. 2.2): every embedding is kept current by ripple_apply_updates, so a
+ * query is a row copy, with no computation at request time; layer L holds the predictions. */
 ripple_status ripple_get_embeddings(ripple_ctx *ctx, uint32_t layer, const uint32_t *ids,
                                     uint32_t n_ids, float *out);
 

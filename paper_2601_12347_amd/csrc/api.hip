@@ -257,7 +257,7 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
                     c->dead_in, c->hole_out, c->hole_in, c->out_pool, c->in_pool, c->in_w, c->alive, c->part_cnt, c->part_deg, c->part_ideg, c->ioff[0], c->ctr, c->D[0], c->D[1],
                     c->tmp, c->PD, c->MSG, c->Pold, c->sold, c->seg_v, c->seg_done, c->seg_base, c->seg_r, c->seg_part, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ioff_all, c->mk, c->ops_d, c->payload_d,
                     c->op_status, c->op_pos_out, c->op_pos_in, c->op_touch, c->touch_out, c->touch_in, c->exp_kind, c->exp_s, c->exp_a,
-                    c->exp_b, c->st_src, c->st_dst, c->st_sign, c->gather_d, c->gather_ids};
+                    c->exp_b, c->st_src, c->st_dst, c->st_sign, c->st_unit, c->gather_d, c->gather_ids};
     for (void *p : ptrs)
         if (p) hipFree(p);
     for (uint32_t l = 0; l <= RIPPLE_MAX_LAYERS; ++l) {
@@ -617,7 +617,7 @@ static void split_batch(const ripple_update *ops, uint32_t n, TouchTable &tt, st
         const ripple_update &op = ops[i];
         for (int attempt = 0; attempt < 2; ++attempt) {
             bool conflict = false;
-            if (op.kind == RIPPLE_EDGE_ADD || op.kind == RIPPLE_EDGE_DEL) {
+            if (op.kind == RIPPLE_EDGE_ADD || op.kind == RIPPLE_EDGE_DEL || op.kind == RIPPLE_EDGE_REWEIGHT) {
                 uint64_t ek = ((uint64_t)op.u << 32) | op.v;
                 uint8_t *fu = tt.find(VKEY | op.u, false), *fv = tt.find(VKEY | op.v, false);
                 if (tt.find(ek, false) || (fu && (*fu & TF_VDEL)) || (fv && (*fv & TF_VDEL))) conflict = true;
@@ -645,7 +645,7 @@ static void split_batch(const ripple_update *ops, uint32_t n, TouchTable &tt, st
         }
         if (op.kind == RIPPLE_VERTEX_DEL) cur.has_vdel = true;
         if (op.kind == RIPPLE_VERTEX_ADD) cur.has_vadd = true;
-        if (op.kind >= RIPPLE_VERTEX_ADD) cur.has_vertex_or_feat = true;
+        if (op.kind >= RIPPLE_VERTEX_ADD && op.kind <= RIPPLE_FEAT_UPDATE) cur.has_vertex_or_feat = true;
     }
     cur.end = n;
     if (cur.end > cur.begin || out.empty()) out.push_back(cur);
@@ -654,8 +654,8 @@ static void split_batch(const ripple_update *ops, uint32_t n, TouchTable &tt, st
 static bool ops_in_range(const ripple_update *ops, uint32_t n_ops, uint32_t n_cap, uint32_t n_feat_rows) {
     for (uint32_t i = 0; i < n_ops; ++i) {
         const ripple_update &op = ops[i];
-        bool bad = op.kind > RIPPLE_FEAT_UPDATE || op.u >= n_cap;
-        if (!bad && op.kind <= RIPPLE_EDGE_DEL) bad = op.v >= n_cap;
+        bool bad = op.kind > RIPPLE_EDGE_REWEIGHT || op.u >= n_cap;
+        if (!bad && (op.kind <= RIPPLE_EDGE_DEL || op.kind == RIPPLE_EDGE_REWEIGHT)) bad = op.v >= n_cap;
         if (!bad && (op.kind == RIPPLE_VERTEX_ADD || op.kind == RIPPLE_FEAT_UPDATE)) bad = op.feat_row >= n_feat_rows;
         if (bad) return false;
     }
@@ -684,7 +684,7 @@ static ripple_status ensure_batch_buffers(ripple_ctx *c, uint32_t n_ops, uint32_
         cap = rp_round_up(cap + cap / 2, 1024);
         uint32_t exp = std::max<uint32_t>(std::max<uint32_t>(want_exp, c->exp_cap), 1u << 20);
         void *old[] = {c->ops_d, c->op_status, c->op_pos_out, c->op_pos_in, c->op_touch, c->touch_out, c->touch_in, c->exp_kind, c->exp_s,
-                       c->exp_a, c->exp_b, c->st_src, c->st_dst, c->st_sign};
+                       c->exp_a, c->exp_b, c->st_src, c->st_dst, c->st_sign, c->st_unit};
         for (void *p : old)
             if (p) hipFree(p);
         c->ops_cap = c->exp_cap = c->touch_cap = c->struct_cap = 0;
@@ -702,6 +702,7 @@ static ripple_status ensure_batch_buffers(ripple_ctx *c, uint32_t n_ops, uint32_
         RP_TRY(dev_alloc(c, &c->st_src, (size_t)cap + exp, false));
         RP_TRY(dev_alloc(c, &c->st_dst, (size_t)cap + exp, false));
         RP_TRY(dev_alloc(c, &c->st_sign, (size_t)cap + exp, false));
+        RP_TRY(dev_alloc(c, &c->st_unit, (size_t)cap + exp, false));
         c->ops_cap = cap;
         c->exp_cap = exp;
         c->touch_cap = cap + exp;

@@ -227,7 +227,7 @@ __device__ __forceinline__ void gat_team_role(const GatArgs &a, uint32_t bid, ui
                 if (threadIdx.x == 0) s_nhit = 0;
                 __syncthreads();
                 for (uint32_t s = threadIdx.x; s < n_st; s += TEAM * 64)
-                    if (a.st_dst[s] == v) {
+                    if (a.st_dst[s] == v && a.st_sign[s] != 0.0f) {
                         const uint32_t k = atomicAdd(&s_nhit, 1u);
                         if (k < GAT_EDGE_HITS) s_hit[k] = s;
                     }
@@ -497,7 +497,7 @@ void rp_launch_gat_scatter(ripple_ctx *c, uint32_t l, bool bootstrap, bool prequ
     a.seg_ld = c->seg_ld;
     a.st_src = c->st_src;
     a.st_dst = c->st_dst;
-    a.st_sign = c->st_sign;
+    a.st_sign = c->st_unit;                         // +1 added, -1 deleted, 0 re-weighted (attention ignores edge weights)
     a.n_struct = &c->ctr->n_struct;
     a.struct_cap = (c->in_w || bootstrap) ? 0u : c->struct_cap;   // weighted graphs: the sign carries the weight, sinks recompute
     if (bootstrap) {                                     // a batch starts with them cleared

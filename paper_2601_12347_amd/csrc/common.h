@@ -164,7 +164,8 @@ struct ripple_ctx {
     uint32_t *exp_kind = nullptr, *exp_a = nullptr, *exp_b = nullptr, *exp_s = nullptr;
     uint32_t struct_cap = 0;
     uint32_t *st_src = nullptr, *st_dst = nullptr;
-    float *st_sign = nullptr;
+    float *st_sign = nullptr;                           // per changed edge: what its sink's weighted sums gain, +alpha / -alpha / alpha_new - alpha_old
+    float *st_unit = nullptr;                           // the same for aggregates that ignore weights: +1 added, -1 deleted, 0 re-weighted
     DevCtr *ctr = nullptr;
     DevCtr *ctr_host = nullptr;                         // pinned mirror
     ripple_update *ops_pin = nullptr;                   // pinned staging for ops

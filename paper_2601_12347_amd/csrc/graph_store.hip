@@ -279,7 +279,7 @@ struct MutArgs {
     uint32_t *exp_s;                             // structural-list slot of an expanded out-edge (weighted graphs)
     uint32_t exp_cap;
     uint32_t *st_src, *st_dst;
-    float *st_sign;
+    float *st_sign, *st_unit;
     uint32_t struct_cap;
     uint32_t *bm0, *bm_sink, *bm_vadd;
     uint32_t *list0;
@@ -295,6 +295,7 @@ struct MutArgs {
     float *X[RIPPLE_MAX_LAYERS + 1];
     float *T[RIPPLE_MAX_LAYERS + 1];             // project-first layers: what every vertex has sent so far (xw[l] floats per vertex), else null
     uint32_t mono_mask;                          // bit l: layer l takes max / min or attention (no structural terms)
+    uint32_t wsum_mask;                          // bit l: layer l aggregates with the edge weights
     int d0_old;                                  // layer 1 does: D0 receives the old feature row instead of the difference
 };
 
@@ -338,6 +339,19 @@ __global__ __launch_bounds__(256) void k_edge_validate(MutArgs a) {
         if (op.kind == RIPPLE_FEAT_UPDATE) {               // needs the live flag only
             if (lane == 0) {
                 a.status[i] = rp_bit(a.alive, op.u) ? 1u : 0u;
+                if (a.defer_touch) a.op_touch[i] = 0;
+            }
+            continue;
+        }
+        if (op.kind == RIPPLE_EDGE_REWEIGHT) {             // the edge must exist; nothing about the rows' shape changes
+            int p = -1;
+            if (a.in_w && rp_bit(a.alive, op.u) && rp_bit(a.alive, op.v)) {
+                const uint2 mi = a.in_meta[op.v];
+                p = rp_wave_find(a.in_pool + mi.x, mi.y, op.u);
+            }
+            if (lane == 0) {
+                a.status[i] = p >= 0 ? 1u : 0u;
+                if (p >= 0) a.pos_in[i] = (uint32_t)p;
                 if (a.defer_touch) a.op_touch[i] = 0;
             }
             continue;
@@ -535,6 +549,7 @@ __global__ __launch_bounds__(256) void k_expand_vdel(MutArgs a) {
                     a.st_src[s] = w;
                     a.st_dst[s] = y;
                     a.st_sign[s] = -1.0f;                   // times the edge weight: k_expand_apply, which finds the edge in y's in-row
+                    a.st_unit[s] = -1.0f;
                 }
                 if (a.in_w) a.exp_s[base + j] = s;
                 rp_set_bit(a.bm_sink, y);
@@ -610,9 +625,22 @@ __global__ __launch_bounds__(256) void k_apply_edges(MutArgs a) {
         if (mr) atomicAdd(&a.ctr->n_rejected, (uint32_t)__popcll(mr));
     }
     if (aborted) return;
-    bool edge = acc && (op.kind == RIPPLE_EDGE_ADD || op.kind == RIPPLE_EDGE_DEL);
+    bool edge = acc && (op.kind == RIPPLE_EDGE_ADD || op.kind == RIPPLE_EDGE_DEL || op.kind == RIPPLE_EDGE_REWEIGHT);
     uint32_t s = wave_reserve(&a.ctr->n_struct, edge);
     if (!edge) return;
+    if (op.kind == RIPPLE_EDGE_REWEIGHT) {           // the weighted sums of the sink gain (alpha_new - alpha_old) h_u
+        float *w = a.in_w + a.in_meta[op.v].x + a.pos_in[i];
+        const float alpha_new = __uint_as_float(op.feat_row);
+        if (s < a.struct_cap) {
+            a.st_src[s] = op.u;
+            a.st_dst[s] = op.v;
+            a.st_sign[s] = alpha_new - *w;
+            a.st_unit[s] = 0.0f;
+        }
+        *w = alpha_new;
+        rp_set_bit(a.bm_sink, op.v);
+        return;
+    }
     float alpha = 1.0f;                              // the edge's weight (1 on unweighted graphs)
     if (op.kind == RIPPLE_EDGE_DEL) {
         if (a.in_w) alpha = a.in_w[a.in_meta[op.v].x + a.pos_in[i]];
@@ -627,6 +655,7 @@ __global__ __launch_bounds__(256) void k_apply_edges(MutArgs a) {
         a.st_src[s] = op.u;
         a.st_dst[s] = op.v;
         a.st_sign[s] = (op.kind == RIPPLE_EDGE_ADD) ? alpha : -alpha;
+        a.st_unit[s] = (op.kind == RIPPLE_EDGE_ADD) ? 1.0f : -1.0f;
     }
     rp_set_bit(a.bm_sink, op.v);
 }
@@ -848,7 +877,8 @@ __global__ __launch_bounds__(256) void k_struct_scatter(MutArgs a) {
         const uint32_t e = (uint32_t)(t / per), l = (uint32_t)(t % per) + 1;
         if ((a.mono_mask >> l) & 1u) continue;               // rows with a changed in-edge are recomputed instead
         uint32_t u = a.st_src[e], v = a.st_dst[e];
-        float sg = a.st_sign[e];
+        const float sg = ((a.wsum_mask >> l) & 1u) ? a.st_sign[e] : a.st_unit[e];
+        if (sg == 0.0f) continue;                            // a new weight means nothing to a layer that ignores weights
         if (a.T[l] == nullptr) {
             const uint32_t dp = a.d[l - 1];
             for (uint32_t c = lane; c < dp; c += 64) {
@@ -930,6 +960,7 @@ static MutArgs make_args(ripple_ctx *c, uint32_t n_ops) {
     a.st_src = c->st_src;
     a.st_dst = c->st_dst;
     a.st_sign = c->st_sign;
+    a.st_unit = c->st_unit;
     a.struct_cap = c->struct_cap;
     a.bm0 = c->bm[0];
     a.bm_sink = c->bm_sink;
@@ -950,8 +981,11 @@ static MutArgs make_args(ripple_ctx *c, uint32_t n_ops) {
         a.T[l] = (l >= 1 && l <= c->L && c->layers[l - 1].proj) ? c->layers[l - 1].T : nullptr;
     }
     a.mono_mask = 0;
-    for (uint32_t l = 1; l <= c->L; ++l)
+    a.wsum_mask = 0;
+    for (uint32_t l = 1; l <= c->L; ++l) {
         if (rp_layer_mono(c, l) || rp_layer_attn(c, l)) a.mono_mask |= 1u << l;
+        if (c->layers[l - 1].agg == RIPPLE_AGG_WSUM) a.wsum_mask |= 1u << l;
+    }
     a.d0_old = rp_layer_mono(c, 1) ? 1 : 0;
     return a;
 }

@@ -1158,7 +1158,7 @@ __device__ __forceinline__ void mono_team_role(const MonoArgs &a, uint32_t bid, 
                 recompute = true;
             } else {
                 for (uint32_t s = threadIdx.x; s < n_st; s += TEAM * 64)
-                    if (a.st_dst[s] == v) {
+                    if (a.st_dst[s] == v && a.st_sign[s] != 0.0f) {
                         const uint32_t k = atomicAdd(&s_nhit, 1u);
                         if (k < MONO_EDGE_HITS) s_hit[k] = s;
                     }
@@ -1409,7 +1409,7 @@ void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l, const uint32_t *count_ptr
     a.l = l;
     a.st_src = c->st_src;
     a.st_dst = c->st_dst;
-    a.st_sign = c->st_sign;
+    a.st_sign = c->st_unit;                         // +1 added, -1 deleted, 0 re-weighted (nothing to a max / min layer)
     a.struct_cap = c->in_w ? 0u : c->struct_cap;   // weighted graphs: the sign carries the weight, sinks recompute
     a.alive = c->alive;
     a.seg_v = c->seg_v;

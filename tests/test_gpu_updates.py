@@ -392,6 +392,69 @@ def test_attention_scores_beyond_the_float_range_are_reported():
             rp.ripple_destroy(ctx)
 
 
+MIXW = {"edge_add": 0.3, "edge_del": 0.2, "feat": 0.2, "vadd": 0.03, "vdel": 0.02, "reweight": 0.25}
+
+
+@pytest.mark.parametrize("mode", [0, 2, 3])
+@pytest.mark.parametrize("kind,widths", [("gcn_wsum", (12, 24, 10)), ("sage_wsum", (16, 96, 40))])
+def test_edge_weight_replacement(mode, kind, widths):
+    """The sixth operation: a quarter of the updates replace the weight of an existing edge. The sink's cached
+    weighted sums gain (alpha_new - alpha_old) times the source's pre-batch row, later messages carry the new
+    weight; sets, rows and cached sums are compared with the oracle after every batch, for every way of moving
+    the messages (the second model ends in a packed project-first layer)."""
+    print("case edge weight replacement", mode, kind, flush=True)
+    pair, graph = make_pair(n=600, e=5000, d0=widths[0], kind=kind, widths=widths, seed=161, slack=128, weighted=True)
+    rp.ripple_set_option(pair.ctx, rp.OPT_SCATTER_MODE, mode)
+    stream = make_stream(pair, graph, MIXW, 163, weighted=True)
+    try:
+        for b, bs in enumerate([8, 60, 200, 40]):
+            ops, payload, _ = stream.next_batch(bs)
+            n_rw = int((ops[:, 0] == ri.OP_EDGE_REWEIGHT).sum())
+            print(" batch", b, bs, "weight replacements", n_rw, flush=True)
+            res, rec, _ = pair.step(ops, payload)
+            assert n_rw > 0 and res.n_rejected == 0
+        pair.check_graph()
+        pair.check_aggregates()
+        # rejected: missing edge; accepted twice in one batch: cut into two pieces, the later weight stays
+        es, ed = pair.ora.edges()
+        u, v = int(es[0]), int(ed[0])
+        miss = next((a, b) for a in range(20) for b in range(20, 40) if not pair.ora.has_edge(a, b))
+        bits = lambda x: int(np.array([x], dtype=np.float32).view(np.uint32)[0])
+        ops = np.array([(ri.OP_EDGE_REWEIGHT, u, v, bits(0.5)), (ri.OP_EDGE_REWEIGHT, miss[0], miss[1], bits(1.0)),
+                        (ri.OP_EDGE_REWEIGHT, u, v, bits(1.5))], dtype=np.uint32)
+        res, rec, _ = pair.step(ops, None)
+        assert res.n_applied == 2 and res.n_rejected == 1 and res.n_sub_batches == 2
+        pair.check_aggregates()
+    finally:
+        pair.close()
+
+
+def test_layers_that_ignore_weights_on_a_weighted_graph():
+    """A weighted graph under a model whose first layer aggregates with the weights and whose second takes the
+    plain mean: an added or deleted edge counts once for the second layer whatever its weight, and a new weight
+    means nothing to it."""
+    print("case mixed weighted / unweighted layers", flush=True)
+    n, e = 500, 4000
+    src, dst, out_law, in_law = ri.chung_lu_graph(n, e, 2.1, 0.03, 171)
+    feats = ri.features(n, 12, 172)
+    w = ri.edge_weights(len(src), 173)
+    first = ri.make_model("gcn_wsum", (12, 20), 174)
+    first[0]["act_out"] = "relu"
+    model = first + ri.make_model("sage_mean", (20, 16, 6), 175)
+    from harness import Pair
+    pair = Pair(n, n + 64, src, dst, feats, model, weights=w)
+    stream = ri.UpdateStream(n, n + 64, src, dst, out_law, in_law, 12, MIXW, 176, weighted=True)
+    try:
+        for b, bs in enumerate([6, 80, 150]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload)
+        pair.check_graph()
+        pair.check_aggregates()
+    finally:
+        pair.close()
+
+
 def test_bf16_store_updates():
     print("case bf16 updates", flush=True)
     pair, graph = make_pair(n=600, e=4000, d0=16, kind="gcn_sum", widths=(16, 64, 24), store="bf16", seed=37)
