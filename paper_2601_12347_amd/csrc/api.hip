@@ -255,9 +255,9 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
     hipStreamSynchronize(c->stream);
     void *ptrs[] = {c->out_meta, c->in_meta, c->out_capv, c->in_capv, c->vstate, c->pend_out, c->pend_in, c->dead_out,
                     c->dead_in, c->hole_out, c->hole_in, c->out_pool, c->in_pool, c->in_w, c->alive, c->part_cnt, c->part_deg, c->part_ideg, c->ioff[0], c->ctr, c->D[0], c->D[1],
-                    c->tmp, c->PD, c->MSG, c->Pold, c->sold, c->seg_v, c->seg_done, c->seg_base, c->seg_r, c->seg_part, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ioff_all, c->mk, c->ops_d, c->payload_d,
+                    c->tmp, c->PD, c->MSG, c->side_v, c->side_acc, c->Pold, c->sold, c->seg_v, c->seg_done, c->seg_base, c->seg_r, c->seg_part, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ioff_all, c->mk, c->ops_d, c->payload_d,
                     c->op_status, c->op_pos_out, c->op_pos_in, c->op_touch, c->touch_out, c->touch_in, c->exp_kind, c->exp_s, c->exp_a,
-                    c->exp_b, c->st_src, c->st_dst, c->st_sign, c->st_unit, c->gather_d, c->gather_ids};
+                    c->exp_b, c->st_src, c->st_dst, c->st_sign, c->st_unit, c->tail_ids, c->tail_q, c->tail_w, c->sk_in, c->sk_out, c->sv_in, c->sv_out, c->sort_tmp, c->gather_d, c->gather_ids};
     for (void *p : ptrs)
         if (p) hipFree(p);
     for (uint32_t l = 0; l <= RIPPLE_MAX_LAYERS; ++l) {
@@ -376,7 +376,7 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
             RP_HIP(c, hipMemcpy(ly.W0h, wt.data(), wt.size() * 2, hipMemcpyHostToDevice));
         }
         // project first where the single linear map shrinks the row at least by half
-        ly.proj = (c->opt_project && !c->opt_deterministic && s.agg < RIPPLE_AGG_MAX && s.d_hidden == 0 && s.self_mode != RIPPLE_SELF_ADD && 2 * s.d_out <= s.d_in) ? 1u : 0u;
+        ly.proj = (c->opt_project && s.agg < RIPPLE_AGG_MAX && s.d_hidden == 0 && s.self_mode != RIPPLE_SELF_ADD && 2 * s.d_out <= s.d_in) ? 1u : 0u;
         ly.selfc = (c->opt_selfcache && s.d_hidden == 0 && s.self_mode == RIPPLE_SELF_CONCAT) ? 1u : 0u;
         if (s.agg == RIPPLE_AGG_ATTN) {
             RP_TRY(dev_alloc(c, &ly.att, (size_t)2 * s.d_out, false));
@@ -475,6 +475,13 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
         for (uint32_t l = 1; l <= c->L; ++l) packed |= c->layers[l - 1].proj && c->layers[l - 1].packed;
         if (packed) RP_TRY(dev_alloc(c, &c->MSG, n * RP_MSG_WORDS, true));
     }
+    if (c->opt_deterministic) {                          // two side entries per wavefront of the pull kernels' grid
+        uint32_t xmax = 1;
+        for (uint32_t l = 1; l <= c->L; ++l) xmax = std::max(xmax, c->xw[l]);
+        const size_t entries = 2 * (size_t)c->n_cu * 8 * 4;
+        RP_TRY(dev_alloc(c, &c->side_v, entries, false));
+        RP_TRY(dev_alloc(c, &c->side_acc, entries * xmax, false));
+    }
     // bitmaps: layers 0..L, then S, then V_added, contiguous; reporting copies separately
     uint32_t *bmall = nullptr, *repall = nullptr, *lists = nullptr, *eoffs = nullptr, *ioffs = nullptr;
     RP_TRY(dev_alloc(c, &bmall, (size_t)c->n_words * (c->L + 3), true));
@@ -519,6 +526,7 @@ extern "C" ripple_status ripple_full_infer(ripple_ctx *c) {
     hipLaunchKernelGGL(k_or_words, dim3(rp_div_up(c->n_words, 256)), dim3(256), 0, c->stream, c->bm[0], c->alive,
                        c->n_words);
     rp_launch_bitmap_to_list(c, c->bm[0], c->all_list, &c->ctr->a[0]);
+    if (c->opt_deterministic) rp_launch_alive_list(c);     // the same list once more, with its in-degree prefix
     for (uint32_t l = 1; l <= c->L; ++l) {
         if (rp_layer_attn(c, l)) {
             rp_launch_gat_project(c, l, c->all_list, &c->ctr->a[0]);
@@ -533,7 +541,7 @@ extern "C" ripple_status ripple_full_infer(ripple_ctx *c) {
             if (c->layers[l - 1].proj) rp_launch_project(c, l, c->all_list, &c->ctr->a[0], true);
             if (c->layers[l - 1].selfc) rp_launch_self_project(c, l, c->all_list, &c->ctr->a[0]);
         }
-        if (c->opt_deterministic) rp_launch_scatter_owner(c, l, true);     // same summation order as the batches use
+        if (c->opt_deterministic) rp_launch_scatter_pull_det(c, l, true);  // same summation order as the batches use
         else rp_launch_pull_all(c, l);
         rp_launch_transform(c, l, c->all_list, &c->ctr->a[0], false);
     }
@@ -684,9 +692,14 @@ static ripple_status ensure_batch_buffers(ripple_ctx *c, uint32_t n_ops, uint32_
         cap = rp_round_up(cap + cap / 2, 1024);
         uint32_t exp = std::max<uint32_t>(std::max<uint32_t>(want_exp, c->exp_cap), 1u << 20);
         void *old[] = {c->ops_d, c->op_status, c->op_pos_out, c->op_pos_in, c->op_touch, c->touch_out, c->touch_in, c->exp_kind, c->exp_s,
-                       c->exp_a, c->exp_b, c->st_src, c->st_dst, c->st_sign, c->st_unit};
+                       c->exp_a, c->exp_b, c->st_src, c->st_dst, c->st_sign, c->st_unit, c->tail_ids, c->tail_q, c->tail_w, c->sk_in, c->sk_out, c->sv_in, c->sv_out, c->sort_tmp};
         for (void *p : old)
             if (p) hipFree(p);
+        c->tail_ids = c->tail_q = nullptr;
+        c->tail_w = nullptr;
+        c->sk_in = c->sk_out = nullptr;
+        c->sv_in = c->sv_out = nullptr;
+        c->sort_tmp = nullptr;
         c->ops_cap = c->exp_cap = c->touch_cap = c->struct_cap = 0;
         RP_TRY(dev_alloc(c, &c->ops_d, cap, false));
         RP_TRY(dev_alloc(c, &c->op_status, cap, true));
@@ -703,6 +716,20 @@ static ripple_status ensure_batch_buffers(ripple_ctx *c, uint32_t n_ops, uint32_
         RP_TRY(dev_alloc(c, &c->st_dst, (size_t)cap + exp, false));
         RP_TRY(dev_alloc(c, &c->st_sign, (size_t)cap + exp, false));
         RP_TRY(dev_alloc(c, &c->st_unit, (size_t)cap + exp, false));
+        if (c->opt_deterministic) {
+            RP_TRY(dev_alloc(c, &c->tail_ids, cap, false));
+            RP_TRY(dev_alloc(c, &c->tail_w, cap, false));
+            RP_TRY(dev_alloc(c, &c->tail_q, (size_t)cap + exp, false));
+            RP_TRY(dev_alloc(c, &c->sk_in, (size_t)cap + exp, false));
+            RP_TRY(dev_alloc(c, &c->sk_out, (size_t)cap + exp, false));
+            RP_TRY(dev_alloc(c, &c->sv_in, (size_t)cap + exp, false));
+            RP_TRY(dev_alloc(c, &c->sv_out, (size_t)cap + exp, false));
+            c->sort_tmp_bytes = rp_sort_u64_tmp_bytes((size_t)cap + exp);
+            if (!c->sort_tmp_bytes) return fail(c, RIPPLE_EDEVICE, "the sort's temporary storage could not be sized");
+            unsigned char *tmp = nullptr;
+            RP_TRY(dev_alloc(c, &tmp, c->sort_tmp_bytes, false));
+            c->sort_tmp = tmp;
+        }
         c->ops_cap = cap;
         c->exp_cap = exp;
         c->touch_cap = cap + exp;
@@ -770,13 +797,19 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
             t = rp_timer_begin(c);
             rp_launch_frontier_compact(c, l, layer_self(c, l), l < c->L, true, multi);
             rp_timer_end(c, t, RIPPLE_PH_COMPACT, (int)l);
-            if (c->layers[l - 1].selfc) {
+            if (c->layers[l - 1].proj || c->layers[l - 1].selfc) {
                 t = rp_timer_begin(c);
-                rp_launch_self_project(c, l, c->list[l - 1], &c->ctr->a[l - 1]);
+                if (rp_has_project_both(c, l)) {
+                    rp_launch_project_both(c, l, c->list[l - 1], &c->ctr->a[l - 1], false);
+                } else {
+                    if (c->layers[l - 1].proj) rp_launch_project(c, l, c->list[l - 1], &c->ctr->a[l - 1], false);
+                    if (c->layers[l - 1].selfc) rp_launch_self_project(c, l, c->list[l - 1], &c->ctr->a[l - 1]);
+                }
+                if (c->layers[l - 1].proj) rp_launch_messages(c, l);
                 rp_timer_end(c, t, RIPPLE_PH_OTHER, (int)l);
             }
             t = rp_timer_begin(c);
-            rp_launch_scatter_owner(c, l, false);
+            rp_launch_scatter_pull_det(c, l, false);
             rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l);
             t = rp_timer_begin(c);
             rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], next_reads_delta(c, l));

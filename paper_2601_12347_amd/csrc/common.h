@@ -49,9 +49,9 @@ struct DevCtr {                      // device-resident counters, one instance p
     uint32_t range_rows;                      // attention layers: rows updated from sums that were not finite
     unsigned long long n_edges;
     uint32_t blocks_done;                     // workgroups of k_capacity that have finished (0 between launches)
-    uint32_t pad2;
+    uint32_t n_tail_q;                        // deterministic mode: in-rows whose appended entries a workgroup puts in order
     uint32_t error;                           // sticky consistency error seen by a kernel
-    uint32_t pad1;
+    uint32_t tail_top;                        // ... and the part of the copy buffer they have taken
 };
 
 #define RP_MONO_LISTED_LONG 64u        // small max / min and attention hops: in-rows longer than this are queued for a workgroup while the hop's vertices are listed
@@ -166,6 +166,17 @@ struct ripple_ctx {
     uint32_t *st_src = nullptr, *st_dst = nullptr;
     float *st_sign = nullptr;                           // per changed edge: what its sink's weighted sums gain, +alpha / -alpha / alpha_new - alpha_old
     float *st_unit = nullptr;                           // the same for aggregates that ignore weights: +1 added, -1 deleted, 0 re-weighted
+    // deterministic mode: appended in-row entries are put in id order through these (ops_cap entries each; queue: touch_cap)
+    uint32_t *tail_ids = nullptr, *tail_q = nullptr;
+    float *tail_w = nullptr;
+    // ... and the pull kernels leave the sums of rows that several wavefronts read in-edges of here (two entries per wavefront)
+    uint32_t *side_v = nullptr;
+    float *side_acc = nullptr;
+    // ... and the changed edges are sorted by (sink, source) before their structural terms are added (struct_cap entries each)
+    unsigned long long *sk_in = nullptr, *sk_out = nullptr;
+    float *sv_in = nullptr, *sv_out = nullptr;
+    void *sort_tmp = nullptr;
+    size_t sort_tmp_bytes = 0;
     DevCtr *ctr = nullptr;
     DevCtr *ctr_host = nullptr;                         // pinned mirror
     ripple_update *ops_pin = nullptr;                   // pinned staging for ops

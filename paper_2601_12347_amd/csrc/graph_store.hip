@@ -126,6 +126,30 @@ __global__ void k_fill_rows(const uint32_t *key, const uint32_t *val, const floa
     }
 }
 
+// In-rows are filled in the order the edges were given (a stable sort by sink has put position e of the
+// sorted sequence at offset e - first[sink] of the sink's row), so that their order is a function of the input.
+__global__ void k_iota(uint32_t *out, uint64_t n) {
+    uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t e = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n; e += stride) out[e] = (uint32_t)e;
+}
+
+__global__ void k_fill_in_rows_ordered(const uint32_t *sorted_dst, const uint32_t *sorted_idx, const uint32_t *src,
+                                       const float *wts, uint64_t n_edges, const uint32_t *first, const uint2 *meta,
+                                       uint32_t *pool, float *wpool) {
+    uint64_t stride = (uint64_t)gridDim.x * blockDim.x;
+    for (uint64_t e = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x; e < n_edges; e += stride) {
+        const uint32_t k = sorted_dst[e], i = sorted_idx[e];
+        const size_t at = (size_t)meta[k].x + ((uint32_t)e - first[k]);
+        pool[at] = src[i];
+        if (wpool) wpool[at] = wts[i];
+    }
+}
+
+__global__ void k_set_len(uint2 *meta, const uint32_t *len, uint32_t n_cap) {
+    uint32_t v = blockIdx.x * blockDim.x + threadIdx.x;
+    if (v < n_cap) meta[v].y = len[v];
+}
+
 __global__ void k_set_alive_prefix(uint32_t *alive, uint32_t n_words, uint32_t n_vertices) {
     uint32_t w = blockIdx.x * blockDim.x + threadIdx.x;
     if (w >= n_words) return;
@@ -184,8 +208,27 @@ ripple_status rp_build_graph(ripple_ctx *c, uint32_t n_vertices, uint64_t n_edge
     } else if (n_edges) {
         hipLaunchKernelGGL(k_fill_rows, dim3(gb), dim3(256), 0, s, src_d, dst_d, (const float *)nullptr, n_edges,
                            c->out_meta, c->out_pool, (float *)nullptr);
-        hipLaunchKernelGGL(k_fill_rows, dim3(gb), dim3(256), 0, s, dst_d, src_d, (const float *)w_d, n_edges, c->in_meta,
-                           c->in_pool, w_d ? c->in_w : (float *)nullptr);
+        // in-rows: stable sort of the edge numbers by sink, then every edge knows its place
+        uint32_t *ord = nullptr;
+        unsigned key_bits = 1;
+        while (key_bits < 32 && (1ull << key_bits) < (unsigned long long)n_vertices) ++key_bits;
+        if (hipMalloc(&ord, 3 * eb + (size_t)c->n_cap * 4) != hipSuccess) {
+            (void)hipGetLastError();
+            c->err = "device allocation for the build failed";
+            rc = RIPPLE_ENOMEM;
+        } else {
+            uint32_t *idx = ord, *sdst = ord + n_edges, *sidx = ord + 2 * n_edges, *first = ord + 3 * n_edges;
+            hipLaunchKernelGGL(k_iota, dim3(gb), dim3(256), 0, s, idx, n_edges);
+            rc = rp_stable_sort_pairs(c, dst_d, sdst, idx, sidx, (size_t)n_edges, key_bits);
+            if (rc == RIPPLE_OK) {
+                rp_exclusive_scan(s, deg_in, first, c->n_cap, c->part_deg, nullptr);
+                hipLaunchKernelGGL(k_fill_in_rows_ordered, dim3(gb), dim3(256), 0, s, sdst, sidx, src_d, (const float *)w_d,
+                                   n_edges, first, c->in_meta, c->in_pool, w_d ? c->in_w : (float *)nullptr);
+                hipLaunchKernelGGL(k_set_len, dim3(vb), dim3(256), 0, s, c->in_meta, deg_in, c->n_cap);
+            }
+            hipStreamSynchronize(s);
+            hipFree(ord);
+        }
     }
     hipMemsetAsync(c->pend_out, 0, (size_t)c->n_cap * 4, s);
     hipMemsetAsync(c->pend_in, 0, (size_t)c->n_cap * 4, s);
@@ -297,6 +340,15 @@ struct MutArgs {
     uint32_t mono_mask;                          // bit l: layer l takes max / min or attention (no structural terms)
     uint32_t wsum_mask;                          // bit l: layer l aggregates with the edge weights
     int d0_old;                                  // layer 1 does: D0 receives the old feature row instead of the difference
+    int det;                                     // deterministic mode: appended in-row entries are put in id order
+    uint32_t *tail_ids, *tail_q;                 // ... through a copy (tail_cap entries) and a queue of rows with many of them
+    float *tail_w;
+    uint32_t tail_cap;
+    unsigned long long *sk_in;                   // ... and the changed edges sorted by (sink, source): keys before / after,
+    const unsigned long long *sk_out;
+    float *sv_in;                                // ... with what each adds to its sink's aggregates (+1 / -1 / 0)
+    const float *sv_out;
+    uint32_t n_sort;                             // entries the sort takes (those past n_struct hold the largest key)
 };
 
 __device__ __forceinline__ void touch_row(const MutArgs &a, uint32_t x, uint32_t bit) {
@@ -827,7 +879,10 @@ __global__ __launch_bounds__(256) void k_cleanup_rows(MutArgs a) {
                     a.ctr->error = 6;                        // cannot happen: space was checked before commit
                 }
             }
-            if (lane == 0) meta[x] = make_uint2(m.x, len);
+            if (lane == 0) {
+                meta[x] = make_uint2(m.x, len);
+                if (a.det && !is_out) a.hole_in[x] = len;    // where this batch's appends start (the hole is filled)
+            }
         }
         if (lane == 0) {
             deadv[x] = 0;
@@ -859,6 +914,90 @@ __global__ void k_apply_adds(MutArgs a) {
         a.in_pool[a.in_meta[op.v].x + p] = op.u;
         if (a.in_w) a.in_w[a.in_meta[op.v].x + p] = __uint_as_float(op.feat_row);
     } else a.ctr->error = 7;
+}
+
+// Deterministic mode. The entries appended above land in the order their atomics were served. A sum that
+// walks a row in storage order is only a function of the graph if that order is one, so the appended part
+// of every touched in-row (it starts where k_cleanup_rows left the row's end) is put in ascending id order;
+// ids are distinct within a row. With the rows built in the order the edges were given, and the fills of
+// k_cleanup_rows being functions of the row and the deleted positions alone, an in-row's order then depends
+// on the batches that were applied and on nothing else. Up to 64 appended entries are ranked in registers by
+// the row's wavefront; longer runs are queued for k_sort_long_tails.
+__global__ __launch_bounds__(256) void k_sort_tails(MutArgs a) {
+    if (a.ctr->abort_flag) return;
+    const int lane = rp_lane();
+    uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    const uint32_t ni = min(a.ctr->n_touch_in, a.touch_cap);
+    for (uint32_t j = gw; j < ni; j += nw) {
+        const uint32_t x = a.touch_in[j];
+        const uint2 m = a.in_meta[x];
+        const uint32_t start = a.hole_in[x];
+        if (start >= m.y || m.y - start < 2u) continue;
+        const uint32_t t = m.y - start;
+        if (t > 64u) {
+            if (lane == 0) a.tail_q[atomicAdd(&a.ctr->n_tail_q, 1u)] = x;
+            continue;
+        }
+        uint32_t *row = a.in_pool + m.x + start;
+        float *wr = a.in_w ? a.in_w + m.x + start : nullptr;
+        const bool mine = (uint32_t)lane < t;
+        const uint32_t id = mine ? row[lane] : 0xFFFFFFFFu;
+        const float wv = (mine && wr) ? wr[lane] : 0.0f;
+        uint32_t rank = 0;
+        for (uint32_t k = 0; k < t; ++k) rank += (__shfl(id, (int)k) < id) ? 1u : 0u;
+        if (mine) {
+            row[rank] = id;
+            if (wr) wr[rank] = wv;
+        }
+    }
+}
+
+// one workgroup per queued row: the appended entries are copied aside, every one counts the smaller ids
+// (the copy is read through LDS, 4096 at a time) and goes to that position
+__global__ __launch_bounds__(1024) void k_sort_long_tails(MutArgs a) {
+    __shared__ uint32_t s_ids[4096];
+    __shared__ uint32_t s_base;
+    if (a.ctr->abort_flag) return;
+    const uint32_t tid = threadIdx.x;
+    const uint32_t n = min(a.ctr->n_tail_q, a.touch_cap);
+    for (uint32_t q = blockIdx.x; q < n; q += gridDim.x) {
+        const uint32_t x = a.tail_q[q];
+        const uint2 m = a.in_meta[x];
+        const uint32_t start = a.hole_in[x];
+        const uint32_t t = m.y - start;
+        __syncthreads();
+        if (tid == 0) s_base = atomicAdd(&a.ctr->tail_top, t);
+        __syncthreads();
+        const uint32_t base = s_base;
+        if ((unsigned long long)base + t > a.tail_cap) {     // cannot happen: a batch appends at most n_ops entries
+            if (tid == 0) a.ctr->error = 10;
+            continue;
+        }
+        uint32_t *row = a.in_pool + m.x + start;
+        float *wr = a.in_w ? a.in_w + m.x + start : nullptr;
+        for (uint32_t i = tid; i < t; i += 1024) {
+            a.tail_ids[base + i] = row[i];
+            if (wr) a.tail_w[base + i] = wr[i];
+        }
+        __syncthreads();
+        for (uint32_t eb = 0; eb < t; eb += 1024) {
+            const uint32_t i = eb + tid;
+            const uint32_t my = (i < t) ? a.tail_ids[base + i] : 0u;
+            uint32_t rank = 0;
+            for (uint32_t tb = 0; tb < t; tb += 4096) {
+                const uint32_t cnt = min(4096u, t - tb);
+                __syncthreads();
+                for (uint32_t k = tid; k < cnt; k += 1024) s_ids[k] = a.tail_ids[base + tb + k];
+                __syncthreads();
+                if (i < t)
+                    for (uint32_t k = 0; k < cnt; ++k) rank += (s_ids[k] < my) ? 1u : 0u;
+            }
+            if (i < t) {
+                row[rank] = my;
+                if (wr) wr[rank] = a.tail_w[base + i];
+            }
+        }
+    }
 }
 
 // X^l[v] += sign * H^{l-1}[u] for every changed edge and every layer, taken
@@ -895,6 +1034,65 @@ __global__ __launch_bounds__(256) void k_struct_scatter(MutArgs a) {
     }
 }
 
+// Deterministic mode: the same terms without atomics. The changed edges are sorted by (sink, source) - a piece of a
+// batch holds at most one operation per edge, so the keys are distinct and the order is a function of the piece -
+// and the wavefront that finds the first entry of a sink adds that sink's terms one after the other, for every
+// layer, with plain loads and stores; eight source rows are in flight at a time.
+__global__ void k_struct_keys(MutArgs a) {
+    const uint32_t e = blockIdx.x * blockDim.x + threadIdx.x;
+    if (e >= a.n_sort) return;
+    const uint32_t n = a.ctr->abort_flag ? 0u : min(a.ctr->n_struct, a.struct_cap);
+    a.sk_in[e] = (e < n) ? (((unsigned long long)a.st_dst[e] << 32) | a.st_src[e]) : ~0ull;
+    a.sv_in[e] = (e < n) ? a.st_unit[e] : 0.0f;
+}
+
+__global__ __launch_bounds__(256) void k_struct_ordered(MutArgs a) {
+    if (a.ctr->abort_flag) return;
+    constexpr int G = 8;
+    const int lane = rp_lane();
+    const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    const uint32_t n = min(min(a.ctr->n_struct, a.struct_cap), a.n_sort);
+    for (uint32_t e0 = gw; e0 < n; e0 += nw) {
+        const uint32_t v = (uint32_t)(a.sk_out[e0] >> 32);
+        if (e0 > 0 && (uint32_t)(a.sk_out[e0 - 1] >> 32) == v) continue;   // not the sink's first entry
+        uint32_t len = 1;                                                  // entries of this sink
+        for (bool more = true; more;) {
+            const uint32_t f = e0 + len + (uint32_t)lane;
+            const unsigned long long other = __ballot(f >= n || (uint32_t)(a.sk_out[f] >> 32) != v);
+            if (other) {
+                len += (uint32_t)__ffsll((long long)other) - 1u;
+                more = false;
+            } else len += 64u;
+        }
+        for (uint32_t l = 1; l <= a.L; ++l) {
+            if ((a.mono_mask >> l) & 1u) continue;
+            const float *Tl = a.T[l];
+            const uint32_t w = Tl ? a.xw[l] : a.d[l - 1];
+            for (uint32_t c0 = 0; c0 < w; c0 += 64) {
+                const uint32_t col = c0 + (uint32_t)lane;
+                float *xp = a.X[l] + (size_t)v * w + col;
+                float x = (col < w) ? *xp : 0.0f;
+                for (uint32_t j0 = 0; j0 < len; j0 += G) {
+                    float val[G], sg[G];
+#pragma unroll
+                    for (int g = 0; g < G; ++g) {
+                        const uint32_t e = e0 + min(j0 + (uint32_t)g, len - 1u);
+                        const uint32_t u = (uint32_t)a.sk_out[e];
+                        sg[g] = (j0 + (uint32_t)g < len) ? a.sv_out[e] : 0.0f;
+                        val[g] = 0.0f;
+                        if (col < w && sg[g] != 0.0f)
+                            val[g] = Tl ? Tl[(size_t)u * w + col] : rp_load_h(a.H[l - 1], a.store, (size_t)u * w + col);
+                    }
+#pragma unroll
+                    for (int g = 0; g < G; ++g)
+                        if (sg[g] != 0.0f) x += sg[g] * val[g];
+                }
+                if (col < w) *xp = x;
+            }
+        }
+    }
+}
+
 __global__ void k_batch_reset(DevCtr *ctr, uint32_t *bitmaps, size_t n_bitmap_words) {
     size_t stride = (size_t)gridDim.x * blockDim.x;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n_bitmap_words; i += stride) bitmaps[i] = 0;
@@ -919,6 +1117,7 @@ __global__ void k_batch_reset(DevCtr *ctr, uint32_t *bitmaps, size_t n_bitmap_wo
         ctr->n_vadd = 0;
         ctr->abort_flag = 0;
         ctr->range_rows = 0;
+        ctr->n_tail_q = ctr->tail_top = 0;
         for (int k = 0; k < 3; ++k)
             for (int l = 0; l <= RIPPLE_MAX_LAYERS; ++l) ctr->mono[k][l] = 0;
     }
@@ -987,6 +1186,16 @@ static MutArgs make_args(ripple_ctx *c, uint32_t n_ops) {
         if (c->layers[l - 1].agg == RIPPLE_AGG_WSUM) a.wsum_mask |= 1u << l;
     }
     a.d0_old = rp_layer_mono(c, 1) ? 1 : 0;
+    a.det = c->opt_deterministic;
+    a.tail_ids = c->tail_ids;
+    a.tail_q = c->tail_q;
+    a.tail_w = c->tail_w;
+    a.tail_cap = c->ops_cap;
+    a.sk_in = c->sk_in;
+    a.sk_out = c->sk_out;
+    a.sv_in = c->sv_in;
+    a.sv_out = c->sv_out;
+    a.n_sort = 0;
     return a;
 }
 
@@ -1016,12 +1225,24 @@ void rp_launch_mutate(ripple_ctx *c, uint32_t n_ops, bool has_vertex_add, bool h
     }
     hipLaunchKernelGGL(k_apply_edges, dim3(tb), dim3(256), 0, s, a);
     int t = rp_timer_begin(c);
-    if (!c->opt_deterministic)                     // that mode recomputes the rows with a changed in-edge instead
-    hipLaunchKernelGGL(k_struct_scatter, dim3(has_vertex_del ? big : std::min<uint32_t>(big, rp_div_up((uint64_t)n_ops * c->L, 4))),
-                       dim3(256), 0, s, a);
+    if (c->opt_deterministic) {
+        // without vertex deletions a piece changes at most one edge per operation; with them, any number up to the lists' size
+        a.n_sort = has_vertex_del ? c->struct_cap : std::min<uint32_t>(n_ops, c->struct_cap);
+        hipLaunchKernelGGL(k_struct_keys, dim3(rp_div_up(a.n_sort, 256)), dim3(256), 0, s, a);
+        rp_sort_pairs_u64(c, c->sk_in, c->sk_out, c->sv_in, c->sv_out, a.n_sort, c->sort_tmp, c->sort_tmp_bytes);
+        hipLaunchKernelGGL(k_struct_ordered, dim3(std::min<uint32_t>(big, rp_div_up(a.n_sort, 4))), dim3(256), 0, s, a);
+    } else {
+        hipLaunchKernelGGL(k_struct_scatter, dim3(has_vertex_del ? big : std::min<uint32_t>(big, rp_div_up((uint64_t)n_ops * c->L, 4))),
+                           dim3(256), 0, s, a);
+    }
     rp_timer_end(c, t, RIPPLE_PH_STRUCT, 0);
     if (has_vertex_or_feat) hipLaunchKernelGGL(k_apply_vertices, dim3(wb), dim3(256), 0, s, a);
     hipLaunchKernelGGL(k_cleanup_rows, dim3(has_vertex_del ? big : std::min<uint32_t>(big, rp_div_up(2 * (uint64_t)n_ops, 4))),
                        dim3(256), 0, s, a);
     hipLaunchKernelGGL(k_apply_adds, dim3(tb), dim3(256), 0, s, a);
+    if (c->opt_deterministic) {
+        hipLaunchKernelGGL(k_sort_tails, dim3(has_vertex_del ? big : std::min<uint32_t>(big, rp_div_up((uint64_t)n_ops, 4))),
+                           dim3(256), 0, s, a);
+        hipLaunchKernelGGL(k_sort_long_tails, dim3(c->n_cu), dim3(1024), 0, s, a);
+    }
 }

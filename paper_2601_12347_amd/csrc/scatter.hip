@@ -151,6 +151,13 @@ struct PullArgs {
     DevCtr *ctr;
     uint32_t l;
     int mode, ratio, allow_disc;
+    // deterministic variants only
+    const uint32_t *bm_rec;        // destinations that are recomputed from all their in-neighbours (bootstrap inference), or null
+    const void *Hprev;             // what a recomputed row sums: rows of H^{l-1} (storage format `store`) ...
+    const float *R;                // ... or, for a project-first layer, of T (what every vertex has sent so far); stride d
+    int store;
+    uint32_t *side_v;              // per wavefront: the destinations of its first and last in-edge, if it has sums for them
+    float *side_acc;               // ... and those sums, d floats per entry
 };
 
 // The part both pull kernels share: which in-edges a chunk holds. Lane j describes row i_lo + j of the
@@ -225,10 +232,26 @@ struct PullScan {
     }
 };
 
+// DET = 1, the deterministic mode's form of both pull kernels. Float addition does not commute bit for bit, so
+// every sum has to be taken in an order that is a function of the graph and the batches alone:
+//   * the graph store keeps the order of an in-row such a function (rows built in the order the edges were given,
+//     appended entries put in id order, holes filled by a fixed rule), the list of destinations is ascending, and
+//     the cut of the in-edge space into chunks and of the chunks into runs per wavefront depends on their number
+//     and the grid only;
+//   * a wavefront carries a destination's partial sum from chunk to chunk, so it finishes every destination once.
+//     Only the destinations of its first and its last in-edge can have in-edges in another wavefront's run; their
+//     sums go to two side entries per wavefront instead of memory, and k_pull_fixup adds the entries of one
+//     destination in wavefront order. All other rows are written with plain loads and stores by their only writer.
+// The changed edges' structural terms have been added before the first hop, in (sink, source) order (k_struct_ordered).
+// Bootstrap inference runs the same kernels with every destination marked as recomputed: every in-edge of such a
+// row contributes, with the source's current row (of H^{l-1}, or of T for a project-first layer) in place of a
+// message, and the sum replaces the row. The hop is always pulled.
+//
 // WT = 1: every message is multiplied by its edge's weight (weighted sum, m = alpha (h - h_old), Sec. 3.3.3)
-template <int NJ, int DISC, int WT>
+template <int NJ, int DISC, int WT, int DET>
 __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
-    if (rp_hop_mode(a.ctr, a.l, a.d, a.mode, a.ratio, a.allow_disc) != (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL)) return;
+    static_assert(!DET || (!DISC && !WT), "the deterministic form pulls into A_l, unweighted");
+    if (!DET && rp_hop_mode(a.ctr, a.l, a.d, a.mode, a.ratio, a.allow_disc) != (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL)) return;
     const uint32_t count = *a.count_ptr;
     if (count == 0) return;
     if (blockIdx.x == 0 && threadIdx.x == 0) a.ctr->hop_mode[a.l] = 1u + (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL);
@@ -243,19 +266,71 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
     const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
     const uint32_t per = (n_chunks + nw - 1) / nw;
     const uint32_t c_begin = min(n_chunks, gw * per), c_end = min(n_chunks, c_begin + per);
-    if (c_begin >= c_end) return;
+    if (c_begin >= c_end) {
+        if (DET && lane == 0) a.side_v[2 * gw] = a.side_v[2 * gw + 1] = 0xFFFFFFFFu;
+        return;
+    }
     PullScan<T, WT> scan;
     scan.begin(a, count, c_begin, lane);
+    constexpr uint32_t NONE = 0xFFFFFFFFu;
+    uint32_t cur = NONE;                                    // destination whose partial sum is held
+    bool cur_rec = false;                                   // ... and whether it is recomputed (DET)
+    float acc[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
+    // DET: the destinations of this run's first and last in-edge, and whether a sum was left for them
+    uint32_t v_head = NONE, v_tail = NONE;
+    bool wrote_head = false, wrote_tail = false;
+    if (DET) {
+        v_head = (uint32_t)__shfl((int)scan.rv, 0);
+        v_tail = a.list[rp_seg_search_wave(a.ioff, 0, count - 1, min(total, c_end * PULL_CHUNK) - 1u)];
+    }
+    auto flush = [&]() {
+        float *xr = a.X + (size_t)cur * d;
+        if (!DET) {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const uint32_t col = lane + 64 * j;
+                if (col < d && acc[j] != 0.0f) unsafeAtomicAdd(&xr[col], acc[j]);
+                acc[j] = 0.0f;
+            }
+            if (DISC && lane == 0) atomicOr(&a.bm_cur[cur >> 5], 1u << (cur & 31));   // once per receiver and chunk
+            return;
+        }
+        if (cur == v_head || cur == v_tail) {
+            const uint32_t slot = 2 * gw + (cur == v_head ? 0u : 1u);
+            if (cur == v_head) wrote_head = true;
+            else wrote_tail = true;
+            xr = a.side_acc + (size_t)slot * d;
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const uint32_t col = lane + 64 * j;
+                if (col < d) xr[col] = acc[j];
+                acc[j] = 0.0f;
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) {
+                const uint32_t col = lane + 64 * j;
+                if (col < d) xr[col] = cur_rec ? acc[j] : xr[col] + acc[j];
+                acc[j] = 0.0f;
+            }
+        }
+    };
     for (uint32_t c = c_begin; c < c_end; ++c) {
         const uint32_t e0 = c * PULL_CHUNK, e1 = min(total, e0 + PULL_CHUNK);
         uint32_t my_v[T], my_u[T];
         float my_w[WT ? T : 1];
         bool dirty[T];
+        bool rec[DET ? T : 1];
         scan.chunk(a, count, e0, e1, lane, my_v, my_u, my_w, dirty);
-        uint32_t cur = 0xFFFFFFFFu;                          // destination whose partial sum is held
-        float acc[NJ];
+        if (DET) {
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
+            for (int t = 0; t < T; ++t) {
+                rec[t] = a.bm_rec && e0 + 64 * t + lane < e1 && rp_bit(a.bm_rec, my_v[t]);
+                dirty[t] = dirty[t] || rec[t];
+            }
+        }
 #pragma unroll
         for (int t = 0; t < T; ++t) {
             unsigned long long mask = __ballot(dirty[t]);
@@ -275,10 +350,16 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
 #pragma unroll
                 for (int g = 0; g < G; ++g) {
                     const uint32_t uk = __shfl(my_u[t], kk[g]);
+                    const bool rk = DET && __shfl((int)rec[DET ? t : 0], kk[g]) != 0;
 #pragma unroll
                     for (int j = 0; j < NJ; ++j) {
                         const uint32_t col = lane + 64 * j;
-                        r[g][j] = (g < n && col < d) ? a.D[(size_t)uk * a.ldd + col] : 0.0f;
+                        float x = 0.0f;
+                        if (g < n && col < d) {
+                            if (rk) x = a.R ? a.R[(size_t)uk * d + col] : rp_load_h(a.Hprev, a.store, (size_t)uk * d + col);
+                            else x = a.D[(size_t)uk * a.ldd + col];
+                        }
+                        r[g][j] = x;
                     }
                 }
 #pragma unroll
@@ -286,17 +367,9 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
                     if (g < n) {
                         const uint32_t vk = __shfl(my_v[t], kk[g]);
                         if (vk != cur) {                     // the destination changes: flush its partial sum
-                            if (cur != 0xFFFFFFFFu) {
-                                float *xr = a.X + (size_t)cur * d;
-#pragma unroll
-                                for (int j = 0; j < NJ; ++j) {
-                                    const uint32_t col = lane + 64 * j;
-                                    if (col < d && acc[j] != 0.0f) unsafeAtomicAdd(&xr[col], acc[j]);
-                                    acc[j] = 0.0f;
-                                }
-                                if (DISC && lane == 0) atomicOr(&a.bm_cur[cur >> 5], 1u << (cur & 31));   // once per receiver and chunk
-                            }
+                            if (cur != NONE) flush();
                             cur = vk;
+                            if (DET) cur_rec = __shfl((int)rec[DET ? t : 0], kk[g]) != 0;
                         }
                         // the weight is fetched again here rather than kept per row in flight (registers)
                         const float wk = WT ? __shfl(my_w[t], kk[g]) : 1.0f;
@@ -306,16 +379,18 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
                 }
             }
         }
-        if (cur != 0xFFFFFFFFu) {
-            float *xr = a.X + (size_t)cur * d;
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-                const uint32_t col = lane + 64 * j;
-                if (col < d && acc[j] != 0.0f) unsafeAtomicAdd(&xr[col], acc[j]);
-            }
-            if (DISC && lane == 0) atomicOr(&a.bm_cur[cur >> 5], 1u << (cur & 31));   // once per receiver and chunk
+        if (!DET) {                                          // one addition per receiver and chunk
+            if (cur != NONE) flush();
+            cur = NONE;
         }
         scan.advance();
+    }
+    if (DET) {
+        if (cur != NONE) flush();
+        if (lane == 0) {
+            a.side_v[2 * gw] = wrote_head ? v_head : NONE;
+            a.side_v[2 * gw + 1] = wrote_tail ? v_tail : NONE;
+        }
     }
 }
 
@@ -331,9 +406,10 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
 // counts). The destination and the partial sums carry over from chunk to chunk: a wavefront adds to a row once,
 // however many chunks the row's in-edges span.
 #define PULL4_QUADS 4                                       // quads (16 rows) in flight per wavefront
-template <int DISC, int WT>
+template <int DISC, int WT, int DET>
 __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
-    if (rp_hop_mode(a.ctr, a.l, a.d, a.mode, a.ratio, a.allow_disc) != (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL)) return;
+    static_assert(!DET || (!DISC && !WT), "the deterministic form pulls into A_l, unweighted");
+    if (!DET && rp_hop_mode(a.ctr, a.l, a.d, a.mode, a.ratio, a.allow_disc) != (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL)) return;
     const uint32_t count = *a.count_ptr;
     if (count == 0) return;
     if (blockIdx.x == 0 && threadIdx.x == 0) a.ctr->hop_mode[a.l] = 1u + (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL);
@@ -341,6 +417,7 @@ __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
     constexpr uint32_t NONE = 0xFFFFFFFFu;
     __shared__ uint32_t s_u[4][PULL_CHUNK], s_v[4][PULL_CHUNK];
     __shared__ float s_w[WT ? 4 : 1][WT ? PULL_CHUNK : 1];
+    __shared__ uint8_t s_r[DET ? 4 : 1][DET ? PULL_CHUNK : 1];   // DET: the entry's destination is recomputed
     const int lane = rp_lane(), wave = threadIdx.x >> 6;
     const uint32_t grp = (uint32_t)lane >> 4, sub = (uint32_t)lane & 15u;
     const uint32_t d = a.d;
@@ -349,12 +426,24 @@ __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
     const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
     const uint32_t per = (n_chunks + nw - 1) / nw;
     const uint32_t c_begin = min(n_chunks, gw * per), c_end = min(n_chunks, c_begin + per);
-    if (c_begin >= c_end) return;
+    if (c_begin >= c_end) {
+        if (DET && lane == 0) a.side_v[2 * gw] = a.side_v[2 * gw + 1] = NONE;
+        return;
+    }
     const uint32_t *msg = (const uint32_t *)a.D;
     const uint32_t my_col = 16u * grp + sub;                // the column this lane sends to memory
     const bool sends = grp < 3u && my_col < d;
     uint32_t cur = NONE;                                    // destination being summed (the same in all lanes)
+    bool cur_rec = false;                                   // ... and whether it is recomputed (DET)
     float acc0 = 0.0f, acc1 = 0.0f, acc2 = 0.0f;            // this group's partial sums of columns sub, 16 + sub, 32 + sub
+    PullScan<T, WT> scan;
+    scan.begin(a, count, c_begin, lane);
+    uint32_t v_head = NONE, v_tail = NONE;                  // DET: see k_scatter_pull
+    bool wrote_head = false, wrote_tail = false;
+    if (DET) {
+        v_head = (uint32_t)__shfl((int)scan.rv, 0);
+        v_tail = a.list[rp_seg_search_wave(a.ioff, 0, count - 1, min(total, c_end * PULL_CHUNK) - 1u)];
+    }
     auto flush = [&]() {
         acc0 += __shfl_xor(acc0, 16);
         acc1 += __shfl_xor(acc1, 16);
@@ -363,12 +452,19 @@ __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
         acc1 += __shfl_xor(acc1, 32);
         acc2 += __shfl_xor(acc2, 32);
         const float mine = grp == 0u ? acc0 : (grp == 1u ? acc1 : acc2);
-        if (sends && mine != 0.0f) unsafeAtomicAdd(&a.X[(size_t)cur * d + my_col], mine);
-        if (DISC && lane == 0) atomicOr(&a.bm_cur[cur >> 5], 1u << (cur & 31));
+        if (!DET) {
+            if (sends && mine != 0.0f) unsafeAtomicAdd(&a.X[(size_t)cur * d + my_col], mine);
+            if (DISC && lane == 0) atomicOr(&a.bm_cur[cur >> 5], 1u << (cur & 31));
+        } else if (cur == v_head || cur == v_tail) {
+            if (cur == v_head) wrote_head = true;
+            else wrote_tail = true;
+            if (sends) a.side_acc[(size_t)(2 * gw + (cur == v_head ? 0u : 1u)) * d + my_col] = mine;
+        } else if (sends) {
+            float *x = &a.X[(size_t)cur * d + my_col];
+            *x = cur_rec ? mine : *x + mine;
+        }
         acc0 = acc1 = acc2 = 0.0f;
     };
-    PullScan<T, WT> scan;
-    scan.begin(a, count, c_begin, lane);
     for (uint32_t c = c_begin; c < c_end; ++c) {
         const uint32_t e0 = c * PULL_CHUNK, e1 = min(total, e0 + PULL_CHUNK);
         uint32_t my_v[T], my_u[T];
@@ -379,12 +475,18 @@ __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
         uint32_t n = 0;
 #pragma unroll
         for (int t = 0; t < T; ++t) {
+            bool rec = false;
+            if (DET) {
+                rec = a.bm_rec && e0 + 64 * t + lane < e1 && rp_bit(a.bm_rec, my_v[t]);
+                dirty[t] = dirty[t] || rec;
+            }
             const unsigned long long mask = __ballot(dirty[t]);
             const uint32_t pos = n + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
             if (dirty[t]) {
                 s_u[wave][pos] = my_u[t];
                 s_v[wave][pos] = my_v[t];
                 if (WT) s_w[wave][pos] = my_w[t];
+                if (DET) s_r[wave][pos] = rec ? 1 : 0;
             }
             n += (uint32_t)__popcll(mask);
         }
@@ -398,13 +500,24 @@ __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
             uint32_t vk[PULL4_QUADS];
             float wk[PULL4_QUADS];
             uint2 ch[PULL4_QUADS];
+            bool rk[PULL4_QUADS];
+            float tv[DET ? PULL4_QUADS : 1][3];              // DET: the three columns of a recomputed row's source
 #pragma unroll
             for (int r = 0; r < PULL4_QUADS; ++r) {          // entries past the list's end repeat its last one: a valid row, not used
                 const uint32_t idx = min(4u * (k0 + r) + grp, n - 1u);
                 const uint32_t uk = s_u[wave][idx];
                 vk[r] = s_v[wave][idx];
                 if (WT) wk[r] = s_w[wave][idx];
-                ch[r] = *(const uint2 *)(msg + (size_t)uk * RP_MSG_WORDS + 2u * sub);
+                rk[r] = DET && s_r[DET ? wave : 0][DET ? idx : 0] != 0;
+                if (DET && rk[r]) {
+                    const float *t = a.R + (size_t)uk * d;
+                    tv[DET ? r : 0][0] = t[sub];
+                    tv[DET ? r : 0][1] = t[16u + sub];
+                    tv[DET ? r : 0][2] = (32u + sub < d) ? t[32u + sub] : 0.0f;
+                    ch[r] = make_uint2(0u, 0u);
+                } else {
+                    ch[r] = *(const uint2 *)(msg + (size_t)uk * RP_MSG_WORDS + 2u * sub);
+                }
             }
 #pragma unroll
             for (int r = 0; r < PULL4_QUADS; ++r) {
@@ -412,6 +525,11 @@ __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
                 if (k < n_quads) {
                     float v0, v1, v2;
                     rp_msg_decode(ch[r], v0, v1, v2);
+                    if (DET && rk[r]) {
+                        v0 = tv[DET ? r : 0][0];
+                        v1 = tv[DET ? r : 0][1];
+                        v2 = tv[DET ? r : 0][2];
+                    }
                     if (WT) {
                         v0 *= wk[r];
                         v1 *= wk[r];
@@ -431,6 +549,7 @@ __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
                                 if (vg != cur) {
                                     if (cur != NONE) flush();
                                     cur = vg;
+                                    if (DET) cur_rec = __builtin_amdgcn_readlane((int)rk[r], 16 * (int)g) != 0;
                                 }
                                 if (grp == g) {
                                     acc0 += v0;
@@ -447,6 +566,71 @@ __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
         scan.advance();
     }
     if (cur != NONE) flush();
+    if (DET && lane == 0) {
+        a.side_v[2 * gw] = wrote_head ? v_head : NONE;
+        a.side_v[2 * gw + 1] = wrote_tail ? v_tail : NONE;
+    }
+}
+
+// Deterministic mode, after a DET pull: the side entries (two per wavefront, in wavefront order; entries of one
+// destination are neighbours, apart from empty ones between them) are added up per destination in that order
+// and the sum is added to the row, or replaces it if the row is recomputed. One wavefront per entry; the one
+// that holds a destination's first entry does the work. Recomputed rows without any in-edge are zeroed here too:
+// no in-edge, so the pull never met them.
+__global__ __launch_bounds__(256) void k_pull_fixup(PullArgs a, uint32_t n_entries) {
+    constexpr uint32_t NONE = 0xFFFFFFFFu;
+    const uint32_t count = *a.count_ptr;
+    if (count == 0) return;
+    const int lane = rp_lane();
+    const uint32_t d = a.d;
+    const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    for (uint32_t i = gw * 64u + lane; a.bm_rec && i < count; i += nw * 64u) {
+        const uint32_t v = a.list[i];
+        if (a.in_meta[v].y == 0 && rp_bit(a.bm_rec, v))
+            for (uint32_t c = 0; c < d; ++c) a.X[(size_t)v * d + c] = 0.0f;
+    }
+    for (uint32_t k = gw; k < n_entries; k += nw) {
+        const uint32_t v = a.side_v[k];
+        if (v == NONE) continue;
+        // the nearest entry before k that is not empty: the same destination means k is not the first
+        bool first = true;
+        for (uint32_t b0 = k; b0 > 0;) {
+            const uint32_t b = b0 - 1u - (uint32_t)lane;                 // lane 0 looks at the nearest one
+            const uint32_t val = ((uint32_t)lane < b0) ? a.side_v[b] : NONE;
+            const unsigned long long m = __ballot(val != NONE);
+            if (m) {
+                first = (uint32_t)__shfl((int)val, __ffsll((long long)m) - 1) != v;
+                break;
+            }
+            b0 = b0 > 64u ? b0 - 64u : 0u;
+        }
+        if (!first) continue;
+        const bool rec = a.bm_rec && rp_bit(a.bm_rec, v);
+        for (uint32_t c0 = 0; c0 < d; c0 += 64) {
+            const uint32_t col = c0 + lane;
+            float t = (col < d) ? a.side_acc[(size_t)k * d + col] : 0.0f;
+            bool more = true;
+            for (uint32_t f0 = k + 1; f0 < n_entries && more; f0 += 64) {
+                const uint32_t f = f0 + (uint32_t)lane;
+                const uint32_t val = (f < n_entries) ? a.side_v[f] : NONE;
+                unsigned long long same = __ballot(val == v);
+                const unsigned long long other = __ballot(val != NONE && val != v);
+                if (other) {                                             // entries past the first other destination are not ours
+                    same &= (1ull << (__ffsll((long long)other) - 1)) - 1ull;
+                    more = false;
+                }
+                while (same) {
+                    const uint32_t e = f0 + (uint32_t)(__ffsll((long long)same) - 1);
+                    same &= same - 1;
+                    if (col < d) t += a.side_acc[(size_t)e * d + col];
+                }
+            }
+            if (col < d) {
+                float *x = &a.X[(size_t)v * d + col];
+                *x = rec ? t : *x + t;
+            }
+        }
+    }
 }
 
 // discover = false: pull into A_l (the hop's list). true: scan every live vertex (c->all_list and
@@ -475,22 +659,61 @@ void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow
     a.in_w = wt ? c->in_w : nullptr;
 #define PULL_CASE(NJ)                                                                                      \
     do {                                                                                                   \
-        if (discover && wt) hipLaunchKernelGGL((k_scatter_pull<NJ, 1, 1>), grid, block, 0, c->stream, a);  \
-        else if (discover) hipLaunchKernelGGL((k_scatter_pull<NJ, 1, 0>), grid, block, 0, c->stream, a);   \
-        else if (wt) hipLaunchKernelGGL((k_scatter_pull<NJ, 0, 1>), grid, block, 0, c->stream, a);         \
-        else hipLaunchKernelGGL((k_scatter_pull<NJ, 0, 0>), grid, block, 0, c->stream, a);                 \
+        if (discover && wt) hipLaunchKernelGGL((k_scatter_pull<NJ, 1, 1, 0>), grid, block, 0, c->stream, a);  \
+        else if (discover) hipLaunchKernelGGL((k_scatter_pull<NJ, 1, 0, 0>), grid, block, 0, c->stream, a);   \
+        else if (wt) hipLaunchKernelGGL((k_scatter_pull<NJ, 0, 1, 0>), grid, block, 0, c->stream, a);         \
+        else hipLaunchKernelGGL((k_scatter_pull<NJ, 0, 0, 0>), grid, block, 0, c->stream, a);                 \
     } while (0)
     if (packed) {
-        if (discover && wt) hipLaunchKernelGGL((k_scatter_pull4<1, 1>), grid, block, 0, c->stream, a);
-        else if (discover) hipLaunchKernelGGL((k_scatter_pull4<1, 0>), grid, block, 0, c->stream, a);
-        else if (wt) hipLaunchKernelGGL((k_scatter_pull4<0, 1>), grid, block, 0, c->stream, a);
-        else hipLaunchKernelGGL((k_scatter_pull4<0, 0>), grid, block, 0, c->stream, a);
+        if (discover && wt) hipLaunchKernelGGL((k_scatter_pull4<1, 1, 0>), grid, block, 0, c->stream, a);
+        else if (discover) hipLaunchKernelGGL((k_scatter_pull4<1, 0, 0>), grid, block, 0, c->stream, a);
+        else if (wt) hipLaunchKernelGGL((k_scatter_pull4<0, 1, 0>), grid, block, 0, c->stream, a);
+        else hipLaunchKernelGGL((k_scatter_pull4<0, 0, 0>), grid, block, 0, c->stream, a);
     } else if (a.d <= 64) PULL_CASE(1);
     else if (a.d <= 128) PULL_CASE(2);
     else if (a.d <= 256) PULL_CASE(4);
     else if (a.d <= 512) PULL_CASE(8);
     else PULL_CASE(16);
 #undef PULL_CASE
+}
+
+// Deterministic mode: the hop is pulled into A_l (bootstrap: into every live vertex, all of them recomputed;
+// c->all_list and c->ioff_all must have been produced by rp_launch_alive_list), then the rows that more than
+// one wavefront had in-edges of are finished.
+void rp_launch_scatter_pull_det(ripple_ctx *c, uint32_t l, bool bootstrap) {
+    const LayerDev &ly = c->layers[l - 1];
+    PullArgs a;
+    a.list = bootstrap ? c->all_list : c->list[l];
+    a.count_ptr = bootstrap ? &c->ctr->n_all : &c->ctr->a[l];
+    a.ioff = bootstrap ? c->ioff_all : c->ioff[l];
+    a.in_meta = c->in_meta;
+    a.in_pool = c->in_pool;
+    a.in_w = nullptr;
+    a.bm_prev = c->bm[l - 1];
+    a.bm_cur = c->bm[l];
+    const bool packed = ly.proj && ly.packed;
+    a.D = packed ? (const float *)c->MSG : (ly.proj ? c->PD : c->D[(l - 1) & 1]);
+    a.d = c->xw[l];
+    a.ldd = ly.proj ? c->pd_ld : a.d;
+    a.X = c->X[l];
+    a.ctr = c->ctr;
+    a.l = l;
+    a.mode = a.ratio = a.allow_disc = 0;
+    a.bm_rec = bootstrap ? c->alive : nullptr;              // bootstrap: every listed vertex is recomputed; batches: none is
+    a.Hprev = c->H[l - 1];
+    a.R = ly.proj ? ly.T : nullptr;
+    a.store = c->store;
+    a.side_v = c->side_v;
+    a.side_acc = c->side_acc;
+    dim3 grid(c->n_cu * 8), block(256);
+    const uint32_t n_entries = 2u * grid.x * 4u;            // two per wavefront
+    if (packed) hipLaunchKernelGGL((k_scatter_pull4<0, 0, 1>), grid, block, 0, c->stream, a);
+    else if (a.d <= 64) hipLaunchKernelGGL((k_scatter_pull<1, 0, 0, 1>), grid, block, 0, c->stream, a);
+    else if (a.d <= 128) hipLaunchKernelGGL((k_scatter_pull<2, 0, 0, 1>), grid, block, 0, c->stream, a);
+    else if (a.d <= 256) hipLaunchKernelGGL((k_scatter_pull<4, 0, 0, 1>), grid, block, 0, c->stream, a);
+    else if (a.d <= 512) hipLaunchKernelGGL((k_scatter_pull<8, 0, 0, 1>), grid, block, 0, c->stream, a);
+    else hipLaunchKernelGGL((k_scatter_pull<16, 0, 0, 1>), grid, block, 0, c->stream, a);
+    hipLaunchKernelGGL(k_pull_fixup, dim3(rp_div_up(n_entries, 4)), block, 0, c->stream, a, n_entries);
 }
 
 // ---------------------------------------------------------------------------------
@@ -569,252 +792,6 @@ void rp_launch_messages(ripple_ctx *c, uint32_t l) {
     hipLaunchKernelGGL(k_messages, dim3(grid), dim3(256), 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1], c->PD, c->pd_ld,
                        ly.T, c->xw[l], ly.packed, c->MSG);
 }
-
-// ---------------------------------------------------------------------------------
-// deterministic aggregation: one owner per destination, sources in a fixed order
-// ---------------------------------------------------------------------------------
-// Float addition does not commute bit for bit, and neither the atomics of the kernels above nor the
-// order of a row's entries (which depends on the order concurrent appends landed in) is the same
-// from run to run. Here one team (a wavefront; a 16-wavefront workgroup for rows of more than OWN_LONG entries)
-// owns a destination of A_l: it collects the sources that contribute, sorts them by a fixed key,
-// adds their rows in that order and writes the row with plain stores, so the result is a function
-// of the graph and the embeddings alone. Destinations in S (a changed in-edge) or V_added are
-// recomputed from all their in-neighbours' current rows, which needs no pre-batch values and no
-// list of changed edges (the structural scatter is not run in this mode); the others add the delta
-// rows of their dirty in-neighbours.
-// The key is a bijective hash of the vertex id, so that rows longer than the sort buffer can be
-// taken in ascending key ranges of even population whatever the ids look like; if a range still
-// overflows, the row starts over with twice as many ranges.
-#define OWN_LONG 1024u
-
-__device__ __forceinline__ uint32_t own_key(uint32_t x) {       // bijection on 32 bits
-    x ^= x >> 16;
-    x *= 0x7feb352du;
-    x ^= x >> 15;
-    x *= 0x846ca68bu;
-    x ^= x >> 16;
-    return x;
-}
-__device__ __forceinline__ uint32_t own_unkey(uint32_t x) {     // its inverse
-    x ^= x >> 16;
-    x *= 0x43021123u;
-    x ^= (x >> 15) ^ (x >> 30);
-    x *= 0x1d69e2a5u;
-    x ^= x >> 16;
-    return x;
-}
-
-struct OwnerArgs {
-    const uint32_t *list;          // A_l (TEAM 1) or the queue of long rows (TEAM 16)
-    const uint32_t *count_ptr;
-    uint32_t *queue, *queue_count; // long rows met by the TEAM 1 kernel
-    const uint2 *in_meta;
-    const uint32_t *in_pool;
-    const uint32_t *bm_prev;       // A_{l-1}
-    const uint32_t *bm_sink, *bm_vadd;
-    const float *D;                // delta rows of layer l-1, by vertex
-    const void *Hprev;             // H^{l-1}
-    int store;
-    uint32_t d;                    // row width (of D, H^{l-1} and X^l)
-    float *X;
-    DevCtr *ctr;
-};
-
-template <int TEAM>
-__device__ __forceinline__ void own_sync() {
-    if (TEAM == 1) __builtin_amdgcn_wave_barrier();
-    else __syncthreads();
-}
-
-// TEAM wavefronts per destination; CAP keys in LDS per team
-template <int NJ, int TEAM>
-__global__ __launch_bounds__(TEAM == 1 ? 256 : 1024) void k_scatter_owner(OwnerArgs a) {
-    constexpr int G = (NJ <= 2) ? 16 : (NJ <= 4 ? 8 : 4);      // rows in flight per wavefront
-    constexpr uint32_t CAP = (TEAM == 1) ? 1024u : 16384u;
-    constexpr int TT = TEAM * 64;                              // threads per team
-    __shared__ uint32_t s_keys[(TEAM == 1 ? 4 : 1) * CAP];
-    __shared__ uint32_t s_n[4], s_over[4];
-    __shared__ float s_part[(TEAM == 1) ? 1 : TEAM * NJ * 64];
-    const uint32_t count = *a.count_ptr;
-    const int lane = rp_lane(), wave = threadIdx.x >> 6;
-    const int tt = (TEAM == 1) ? lane : (int)threadIdx.x;     // thread within the team
-    const int slot = (TEAM == 1) ? wave : 0;                   // the team's counters
-    uint32_t *buf = s_keys + (TEAM == 1 ? wave * CAP : 0);
-    const uint32_t d = a.d;
-    const uint32_t team = (TEAM == 1) ? ((blockIdx.x * blockDim.x + threadIdx.x) >> 6) : blockIdx.x;
-    const uint32_t n_teams = (TEAM == 1) ? ((gridDim.x * blockDim.x) >> 6) : gridDim.x;
-    for (uint32_t i = team; i < count; i += n_teams) {
-        const uint32_t v = a.list[i];
-        const uint2 m = a.in_meta[v];
-        if (TEAM == 1 && m.y > OWN_LONG) {                     // left to the workgroup kernel
-            if (lane == 0) a.queue[atomicAdd(a.queue_count, 1u)] = v;
-            continue;
-        }
-        const bool recompute = rp_bit(a.bm_sink, v) || rp_bit(a.bm_vadd, v);
-        uint32_t bits = 0;                                     // 2^bits key ranges
-        while (((unsigned long long)(CAP / 4) << bits) < m.y) ++bits;
-        float acc[NJ];
-        for (;;) {                                             // until no range overflows
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
-            bool overflow = false;
-            for (uint32_t r = 0; r < (1u << bits) && !overflow; ++r) {
-                if (tt == 0) {
-                    s_n[slot] = 0;
-                    s_over[slot] = 0;
-                }
-                own_sync<TEAM>();
-                // collect the keys of the contributing sources that fall into range r, four blocks of the row per round
-                for (uint32_t base = 0; base < m.y; base += 4 * TT) {
-                    uint32_t key[4];
-                    bool take[4];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const uint32_t e = base + q * TT + tt;
-                        take[q] = false;
-                        key[q] = 0;
-                        if (e < m.y) {
-                            const uint32_t u = a.in_pool[m.x + e];
-                            key[q] = own_key(u);
-                            take[q] = (bits == 0 || (key[q] >> (32 - bits)) == r) && (recompute || rp_bit(a.bm_prev, u));
-                        }
-                    }
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        const unsigned long long mask = __ballot(take[q]);
-                        if (!mask) continue;
-                        const uint32_t k = (uint32_t)__popcll(mask);
-                        uint32_t pos = 0;
-                        if (lane == 0) pos = atomicAdd(&s_n[slot], k);
-                        pos = __shfl(pos, 0);
-                        if (pos + k > CAP) {
-                            if (lane == 0) s_over[slot] = 1;
-                        } else if (take[q]) {
-                            buf[pos + (uint32_t)__popcll(mask & ((1ull << lane) - 1ull))] = key[q];
-                        }
-                    }
-                }
-                own_sync<TEAM>();
-                const bool over = s_over[slot] != 0;
-                const uint32_t n = s_n[slot];
-                own_sync<TEAM>();                              // everyone has read the counters before they are reset
-                if (over) {
-                    overflow = true;
-                    break;
-                }
-                // ascending sort (bitonic, padded to a power of two)
-                uint32_t p2 = 64;
-                while (p2 < n) p2 <<= 1;
-                for (uint32_t x = n + tt; x < p2; x += TT) buf[x] = 0xFFFFFFFFu;
-                for (uint32_t k2 = 2; k2 <= p2 && n > 1; k2 <<= 1)
-                    for (uint32_t j2 = k2 >> 1; j2 > 0; j2 >>= 1) {
-                        own_sync<TEAM>();
-                        for (uint32_t x = tt; x < p2; x += TT) {
-                            const uint32_t y = x ^ j2;
-                            if (y > x) {
-                                const uint32_t kx = buf[x], ky = buf[y];
-                                if ((kx > ky) == ((x & k2) == 0)) {
-                                    buf[x] = ky;
-                                    buf[y] = kx;
-                                }
-                            }
-                        }
-                    }
-                own_sync<TEAM>();
-                // add the rows in key order: a wavefront takes every TEAM-th one, G in flight
-                float part[NJ];
-#pragma unroll
-                for (int j = 0; j < NJ; ++j) part[j] = 0.0f;
-                for (uint32_t j0 = (uint32_t)(TEAM == 1 ? 0 : wave); j0 < n; j0 += G * TEAM) {
-                    float rr[G][NJ];
-#pragma unroll
-                    for (int g = 0; g < G; ++g) {
-                        const uint32_t idx = j0 + g * TEAM;
-                        const uint32_t u = own_unkey(buf[min(idx, n - 1)]);
-#pragma unroll
-                        for (int j = 0; j < NJ; ++j) {
-                            const uint32_t col = lane + 64 * j;
-                            float x = 0.0f;
-                            if (idx < n && col < d)
-                                x = recompute ? rp_load_h(a.Hprev, a.store, (size_t)u * d + col) : a.D[(size_t)u * d + col];
-                            rr[g][j] = x;
-                        }
-                    }
-#pragma unroll
-                    for (int g = 0; g < G; ++g)
-#pragma unroll
-                        for (int j = 0; j < NJ; ++j) part[j] += rr[g][j];
-                }
-                if (TEAM == 1) {
-#pragma unroll
-                    for (int j = 0; j < NJ; ++j) acc[j] += part[j];
-                } else {                                       // the wavefronts' partial sums, always combined in the same order
-#pragma unroll
-                    for (int j = 0; j < NJ; ++j) s_part[(wave * NJ + j) * 64 + lane] = part[j];
-                    __syncthreads();
-#pragma unroll
-                    for (int j = 0; j < NJ; ++j) {
-                        float t = s_part[j * 64 + lane];
-                        for (int w = 1; w < TEAM; ++w) t += s_part[(w * NJ + j) * 64 + lane];
-                        acc[j] += t;
-                    }
-                }
-                own_sync<TEAM>();
-            }
-            if (!overflow) break;
-            if (++bits > 24) {                                 // cannot happen with distinct ids in a row
-                if (tt == 0) a.ctr->error = 9;
-                break;
-            }
-        }
-        if (TEAM == 1 || wave == 0) {
-            float *xr = a.X + (size_t)v * d;
-#pragma unroll
-            for (int j = 0; j < NJ; ++j) {
-                const uint32_t col = lane + 64 * j;
-                if (col < d) xr[col] = recompute ? acc[j] : xr[col] + acc[j];
-            }
-        }
-    }
-}
-
-// every destination of A_l by a wavefront, the long rows among them afterwards by a workgroup each.
-// bootstrap: every live vertex (listed in c->all_list, count in ctr->a[0]) is recomputed.
-void rp_launch_scatter_owner(ripple_ctx *c, uint32_t l, bool bootstrap) {
-    OwnerArgs a;
-    a.list = bootstrap ? c->all_list : c->list[l];
-    a.count_ptr = bootstrap ? &c->ctr->a[0] : &c->ctr->a[l];
-    a.queue = bootstrap ? c->list[0] : c->all_list; // scratch that is free at that point
-    a.queue_count = &c->ctr->n_all;
-    a.in_meta = c->in_meta;
-    a.in_pool = c->in_pool;
-    a.bm_prev = c->bm[l - 1];
-    a.bm_sink = bootstrap ? c->alive : c->bm_sink;  // "recompute" for every listed vertex
-    a.bm_vadd = bootstrap ? c->alive : c->bm_vadd;
-    a.D = c->D[(l - 1) & 1];
-    a.Hprev = c->H[l - 1];
-    a.store = c->store;
-    a.d = c->xw[l];
-    a.X = c->X[l];
-    a.ctr = c->ctr;
-    hipMemsetAsync(&c->ctr->n_all, 0, 4, c->stream);
-    OwnerArgs b = a;
-    b.list = a.queue;
-    b.count_ptr = &c->ctr->n_all;
-    dim3 grid(c->n_cu * 8), block(256);
-#define OWN_CASE(NJ)                                                                        \
-    do {                                                                                    \
-        hipLaunchKernelGGL((k_scatter_owner<NJ, 1>), grid, block, 0, c->stream, a);         \
-        hipLaunchKernelGGL((k_scatter_owner<NJ, 16>), dim3(c->n_cu), dim3(1024), 0, c->stream, b); \
-    } while (0)
-    if (a.d <= 64) OWN_CASE(1);
-    else if (a.d <= 128) OWN_CASE(2);
-    else if (a.d <= 256) OWN_CASE(4);
-    else if (a.d <= 512) OWN_CASE(8);
-    else OWN_CASE(16);
-#undef OWN_CASE
-}
-
 
 // ---------------------------------------------------------------------------------
 // max / min aggregation: keep, raise or recompute (Sec. 3.4.2)

@@ -515,14 +515,14 @@ def test_deterministic_mode_is_bit_reproducible(kind, widths, store):
     """With RIPPLE_OPT_DETERMINISTIC every aggregate row has one owner that adds its sources in a fixed
     order: two contexts fed the same operations must agree bit for bit after every batch (bootstrap
     included), and both must match the oracle like the default mode does. The graph has rows longer
-    than a wavefront owns (1,024 entries) and than the sort buffer takes at once, so the workgroup variant and the key ranges run too."""
+    than a wavefront owns (1,024 entries), so the workgroup variant runs too."""
     print("case deterministic", kind, store, flush=True)
     kw = dict(n=20000, e=240000, d0=widths[0], kind=kind, widths=widths, seed=81, slack=256, store=store,
               top_share=0.04, deterministic=True)
     pair, graph = make_pair(**kw)
     twin, _ = make_pair(**kw)
     deg_in, _ = rp.ripple_get_degrees(pair.ctx, 1, pair.cap)
-    assert deg_in.max() > 4096, "rows that need several key ranges would not be exercised"
+    assert deg_in.max() > 4096, "the workgroup variant would not be exercised"
     stream = make_stream(pair, graph, MIXV, 83)
     try:
         for l in range(pair.L + 1):
@@ -541,6 +541,70 @@ def test_deterministic_mode_is_bit_reproducible(kind, widths, store):
                                       rp.ripple_get_aggregates(twin.ctx, l, w, n_rows=twin.cap).view(np.uint32))
         pair.check_graph()
         pair.check_aggregates(tol=1e-3 if store == "bf16" else None)
+    finally:
+        pair.close()
+        twin.close()
+
+
+def _in_rows(ctx, cap, n_edges):
+    """The in-rows in storage order: for every sink, its sources as the store holds them."""
+    s, d, n = rp.ripple_export_edges(ctx, 1, n_edges + 16)
+    assert n == n_edges
+    return s[:n].astype(np.int64), d[:n].astype(np.int64)
+
+
+def test_deterministic_mode_keeps_in_rows_in_a_reproducible_order():
+    """The deterministic mode adds a row's sources in the order the in-row stores them, so that order has to
+    be a function of the input and the batches: rows are built in the order the edges were given, and
+    what a batch appends to a row ends up in ascending id order, whether it is a handful of entries (ranked by
+    a wavefront), more than 64 (copied aside by a workgroup) or more than 4,096 (several LDS tiles). Deletions
+    in the same rows and a second context fed the same batches are checked as well."""
+    print("case deterministic row order", flush=True)
+    kw = dict(n=9000, e=60000, d0=16, kind="sage_mean", widths=(16, 40, 10), seed=91, slack=64, deterministic=True)
+    pair, graph = make_pair(**kw)
+    twin, _ = make_pair(**kw)
+    src, dst = graph[0].astype(np.int64), graph[1].astype(np.int64)
+    try:
+        order = np.argsort(dst, kind="stable")
+        got_s, got_d = _in_rows(pair.ctx, pair.cap, len(src))
+        assert np.array_equal(got_d, dst[order]) and np.array_equal(got_s, src[order]), "rows are not in input order"
+        rng = np.random.default_rng(92)
+        have = set(zip(src.tolist(), dst.tolist()))
+        sinks = {5: 5000, 6: 300, 7: 40, 8: 2}               # sink -> edges it gains in one batch
+        ops = []
+        for v, k in sinks.items():
+            cand = [u for u in rng.permutation(9000).tolist() if (u, v) not in have][:k]
+            ops += [(ri.OP_EDGE_ADD, u, v, 0) for u in cand]
+        for v in (5, 6, 7):                                   # and loses: holes are filled before the appends
+            ins = src[dst == v]
+            ops += [(ri.OP_EDGE_DEL, int(u), v, 0) for u in ins[: min(3, len(ins))]]
+        ops = np.array(ops, dtype=np.uint32)
+        ops = ops[rng.permutation(len(ops))]
+        before_s, before_d = _in_rows(pair.ctx, pair.cap, len(src))
+        none = np.zeros((0, 16), dtype=np.float32)
+        res, rec, _ = pair.step(ops, none)
+        assert res.n_rejected == 0
+        rp.ripple_apply_updates(twin.ctx, ops, none)
+        n_edges = pair.ora.n_edges()
+        a_s, a_d = _in_rows(pair.ctx, pair.cap, n_edges)
+        b_s, b_d = _in_rows(twin.ctx, twin.cap, n_edges)
+        assert np.array_equal(a_s, b_s) and np.array_equal(a_d, b_d), "two runs store their in-rows differently"
+        for v, k in sinks.items():
+            row = a_s[a_d == v]
+            tail = row[len(row) - k:]
+            assert np.all(np.diff(tail) > 0), f"sink {v}: the {k} appended sources are not in ascending order"
+            old = set(before_s[before_d == v].tolist())
+            assert not (set(tail.tolist()) & old)
+        for l in range(pair.L + 1):
+            assert np.array_equal(pair.gpu_layer(l).view(np.uint32), twin.gpu_layer(l).view(np.uint32))
+        stream = make_stream(pair, graph, MIXV, 93)           # the stream does not know the edges above: some ops are rejected
+        ops2, payload2, _ = stream.next_batch(500)
+        pair.step(ops2, payload2)
+        rp.ripple_apply_updates(twin.ctx, ops2, payload2)
+        for l in range(pair.L + 1):
+            assert np.array_equal(pair.gpu_layer(l).view(np.uint32), twin.gpu_layer(l).view(np.uint32))
+        pair.check_graph()
+        pair.check_aggregates()
     finally:
         pair.close()
         twin.close()
