@@ -268,7 +268,7 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
         LayerDev &ly = c->layers[l];
         void *w[] = {ly.W0, ly.b0, ly.W1, ly.b1, ly.W0h, ly.W1h, ly.bzero, (ly.Wn != ly.W0) ? ly.Wn : nullptr, ly.PS,
                      ly.W0s, ly.W1s, (ly.Wns != ly.W0s) ? ly.Wns : nullptr,
-                     ly.att, ly.P, ly.ssrc, ly.sdst, ly.den, ly.T, ly.Wc, ly.bzero_c};
+                     ly.att, ly.P, ly.ssrc, ly.sdst, ly.den, ly.T, ly.Wc, ly.bzero_c, ly.Wc96};
         for (void *p : w)
             if (p) hipFree(p);
     }
@@ -411,6 +411,16 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
             RP_TRY(dev_alloc(c, &ly.Wc, wc.size(), false));
             RP_HIP(c, hipMemcpy(ly.Wc, wc.data(), wc.size() * 4, hipMemcpyHostToDevice));
             RP_TRY(dev_alloc(c, &ly.bzero_c, (size_t)128, true));
+            if (s.d_out <= 48) {
+                std::vector<float> w96((size_t)kp * 96, 0.0f);
+                for (uint32_t k = 0; k < s.d_in; ++k)
+                    for (uint32_t j = 0; j < s.d_out; ++j) {
+                        w96[(size_t)k * 96 + j] = s.W0[(size_t)k * s.d_out + j];
+                        w96[(size_t)k * 96 + 48 + j] = s.W0[(size_t)(s.d_in + k) * s.d_out + j];
+                    }
+                RP_TRY(dev_alloc(c, &ly.Wc96, w96.size(), false));
+                RP_HIP(c, hipMemcpy(ly.Wc96, w96.data(), w96.size() * 4, hipMemcpyHostToDevice));
+            }
         }
         if (s.d_hidden) {
             ly.K1pad = rp_round_up(s.d_hidden, 32);

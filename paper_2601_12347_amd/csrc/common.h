@@ -84,8 +84,10 @@ struct LayerDev {
     uint32_t selfc;
     float *PS;
     // project-first layers with a cached self term: [W_self | W_neigh] as one matrix [roundup(d_in,32) x 128] (W_neigh
-    // from column 64 on) and 128 zeros, so that one pass over the rows of A_{l-1} yields both products; else null
-    float *Wc, *bzero_c;
+    // from column 64 on) and 128 zeros, so that one pass over the rows of A_{l-1} yields both products; else null.
+    // Wc96: the same for d_out <= 48 as [roundup(d_in,32) x 96] with W_neigh from column 48 on (a quarter fewer
+    // matrix-core operations; used when many rows are expected), else null
+    float *Wc, *bzero_c, *Wc96;
     // attention layers: projected rows P[v] = H^{l-1}[v] W0 [n x d_out], scores a_src . P[v] and a_dst . P[v],
     // denominators of the softmax (the numerators are the layer's X rows); att = a_src then a_dst on the device
     float *att, *P, *ssrc, *sdst, *den;

@@ -57,7 +57,7 @@ struct TArgs {
     float *tmp_out;
     uint32_t tmp_out_ld;
     // two products from one pass over the rows (out_mode 2 only): the weight matrix holds a second block of
-    // columns from split_col on (a multiple of 64); columns [0, N1) go to tmp_out, columns [split_col, N) to
+    // columns from split_col on (a multiple of 4); columns [0, N1) go to tmp_out, columns [split_col, N) to
     // tmp_out2 as its columns 0 .. N - split_col - 1. split_col = 0: one block, N1 = N.
     uint32_t split_col, N1;
     float *tmp_out2;
@@ -369,7 +369,7 @@ __device__ __forceinline__ void epilogue_staged(const TArgs &a, floatx16 (&acc)[
                                                 const float *s_scale, uint32_t row0, uint32_t count, uint32_t n0, int wm,
                                                 int wn, int tid) {
     constexpr int C_LD = BN + 4;
-    constexpr int ITER = BM * BN / 4 / 256, U = (ITER >= 8) ? 4 : ITER / 2;
+    constexpr int ITER = BM * BN / 4 / 256, U = (ITER % 8 == 0) ? 4 : (ITER % 6 == 0) ? 3 : ITER / 2;
     static_assert(U >= 1 && ITER % (2 * U) == 0, "tile size");
     const int lane = tid & 63;
     const bool vec = (a.N & 3u) == 0 && (a.out_mode == 1 || (a.tmp_out_ld & 3u) == 0) &&
@@ -460,8 +460,8 @@ __global__ __launch_bounds__(256) void k_transform_addend_only(TArgs a) {
     else addend_only_rows<false>(a);
 }
 
-template <int WAVES_M, int WAVES_N, int TM, int TN, int STAGES, int MODE, int STORE>
-__global__ __launch_bounds__(256, 2) void k_transform_f32(TArgs a) {
+template <int WAVES_M, int WAVES_N, int TM, int TN, int STAGES, int MODE, int STORE, int MINB = 2>
+__global__ __launch_bounds__(256, MINB) void k_transform_f32(TArgs a) {
     constexpr int BM = WAVES_M * TM * 32, BN = WAVES_N * TN * 32;
     constexpr int NA = BM / 32, NB = BN / 32;              // float4 per thread per slice (A, B)
     constexpr bool TWO = (MODE == 2) || (MODE == 1 && STORE == 1);
@@ -1085,7 +1085,10 @@ static void launch_fast(ripple_ctx *c, const TArgs &a, bool narrow, uint32_t row
                            dim3(256), 0, c->stream, a);
         return;
     }
-    if (a.Npad >= 256 && !narrow) {
+    if (a.Npad == 96) {                                    // [W_self | W_neigh] of a narrow layer: three 32-column blocks per wavefront
+        hipLaunchKernelGGL((k_transform_f32<4, 1, 1, 3, 3, MODE, STORE>), dim3(tile_grid(c, rows_hint, 128, c->n_cu * 2), 1), dim3(256),
+                           0, c->stream, a);
+    } else if (a.Npad >= 256 && !narrow) {
         hipLaunchKernelGGL((k_transform_f32<1, 4, 2, 2, 3, MODE, STORE>), dim3(tile_grid(c, rows_hint, 64, c->n_cu * 2), a.Npad / 256),
                            dim3(256), 0, c->stream, a);
     } else if (a.Npad == 128 && !narrow) {
@@ -1222,7 +1225,14 @@ void rp_launch_project_both(ripple_ctx *c, uint32_t l, const uint32_t *list, con
     a.N1 = ly.d_out;
     a.tmp_out2 = bootstrap ? ly.T : c->PD;
     a.tmp_out2_ld = bootstrap ? ly.d_out : c->pd_ld;
-    launch_t(c, a, true, bootstrap ? c->n_cap : rp_rows_hint(c, l - 1));
+    const uint32_t hint = bootstrap ? c->n_cap : rp_rows_hint(c, l - 1);
+    if (ly.Wc96 && hint > 2048) {                  // many rows: the products are bound by the matrix cores, 96 columns instead of 128
+        a.W = ly.Wc96;
+        a.N = 48 + ly.d_out;
+        a.Npad = 96;
+        a.split_col = 48;
+    }
+    launch_t(c, a, true, hint);
 }
 
 // Attention layer l: P[v] = H^{l-1}[v] W0 for the listed vertices (fp32, no bias, no activation).
