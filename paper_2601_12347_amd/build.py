@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libripple.so")
-SOURCES = ["api.hip", "graph_store.hip", "frontier.hip", "scatter.hip", "attention.hip", "transform.hip", "peaks.hip", "order.hip"]
+SOURCES = ["api.hip", "graph_store.hip", "frontier.hip", "scatter.hip", "attention.hip", "transform.hip", "transform_stream.hip", "peaks.hip", "order.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function", "-Wno-unused-value",
          # packed fp32 instructions are kept out of the generated code on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -1347,6 +1347,9 @@ extern "C" ripple_status ripple_set_option(ripple_ctx *c, int option, int64_t va
         if (c->state != 1) return fail(c, RIPPLE_ESTATE, "packed messages must be chosen before load_model");
         c->opt_pack = value ? 1 : 0;
         return RIPPLE_OK;
+    case RIPPLE_OPT_STREAM_TRANSFORM:
+        c->opt_stream = value ? 1 : 0;
+        return RIPPLE_OK;
     case RIPPLE_OPT_PULL_RATIO:
         if (value < 1 || value > 1024) return fail(c, RIPPLE_EINVAL, "pull ratio must be in 1..1024");
         c->opt_pull_ratio = (int)value;
