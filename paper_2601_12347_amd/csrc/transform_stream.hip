@@ -3,19 +3,27 @@
 
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
 
-// Streaming variant for the shape that dominates large batches: x W with K = N = 256 (x = X^l[v], scaled for mean), fp32
-// rows, H updated in place (ADD: plus an unscaled cached row; DELTA: the delta row is written too). Workgroups are
-// persistent and nothing of a tile waits for memory on its own: the finished tile's accumulators are parked in a second
-// set of registers and leave for memory chunk by chunk during the K steps of the next tile (the rows they are added to
-// are requested one step before they are used, and each lane stores straight from its accumulator layout: 32 lanes
-// cover one 128-byte line of a row), and the first slices of the next tile's rows are requested during the last steps
-// of the current one. The matrix cores then only ever wait for the barriers around the LDS slices.
+// Streaming variant of the row transform (the Compute step of Sec. 3.3 in re-apply form) for the shape that dominates
+// large batches: x W with K = N = 256 (x = X^l[v], divided by the in-degree for mean), fp32 rows, H updated in place
+// (ADD: plus an unscaled cached row; DELTA: the delta row is written too).
+//
+// Workgroups are persistent and no part of a tile waits for memory on its own:
+//  * the finished tile's accumulators are parked in a second set of registers and leave for memory in eight chunks
+//    during the K steps of the next tile. The values a chunk is combined with (cached row, old row) are requested two
+//    steps before the chunk is finished, so the first two chunks of a tile are requested during its own last steps;
+//    every lane stores straight from its accumulator layout (32 lanes cover one 128-byte line of a row);
+//  * the first slices of the next tile's rows are requested during the last steps of the current one;
+//  * the mean's 1/deg is applied to the finished row instead of the gathered one, so staging is a plain copy.
+// Every array is addressed through a buffer descriptor with 32-bit offsets (row id * 1 KB + constants): as flat
+// addresses the compiler keeps dozens of 64-bit pointers alive across the unrolled steps, which no register file holds.
+// The launch therefore requires vertex_capacity * 1 KB < 4 GB.
 template <bool ADD, bool DELTA>
-__global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a) {
-    constexpr int BM = 64, BN = 256, KS = 8, STAGES = 2, NA = 2, NB = 8;
+__global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n_cap) {
+    constexpr int BM = 64, BN = 256, KS = 8, STAGES = 2, NA = 2, NB = 8, LEAD = 2;
     __shared__ __attribute__((aligned(16))) float As[BM][T_BK + 1];
     __shared__ __attribute__((aligned(16))) float Bs[T_BK][BN];
     __shared__ uint32_t s_vtx[2][BM];
+    __shared__ float s_scale[2][BM];
 
     const int tid = threadIdx.x, lane = tid & 63, wn = tid >> 6;
     const uint32_t count = *a.count_ptr;
@@ -23,44 +31,48 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a) {
     uint32_t tile = blockIdx.x;
     if (tile >= n_tiles) return;
 
+    constexpr uint32_t RSRC3 = 0x00020000u;                // raw buffer, 32-bit elements
+    const uint32_t row_bytes_total = n_cap * 1024u;        // < 4 GB (checked by the launch)
+    const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc((void *)a.W, 0, 256 * 256 * 4, RSRC3);
+    const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc((void *)a.X, 0, row_bytes_total, RSRC3);
+    const __amdgpu_buffer_rsrc_t hres = __builtin_amdgcn_make_buffer_rsrc(a.Hout, 0, row_bytes_total, RSRC3);
+    const __amdgpu_buffer_rsrc_t pres = __builtin_amdgcn_make_buffer_rsrc((void *)(ADD ? a.addend : a.X), 0, row_bytes_total, RSRC3);
+    const __amdgpu_buffer_rsrc_t dres = __builtin_amdgcn_make_buffer_rsrc((void *)(DELTA ? a.D : (float *)a.Hout), 0, row_bytes_total, RSRC3);
+
     const uint32_t c4a = (tid % (T_BK / 4)) * 4;
     const int r_own = tid / (T_BK / 4);                    // this thread stages rows r_own and r_own + 32 of every slice
-    const float *Xc = a.X + c4a;
+    const uint32_t wo = (uint32_t)tid * 16u;               // its eight 16-byte pieces of a weight slice lie 4 KB apart
+    const uint32_t colb = (wn * 64 + (lane & 31)) * 4u;    // byte offset of its first output column in a row
     float bias[2];
 #pragma unroll
     for (int sn = 0; sn < 2; ++sn) bias[sn] = a.bias[wn * 64 + sn * 32 + (lane & 31)];
 
-    uint32_t v_cur[NA], v_nxt[NA];
+    // byte offsets of the two rows this thread stages, for the current and the next tile; rows past the end repeat
+    // the last one and are never stored
+    uint32_t xo_cur[NA], xo_nxt[NA];
     float sc_cur[NA], sc_nxt[NA];
 #pragma unroll
     for (int i = 0; i < NA; ++i) {
-        v_cur[i] = a.list[min(tile * BM + r_own + i * 32, count - 1u)];   // rows past the end repeat the last one; never stored
-        v_nxt[i] = v_cur[i];
-    }
-#pragma unroll
-    for (int i = 0; i < NA; ++i) {
-        const uint32_t deg = a.in_meta[v_cur[i]].y;
+        const uint32_t v = a.list[min(tile * BM + r_own + i * 32, count - 1u)];
+        xo_cur[i] = v * 1024u + c4a * 4u;
+        xo_nxt[i] = xo_cur[i];
+        const uint32_t deg = a.in_meta[v].y;
         sc_cur[i] = a.mean ? 1.0f / (float)(deg > 1u ? deg : 1u) : 1.0f;
         sc_nxt[i] = sc_cur[i];
-    }
-
-    if (c4a == 0) {                                        // nothing is parked yet: its row ids only have to be valid
-#pragma unroll
-        for (int i = 0; i < NA; ++i) s_vtx[1][r_own + i * 32] = v_cur[i];
+        if (c4a == 0) {                                    // nothing is parked yet: its row ids only have to be valid
+            s_vtx[1][r_own + i * 32] = v;
+            s_scale[1][r_own + i * 32] = 1.0f;
+        }
     }
 
     floatx4 ra[STAGES][NA], rb[NB];
-    // The weights are read through a buffer descriptor: a thread's eight 16-byte pieces of a slice lie 4 KB apart and
-    // the slices 32 KB, all of it constants beside one offset register (as flat addresses the compiler keeps
-    // sixty-four 64-bit pointers alive, which no register file holds).
-    const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc((void *)a.W, 0, 256 * 256 * 4, 0x00020000);
-    const uint32_t wo = (uint32_t)tid * 16u;
 #pragma unroll
     for (int i = 0; i < NB; ++i) rb[i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(wres, wo, i * 4096, 0));
 #pragma unroll
     for (int st = 0; st < STAGES; ++st)
 #pragma unroll
-        for (int i = 0; i < NA; ++i) ra[st][i] = *(const floatx4 *)(Xc + (size_t)v_cur[i] * 256 + st * T_BK);
+        for (int i = 0; i < NA; ++i)
+            ra[st][i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(xres, xo_cur[i] + st * T_BK * 4, 0, 0));
 
     floatx16 acc[2][2], accp[2][2];
 #pragma unroll
@@ -73,46 +85,57 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a) {
                 accp[i][j][r] = 0.0f;
             }
     uint32_t prev_rows = 0;                                // valid rows of the parked tile (0: nothing parked)
-    int par = 0;
-    float pa[8], po[8];                                    // addend and old values of the chunk in flight
-    uint32_t pv[4];                                        // the vertices of its four rows
+    int par = 0;                                           // s_vtx / s_scale [par]: the current tile, [par ^ 1]: the parked one
+    float pa[LEAD][8], po[LEAD][8];                        // cached-row and old values of the chunks in flight
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        pa[e] = 0.0f;
-        po[e] = 0.0f;
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) pv[j] = 0;
-    const uint32_t col0 = wn * 64 + (lane & 31);
-
-    // chunk c of a parked tile: accumulator elements 4 (c & 3) .. + 3 of blocks [c >> 2][0] and [c >> 2][1]
-    auto chunk_request = [&](int c, const uint32_t *vtx) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) pv[j] = vtx[(c >> 2) * 32 + (c & 3) * 8 + (lane >> 5) * 4 + j];
+    for (int q = 0; q < LEAD; ++q)
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            const size_t h = (size_t)pv[e & 3] * 256 + col0 + (e >> 2) * 32;
-            if (ADD) pa[e] = a.addend[h];
-            if (DELTA) po[e] = ((const float *)a.Hout)[h];
+            pa[q][e] = 0.0f;
+            po[q][e] = 0.0f;
         }
-    };
-    auto chunk_finish = [&](int c, uint32_t rows) {
+
+    // Chunk c of a tile: accumulator elements 4 (c & 3) .. + 3 of blocks [c >> 2][0] and [c >> 2][1], i.e. for this lane
+    // four rows and two columns 32 apart. `buf` names the tile's entry in s_vtx / s_scale.
+    auto chunk_request = [&](int c, int buf) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const int sn = e >> 2, j = e & 3;
-            const int lr = (c >> 2) * 32 + (c & 3) * 8 + (lane >> 5) * 4 + j;
-            float z = accp[c >> 2][sn][(c & 3) * 4 + j] + bias[sn] + (ADD ? pa[e] : 0.0f);
+            const uint32_t v = s_vtx[buf][(c >> 2) * 32 + (c & 3) * 8 + (lane >> 5) * 4 + j];
+            const uint32_t off = v * 1024u + colb + sn * 128u;
+            if (ADD) pa[c % LEAD][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(pres, off, 0, 0));
+            if (DELTA) po[c % LEAD][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(hres, off, 0, 0));
+        }
+    };
+    auto chunk_finish = [&](int c, int buf, uint32_t rows) {
+        const int lr0 = (c >> 2) * 32 + (c & 3) * 8 + (lane >> 5) * 4;
+        uint32_t rowoff[4];
+        float rsc[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            rowoff[j] = s_vtx[buf][lr0 + j] * 1024u;
+            rsc[j] = s_scale[buf][lr0 + j];
+        }
+        // rows past the end of the list get an offset beyond the buffer (and below 4 GB with the column added):
+        // the hardware drops such stores
+#pragma unroll
+        for (int j = 0; j < 4; ++j) rowoff[j] = (((uint32_t)(lr0 + j) < rows) ? rowoff[j] : 0xFFFFF000u) + colb;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int sn = e >> 2, j = e & 3;
+            float z = accp[c >> 2][sn][(c & 3) * 4 + j] * rsc[j] + bias[sn] + (ADD ? pa[c % LEAD][e] : 0.0f);
             if (a.act == RIPPLE_ACT_RELU) z = z > 0.0f ? z : 0.0f;
-            if ((uint32_t)lr < rows) {
-                const size_t h = (size_t)pv[j] * 256 + col0 + sn * 32;
-                ((float *)a.Hout)[h] = z;
-                if (DELTA) a.D[h] = a.d_old ? po[e] : z - po[e];
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, z), hres, rowoff[j] + sn * 128u, 0, 0);
+            if (DELTA) {
+                const float d = a.d_old ? po[c % LEAD][e] : z - po[c % LEAD][e];
+                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, d), dres, rowoff[j] + sn * 128u, 0, 0);
             }
         }
     };
 
     for (;;) {
         const uint32_t tile_n = tile + gridDim.x;
+        uint32_t v_nxt[NA];
 #pragma unroll
         for (int i = 0; i < NA; ++i) v_nxt[i] = a.list[min(tile_n * BM + r_own + i * 32, count - 1u)];
 #pragma unroll
@@ -120,7 +143,7 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a) {
             __syncthreads();                               // the matrix cores are done with the previous slice
 #pragma unroll
             for (int i = 0; i < NA; ++i) {
-                const floatx4 val = ra[s % STAGES][i] * sc_cur[i];
+                const floatx4 val = ra[s % STAGES][i];
                 float *dst = &As[r_own + i * 32][c4a];
                 dst[0] = val.x;
                 dst[1] = val.y;
@@ -132,31 +155,36 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a) {
                 const int idx = tid + i * 256;
                 *(floatx4 *)&Bs[idx / (BN / 4)][(idx % (BN / 4)) * 4] = rb[i];
             }
-            if (s == 0 && c4a == 0) {
-#pragma unroll
-                for (int i = 0; i < NA; ++i) s_vtx[par][r_own + i * 32] = v_cur[i];
-            }
-            __syncthreads();
-            {                                              // weights of the next slice (after the last: slice 0 again, for the next tile)
-#pragma unroll
-                for (int i = 0; i < NB; ++i)
-                    rb[i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(wres, wo, ((s + 1) % KS) * T_BK * BN * 4 + i * 4096, 0));
-            }
-            if (s == 2) {                                  // the next tile's scale factors
+            if (s == 0 && c4a == 0) {                      // this tile's row ids and scale factors, for when it is written out
 #pragma unroll
                 for (int i = 0; i < NA; ++i) {
+                    s_vtx[par][r_own + i * 32] = xo_cur[i] >> 10;
+                    s_scale[par][r_own + i * 32] = sc_cur[i];
+                }
+            }
+            __syncthreads();
+            // weights of the next slice (after the last: slice 0 again, for the next tile)
+#pragma unroll
+            for (int i = 0; i < NB; ++i)
+                rb[i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(wres, wo, ((s + 1) % KS) * T_BK * BN * 4 + i * 4096, 0));
+            if (s == 1) {                                  // the next tile's rows: offsets and scale factors
+#pragma unroll
+                for (int i = 0; i < NA; ++i) {
+                    xo_nxt[i] = v_nxt[i] * 1024u + c4a * 4u;
                     const uint32_t deg = a.in_meta[v_nxt[i]].y;
                     sc_nxt[i] = a.mean ? 1.0f / (float)(deg > 1u ? deg : 1u) : 1.0f;
                 }
             }
 #pragma unroll
             for (int i = 0; i < NA; ++i) {                 // rows of the slice STAGES steps ahead: this tile's, then the next tile's
-                const uint32_t v = (s + STAGES < KS) ? v_cur[i] : v_nxt[i];
-                ra[s % STAGES][i] = *(const floatx4 *)(Xc + (size_t)v * 256 + ((s + STAGES) % KS) * T_BK);
+                const uint32_t xo = (s + STAGES < KS) ? xo_cur[i] : xo_nxt[i];
+                ra[s % STAGES][i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(xres, xo + ((s + STAGES) % KS) * T_BK * 4, 0, 0));
             }
-            // the parked tile: finish the chunk requested one step ago, request the next one
-            if (s > 0) chunk_finish(s - 1, prev_rows);
-            chunk_request(s, s_vtx[par ^ 1]);
+            // the parked tile: finish the chunk requested LEAD steps ago, request the one LEAD chunks on (the
+            // first LEAD chunks of the tile being multiplied, once the parked one has none left)
+            chunk_finish(s, par ^ 1, prev_rows);
+            if (s + LEAD < KS) chunk_request(s + LEAD, par ^ 1);
+            else chunk_request(s + LEAD - KS, par);
             __builtin_amdgcn_sched_barrier(0);
             float av[2][2], bv[2][2];
 #pragma unroll
@@ -180,7 +208,6 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a) {
                     for (int j = 0; j < 2; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][i], bv[cur][j], acc[i][j], 0, 0, 0);
             }
-            if (s == KS - 1) chunk_finish(KS - 1, prev_rows);
         }
         // park the tile, move on
 #pragma unroll
@@ -194,18 +221,18 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a) {
         prev_rows = min((uint32_t)BM, count - tile * BM);
 #pragma unroll
         for (int i = 0; i < NA; ++i) {
-            v_cur[i] = v_nxt[i];
+            xo_cur[i] = xo_nxt[i];
             sc_cur[i] = sc_nxt[i];
         }
         par ^= 1;
         tile = tile_n;
         if (tile >= n_tiles) break;
     }
-    __syncthreads();                                       // s_vtx[par ^ 1] of the last tile is complete since its first step
+    // the last tile: its first LEAD chunks are on their way already
 #pragma unroll
     for (int c = 0; c < KS; ++c) {
-        chunk_request(c, s_vtx[par ^ 1]);
-        chunk_finish(c, prev_rows);
+        chunk_finish(c, par ^ 1, prev_rows);
+        if (c + LEAD < KS) chunk_request(c + LEAD, par ^ 1);
     }
 }
 
@@ -214,12 +241,12 @@ bool rp_launch_stream(ripple_ctx *c, const TArgs &a, uint32_t rows_hint) {
     if (!c->opt_stream || a.a_mode != 0 || a.store || a.Ws || a.out_mode != 1) return false;
     if (a.K != 256 || a.Kpad != 256 || a.N != 256 || a.Npad != 256 || a.d_in != 256) return false;
     if (a.addend && a.addend_scaled) return false;
-    if (rows_hint < 64u * 4u * 2u * c->n_cu) return false;   // at least four tiles per persistent workgroup
+    if ((uint64_t)c->n_cap * 1024u > 0xFFFFF000ull) return false;   // 32-bit byte offsets into the row arrays, the top 4 KB kept free
+    if (rows_hint < 64u * 4u * 2u * c->n_cu) return false;          // at least four tiles per persistent workgroup
     const dim3 grid(2 * c->n_cu), block(256);
-    if (a.addend && a.D) hipLaunchKernelGGL((k_transform_stream<true, true>), grid, block, 0, c->stream, a);
-    else if (a.addend) hipLaunchKernelGGL((k_transform_stream<true, false>), grid, block, 0, c->stream, a);
-    else if (a.D) hipLaunchKernelGGL((k_transform_stream<false, true>), grid, block, 0, c->stream, a);
-    else hipLaunchKernelGGL((k_transform_stream<false, false>), grid, block, 0, c->stream, a);
+    if (a.addend && a.D) hipLaunchKernelGGL((k_transform_stream<true, true>), grid, block, 0, c->stream, a, c->n_cap);
+    else if (a.addend) hipLaunchKernelGGL((k_transform_stream<true, false>), grid, block, 0, c->stream, a, c->n_cap);
+    else if (a.D) hipLaunchKernelGGL((k_transform_stream<false, true>), grid, block, 0, c->stream, a, c->n_cap);
+    else hipLaunchKernelGGL((k_transform_stream<false, false>), grid, block, 0, c->stream, a, c->n_cap);
     return true;
 }
-
