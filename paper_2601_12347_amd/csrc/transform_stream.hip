@@ -96,40 +96,37 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n
         }
 
     // Chunk c of a tile: accumulator elements 4 (c & 3) .. + 3 of blocks [c >> 2][0] and [c >> 2][1], i.e. for this lane
-    // four rows and two columns 32 apart. `buf` names the tile's entry in s_vtx / s_scale.
-    auto chunk_request = [&](int c, int buf) {
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int sn = e >> 2, j = e & 3;
-            const uint32_t v = s_vtx[buf][(c >> 2) * 32 + (c & 3) * 8 + (lane >> 5) * 4 + j];
-            const uint32_t off = v * 1024u + colb + sn * 128u;
-            if (ADD) pa[c % LEAD][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(pres, off, 0, 0));
-            if (DELTA) po[c % LEAD][e] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(hres, off, 0, 0));
-        }
-    };
-    auto chunk_finish = [&](int c, int buf, uint32_t rows) {
+    // four rows (j) and two columns 32 apart (sn); element e = 4 sn + j. `buf` names the tile's entry in s_vtx / s_scale.
+    // The pieces below are issued between the matrix-core operations of a step, where the wavefront has issue slots
+    // to spare: in front of them they would delay every product of the step.
+    uint32_t rowoff[4];                                    // byte offsets of the chunk being finished (rows past the end of the
+    float rsc[4];                                          // list: beyond the buffer, so that the hardware drops their stores)
+    auto finish_rows = [&](int c, int buf, uint32_t rows) {
         const int lr0 = (c >> 2) * 32 + (c & 3) * 8 + (lane >> 5) * 4;
-        uint32_t rowoff[4];
-        float rsc[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             rowoff[j] = s_vtx[buf][lr0 + j] * 1024u;
             rsc[j] = s_scale[buf][lr0 + j];
         }
-        // rows past the end of the list get an offset beyond the buffer (and below 4 GB with the column added):
-        // the hardware drops such stores
 #pragma unroll
         for (int j = 0; j < 4; ++j) rowoff[j] = (((uint32_t)(lr0 + j) < rows) ? rowoff[j] : 0xFFFFF000u) + colb;
+    };
+    auto finish_elem = [&](int c, int e) {
+        const int sn = e >> 2, j = e & 3;
+        float z = accp[c >> 2][sn][(c & 3) * 4 + j] * rsc[j] + bias[sn] + (ADD ? pa[c % LEAD][e] : 0.0f);
+        if (a.act == RIPPLE_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, z), hres, rowoff[j] + sn * 128u, 0, 0);
+        if (DELTA) {
+            const float d = a.d_old ? po[c % LEAD][e] : z - po[c % LEAD][e];
+            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, d), dres, rowoff[j] + sn * 128u, 0, 0);
+        }
+    };
+    auto request_row = [&](int c, int buf, int j) {        // both columns of row j of chunk c
+        const uint32_t off = s_vtx[buf][(c >> 2) * 32 + (c & 3) * 8 + (lane >> 5) * 4 + j] * 1024u + colb;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int sn = e >> 2, j = e & 3;
-            float z = accp[c >> 2][sn][(c & 3) * 4 + j] * rsc[j] + bias[sn] + (ADD ? pa[c % LEAD][e] : 0.0f);
-            if (a.act == RIPPLE_ACT_RELU) z = z > 0.0f ? z : 0.0f;
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, z), hres, rowoff[j] + sn * 128u, 0, 0);
-            if (DELTA) {
-                const float d = a.d_old ? po[c % LEAD][e] : z - po[c % LEAD][e];
-                __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, d), dres, rowoff[j] + sn * 128u, 0, 0);
-            }
+        for (int sn = 0; sn < 2; ++sn) {
+            if (ADD) pa[c % LEAD][sn * 4 + j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(pres, off + sn * 128u, 0, 0));
+            if (DELTA) po[c % LEAD][sn * 4 + j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(hres, off + sn * 128u, 0, 0));
         }
     };
 
@@ -180,11 +177,9 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n
                 const uint32_t xo = (s + STAGES < KS) ? xo_cur[i] : xo_nxt[i];
                 ra[s % STAGES][i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(xres, xo + ((s + STAGES) % KS) * T_BK * 4, 0, 0));
             }
-            // the parked tile: finish the chunk requested LEAD steps ago, request the one LEAD chunks on (the
-            // first LEAD chunks of the tile being multiplied, once the parked one has none left)
-            chunk_finish(s, par ^ 1, prev_rows);
-            if (s + LEAD < KS) chunk_request(s + LEAD, par ^ 1);
-            else chunk_request(s + LEAD - KS, par);
+            // the parked tile: chunk s, requested LEAD steps ago, is finished during this step's products, and the chunk
+            // LEAD on is requested (the first LEAD chunks of the tile being multiplied, once the parked one has none left)
+            finish_rows(s, par ^ 1, prev_rows);
             __builtin_amdgcn_sched_barrier(0);
             float av[2][2], bv[2][2];
 #pragma unroll
@@ -207,6 +202,14 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n
 #pragma unroll
                     for (int j = 0; j < 2; ++j)
                         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][i], bv[cur][j], acc[i][j], 0, 0, 0);
+                const int q = kk >> 1;                     // one piece of the parked tile's traffic per pair of k
+                if (q < 8) {
+                    finish_elem(s, q);
+                } else if (q < 12) {
+                    if (s + LEAD < KS) request_row(s + LEAD, par ^ 1, q - 8);
+                    else request_row(s + LEAD - KS, par, q - 8);
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         // park the tile, move on
@@ -231,8 +234,13 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n
     // the last tile: its first LEAD chunks are on their way already
 #pragma unroll
     for (int c = 0; c < KS; ++c) {
-        chunk_finish(c, par ^ 1, prev_rows);
-        if (c + LEAD < KS) chunk_request(c + LEAD, par ^ 1);
+        finish_rows(c, par ^ 1, prev_rows);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) finish_elem(c, e);
+        if (c + LEAD < KS) {
+#pragma unroll
+            for (int j = 0; j < 4; ++j) request_row(c + LEAD, par ^ 1, j);
+        }
     }
 }
 
