@@ -2,26 +2,33 @@
 #include "kernels.h"
 
 typedef uint32_t uintx4 __attribute__((ext_vector_type(4)));
+typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
+typedef float floatx2 __attribute__((ext_vector_type(2)));
 
 // Streaming variant of the row transform (the Compute step of Sec. 3.3 in re-apply form) for the shape that dominates
 // large batches: x W with K = N = 256 (x = X^l[v], divided by the in-degree for mean), fp32 rows, H updated in place
 // (ADD: plus an unscaled cached row; DELTA: the delta row is written too).
 //
-// Workgroups are persistent and no part of a tile waits for memory on its own:
+// A workgroup of four wavefronts owns 64-row tiles; wavefront w owns 64 output columns, as two 32-column blocks of
+// interleaved columns (block j holds columns 64 w + 2 n + j), so that everything a lane reads or writes per row is
+// eight adjacent bytes. Workgroups are persistent and no part of a tile waits for memory on its own:
+//  * the weights never pass through LDS: a wavefront only needs its own 64 columns, so each lane loads the two
+//    numbers it feeds into the matrix cores for a pair of k straight from the (L2-resident) matrix, one step ahead,
+//    into the register the same pair of k of the current step has just freed;
+//  * the gathered rows pass through a double-buffered LDS slice (one barrier per step): slice s + 1 is written while
+//    slice s is multiplied, from registers requested two steps earlier, also across the tile boundary;
 //  * the finished tile's accumulators are parked in a second set of registers and leave for memory in eight chunks
-//    during the K steps of the next tile. The values a chunk is combined with (cached row, old row) are requested two
-//    steps before the chunk is finished, so the first two chunks of a tile are requested during its own last steps;
-//    every lane stores straight from its accumulator layout (32 lanes cover one 128-byte line of a row);
-//  * the first slices of the next tile's rows are requested during the last steps of the current one;
+//    during the K steps of the next tile; the cached / old values a chunk is combined with are requested two steps
+//    before the chunk is finished (the first two chunks of a tile during its own last steps);
+//  * all of this is issued between the matrix-core operations of a step, where the wavefront has issue slots to spare;
 //  * the mean's 1/deg is applied to the finished row instead of the gathered one, so staging is a plain copy.
 // Every array is addressed through a buffer descriptor with 32-bit offsets (row id * 1 KB + constants): as flat
 // addresses the compiler keeps dozens of 64-bit pointers alive across the unrolled steps, which no register file holds.
-// The launch therefore requires vertex_capacity * 1 KB < 4 GB.
+// The launch therefore requires vertex_capacity * 1 KB < 4 GB - 4 KB.
 template <bool ADD, bool DELTA>
 __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n_cap) {
-    constexpr int BM = 64, BN = 256, KS = 8, STAGES = 2, NA = 2, NB = 8, LEAD = 2;
-    __shared__ __attribute__((aligned(16))) float As[BM][T_BK + 1];
-    __shared__ __attribute__((aligned(16))) float Bs[T_BK][BN];
+    constexpr int BM = 64, KS = 8, NA = 2, LEAD = 2, KP = T_BK / 2;
+    __shared__ __attribute__((aligned(16))) float As[2][BM][T_BK + 1];
     __shared__ uint32_t s_vtx[2][BM];
     __shared__ float s_scale[2][BM];
 
@@ -32,7 +39,7 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n
     if (tile >= n_tiles) return;
 
     constexpr uint32_t RSRC3 = 0x00020000u;                // raw buffer, 32-bit elements
-    const uint32_t row_bytes_total = n_cap * 1024u;        // < 4 GB (checked by the launch)
+    const uint32_t row_bytes_total = n_cap * 1024u;        // < 4 GB - 4 KB (checked by the launch)
     const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc((void *)a.W, 0, 256 * 256 * 4, RSRC3);
     const __amdgpu_buffer_rsrc_t xres = __builtin_amdgcn_make_buffer_rsrc((void *)a.X, 0, row_bytes_total, RSRC3);
     const __amdgpu_buffer_rsrc_t hres = __builtin_amdgcn_make_buffer_rsrc(a.Hout, 0, row_bytes_total, RSRC3);
@@ -41,11 +48,9 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n
 
     const uint32_t c4a = (tid % (T_BK / 4)) * 4;
     const int r_own = tid / (T_BK / 4);                    // this thread stages rows r_own and r_own + 32 of every slice
-    const uint32_t wo = (uint32_t)tid * 16u;               // its eight 16-byte pieces of a weight slice lie 4 KB apart
-    const uint32_t colb = (wn * 64 + (lane & 31)) * 4u;    // byte offset of its first output column in a row
-    float bias[2];
-#pragma unroll
-    for (int sn = 0; sn < 2; ++sn) bias[sn] = a.bias[wn * 64 + sn * 32 + (lane & 31)];
+    const uint32_t colb = (wn * 64 + 2 * (lane & 31)) * 4u;    // byte offset of its two adjacent output columns in a row
+    const uint32_t wvo = (lane >> 5) * 1024u + colb;       // weights: row (lane >> 5) of a pair of k, those two columns
+    const floatx2 bias = *(const floatx2 *)(a.bias + wn * 64 + 2 * (lane & 31));
 
     // byte offsets of the two rows this thread stages, for the current and the next tile; rows past the end repeat
     // the last one and are never stored
@@ -65,14 +70,34 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n
         }
     }
 
-    floatx4 ra[STAGES][NA], rb[NB];
+    auto load_x = [&](uint32_t xo, int slice) {
+        return __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(xres, xo + slice * T_BK * 4, 0, 0));
+    };
+    auto load_w = [&](int slice, int q) {                  // pair q of k of a slice: the lane's operand for both column blocks
+        return __builtin_bit_cast(floatx2, __builtin_amdgcn_raw_buffer_load_b64(wres, wvo, slice * T_BK * 1024 + q * 2048, 0));
+    };
+    auto stage_x = [&](int buf, const floatx4 (&r)[NA]) {
 #pragma unroll
-    for (int i = 0; i < NB; ++i) rb[i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(wres, wo, i * 4096, 0));
+        for (int i = 0; i < NA; ++i) {
+            float *dst = &As[buf][r_own + i * 32][c4a];
+            dst[0] = r[i].x;
+            dst[1] = r[i].y;
+            dst[2] = r[i].z;
+            dst[3] = r[i].w;
+        }
+    };
+
+    floatx4 ra[2][NA];                                     // ra[p]: the slice that goes to As[p] next
+    floatx2 bq[KP];
 #pragma unroll
-    for (int st = 0; st < STAGES; ++st)
+    for (int i = 0; i < NA; ++i) ra[0][i] = load_x(xo_cur[i], 0);
 #pragma unroll
-        for (int i = 0; i < NA; ++i)
-            ra[st][i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(xres, xo_cur[i] + st * T_BK * 4, 0, 0));
+    for (int i = 0; i < NA; ++i) ra[1][i] = load_x(xo_cur[i], 1);
+#pragma unroll
+    for (int q = 0; q < KP; ++q) bq[q] = load_w(0, q);
+    stage_x(0, ra[0]);
+#pragma unroll
+    for (int i = 0; i < NA; ++i) ra[0][i] = load_x(xo_cur[i], 2);
 
     floatx16 acc[2][2], accp[2][2];
 #pragma unroll
@@ -86,19 +111,17 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n
             }
     uint32_t prev_rows = 0;                                // valid rows of the parked tile (0: nothing parked)
     int par = 0;                                           // s_vtx / s_scale [par]: the current tile, [par ^ 1]: the parked one
-    float pa[LEAD][8], po[LEAD][8];                        // cached-row and old values of the chunks in flight
+    floatx2 pa[LEAD][4], po[LEAD][4];                      // cached-row and old values of the chunks in flight
 #pragma unroll
     for (int q = 0; q < LEAD; ++q)
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            pa[q][e] = 0.0f;
-            po[q][e] = 0.0f;
+        for (int j = 0; j < 4; ++j) {
+            pa[q][j] = (floatx2)(0.0f);
+            po[q][j] = (floatx2)(0.0f);
         }
 
     // Chunk c of a tile: accumulator elements 4 (c & 3) .. + 3 of blocks [c >> 2][0] and [c >> 2][1], i.e. for this lane
-    // four rows (j) and two columns 32 apart (sn); element e = 4 sn + j. `buf` names the tile's entry in s_vtx / s_scale.
-    // The pieces below are issued between the matrix-core operations of a step, where the wavefront has issue slots
-    // to spare: in front of them they would delay every product of the step.
+    // four rows (j) with its two columns each. `buf` names the tile's entry in s_vtx / s_scale.
     uint32_t rowoff[4];                                    // byte offsets of the chunk being finished (rows past the end of the
     float rsc[4];                                          // list: beyond the buffer, so that the hardware drops their stores)
     auto finish_rows = [&](int c, int buf, uint32_t rows) {
@@ -111,23 +134,24 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n
 #pragma unroll
         for (int j = 0; j < 4; ++j) rowoff[j] = (((uint32_t)(lr0 + j) < rows) ? rowoff[j] : 0xFFFFF000u) + colb;
     };
-    auto finish_elem = [&](int c, int e) {
-        const int sn = e >> 2, j = e & 3;
-        float z = accp[c >> 2][sn][(c & 3) * 4 + j] * rsc[j] + bias[sn] + (ADD ? pa[c % LEAD][e] : 0.0f);
-        if (a.act == RIPPLE_ACT_RELU) z = z > 0.0f ? z : 0.0f;
-        __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, z), hres, rowoff[j] + sn * 128u, 0, 0);
+    auto finish_row = [&](int c, int j) {
+        floatx2 z;
+        z.x = accp[c >> 2][0][(c & 3) * 4 + j] * rsc[j] + bias.x + (ADD ? pa[c % LEAD][j].x : 0.0f);
+        z.y = accp[c >> 2][1][(c & 3) * 4 + j] * rsc[j] + bias.y + (ADD ? pa[c % LEAD][j].y : 0.0f);
+        if (a.act == RIPPLE_ACT_RELU) {
+            z.x = z.x > 0.0f ? z.x : 0.0f;
+            z.y = z.y > 0.0f ? z.y : 0.0f;
+        }
+        __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(uintx2, z), hres, rowoff[j], 0, 0);
         if (DELTA) {
-            const float d = a.d_old ? po[c % LEAD][e] : z - po[c % LEAD][e];
-            __builtin_amdgcn_raw_buffer_store_b32(__builtin_bit_cast(uint32_t, d), dres, rowoff[j] + sn * 128u, 0, 0);
+            const floatx2 d = a.d_old ? po[c % LEAD][j] : z - po[c % LEAD][j];
+            __builtin_amdgcn_raw_buffer_store_b64(__builtin_bit_cast(uintx2, d), dres, rowoff[j], 0, 0);
         }
     };
-    auto request_row = [&](int c, int buf, int j) {        // both columns of row j of chunk c
+    auto request_row = [&](int c, int buf, int j) {
         const uint32_t off = s_vtx[buf][(c >> 2) * 32 + (c & 3) * 8 + (lane >> 5) * 4 + j] * 1024u + colb;
-#pragma unroll
-        for (int sn = 0; sn < 2; ++sn) {
-            if (ADD) pa[c % LEAD][sn * 4 + j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(pres, off + sn * 128u, 0, 0));
-            if (DELTA) po[c % LEAD][sn * 4 + j] = __builtin_bit_cast(float, __builtin_amdgcn_raw_buffer_load_b32(hres, off + sn * 128u, 0, 0));
-        }
+        if (ADD) pa[c % LEAD][j] = __builtin_bit_cast(floatx2, __builtin_amdgcn_raw_buffer_load_b64(pres, off, 0, 0));
+        if (DELTA) po[c % LEAD][j] = __builtin_bit_cast(floatx2, __builtin_amdgcn_raw_buffer_load_b64(hres, off, 0, 0));
     };
 
     for (;;) {
@@ -137,21 +161,8 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n
         for (int i = 0; i < NA; ++i) v_nxt[i] = a.list[min(tile_n * BM + r_own + i * 32, count - 1u)];
 #pragma unroll
         for (int s = 0; s < KS; ++s) {
-            __syncthreads();                               // the matrix cores are done with the previous slice
-#pragma unroll
-            for (int i = 0; i < NA; ++i) {
-                const floatx4 val = ra[s % STAGES][i];
-                float *dst = &As[r_own + i * 32][c4a];
-                dst[0] = val.x;
-                dst[1] = val.y;
-                dst[2] = val.z;
-                dst[3] = val.w;
-            }
-#pragma unroll
-            for (int i = 0; i < NB; ++i) {
-                const int idx = tid + i * 256;
-                *(floatx4 *)&Bs[idx / (BN / 4)][(idx % (BN / 4)) * 4] = rb[i];
-            }
+            // every wavefront is done with slice s - 1 (As[(s + 1) & 1] may be overwritten) and has written its part of slice s
+            __syncthreads();
             if (s == 0 && c4a == 0) {                      // this tile's row ids and scale factors, for when it is written out
 #pragma unroll
                 for (int i = 0; i < NA; ++i) {
@@ -159,11 +170,6 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n
                     s_scale[par][r_own + i * 32] = sc_cur[i];
                 }
             }
-            __syncthreads();
-            // weights of the next slice (after the last: slice 0 again, for the next tile)
-#pragma unroll
-            for (int i = 0; i < NB; ++i)
-                rb[i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(wres, wo, ((s + 1) % KS) * T_BK * BN * 4 + i * 4096, 0));
             if (s == 1) {                                  // the next tile's rows: offsets and scale factors
 #pragma unroll
                 for (int i = 0; i < NA; ++i) {
@@ -172,42 +178,40 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n
                     sc_nxt[i] = a.mean ? 1.0f / (float)(deg > 1u ? deg : 1u) : 1.0f;
                 }
             }
+            float av[2][2];
 #pragma unroll
-            for (int i = 0; i < NA; ++i) {                 // rows of the slice STAGES steps ahead: this tile's, then the next tile's
-                const uint32_t xo = (s + STAGES < KS) ? xo_cur[i] : xo_nxt[i];
-                ra[s % STAGES][i] = __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(xres, xo + ((s + STAGES) % KS) * T_BK * 4, 0, 0));
-            }
-            // the parked tile: chunk s, requested LEAD steps ago, is finished during this step's products, and the chunk
-            // LEAD on is requested (the first LEAD chunks of the tile being multiplied, once the parked one has none left)
-            finish_rows(s, par ^ 1, prev_rows);
-            __builtin_amdgcn_sched_barrier(0);
-            float av[2][2], bv[2][2];
+            for (int i = 0; i < 2; ++i) av[0][i] = As[s & 1][i * 32 + (lane & 31)][lane >> 5];
 #pragma unroll
-            for (int i = 0; i < 2; ++i) av[0][i] = As[i * 32 + (lane & 31)][lane >> 5];
+            for (int q = 0; q < KP; ++q) {
+                const int cur = q & 1, nxt = cur ^ 1;
+                if (q + 1 < KP) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j) bv[0][j] = Bs[lane >> 5][(wn * 2 + j) * 32 + (lane & 31)];
-#pragma unroll
-            for (int kk = 0; kk < T_BK; kk += 2) {
-                const int cur = (kk >> 1) & 1, nxt = cur ^ 1;
-                if (kk + 2 < T_BK) {
-                    const int kq = kk + 2 + (lane >> 5);
-#pragma unroll
-                    for (int i = 0; i < 2; ++i) av[nxt][i] = As[i * 32 + (lane & 31)][kq];
-#pragma unroll
-                    for (int j = 0; j < 2; ++j) bv[nxt][j] = Bs[kq][(wn * 2 + j) * 32 + (lane & 31)];
+                    for (int i = 0; i < 2; ++i) av[nxt][i] = As[s & 1][i * 32 + (lane & 31)][2 * (q + 1) + (lane >> 5)];
                 }
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int i = 0; i < 2; ++i)
-#pragma unroll
-                    for (int j = 0; j < 2; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][i], bv[cur][j], acc[i][j], 0, 0, 0);
-                const int q = kk >> 1;                     // one piece of the parked tile's traffic per pair of k
-                if (q < 8) {
-                    finish_elem(s, q);
-                } else if (q < 12) {
+                for (int i = 0; i < 2; ++i) {
+                    acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][i], bq[q].x, acc[i][0], 0, 0, 0);
+                    acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][i], bq[q].y, acc[i][1], 0, 0, 0);
+                }
+                // between the products: the same pair of k of the next slice (after the last: slice 0, for the next tile) ...
+                bq[q] = load_w((s + 1) % KS, q);
+                // ... and one piece of the parked tile's traffic or of the row staging. Chunk s of the parked tile,
+                // requested LEAD steps ago, is finished; the chunk LEAD on is requested (the first LEAD chunks of the
+                // tile being multiplied, once the parked one has none left).
+                if (q == 0) {
+                    finish_rows(s, par ^ 1, prev_rows);
+                } else if (q <= 4) {
+                    finish_row(s, q - 1);
+                } else if (q >= 8 && q < 12) {
                     if (s + LEAD < KS) request_row(s + LEAD, par ^ 1, q - 8);
                     else request_row(s + LEAD - KS, par, q - 8);
+                } else if (q == 12) {                      // slice s + 1 into the other LDS buffer
+                    stage_x((s + 1) & 1, ra[(s + 1) & 1]);
+                } else if (q == 13) {                      // and slice s + 3 into the registers it came from
+#pragma unroll
+                    for (int i = 0; i < NA; ++i)
+                        ra[(s + 1) & 1][i] = load_x((s + 3 < KS) ? xo_cur[i] : xo_nxt[i], (s + 3) % KS);
                 }
                 __builtin_amdgcn_sched_barrier(0);
             }
@@ -236,7 +240,7 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n
     for (int c = 0; c < KS; ++c) {
         finish_rows(c, par ^ 1, prev_rows);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) finish_elem(c, e);
+        for (int j = 0; j < 4; ++j) finish_row(c, j);
         if (c + LEAD < KS) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) request_row(c + LEAD, par ^ 1, j);
