@@ -268,7 +268,7 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
         LayerDev &ly = c->layers[l];
         void *w[] = {ly.W0, ly.b0, ly.W1, ly.b1, ly.W0h, ly.W1h, ly.bzero, (ly.Wn != ly.W0) ? ly.Wn : nullptr, ly.PS,
                      ly.W0s, ly.W1s, (ly.Wns != ly.W0s) ? ly.Wns : nullptr,
-                     ly.att, ly.P, ly.ssrc, ly.sdst, ly.den, ly.T, ly.Wc, ly.bzero_c, ly.Wc96};
+                     ly.att, ly.P, ly.ssrc, ly.sdst, ly.den, ly.T, ly.Wc, ly.bzero_c, ly.Wc96, ly.Wc96p};
         for (void *p : w)
             if (p) hipFree(p);
     }
@@ -420,6 +420,18 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
                     }
                 RP_TRY(dev_alloc(c, &ly.Wc96, w96.size(), false));
                 RP_HIP(c, hipMemcpy(ly.Wc96, w96.data(), w96.size() * 4, hipMemcpyHostToDevice));
+                if (s.d_in == 256 && s.d_out > 16) {           // [k][n][j]: n < 16 column 16 j + n of W_self, else 16 j + n - 16 of W_neigh
+                    std::vector<float> wp((size_t)256 * 96, 0.0f);
+                    for (uint32_t k = 0; k < 256; ++k)
+                        for (uint32_t n = 0; n < 32; ++n)
+                            for (uint32_t j = 0; j < 3; ++j) {
+                                const uint32_t col = 16 * j + (n & 15u);
+                                if (col >= s.d_out) continue;
+                                wp[((size_t)k * 32 + n) * 3 + j] = s.W0[(size_t)((n < 16 ? 0 : s.d_in) + k) * s.d_out + col];
+                            }
+                    RP_TRY(dev_alloc(c, &ly.Wc96p, wp.size(), false));
+                    RP_HIP(c, hipMemcpy(ly.Wc96p, wp.data(), wp.size() * 4, hipMemcpyHostToDevice));
+                }
             }
         }
         if (s.d_hidden) {

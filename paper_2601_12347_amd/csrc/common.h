@@ -87,7 +87,8 @@ struct LayerDev {
     // from column 64 on) and 128 zeros, so that one pass over the rows of A_{l-1} yields both products; else null.
     // Wc96: the same for d_out <= 48 as [roundup(d_in,32) x 96] with W_neigh from column 48 on (a quarter fewer
     // matrix-core operations; used when many rows are expected), else null
-    float *Wc, *bzero_c, *Wc96;
+    // Wc96p: the 96 columns permuted for k_project_both_stream, [256][32][3] (d_in = 256 only), else null
+    float *Wc, *bzero_c, *Wc96, *Wc96p;
     // attention layers: projected rows P[v] = H^{l-1}[v] W0 [n x d_out], scores a_src . P[v] and a_dst . P[v],
     // denominators of the softmax (the numerators are the layer's X rows); att = a_src then a_dst on the device
     float *att, *P, *ssrc, *sdst, *den;

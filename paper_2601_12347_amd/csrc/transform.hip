@@ -1184,6 +1184,7 @@ void rp_launch_project_both(ripple_ctx *c, uint32_t l, const uint32_t *list, con
     a.tmp_out2 = bootstrap ? ly.T : c->PD;
     a.tmp_out2_ld = bootstrap ? ly.d_out : c->pd_ld;
     const uint32_t hint = bootstrap ? c->n_cap : rp_rows_hint(c, l - 1);
+    if (rp_launch_project_both_stream(c, l, list, count_d, a.tmp_out2, a.tmp_out2_ld, hint)) return;
     if (ly.Wc96 && hint > 2048) {                  // many rows: the products are bound by the matrix cores, 96 columns instead of 128
         a.W = ly.Wc96;
         a.N = 48 + ly.d_out;

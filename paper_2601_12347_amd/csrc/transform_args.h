@@ -49,3 +49,6 @@ struct TArgs {
 
 // transform_stream.hip: launches the streaming kernel if the arguments have its shape and enough rows are expected
 bool rp_launch_stream(ripple_ctx *c, const TArgs &a, uint32_t rows_hint);
+// the same for both products of a narrow project-first layer with a cached self term (second product into out2)
+bool rp_launch_project_both_stream(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, float *out2,
+                                   uint32_t ld2, uint32_t rows_hint);

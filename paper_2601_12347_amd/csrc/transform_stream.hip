@@ -262,3 +262,178 @@ bool rp_launch_stream(ripple_ctx *c, const TArgs &a, uint32_t rows_hint) {
     else hipLaunchKernelGGL((k_transform_stream<false, false>), grid, block, 0, c->stream, a, c->n_cap);
     return true;
 }
+
+// ---------------------------------------------------------------------------------
+// Both products of a narrow project-first layer, H^{l-1}[v] W_self (into PS) and H^{l-1}[v] W_neigh (into PD, or T at
+// the bootstrap), for d_in = 256 and d_out <= 48 on fp32 rows. Every wavefront is on its own: it owns 32-row tiles and
+// all 96 columns (three matrix-core blocks), stages its rows through a private, double-buffered LDS slice and reads the
+// weights straight from L2 into the operand registers half a step ahead, so there is no barrier anywhere and three
+// wavefronts per SIMD cover one another's waits. The weight matrix comes permuted, [k][n][j] with three adjacent
+// floats per lane: position n < 16 of block j is column 16 j + n of W_self, n >= 16 column 16 j + n - 16 of W_neigh,
+// so a lane ends up with columns (c, 16 + c, 32 + c) of one of the two products.
+// ---------------------------------------------------------------------------------
+struct PArgs {
+    const uint32_t *list;
+    const uint32_t *count_ptr;
+    const float *H;                // [n_cap x 256]
+    const float *Wp;               // [256][32][3]
+    float *out1, *out2;            // PS [n_cap x ld1], PD or T [n_cap x ld2]
+    uint32_t ld1, ld2, d_out, n_cap;
+};
+
+typedef uint32_t uintx3 __attribute__((ext_vector_type(3)));
+typedef float floatx3 __attribute__((ext_vector_type(3)));
+
+__global__ __launch_bounds__(256, 3) void k_project_both_stream(PArgs a) {
+    constexpr int BM = 32, KS = 8, NA = 4, KP = T_BK / 2, WLEAD = 8;
+    __shared__ __attribute__((aligned(16))) float As_all[4][2][BM][T_BK + 1];
+    __shared__ uint32_t s_vtx_all[4][BM];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    float (*As)[BM][T_BK + 1] = As_all[wave];
+    uint32_t *s_vtx = s_vtx_all[wave];
+    const uint32_t count = *a.count_ptr;
+    const uint32_t n_tiles = (count + BM - 1) / BM;
+    const uint32_t n_waves = gridDim.x * 4u;
+    uint32_t tile = blockIdx.x * 4u + wave;
+    if (tile >= n_tiles) return;
+
+    constexpr uint32_t RSRC3 = 0x00020000u;
+    const __amdgpu_buffer_rsrc_t wres = __builtin_amdgcn_make_buffer_rsrc((void *)a.Wp, 0, 256 * 96 * 4, RSRC3);
+    const __amdgpu_buffer_rsrc_t hres = __builtin_amdgcn_make_buffer_rsrc((void *)a.H, 0, a.n_cap * 1024u, RSRC3);
+
+    const uint32_t c4a = (lane & 7) * 4;                   // the lane stages rows (lane >> 3) + 8 i, i = 0..3, of every slice
+    const int r_own = lane >> 3;
+    const uint32_t wvo = (lane >> 5) * 384u + (lane & 31) * 12u;   // weights: row (lane >> 5) of a pair of k, its three numbers
+
+    auto load_h = [&](uint32_t ho, int slice) {
+        return __builtin_bit_cast(floatx4, __builtin_amdgcn_raw_buffer_load_b128(hres, ho + slice * T_BK * 4, 0, 0));
+    };
+    auto load_w = [&](int slice, int q) {
+        return __builtin_bit_cast(floatx3, __builtin_amdgcn_raw_buffer_load_b96(wres, wvo, slice * T_BK * 384 + q * 768, 0));
+    };
+    auto stage = [&](int buf, const floatx4 (&r)[NA]) {
+#pragma unroll
+        for (int i = 0; i < NA; ++i) {
+            float *dst = &As[buf][r_own + 8 * i][c4a];
+            dst[0] = r[i].x;
+            dst[1] = r[i].y;
+            dst[2] = r[i].z;
+            dst[3] = r[i].w;
+        }
+    };
+
+    uint32_t ho_cur[NA], ho_nxt[NA];
+#pragma unroll
+    for (int i = 0; i < NA; ++i) {
+        ho_cur[i] = a.list[min(tile * BM + r_own + 8 * i, count - 1u)] * 1024u + c4a * 4u;   // rows past the end repeat the last one
+        ho_nxt[i] = ho_cur[i];
+    }
+    floatx4 ra[2][NA];
+    floatx3 bq[WLEAD];                                     // bq[q % WLEAD]: pair q of k, requested WLEAD pairs before its use
+#pragma unroll
+    for (int i = 0; i < NA; ++i) ra[0][i] = load_h(ho_cur[i], 0);
+#pragma unroll
+    for (int i = 0; i < NA; ++i) ra[1][i] = load_h(ho_cur[i], 1);
+#pragma unroll
+    for (int q = 0; q < WLEAD; ++q) bq[q] = load_w(0, q);
+    stage(0, ra[0]);
+#pragma unroll
+    for (int i = 0; i < NA; ++i) ra[0][i] = load_h(ho_cur[i], 2);
+
+    floatx16 acc[3];
+#pragma unroll
+    for (int j = 0; j < 3; ++j)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
+
+    // where this lane's three columns go
+    const uint32_t sub = lane & 15u;
+    const bool second = (lane & 16) != 0;
+    float *const obase = (second ? a.out2 : a.out1) + sub;
+    const uint32_t old = second ? a.ld2 : a.ld1;
+
+    for (;;) {
+        const uint32_t tile_n = tile + n_waves;
+        uint32_t v_nxt[NA];
+#pragma unroll
+        for (int i = 0; i < NA; ++i) v_nxt[i] = a.list[min(tile_n * BM + r_own + 8 * i, count - 1u)];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            // the wavefront's LDS accesses are served in order: slice s (written during step s - 1) is complete
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            if (s == 0 && c4a == 0) {
+#pragma unroll
+                for (int i = 0; i < NA; ++i) s_vtx[r_own + 8 * i] = ho_cur[i] >> 10;
+            }
+            if (s == 1) {
+#pragma unroll
+                for (int i = 0; i < NA; ++i) ho_nxt[i] = v_nxt[i] * 1024u + c4a * 4u;
+            }
+            float av[2];
+            av[0] = As[s & 1][lane & 31][lane >> 5];
+#pragma unroll
+            for (int q = 0; q < KP; ++q) {
+                const int cur = q & 1, nxt = cur ^ 1;
+                if (q + 1 < KP) av[nxt] = As[s & 1][lane & 31][2 * (q + 1) + (lane >> 5)];
+                __builtin_amdgcn_sched_barrier(0);
+                acc[0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur], bq[q % WLEAD].x, acc[0], 0, 0, 0);
+                acc[1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur], bq[q % WLEAD].y, acc[1], 0, 0, 0);
+                acc[2] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur], bq[q % WLEAD].z, acc[2], 0, 0, 0);
+                // the pair WLEAD on (past the slice's end: of the next slice; after the last slice: slice 0, for the next tile)
+                bq[q % WLEAD] = (q + WLEAD < KP) ? load_w(s, q + WLEAD) : load_w((s + 1) % KS, q + WLEAD - KP);
+                if (q == 10) {                             // slice s + 1 into the other LDS buffer
+                    stage((s + 1) & 1, ra[(s + 1) & 1]);
+                } else if (q == 11) {                      // and slice s + 3 into the registers it came from
+#pragma unroll
+                    for (int i = 0; i < NA; ++i)
+                        ra[(s + 1) & 1][i] = load_h((s + 3 < KS) ? ho_cur[i] : ho_nxt[i], (s + 3) % KS);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+        // the tile's 32 x 96 results leave straight from the accumulators: element r of block j is row
+        // 8 (r >> 2) + 4 (lane >> 5) + (r & 3), column 16 j + sub of this lane's product
+        const uint32_t rows = min((uint32_t)BM, count - tile * BM);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const uint32_t lr = (r >> 2) * 8 + (lane >> 5) * 4 + (r & 3);
+            if (lr < rows) {
+                float *o = obase + (size_t)s_vtx[lr] * old;
+                o[0] = acc[0][r];
+                if (16u + sub < a.d_out) o[16] = acc[1][r];
+                if (32u + sub < a.d_out) o[32] = acc[2][r];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < 3; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[j][r] = 0.0f;
+#pragma unroll
+        for (int i = 0; i < NA; ++i) ho_cur[i] = ho_nxt[i];
+        tile = tile_n;
+        if (tile >= n_tiles) break;
+    }
+}
+
+bool rp_launch_project_both_stream(ripple_ctx *c, uint32_t l, const uint32_t *list, const uint32_t *count_d, float *out2,
+                                   uint32_t ld2, uint32_t rows_hint) {
+    const LayerDev &ly = c->layers[l - 1];
+    if (!c->opt_stream || !ly.Wc96p || c->store || ly.d_in != 256 || ly.d_out > 48 || ly.d_out < 17) return false;
+    if ((uint64_t)c->n_cap * 1024u > 0xFFFFF000ull) return false;
+    if (rows_hint < 131072u) return false;                         // enough 32-row tiles for every wavefront of the chip
+    PArgs a;
+    a.list = list;
+    a.count_ptr = count_d;
+    a.H = (const float *)c->H[l - 1];
+    a.Wp = ly.Wc96p;
+    a.out1 = ly.PS;
+    a.ld1 = ly.d_out;
+    a.out2 = out2;
+    a.ld2 = ld2;
+    a.d_out = ly.d_out;
+    a.n_cap = c->n_cap;
+    hipLaunchKernelGGL(k_project_both_stream, dim3(3 * c->n_cu), dim3(256), 0, c->stream, a);
+    return true;
+}
