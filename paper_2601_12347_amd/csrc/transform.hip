@@ -412,6 +412,70 @@ __device__ __forceinline__ void addend_only_rows(const TArgs &a) {
     }
 }
 
+// The same for sum / mean layers (no denominators), element by element over the flattened (slot, column) space: rows
+// of a narrow layer (47 columns) leave a quarter of a wavefront idle when a lane is a column, and consecutive slots are
+// mostly consecutive vertices, so consecutive lanes read consecutive addresses across row ends. OLD: the stored row is
+// read (a delta row is written); ADD2: there is a cached self term.
+template <bool BF, bool OLD, bool ADD2>
+__global__ __launch_bounds__(256) void k_transform_addend_flat(TArgs a) {
+    constexpr int U = 4;                                   // elements per thread and round: their loads overlap
+    const uint32_t count = *a.count_ptr;
+    const uint32_t total = count * a.N;                    // < 2^32 (checked by the launch)
+    const uint32_t stride = gridDim.x * blockDim.x;
+    for (uint64_t e0 = blockIdx.x * blockDim.x + threadIdx.x; e0 < total; e0 += (uint64_t)stride * U) {
+        uint32_t col[U];
+        size_t hidx[U];
+        float sc[U], y[U], p[U], old[U];
+        bool ok[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const uint64_t e = e0 + (uint64_t)u * stride;
+            ok[u] = e < total;
+            const uint32_t ec = ok[u] ? (uint32_t)e : total - 1u;   // past the end: the last element again, not stored
+            const uint32_t slot = ec / a.N;
+            col[u] = ec - slot * a.N;
+            const uint32_t v = a.list[slot];
+            hidx[u] = (size_t)v * a.N + col[u];
+            const uint32_t deg = a.in_meta[v].y;
+            sc[u] = a.mean ? 1.0f / (float)(deg > 1u ? deg : 1u) : 1.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            y[u] = a.addend[hidx[u]];
+            p[u] = ADD2 ? a.addend2[hidx[u]] : 0.0f;
+            old[u] = !OLD ? 0.0f : BF ? __bfloat162float(((const __hip_bfloat16 *)a.Hout)[hidx[u]]) : ((const float *)a.Hout)[hidx[u]];
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            if (!ok[u]) continue;
+            float z = y[u] * sc[u] + a.bias[col[u]] + p[u];
+            if (a.act == RIPPLE_ACT_RELU) z = z > 0.0f ? z : 0.0f;
+            if (BF) {
+                const __hip_bfloat16 zr = __float2bfloat16(z);
+                z = __bfloat162float(zr);
+                ((__hip_bfloat16 *)a.Hout)[hidx[u]] = zr;
+            } else {
+                ((float *)a.Hout)[hidx[u]] = z;
+            }
+            if (OLD) a.D[hidx[u]] = a.d_old ? old[u] : z - old[u];
+        }
+    }
+}
+
+static void launch_addend_flat(ripple_ctx *c, const TArgs &a) {
+    const dim3 grid(c->n_cu * 16), block(256);
+#define RP_FLAT(BF, OLD, ADD2) hipLaunchKernelGGL((k_transform_addend_flat<BF, OLD, ADD2>), grid, block, 0, c->stream, a)
+    const bool old = a.D != nullptr, add2 = a.addend2 != nullptr;
+    if (a.store) {
+        if (old) { if (add2) RP_FLAT(true, true, true); else RP_FLAT(true, true, false); }
+        else { if (add2) RP_FLAT(true, false, true); else RP_FLAT(true, false, false); }
+    } else {
+        if (old) { if (add2) RP_FLAT(false, true, true); else RP_FLAT(false, true, false); }
+        else { if (add2) RP_FLAT(false, false, true); else RP_FLAT(false, false, false); }
+    }
+#undef RP_FLAT
+}
+
 __global__ __launch_bounds__(256) void k_transform_addend_only(TArgs a) {
     if (a.store) addend_only_rows<true>(a);
     else addend_only_rows<false>(a);
@@ -1252,7 +1316,8 @@ void rp_launch_transform(ripple_ctx *c, uint32_t l, const uint32_t *list, const 
         a.act = (int)ly.act_out;
         if (ly.self_mode == RIPPLE_SELF_NONE || ly.selfc) {
             a.addend2 = ly.selfc ? ly.PS : nullptr;
-            hipLaunchKernelGGL(k_transform_addend_only, dim3(c->n_cu * 8), dim3(256), 0, c->stream, a);
+            if (hint >= 65536u && (uint64_t)c->n_cap * a.N < (1ull << 32)) launch_addend_flat(c, a);  // many rows: every lane busy, whatever the row width
+            else hipLaunchKernelGGL(k_transform_addend_only, dim3(c->n_cu * 8), dim3(256), 0, c->stream, a);
             return;
         }
         a.a_mode = 4;                            // h_self * W_self: the first d_in rows of W0
