@@ -294,7 +294,7 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
                 if (col < d && acc[j] != 0.0f) unsafeAtomicAdd(&xr[col], acc[j]);
                 acc[j] = 0.0f;
             }
-            if (DISC && lane == 0) atomicOr(&a.bm_cur[cur >> 5], 1u << (cur & 31));   // once per receiver and chunk
+            if (DISC && lane == 0) atomicOr(&a.bm_cur[cur >> 5], 1u << (cur & 31));   // once per receiver and wavefront
             return;
         }
         if (cur == v_head || cur == v_tail) {
@@ -379,18 +379,12 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
                 }
             }
         }
-        if (!DET) {                                          // one addition per receiver and chunk
-            if (cur != NONE) flush();
-            cur = NONE;
-        }
-        scan.advance();
+        scan.advance();                                      // the destination and its partial sum carry over to the next chunk
     }
-    if (DET) {
-        if (cur != NONE) flush();
-        if (lane == 0) {
-            a.side_v[2 * gw] = wrote_head ? v_head : NONE;
-            a.side_v[2 * gw + 1] = wrote_tail ? v_tail : NONE;
-        }
+    if (cur != NONE) flush();
+    if (DET && lane == 0) {
+        a.side_v[2 * gw] = wrote_head ? v_head : NONE;
+        a.side_v[2 * gw + 1] = wrote_tail ? v_tail : NONE;
     }
 }
 
