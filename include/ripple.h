@@ -184,9 +184,10 @@ typedef enum {
                                      8 bytes, so that a number is off by at most 2^-19 of the largest of its three. What the
                                      rounding takes from a message is carried into the sender's next one: the cached
                                      aggregates stay the exact sum of what was sent and nothing accumulates. */
-    RIPPLE_OPT_STREAM_TRANSFORM = 11, /* 0/1 (default 1): large row updates of 256 -> 256 layers (fp32 rows) run in persistent
+    RIPPLE_OPT_STREAM_TRANSFORM = 11, /* 0/1/2 (default 1): large row updates of 256 -> 256 layers (fp32 rows) run in persistent
                                      workgroups that write a finished tile while the next one is being multiplied; 0 keeps
-                                     the one-tile-per-workgroup kernel. Same arithmetic, same results. */
+                                     the one-tile-per-workgroup kernel; 2 takes the streaming kernel whatever the number of
+                                     rows (for tests). Same arithmetic up to rounding order. */
     RIPPLE_OPT_DETERMINISTIC = 6  /* 0/1 (default 0), before load_model: every sum is taken in an order that is a function of
                                      the graph and the batches alone (no float atomics: in-rows keep a reproducible order,
                                      hops are gathered along them, rows that several wavefronts read are finished in

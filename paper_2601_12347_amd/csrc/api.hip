@@ -1360,7 +1360,8 @@ extern "C" ripple_status ripple_set_option(ripple_ctx *c, int option, int64_t va
         c->opt_pack = value ? 1 : 0;
         return RIPPLE_OK;
     case RIPPLE_OPT_STREAM_TRANSFORM:
-        c->opt_stream = value ? 1 : 0;
+        if (value < 0 || value > 2) return fail(c, RIPPLE_EINVAL, "RIPPLE_OPT_STREAM_TRANSFORM must be 0, 1 or 2");
+        c->opt_stream = (int)value;
         return RIPPLE_OK;
     case RIPPLE_OPT_PULL_RATIO:
         if (value < 1 || value > 1024) return fail(c, RIPPLE_EINVAL, "pull ratio must be in 1..1024");

@@ -208,7 +208,7 @@ struct ripple_ctx {
     int opt_project = 1;                        // allow project-first layers (read by load_model)
     int opt_selfcache = 1;                      // allow cached self projections (read by load_model)
     int opt_sparse = 1;                         // small frontiers are listed as they are marked (no bitmap scan)
-    int opt_stream = 1;                         // large 256 -> 256 row updates: persistent workgroups, tiles written while the next is multiplied
+    int opt_stream = 1;                         // large 256 -> 256 row updates: persistent workgroups, tiles written while the next is multiplied (2: any size)
     int opt_split = 0;                          // fp32 storage: products on the bf16 matrix cores, operands split in three (read by load_model)
     int opt_deterministic = 0;                  // bit-reproducible aggregation (owner kernels, no float atomics)
     int opt_pull_ratio = 1;                     // pull when messages * width * ratio >= scanned in-edges

@@ -13,8 +13,8 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 // interleaved columns (block j holds columns 64 w + 2 n + j), so that everything a lane reads or writes per row is
 // eight adjacent bytes. Workgroups are persistent and no part of a tile waits for memory on its own:
 //  * the weights never pass through LDS: a wavefront only needs its own 64 columns, so each lane loads the two
-//    numbers it feeds into the matrix cores for a pair of k straight from the (L2-resident) matrix, one step ahead,
-//    into the register the same pair of k of the current step has just freed;
+//    numbers it feeds into the matrix cores for a pair of k straight from the (L2-resident) matrix, eight pairs
+//    (half a step) ahead, into the register an earlier pair has just freed;
 //  * the gathered rows pass through a double-buffered LDS slice (one barrier per step): slice s + 1 is written while
 //    slice s is multiplied, from registers requested two steps earlier, also across the tile boundary;
 //  * the finished tile's accumulators are parked in a second set of registers and leave for memory in eight chunks
@@ -27,7 +27,7 @@ typedef float floatx2 __attribute__((ext_vector_type(2)));
 // The launch therefore requires vertex_capacity * 1 KB < 4 GB - 4 KB.
 template <bool ADD, bool DELTA>
 __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n_cap) {
-    constexpr int BM = 64, KS = 8, NA = 2, LEAD = 2, KP = T_BK / 2;
+    constexpr int BM = 64, KS = 8, NA = 2, LEAD = 2, KP = T_BK / 2, WLEAD = 8;
     __shared__ __attribute__((aligned(16))) float As[2][BM][T_BK + 1];
     __shared__ uint32_t s_vtx[2][BM];
     __shared__ float s_scale[2][BM];
@@ -88,13 +88,13 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n
     };
 
     floatx4 ra[2][NA];                                     // ra[p]: the slice that goes to As[p] next
-    floatx2 bq[KP];
+    floatx2 bq[WLEAD];                                     // bq[q % WLEAD]: pair q of k, requested WLEAD pairs before its use
 #pragma unroll
     for (int i = 0; i < NA; ++i) ra[0][i] = load_x(xo_cur[i], 0);
 #pragma unroll
     for (int i = 0; i < NA; ++i) ra[1][i] = load_x(xo_cur[i], 1);
 #pragma unroll
-    for (int q = 0; q < KP; ++q) bq[q] = load_w(0, q);
+    for (int q = 0; q < WLEAD; ++q) bq[q] = load_w(0, q);
     stage_x(0, ra[0]);
 #pragma unroll
     for (int i = 0; i < NA; ++i) ra[0][i] = load_x(xo_cur[i], 2);
@@ -191,11 +191,12 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int i = 0; i < 2; ++i) {
-                    acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][i], bq[q].x, acc[i][0], 0, 0, 0);
-                    acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][i], bq[q].y, acc[i][1], 0, 0, 0);
+                    acc[i][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][i], bq[q % WLEAD].x, acc[i][0], 0, 0, 0);
+                    acc[i][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(av[cur][i], bq[q % WLEAD].y, acc[i][1], 0, 0, 0);
                 }
-                // between the products: the same pair of k of the next slice (after the last: slice 0, for the next tile) ...
-                bq[q] = load_w((s + 1) % KS, q);
+                // between the products: the pair WLEAD on (past the slice's end: of the next slice; after the last
+                // slice: slice 0, for the next tile) ...
+                bq[q % WLEAD] = (q + WLEAD < KP) ? load_w(s, q + WLEAD) : load_w((s + 1) % KS, q + WLEAD - KP);
                 // ... and one piece of the parked tile's traffic or of the row staging. Chunk s of the parked tile,
                 // requested LEAD steps ago, is finished; the chunk LEAD on is requested (the first LEAD chunks of the
                 // tile being multiplied, once the parked one has none left).
@@ -248,7 +249,8 @@ __global__ __launch_bounds__(256, 2) void k_transform_stream(TArgs a, uint32_t n
     }
 }
 
-// x W with K = N = 256 on fp32 rows, H updated in place, and enough rows for every persistent workgroup to see several tiles
+// x W with K = N = 256 on fp32 rows, H updated in place, and enough rows for every persistent workgroup to see several
+// tiles (RIPPLE_OPT_STREAM_TRANSFORM = 2: whatever the number of rows)
 bool rp_launch_stream(ripple_ctx *c, const TArgs &a, uint32_t rows_hint) {
     if (!c->opt_stream || a.a_mode != 0 || a.store || a.Ws || a.out_mode != 1) return false;
     if (a.K != 256 || a.Kpad != 256 || a.N != 256 || a.Npad != 256 || a.d_in != 256) return false;

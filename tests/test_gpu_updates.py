@@ -75,6 +75,37 @@ def test_push_and_pull_scatter_agree_with_oracle(mode, kind, widths):
         pair.close()
 
 
+STREAM_CASES = [(mode, kind, widths, weighted) for kind, widths, weighted in
+                [("sage_mean", (24, 256, 256, 40), False), ("gcn_sum", (24, 256, 256, 256, 12), False),
+                 ("gcn_wsum", (16, 256, 256, 30), True), ("sage_mean", (24, 256, 256, 256), False)]
+                for mode in (0, 1, 2, 3) if not (weighted and mode == 1)]
+
+
+@pytest.mark.parametrize("mode,kind,widths,weighted", STREAM_CASES)
+def test_streaming_row_update_at_any_size(mode, kind, widths, weighted):
+    """Layers of 256 -> 256 forced onto the persistent streaming row update whatever the number of rows (it is chosen
+    for large hops only otherwise): hops of a handful of rows, of less than a tile, of a few tiles with a ragged last
+    one. Every row of every layer, the cached aggregates and the sets against the oracle after every batch, in
+    every scatter mode, with delta rows written (a 256 -> 256 layer before another) and without (before a
+    project-first layer, or last), with and without a cached self term."""
+    print("case streaming row update", mode, kind, widths, flush=True)
+    pair, graph = make_pair(n=1300, e=14000, d0=widths[0], kind=kind, widths=widths, seed=171, slack=96, weighted=weighted)
+    rp.ripple_set_option(pair.ctx, rp.OPT_STREAM_TRANSFORM, 2)
+    rp.ripple_set_option(pair.ctx, rp.OPT_SCATTER_MODE, mode)
+    rp.ripple_full_infer(pair.ctx)                       # the bootstrap through the streaming kernel as well
+    stream = make_stream(pair, graph, MIXV, 173, weighted=weighted)
+    try:
+        pair.check_embeddings()
+        for b, bs in enumerate([1, 30, 250, 250, 5]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            pair.step(ops, payload)
+            pair.check_aggregates()
+        pair.check_graph()
+    finally:
+        pair.close()
+
+
 PACKED_CASES = [(mode, *case) for case in [("sage_mean", (12, 96, 47), "f32", False), ("gcn_sum", (80, 33), "f32", False),
                                            ("gcn_wsum", (16, 100, 40), "f32", True), ("gcn_sum", (24, 88, 44), "bf16", False)]
                 for mode in (0, 1, 2, 3) if not (case[3] and mode == 1)]      # weighted layers have no push kernel
