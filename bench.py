@@ -37,7 +37,7 @@ def log(*a):
 # the profiler on itself; for any other workload `traffic` is null.
 TRAFFIC_SOURCE = "profiles/hbm_traffic_dense_sage_mean_bs10000_pmc.txt"
 MEASURED_TRAFFIC_BYTES = {
-    ("dense_sage_mean", 10000): {"scatter_l3": 9.9e9, "scatter_l2": 6.5e9, "transform_l2": 5.0e9, "transform_l3": 5.3e9},
+    ("dense_sage_mean", 10000): {"scatter_l3": 9.9e9, "scatter_l2": 6.2e9, "transform_l2": 4.9e9, "transform_l3": 5.0e9},
 }
 
 
@@ -191,6 +191,8 @@ def main():
     ap.add_argument("--split-mfma", type=int, default=-1,
                     help="fp32 storage: 1 = products on the bf16 matrix cores with operands split in three, 0 = fp32 matrix path")
     ap.add_argument("--bf16-mfma", type=int, default=1, help="bf16 storage only: 0 = multiply on the fp32 matrix path")
+    ap.add_argument("--stream-transform", type=int, default=-1,
+                    help="0 = tiled kernels for the 256 -> 256 row updates and the last layer's projections; 1 = streaming kernels on large hops (default); 2 = at any size")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="leave the library's per-kernel HIP events off (no roofline object; lowest latency)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -246,6 +248,8 @@ def main():
     rp.ripple_set_option(ctx, rp.OPT_SCATTER_MODE, args.scatter_mode)
     if args.sparse_frontier >= 0:
         rp.ripple_set_option(ctx, rp.OPT_SPARSE_FRONTIER, args.sparse_frontier)
+    if args.stream_transform >= 0:
+        rp.ripple_set_option(ctx, rp.OPT_STREAM_TRANSFORM, args.stream_transform)
     rp.ripple_set_option(ctx, rp.OPT_BF16_MFMA, args.bf16_mfma)
     if args.pull_ratio:
         rp.ripple_set_option(ctx, rp.OPT_PULL_RATIO, args.pull_ratio)
