@@ -193,6 +193,7 @@ def main():
     ap.add_argument("--bf16-mfma", type=int, default=1, help="bf16 storage only: 0 = multiply on the fp32 matrix path")
     ap.add_argument("--stream-transform", type=int, default=-1,
                     help="0 = tiled kernels for the 256 -> 256 row updates and the last layer's projections; 1 = streaming kernels on large hops (default); 2 = at any size")
+    ap.add_argument("--sorted-messages", type=int, default=-1, help="RIPPLE_OPT_SORTED_MESSAGES (default 1)")
     ap.add_argument("--no-kernel-timing", action="store_true",
                     help="leave the library's per-kernel HIP events off (no roofline object; lowest latency)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -248,6 +249,8 @@ def main():
     rp.ripple_set_option(ctx, rp.OPT_SCATTER_MODE, args.scatter_mode)
     if args.sparse_frontier >= 0:
         rp.ripple_set_option(ctx, rp.OPT_SPARSE_FRONTIER, args.sparse_frontier)
+    if args.sorted_messages >= 0:
+        rp.ripple_set_option(ctx, rp.OPT_SORTED_MESSAGES, args.sorted_messages)
     if args.stream_transform >= 0:
         rp.ripple_set_option(ctx, rp.OPT_STREAM_TRANSFORM, args.stream_transform)
     rp.ripple_set_option(ctx, rp.OPT_BF16_MFMA, args.bf16_mfma)

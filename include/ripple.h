@@ -136,7 +136,8 @@ typedef struct {
     uint32_t mono_recomputed[RIPPLE_MAX_LAYERS + 1];
     /* sum, mean and weighted-sum layers: how hop l moved its messages (Sec. 3.5 compares the costs): 1 pushed
      * along the out-edges of A_{l-1}, 2 pulled through the in-rows of A_l, 3 one scan of all in-rows that also
-     * found A_l; 0 where no such kernel ran (no messages, other aggregators, deterministic mode). A batch that
+     * found A_l, 4 gathered from the list of the hop's messages sorted by destination (RIPPLE_OPT_SORTED_MESSAGES);
+     * 0 where no such kernel ran (no messages, other aggregators, deterministic mode). A batch that
      * was cut into pieces reports its last piece. */
     uint32_t hop_mode[RIPPLE_MAX_LAYERS + 1];
     /* operations of the batch, counted from its start, that took effect: n_ops on success; on a capacity or
@@ -188,6 +189,11 @@ typedef enum {
                                      workgroups that write a finished tile while the next one is being multiplied; 0 keeps
                                      the one-tile-per-workgroup kernel; 2 takes the streaming kernel whatever the number of
                                      rows (for tests). Same arithmetic up to rounding order. */
+    RIPPLE_OPT_SORTED_MESSAGES = 12, /* 0/1/2 (default 1): a hop that would be pulled while few of the scanned in-row entries
+                                      carry a message is scattered from the list of its messages instead, which the out-edge
+                                      walk writes down and a radix sort orders by destination; 1 where the previous batch's
+                                      counts say so, 2 wherever a hop is pulled (tests), 0 never. Same results up to the order
+                                      of the sums. Not used in the deterministic mode, by weighted-sum layers or packed rows. */
     RIPPLE_OPT_DETERMINISTIC = 6  /* 0/1 (default 0), before load_model: every sum is taken in an order that is a function of
                                      the graph and the batches alone (no float atomics: in-rows keep a reproducible order,
                                      hops are gathered along them, rows that several wavefronts read are finished in

@@ -28,6 +28,7 @@ OPT_SPARSE_FRONTIER = 8
 OPT_ROW_SEGMENTS = 9
 OPT_PACKED_MESSAGES = 10
 OPT_STREAM_TRANSFORM = 11
+OPT_SORTED_MESSAGES = 12
 AGG = {"sum": 0, "mean": 1, "wsum": 2, "max": 3, "min": 4, "attn": 5}
 SELF = {"none": 0, "concat": 1, "add": 2}
 ACT = {"none": 0, "relu": 1}

@@ -257,7 +257,7 @@ extern "C" void ripple_destroy(ripple_ctx *c) {
                     c->dead_in, c->hole_out, c->hole_in, c->out_pool, c->in_pool, c->in_w, c->alive, c->part_cnt, c->part_deg, c->part_ideg, c->ioff[0], c->ctr, c->D[0], c->D[1],
                     c->tmp, c->PD, c->MSG, c->side_v, c->side_acc, c->Pold, c->sold, c->seg_v, c->seg_done, c->seg_base, c->seg_r, c->seg_part, c->bm[0], c->rep[0], c->list[0], c->eoff[0], c->all_list, c->ioff_all, c->mk, c->ops_d, c->payload_d,
                     c->op_status, c->op_pos_out, c->op_pos_in, c->op_touch, c->touch_out, c->touch_in, c->exp_kind, c->exp_s, c->exp_a,
-                    c->exp_b, c->st_src, c->st_dst, c->st_sign, c->st_unit, c->tail_ids, c->tail_q, c->tail_w, c->sk_in, c->sk_out, c->sv_in, c->sv_out, c->sort_tmp, c->gather_d, c->gather_ids};
+                    c->exp_b, c->st_src, c->st_dst, c->st_sign, c->st_unit, c->tail_ids, c->tail_q, c->tail_w, c->sk_in, c->sk_out, c->sv_in, c->sv_out, c->sort_tmp, c->gather_d, c->gather_ids, c->pk_a, c->pk_b, c->pv_a, c->pv_b, c->pair_tmp};
     for (void *p : ptrs)
         if (p) hipFree(p);
     for (uint32_t l = 0; l <= RIPPLE_MAX_LAYERS; ++l) {
@@ -503,6 +503,25 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
         const size_t entries = 2 * (size_t)c->n_cu * 8 * 4;
         RP_TRY(dev_alloc(c, &c->side_v, entries, false));
         RP_TRY(dev_alloc(c, &c->side_acc, entries * xmax, false));
+    }
+    if (!c->opt_deterministic) {
+        // (destination, source) pairs of a hop's messages, before and after the sort by destination: room for a quarter
+        // of the edge capacity (a hop with more messages than that is pulled or discovers), at most 2^25
+        c->pair_cap = (uint32_t)std::min<uint64_t>(std::max<uint64_t>(c->pool_cap / 4, 1u << 14), 1u << 25);
+        c->pair_bits = 1;
+        while (c->pair_bits < 32 && (1ull << c->pair_bits) <= n) ++c->pair_bits;   // 2^bits > every vertex id; the filler key has all of them set
+        c->pair_tmp_bytes = rp_sort_u32_tmp_bytes(c->pair_cap);
+        if (c->pair_tmp_bytes) {
+            uint8_t *tmp = nullptr;
+            RP_TRY(dev_alloc(c, &c->pk_a, c->pair_cap, false));
+            RP_TRY(dev_alloc(c, &c->pk_b, c->pair_cap, false));
+            RP_TRY(dev_alloc(c, &c->pv_a, c->pair_cap, false));
+            RP_TRY(dev_alloc(c, &c->pv_b, c->pair_cap, false));
+            RP_TRY(dev_alloc(c, &tmp, c->pair_tmp_bytes, false));
+            c->pair_tmp = tmp;
+        } else {
+            c->pair_cap = 0;
+        }
     }
     // bitmaps: layers 0..L, then S, then V_added, contiguous; reporting copies separately
     uint32_t *bmall = nullptr, *repall = nullptr, *lists = nullptr, *eoffs = nullptr, *ioffs = nullptr;
@@ -912,8 +931,20 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
             rp_launch_alive_list(c);
             have_all = true;
         }
+        // A hop that the last batch pulled through in-rows holding at least eight times as many entries as it had
+        // messages is taken from the sorted list of its messages (k_scatter_sorted): the out-edge walk writes the
+        // list, and as many entries are sorted as the last batch had messages, and a quarter more. The kernels make
+        // sure on the device that the list is only used if this batch's messages fit; else the hop is pulled.
+        uint32_t pair_cap = 0;
+        if (may_pull && !wsum && !sparse && c->pair_cap && c->opt_sorted && !(c->layers[l - 1].proj && c->layers[l - 1].packed)) {
+            if (c->opt_sorted == 2) pair_cap = c->pair_cap;
+            else if (c->hints_valid && c->last_m[l] && RP_SORTED_FACTOR * c->last_m[l] <= c->last_isum[l]) {
+                const uint64_t want = ((uint64_t)c->last_m[l] + c->last_m[l] / 4 + 4096) & ~4095ull;
+                if (want <= c->pair_cap) pair_cap = (uint32_t)want;
+            }
+        }
         if (sparse) rp_launch_frontier_sparse(c, l, layer_self(c, l), l < c->L);
-        else rp_launch_frontier_mark(c, l, may_disc);
+        else rp_launch_frontier_mark(c, l, may_disc, pair_cap);
         rp_timer_end(c, t, RIPPLE_PH_FRONTIER, (int)l);
         const bool both = rp_has_project_both(c, l);
         if (c->layers[l - 1].proj) {                   // what travels is already multiplied by W_neigh
@@ -940,7 +971,8 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
         }
         t = rp_timer_begin(c);
         if (!wsum && (c->opt_scatter < 2 || !may_pull)) rp_launch_scatter_push(c, l, may_pull, may_disc);
-        if (may_pull) rp_launch_scatter_pull(c, l, false, may_disc);
+        if (pair_cap && !rp_launch_scatter_sorted(c, l, may_disc, pair_cap)) pair_cap = 0;
+        if (may_pull) rp_launch_scatter_pull(c, l, false, may_disc, pair_cap);
         rp_timer_end(c, t, RIPPLE_PH_SCATTER, (int)l);
         t = rp_timer_begin(c);
         rp_launch_transform(c, l, c->list[l], &c->ctr->a[l], next_reads_delta(c, l));
@@ -1053,6 +1085,7 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
             msgs[l] += h.m[l];
             tchd[l] += h.touched[l];
             c->last_m[l] = h.m[l];
+            c->last_isum[l] = h.isum[l];
             hop_mode[l] = h.hop_mode[l];
             for (int k = 0; k < 3; ++k) mono[k][l] += h.mono[k][l];
             c->last_cand[l] = h.mono[0][l] + h.mono[1][l] + h.mono[2][l];
@@ -1362,6 +1395,10 @@ extern "C" ripple_status ripple_set_option(ripple_ctx *c, int option, int64_t va
     case RIPPLE_OPT_STREAM_TRANSFORM:
         if (value < 0 || value > 2) return fail(c, RIPPLE_EINVAL, "RIPPLE_OPT_STREAM_TRANSFORM must be 0, 1 or 2");
         c->opt_stream = (int)value;
+        return RIPPLE_OK;
+    case RIPPLE_OPT_SORTED_MESSAGES:
+        if (value < 0 || value > 2) return fail(c, RIPPLE_EINVAL, "RIPPLE_OPT_SORTED_MESSAGES must be 0, 1 or 2");
+        c->opt_sorted = (int)value;
         return RIPPLE_OK;
     case RIPPLE_OPT_PULL_RATIO:
         if (value < 1 || value > 1024) return fail(c, RIPPLE_EINVAL, "pull ratio must be in 1..1024");

@@ -196,6 +196,14 @@ struct ripple_ctx {
     bool hints_valid = false;                           // last_a / last_cand describe a batch (not the state after the bootstrap)
     uint32_t last_cand[RIPPLE_MAX_LAYERS + 1] = {0};
     uint32_t last_m[RIPPLE_MAX_LAYERS + 1] = {0};       // messages per hop of the last batch (a size hint)
+    uint32_t last_isum[RIPPLE_MAX_LAYERS + 1] = {0};    // in-row entries a pull of that hop would have scanned
+    // messages of a hop as (destination, source) pairs, as the out-edge walk lists them and sorted by destination
+    uint32_t *pk_a = nullptr, *pk_b = nullptr, *pv_a = nullptr, *pv_b = nullptr;
+    uint32_t pair_cap = 0;
+    void *pair_tmp = nullptr;
+    size_t pair_tmp_bytes = 0;
+    unsigned pair_bits = 32;                            // key bits that tell vertex ids and the filler key apart
+    int opt_sorted = 1;                                 // 0 never, 1 where the last batch says it pays, 2 wherever a hop is pulled
     uint32_t last_n_ops = 0;                            // operations of the last single-piece batch    // candidates of the last batch's max / min hops (a size hint)
     bool last_from_rep = false;
     bool push_margin[RIPPLE_MAX_LAYERS + 1] = {false};  // last batch pushed at this hop by a wide margin
@@ -368,12 +376,22 @@ __device__ __forceinline__ float rp_msg_decode_col(uint2 c, uint32_t col) {
 #define RP_HOP_PUSH 0
 #define RP_HOP_PULL 1
 #define RP_HOP_DISCOVER 2
+#define RP_HOP_SORTED 3                 // a pull whose messages were listed by the out-edge walk and sorted by destination (reported only)
 __device__ __forceinline__ int rp_hop_mode(const DevCtr *ctr, uint32_t l, uint32_t d, int mode, int ratio, int allow_disc) {
     const unsigned long long m = ctr->m[l];
     if (allow_disc && m > 0 && (mode == 3 || ((mode == 0 || mode == 4) && m * 8ull >= ctr->n_edges))) return RP_HOP_DISCOVER;
     if (mode == 1) return RP_HOP_PUSH;
     if (mode >= 2) return RP_HOP_PULL;
     return (m > 0 && m * d * 4ull * (unsigned long long)ratio >= 8ull * ctr->isum[l]) ? RP_HOP_PULL : RP_HOP_PUSH;
+}
+
+// A hop that would be pulled is taken from the sorted list of its messages instead when the list was made (M fits
+// the `cap` entries the host sorted) and the in-rows that a pull would scan hold at least RP_SORTED_FACTOR times as
+// many entries as there are messages (force: whatever they hold): sorting a pair costs about as much as eight
+// tests of an in-neighbour. M: out-edges of A_{l-1}.
+#define RP_SORTED_FACTOR 8ull
+__device__ __forceinline__ bool rp_hop_sorted(const DevCtr *ctr, uint32_t l, uint32_t M, uint32_t cap, int force) {
+    return cap && M > 0 && M <= cap && (force || RP_SORTED_FACTOR * M <= ctr->isum[l]);
 }
 
 // position of `target` in row[0..len), searched by one wavefront; -1 when absent. Long (hub) rows

@@ -87,10 +87,11 @@ __device__ __forceinline__ void sparse_enter(const SparseArgs &s, uint32_t v, bo
     sparse_enter_many<1>(s, one, from_edge);
 }
 
-template <bool SPARSE>
+// EMIT: edge e of the flattened out-edge space is also written down as the pair (destination, source) in pk[e], pv[e]
+template <bool SPARSE, bool EMIT = false>
 __device__ __forceinline__ void frontier_walk(const uint32_t *list, const uint32_t *count_ptr, const uint32_t *eoff,
                                               const uint2 *out_meta, const uint32_t *out_pool, uint8_t *mk,
-                                              const SparseArgs &sp) {
+                                              const SparseArgs &sp, uint32_t *pk = nullptr, uint32_t *pv = nullptr) {
     const uint32_t count = *count_ptr;
     if (count == 0) return;
     constexpr int T = MARK_CHUNK / 64;
@@ -105,10 +106,11 @@ __device__ __forceinline__ void frontier_walk(const uint32_t *list, const uint32
     if (c_begin >= c_end) return;
     const uint32_t last = count - 1;
     uint32_t i_lo = rp_seg_search_wave(eoff, 0, last, c_begin * chunk);
-    uint32_t rbase, bnd;                                    // lane j: row i_lo + j
+    uint32_t rbase, bnd, rsrc = 0;                          // lane j: row i_lo + j
     {
         const uint32_t ri = min(last, i_lo + lane);
-        rbase = out_meta[list[ri]].x - eoff[ri];            // pool position of edge e: rbase + e (mod 2^32)
+        rsrc = list[ri];
+        rbase = out_meta[rsrc].x - eoff[ri];                // pool position of edge e: rbase + e (mod 2^32)
         bnd = eoff[min(count, i_lo + 1 + lane)];
     }
     for (uint32_t c = c_begin; c < c_end; ++c) {
@@ -123,6 +125,13 @@ __device__ __forceinline__ void frontier_walk(const uint32_t *list, const uint32
                 const int r = (int)min(63u, rp_count_le(bnd, e));
                 const uint32_t base = __shfl(rbase, r);
                 v[t] = (e < e1) ? out_pool[base + e] : 0xFFFFFFFFu;
+                if (EMIT) {
+                    const uint32_t u = __shfl(rsrc, r);
+                    if (e < e1) {
+                        pk[e] = v[t];
+                        pv[e] = u;
+                    }
+                }
             }
             i_nx = min(last, i_lo + rp_count_le(bnd, e1));
         } else {
@@ -133,15 +142,21 @@ __device__ __forceinline__ void frontier_walk(const uint32_t *list, const uint32
                 v[t] = 0xFFFFFFFFu;
                 if (e < e1) {
                     const uint32_t i = rp_seg_search(eoff, i_lo, i_hi, e);
-                    v[t] = out_pool[out_meta[list[i]].x + (e - eoff[i])];
+                    const uint32_t u = list[i];
+                    v[t] = out_pool[out_meta[u].x + (e - eoff[i])];
+                    if (EMIT) {
+                        pk[e] = v[t];
+                        pv[e] = u;
+                    }
                 }
             }
             i_nx = rp_seg_forward(eoff, i_hi, last, e1);
         }
-        uint32_t rbase_n, bnd_n;                            // next chunk's rows, requested before the marks
+        uint32_t rbase_n, bnd_n, rsrc_n;                    // next chunk's rows, requested before the marks
         {
             const uint32_t ri = min(last, i_nx + lane);
-            rbase_n = out_meta[list[ri]].x - eoff[ri];
+            rsrc_n = list[ri];
+            rbase_n = out_meta[rsrc_n].x - eoff[ri];
             bnd_n = eoff[min(count, i_nx + 1 + lane)];
         }
         if (SPARSE) {
@@ -154,7 +169,27 @@ __device__ __forceinline__ void frontier_walk(const uint32_t *list, const uint32
         i_lo = i_nx;
         rbase = rbase_n;
         bnd = bnd_n;
+        rsrc = rsrc_n;
     }
+}
+
+// The walk that also lists the hop's messages as (destination, source) pairs for the sorted scatter: pair_cap entries
+// will be sorted, so the list is written only if the hop's out-edges fit, and the entries behind them get the key
+// that sorts last.
+__global__ __launch_bounds__(256) void k_frontier_mark_pairs(const uint32_t *list, const uint32_t *count_ptr,
+                                                             const uint32_t *eoff, const uint2 *out_meta,
+                                                             const uint32_t *out_pool, uint8_t *mk, const DevCtr *ctr,
+                                                             uint32_t l, uint32_t d, int mode, int ratio, int allow_disc,
+                                                             uint32_t *pk, uint32_t *pv, uint32_t pair_cap) {
+    if (allow_disc && rp_hop_mode(ctr, l, d, mode, ratio, allow_disc) == RP_HOP_DISCOVER) return;
+    const uint32_t count = *count_ptr;
+    const uint32_t M = count ? eoff[count] : 0u;
+    if (M == 0 || M > pair_cap) {
+        frontier_walk<false>(list, count_ptr, eoff, out_meta, out_pool, mk, SparseArgs());
+        return;
+    }
+    frontier_walk<false, true>(list, count_ptr, eoff, out_meta, out_pool, mk, SparseArgs(), pk, pv);
+    for (uint32_t i = M + blockIdx.x * blockDim.x + threadIdx.x; i < pair_cap; i += gridDim.x * blockDim.x) pk[i] = 0xFFFFFFFFu;
 }
 
 __global__ __launch_bounds__(256) void k_frontier_mark(const uint32_t *list, const uint32_t *count_ptr,
@@ -553,7 +588,13 @@ __global__ __launch_bounds__(1024) void k_list_eoff(const uint32_t *list, const 
     }
 }
 
-void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l, bool allow_disc) {
+void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l, bool allow_disc, uint32_t pair_cap) {
+    if (pair_cap) {
+        hipLaunchKernelGGL(k_frontier_mark_pairs, dim3(c->n_cu * 8), dim3(256), 0, c->stream, c->list[l - 1],
+                           &c->ctr->a[l - 1], c->eoff[l - 1], c->out_meta, c->out_pool, c->mk, c->ctr, l, c->xw[l],
+                           rp_layer_mode(c, l), c->opt_pull_ratio, allow_disc ? 1 : 0, c->pk_a, c->pv_a, pair_cap);
+        return;
+    }
     hipLaunchKernelGGL(k_frontier_mark, dim3(c->n_cu * 8), dim3(256), 0, c->stream, c->list[l - 1], &c->ctr->a[l - 1],
                        c->eoff[l - 1], c->out_meta, c->out_pool, c->mk, c->ctr, l, c->xw[l], rp_layer_mode(c, l),
                        c->opt_pull_ratio, allow_disc ? 1 : 0);

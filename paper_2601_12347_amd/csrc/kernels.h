@@ -16,11 +16,14 @@ void rp_launch_mutate(ripple_ctx *c, uint32_t n_ops, bool has_vertex_add, bool h
 ripple_status rp_stable_sort_pairs(ripple_ctx *c, const uint32_t *keys_in, uint32_t *keys_out, const uint32_t *vals_in,
                                    uint32_t *vals_out, size_t n, unsigned key_bits);
 size_t rp_sort_u64_tmp_bytes(size_t n_max);
+size_t rp_sort_u32_tmp_bytes(size_t n_max);
+bool rp_sort_pairs_u32(ripple_ctx *c, const uint32_t *keys_in, uint32_t *keys_out, const uint32_t *vals_in, uint32_t *vals_out,
+                       size_t n, unsigned key_bits, void *tmp, size_t tmp_bytes);
 void rp_sort_pairs_u64(ripple_ctx *c, const unsigned long long *keys_in, unsigned long long *keys_out, const float *vals_in,
                        float *vals_out, size_t n, void *tmp, size_t tmp_bytes);
 
 // frontier.hip
-void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l, bool allow_disc);
+void rp_launch_frontier_mark(ripple_ctx *c, uint32_t l, bool allow_disc, uint32_t pair_cap = 0);
 void rp_launch_alive_list(ripple_ctx *c);
 void rp_launch_frontier_compact(ripple_ctx *c, uint32_t l, bool self_term, bool want_out, bool want_in,
                                 bool accumulate_rep, bool pruned = false);
@@ -37,7 +40,8 @@ void rp_launch_frontier_sparse(ripple_ctx *c, uint32_t l, bool self_term, bool w
 // scatter.hip
 void rp_launch_scatter_push(ripple_ctx *c, uint32_t l, bool may_pull, bool allow_disc);
 void rp_launch_scatter_pull_det(ripple_ctx *c, uint32_t l, bool bootstrap);
-void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow_disc);
+void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow_disc, uint32_t pair_cap = 0);
+bool rp_launch_scatter_sorted(ripple_ctx *c, uint32_t l, bool allow_disc, uint32_t pair_cap);
 void rp_launch_pull_all(ripple_ctx *c, uint32_t l);
 void rp_launch_messages(ripple_ctx *c, uint32_t l);
 void rp_launch_scatter_mono(ripple_ctx *c, uint32_t l, const uint32_t *count_ptr, bool listed);

@@ -151,6 +151,10 @@ struct PullArgs {
     DevCtr *ctr;
     uint32_t l;
     int mode, ratio, allow_disc;
+    // the hop's messages may have been listed and sorted instead (rp_hop_sorted): then the pull leaves the hop alone
+    const uint32_t *m_eoff, *m_count;   // out-degree prefix over A_{l-1} and |A_{l-1}|: the number of messages
+    uint32_t sorted_cap;           // entries the host sorted (0: no list was made)
+    int sorted_force;
     // deterministic variants only
     const uint32_t *bm_rec;        // destinations that are recomputed from all their in-neighbours (bootstrap inference), or null
     const void *Hprev;             // what a recomputed row sums: rows of H^{l-1} (storage format `store`) ...
@@ -252,6 +256,10 @@ template <int NJ, int DISC, int WT, int DET>
 __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
     static_assert(!DET || (!DISC && !WT), "the deterministic form pulls into A_l, unweighted");
     if (!DET && rp_hop_mode(a.ctr, a.l, a.d, a.mode, a.ratio, a.allow_disc) != (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL)) return;
+    if (!DET && !DISC && a.sorted_cap) {
+        const uint32_t cp = *a.m_count;
+        if (rp_hop_sorted(a.ctr, a.l, cp ? a.m_eoff[cp] : 0u, a.sorted_cap, a.sorted_force)) return;
+    }
     const uint32_t count = *a.count_ptr;
     if (count == 0) return;
     if (blockIdx.x == 0 && threadIdx.x == 0) a.ctr->hop_mode[a.l] = 1u + (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL);
@@ -386,6 +394,111 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
         a.side_v[2 * gw] = wrote_head ? v_head : NONE;
         a.side_v[2 * gw + 1] = wrote_tail ? v_tail : NONE;
     }
+}
+
+// The same hop from the list of its messages. A pull finds the messages by testing every in-neighbour of every vertex
+// of A_l against the bitmap of A_{l-1}; when few of them carry a message (hop 2 of a large batch on the dense
+// graph: 4.6 M of 110 M), those tests, each a request to the L2 that a compute unit can only have so many of in
+// flight, are most of the hop. The out-edge walk that marks A_l has every message in its hands, so it writes them
+// down as (destination, source) pairs (k_frontier_mark_pairs), a radix sort (rocPRIM) puts them in destination
+// order, and this kernel is the pull's inner part over that list: every wavefront takes a contiguous run of pairs,
+// gathers the sources' delta rows G at a time, sums while the destination stays and sends one row of atomic
+// additions per destination and wavefront. The host sorts `cap` entries, a number it takes from the previous batch;
+// whether the list is used is decided here, like the hop's mode, from the hop's own counters.
+struct SortedArgs {
+    const uint32_t *pk, *pv;       // sorted: destination, source
+    const uint32_t *m_eoff, *m_count;
+    uint32_t cap;
+    int force;
+    const float *D;
+    uint32_t ldd, d;
+    float *X;
+    DevCtr *ctr;
+    uint32_t l;
+    int mode, ratio, allow_disc;
+};
+
+template <int NJ>
+__global__ __launch_bounds__(256) void k_scatter_sorted(SortedArgs a) {
+    if (rp_hop_mode(a.ctr, a.l, a.d, a.mode, a.ratio, a.allow_disc) != RP_HOP_PULL) return;
+    const uint32_t cp = *a.m_count;
+    const uint32_t M = cp ? a.m_eoff[cp] : 0u;
+    if (!rp_hop_sorted(a.ctr, a.l, M, a.cap, a.force)) return;
+    if (blockIdx.x == 0 && threadIdx.x == 0) a.ctr->hop_mode[a.l] = 1u + RP_HOP_SORTED;
+    constexpr int G = (NJ >= 8) ? 2 : (NJ == 4 ? 4 : 8 / NJ);   // message rows per round trip (and up to as many destination rows)
+    constexpr uint32_t NONE = 0xFFFFFFFFu;
+    const int lane = rp_lane();
+    const uint32_t d = a.d;
+    const uint32_t n_chunks = (M + 63u) / 64u;
+    const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
+    const uint32_t per = (n_chunks + nw - 1) / nw;
+    const uint32_t c_begin = min(n_chunks, gw * per), c_end = min(n_chunks, c_begin + per);
+    if (c_begin >= c_end) return;
+    // A destination whose pairs all lie inside this wavefront's run has no other writer: its row is read like one
+    // more message when its first pair comes up, summed with the messages and stored with plain stores (a row of
+    // float atomics costs the L2 one operation per number: 1.5 M rows of 256 took 0.9 ms that way, more than the
+    // gathers). Only the destinations of the run's first and last pair can have pairs in a neighbour's run; their sums
+    // go to memory as atomic additions.
+    const uint32_t v_first = a.pk[c_begin * 64u], v_last = a.pk[min(M, c_end * 64u) - 1u];
+    uint32_t cur = NONE;
+    float acc[NJ];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
+    auto flush = [&]() {
+        float *xr = a.X + (size_t)cur * d;
+        const bool shared = cur == v_first || cur == v_last;
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) {
+            const uint32_t col = lane + 64 * j;
+            if (col < d) {
+                if (!shared) xr[col] = acc[j];
+                else if (acc[j] != 0.0f) unsafeAtomicAdd(&xr[col], acc[j]);
+            }
+        }
+    };
+    uint32_t e = c_begin * 64u + lane;
+    uint32_t nv = (e < M) ? a.pk[e] : NONE, nu = (e < M) ? a.pv[e] : 0u;
+    for (uint32_t c = c_begin; c < c_end; ++c) {
+        const uint32_t my_v = nv, my_u = nu;
+        const uint32_t n = min(64u, M - c * 64u);
+        e += 64u;                                            // the next chunk's pairs are on their way during the gathers
+        nv = (c + 1 < c_end && e < M) ? a.pk[e] : NONE;
+        nu = (c + 1 < c_end && e < M) ? a.pv[e] : 0u;
+        for (uint32_t k0 = 0; k0 < n; k0 += G) {
+            float r[G][NJ], rx[G][NJ];
+            uint32_t vk[G];
+            uint32_t prev = cur;                             // every pair before k0 has been summed: cur is pair k0 - 1's destination
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const int k = (int)min(k0 + g, 63u);
+                const uint32_t uk = (uint32_t)__builtin_amdgcn_readlane((int)my_u, k);
+                vk[g] = (uint32_t)__builtin_amdgcn_readlane((int)my_v, k);
+                const bool live = k0 + g < n;
+                const bool own = live && vk[g] != prev && vk[g] != v_first && vk[g] != v_last;   // first pair of an unshared destination
+                prev = vk[g];
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    const uint32_t col = lane + 64 * j;
+                    r[g][j] = (live && col < d) ? a.D[(size_t)uk * a.ldd + col] : 0.0f;
+                    rx[g][j] = (own && col < d) ? a.X[(size_t)vk[g] * d + col] : 0.0f;
+                }
+            }
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                if (k0 + g < n) {
+                    if (vk[g] != cur) {
+                        if (cur != NONE) flush();
+                        cur = vk[g];
+#pragma unroll
+                        for (int j = 0; j < NJ; ++j) acc[j] = rx[g][j];
+                    }
+#pragma unroll
+                    for (int j = 0; j < NJ; ++j) acc[j] += r[g][j];
+                }
+            }
+        }
+    }
+    if (cur != NONE) flush();
 }
 
 // The same hop for packed message rows (one 128-byte line each, see rp_msg_encode). Decoding a row costs a dozen
@@ -629,8 +742,12 @@ __global__ __launch_bounds__(256) void k_pull_fixup(PullArgs a, uint32_t n_entri
 
 // discover = false: pull into A_l (the hop's list). true: scan every live vertex (c->all_list and
 // c->ioff_all must have been produced by rp_launch_alive_list) and mark the receivers in bm[l].
-void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow_disc) {
+void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow_disc, uint32_t pair_cap) {
     PullArgs a;
+    a.m_eoff = c->eoff[l - 1];
+    a.m_count = &c->ctr->a[l - 1];
+    a.sorted_cap = discover ? 0u : pair_cap;
+    a.sorted_force = c->opt_sorted == 2;
     a.list = discover ? c->all_list : c->list[l];
     a.count_ptr = discover ? &c->ctr->n_all : &c->ctr->a[l];
     a.ioff = discover ? c->ioff_all : c->ioff[l];
@@ -671,12 +788,46 @@ void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow
 #undef PULL_CASE
 }
 
+// Sorts the pairs the out-edge walk wrote (pair_cap entries; the filler key sorts last) and enqueues the kernel that
+// scatters from the sorted list. False, and nothing enqueued, if the sort could not be set up: the caller then has
+// to launch the pull without a list (pair_cap 0).
+bool rp_launch_scatter_sorted(ripple_ctx *c, uint32_t l, bool allow_disc, uint32_t pair_cap) {
+    if (!rp_sort_pairs_u32(c, c->pk_a, c->pk_b, c->pv_a, c->pv_b, pair_cap, c->pair_bits, c->pair_tmp, c->pair_tmp_bytes)) return false;
+    const LayerDev &ly = c->layers[l - 1];
+    SortedArgs a;
+    a.pk = c->pk_b;
+    a.pv = c->pv_b;
+    a.m_eoff = c->eoff[l - 1];
+    a.m_count = &c->ctr->a[l - 1];
+    a.cap = pair_cap;
+    a.force = c->opt_sorted == 2;
+    a.D = ly.proj ? c->PD : c->D[(l - 1) & 1];
+    a.d = c->xw[l];
+    a.ldd = ly.proj ? c->pd_ld : a.d;
+    a.X = c->X[l];
+    a.ctr = c->ctr;
+    a.l = l;
+    a.mode = rp_layer_mode(c, l);
+    a.ratio = c->opt_pull_ratio;
+    a.allow_disc = allow_disc ? 1 : 0;
+    dim3 grid(c->n_cu * 8), block(256);
+    if (a.d <= 64) hipLaunchKernelGGL((k_scatter_sorted<1>), grid, block, 0, c->stream, a);
+    else if (a.d <= 128) hipLaunchKernelGGL((k_scatter_sorted<2>), grid, block, 0, c->stream, a);
+    else if (a.d <= 256) hipLaunchKernelGGL((k_scatter_sorted<4>), grid, block, 0, c->stream, a);
+    else if (a.d <= 512) hipLaunchKernelGGL((k_scatter_sorted<8>), grid, block, 0, c->stream, a);
+    else hipLaunchKernelGGL((k_scatter_sorted<16>), grid, block, 0, c->stream, a);
+    return true;
+}
+
 // Deterministic mode: the hop is pulled into A_l (bootstrap: into every live vertex, all of them recomputed;
 // c->all_list and c->ioff_all must have been produced by rp_launch_alive_list), then the rows that more than
 // one wavefront had in-edges of are finished.
 void rp_launch_scatter_pull_det(ripple_ctx *c, uint32_t l, bool bootstrap) {
     const LayerDev &ly = c->layers[l - 1];
     PullArgs a;
+    a.m_eoff = a.m_count = nullptr;
+    a.sorted_cap = 0;
+    a.sorted_force = 0;
     a.list = bootstrap ? c->all_list : c->list[l];
     a.count_ptr = bootstrap ? &c->ctr->n_all : &c->ctr->a[l];
     a.ioff = bootstrap ? c->ioff_all : c->ioff[l];

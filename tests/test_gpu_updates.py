@@ -75,6 +75,41 @@ def test_push_and_pull_scatter_agree_with_oracle(mode, kind, widths):
         pair.close()
 
 
+@pytest.mark.parametrize("sorted_opt", [0, 1, 2])
+@pytest.mark.parametrize("kind,widths,project_first", [("sage_mean", (16, 40, 24, 10), 1), ("gcn_sum", (100, 256, 70), 0),
+                                                       ("gcn_sum", (12, 300, 520, 20), 1), ("gin_sum", (16, 32, 12, 6), 1)])
+def test_sorted_messages_agree_with_oracle(sorted_opt, kind, widths, project_first):
+    """Hops scattered from the list of their messages, written down by the out-edge walk and sorted by destination,
+    against the same hops pulled through the in-rows (option 0) and against the oracle: every row of every layer,
+    the cached aggregates and the sets after every batch. Option 2 takes the list wherever a hop is pulled (the
+    scatter mode is forced to pull so that hops of a few messages get there, and the report says so); option 1
+    leaves the choice to the previous batch's counts. Rows of up to 520 columns, project-first layers on and off
+    (unpacked projected rows travel through the list as well), a batch with more messages than the one before."""
+    print("case sorted messages", sorted_opt, kind, widths, flush=True)
+    pair, graph = make_pair(n=900, e=9000, d0=widths[0], kind=kind, widths=widths, seed=61, slack=128,
+                            project_first=bool(project_first), packed=False)
+    rp.ripple_set_option(pair.ctx, rp.OPT_SCATTER_MODE, 2)
+    rp.ripple_set_option(pair.ctx, rp.OPT_SORTED_MESSAGES, sorted_opt)
+    rp.ripple_set_option(pair.ctx, rp.OPT_SPARSE_FRONTIER, 0)    # hops that list their set while marking write no message list
+    stream = make_stream(pair, graph, MIXV, 63)
+    L = len(widths) - 1
+    try:
+        for b, bs in enumerate([3, 40, 200, 30, 400]):
+            print(" batch", b, bs, flush=True)
+            ops, payload, _ = stream.next_batch(bs)
+            res, _, _ = pair.step(ops, payload)
+            modes = list(res.hop_mode[1:L + 1])
+            print("  hop modes", modes, "messages", list(res.messages[1:L + 1]), flush=True)
+            if sorted_opt == 2:
+                assert all(m == 4 for m, msgs in zip(modes[1:], list(res.messages[2:L + 1])) if msgs), modes
+            if sorted_opt == 0:
+                assert 4 not in modes, modes
+        pair.check_graph()
+        pair.check_aggregates()
+    finally:
+        pair.close()
+
+
 STREAM_CASES = [(mode, kind, widths, weighted) for kind, widths, weighted in
                 [("sage_mean", (24, 256, 256, 40), False), ("gcn_sum", (24, 256, 256, 256, 12), False),
                  ("gcn_wsum", (16, 256, 256, 30), True), ("sage_mean", (24, 256, 256, 256), False)]
