@@ -281,6 +281,9 @@ def test_dense_configs_sampled_rows(dense_graph, name):
             L_ = len(model)
             assert res.messages[L_] * 8 >= res.n_edges and res.hop_mode[L_] == 3, list(res.hop_mode)
             assert res.hop_mode[1] == 1, list(res.hop_mode)
+            # ... and the hop between them (4.6 M messages, 110 M in-row entries) is scattered from the sorted
+            # list of its messages
+            assert res.hop_mode[2] == 4, list(res.hop_mode)
         sets = oracle.affected_sets(ora, rec, model)
         print(f"  oracle sets {time.time() - t0:.0f}s sizes {[len(s) for s in sets]}", flush=True)
         L = len(model)
