@@ -52,6 +52,7 @@ struct DevCtr {                      // device-resident counters, one instance p
     uint32_t n_tail_q;                        // deterministic mode: in-rows whose appended entries a workgroup puts in order
     uint32_t error;                           // sticky consistency error seen by a kernel
     uint32_t tail_top;                        // ... and the part of the copy buffer they have taken
+    uint32_t pull_next[RIPPLE_MAX_LAYERS + 1];// pull scatter of hop l: runs of chunks handed out so far
 };
 
 #define RP_MONO_LISTED_LONG 64u        // small max / min and attention hops: in-rows longer than this are queued for a workgroup while the hop's vertices are listed

@@ -1107,6 +1107,7 @@ __global__ void k_batch_reset(DevCtr *ctr, uint32_t *bitmaps, size_t n_bitmap_wo
             ctr->n_big[l] = 0;
             ctr->n_seg[l] = 0;
             ctr->hop_mode[l] = 0;
+            ctr->pull_next[l] = 0;
         }
         ctr->n_struct = 0;
         ctr->n_touch_out = ctr->n_touch_in = 0;

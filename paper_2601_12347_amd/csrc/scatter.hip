@@ -135,6 +135,14 @@ void rp_launch_scatter_push(ripple_ctx *c, uint32_t l, bool may_pull, bool allow
 // chunk's rows are requested before the gathers of the current one.
 // DISC = 0: destinations are A_l. DISC = 1 (discovering hop): destinations are all live vertices and
 // those that receive a message are marked in the hop's bitmap.
+#define PULL_RUN 8                      // chunks a wavefront takes at a time on a large hop
+// the next run's number, fetched by lane 0 for the wavefront
+__device__ __forceinline__ uint32_t rp_next_run(uint32_t *counter, int lane) {
+    uint32_t r = 0;
+    if (lane == 0) r = atomicAdd(counter, 1u);
+    return (uint32_t)__builtin_amdgcn_readfirstlane((int)r);
+}
+
 struct PullArgs {
     const uint32_t *list;          // destinations, ascending
     const uint32_t *count_ptr;
@@ -204,24 +212,43 @@ struct PullScan {
             }
             i_nx = min(last, i_lo + rp_count_le(bnd, e1));
         } else {
-            const uint32_t i_hi = rp_seg_forward(a.ioff, i_lo, last, e1 - 1);
+            // Short rows (a stretch of vertices with fewer than four in-neighbours on average, e.g. vertices created
+            // by earlier batches, which sit together at the end of the id range): the chunk is taken in pieces of
+            // 64 rows, each like a chunk that fits. (A search per edge instead made such chunks several times as
+            // slow as the others, and since a wavefront's chunks are neighbours, the wavefronts at the end of the
+            // id range then held up the whole hop: 2.1 -> 3.8 ms after 400 batches that each create 100 vertices.)
 #pragma unroll
             for (int t = 0; t < T; ++t) {
-                const uint32_t e = e0 + 64 * t + lane;
                 my_v[t] = 0;
                 my_u[t] = 0;
                 if (WT) my_w[t] = 0.0f;
                 dirty[t] = false;
-                if (e < e1) {
-                    const uint32_t i = rp_seg_search(a.ioff, i_lo, i_hi, e);
-                    my_v[t] = a.list[i];
-                    const uint32_t pos = a.in_meta[my_v[t]].x + (e - a.ioff[i]);
-                    my_u[t] = a.in_pool[pos];
-                    if (WT) my_w[t] = a.in_w[pos];
-                    dirty[t] = (a.bm_prev[my_u[t] >> 5] >> (my_u[t] & 31)) & 1u;
-                }
             }
-            i_nx = rp_seg_forward(a.ioff, i_hi, last, e1);
+            uint32_t il = i_lo, rv_p = rv, rb_p = rbase, bn_p = bnd, es = e0;
+            for (;;) {
+                const uint32_t top = min(e1, (uint32_t)__shfl(bn_p, 63));   // edges [es, top) lie in the 64 rows held
+#pragma unroll
+                for (int t = 0; t < T; ++t) {
+                    const uint32_t e = e0 + 64 * t + lane;
+                    const int r = (int)min(63u, rp_count_le(bn_p, e));
+                    const uint32_t v = __shfl(rv_p, r);
+                    const uint32_t base = __shfl(rb_p, r);
+                    if (e >= es && e < top) {
+                        my_v[t] = v;
+                        my_u[t] = a.in_pool[base + e];
+                        if (WT) my_w[t] = a.in_w[base + e];
+                        dirty[t] = (a.bm_prev[my_u[t] >> 5] >> (my_u[t] & 31)) & 1u;
+                    }
+                }
+                if (top >= e1) break;
+                es = top;
+                il = min(last, il + 64u);
+                const uint32_t rp = min(last, il + lane);
+                rv_p = a.list[rp];
+                rb_p = a.in_meta[rv_p].x - a.ioff[rp];
+                bn_p = a.ioff[min(count, il + 1 + lane)];
+            }
+            i_nx = min(last, il + rp_count_le(bn_p, e1));
         }
         const uint32_t ri = min(last, i_nx + lane);
         rv_n = a.list[ri];
@@ -272,8 +299,15 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
     const uint32_t total = a.ioff[count];
     const uint32_t n_chunks = (total + PULL_CHUNK - 1) / PULL_CHUNK;
     const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
-    const uint32_t per = (n_chunks + nw - 1) / nw;
-    const uint32_t c_begin = min(n_chunks, gw * per), c_end = min(n_chunks, c_begin + per);
+    // DET: a fixed run of chunks per wavefront. Otherwise a wavefront starts with the run of its own number and then
+    // fetches runs from a counter until none is left (runs of PULL_RUN chunks on large hops, of one chunk when there
+    // are fewer chunks than wavefronts would need): chunks differ in cost (a stretch of short in-rows ends a sum every few edges), stretches of
+    // such chunks exist (the vertices that earlier batches created sit together at the end of the id range), and
+    // with fixed runs the few wavefronts that own such a stretch held up the hop (3.4 instead of 2.1 ms after 400
+    // batches that each create 100 vertices).
+    const uint32_t per = DET ? (n_chunks + nw - 1) / nw : max(1u, min((uint32_t)PULL_RUN, n_chunks / (2u * nw)));
+    uint32_t c_begin = min(n_chunks, gw * per);             // the first run needs no counter
+    uint32_t c_end = min(n_chunks, c_begin + per);
     if (c_begin >= c_end) {
         if (DET && lane == 0) a.side_v[2 * gw] = a.side_v[2 * gw + 1] = 0xFFFFFFFFu;
         return;
@@ -325,6 +359,7 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
             }
         }
     };
+    for (;;) {
     for (uint32_t c = c_begin; c < c_end; ++c) {
         const uint32_t e0 = c * PULL_CHUNK, e1 = min(total, e0 + PULL_CHUNK);
         uint32_t my_v[T], my_u[T];
@@ -390,6 +425,13 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
         scan.advance();                                      // the destination and its partial sum carry over to the next chunk
     }
     if (cur != NONE) flush();
+    cur = NONE;
+    if (DET || (unsigned long long)nw * per >= n_chunks) break;   // every run was somebody's first
+    c_begin = (nw + rp_next_run(&a.ctr->pull_next[a.l], lane)) * per;
+    if (c_begin >= n_chunks) break;
+    c_end = min(n_chunks, c_begin + per);
+    scan.begin(a, count, c_begin, lane);
+    }
     if (DET && lane == 0) {
         a.side_v[2 * gw] = wrote_head ? v_head : NONE;
         a.side_v[2 * gw + 1] = wrote_tail ? v_tail : NONE;
@@ -531,8 +573,10 @@ __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
     const uint32_t total = a.ioff[count];
     const uint32_t n_chunks = (total + PULL_CHUNK - 1) / PULL_CHUNK;
     const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
-    const uint32_t per = (n_chunks + nw - 1) / nw;
-    const uint32_t c_begin = min(n_chunks, gw * per), c_end = min(n_chunks, c_begin + per);
+    // runs of chunks: fixed per wavefront (DET) or fetched from a counter, see k_scatter_pull
+    const uint32_t per = DET ? (n_chunks + nw - 1) / nw : max(1u, min((uint32_t)PULL_RUN, n_chunks / (2u * nw)));
+    uint32_t c_begin = min(n_chunks, gw * per);             // the first run needs no counter
+    uint32_t c_end = min(n_chunks, c_begin + per);
     if (c_begin >= c_end) {
         if (DET && lane == 0) a.side_v[2 * gw] = a.side_v[2 * gw + 1] = NONE;
         return;
@@ -572,6 +616,7 @@ __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
         }
         acc0 = acc1 = acc2 = 0.0f;
     };
+    for (;;) {
     for (uint32_t c = c_begin; c < c_end; ++c) {
         const uint32_t e0 = c * PULL_CHUNK, e1 = min(total, e0 + PULL_CHUNK);
         uint32_t my_v[T], my_u[T];
@@ -673,6 +718,13 @@ __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
         scan.advance();
     }
     if (cur != NONE) flush();
+    cur = NONE;
+    if (DET || (unsigned long long)nw * per >= n_chunks) break;   // every run was somebody's first
+    c_begin = (nw + rp_next_run(&a.ctr->pull_next[a.l], lane)) * per;
+    if (c_begin >= n_chunks) break;
+    c_end = min(n_chunks, c_begin + per);
+    scan.begin(a, count, c_begin, lane);
+    }
     if (DET && lane == 0) {
         a.side_v[2 * gw] = wrote_head ? v_head : NONE;
         a.side_v[2 * gw + 1] = wrote_tail ? v_tail : NONE;
