@@ -37,7 +37,7 @@ def log(*a):
 # the profiler on itself; for any other workload `traffic` is null.
 TRAFFIC_SOURCE = "profiles/hbm_traffic_dense_sage_mean_bs10000_pmc.txt"
 MEASURED_TRAFFIC_BYTES = {
-    ("dense_sage_mean", 10000): {"scatter_l3": 9.9e9, "scatter_l2": 6.2e9, "transform_l2": 4.9e9, "transform_l3": 5.0e9},
+    ("dense_sage_mean", 10000): {"scatter_l3": 10.0e9, "scatter_l2": 7.2e9, "transform_l2": 4.9e9, "transform_l3": 5.0e9},
 }
 
 
