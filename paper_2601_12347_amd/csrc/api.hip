@@ -931,15 +931,16 @@ static void enqueue_piece(ripple_ctx *c, const SubBatch &sb, bool multi) {
             rp_launch_alive_list(c);
             have_all = true;
         }
-        // A hop that the last batch pulled through in-rows holding at least eight times as many entries as it had
-        // messages is taken from the sorted list of its messages (k_scatter_sorted): the out-edge walk writes the
-        // list, and as many entries are sorted as the last batch had messages, and a quarter more. The kernels make
-        // sure on the device that the list is only used if this batch's messages fit; else the hop is pulled. Below a
-        // million messages the sort's half a dozen launches cost more than the pull's scan.
+        // A hop that the last batch pulled (or took from the list already) through in-rows holding enough entries for the
+        // sort to pay (rp_sorted_pays) is taken from the sorted list of its messages (k_scatter_sorted): the out-edge
+        // walk writes the list, and as many entries are sorted as the last batch had messages, and a quarter more. The
+        // kernels make sure on the device that the list is only used if this batch's messages fit and the sort
+        // still pays; else the hop is pulled.
         uint32_t pair_cap = 0;
         if (may_pull && !wsum && !sparse && c->pair_cap && c->opt_sorted && !(c->layers[l - 1].proj && c->layers[l - 1].packed)) {
             if (c->opt_sorted == 2) pair_cap = c->pair_cap;
-            else if (c->hints_valid && c->last_m[l] >= (1u << 20) && RP_SORTED_FACTOR * c->last_m[l] <= c->last_isum[l]) {
+            else if (c->hints_valid && c->last_m[l] && rp_sorted_pays(c->last_m[l], c->last_isum[l]) &&
+                     (c->last_hop_mode[l] == 1u + RP_HOP_PULL || c->last_hop_mode[l] == 1u + RP_HOP_SORTED)) {
                 const uint64_t want = ((uint64_t)c->last_m[l] + c->last_m[l] / 4 + 4096) & ~4095ull;
                 if (want <= c->pair_cap) pair_cap = (uint32_t)want;
             }
@@ -1087,6 +1088,7 @@ extern "C" ripple_status ripple_apply_updates(ripple_ctx *c, const ripple_update
             tchd[l] += h.touched[l];
             c->last_m[l] = h.m[l];
             c->last_isum[l] = h.isum[l];
+            c->last_hop_mode[l] = h.hop_mode[l];
             hop_mode[l] = h.hop_mode[l];
             for (int k = 0; k < 3; ++k) mono[k][l] += h.mono[k][l];
             c->last_cand[l] = h.mono[0][l] + h.mono[1][l] + h.mono[2][l];

@@ -198,6 +198,7 @@ struct ripple_ctx {
     uint32_t last_cand[RIPPLE_MAX_LAYERS + 1] = {0};
     uint32_t last_m[RIPPLE_MAX_LAYERS + 1] = {0};       // messages per hop of the last batch (a size hint)
     uint32_t last_isum[RIPPLE_MAX_LAYERS + 1] = {0};    // in-row entries a pull of that hop would have scanned
+    uint32_t last_hop_mode[RIPPLE_MAX_LAYERS + 1] = {0};// 1 + RP_HOP_* of the kernel that moved that hop's messages
     // messages of a hop as (destination, source) pairs, as the out-edge walk lists them and sorted by destination
     uint32_t *pk_a = nullptr, *pk_b = nullptr, *pv_a = nullptr, *pv_b = nullptr;
     uint32_t pair_cap = 0;
@@ -387,12 +388,16 @@ __device__ __forceinline__ int rp_hop_mode(const DevCtr *ctr, uint32_t l, uint32
 }
 
 // A hop that would be pulled is taken from the sorted list of its messages instead when the list was made (M fits
-// the `cap` entries the host sorted) and the in-rows that a pull would scan hold at least RP_SORTED_FACTOR times as
-// many entries as there are messages (force: whatever they hold): sorting a pair costs about as much as eight
-// tests of an in-neighbour. M: out-edges of A_{l-1}.
+// the `cap` entries the host sorted) and it pays (force: whenever the list was made): sorting a pair costs about as
+// much as eight tests of an in-neighbour, and the sort's launches as much as six million of them, so the in-rows
+// that a pull would scan have to hold more than 8 M + 6 * 2^20 entries. M: out-edges of A_{l-1}.
 #define RP_SORTED_FACTOR 8ull
+#define RP_SORTED_FIXED (6ull << 20)
+static inline bool rp_sorted_pays(unsigned long long m, unsigned long long in_entries) {
+    return RP_SORTED_FACTOR * m + RP_SORTED_FIXED <= in_entries;
+}
 __device__ __forceinline__ bool rp_hop_sorted(const DevCtr *ctr, uint32_t l, uint32_t M, uint32_t cap, int force) {
-    return cap && M > 0 && M <= cap && (force || RP_SORTED_FACTOR * M <= ctr->isum[l]);
+    return cap && M > 0 && M <= cap && (force || RP_SORTED_FACTOR * M + RP_SORTED_FIXED <= ctr->isum[l]);
 }
 
 // position of `target` in row[0..len), searched by one wavefront; -1 when absent. Long (hub) rows
