@@ -455,7 +455,8 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
         if (c->layers[l - 1].selfc) RP_TRY(dev_alloc(c, &c->layers[l - 1].PS, n * c->d[l], true));
         if (c->layers[l - 1].proj) {
             RP_TRY(dev_alloc(c, &c->layers[l - 1].T, n * c->d[l], true));
-            c->layers[l - 1].packed = c->opt_pack ? rp_msg_packed(c->d[l]) : 0u;
+            // packed rows are addressed with 32-bit byte offsets (vertex id * 128): below 2^25 vertices
+            c->layers[l - 1].packed = (c->opt_pack && n < (1u << 25)) ? rp_msg_packed(c->d[l]) : 0u;
         }
     }
     {

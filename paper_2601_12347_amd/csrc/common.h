@@ -359,6 +359,14 @@ __device__ __forceinline__ void rp_msg_decode(uint2 c, float &v0, float &v1, flo
     v1 = (float)q1 * f;
     v2 = (float)q2 * f;
 }
+// the same in parts: the three integers as floats and the chunk's factor; (float)q * f is exact, so a fused
+// multiply-add of the two into a sum rounds as the sum of the decoded value would
+__device__ __forceinline__ void rp_msg_decode_parts(uint2 c, float &q0, float &q1, float &q2, float &f) {
+    f = __uint_as_float(((c.y >> 25) + 45u) << 23);
+    q0 = (float)(((int)(c.x << 13)) >> 13);
+    q1 = (float)(((int)(__builtin_amdgcn_alignbit(c.y, c.x, 19) << 13)) >> 13);
+    q2 = (float)(((int)(c.y << 7)) >> 13);
+}
 // column `col` alone (kernels that give every lane one column)
 __device__ __forceinline__ float rp_msg_decode_col(uint2 c, uint32_t col) {
     float v0, v1, v2;

@@ -19,6 +19,8 @@
 #define PULL_CHUNK 256
 
 // PK = 1 (NJ = 1 only): the message rows are packed 128-byte lines (D points at them)
+typedef uint32_t uintx2 __attribute__((ext_vector_type(2)));
+
 template <int NJ, int PK>
 __global__ __launch_bounds__(256) void k_scatter_push(const uint32_t *list, const uint32_t *count_ptr,
                                                       const uint32_t *eoff, const float *D, uint32_t ldd, uint32_t d,
@@ -154,6 +156,7 @@ struct PullArgs {
     uint32_t *bm_cur;              // bitmap of A_l: receivers are marked here when discovering
     const float *D;                // delta rows, indexed by vertex
     uint32_t ldd;                  // their row stride
+    uint32_t msg_bytes;            // packed message rows (k_scatter_pull4): size of the table in bytes, below 4 GB
     uint32_t d;
     float *X;
     DevCtr *ctr;
@@ -555,6 +558,7 @@ __global__ __launch_bounds__(256) void k_scatter_sorted(SortedArgs a) {
 // counts). The destination and the partial sums carry over from chunk to chunk: a wavefront adds to a row once,
 // however many chunks the row's in-edges span.
 #define PULL4_QUADS 4                                       // quads (16 rows) in flight per wavefront
+#define PULL4_PAD 0xFFFFFFFEu                               // destination of the entries that fill a chunk's last round
 template <int DISC, int WT, int DET>
 __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
     static_assert(!DET || (!DISC && !WT), "the deterministic form pulls into A_l, unweighted");
@@ -564,9 +568,12 @@ __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
     if (blockIdx.x == 0 && threadIdx.x == 0) a.ctr->hop_mode[a.l] = 1u + (DISC ? RP_HOP_DISCOVER : RP_HOP_PULL);
     constexpr int T = PULL_CHUNK / 64;
     constexpr uint32_t NONE = 0xFFFFFFFFu;
-    __shared__ uint32_t s_u[4][PULL_CHUNK], s_v[4][PULL_CHUNK];
-    __shared__ float s_w[WT ? 4 : 1][WT ? PULL_CHUNK : 1];
-    __shared__ uint8_t s_r[DET ? 4 : 1][DET ? PULL_CHUNK : 1];   // DET: the entry's destination is recomputed
+    constexpr uint32_t LIST = PULL_CHUNK + 4 * PULL4_QUADS; // a round always reads 4 PULL4_QUADS entries
+    // per dirty in-edge: (byte offset of the source's message row, destination); what the inner loop needs per quad
+    // is then one 8-byte LDS read and one addition in front of the row's load
+    __shared__ uint2 s_e[4][LIST];
+    __shared__ float s_w[WT ? 4 : 1][WT ? LIST : 1];
+    __shared__ uint8_t s_r[DET ? 4 : 1][DET ? LIST : 1];        // DET: the entry's destination is recomputed
     const int lane = rp_lane(), wave = threadIdx.x >> 6;
     const uint32_t grp = (uint32_t)lane >> 4, sub = (uint32_t)lane & 15u;
     const uint32_t d = a.d;
@@ -581,7 +588,9 @@ __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
         if (DET && lane == 0) a.side_v[2 * gw] = a.side_v[2 * gw + 1] = NONE;
         return;
     }
-    const uint32_t *msg = (const uint32_t *)a.D;
+    // message rows through a buffer descriptor: 32-bit byte offsets (row offset from LDS + this lane's chunk)
+    const __amdgpu_buffer_rsrc_t mres = __builtin_amdgcn_make_buffer_rsrc((void *)a.D, 0, a.msg_bytes, 0x00020000u);
+    const uint32_t sub8 = 8u * sub;
     const uint32_t my_col = 16u * grp + sub;                // the column this lane sends to memory
     const bool sends = grp < 3u && my_col < d;
     uint32_t cur = NONE;                                    // destination being summed (the same in all lanes)
@@ -635,12 +644,17 @@ __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
             const unsigned long long mask = __ballot(dirty[t]);
             const uint32_t pos = n + __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
             if (dirty[t]) {
-                s_u[wave][pos] = my_u[t];
-                s_v[wave][pos] = my_v[t];
+                s_e[wave][pos] = make_uint2(my_u[t] << 7, my_v[t]);
                 if (WT) s_w[wave][pos] = my_w[t];
                 if (DET) s_r[wave][pos] = rec ? 1 : 0;
             }
             n += (uint32_t)__popcll(mask);
+        }
+        // the entries a round reads past the list's end: row 0 (valid memory), a destination that never matches
+        if (lane < 4 * PULL4_QUADS) {
+            s_e[wave][n + lane] = make_uint2(0u, PULL4_PAD);
+            if (WT) s_w[wave][n + lane] = 0.0f;
+            if (DET) s_r[DET ? wave : 0][DET ? n + lane : 0] = 0;
         }
         // LDS accesses of one wavefront are executed in order, so the loads below see the stores above without a
         // workgroup barrier; the fence keeps the compiler from moving them across each other
@@ -649,64 +663,61 @@ __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         const uint32_t n_quads = (n + 3u) >> 2;
         for (uint32_t k0 = 0; k0 < n_quads; k0 += PULL4_QUADS) {
-            uint32_t vk[PULL4_QUADS];
+            uint2 ent[PULL4_QUADS];
             float wk[PULL4_QUADS];
             uint2 ch[PULL4_QUADS];
             bool rk[PULL4_QUADS];
             float tv[DET ? PULL4_QUADS : 1][3];              // DET: the three columns of a recomputed row's source
 #pragma unroll
-            for (int r = 0; r < PULL4_QUADS; ++r) {          // entries past the list's end repeat its last one: a valid row, not used
-                const uint32_t idx = min(4u * (k0 + r) + grp, n - 1u);
-                const uint32_t uk = s_u[wave][idx];
-                vk[r] = s_v[wave][idx];
+            for (int r = 0; r < PULL4_QUADS; ++r) {
+                const uint32_t idx = 4u * (k0 + r) + grp;
+                ent[r] = s_e[wave][idx];
                 if (WT) wk[r] = s_w[wave][idx];
                 rk[r] = DET && s_r[DET ? wave : 0][DET ? idx : 0] != 0;
                 if (DET && rk[r]) {
-                    const float *t = a.R + (size_t)uk * d;
+                    const float *t = a.R + (size_t)(ent[r].x >> 7) * d;
                     tv[DET ? r : 0][0] = t[sub];
                     tv[DET ? r : 0][1] = t[16u + sub];
                     tv[DET ? r : 0][2] = (32u + sub < d) ? t[32u + sub] : 0.0f;
                     ch[r] = make_uint2(0u, 0u);
                 } else {
-                    ch[r] = *(const uint2 *)(msg + (size_t)uk * RP_MSG_WORDS + 2u * sub);
+                    const uintx2 w2 = __builtin_bit_cast(uintx2, __builtin_amdgcn_raw_buffer_load_b64(mres, ent[r].x + sub8, 0, 0));
+                    ch[r] = make_uint2(w2.x, w2.y);
                 }
             }
 #pragma unroll
             for (int r = 0; r < PULL4_QUADS; ++r) {
                 const uint32_t k = k0 + r;
                 if (k < n_quads) {
-                    float v0, v1, v2;
-                    rp_msg_decode(ch[r], v0, v1, v2);
+                    // the three columns as (integer, as a float) x (the chunk's power of two): one fused
+                    // multiply-add per column takes them into the sums (the product is exact)
+                    float q0, q1, q2, f;
+                    rp_msg_decode_parts(ch[r], q0, q1, q2, f);
                     if (DET && rk[r]) {
-                        v0 = tv[DET ? r : 0][0];
-                        v1 = tv[DET ? r : 0][1];
-                        v2 = tv[DET ? r : 0][2];
+                        q0 = tv[DET ? r : 0][0];
+                        q1 = tv[DET ? r : 0][1];
+                        q2 = tv[DET ? r : 0][2];
+                        f = 1.0f;
                     }
-                    if (WT) {
-                        v0 *= wk[r];
-                        v1 *= wk[r];
-                        v2 *= wk[r];
-                    }
-                    const uint32_t v_first = (uint32_t)__builtin_amdgcn_readlane((int)vk[r], 0);
-                    const uint32_t v_last = (uint32_t)__builtin_amdgcn_readlane((int)vk[r], 48);
-                    if (4u * k + 3u < n && v_first == cur && v_last == cur) {   // the whole quad goes on
-                        acc0 += v0;
-                        acc1 += v1;
-                        acc2 += v2;
+                    if (WT) f *= wk[r];                      // a power of two times the weight: exact
+                    if (!__any(ent[r].y != cur)) {           // the whole quad goes on
+                        acc0 = __builtin_fmaf(q0, f, acc0);
+                        acc1 = __builtin_fmaf(q1, f, acc1);
+                        acc2 = __builtin_fmaf(q2, f, acc2);
                     } else {                                 // entry by entry (they are sorted by destination)
 #pragma unroll
                         for (uint32_t g = 0; g < 4u; ++g) {
-                            if (4u * k + g < n) {
-                                const uint32_t vg = (uint32_t)__builtin_amdgcn_readlane((int)vk[r], 16 * (int)g);
+                            const uint32_t vg = (uint32_t)__builtin_amdgcn_readlane((int)ent[r].y, 16 * (int)g);
+                            if (vg != PULL4_PAD) {
                                 if (vg != cur) {
                                     if (cur != NONE) flush();
                                     cur = vg;
                                     if (DET) cur_rec = __builtin_amdgcn_readlane((int)rk[r], 16 * (int)g) != 0;
                                 }
                                 if (grp == g) {
-                                    acc0 += v0;
-                                    acc1 += v1;
-                                    acc2 += v2;
+                                    acc0 = __builtin_fmaf(q0, f, acc0);
+                                    acc1 = __builtin_fmaf(q1, f, acc1);
+                                    acc2 = __builtin_fmaf(q2, f, acc2);
                                 }
                             }
                         }
@@ -811,6 +822,7 @@ void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow
     a.D = packed ? (const float *)c->MSG : (c->layers[l - 1].proj ? c->PD : c->D[(l - 1) & 1]);
     a.d = c->xw[l];
     a.ldd = c->layers[l - 1].proj ? c->pd_ld : a.d;
+    a.msg_bytes = (uint32_t)(c->n_cap * (RP_MSG_WORDS * 4u));   // packed layers exist below 2^25 vertices only
     a.X = c->X[l];
     a.ctr = c->ctr;
     a.l = l;
@@ -892,6 +904,7 @@ void rp_launch_scatter_pull_det(ripple_ctx *c, uint32_t l, bool bootstrap) {
     a.D = packed ? (const float *)c->MSG : (ly.proj ? c->PD : c->D[(l - 1) & 1]);
     a.d = c->xw[l];
     a.ldd = ly.proj ? c->pd_ld : a.d;
+    a.msg_bytes = (uint32_t)(c->n_cap * (RP_MSG_WORDS * 4u));
     a.X = c->X[l];
     a.ctr = c->ctr;
     a.l = l;
