@@ -424,7 +424,7 @@ bool rp_launch_project_both_stream(ripple_ctx *c, uint32_t l, const uint32_t *li
     const LayerDev &ly = c->layers[l - 1];
     if (!c->opt_stream || !ly.Wc96p || c->store || ly.d_in != 256 || ly.d_out > 48 || ly.d_out < 17) return false;
     if ((uint64_t)c->n_cap * 1024u > 0xFFFFF000ull) return false;
-    if (rows_hint < 131072u) return false;                         // enough 32-row tiles for every wavefront of the chip
+    if (rows_hint < 131072u && c->opt_stream != 2) return false;   // enough 32-row tiles for every wavefront of the chip (2: any number, for tests)
     PArgs a;
     a.list = list;
     a.count_ptr = count_d;

@@ -112,7 +112,8 @@ def test_sorted_messages_agree_with_oracle(sorted_opt, kind, widths, project_fir
 
 STREAM_CASES = [(mode, kind, widths, weighted) for kind, widths, weighted in
                 [("sage_mean", (24, 256, 256, 40), False), ("gcn_sum", (24, 256, 256, 256, 12), False),
-                 ("gcn_wsum", (16, 256, 256, 30), True), ("sage_mean", (24, 256, 256, 256), False)]
+                 ("gcn_wsum", (16, 256, 256, 30), True), ("sage_mean", (24, 256, 256, 256), False),
+                 ("sage_mean", (24, 256, 256, 24), False)]
                 for mode in (0, 1, 2, 3) if not (weighted and mode == 1)]
 
 
@@ -122,7 +123,9 @@ def test_streaming_row_update_at_any_size(mode, kind, widths, weighted):
     for large hops only otherwise): hops of a handful of rows, of less than a tile, of a few tiles with a ragged last
     one. Every row of every layer, the cached aggregates and the sets against the oracle after every batch, in
     every scatter mode, with delta rows written (a 256 -> 256 layer before another) and without (before a
-    project-first layer, or last), with and without a cached self term."""
+    project-first layer, or last), with and without a cached self term. The same option forces the kernel that takes
+    both products of a narrow project-first GraphSAGE layer in one pass (256 -> 40: packed messages, 256 -> 24:
+    one-line fp32 messages) onto these small hops and onto the bootstrap."""
     print("case streaming row update", mode, kind, widths, flush=True)
     pair, graph = make_pair(n=1300, e=14000, d0=widths[0], kind=kind, widths=widths, seed=171, slack=96, weighted=weighted)
     rp.ripple_set_option(pair.ctx, rp.OPT_STREAM_TRANSFORM, 2)
