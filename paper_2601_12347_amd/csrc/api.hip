@@ -498,10 +498,14 @@ extern "C" ripple_status ripple_load_model(ripple_ctx *c, uint32_t n_layers, con
         for (uint32_t l = 1; l <= c->L; ++l) packed |= c->layers[l - 1].proj && c->layers[l - 1].packed;
         if (packed) RP_TRY(dev_alloc(c, &c->MSG, n * RP_MSG_WORDS, true));
     }
-    if (c->opt_deterministic) {                          // two side entries per wavefront of the pull kernels' grid
+    if (c->opt_deterministic) {                          // two side entries per run of chunks of the pull kernels
         uint32_t xmax = 1;
         for (uint32_t l = 1; l <= c->L; ++l) xmax = std::max(xmax, c->xw[l]);
-        const size_t entries = 2 * (size_t)c->n_cu * 8 * 4;
+        // runs: up to four per wavefront of the grid while a run is shorter than eight chunks, else an eighth of the chunks
+        // (256 in-row entries each) that the in-row pool can hold
+        const size_t nw = (size_t)c->n_cu * 8 * 4;
+        c->side_runs = (uint32_t)std::max<size_t>(4 * nw, c->pool_cap / (256 * 8) + 2);
+        const size_t entries = 2 * (size_t)c->side_runs;
         RP_TRY(dev_alloc(c, &c->side_v, entries, false));
         RP_TRY(dev_alloc(c, &c->side_acc, entries * xmax, false));
     }

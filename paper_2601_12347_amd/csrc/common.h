@@ -173,9 +173,10 @@ struct ripple_ctx {
     // deterministic mode: appended in-row entries are put in id order through these (ops_cap entries each; queue: touch_cap)
     uint32_t *tail_ids = nullptr, *tail_q = nullptr;
     float *tail_w = nullptr;
-    // ... and the pull kernels leave the sums of rows that several wavefronts read in-edges of here (two entries per wavefront)
+    // ... and the pull kernels leave the sums of rows whose in-edges lie in more than one run of chunks here (two entries per run)
     uint32_t *side_v = nullptr;
     float *side_acc = nullptr;
+    uint32_t side_runs = 0;                             // runs there is room for
     // ... and the changed edges are sorted by (sink, source) before their structural terms are added (struct_cap entries each)
     unsigned long long *sk_in = nullptr, *sk_out = nullptr;
     float *sv_in = nullptr, *sv_out = nullptr;

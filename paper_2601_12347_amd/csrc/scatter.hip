@@ -171,7 +171,8 @@ struct PullArgs {
     const void *Hprev;             // what a recomputed row sums: rows of H^{l-1} (storage format `store`) ...
     const float *R;                // ... or, for a project-first layer, of T (what every vertex has sent so far); stride d
     int store;
-    uint32_t *side_v;              // per wavefront: the destinations of its first and last in-edge, if it has sums for them
+    uint32_t side_runs;            // runs the side entries have room for (two entries per run)
+    uint32_t *side_v;              // per run: the destinations of its first and last in-edge, if it has sums for them
     float *side_acc;               // ... and those sums, d floats per entry
 };
 
@@ -270,12 +271,12 @@ struct PullScan {
 // every sum has to be taken in an order that is a function of the graph and the batches alone:
 //   * the graph store keeps the order of an in-row such a function (rows built in the order the edges were given,
 //     appended entries put in id order, holes filled by a fixed rule), the list of destinations is ascending, and
-//     the cut of the in-edge space into chunks and of the chunks into runs per wavefront depends on their number
-//     and the grid only;
-//   * a wavefront carries a destination's partial sum from chunk to chunk, so it finishes every destination once.
-//     Only the destinations of its first and its last in-edge can have in-edges in another wavefront's run; their
-//     sums go to two side entries per wavefront instead of memory, and k_pull_fixup adds the entries of one
-//     destination in wavefront order. All other rows are written with plain loads and stores by their only writer.
+//     the cut of the in-edge space into chunks and of the chunks into runs (every nw-th run is one wavefront's)
+//     depends on their number and the grid only;
+//   * within a run a wavefront carries a destination's partial sum from chunk to chunk, so a run finishes every
+//     destination once. Only the destinations of a run's first and last in-edge can have in-edges in another run;
+//     their sums go to two side entries per run instead of memory, and k_pull_fixup adds the entries of one
+//     destination in run order. All other rows are written with plain loads and stores by their only writer.
 // The changed edges' structural terms have been added before the first hop, in (sink, source) order (k_struct_ordered).
 // Bootstrap inference runs the same kernels with every destination marked as recomputed: every in-edge of such a
 // row contributes, with the source's current row (of H^{l-1}, or of T for a project-first layer) in place of a
@@ -302,19 +303,28 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
     const uint32_t total = a.ioff[count];
     const uint32_t n_chunks = (total + PULL_CHUNK - 1) / PULL_CHUNK;
     const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
-    // DET: a fixed run of chunks per wavefront. Otherwise a wavefront starts with the run of its own number and then
-    // fetches runs from a counter until none is left (runs of PULL_RUN chunks on large hops, of one chunk when there
-    // are fewer chunks than wavefronts would need): chunks differ in cost (a stretch of short in-rows ends a sum every few edges), stretches of
-    // such chunks exist (the vertices that earlier batches created sit together at the end of the id range), and
-    // with fixed runs the few wavefronts that own such a stretch held up the hop (3.4 instead of 2.1 ms after 400
-    // batches that each create 100 vertices).
-    const uint32_t per = DET ? (n_chunks + nw - 1) / nw : max(1u, min((uint32_t)PULL_RUN, n_chunks / (2u * nw)));
-    uint32_t c_begin = min(n_chunks, gw * per);             // the first run needs no counter
-    uint32_t c_end = min(n_chunks, c_begin + per);
-    if (c_begin >= c_end) {
-        if (DET && lane == 0) a.side_v[2 * gw] = a.side_v[2 * gw + 1] = 0xFFFFFFFFu;
+    // The chunks are handed out in runs (PULL_RUN chunks on large hops, one chunk when there are fewer chunks than
+    // wavefronts would need). A wavefront starts with the run of its own number; after that it fetches runs from a
+    // counter until none is left, or, in the deterministic mode, takes every nw-th run (a cut that depends on the
+    // number of chunks and the grid alone). One long contiguous run per wavefront is what the first version had:
+    // chunks differ in cost (a stretch of short in-rows ends a sum every few edges), stretches of such chunks exist
+    // (the vertices that earlier batches created sit together at the end of the id range), and the few wavefronts
+    // that owned such a stretch held up the hop (3.4 instead of 2.1 ms after 400 batches that each create 100
+    // vertices; in the deterministic mode 7.4 instead of 2.5 ms at hop 2).
+    const uint32_t per = max(1u, min((uint32_t)PULL_RUN, n_chunks / (2u * nw)));
+    const uint32_t n_runs = (n_chunks + per - 1) / per;
+    uint32_t run = gw;                                      // the first run needs no counter
+    if (DET && n_runs > a.side_runs) {                      // cannot happen: the side entries are sized for the in-row pool
+        if (gw == 0 && lane == 0) a.ctr->error = 9;
         return;
     }
+    if (run >= n_runs) {
+        if (DET && lane == 0)
+            for (; run < a.side_runs; run += nw) a.side_v[2 * run] = a.side_v[2 * run + 1] = 0xFFFFFFFFu;
+        return;
+    }
+    uint32_t c_begin = run * per;
+    uint32_t c_end = min(n_chunks, c_begin + per);
     PullScan<T, WT> scan;
     scan.begin(a, count, c_begin, lane);
     constexpr uint32_t NONE = 0xFFFFFFFFu;
@@ -323,7 +333,7 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
     float acc[NJ];
 #pragma unroll
     for (int j = 0; j < NJ; ++j) acc[j] = 0.0f;
-    // DET: the destinations of this run's first and last in-edge, and whether a sum was left for them
+    // DET: the destinations of the current run's first and last in-edge, and whether a sum was left for them
     uint32_t v_head = NONE, v_tail = NONE;
     bool wrote_head = false, wrote_tail = false;
     if (DET) {
@@ -343,7 +353,7 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
             return;
         }
         if (cur == v_head || cur == v_tail) {
-            const uint32_t slot = 2 * gw + (cur == v_head ? 0u : 1u);
+            const uint32_t slot = 2 * run + (cur == v_head ? 0u : 1u);
             if (cur == v_head) wrote_head = true;
             else wrote_tail = true;
             xr = a.side_acc + (size_t)slot * d;
@@ -429,16 +439,28 @@ __global__ __launch_bounds__(256) void k_scatter_pull(PullArgs a) {
     }
     if (cur != NONE) flush();
     cur = NONE;
-    if (DET || (unsigned long long)nw * per >= n_chunks) break;   // every run was somebody's first
-    c_begin = (nw + rp_next_run(&a.ctr->pull_next[a.l], lane)) * per;
-    if (c_begin >= n_chunks) break;
+    if (DET) {
+        if (lane == 0) {
+            a.side_v[2 * run] = wrote_head ? v_head : NONE;
+            a.side_v[2 * run + 1] = wrote_tail ? v_tail : NONE;
+        }
+        wrote_head = wrote_tail = false;
+        run += nw;
+    } else {
+        if ((unsigned long long)nw * per >= n_chunks) break;      // every run was somebody's first
+        run = nw + rp_next_run(&a.ctr->pull_next[a.l], lane);
+    }
+    if (run >= n_runs) break;
+    c_begin = run * per;
     c_end = min(n_chunks, c_begin + per);
     scan.begin(a, count, c_begin, lane);
+    if (DET) {
+        v_head = (uint32_t)__shfl((int)scan.rv, 0);
+        v_tail = a.list[rp_seg_search_wave(a.ioff, 0, count - 1, min(total, c_end * PULL_CHUNK) - 1u)];
     }
-    if (DET && lane == 0) {
-        a.side_v[2 * gw] = wrote_head ? v_head : NONE;
-        a.side_v[2 * gw + 1] = wrote_tail ? v_tail : NONE;
     }
+    if (DET && lane == 0)                                         // the runs of this wavefront's numbers that do not exist
+        for (; run < a.side_runs; run += nw) a.side_v[2 * run] = a.side_v[2 * run + 1] = NONE;
 }
 
 // The same hop from the list of its messages. A pull finds the messages by testing every in-neighbour of every vertex
@@ -580,14 +602,21 @@ __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
     const uint32_t total = a.ioff[count];
     const uint32_t n_chunks = (total + PULL_CHUNK - 1) / PULL_CHUNK;
     const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
-    // runs of chunks: fixed per wavefront (DET) or fetched from a counter, see k_scatter_pull
-    const uint32_t per = DET ? (n_chunks + nw - 1) / nw : max(1u, min((uint32_t)PULL_RUN, n_chunks / (2u * nw)));
-    uint32_t c_begin = min(n_chunks, gw * per);             // the first run needs no counter
-    uint32_t c_end = min(n_chunks, c_begin + per);
-    if (c_begin >= c_end) {
-        if (DET && lane == 0) a.side_v[2 * gw] = a.side_v[2 * gw + 1] = NONE;
+    // runs of chunks: every nw-th one (DET) or fetched from a counter, see k_scatter_pull
+    const uint32_t per = max(1u, min((uint32_t)PULL_RUN, n_chunks / (2u * nw)));
+    const uint32_t n_runs = (n_chunks + per - 1) / per;
+    uint32_t run = gw;                                      // the first run needs no counter
+    if (DET && n_runs > a.side_runs) {                      // cannot happen: the side entries are sized for the in-row pool
+        if (gw == 0 && lane == 0) a.ctr->error = 9;
         return;
     }
+    if (run >= n_runs) {
+        if (DET && lane == 0)
+            for (; run < a.side_runs; run += nw) a.side_v[2 * run] = a.side_v[2 * run + 1] = NONE;
+        return;
+    }
+    uint32_t c_begin = run * per;
+    uint32_t c_end = min(n_chunks, c_begin + per);
     // message rows through a buffer descriptor: 32-bit byte offsets (row offset from LDS + this lane's chunk)
     const __amdgpu_buffer_rsrc_t mres = __builtin_amdgcn_make_buffer_rsrc((void *)a.D, 0, a.msg_bytes, 0x00020000u);
     const uint32_t sub8 = 8u * sub;
@@ -618,7 +647,7 @@ __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
         } else if (cur == v_head || cur == v_tail) {
             if (cur == v_head) wrote_head = true;
             else wrote_tail = true;
-            if (sends) a.side_acc[(size_t)(2 * gw + (cur == v_head ? 0u : 1u)) * d + my_col] = mine;
+            if (sends) a.side_acc[(size_t)(2 * run + (cur == v_head ? 0u : 1u)) * d + my_col] = mine;
         } else if (sends) {
             float *x = &a.X[(size_t)cur * d + my_col];
             *x = cur_rec ? mine : *x + mine;
@@ -730,27 +759,44 @@ __global__ __launch_bounds__(256) void k_scatter_pull4(PullArgs a) {
     }
     if (cur != NONE) flush();
     cur = NONE;
-    if (DET || (unsigned long long)nw * per >= n_chunks) break;   // every run was somebody's first
-    c_begin = (nw + rp_next_run(&a.ctr->pull_next[a.l], lane)) * per;
-    if (c_begin >= n_chunks) break;
+    if (DET) {
+        if (lane == 0) {
+            a.side_v[2 * run] = wrote_head ? v_head : NONE;
+            a.side_v[2 * run + 1] = wrote_tail ? v_tail : NONE;
+        }
+        wrote_head = wrote_tail = false;
+        run += nw;
+    } else {
+        if ((unsigned long long)nw * per >= n_chunks) break;      // every run was somebody's first
+        run = nw + rp_next_run(&a.ctr->pull_next[a.l], lane);
+    }
+    if (run >= n_runs) break;
+    c_begin = run * per;
     c_end = min(n_chunks, c_begin + per);
     scan.begin(a, count, c_begin, lane);
+    if (DET) {
+        v_head = (uint32_t)__shfl((int)scan.rv, 0);
+        v_tail = a.list[rp_seg_search_wave(a.ioff, 0, count - 1, min(total, c_end * PULL_CHUNK) - 1u)];
     }
-    if (DET && lane == 0) {
-        a.side_v[2 * gw] = wrote_head ? v_head : NONE;
-        a.side_v[2 * gw + 1] = wrote_tail ? v_tail : NONE;
     }
+    if (DET && lane == 0)                                         // the runs of this wavefront's numbers that do not exist
+        for (; run < a.side_runs; run += nw) a.side_v[2 * run] = a.side_v[2 * run + 1] = NONE;
 }
 
-// Deterministic mode, after a DET pull: the side entries (two per wavefront, in wavefront order; entries of one
+// Deterministic mode, after a DET pull: the side entries (two per run of chunks, in run order; entries of one
 // destination are neighbours, apart from empty ones between them) are added up per destination in that order
 // and the sum is added to the row, or replaces it if the row is recomputed. One wavefront per entry; the one
 // that holds a destination's first entry does the work. Recomputed rows without any in-edge are zeroed here too:
 // no in-edge, so the pull never met them.
-__global__ __launch_bounds__(256) void k_pull_fixup(PullArgs a, uint32_t n_entries) {
+__global__ __launch_bounds__(256) void k_pull_fixup(PullArgs a, uint32_t n_entries, uint32_t pull_nw) {
     constexpr uint32_t NONE = 0xFFFFFFFFu;
     const uint32_t count = *a.count_ptr;
     if (count == 0) return;
+    {   // only the entries of runs that exist can hold anything (the same cut as in the pull kernels)
+        const uint32_t n_chunks = (a.ioff[count] + PULL_CHUNK - 1) / PULL_CHUNK;
+        const uint32_t per = max(1u, min((uint32_t)PULL_RUN, n_chunks / (2u * pull_nw)));
+        n_entries = min(n_entries, 2u * ((n_chunks + per - 1) / per));
+    }
     const int lane = rp_lane();
     const uint32_t d = a.d;
     const uint32_t gw = (blockIdx.x * blockDim.x + threadIdx.x) >> 6, nw = (gridDim.x * blockDim.x) >> 6;
@@ -811,6 +857,7 @@ void rp_launch_scatter_pull(ripple_ctx *c, uint32_t l, bool discover, bool allow
     a.m_count = &c->ctr->a[l - 1];
     a.sorted_cap = discover ? 0u : pair_cap;
     a.sorted_force = c->opt_sorted == 2;
+    a.side_runs = 0;
     a.list = discover ? c->all_list : c->list[l];
     a.count_ptr = discover ? &c->ctr->n_all : &c->ctr->a[l];
     a.ioff = discover ? c->ioff_all : c->ioff[l];
@@ -916,14 +963,16 @@ void rp_launch_scatter_pull_det(ripple_ctx *c, uint32_t l, bool bootstrap) {
     a.side_v = c->side_v;
     a.side_acc = c->side_acc;
     dim3 grid(c->n_cu * 8), block(256);
-    const uint32_t n_entries = 2u * grid.x * 4u;            // two per wavefront
+    a.side_runs = c->side_runs;
+    const uint32_t n_entries = 2u * c->side_runs;           // two per run
     if (packed) hipLaunchKernelGGL((k_scatter_pull4<0, 0, 1>), grid, block, 0, c->stream, a);
     else if (a.d <= 64) hipLaunchKernelGGL((k_scatter_pull<1, 0, 0, 1>), grid, block, 0, c->stream, a);
     else if (a.d <= 128) hipLaunchKernelGGL((k_scatter_pull<2, 0, 0, 1>), grid, block, 0, c->stream, a);
     else if (a.d <= 256) hipLaunchKernelGGL((k_scatter_pull<4, 0, 0, 1>), grid, block, 0, c->stream, a);
     else if (a.d <= 512) hipLaunchKernelGGL((k_scatter_pull<8, 0, 0, 1>), grid, block, 0, c->stream, a);
     else hipLaunchKernelGGL((k_scatter_pull<16, 0, 0, 1>), grid, block, 0, c->stream, a);
-    hipLaunchKernelGGL(k_pull_fixup, dim3(rp_div_up(n_entries, 4)), block, 0, c->stream, a, n_entries);
+    hipLaunchKernelGGL(k_pull_fixup, dim3(std::min<uint32_t>(rp_div_up(n_entries, 4), c->n_cu * 32)), block, 0, c->stream, a, n_entries,
+                       grid.x * 4u);
 }
 
 // ---------------------------------------------------------------------------------
