@@ -303,10 +303,11 @@ def test_dense_configs_sampled_rows(dense_graph, name):
         rp.ripple_destroy(ctx)
 
 
-@pytest.mark.parametrize("name,bs", [("dense_sage_mean_4layer", 1000), ("reddit_sage_mean", 1000), ("dense_gat", 10000)])
+@pytest.mark.parametrize("name,bs", [("dense_sage_mean_4layer", 1000), ("reddit_sage_mean", 1000), ("dense_gat", 10000),
+                                     ("dense_gcn_wsum", 10000)])
 def test_deep_and_reddit_shaped_configs(dense_graph, name, bs):
-    """Four layers on the dense graph, and a graph of Reddit's shape (average in-degree 492, 602
-    features). Affected sets are compared in full. At this density the in-neighbourhood cone of even
+    """Four layers on the dense graph, a graph of Reddit's shape (average in-degree 492, 602
+    features), attention and the weighted sum (one weight per edge) at full size. Affected sets are compared in full. At this density the in-neighbourhood cone of even
     a handful of final-layer rows is most of the graph, so the rows are checked hop by hop instead:
     for a sample of A_l the oracle applies layer l (fp64) to the library's own stored H^{l-1}, which
     an earlier step of the same loop has checked the same way, down to the features."""
@@ -321,14 +322,19 @@ def test_deep_and_reddit_shaped_configs(dense_graph, name, bs):
     model = ri.make_model(cfg.model, cfg.widths, cfg.weight_seed)
     print("case", name, flush=True)
     t0 = time.time()
-    ctx = rp.ripple_init_graph(cfg.n, cfg.vertex_capacity, src, dst, feats, store=cfg.store,
-                               edge_capacity=cfg.edge_capacity)
+    weights = ri.edge_weights(len(src), cfg.graph_seed + 100) if cfg.weighted else None
+    if weights is None:
+        ctx = rp.ripple_init_graph(cfg.n, cfg.vertex_capacity, src, dst, feats, store=cfg.store,
+                                   edge_capacity=cfg.edge_capacity)
+    else:
+        ctx = rp.ripple_init_graph_weighted(cfg.n, cfg.vertex_capacity, src, dst, weights, feats, store=cfg.store,
+                                            edge_capacity=cfg.edge_capacity)
     try:
         rp.ripple_load_model(ctx, model)
         rp.ripple_full_infer(ctx)
         stream = ri.UpdateStream(cfg.n, cfg.vertex_capacity, src, dst, out_law, in_law, cfg.d0, cfg.mix,
-                                 cfg.stream_seed)
-        ora = oracle.GraphState(cfg.n, cfg.vertex_capacity, src, dst, feats)
+                                 cfg.stream_seed, weighted=cfg.weighted)
+        ora = oracle.GraphState(cfg.n, cfg.vertex_capacity, src, dst, feats, weights=weights)
         print(f"  bootstrap and oracle state {time.time() - t0:.0f}s", flush=True)
         L = len(model)
         rng = np.random.default_rng(6)
