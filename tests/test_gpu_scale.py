@@ -303,11 +303,13 @@ def test_dense_configs_sampled_rows(dense_graph, name):
         rp.ripple_destroy(ctx)
 
 
-@pytest.mark.parametrize("name,bs", [("dense_sage_mean_4layer", 1000), ("reddit_sage_mean", 1000), ("dense_gat", 10000),
-                                     ("dense_gcn_wsum", 10000)])
-def test_deep_and_reddit_shaped_configs(dense_graph, name, bs):
+@pytest.mark.parametrize("name,bs,det", [("dense_sage_mean_4layer", 1000, 0), ("reddit_sage_mean", 1000, 0),
+                                         ("dense_gat", 10000, 0), ("dense_gcn_wsum", 10000, 0),
+                                         ("dense_sage_mean", 10000, 1)])
+def test_deep_and_reddit_shaped_configs(dense_graph, name, bs, det):
     """Four layers on the dense graph, a graph of Reddit's shape (average in-degree 492, 602
-    features), attention and the weighted sum (one weight per edge) at full size. Affected sets are compared in full. At this density the in-neighbourhood cone of even
+    features), attention, the weighted sum (one weight per edge) and the deterministic mode of the headline model
+    (60 K runs of chunks, two side entries each) at full size. Affected sets are compared in full. At this density the in-neighbourhood cone of even
     a handful of final-layer rows is most of the graph, so the rows are checked hop by hop instead:
     for a sample of A_l the oracle applies layer l (fp64) to the library's own stored H^{l-1}, which
     an earlier step of the same loop has checked the same way, down to the features."""
@@ -320,7 +322,7 @@ def test_deep_and_reddit_shaped_configs(dense_graph, name, bs):
         print(f" graph generated in {time.time() - t0:.0f}s", flush=True)
     feats = ri.features(cfg.n, cfg.d0, cfg.feat_seed)
     model = ri.make_model(cfg.model, cfg.widths, cfg.weight_seed)
-    print("case", name, flush=True)
+    print("case", name, "deterministic" if det else "", flush=True)
     t0 = time.time()
     weights = ri.edge_weights(len(src), cfg.graph_seed + 100) if cfg.weighted else None
     if weights is None:
@@ -330,6 +332,8 @@ def test_deep_and_reddit_shaped_configs(dense_graph, name, bs):
         ctx = rp.ripple_init_graph_weighted(cfg.n, cfg.vertex_capacity, src, dst, weights, feats, store=cfg.store,
                                             edge_capacity=cfg.edge_capacity)
     try:
+        if det:
+            rp.ripple_set_option(ctx, rp.OPT_DETERMINISTIC, 1)
         rp.ripple_load_model(ctx, model)
         rp.ripple_full_infer(ctx)
         stream = ri.UpdateStream(cfg.n, cfg.vertex_capacity, src, dst, out_law, in_law, cfg.d0, cfg.mix,
