@@ -371,6 +371,30 @@ def test_deep_and_reddit_shaped_configs(dense_graph, name, bs, det):
             print(f"  layer {l}: {len(rows)} rows from {len(need)} inputs, max rel err {err:.2e} {time.time() - t0:.0f}s",
                   flush=True)
             assert err <= TOL[cfg.store], (l, err)
+        if det:
+            # a second context fed the same operations ends up with the same bits (all rows of the last layer, a
+            # sample of 200,000 rows of every other layer)
+            ctx2 = rp.ripple_init_graph(cfg.n, cfg.vertex_capacity, src, dst, feats, store=cfg.store,
+                                        edge_capacity=cfg.edge_capacity)
+            try:
+                rp.ripple_set_option(ctx2, rp.OPT_DETERMINISTIC, 1)
+                rp.ripple_load_model(ctx2, model)
+                rp.ripple_full_infer(ctx2)
+                stream2 = ri.UpdateStream(cfg.n, cfg.vertex_capacity, src, dst, out_law, in_law, cfg.d0, cfg.mix,
+                                          cfg.stream_seed, weighted=cfg.weighted)
+                for b in range(2):
+                    ops, payload, _ = stream2.next_batch(bs)
+                    rp.ripple_apply_updates(ctx2, ops, payload)
+                ids = np.sort(rng.choice(cfg.n, size=200_000, replace=False)).astype(np.uint32)
+                for l in range(1, L + 1):
+                    pick = None if l == L else ids
+                    kw = dict(n_rows=cfg.vertex_capacity) if pick is None else dict(ids=pick)
+                    one = rp.ripple_get_embeddings(ctx, l, cfg.widths[l], **kw)
+                    two = rp.ripple_get_embeddings(ctx2, l, cfg.widths[l], **kw)
+                    assert np.array_equal(one.view(np.uint32), two.view(np.uint32)), f"layer {l}: bits differ between two contexts"
+                print(f"  two contexts agree bit for bit {time.time() - t0:.0f}s", flush=True)
+            finally:
+                rp.ripple_destroy(ctx2)
     finally:
         rp.ripple_destroy(ctx)
 
