@@ -375,7 +375,10 @@ def main():
                    **({"aggregation": "deterministic"} if args.deterministic else {})},
         "per_batch": {"a_l": [st.rows[l] / max(st.batches, 1) for l in range(L + 1)],
                       "messages_l": [st.msgs[l] / max(st.batches, 1) for l in range(L + 1)],
-                      "phase_ms": other},
+                      "phase_ms": other,
+                      # how the last timed batch moved each hop's messages: 1 pushed, 2 pulled, 3 one scan of all in-rows
+                      # that also finds the hop's set, 4 from the list of the hop's messages sorted by destination
+                      "hop_mode_last_batch": [int(res.hop_mode[l]) for l in range(1, L + 1)]},
         "aggregate_width": {f"l{l}": layer_info[l][0] for l in layer_info},
         **({"max_min_split_per_batch": {f"l{l}": dict(zip(("unchanged", "incremental", "recomputed"),
                                                           (mono[:, l] / max(args.steps, 1)).tolist()))
