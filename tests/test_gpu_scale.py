@@ -305,11 +305,13 @@ def test_dense_configs_sampled_rows(dense_graph, name):
 
 @pytest.mark.parametrize("name,bs,det", [("dense_sage_mean_4layer", 1000, 0), ("reddit_sage_mean", 1000, 0),
                                          ("dense_gat", 10000, 0), ("dense_gcn_wsum", 10000, 0),
-                                         ("dense_sage_mean", 10000, 1)])
+                                         ("dense_sage_mean", 10000, 1), ("dense_sage_mean", (10000, 1000, 10000), 0)])
 def test_deep_and_reddit_shaped_configs(dense_graph, name, bs, det):
     """Four layers on the dense graph, a graph of Reddit's shape (average in-degree 492, 602
     features), attention, the weighted sum (one weight per edge) and the deterministic mode of the headline model
-    (60 K runs of chunks, two side entries each) at full size. Affected sets are compared in full. At this density the in-neighbourhood cone of even
+    (60 K runs of chunks, two side entries each) at full size; and a sequence of batch sizes (10,000, 1,000, 10,000)
+    that makes the size the host sorts the second hop's messages for too small for the third batch, which then has
+    to fall back to the pull on the device. Affected sets are compared in full. At this density the in-neighbourhood cone of even
     a handful of final-layer rows is most of the graph, so the rows are checked hop by hop instead:
     for a sample of A_l the oracle applies layer l (fp64) to the library's own stored H^{l-1}, which
     an earlier step of the same loop has checked the same way, down to the features."""
@@ -342,8 +344,10 @@ def test_deep_and_reddit_shaped_configs(dense_graph, name, bs, det):
         print(f"  bootstrap and oracle state {time.time() - t0:.0f}s", flush=True)
         L = len(model)
         rng = np.random.default_rng(6)
-        for b in range(2):
-            ops, payload, _ = stream.next_batch(bs)
+        sizes = bs if isinstance(bs, tuple) else (bs, bs)
+        modes = []
+        for b, nb in enumerate(sizes):
+            ops, payload, _ = stream.next_batch(nb)
             rec = ora.apply_batch(ops, payload)
             res = rp.ripple_apply_updates(ctx, ops, payload)
             assert res.n_applied == int(rec.accepted.sum()) and res.n_rejected == 0
@@ -352,7 +356,12 @@ def test_deep_and_reddit_shaped_configs(dense_graph, name, bs, det):
             for l in range(L + 1):
                 got, n = rp.ripple_get_affected(ctx, l, cfg.vertex_capacity)
                 assert n == len(sets[l]) and np.array_equal(got.astype(np.int64), sets[l]), f"affected set {l}"
-            print(f"  batch {b}: sets {[len(s) for s in sets]} {time.time() - t0:.0f}s", flush=True)
+            modes.append(list(res.hop_mode[1:L + 1]))
+            print(f"  batch {b}: sets {[len(s) for s in sets]} hop modes {modes[-1]} {time.time() - t0:.0f}s", flush=True)
+        if isinstance(bs, tuple):
+            # the 1,000-update batch takes hop 2 from the sorted list (sized by the batch before it); the batch after it
+            # has fifteen times as many messages as the host sorted room for and is pulled
+            assert modes[1][1] == 4 and modes[2][1] == 2, modes
         a_in = oracle.in_adjacency(ora)
         touched = np.asarray(sorted(rec.feat), dtype=np.int64)
         got0 = rp.ripple_get_embeddings(ctx, 0, cfg.widths[0], ids=touched.astype(np.uint32))
@@ -382,8 +391,8 @@ def test_deep_and_reddit_shaped_configs(dense_graph, name, bs, det):
                 rp.ripple_full_infer(ctx2)
                 stream2 = ri.UpdateStream(cfg.n, cfg.vertex_capacity, src, dst, out_law, in_law, cfg.d0, cfg.mix,
                                           cfg.stream_seed, weighted=cfg.weighted)
-                for b in range(2):
-                    ops, payload, _ = stream2.next_batch(bs)
+                for nb in sizes:
+                    ops, payload, _ = stream2.next_batch(nb)
                     rp.ripple_apply_updates(ctx2, ops, payload)
                 ids = np.sort(rng.choice(cfg.n, size=200_000, replace=False)).astype(np.uint32)
                 for l in range(1, L + 1):
